@@ -1,0 +1,131 @@
+"""ctypes access to the CPU oracle (`fho.c`).
+
+TEST INFRASTRUCTURE ONLY: the oracle defines the expected result of the group
+quantiser (FedHybrid Section 4.4.1, normal-channel quantisation; Section 3,
+compress in forward / decompress in backward).  Only the tests, the smoke check
+and the benchmark's CPU-baseline leg import this package.  It neither imports nor
+is imported by the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libfho.so")
+_SRC = os.path.join(_HERE, "fho.c")
+
+F32, BF16 = 0, 1
+NEAREST, STOCHASTIC = 0, 1
+
+_DTYPES = {"f32": F32, "bf16": BF16, F32: F32, BF16: BF16}
+_ROUNDS = {"nearest": NEAREST, "stochastic": STOCHASTIC, NEAREST: NEAREST, STOCHASTIC: STOCHASTIC}
+
+
+def build(force: bool = True) -> str:
+    """Compile fho.c into libfho.so with gcc (strict binary32 semantics: no
+    contraction, no fast-math)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True, cwd=_HERE)
+    return _SO
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = ctypes.CDLL(_SO)
+        u32p = ctypes.POINTER(ctypes.c_uint32)
+        L.fho_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        L.fho_philox4x32_10.restype = None
+        L.fho_random16.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]
+        L.fho_random16.restype = ctypes.c_uint32
+        L.fho_packed_bytes.argtypes = [ctypes.c_int64, ctypes.c_int]
+        L.fho_packed_bytes.restype = ctypes.c_size_t
+        L.fho_meta_bytes.argtypes = [ctypes.c_int64, ctypes.c_int]
+        L.fho_meta_bytes.restype = ctypes.c_size_t
+        L.fho_compress.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                   ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
+                                   ctypes.c_void_p, ctypes.c_void_p]
+        L.fho_compress.restype = ctypes.c_int
+        L.fho_decompress.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int,
+                                     ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        L.fho_decompress.restype = ctypes.c_int
+        L.fho_unpack_codes.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+        L.fho_unpack_codes.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def philox4x32_10(ctr, key) -> Tuple[int, int, int, int]:
+    c = (ctypes.c_uint32 * 4)(*[int(v) & 0xFFFFFFFF for v in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(v) & 0xFFFFFFFF for v in key])
+    o = (ctypes.c_uint32 * 4)()
+    lib().fho_philox4x32_10(c, k, o)
+    return tuple(int(v) for v in o)
+
+
+def random16(seed: int, tensor_id: int, index: int) -> int:
+    return int(lib().fho_random16(seed, tensor_id, index))
+
+
+def packed_bytes(numel: int, bits: int) -> int:
+    return int(lib().fho_packed_bytes(numel, bits))
+
+
+def meta_bytes(numel: int, group_size: int) -> int:
+    return int(lib().fho_meta_bytes(numel, group_size))
+
+
+def _check_input(x: np.ndarray, dtype) -> int:
+    d = _DTYPES[dtype]
+    want = np.float32 if d == F32 else np.uint16
+    if x.dtype != want or not x.flags.c_contiguous:
+        raise TypeError(f"expected C-contiguous {want.__name__} array for dtype {dtype!r}")
+    return d
+
+
+def compress(x: np.ndarray, group_size: int, bits: int, rounding="nearest", seed: int = 0,
+             tensor_id: int = 0, dtype="f32") -> Tuple[np.ndarray, np.ndarray]:
+    """-> (packed uint8[packed_bytes], meta float32[n_groups, 2] = {scale, zero})."""
+    d = _check_input(x, dtype)
+    n = int(x.size)
+    packed = np.empty(packed_bytes(n, bits), dtype=np.uint8)
+    meta = np.empty((meta_bytes(n, group_size) // 8, 2), dtype=np.float32)
+    rc = lib().fho_compress(x.ctypes.data, d, n, group_size, bits, _ROUNDS[rounding], seed, tensor_id,
+                            packed.ctypes.data, meta.ctypes.data)
+    if rc != 0:
+        raise ValueError("fho_compress rejected its arguments")
+    return packed, meta
+
+
+def decompress(packed: np.ndarray, meta: np.ndarray, numel: int, group_size: int, bits: int,
+               out_dtype="f32") -> np.ndarray:
+    """-> float32[numel], or uint16[numel] bf16 bit patterns."""
+    d = _DTYPES[out_dtype]
+    out = np.empty(numel, dtype=np.float32 if d == F32 else np.uint16)
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    meta = np.ascontiguousarray(meta, dtype=np.float32)
+    rc = lib().fho_decompress(packed.ctypes.data, meta.ctypes.data, int(numel), group_size, bits, d,
+                              out.ctypes.data)
+    if rc != 0:
+        raise ValueError("fho_decompress rejected its arguments")
+    return out
+
+
+def unpack_codes(packed: np.ndarray, numel: int, bits: int) -> np.ndarray:
+    codes = np.empty(numel, dtype=np.uint8)
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    rc = lib().fho_unpack_codes(packed.ctypes.data, int(numel), bits, codes.ctypes.data)
+    if rc != 0:
+        raise ValueError("fho_unpack_codes rejected its arguments")
+    return codes

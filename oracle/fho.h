@@ -1,0 +1,66 @@
+/*
+ * fho.h -- CPU oracle for the group quantiser that FedHybrid applies to normal
+ * (non-salient) channels of a saved activation (paper Section 4.4.1, "Channel-wise
+ * Mix Compression": normal channels are quantised with the conventional linear
+ * scale; Section 3, "Activation compression": compress in the forward pass,
+ * decompress in the backward pass).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, single-threaded, scalar C
+ * implementation whose only job is to say what the right answer is.  Nothing in
+ * the product path may include, link or call it; only the tests, the smoke check
+ * and the benchmark's CPU-baseline leg do.  It shares no code, header, table or
+ * constant generator with the HIP implementation.
+ *
+ * All pointers are HOST pointers.  All floating-point work is IEEE-754 binary32,
+ * round-to-nearest-even, no fused contraction except the one explicit fmaf in
+ * decompression, no flush-to-zero (build with -ffp-contract=off).  The quantisation
+ * decision is an integer decided by floating point, so it is taken in the
+ * precision the kernels use (binary32) rather than in binary64.
+ *
+ * The paper names the quantiser but prints no formula, bit width, rounding rule or
+ * storage layout for it; the definition implemented here is written out in the
+ * comment of each function in fho.c.
+ */
+#ifndef FHO_H
+#define FHO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { FHO_F32 = 0, FHO_BF16 = 1 };
+enum { FHO_ROUND_NEAREST = 0, FHO_ROUND_STOCHASTIC = 1 };
+
+/* Philox4x32-10 block function (Salmon, Moraes, Dror, Shaw: "Parallel random
+ * numbers: as easy as 1, 2, 3", SC'11, Section 3.3 and Table 2). */
+void fho_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* The 16 random bits that stochastic rounding spends on element `index` of the
+ * tensor `tensor_id` under `seed`. */
+uint32_t fho_random16(uint64_t seed, uint64_t tensor_id, uint64_t index);
+
+/* ceil(numel*bits/8) rounded up to a multiple of 16; 8 bytes per group. */
+size_t fho_packed_bytes(int64_t numel, int bits);
+size_t fho_meta_bytes(int64_t numel, int group_size);
+
+/* Forward side.  x: numel elements of `dtype` (bf16 as uint16 bit patterns).
+ * packed: fho_packed_bytes() bytes, fully written (padding zero).
+ * meta: 2 floats per group, {scale, zero}.  Returns 0, or -1 on a bad argument. */
+int fho_compress(const void *x, int dtype, int64_t numel, int group_size, int bits,
+                 int rounding, uint64_t seed, uint64_t tensor_id,
+                 uint8_t *packed, float *meta);
+
+/* Backward side.  out: numel elements of `out_dtype`. */
+int fho_decompress(const uint8_t *packed, const float *meta, int64_t numel,
+                   int group_size, int bits, int out_dtype, void *out);
+
+/* The unpacked code of every element (one byte each), for tests that look at codes. */
+int fho_unpack_codes(const uint8_t *packed, int64_t numel, int bits, uint8_t *codes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FHO_H */
