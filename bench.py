@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the activation compress + decompress round trip on one MI355X.
+
+A step is one pass of the whole hot path over one tensor set: every tensor is
+compressed (range statistics, quantisation, bit-packing) and then decompressed
+(unpack, fused dequantise) through the batched C-ABI entry points, with the inputs
+already resident in device memory.  The default workload is the mixed-plan 2 GiB
+stress set (48 fp32 tensors, per-tensor 2/4/8 bits, nearest or stochastic rounding).
+
+Prints one JSON line: whole-job input GB/s, the roofline of the dominant kernel
+(algorithmic bytes / event-timed duration vs the 8 TB/s HBM peak) and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(spec, out_itemsize=4):
+    """(compress bytes, decompress bytes) one tensor moves: input read + codes and
+    meta written; codes and meta read + output written."""
+    n = spec.numel
+    codes = (n * spec.bits + 7) // 8
+    meta = 8 * ((n + spec.group_size - 1) // spec.group_size)
+    return n * spec.itemsize + codes + meta, codes + meta + n * out_itemsize
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload configuration 1..5 (default 5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-tensor", action="store_true",
+                    help="time single-tensor fh_roundtrip calls instead of the batched entry point")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on ONE GPU (tensors are independent: no collective, no "
+              "sharding code exists); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    lib = os.path.join(ROOT, "paper_2510_11400_amd", "libfedhybrid.so")
+    if not os.path.exists(lib):
+        from paper_2510_11400_amd.build import build_library
+        build_library()
+    from paper_2510_11400_amd import api, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    w = W.full_config(args.config)
+    t0 = time.time()
+    host = []                                   # kept for the CPU baseline sample
+    entries = []
+    for spec, x in W.iter_materialised(w):
+        host.append(x)
+        xd = torch.from_numpy(x.view(np.int16) if spec.dtype == "bf16" else x).to(dev)
+        if spec.dtype == "bf16":
+            xd = xd.view(torch.bfloat16)
+        pk, mt = api.alloc_compressed(x.size, spec.group_size, spec.bits, dev)
+        out = torch.empty(x.size, dtype=torch.float32, device=dev)
+        entries.append(api.BatchEntry(spec.group_size, spec.bits, spec.rounding, spec.seed, spec.tensor_id,
+                                      x=xd, packed=pk, meta=mt, out=out))
+    batch = api.Batch(entries)
+    torch.cuda.synchronize()
+    print(f"[bench] {w.name}: {len(w.tensors)} tensors, {w.nbytes / 2**20:.1f} MiB resident "
+          f"(generated + uploaded in {time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
+
+    cbytes = sum(algorithmic_bytes(s)[0] for s in w.tensors)
+    dbytes = sum(algorithmic_bytes(s)[1] for s in w.tensors)
+    launches_c = launches_d = 1
+    stream = torch.cuda.current_stream()
+
+    def step(events=None):
+        if args.per_tensor:
+            for e in entries:
+                api.fh_roundtrip(e.x, e.group_size, e.bits, e.rounding, e.seed, e.tensor_id,
+                                 packed=e.packed, meta=e.meta, out=e.out, stream=stream)
+            return
+        if events is not None:
+            events[0].record(stream)
+        api.fh_compress_batch(batch, stream)
+        if events is not None:
+            events[1].record(stream)
+        api.fh_decompress_batch(batch, stream)
+        if events is not None:
+            events[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = w.nbytes / (elapsed / args.steps) / 1e9          # input GB/s over the round trip
+    result = {
+        "metric": "activation compress+decompress GB/s and % of HBM peak on 1 MI355X",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if w.tensors[0].dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "tensors": len(w.tensors), "input_bytes": w.nbytes,
+                   "entry_point": "fh_roundtrip (per tensor)" if args.per_tensor
+                   else "fh_compress_batch + fh_decompress_batch",
+                   "group_size": w.tensors[0].group_size,
+                   "bits": sorted({t.bits for t in w.tensors}),
+                   "rounding": sorted({t.rounding for t in w.tensors})},
+        "round_trip_algorithmic_bytes": cbytes + dbytes,
+        "hbm_frac_round_trip": round((cbytes + dbytes) / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+
+    if not args.per_tensor:
+        c_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps / launches_c
+        d_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps / launches_d
+        kern = {
+            "compress_kernel": {"ms": round(c_ms, 4), "bytes": cbytes, "GBps": round(cbytes / c_ms / 1e6, 1)},
+            "decompress_kernel": {"ms": round(d_ms, 4), "bytes": dbytes, "GBps": round(dbytes / d_ms / 1e6, 1)},
+        }
+        dom = "compress_kernel" if c_ms >= d_ms else "decompress_kernel"
+        result["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS,
+                              "unit": "GB/s", "frac": round(kern[dom]["GBps"] / HBM_PEAK_GBS, 4),
+                              "traffic": None}
+        result["kernels"] = kern
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample: the leading `frac` of every tensor (whole groups), so the mix of
+        # bit widths, rounding modes and distributions is that of the workload
+        target_elems = 300_000_000
+        frac = min(1.0, target_elems / max(1, w.numel))
+        t_cpu = 0.0
+        sample_bytes = 0
+        for spec, x in zip(w.tensors, host):
+            n = min(x.size, max(spec.group_size, int(x.size * frac) // spec.group_size * spec.group_size))
+            xs = np.ascontiguousarray(x[:n])
+            t1 = time.perf_counter()
+            p, m = oracle.compress(xs, spec.group_size, spec.bits, spec.rounding, spec.seed, spec.tensor_id,
+                                   dtype=spec.dtype)
+            oracle.decompress(p, m, n, spec.group_size, spec.bits)
+            t_cpu += time.perf_counter() - t1
+            sample_bytes += n * spec.itemsize
+        result["cpu_baseline"] = {
+            "value": round(sample_bytes / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"leading {frac:.4f} of each of the {len(w.tensors)} tensors "
+                      f"({sample_bytes / 2**20:.1f} MiB input, {t_cpu:.1f} s, compress + decompress)"}
+
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,138 @@
+/*
+ * fedhybrid.h -- C ABI of the MI355X (gfx950) activation compressor.
+ *
+ * What it computes: the quantisation that FedHybrid's local training engine applies
+ * to the normal (non-salient) channels of an activation saved in the forward pass,
+ * and its inverse on the backward pass (paper Section 3, "Activation compression":
+ * compress in forward, decompress during backpropagation; Section 4.4.1,
+ * "Channel-wise Mix Compression": normal channels undergo linear-scale
+ * quantisation, zeros must survive decompression).  The paper prints no formula,
+ * bit width, rounding rule or layout for that quantiser; the definition used is:
+ *
+ *   - the flattened tensor is cut into consecutive groups of `group_size` elements
+ *     (the last may be short);
+ *   - per group: mn = min, mx = max, range = mx - mn, L = 2^bits - 1,
+ *     zero = mn (with -0.0 stored as +0.0); if range < 2^-100 the group is
+ *     degenerate: scale = 0 and every code is 0; otherwise scale = range / L and
+ *     codes are taken from q = clamp((x - mn) * (L / range), 0, L) by
+ *       nearest:    code = rint(q)                      (ties to even)
+ *       stochastic: code = floor(q) + [u < q - floor(q)], u = h / 2^16,
+ *     where h are 16 bits of Philox4x32-10 output owned by the element: key = seed,
+ *     counter = (element_index / 8, tensor_id), element i taking half-word (i mod 8)
+ *     of the four output words in little-endian order;
+ *   - codes are bit-packed in element order, element i at bits [(i*bits) mod 8, +bits)
+ *     of byte floor(i*bits/8); bytes up to fh_packed_bytes() are zero-filled;
+ *   - meta is one {float scale; float zero;} pair per group;
+ *   - decompression returns fmaf(code, scale, zero) (single rounding), optionally
+ *     rounded to bf16 (nearest even).
+ *   All arithmetic is IEEE binary32.  Inputs must be finite with |x| < 2^126.
+ *
+ * Conventions
+ *   - Every data pointer (x, packed, meta, out) is a DEVICE pointer into memory the
+ *     caller owns; the parameter and item structs are HOST memory and are read
+ *     before the call returns.  The library allocates nothing, keeps no state, and
+ *     never synchronises: work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the caller orders it.
+ *   - x, packed and out must be 16-byte aligned, meta 8-byte aligned.
+ *   - All argument checks run on the host before anything is launched; a call that
+ *     returns an error has touched no device memory.  numel == 0 is FH_OK and
+ *     launches nothing.
+ *   - Results are a pure function of the arguments: independent of launch geometry,
+ *     of batching, and of the device the call runs on.
+ */
+#ifndef FEDHYBRID_H
+#define FEDHYBRID_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fh_status {
+    FH_OK = 0,
+    FH_ERR_NULL = 1,             /* a required pointer is NULL */
+    FH_ERR_BAD_DTYPE = 2,
+    FH_ERR_BAD_GROUP = 3,        /* group_size not in {64, 128, 256} */
+    FH_ERR_BAD_BITS = 4,         /* bits not in {2, 4, 8} */
+    FH_ERR_BAD_ROUND = 5,
+    FH_ERR_BAD_NUMEL = 6,        /* negative, or too large to index */
+    FH_ERR_BUFFER_TOO_SMALL = 7, /* a *_cap is below what the call writes or reads */
+    FH_ERR_ALIGNMENT = 8,
+    FH_ERR_LAUNCH = 9,           /* the HIP runtime refused the launch */
+    FH_ERR_BAD_COUNT = 10        /* negative item count */
+} fh_status;
+
+typedef enum fh_dtype { FH_F32 = 0, FH_BF16 = 1 } fh_dtype;
+typedef enum fh_round { FH_ROUND_NEAREST = 0, FH_ROUND_STOCHASTIC = 1 } fh_round;
+
+/* Quantiser parameters of one tensor (host memory). */
+typedef struct fh_params {
+    int32_t  group_size;   /* 64 | 128 | 256 contiguous elements */
+    int32_t  bits;         /* 2 | 4 | 8 */
+    int32_t  rounding;     /* fh_round */
+    int32_t  reserved;     /* must be 0 */
+    uint64_t seed;         /* Philox key; read only when rounding is stochastic */
+    uint64_t tensor_id;    /* upper half of the Philox counter; idem */
+} fh_params;
+
+/* One tensor of a batched call (host memory; the pointers inside are device
+ * pointers).  Fields a call does not use may be NULL / 0:
+ *   compress   reads x, writes packed + meta;
+ *   decompress reads packed + meta, writes out;
+ *   roundtrip  uses all of them. */
+typedef struct fh_item {
+    const void *x;          int32_t x_dtype;   int32_t out_dtype;   /* fh_dtype */
+    int64_t     numel;
+    void       *packed;     size_t packed_cap;  /* >= fh_packed_bytes(numel, bits) */
+    void       *meta;       size_t meta_cap;    /* >= fh_meta_bytes(numel, group_size) */
+    void       *out;        size_t out_cap;     /* >= numel * sizeof(out_dtype) */
+    fh_params   params;
+} fh_item;
+
+/* ceil(numel * bits / 8) rounded up to a multiple of 16; 0 for numel <= 0 or bad bits. */
+size_t fh_packed_bytes(int64_t numel, int32_t bits);
+/* 8 * ceil(numel / group_size); 0 for numel <= 0 or group_size <= 0. */
+size_t fh_meta_bytes(int64_t numel, int32_t group_size);
+
+/* Forward side (Section 3: "compresses the training activation during the forward
+ * pass"; quantiser of Section 4.4.1).  Reads numel elements of x_dtype at x, writes
+ * fh_packed_bytes() bytes at packed (padding included, zero) and fh_meta_bytes()
+ * bytes at meta. */
+fh_status fh_compress(const void *x, fh_dtype x_dtype, int64_t numel, const fh_params *params,
+                      void *packed, size_t packed_cap, void *meta, size_t meta_cap, void *stream);
+
+/* Backward side (Section 3: "decompresses the saved activation during
+ * backpropagation"; Section 4.4.1: reconstruction of floating-point values from the
+ * quantisation codes).  Writes numel elements of out_dtype at out.  params->rounding,
+ * seed and tensor_id are ignored. */
+fh_status fh_decompress(const void *packed, const void *meta, int64_t numel, const fh_params *params,
+                        fh_dtype out_dtype, void *out, size_t out_cap, void *stream);
+
+/* fh_compress followed by fh_decompress on the same stream, through the caller's
+ * packed/meta buffers: the memory traffic of the method as a training step incurs
+ * it (the codes are written to and read back from device memory, not kept in
+ * registers). */
+fh_status fh_roundtrip(const void *x, fh_dtype x_dtype, int64_t numel, const fh_params *params,
+                       void *packed, size_t packed_cap, void *meta, size_t meta_cap,
+                       fh_dtype out_dtype, void *out, size_t out_cap, void *stream);
+
+/* The same three operations over a set of tensors, as a training step saves and
+ * restores them (Section 4.3: the plan marks many tensors of one model for
+ * compression).  Tensors are processed by as few kernel launches as possible (one
+ * per run of up to fh_batch_capacity() items that share dtype and group size), so
+ * small tensors do not each pay a launch.  Items with numel == 0 are skipped.  All
+ * items are validated before the first launch.  Results are identical to calling
+ * the single-tensor entry points item by item. */
+fh_status fh_compress_batch(const fh_item *items, int32_t count, void *stream);
+fh_status fh_decompress_batch(const fh_item *items, int32_t count, void *stream);
+fh_status fh_roundtrip_batch(const fh_item *items, int32_t count, void *stream);
+int32_t   fh_batch_capacity(void);
+
+const char *fh_status_string(fh_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FEDHYBRID_H */

@@ -1,0 +1,258 @@
+"""Thin ctypes binding over libfedhybrid.so: argument marshalling only.
+
+Every step of the method runs in the HIP kernels behind the C ABI declared in
+include/fedhybrid.h (FedHybrid Section 3: compress in the forward pass, decompress in
+the backward pass; Section 4.4.1: linear-scale quantisation of normal channels).
+PyTorch supplies device memory and the current HIP stream, nothing else.  There is
+no CPU fallback: if the library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfedhybrid.so")
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it with `python -m paper_2510_11400_amd.build` "
+        "(hipcc, gfx950). There is no fallback implementation.")
+
+_lib = ctypes.CDLL(_LIB_PATH)
+
+FH_F32, FH_BF16 = 0, 1
+FH_ROUND_NEAREST, FH_ROUND_STOCHASTIC = 0, 1
+
+EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "fh_roundtrip",
+           "fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch", "fh_batch_capacity",
+           "fh_status_string")
+
+
+class fh_params(ctypes.Structure):
+    _fields_ = [("group_size", ctypes.c_int32), ("bits", ctypes.c_int32), ("rounding", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("seed", ctypes.c_uint64), ("tensor_id", ctypes.c_uint64)]
+
+
+class fh_item(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("x_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("numel", ctypes.c_int64),
+                ("packed", ctypes.c_void_p), ("packed_cap", ctypes.c_size_t),
+                ("meta", ctypes.c_void_p), ("meta_cap", ctypes.c_size_t),
+                ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t),
+                ("params", fh_params)]
+
+
+_P = ctypes.POINTER
+_lib.fh_packed_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32]
+_lib.fh_packed_bytes.restype = ctypes.c_size_t
+_lib.fh_meta_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32]
+_lib.fh_meta_bytes.restype = ctypes.c_size_t
+_lib.fh_compress.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, _P(fh_params),
+                             ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fh_compress.restype = ctypes.c_int
+_lib.fh_decompress.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, _P(fh_params),
+                               ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fh_decompress.restype = ctypes.c_int
+_lib.fh_roundtrip.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, _P(fh_params),
+                              ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                              ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fh_roundtrip.restype = ctypes.c_int
+for _name in ("fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch"):
+    getattr(_lib, _name).argtypes = [_P(fh_item), ctypes.c_int32, ctypes.c_void_p]
+    getattr(_lib, _name).restype = ctypes.c_int
+_lib.fh_batch_capacity.argtypes = []
+_lib.fh_batch_capacity.restype = ctypes.c_int32
+_lib.fh_status_string.argtypes = [ctypes.c_int]
+_lib.fh_status_string.restype = ctypes.c_char_p
+
+
+class FedHybridError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = int(status)
+        super().__init__(f"fedhybrid status {self.status}: {status_string(self.status)}")
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise FedHybridError(status)
+
+
+def raw_library() -> ctypes.CDLL:
+    """The loaded C library, for callers that marshal their own arguments."""
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return _lib.fh_status_string(int(status)).decode()
+
+
+def packed_bytes(numel: int, bits: int) -> int:
+    return int(_lib.fh_packed_bytes(numel, bits))
+
+
+def meta_bytes(numel: int, group_size: int) -> int:
+    return int(_lib.fh_meta_bytes(numel, group_size))
+
+
+def batch_capacity() -> int:
+    return int(_lib.fh_batch_capacity())
+
+
+_DT = {torch.float32: FH_F32, torch.bfloat16: FH_BF16}
+_ROUND = {"nearest": FH_ROUND_NEAREST, "stochastic": FH_ROUND_STOCHASTIC,
+          FH_ROUND_NEAREST: FH_ROUND_NEAREST, FH_ROUND_STOCHASTIC: FH_ROUND_STOCHASTIC}
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    try:
+        return _DT[t.dtype]
+    except KeyError:
+        raise TypeError(f"unsupported dtype {t.dtype}; expected float32 or bfloat16") from None
+
+
+def _device_tensor(t: torch.Tensor, what: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{what} must live in device memory (got a {t.device} tensor)")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def make_params(group_size: int, bits: int, rounding="nearest", seed: int = 0, tensor_id: int = 0) -> fh_params:
+    return fh_params(int(group_size), int(bits), _ROUND[rounding], 0,
+                     int(seed) & 0xFFFFFFFFFFFFFFFF, int(tensor_id) & 0xFFFFFFFFFFFFFFFF)
+
+
+def alloc_compressed(numel: int, group_size: int, bits: int, device) -> "tuple[torch.Tensor, torch.Tensor]":
+    """Device buffers of exactly the sizes fh_compress writes: (packed uint8, meta float32[n_g, 2])."""
+    packed = torch.empty(packed_bytes(numel, bits), dtype=torch.uint8, device=device)
+    meta = torch.empty((meta_bytes(numel, group_size) // 8, 2), dtype=torch.float32, device=device)
+    return packed, meta
+
+
+def fh_compress(x: torch.Tensor, group_size: int, bits: int, rounding="nearest", seed: int = 0,
+                tensor_id: int = 0, packed: Optional[torch.Tensor] = None,
+                meta: Optional[torch.Tensor] = None, stream=None):
+    """Enqueue compression of `x`; returns (packed, meta) device tensors."""
+    _device_tensor(x, "x")
+    n = x.numel()
+    if packed is None or meta is None:
+        packed, meta = alloc_compressed(n, group_size, bits, x.device)
+    p = make_params(group_size, bits, rounding, seed, tensor_id)
+    with torch.cuda.device(x.device):
+        _check(_lib.fh_compress(x.data_ptr(), _dtype_code(x), n, ctypes.byref(p),
+                                packed.data_ptr(), packed.numel() * packed.element_size(),
+                                meta.data_ptr(), meta.numel() * meta.element_size(), _stream_ptr(stream)))
+    return packed, meta
+
+
+def fh_decompress(packed: torch.Tensor, meta: torch.Tensor, numel: int, group_size: int, bits: int,
+                  out_dtype=torch.float32, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Enqueue decompression; returns the flat restored tensor."""
+    _device_tensor(packed, "packed")
+    _device_tensor(meta, "meta")
+    if out is None:
+        out = torch.empty(numel, dtype=out_dtype, device=packed.device)
+    _device_tensor(out, "out")
+    if packed.numel() * packed.element_size() < packed_bytes(numel, bits) or \
+            meta.numel() * meta.element_size() < meta_bytes(numel, group_size):
+        raise FedHybridError(7)
+    p = make_params(group_size, bits)
+    with torch.cuda.device(packed.device):
+        _check(_lib.fh_decompress(packed.data_ptr(), meta.data_ptr(), numel, ctypes.byref(p),
+                                  _dtype_code(out), out.data_ptr(), out.numel() * out.element_size(),
+                                  _stream_ptr(stream)))
+    return out
+
+
+def fh_roundtrip(x: torch.Tensor, group_size: int, bits: int, rounding="nearest", seed: int = 0,
+                 tensor_id: int = 0, out_dtype=torch.float32, packed=None, meta=None, out=None, stream=None):
+    """Compress then decompress on one stream; returns (packed, meta, out)."""
+    _device_tensor(x, "x")
+    n = x.numel()
+    if packed is None or meta is None:
+        packed, meta = alloc_compressed(n, group_size, bits, x.device)
+    if out is None:
+        out = torch.empty(n, dtype=out_dtype, device=x.device)
+    p = make_params(group_size, bits, rounding, seed, tensor_id)
+    with torch.cuda.device(x.device):
+        _check(_lib.fh_roundtrip(x.data_ptr(), _dtype_code(x), n, ctypes.byref(p),
+                                 packed.data_ptr(), packed.numel() * packed.element_size(),
+                                 meta.data_ptr(), meta.numel() * meta.element_size(),
+                                 _dtype_code(out), out.data_ptr(), out.numel() * out.element_size(),
+                                 _stream_ptr(stream)))
+    return packed, meta, out
+
+
+@dataclass
+class BatchEntry:
+    """One tensor of a batched call; buffers a call does not use may stay None."""
+    group_size: int
+    bits: int
+    rounding: object = "nearest"
+    seed: int = 0
+    tensor_id: int = 0
+    x: Optional[torch.Tensor] = None
+    packed: Optional[torch.Tensor] = None
+    meta: Optional[torch.Tensor] = None
+    out: Optional[torch.Tensor] = None
+    numel: Optional[int] = None
+
+
+class Batch:
+    """A marshalled fh_item array, reusable across calls (the buffers are fixed)."""
+
+    def __init__(self, entries: Sequence[BatchEntry]):
+        self.entries: List[BatchEntry] = list(entries)
+        self.items = (fh_item * max(1, len(self.entries)))()
+        self.count = len(self.entries)
+        self.device = None
+        for it, e in zip(self.items, self.entries):
+            ref = e.x if e.x is not None else e.packed
+            if ref is None:
+                raise ValueError("a batch entry needs at least x or packed")
+            self.device = self.device or ref.device
+            n = e.numel if e.numel is not None else (e.x.numel() if e.x is not None else e.out.numel())
+            it.numel = n
+            it.params = make_params(e.group_size, e.bits, e.rounding, e.seed, e.tensor_id)
+            if e.x is not None:
+                _device_tensor(e.x, "x")
+                it.x, it.x_dtype = e.x.data_ptr(), _dtype_code(e.x)
+            if e.packed is not None:
+                _device_tensor(e.packed, "packed")
+                it.packed, it.packed_cap = e.packed.data_ptr(), e.packed.numel() * e.packed.element_size()
+            if e.meta is not None:
+                _device_tensor(e.meta, "meta")
+                it.meta, it.meta_cap = e.meta.data_ptr(), e.meta.numel() * e.meta.element_size()
+            if e.out is not None:
+                _device_tensor(e.out, "out")
+                it.out, it.out_dtype, it.out_cap = (e.out.data_ptr(), _dtype_code(e.out),
+                                                    e.out.numel() * e.out.element_size())
+
+    def _call(self, fn, stream) -> None:
+        if self.count == 0:
+            return
+        with torch.cuda.device(self.device):
+            _check(fn(self.items, self.count, _stream_ptr(stream)))
+
+
+def fh_compress_batch(batch: Batch, stream=None) -> None:
+    batch._call(_lib.fh_compress_batch, stream)
+
+
+def fh_decompress_batch(batch: Batch, stream=None) -> None:
+    batch._call(_lib.fh_decompress_batch, stream)
+
+
+def fh_roundtrip_batch(batch: Batch, stream=None) -> None:
+    batch._call(_lib.fh_roundtrip_batch, stream)

@@ -1,0 +1,52 @@
+"""Build libfedhybrid.so (HIP kernels + C ABI) in-tree for gfx950 with hipcc.
+
+Cross-compiles without a GPU.  Run as `python -m paper_2510_11400_amd.build`.
+"""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libfedhybrid.so")
+SOURCES = ("fh_abi.hip", "fh_compress.hip", "fh_decompress.hip")
+
+# Strict binary32 semantics on the device: no contraction (the one fused multiply-add
+# of the method is written explicitly), IEEE division, denormals kept.  Packed-fp32
+# instruction selection is disabled.
+FLAGS = [
+    "-std=c++17", "-O3", "--offload-arch=gfx950", "-fPIC",
+    "-ffp-contract=off", "-fno-fast-math",
+    "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-gpu-flush-denormals-to-zero",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-command-line-argument",
+]
+
+
+def hipcc() -> str:
+    exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(exe):
+        raise RuntimeError("hipcc not found; ROCm is required to build libfedhybrid.so")
+    return exe
+
+
+def build_library(verbose: bool = False, extra_flags=()) -> str:
+    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = [hipcc(), *FLAGS, *extra_flags, "-shared", "-o", LIB, *srcs]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, cwd=CSRC, capture_output=True, text=True)
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
+    if verbose and err.strip():
+        print(err, file=sys.stderr)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

@@ -1,0 +1,169 @@
+// Backward side of the group quantiser on gfx950: unpack + fused dequantise.
+//
+// The output side carries almost all the bytes, so the lane layout is chosen for it:
+// each lane produces exactly one 128-bit store (4 fp32 or 8 bf16 consecutive
+// elements) and a wave's store is one contiguous span.  The codes a lane needs are
+// 8..64 bits of the packed stream; lanes read the aligned 32-bit word that holds
+// them (neighbouring lanes share a word when bits < 8, which the memory pipeline
+// serves as one access) and shift their part out.  scale/zero come from an 8-byte
+// load that all lanes of a group share.
+//
+// Reconstruction follows the paper's Section 4.4.1 (floating-point values are rebuilt
+// from the quantisation codes): x^ = fma(code, scale, zero), one rounding.
+#include "fh_device.hpp"
+#include "fh_kernels.hpp"
+
+namespace fh {
+
+namespace {
+
+constexpr int kRowsPerWave = 4;
+
+template <typename OutT> struct OutTraits;
+template <> struct OutTraits<float>    { static constexpr int EPL = 4; };
+template <> struct OutTraits<uint16_t> { static constexpr int EPL = 8; };
+
+template <typename OutT> constexpr int tile_elems()
+{
+    return (kBlock / kWave) * kRowsPerWave * kWave * OutTraits<OutT>::EPL;
+}
+
+template <int G> struct Log2;
+template <> struct Log2<64>  { static constexpr int v = 6; };
+template <> struct Log2<128> { static constexpr int v = 7; };
+template <> struct Log2<256> { static constexpr int v = 8; };
+
+// The EPL*B code bits of the lane whose first element is i0, right-aligned in c0 (and
+// c1 for the 64-bit case).
+template <int EPL, int B>
+__device__ __forceinline__ void load_codes(const uint8_t* packed, int64_t i0, uint32_t& c0, uint32_t& c1)
+{
+    constexpr int NBITS = EPL * B;
+    const uint64_t off = (uint64_t)i0 * B / 8;                // byte offset, multiple of NBITS/8
+    c1 = 0u;
+    if constexpr (NBITS == 64) {
+        const u32x2 w = *reinterpret_cast<const u32x2*>(packed + off);
+        c0 = w.x; c1 = w.y;
+    } else if constexpr (NBITS == 32) {
+        c0 = *reinterpret_cast<const uint32_t*>(packed + off);
+    } else {                                                  // 16 or 8 bits inside an aligned word
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(packed + (off & ~(uint64_t)3));
+        c0 = (w >> (((uint32_t)off & 3u) * 8u)) & ((1u << NBITS) - 1u);
+    }
+}
+
+template <int B>
+__device__ __forceinline__ float dequant(uint32_t bitsword, int j, float scale, float zero)
+{
+    const uint32_t code = (bitsword >> (j * B)) & ((1u << B) - 1u);
+    return __builtin_fmaf((float)code, scale, zero);          // single rounding
+}
+
+template <typename OutT, int G, int B>
+__device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32_t tile)
+{
+    constexpr int EPL = OutTraits<OutT>::EPL;
+    constexpr int ROW = kWave * EPL;
+    constexpr int WAVE_SPAN = kRowsPerWave * ROW;
+    constexpr int TILE = (kBlock / kWave) * WAVE_SPAN;
+    constexpr int PER_WORD = 32 / B;                          // codes per 32-bit word
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t numel = it.numel;
+    const int64_t wave_base = (int64_t)tile * TILE + (int64_t)wave * WAVE_SPAN;
+    if (wave_base >= numel) return;
+
+    const bool interior = wave_base + WAVE_SPAN <= numel;
+    uint32_t c0[kRowsPerWave], c1[kRowsPerWave];
+    f32x2 m[kRowsPerWave];
+#pragma unroll
+    for (int r = 0; r < kRowsPerWave; ++r) {
+        const int64_t i0 = wave_base + r * ROW + lane * EPL;
+        c0[r] = 0u; c1[r] = 0u; m[r] = f32x2{0.0f, 0.0f};
+        if (interior || i0 < numel) {
+            // a lane whose first element exists reads inside the padded code stream and
+            // inside the meta array (its group exists)
+            load_codes<EPL, B>(it.packed, i0, c0[r], c1[r]);
+            m[r] = *reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v));
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kRowsPerWave; ++r) {
+        const int64_t i0 = wave_base + r * ROW + lane * EPL;
+        float v[EPL];
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const uint32_t word = (j < PER_WORD) ? c0[r] : c1[r];
+            v[j] = dequant<B>(word, j % PER_WORD, m[r].x, m[r].y);
+        }
+        if constexpr (EPL == 4) {
+            float* dst = static_cast<float*>(it.out) + i0;
+            if (interior || i0 + EPL <= numel) {
+                *reinterpret_cast<f32x4*>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) if (i0 + j < numel) dst[j] = v[j];
+            }
+        } else {
+            uint16_t* dst = static_cast<uint16_t*>(it.out) + i0;
+            if (interior || i0 + EPL <= numel) {
+                u32x4 o;
+                o.x = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
+                o.y = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
+                o.z = bf16_bits(v[4]) | (bf16_bits(v[5]) << 16);
+                o.w = bf16_bits(v[6]) | (bf16_bits(v[7]) << 16);
+                *reinterpret_cast<u32x4*>(dst) = o;
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) if (i0 + j < numel) dst[j] = (uint16_t)bf16_bits(v[j]);
+            }
+        }
+    }
+}
+
+template <typename OutT, int G>
+__global__ __launch_bounds__(kBlock) void decompress_kernel(const DecompressBatch args)
+{
+    const uint32_t bid = blockIdx.x;
+    int lo = 0, hi = args.count;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (args.tile_start[mid] <= bid) lo = mid; else hi = mid;
+    }
+    const DecompressItem& it = args.item[lo];
+    const uint32_t tile = bid - args.tile_start[lo];
+    switch (it.bits) {
+        case 2: decompress_tile<OutT, G, 2>(it, tile); break;
+        case 4: decompress_tile<OutT, G, 4>(it, tile); break;
+        case 8: decompress_tile<OutT, G, 8>(it, tile); break;
+        default: break;
+    }
+}
+
+}  // namespace
+
+int decompress_tile_elems(int out_dtype, int)
+{
+    return out_dtype == 0 ? tile_elems<float>() : tile_elems<uint16_t>();
+}
+
+hipError_t launch_decompress(const DecompressBatch& b, int out_dtype, int group_size, hipStream_t s)
+{
+    const uint32_t tiles = b.tile_start[b.count];
+    if (tiles == 0) return hipSuccess;
+    const dim3 grid(tiles), block(kBlock);
+#define FH_LAUNCH(T, GS) hipLaunchKernelGGL((decompress_kernel<T, GS>), grid, block, 0, s, b)
+    if (out_dtype == 0) {
+        if (group_size == 64) FH_LAUNCH(float, 64);
+        else if (group_size == 128) FH_LAUNCH(float, 128);
+        else FH_LAUNCH(float, 256);
+    } else {
+        if (group_size == 64) FH_LAUNCH(uint16_t, 64);
+        else if (group_size == 128) FH_LAUNCH(uint16_t, 128);
+        else FH_LAUNCH(uint16_t, 256);
+    }
+#undef FH_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace fh

@@ -1,0 +1,160 @@
+// Device-side building blocks for the gfx950 group quantiser: cross-lane min/max,
+// Philox4x32-10, bf16 conversion, 128-bit memory access.  Wave size is 64.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fh {
+
+constexpr int kWave = 64;
+
+// ---- 128-bit vectors -------------------------------------------------------------
+typedef float    f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float    f32x2 __attribute__((ext_vector_type(2)));
+
+// ---- min / max ---------------------------------------------------------------------
+// Written as the machine instructions themselves.  The inputs are finite by contract,
+// so no NaN canonicalisation is wanted in front of them, and the result must not
+// depend on how a compiler folds min/max against infinities.  v_min_f32 / v_max_f32
+// return the smaller / larger operand; for +0 vs -0 either may come back, which the
+// caller canonicalises.
+__device__ __forceinline__ float vmin(float a, float b)
+{
+    float r;
+    asm volatile("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmax(float a, float b)
+{
+    float r;
+    asm volatile("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmin3(float a, float b, float c)
+{
+    float r;
+    asm volatile("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c)
+{
+    float r;
+    asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// ---- DPP lane exchange -----------------------------------------------------------
+// min(v, v permuted inside its 16-lane row) in one instruction.  A DPP operand read
+// needs two wait states after a VALU write of the same register, which the compiler's
+// hazard pass cannot see inside an asm block, hence the s_nop.
+#define FH_DPP_OP(NAME, OPC, CTRL)                                                       \
+    __device__ __forceinline__ float NAME(float v)                                       \
+    {                                                                                    \
+        float r;                                                                         \
+        asm volatile("s_nop 1\n\t" OPC " %0, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf" \
+                     : "=v"(r) : "v"(v));                                                \
+        return r;                                                                        \
+    }
+FH_DPP_OP(min_xor1,   "v_min_f32_dpp", "quad_perm:[1,0,3,2]")   // lane i with lane i^1
+FH_DPP_OP(max_xor1,   "v_max_f32_dpp", "quad_perm:[1,0,3,2]")
+FH_DPP_OP(min_xor2,   "v_min_f32_dpp", "quad_perm:[2,3,0,1]")   // lane i with lane i^2
+FH_DPP_OP(max_xor2,   "v_max_f32_dpp", "quad_perm:[2,3,0,1]")
+FH_DPP_OP(min_half,   "v_min_f32_dpp", "row_half_mirror")       // lane i with lane 7-i of its 8
+FH_DPP_OP(max_half,   "v_max_f32_dpp", "row_half_mirror")
+FH_DPP_OP(min_mirror, "v_min_f32_dpp", "row_mirror")            // lane i with lane 15-i of its 16
+FH_DPP_OP(max_mirror, "v_max_f32_dpp", "row_mirror")
+#undef FH_DPP_OP
+
+// Both halves of a permlane swap of a value with itself (gfx950).  The second operand
+// goes through an empty asm so the compiler treats the two inputs as unrelated values:
+// the swap moves data between lanes, and its two results differ even when its two
+// inputs are the same register.
+template <int WIDTH>
+__device__ __forceinline__ void self_swap(float v, float& first, float& second)
+{
+    const uint32_t a = __builtin_bit_cast(uint32_t, v);
+    uint32_t b = a;
+    asm volatile("" : "+v"(b));
+    u32x2 r;
+    if constexpr (WIDTH == 16) r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+    else r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+    const uint32_t r0 = r.x, r1 = r.y;   // scalars first: bit_cast wants an object, not a vector lane
+    first = __builtin_bit_cast(float, r0);
+    second = __builtin_bit_cast(float, r1);
+}
+
+// Min and max over aligned runs of LANES consecutive lanes; every lane of the run
+// ends with the run's result.  min/max are exact and order-independent, so any
+// exchange order gives the same value.  All 64 lanes must be active.
+template <int LANES>
+__device__ __forceinline__ void group_minmax(float& mn, float& mx)
+{
+    static_assert(LANES == 4 || LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "run length");
+    mn = min_xor1(mn);  mx = max_xor1(mx);
+    mn = min_xor2(mn);  mx = max_xor2(mx);
+    if constexpr (LANES >= 8) {   // quads are uniform now: mirroring 8 lanes swaps the two quads
+        mn = min_half(mn);  mx = max_half(mx);
+    }
+    if constexpr (LANES >= 16) {  // halves are uniform: mirroring 16 lanes swaps the two halves
+        mn = min_mirror(mn);  mx = max_mirror(mx);
+    }
+    if constexpr (LANES >= 32) {
+        // v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the
+        // even rows of its second: two copies of v come back as rows {0,0,2,2} and
+        // {1,1,3,3}, whose min/max is the 32-lane result.
+        float a, b;
+        self_swap<16>(mn, a, b);  mn = vmin(a, b);
+        self_swap<16>(mx, a, b);  mx = vmax(a, b);
+    }
+    if constexpr (LANES >= 64) {
+        // v_permlane32_swap exchanges lanes 32..63 of the first operand with lanes 0..31
+        // of the second: {lo,lo} and {hi,hi}.
+        float a, b;
+        self_swap<32>(mn, a, b);  mn = vmin(a, b);
+        self_swap<32>(mx, a, b);  mx = vmax(a, b);
+    }
+}
+
+// ---- Philox4x32-10 ---------------------------------------------------------------
+// Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3" (SC'11),
+// Section 3.3: ten rounds of
+//   (c0,c1,c2,c3) <- (hi(M1*c2) ^ c1 ^ k0, lo(M1*c2), hi(M0*c0) ^ c3 ^ k1, lo(M0*c0)),
+// the key advancing by the Weyl constants between rounds.  The key schedule is
+// wave-uniform, so it lives in scalar registers.
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    constexpr uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)M0 * c0;
+        const uint64_t p1 = (uint64_t)M1 * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += W0;
+        k1 += W1;
+    }
+    return u32x4{c0, c1, c2, c3};
+}
+
+// ---- bf16 ------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __builtin_bit_cast(float, pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __builtin_bit_cast(float, pair & 0xFFFF0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN kept quiet).
+__device__ __forceinline__ uint32_t bf16_bits(float f)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+}  // namespace fh

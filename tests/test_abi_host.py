@@ -1,0 +1,114 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, sizes its buffers like the definition says, and rejects
+bad arguments before anything could be launched."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2510_11400_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "fedhybrid.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fh_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert set(names) == set(api.EXPORTS)
+    lib = api.raw_library()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_size_helpers_match_the_definition():
+    for bits in (2, 4, 8):
+        for n in (1, 7, 8, 63, 64, 65, 255, 256, 257, 4095, 4096, 4097, 10 ** 9 + 7):
+            raw = -(-n * bits // 8)
+            assert api.packed_bytes(n, bits) == -(-raw // 16) * 16 == oracle.packed_bytes(n, bits)
+    for g in (64, 128, 256):
+        for n in (1, g - 1, g, g + 1, 10 ** 9 + 7):
+            assert api.meta_bytes(n, g) == 8 * -(-n // g) == oracle.meta_bytes(n, g)
+    assert api.packed_bytes(0, 4) == 0 and api.packed_bytes(-3, 4) == 0 and api.packed_bytes(10, 3) == 0
+    assert api.meta_bytes(0, 64) == 0 and api.meta_bytes(5, 0) == 0
+    assert 1 <= api.batch_capacity() <= 64
+
+
+def test_struct_layout_matches_the_header():
+    assert ctypes.sizeof(api.fh_params) == 32
+    assert ctypes.sizeof(api.fh_item) == 8 + 8 + 8 + 16 + 16 + 16 + 32
+    assert api.fh_item.params.offset == 72
+
+
+FAKE = 0x10000  # an aligned non-NULL address; never dereferenced because validation fails first
+
+
+def _compress(x=FAKE, dtype=0, n=1024, g=256, b=4, r=0, packed=FAKE, pcap=1 << 20, meta=FAKE, mcap=1 << 20):
+    p = api.fh_params(g, b, r, 0, 0, 0)
+    return api.raw_library().fh_compress(x, dtype, n, ctypes.byref(p), packed, pcap, meta, mcap, None)
+
+
+def _decompress(packed=FAKE, meta=FAKE, n=1024, g=256, b=4, odt=0, out=FAKE, ocap=1 << 20):
+    p = api.fh_params(g, b, 0, 0, 0, 0)
+    return api.raw_library().fh_decompress(packed, meta, n, ctypes.byref(p), odt, out, ocap, None)
+
+
+def test_compress_rejects_bad_arguments_before_any_launch():
+    assert _compress(g=100) == 3 and _compress(g=512) == 3
+    assert _compress(b=3) == 4 and _compress(b=16) == 4
+    assert _compress(r=2) == 5
+    assert _compress(dtype=7) == 2
+    assert _compress(n=-1) == 6
+    assert _compress(x=None) == 1 and _compress(packed=None) == 1 and _compress(meta=None) == 1
+    assert _compress(x=FAKE + 4) == 8 and _compress(packed=FAKE + 8) == 8 and _compress(meta=FAKE + 4) == 8
+    assert _compress(pcap=511) == 7 and _compress(mcap=31) == 7
+    assert api.raw_library().fh_compress(FAKE, 0, 1024, None, FAKE, 1 << 20, FAKE, 1 << 20, None) == 1
+    # numel == 0 is fine and launches nothing, whatever the pointers
+    assert _compress(n=0, x=None, packed=None, meta=None) == 0
+
+
+def test_decompress_rejects_bad_arguments_before_any_launch():
+    assert _decompress(g=32) == 3 and _decompress(b=1) == 4 and _decompress(odt=2) == 2
+    assert _decompress(n=-5) == 6
+    assert _decompress(packed=None) == 1 and _decompress(meta=None) == 1 and _decompress(out=None) == 1
+    assert _decompress(out=FAKE + 2) == 8
+    assert _decompress(ocap=4095) == 7 and _decompress(odt=1, ocap=2047) == 7
+    assert _decompress(n=0, out=None) == 0
+
+
+def test_batch_validates_every_item_before_the_first_launch():
+    items = (api.fh_item * 2)()
+    for it in items:
+        it.x = it.packed = it.meta = it.out = FAKE
+        it.numel = 256
+        it.packed_cap = it.meta_cap = it.out_cap = 1 << 20
+        it.params = api.fh_params(256, 8, 0, 0, 0, 0)
+    items[1].params.bits = 5                      # second item is bad: nothing may run
+    lib = api.raw_library()
+    assert lib.fh_compress_batch(items, 2, None) == 4
+    assert lib.fh_decompress_batch(items, 2, None) == 4
+    assert lib.fh_roundtrip_batch(items, 2, None) == 4
+    assert lib.fh_compress_batch(items, -1, None) == 10
+    assert lib.fh_compress_batch(None, 1, None) == 1
+    assert lib.fh_compress_batch(None, 0, None) == 0
+
+
+def test_status_strings():
+    seen = set()
+    for s in range(0, 11):
+        msg = api.status_string(s)
+        assert msg and msg != "unknown status"
+        seen.add(msg)
+    assert len(seen) == 11
+    assert api.status_string(99) == "unknown status"
+    with pytest.raises(api.FedHybridError) as e:
+        api._check(4)
+    assert "bits" in str(e.value)

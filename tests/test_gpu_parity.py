@@ -1,0 +1,285 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on a real MI355X.
+
+Bar: packed codes and per-group meta bit-exact; restored values bit-exact as well
+(both sides take the quantisation decision in binary32 and restore with one fused
+multiply-add), which subsumes the 1e-6 relative bound that is also asserted.
+Inputs come from the seeded workload generators; expected values only from oracle/.
+"""
+from __future__ import annotations
+
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_11400_amd import workloads as W
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+f32 = np.float32
+REL_TOL = 1e-6            # restored fp32 values, relative to max(|x^|, scale)
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def api():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a visible MI355X")
+    from paper_2510_11400_amd import api as _api
+    return _api
+
+
+def _to_device(x: np.ndarray, dtype: str):
+    t = torch.from_numpy(x.view(np.int16) if dtype == "bf16" else x).cuda()
+    return t.view(torch.bfloat16) if dtype == "bf16" else t
+
+
+def _host(t):
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def _oracle_roundtrip(x, spec, out_dtype="f32"):
+    p, m = oracle.compress(x, spec.group_size, spec.bits, spec.rounding, spec.seed, spec.tensor_id, dtype=spec.dtype)
+    o = oracle.decompress(p, m, x.size, spec.group_size, spec.bits, out_dtype)
+    return p, m, o
+
+
+def _assert_same(name, G, gp, gm, go, p, m, o, out_dtype="f32"):
+    gm = gm.reshape(-1, 2)
+    if not np.array_equal(gm.view(np.uint32), m.view(np.uint32)):
+        bad = np.flatnonzero((gm.view(np.uint32) != m.view(np.uint32)).any(axis=1))
+        raise AssertionError(f"{name}: meta differs in {bad.size} groups, first {bad[:5]}: "
+                             f"gpu {gm[bad[0]]} oracle {m[bad[0]]}")
+    if not np.array_equal(gp, p):
+        bad = np.flatnonzero(gp != p)
+        raise AssertionError(f"{name}: packed differs in {bad.size} bytes, first at {bad[:5]}: "
+                             f"gpu {gp[bad[:5]]} oracle {p[bad[:5]]}")
+    if out_dtype == "f32":
+        # the stated floating-point bar ...
+        scale = m[np.arange(o.size) // G, 0] if o.size else o
+        denom = np.maximum(np.abs(o), np.abs(scale)).astype(np.float64)
+        err = np.abs(go.astype(np.float64) - o.astype(np.float64))
+        assert (err <= REL_TOL * denom).all(), f"{name}: restored values beyond {REL_TOL} relative"
+        # ... and the stronger one the design gives
+        assert np.array_equal(go.view(np.uint32), o.view(np.uint32)), f"{name}: restored values not bit-exact"
+    else:
+        assert np.array_equal(go, o), f"{name}: bf16 restored values differ"
+
+
+def _run_single(api, x, spec, out_dtype="f32"):
+    xd = _to_device(x, spec.dtype)
+    tdt = torch.float32 if out_dtype == "f32" else torch.bfloat16
+    gp, gm = api.fh_compress(xd, spec.group_size, spec.bits, spec.rounding, spec.seed, spec.tensor_id)
+    go = api.fh_decompress(gp, gm, x.size, spec.group_size, spec.bits, out_dtype=tdt)
+    torch.cuda.synchronize()
+    return _host(gp), _host(gm), _host(go)
+
+
+# ------------------------------------------------------------- small sets ----
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_small_configuration_single_tensor_calls(api, idx):
+    w = W.small_variant(idx)
+    _say(f"[parity] small variant {idx}: {w.name}, {len(w.tensors)} tensors")
+    for spec in w.tensors:
+        x = W.materialise(w, spec)
+        p, m, o = _oracle_roundtrip(x, spec)
+        gp, gm, go = _run_single(api, x, spec)
+        _assert_same(f"{w.name}/t{spec.tensor_id}", spec.group_size, gp, gm, go, p, m, o)
+
+
+def _batch_roundtrip(api, w, specs, arrays, out_dtype="f32"):
+    tdt = torch.float32 if out_dtype == "f32" else torch.bfloat16
+    entries = []
+    for spec, x in zip(specs, arrays):
+        xd = _to_device(x, spec.dtype)
+        pk, mt = api.alloc_compressed(x.size, spec.group_size, spec.bits, xd.device)
+        pk.fill_(0xAB)                                   # stale bytes must all be overwritten
+        mt.fill_(float("nan"))
+        out = torch.full((x.size,), float("nan"), dtype=tdt, device=xd.device)
+        entries.append(api.BatchEntry(spec.group_size, spec.bits, spec.rounding, spec.seed, spec.tensor_id,
+                                      x=xd, packed=pk, meta=mt, out=out))
+    batch = api.Batch(entries)
+    api.fh_roundtrip_batch(batch)
+    torch.cuda.synchronize()
+    return entries
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_small_configuration_batched_call(api, idx):
+    w = W.small_variant(idx)
+    _say(f"[parity] small variant {idx} batched")
+    arrays = [W.materialise(w, s) for s in w.tensors]
+    entries = _batch_roundtrip(api, w, w.tensors, arrays)
+    for spec, x, e in zip(w.tensors, arrays, entries):
+        p, m, o = _oracle_roundtrip(x, spec)
+        _assert_same(f"{w.name}/t{spec.tensor_id}", spec.group_size, _host(e.packed), _host(e.meta), _host(e.out), p, m, o)
+
+
+# ---------------------------------------------------- ragged and edge cases ----
+
+RAGGED = (1, 2, 7, 8, 9, 63, 64, 65, 255, 256, 257, 511, 513, 1023, 2047, 2049, 4095, 4096, 4097,
+          8191, 12345, 16384 + 3, 3 * 4096 + 1000, 100003)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rounding", ["nearest", "stochastic"])
+def test_ragged_sizes_all_groups_and_widths(api, dtype, rounding):
+    rng = np.random.default_rng(np.random.SeedSequence([17, len(dtype), len(rounding)]))
+    for G in (64, 128, 256):
+        for bits in (2, 4, 8):
+            _say(f"[parity] ragged {dtype} {rounding} G={G} B={bits}")
+            for n in RAGGED:
+                x = rng.standard_normal(n).astype(f32)
+                x[rng.random(n) < 0.3] = 0
+                if dtype == "bf16":
+                    x = W._to_bf16_bits(x)
+                spec = W.TensorSpec(n % 7, (n,), dtype, "gauss", G, bits, rounding, seed=n + bits)
+                for out_dtype in ("f32", "bf16"):
+                    p, m, o = _oracle_roundtrip(x, spec, out_dtype)
+                    gp, gm, go = _run_single(api, x, spec, out_dtype)
+                    _assert_same(f"{dtype}/{rounding}/G{G}/B{bits}/n{n}/{out_dtype}", G, gp, gm, go, p, m, o, out_dtype)
+
+
+def test_empty_tensor_is_accepted_and_launches_nothing(api):
+    x = torch.empty(0, device="cuda")
+    p, m = api.fh_compress(x, 256, 4)
+    assert p.numel() == 0 and m.numel() == 0
+    o = api.fh_decompress(p, m, 0, 256, 4)
+    assert o.numel() == 0
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("rounding", ["nearest", "stochastic"])
+def test_degenerate_and_signed_zero_groups(api, rounding):
+    G = 64
+    blocks = [np.zeros(G), np.full(G, 2.5), np.full(G, -7.25), np.full(G, -0.0), np.full(G, 1e-38),
+              np.array([1.0, 1.0 + 2.0 ** -23] * (G // 2)), np.array([0.0, 2.0 ** -101] * (G // 2)),
+              np.array([-0.0, 0.0, 1.0, -0.0, 0.5, 0.0, 3.0, -0.0] * (G // 8)),
+              np.array([1e-40, 3e-40, 0.0, 2e-39] * (G // 4)),          # denormals
+              np.linspace(-1e30, 1e30, G)]
+    x = np.concatenate(blocks * 9).astype(f32)           # > one tile, ragged against 4096
+    for G_ in (64, 128, 256):
+        for bits in (2, 4, 8):
+            spec = W.TensorSpec(3, (x.size,), "f32", "gauss", G_, bits, rounding, seed=5)
+            p, m, o = _oracle_roundtrip(x, spec)
+            gp, gm, go = _run_single(api, x, spec)
+            _assert_same(f"degenerate/G{G_}/B{bits}", G_, gp, gm, go, p, m, o)
+
+
+def test_values_on_the_grid_and_zeros_come_back_exactly(api):
+    # Section 4.4.1: zeros must be preserved by decompression
+    w = W.small_variant(3)
+    spec0 = w.tensors[0]
+    x = W.materialise(w, spec0)
+    for rounding in ("nearest", "stochastic"):
+        for bits in (2, 4, 8):
+            spec = W.TensorSpec(1, spec0.shape, "f32", "relu6", 128, bits, rounding, seed=9)
+            gp, gm, go = _run_single(api, x, spec)
+            g = np.arange(x.size) // 128
+            z = (x == 0) & (gm.reshape(-1, 2)[g, 1] == 0)
+            assert z.sum() > x.size // 4
+            assert (go[z] == 0).all() and not np.signbit(go[z]).any()
+    L = 15
+    k = np.random.default_rng(3).integers(0, L + 1, 8192)
+    k[::256] = 0
+    k[1::256] = L
+    xg = (f32(-1.5) + k.astype(f32) * f32(2.0 ** -5)).astype(f32)
+    for rounding in ("nearest", "stochastic"):
+        spec = W.TensorSpec(0, (xg.size,), "f32", "gauss", 256, 4, rounding, seed=1)
+        _, _, go = _run_single(api, xg, spec)
+        assert np.array_equal(go, xg)
+
+
+def test_same_bits_whatever_the_batching_and_repeatable(api):
+    w = W.small_variant(2)
+    arrays = [W.materialise(w, s) for s in w.tensors]
+    first = _batch_roundtrip(api, w, w.tensors, arrays)
+    for rep in range(3):
+        again = _batch_roundtrip(api, w, w.tensors, arrays)
+        for a, b in zip(first, again):
+            assert torch.equal(a.packed, b.packed) and torch.equal(a.out, b.out)
+    for spec, x, e in zip(w.tensors, arrays, first):
+        gp, gm, go = _run_single(api, x, spec)
+        assert np.array_equal(gp, _host(e.packed)) and np.array_equal(go, _host(e.out))
+
+
+def test_more_items_than_one_launch_holds(api):
+    cap = api.batch_capacity()
+    n_items = 2 * cap + 5
+    rng = np.random.default_rng(5)
+    specs, arrays = [], []
+    for i in range(n_items):
+        n = int(rng.integers(1, 3000))
+        specs.append(W.TensorSpec(i, (n,), "f32", "gauss", (64, 128, 256)[i % 3], (2, 4, 8)[i % 3],
+                                  ("nearest", "stochastic")[i % 2], seed=i))
+        arrays.append(rng.standard_normal(n).astype(f32))
+    entries = _batch_roundtrip(api, None, specs, arrays)
+    for spec, x, e in zip(specs, arrays, entries):
+        p, m, o = _oracle_roundtrip(x, spec)
+        _assert_same(f"many/{spec.tensor_id}", spec.group_size, _host(e.packed), _host(e.meta), _host(e.out), p, m, o)
+
+
+def test_binding_refuses_host_tensors_and_bad_parameters(api):
+    with pytest.raises(ValueError):
+        api.fh_compress(torch.zeros(256), 256, 4)
+    x = torch.zeros(1024, device="cuda")
+    with pytest.raises(api.FedHybridError):
+        api.fh_compress(x, 100, 4)
+    with pytest.raises(api.FedHybridError):
+        api.fh_compress(x, 256, 3)
+    with pytest.raises(api.FedHybridError):
+        api.fh_compress(x, 256, 4, packed=torch.empty(16, dtype=torch.uint8, device="cuda"),
+                        meta=torch.empty((4, 2), device="cuda"))
+    with pytest.raises(TypeError):
+        api.fh_compress(x.double(), 256, 4)
+
+
+# ------------------------------------------------ full-size configurations ----
+
+def _full_config_check(api, idx, out_dtype="f32"):
+    """Whole configuration, batched exactly as the benchmark launches it, every byte
+    compared.  The oracle runs on host threads (it is single-threaded per tensor)."""
+    w = W.full_config(idx)
+    _say(f"[parity] full configuration {idx}: {w.name}, {w.nbytes / 2**20:.1f} MiB")
+    arrays = [None] * len(w.tensors)
+    expect = [None] * len(w.tensors)
+
+    def work(i):
+        x = W.materialise(w, w.tensors[i])
+        arrays[i] = x
+        expect[i] = _oracle_roundtrip(x, w.tensors[i], out_dtype)
+        return i
+
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        for i in pool.map(work, range(len(w.tensors))):
+            if i % 8 == 0:
+                _say(f"[parity]   oracle done for tensor {i}")
+    entries = _batch_roundtrip(api, w, w.tensors, arrays, out_dtype)
+    _say("[parity]   GPU round trip done, comparing")
+    for spec, e, (p, m, o) in zip(w.tensors, entries, expect):
+        _assert_same(f"{w.name}/t{spec.tensor_id}", spec.group_size, _host(e.packed), _host(e.meta), _host(e.out), p, m, o, out_dtype)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_full_configuration_bit_exact(api, idx):
+    _full_config_check(api, idx)
+
+
+@pytest.mark.timeout(600)
+def test_full_configuration_4_transformer_bf16(api):
+    _full_config_check(api, 4)
+
+
+@pytest.mark.timeout(600)
+def test_full_configuration_5_mixed_2gib(api):
+    _full_config_check(api, 5)
