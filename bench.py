@@ -150,7 +150,7 @@ def main() -> int:
         import oracle
         # bounded sample: the leading `frac` of every tensor (whole groups), so the mix of
         # bit widths, rounding modes and distributions is that of the workload
-        target_elems = 300_000_000
+        target_elems = 600_000_000
         frac = min(1.0, target_elems / max(1, w.numel))
         t_cpu = 0.0
         sample_bytes = 0

@@ -19,7 +19,10 @@ namespace {
 
 constexpr int kEPL = 8;                  // elements per lane
 constexpr int kRow = kWave * kEPL;       // elements one wave covers per row: 512
-constexpr int kRowsPerWave = 2;          // rows whose loads are issued before any is consumed
+#ifndef FH_COMPRESS_ROWS
+#define FH_COMPRESS_ROWS 2
+#endif
+constexpr int kRowsPerWave = FH_COMPRESS_ROWS;   // rows whose loads are issued before any is consumed
 constexpr int kWaveSpan = kRowsPerWave * kRow;
 constexpr int kTile = (kBlock / kWave) * kWaveSpan;   // 4096 elements per workgroup
 
@@ -80,11 +83,11 @@ template <int B>
 __device__ __forceinline__ void store_codes(uint8_t* dst, uint32_t w0, uint32_t w1)
 {
     if constexpr (B == 8) {
-        *reinterpret_cast<u32x2*>(dst) = u32x2{w0, w1};
+        code_store(reinterpret_cast<u32x2*>(dst), u32x2{w0, w1});
     } else if constexpr (B == 4) {
-        *reinterpret_cast<uint32_t*>(dst) = w0;
+        code_store(reinterpret_cast<uint32_t*>(dst), w0);
     } else {
-        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)w0;
+        code_store(reinterpret_cast<uint16_t*>(dst), (uint16_t)w0);
     }
 }
 
@@ -93,7 +96,7 @@ template <typename InT> struct Loader;
 template <> struct Loader<float> {
     __device__ static __forceinline__ void full(const void* base, int64_t i0, float (&x)[kEPL]) {
         const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + i0);
-        const f32x4 a = p[0], b = p[1];
+        const f32x4 a = stream_load(p), b = stream_load(p + 1);
         x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
         x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
     }
@@ -104,7 +107,7 @@ template <> struct Loader<float> {
 
 template <> struct Loader<uint16_t> {   // bf16 bit patterns; widening is exact
     __device__ static __forceinline__ void full(const void* base, int64_t i0, float (&x)[kEPL]) {
-        const u32x4 a = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + i0);
+        const u32x4 a = stream_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + i0));
         x[0] = bf16_lo(a.x); x[1] = bf16_hi(a.x); x[2] = bf16_lo(a.y); x[3] = bf16_hi(a.y);
         x[4] = bf16_lo(a.z); x[5] = bf16_hi(a.z); x[6] = bf16_lo(a.w); x[7] = bf16_hi(a.w);
     }

@@ -17,7 +17,10 @@ namespace fh {
 
 namespace {
 
-constexpr int kRowsPerWave = 4;
+#ifndef FH_DECOMPRESS_ROWS
+#define FH_DECOMPRESS_ROWS 4
+#endif
+constexpr int kRowsPerWave = FH_DECOMPRESS_ROWS;   // rows whose loads are issued before any store
 
 template <typename OutT> struct OutTraits;
 template <> struct OutTraits<float>    { static constexpr int EPL = 4; };
@@ -59,6 +62,26 @@ __device__ __forceinline__ float dequant(uint32_t bitsword, int j, float scale, 
     return __builtin_fmaf((float)code, scale, zero);          // single rounding
 }
 
+// Restore the EPL elements of one lane from its code bits and its group's meta.
+template <int EPL, int B>
+__device__ __forceinline__ void restore(uint32_t c0, uint32_t c1, f32x2 m, float (&v)[EPL])
+{
+    constexpr int PER_WORD = 32 / B;                          // codes per 32-bit word
+#pragma unroll
+    for (int j = 0; j < EPL; ++j)
+        v[j] = dequant<B>((j < PER_WORD) ? c0 : c1, j % PER_WORD, m.x, m.y);
+}
+
+__device__ __forceinline__ u32x4 pack_bf16x8(const float (&v)[8])
+{
+    u32x4 o;
+    o.x = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
+    o.y = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
+    o.z = bf16_bits(v[4]) | (bf16_bits(v[5]) << 16);
+    o.w = bf16_bits(v[6]) | (bf16_bits(v[7]) << 16);
+    return o;
+}
+
 template <typename OutT, int G, int B>
 __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32_t tile)
 {
@@ -66,39 +89,50 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
     constexpr int ROW = kWave * EPL;
     constexpr int WAVE_SPAN = kRowsPerWave * ROW;
     constexpr int TILE = (kBlock / kWave) * WAVE_SPAN;
-    constexpr int PER_WORD = 32 / B;                          // codes per 32-bit word
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t numel = it.numel;
     const int64_t wave_base = (int64_t)tile * TILE + (int64_t)wave * WAVE_SPAN;
     if (wave_base >= numel) return;
 
-    const bool interior = wave_base + WAVE_SPAN <= numel;
-    uint32_t c0[kRowsPerWave], c1[kRowsPerWave];
-    f32x2 m[kRowsPerWave];
+    if (wave_base + WAVE_SPAN <= numel) {
+        // ---- interior: all loads first, then one 128-bit store per lane and row ----
+        uint32_t c0[kRowsPerWave], c1[kRowsPerWave];
+        f32x2 m[kRowsPerWave];
 #pragma unroll
-    for (int r = 0; r < kRowsPerWave; ++r) {
-        const int64_t i0 = wave_base + r * ROW + lane * EPL;
-        c0[r] = 0u; c1[r] = 0u; m[r] = f32x2{0.0f, 0.0f};
-        if (interior || i0 < numel) {
-            // a lane whose first element exists reads inside the padded code stream and
-            // inside the meta array (its group exists)
+        for (int r = 0; r < kRowsPerWave; ++r) {
+            const int64_t i0 = wave_base + r * ROW + lane * EPL;
             load_codes<EPL, B>(it.packed, i0, c0[r], c1[r]);
             m[r] = *reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v));
         }
-    }
 #pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r) {
+            const int64_t i0 = wave_base + r * ROW + lane * EPL;
+            float v[EPL];
+            restore<EPL, B>(c0[r], c1[r], m[r], v);
+            if constexpr (EPL == 4) {
+                stream_store(reinterpret_cast<f32x4*>(static_cast<float*>(it.out) + i0), f32x4{v[0], v[1], v[2], v[3]});
+            } else {
+                stream_store(reinterpret_cast<u32x4*>(static_cast<uint16_t*>(it.out) + i0), pack_bf16x8(v));
+            }
+        }
+        return;
+    }
+
+    // ---- edge: the tensor ends inside this wave's span ----
     for (int r = 0; r < kRowsPerWave; ++r) {
         const int64_t i0 = wave_base + r * ROW + lane * EPL;
+        if (i0 >= numel) continue;
+        // a lane whose first element exists reads inside the padded code stream and inside
+        // the meta array (its group exists)
+        uint32_t c0, c1;
+        load_codes<EPL, B>(it.packed, i0, c0, c1);
+        const f32x2 m = *reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v));
         float v[EPL];
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-            const uint32_t word = (j < PER_WORD) ? c0[r] : c1[r];
-            v[j] = dequant<B>(word, j % PER_WORD, m[r].x, m[r].y);
-        }
+        restore<EPL, B>(c0, c1, m, v);
         if constexpr (EPL == 4) {
             float* dst = static_cast<float*>(it.out) + i0;
-            if (interior || i0 + EPL <= numel) {
+            if (i0 + EPL <= numel) {
                 *reinterpret_cast<f32x4*>(dst) = f32x4{v[0], v[1], v[2], v[3]};
             } else {
 #pragma unroll
@@ -106,13 +140,8 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
             }
         } else {
             uint16_t* dst = static_cast<uint16_t*>(it.out) + i0;
-            if (interior || i0 + EPL <= numel) {
-                u32x4 o;
-                o.x = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
-                o.y = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
-                o.z = bf16_bits(v[4]) | (bf16_bits(v[5]) << 16);
-                o.w = bf16_bits(v[6]) | (bf16_bits(v[7]) << 16);
-                *reinterpret_cast<u32x4*>(dst) = o;
+            if (i0 + EPL <= numel) {
+                *reinterpret_cast<u32x4*>(dst) = pack_bf16x8(v);
             } else {
 #pragma unroll
                 for (int j = 0; j < EPL; ++j) if (i0 + j < numel) dst[j] = (uint16_t)bf16_bits(v[j]);
@@ -124,7 +153,14 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
 template <typename OutT, int G>
 __global__ __launch_bounds__(kBlock) void decompress_kernel(const DecompressBatch args)
 {
+    // Tiles are taken from the end of the set backwards: the backward pass needs the
+    // tensors in the reverse of the order the forward pass saved them, and the codes
+    // written last are the ones most likely still held by the memory-side cache.
+#ifndef FH_DECOMPRESS_FORWARD
+    const uint32_t bid = gridDim.x - 1u - blockIdx.x;
+#else
     const uint32_t bid = blockIdx.x;
+#endif
     int lo = 0, hi = args.count;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;

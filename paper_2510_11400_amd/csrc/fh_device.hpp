@@ -15,6 +15,48 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float    f32x2 __attribute__((ext_vector_type(2)));
 
+// ---- streaming memory access --------------------------------------------------------
+// The activation, the code stream and the restored tensor are each touched once per
+// call, so they are loaded and stored with the non-temporal hint where that measures
+// faster (FH_NT_LOAD / FH_NT_STORE, decided by measurement on MI355X).
+#ifndef FH_NT_LOAD
+#define FH_NT_LOAD 1
+#endif
+#ifndef FH_NT_STORE
+#define FH_NT_STORE 1
+#endif
+template <typename T>
+__device__ __forceinline__ T stream_load(const T* p)
+{
+#if FH_NT_LOAD
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+#ifndef FH_NT_CODE_STORE
+#define FH_NT_CODE_STORE 0
+#endif
+// The code stream is small and is read back by the backward side.
+template <typename T>
+__device__ __forceinline__ void code_store(T* p, T v)
+{
+#if FH_NT_CODE_STORE
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+template <typename T>
+__device__ __forceinline__ void stream_store(T* p, T v)
+{
+#if FH_NT_STORE
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
 // ---- min / max ---------------------------------------------------------------------
 // Written as the machine instructions themselves.  The inputs are finite by contract,
 // so no NaN canonicalisation is wanted in front of them, and the result must not
