@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="workload configuration 1..5 (default 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
+                    help="also run N plain 1 GiB device copies before the timed region, so that a "
+                         "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE against a known size")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()
@@ -108,6 +111,14 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
+    if args.copy_calibration > 0:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calibration):
+            dst.copy_(src)                      # plain device copy: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
@@ -141,9 +152,13 @@ def main() -> int:
             "decompress_kernel": {"ms": round(d_ms, 4), "bytes": dbytes, "GBps": round(dbytes / d_ms / 1e6, 1)},
         }
         dom = "compress_kernel" if c_ms >= d_ms else "decompress_kernel"
+        # measured HBM bytes per launch of that kernel, from the committed counter summary of
+        # this workload; None when there is none or the kernel sources changed since
+        from paper_2510_11400_amd.profile_summary import read_traffic
+        traffic = read_traffic(os.path.join(ROOT, "profiles", f"compress_decompress_{w.name}.txt")).get(dom)
         result["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": round(kern[dom]["GBps"] / HBM_PEAK_GBS, 4),
-                              "traffic": None}
+                              "traffic": traffic}
         result["kernels"] = kern
 
     if not args.no_cpu_baseline:

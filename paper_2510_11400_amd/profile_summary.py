@@ -1,0 +1,148 @@
+"""Turn rocprofv3 CSV output of `bench.py` runs into the short text summary kept
+under profiles/ (per-kernel durations, HBM traffic per launch from the FETCH_SIZE and
+WRITE_SIZE counters, the copy-kernel calibration of those counters), and read such a
+summary back for bench.py's `roofline.traffic`.
+
+Usage (after the three rocprofv3 runs described in the summary's header):
+    python -m paper_2510_11400_amd.profile_summary --trace DIR --fetch DIR --write DIR \
+        --bench-json FILE --out profiles/NAME.txt
+"""
+from __future__ import annotations
+
+import argparse
+import csv
+import glob
+import hashlib
+import json
+import os
+from collections import defaultdict
+from typing import Dict, Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+KERNEL_SOURCES = ("fh_device.hpp", "fh_kernels.hpp", "fh_compress.hip", "fh_decompress.hip", "fh_abi.hip")
+KERNELS = {"compress_kernel": "::compress_kernel<", "decompress_kernel": "::decompress_kernel<"}
+COPY_MARKERS = ("copyBuffer", "copy_kernel", "CopyKernel")
+
+
+def kernel_source_digest() -> str:
+    """sha256 over the kernel sources: counters are only valid for the code they were taken on."""
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(HERE, "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def _one(pattern: str) -> str:
+    hits = sorted(glob.glob(pattern, recursive=True))
+    if not hits:
+        raise FileNotFoundError(pattern)
+    return hits[0]
+
+
+def _classify(name: str) -> Optional[str]:
+    for key, marker in KERNELS.items():
+        if marker in name:
+            return key
+    if any(m in name for m in COPY_MARKERS):
+        return "copy"
+    return None
+
+
+def _durations(trace_dir: str) -> Dict[str, dict]:
+    out = defaultdict(lambda: {"calls": 0, "total_ns": 0})
+    with open(_one(os.path.join(trace_dir, "**", "*kernel_trace.csv"))) as fh:
+        for row in csv.DictReader(fh):
+            k = _classify(row["Kernel_Name"])
+            if k:
+                out[k]["calls"] += 1
+                out[k]["total_ns"] += int(row["End_Timestamp"]) - int(row["Start_Timestamp"])
+    return out
+
+
+def _counter(pmc_dir: str, counter: str) -> Dict[str, float]:
+    """Mean counter value (KiB) per dispatch for each classified kernel."""
+    acc = defaultdict(list)
+    with open(_one(os.path.join(pmc_dir, "**", "*counter_collection.csv"))) as fh:
+        for row in csv.DictReader(fh):
+            if row["Counter_Name"] != counter:
+                continue
+            k = _classify(row["Kernel_Name"])
+            if k:
+                acc[k].append(float(row["Counter_Value"]))
+    return {k: sum(v) / len(v) for k, v in acc.items()}
+
+
+def summarise(trace_dir, fetch_dir, write_dir, bench_json, copy_bytes, commands) -> str:
+    dur = _durations(trace_dir)
+    fetch = _counter(fetch_dir, "FETCH_SIZE")
+    write = _counter(write_dir, "WRITE_SIZE")
+    bench = json.loads(open(bench_json).read().strip().splitlines()[-1])
+    # a copy of `copy_bytes` reads and writes that many bytes: the factor turns KiB counts into bytes
+    f_factor = copy_bytes / (fetch["copy"] * 1024.0)
+    w_factor = copy_bytes / (write["copy"] * 1024.0)
+    lines = ["# rocprofv3 summary: " + bench["config"]["workload"],
+             "# commands (each from the repository root, after `cd /tmp && export TMPDIR=/tmp`):"]
+    lines += ["#   " + c for c in commands]
+    lines += ["kernel_source_sha256 = " + kernel_source_digest(),
+              f"workload = {bench['config']['workload']}",
+              f"calibration_copy_bytes = {copy_bytes}",
+              f"fetch_size_factor = {f_factor:.4f}    # true bytes / (FETCH_SIZE KiB * 1024), from the plain copy",
+              f"write_size_factor = {w_factor:.4f}    # true bytes / (WRITE_SIZE KiB * 1024), from the plain copy",
+              ""]
+    for k in KERNELS:
+        d = dur[k]
+        avg_us = d["total_ns"] / max(1, d["calls"]) / 1e3
+        fb = fetch[k] * 1024.0 * f_factor
+        wb = write[k] * 1024.0 * w_factor
+        alg = bench["kernels"][k]["bytes"]
+        lines += [f"[{k}]",
+                  f"calls = {d['calls']}",
+                  f"avg_duration_us = {avg_us:.1f}    # rocprofv3 --kernel-trace",
+                  f"bench_event_duration_us = {bench['kernels'][k]['ms'] * 1e3:.1f}    # HIP events inside bench.py, same run",
+                  f"fetch_size_kib_per_launch = {fetch[k]:.0f}",
+                  f"write_size_kib_per_launch = {write[k]:.0f}",
+                  f"traffic_bytes_per_launch = {fb + wb:.0f}",
+                  f"algorithmic_bytes_per_launch = {alg}",
+                  f"traffic_over_algorithmic = {(fb + wb) / alg:.4f}",
+                  f"achieved_GBps_algorithmic = {alg / avg_us / 1e3:.1f}",
+                  ""]
+    lines += ["[bench_line]", json.dumps(bench)]
+    return "\n".join(lines) + "\n"
+
+
+def read_traffic(path: str) -> Dict[str, float]:
+    """{kernel: HBM bytes per launch} from a summary, or {} when it was taken on other kernel code."""
+    if not os.path.exists(path):
+        return {}
+    out, section, digest = {}, None, None
+    with open(path) as fh:
+        for raw in fh:
+            line = raw.split("#")[0].strip()
+            if line.startswith("[") and line.endswith("]"):
+                section = line[1:-1]
+            elif line.startswith("kernel_source_sha256"):
+                digest = line.split("=")[1].strip()
+            elif line.startswith("traffic_bytes_per_launch") and section in KERNELS:
+                out[section] = float(line.split("=")[1])
+    return out if digest == kernel_source_digest() else {}
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--trace", required=True)
+    ap.add_argument("--fetch", required=True)
+    ap.add_argument("--write", required=True)
+    ap.add_argument("--bench-json", required=True)
+    ap.add_argument("--copy-bytes", type=int, default=1 << 30)
+    ap.add_argument("--out", required=True)
+    ap.add_argument("--command", action="append", default=[])
+    a = ap.parse_args()
+    text = summarise(a.trace, a.fetch, a.write, a.bench_json, a.copy_bytes, a.command)
+    with open(a.out, "w") as fh:
+        fh.write(text)
+    print(text)
+
+
+if __name__ == "__main__":
+    main()
