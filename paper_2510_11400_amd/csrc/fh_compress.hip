@@ -31,52 +31,109 @@ template <> struct Log2<64>  { static constexpr int v = 6; };
 template <> struct Log2<128> { static constexpr int v = 7; };
 template <> struct Log2<256> { static constexpr int v = 8; };
 
-// Quantise and pack the 8 values of one lane.  `valid` = number of leading elements
-// that exist (8 except in the last lanes of a tensor); codes of the others are 0.
-template <int B, bool STOCH>
+// ---- quantise + pack ---------------------------------------------------------------
+// Each element first becomes a 32-bit word with its code in one known byte and zeros
+// in the code's unused upper bits; v_perm_b32 then gathers those bytes.
+//
+// nearest:    r = q + 2^23 rounds q to an integer with ties to even (the sum lies in
+//             [2^23, 2^24), where the float spacing is 1), and leaves it in the low
+//             mantissa bits: byte 0 of r is rint(q).
+// stochastic: with Q = q * 2^16 (exact) and C = ceil(Q),
+//                 floor(q) + [h / 2^16 < q - floor(q)]  ==  (C + 65535 - h) >> 16
+//             because h < frac(q) * 2^16  <=>  h < ceil(frac(q) * 2^16)  <=>  the low
+//             16 bits of C plus (65535 - h) carry.  The sum is below 2^24, so byte 2
+//             is the code.  -C comes from v_cvt_flr_i32_f32(-Q); 65535 - h is a
+//             half-word of the complemented random word, picked by SDWA in the subtract.
+template <bool STOCH> struct CodeByte { static constexpr uint32_t pos = STOCH ? 2u : 0u; };
+
+template <int HALF>
+__device__ __forceinline__ uint32_t halfword_minus(uint32_t not_word, int neg_c)
+{
+    uint32_t d;
+    if constexpr (HALF == 0)
+        asm volatile("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:DWORD"
+                     : "=v"(d) : "v"(not_word), "v"(neg_c));
+    else
+        asm volatile("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:DWORD"
+                     : "=v"(d) : "v"(not_word), "v"(neg_c));
+    return d;
+}
+
+// [code(a), code(b), 0, 0] from the code bytes of two element words.
+template <uint32_t POS>
+__device__ __forceinline__ uint32_t pair_bytes(uint32_t a, uint32_t b)
+{
+    return __builtin_amdgcn_perm(b, a, 0x0c0c0000u | ((4u + POS) << 8) | POS);
+}
+// [code(a), code(b), code(c), code(d)]
+template <uint32_t POS>
+__device__ __forceinline__ uint32_t quad_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    return __builtin_amdgcn_perm(pair_bytes<POS>(c, d), pair_bytes<POS>(a, b), 0x05040100u);
+}
+
+// Quantise the 8 values of one lane and pack their codes.  `valid` = number of leading
+// elements that exist (8 except in the last lanes of a tensor); the others get code 0.
+// (ctr_lo, ctr_hi) is the Philox block index of these 8 elements.
+template <int B, bool STOCH, bool FULL>
 __device__ __forceinline__ void quantise8(const float (&x)[kEPL], float mn, float inv, int valid,
-                                          int64_t i0, uint64_t seed, uint64_t tensor_id,
+                                          uint32_t ctr_lo, uint32_t ctr_hi, uint64_t seed, uint64_t tensor_id,
                                           uint32_t& w0, uint32_t& w1)
 {
     constexpr float Lf = (float)((1 << B) - 1);
-    uint32_t code[kEPL];
-    u32x4 rnd = {0u, 0u, 0u, 0u};
+    constexpr uint32_t POS = CodeByte<STOCH>::pos;
+    uint32_t e[kEPL];
+    uint32_t nrnd[4] = {0u, 0u, 0u, 0u};
     if constexpr (STOCH) {
-        const uint64_t blk = (uint64_t)i0 >> 3;
-        rnd = philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32),
-                            (uint32_t)tensor_id, (uint32_t)(tensor_id >> 32),
-                            (uint32_t)seed, (uint32_t)(seed >> 32));
+        const u32x4 rnd = philox4x32_10(ctr_lo, ctr_hi, (uint32_t)tensor_id, (uint32_t)(tensor_id >> 32),
+                                        (uint32_t)seed, (uint32_t)(seed >> 32));
+        nrnd[0] = ~rnd.x; nrnd[1] = ~rnd.y; nrnd[2] = ~rnd.z; nrnd[3] = ~rnd.w;
     }
 #pragma unroll
     for (int j = 0; j < kEPL; ++j) {
         const float t = x[j] - mn;
         float q = t * inv;
         q = __builtin_amdgcn_fmed3f(q, 0.0f, Lf);            // clamp to [0, L]
-        uint32_t c;
         if constexpr (STOCH) {
-            const float k = __builtin_floorf(q);
-            const float f = q - k;                            // exact
-            const uint32_t word = rnd[j >> 1];
-            const uint32_t h = (j & 1) ? (word >> 16) : (word & 0xFFFFu);
-            const float u = (float)h * 0x1p-16f;
-            c = (uint32_t)k + (u < f ? 1u : 0u);
+            const float Q = q * 65536.0f;                     // exact
+            int neg_c;
+            asm volatile("v_cvt_flr_i32_f32_e64 %0, -%1" : "=v"(neg_c) : "v"(Q));   // -ceil(Q)
+            e[j] = (j & 1) ? halfword_minus<1>(nrnd[j >> 1], neg_c) : halfword_minus<0>(nrnd[j >> 1], neg_c);
         } else {
-            c = (uint32_t)__builtin_rintf(q);                 // v_rndne_f32: ties to even
+            e[j] = __builtin_bit_cast(uint32_t, q + 0x1p23f);
         }
-        code[j] = (j < valid) ? c : 0u;
+        if constexpr (!FULL) e[j] = (j < valid) ? e[j] : 0u;
     }
     if constexpr (B == 8) {
-        w0 = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
-        w1 = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
-    } else if constexpr (B == 4) {
-        w0 = code[0] | (code[1] << 4) | (code[2] << 8) | (code[3] << 12) |
-             (code[4] << 16) | (code[5] << 20) | (code[6] << 24) | (code[7] << 28);
+        w0 = quad_bytes<POS>(e[0], e[1], e[2], e[3]);
+        w1 = quad_bytes<POS>(e[4], e[5], e[6], e[7]);
+    } else if constexpr (B == 4) {                            // byte k = code(2k) | code(2k+1) << 4
+        const uint32_t even = quad_bytes<POS>(e[0], e[2], e[4], e[6]);
+        const uint32_t odd = quad_bytes<POS>(e[1], e[3], e[5], e[7]);
+        w0 = (odd << 4) | even;
         w1 = 0u;
-    } else {
-        w0 = code[0] | (code[1] << 2) | (code[2] << 4) | (code[3] << 6) |
-             (code[4] << 8) | (code[5] << 10) | (code[6] << 12) | (code[7] << 14);
+    } else {                                                  // byte k = codes 4k .. 4k+3, two bits each
+        const uint32_t c0 = pair_bytes<POS>(e[0], e[4]), c1 = pair_bytes<POS>(e[1], e[5]);
+        const uint32_t c2 = pair_bytes<POS>(e[2], e[6]), c3 = pair_bytes<POS>(e[3], e[7]);
+        w0 = (c3 << 6) | ((c2 << 4) | ((c1 << 2) | c0));
         w1 = 0u;
     }
+}
+
+// scale = range / L and inv = L / range with ONE division per lane: even lanes divide
+// range by L, odd lanes L by range, and neighbours (always in the same group, so they
+// hold the same range) trade results.
+template <int B>
+__device__ __forceinline__ void scale_and_inverse(float range, bool odd_lane, float& scale, float& inv)
+{
+    constexpr float Lf = (float)((1 << B) - 1);
+    const bool degenerate = range < 0x1p-100f;
+    const float num = odd_lane ? Lf : range;
+    const float den = odd_lane ? range : Lf;
+    const float mine = num / den;                             // IEEE-correct division
+    const float other = from_pair_lane(mine);
+    scale = degenerate ? 0.0f : (odd_lane ? other : mine);
+    inv = degenerate ? 0.0f : (odd_lane ? mine : other);
 }
 
 template <int B>
@@ -94,25 +151,25 @@ __device__ __forceinline__ void store_codes(uint8_t* dst, uint32_t w0, uint32_t 
 template <typename InT> struct Loader;
 
 template <> struct Loader<float> {
-    __device__ static __forceinline__ void full(const void* base, int64_t i0, float (&x)[kEPL]) {
-        const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + i0);
+    __device__ static __forceinline__ void full(const float* base, uint32_t i0, float (&x)[kEPL]) {
+        const f32x4* p = reinterpret_cast<const f32x4*>(base + i0);
         const f32x4 a = stream_load(p), b = stream_load(p + 1);
         x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
         x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
     }
-    __device__ static __forceinline__ float one(const void* base, int64_t i) {
-        return static_cast<const float*>(base)[i];
+    __device__ static __forceinline__ float one(const float* base, uint32_t i) {
+        return base[i];
     }
 };
 
 template <> struct Loader<uint16_t> {   // bf16 bit patterns; widening is exact
-    __device__ static __forceinline__ void full(const void* base, int64_t i0, float (&x)[kEPL]) {
-        const u32x4 a = stream_load(reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + i0));
+    __device__ static __forceinline__ void full(const uint16_t* base, uint32_t i0, float (&x)[kEPL]) {
+        const u32x4 a = stream_load(reinterpret_cast<const u32x4*>(base + i0));
         x[0] = bf16_lo(a.x); x[1] = bf16_hi(a.x); x[2] = bf16_lo(a.y); x[3] = bf16_hi(a.y);
         x[4] = bf16_lo(a.z); x[5] = bf16_hi(a.z); x[6] = bf16_lo(a.w); x[7] = bf16_hi(a.w);
     }
-    __device__ static __forceinline__ float one(const void* base, int64_t i) {
-        return __builtin_bit_cast(float, (uint32_t)static_cast<const uint16_t*>(base)[i] << 16);
+    __device__ static __forceinline__ float one(const uint16_t* base, uint32_t i) {
+        return __builtin_bit_cast(float, (uint32_t)base[i] << 16);
     }
 };
 
@@ -120,42 +177,48 @@ template <typename InT, int G, int B, bool STOCH>
 __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t tile)
 {
     constexpr int LPG = G / kEPL;                             // lanes per group
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int LOGG = Log2<G>::v;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool odd_lane = lane & 1u;
     const int64_t numel = it.numel;
+    // everything derived from wave_base is wave-uniform and lives in scalar registers;
+    // lanes add 32-bit offsets
     const int64_t wave_base = (int64_t)tile * kTile + (int64_t)wave * kWaveSpan;
     const int64_t padded_elems = (int64_t)(it.packed_padded * 8u / (unsigned)B);
     const int64_t extent = numel > padded_elems ? numel : padded_elems;
     if (wave_base >= extent) return;
+
+    const InT* xw = static_cast<const InT*>(it.x) + wave_base;
+    uint8_t* pw = it.packed + ((uint64_t)wave_base * B >> 3);
+    float* mw = it.meta + 2 * (wave_base >> LOGG);
+    const uint32_t lane_elem = lane * kEPL;                   // first element of the lane inside a row
 
     if (wave_base + kWaveSpan <= numel) {
         // ---- interior: every element exists, every access is a full vector ----
         float x[kRowsPerWave][kEPL];
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r)
-            Loader<InT>::full(it.x, wave_base + r * kRow + lane * kEPL, x[r]);
+            Loader<InT>::full(xw, r * kRow + lane_elem, x[r]);
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r) {
-            const int64_t i0 = wave_base + r * kRow + lane * kEPL;
+            const uint32_t e0 = r * kRow + lane_elem;         // element offset from wave_base
             float mn = vmin3(x[r][0], x[r][1], x[r][2]), mx = vmax3(x[r][0], x[r][1], x[r][2]);
             mn = vmin3(mn, x[r][3], x[r][4]);  mx = vmax3(mx, x[r][3], x[r][4]);
             mn = vmin3(mn, x[r][5], x[r][6]);  mx = vmax3(mx, x[r][5], x[r][6]);
             mn = vmin(mn, x[r][7]);            mx = vmax(mx, x[r][7]);
             group_minmax<LPG>(mn, mx);
-            float scale, zero, inv;
-            {
-                constexpr float Lf = (float)((1 << B) - 1);
-                const float range = mx - mn;
-                const bool degenerate = range < 0x1p-100f;
-                zero = mn + 0.0f;                             // -0.0 -> +0.0
-                scale = degenerate ? 0.0f : range / Lf;       // IEEE-correct divisions
-                inv = degenerate ? 0.0f : Lf / range;
-            }
+            float scale, inv;
+            scale_and_inverse<B>(mx - mn, odd_lane, scale, inv);
             if ((lane & (LPG - 1)) == 0)
-                *reinterpret_cast<f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v)) = f32x2{scale, zero};
+                *reinterpret_cast<f32x2*>(mw + 2 * (e0 >> LOGG)) = f32x2{scale, mn + 0.0f};   // -0.0 -> +0.0
+            // a row starts on a multiple of 512 elements = 64 Philox blocks, so adding the
+            // lane never carries out of the low counter word
+            const uint64_t blk = (uint64_t)(wave_base + r * kRow) >> 3;
             uint32_t w0, w1;
-            quantise8<B, STOCH>(x[r], mn, inv, kEPL, i0, it.seed, it.tensor_id, w0, w1);
-            store_codes<B>(it.packed + (uint64_t)i0 * B / 8, w0, w1);
+            quantise8<B, STOCH, true>(x[r], mn, inv, kEPL, (uint32_t)blk + lane, (uint32_t)(blk >> 32),
+                                      it.seed, it.tensor_id, w0, w1);
+            store_codes<B>(pw + (e0 * B >> 3), w0, w1);
         }
         return;
     }
@@ -165,7 +228,8 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
     for (int r = 0; r < kRowsPerWave; ++r) {
         const int64_t row_base = wave_base + r * kRow;
         if (row_base >= extent) break;                        // wave-uniform
-        const int64_t i0 = row_base + lane * kEPL;
+        const uint32_t e0 = r * kRow + lane_elem;
+        const int64_t i0 = row_base + lane_elem;
         const int64_t left = numel - i0;
         const int valid = left >= kEPL ? kEPL : (left > 0 ? (int)left : 0);
         float x[kEPL];
@@ -173,7 +237,7 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
 #pragma unroll
         for (int j = 0; j < kEPL; ++j) {
             const bool ok = j < valid;
-            x[j] = ok ? Loader<InT>::one(it.x, i0 + j) : 0.0f;
+            x[j] = ok ? Loader<InT>::one(xw, e0 + j) : 0.0f;
             const float lo = ok ? x[j] : __builtin_inff();
             const float hi = ok ? x[j] : -__builtin_inff();
             mn = j == 0 ? lo : vmin(mn, lo);
@@ -181,21 +245,19 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
         }
         group_minmax<LPG>(mn, mx);
         if (mn > mx) { mn = 0.0f; mx = 0.0f; }                // a run with no element at all
-        constexpr float Lf = (float)((1 << B) - 1);
-        const float range = mx - mn;
-        const bool degenerate = range < 0x1p-100f;
-        const float zero = mn + 0.0f;
-        const float scale = degenerate ? 0.0f : range / Lf;
-        const float inv = degenerate ? 0.0f : Lf / range;
+        float scale, inv;
+        scale_and_inverse<B>(mx - mn, odd_lane, scale, inv);
         // a group exists iff its first element does
         if ((lane & (LPG - 1)) == 0 && i0 < numel)
-            *reinterpret_cast<f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v)) = f32x2{scale, zero};
+            *reinterpret_cast<f32x2*>(mw + 2 * (e0 >> LOGG)) = f32x2{scale, mn + 0.0f};
+        const uint64_t blk = (uint64_t)row_base >> 3;
         uint32_t w0, w1;
-        quantise8<B, STOCH>(x, mn, inv, valid, i0, it.seed, it.tensor_id, w0, w1);
+        quantise8<B, STOCH, false>(x, mn, inv, valid, (uint32_t)blk + lane, (uint32_t)(blk >> 32),
+                                   it.seed, it.tensor_id, w0, w1);
         // chunks are size-aligned and the padded length is a multiple of 16, so a chunk is
         // either wholly inside the buffer or wholly outside
         const uint64_t off = (uint64_t)i0 * B / 8;
-        if (off < it.packed_padded) store_codes<B>(it.packed + off, w0, w1);
+        if (off < it.packed_padded) store_codes<B>(pw + (e0 * B >> 3), w0, w1);
     }
 }
 

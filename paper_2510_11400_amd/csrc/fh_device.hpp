@@ -88,27 +88,36 @@ __device__ __forceinline__ float vmax3(float a, float b, float c)
     return r;
 }
 
-// ---- DPP lane exchange -----------------------------------------------------------
-// min(v, v permuted inside its 16-lane row) in one instruction.  A DPP operand read
-// needs two wait states after a VALU write of the same register, which the compiler's
-// hazard pass cannot see inside an asm block, hence the s_nop.
-#define FH_DPP_OP(NAME, OPC, CTRL)                                                       \
-    __device__ __forceinline__ float NAME(float v)                                       \
-    {                                                                                    \
-        float r;                                                                         \
-        asm volatile("s_nop 1\n\t" OPC " %0, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf" \
-                     : "=v"(r) : "v"(v));                                                \
-        return r;                                                                        \
+// ---- cross-lane min / max ----------------------------------------------------------
+// One DPP step folds a lane with its partner inside the 16-lane row: xor 1 and xor 2
+// through quad_perm, then row_half_mirror (lane i <-> 7-i of its 8) once quads are
+// uniform, then row_mirror (i <-> 15-i) once halves are uniform.  min and max chains
+// are interleaved so that each DPP read sits two wait states after the VALU write of
+// its register (a hazard the compiler cannot see inside an asm block): the other
+// chain's instruction plus one s_nop.  The block opens and closes with s_nop 1 so it
+// is safe against whatever the compiler schedules around it.
+#define FH_DPP_STEP(CTRL)                                                           \
+    "v_min_f32_dpp %0, %0, %0 " CTRL " row_mask:0xf bank_mask:0xf\n\t"              \
+    "v_max_f32_dpp %1, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf\n\t"
+template <int LANES>
+__device__ __forceinline__ void row_minmax(float& mn, float& mx)
+{
+    static_assert(LANES == 4 || LANES == 8 || LANES == 16, "within one DPP row");
+    if constexpr (LANES == 4) {
+        asm volatile("s_nop 1\n\t" FH_DPP_STEP("quad_perm:[1,0,3,2]") "s_nop 0\n\t"
+                     FH_DPP_STEP("quad_perm:[2,3,0,1]") "s_nop 1" : "+v"(mn), "+v"(mx));
+    } else if constexpr (LANES == 8) {
+        asm volatile("s_nop 1\n\t" FH_DPP_STEP("quad_perm:[1,0,3,2]") "s_nop 0\n\t"
+                     FH_DPP_STEP("quad_perm:[2,3,0,1]") "s_nop 0\n\t"
+                     FH_DPP_STEP("row_half_mirror") "s_nop 1" : "+v"(mn), "+v"(mx));
+    } else {
+        asm volatile("s_nop 1\n\t" FH_DPP_STEP("quad_perm:[1,0,3,2]") "s_nop 0\n\t"
+                     FH_DPP_STEP("quad_perm:[2,3,0,1]") "s_nop 0\n\t"
+                     FH_DPP_STEP("row_half_mirror") "s_nop 0\n\t"
+                     FH_DPP_STEP("row_mirror") "s_nop 1" : "+v"(mn), "+v"(mx));
     }
-FH_DPP_OP(min_xor1,   "v_min_f32_dpp", "quad_perm:[1,0,3,2]")   // lane i with lane i^1
-FH_DPP_OP(max_xor1,   "v_max_f32_dpp", "quad_perm:[1,0,3,2]")
-FH_DPP_OP(min_xor2,   "v_min_f32_dpp", "quad_perm:[2,3,0,1]")   // lane i with lane i^2
-FH_DPP_OP(max_xor2,   "v_max_f32_dpp", "quad_perm:[2,3,0,1]")
-FH_DPP_OP(min_half,   "v_min_f32_dpp", "row_half_mirror")       // lane i with lane 7-i of its 8
-FH_DPP_OP(max_half,   "v_max_f32_dpp", "row_half_mirror")
-FH_DPP_OP(min_mirror, "v_min_f32_dpp", "row_mirror")            // lane i with lane 15-i of its 16
-FH_DPP_OP(max_mirror, "v_max_f32_dpp", "row_mirror")
-#undef FH_DPP_OP
+}
+#undef FH_DPP_STEP
 
 // Both halves of a permlane swap of a value with itself (gfx950).  The second operand
 // goes through an empty asm so the compiler treats the two inputs as unrelated values:
@@ -135,14 +144,7 @@ template <int LANES>
 __device__ __forceinline__ void group_minmax(float& mn, float& mx)
 {
     static_assert(LANES == 4 || LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "run length");
-    mn = min_xor1(mn);  mx = max_xor1(mx);
-    mn = min_xor2(mn);  mx = max_xor2(mx);
-    if constexpr (LANES >= 8) {   // quads are uniform now: mirroring 8 lanes swaps the two quads
-        mn = min_half(mn);  mx = max_half(mx);
-    }
-    if constexpr (LANES >= 16) {  // halves are uniform: mirroring 16 lanes swaps the two halves
-        mn = min_mirror(mn);  mx = max_mirror(mx);
-    }
+    row_minmax<(LANES < 16 ? LANES : 16)>(mn, mx);
     if constexpr (LANES >= 32) {
         // v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the
         // even rows of its second: two copies of v come back as rows {0,0,2,2} and
@@ -160,6 +162,13 @@ __device__ __forceinline__ void group_minmax(float& mn, float& mx)
     }
 }
 
+// The value held by the neighbouring lane (lane ^ 1).
+__device__ __forceinline__ float from_pair_lane(float v)
+{
+    return __builtin_bit_cast(float,
+        __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+}
+
 // ---- Philox4x32-10 ---------------------------------------------------------------
 // Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3" (SC'11),
 // Section 3.3: ten rounds of
@@ -175,8 +184,9 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = (uint64_t)M0 * c0;
         const uint64_t p1 = (uint64_t)M1 * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        // three-way xor in one v_bitop3_b32 (truth table 0x96)
+        const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+        const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
