@@ -26,6 +26,23 @@ constexpr int kRowsPerWave = FH_COMPRESS_ROWS;   // rows whose loads are issued 
 constexpr int kWaveSpan = kRowsPerWave * kRow;
 constexpr int kTile = (kBlock / kWave) * kWaveSpan;   // 4096 elements per workgroup
 
+// Per-wave LDS staging area: the codes of the wave's span in element order (at most one
+// byte per element) followed by its groups' {scale, zero} pairs (at most span/64).
+// Each wave only touches its own area, so no workgroup barrier is involved.
+#ifndef FH_COMPRESS_LDS
+#define FH_COMPRESS_LDS 1
+#endif
+// the staging area is written and read back through different widths
+typedef uint16_t __attribute__((may_alias)) stage_u16;
+typedef uint32_t __attribute__((may_alias)) stage_u32;
+typedef u32x2 __attribute__((may_alias)) stage_u32x2;
+typedef u32x4 __attribute__((may_alias)) stage_u32x4;
+typedef f32x2 __attribute__((may_alias)) stage_f32x2;
+constexpr int kStageCodeBytes = kWaveSpan;
+constexpr int kStageMetaBytes = (kWaveSpan / 64) * 8;
+constexpr int kStageDwords = (kStageCodeBytes + kStageMetaBytes) / 4;
+static_assert(kRowsPerWave == 2 || !FH_COMPRESS_LDS, "the staged store assumes two rows per wave");
+
 template <int G> struct Log2;
 template <> struct Log2<64>  { static constexpr int v = 6; };
 template <> struct Log2<128> { static constexpr int v = 7; };
@@ -174,7 +191,7 @@ template <> struct Loader<uint16_t> {   // bf16 bit patterns; widening is exact
 };
 
 template <typename InT, int G, int B, bool STOCH>
-__device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t tile)
+__device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t tile, uint32_t* stage)
 {
     constexpr int LPG = G / kEPL;                             // lanes per group
     constexpr int LOGG = Log2<G>::v;
@@ -193,6 +210,8 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
     uint8_t* pw = it.packed + ((uint64_t)wave_base * B >> 3);
     float* mw = it.meta + 2 * (wave_base >> LOGG);
     const uint32_t lane_elem = lane * kEPL;                   // first element of the lane inside a row
+    uint8_t* stage_codes = reinterpret_cast<uint8_t*>(stage + wave * kStageDwords);
+    float* stage_meta = reinterpret_cast<float*>(stage_codes + kStageCodeBytes);
 
     if (wave_base + kWaveSpan <= numel) {
         // ---- interior: every element exists, every access is a full vector ----
@@ -210,16 +229,49 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
             group_minmax<LPG>(mn, mx);
             float scale, inv;
             scale_and_inverse<B>(mx - mn, odd_lane, scale, inv);
+#if FH_COMPRESS_LDS
+            if ((lane & (LPG - 1)) == 0)
+                *reinterpret_cast<stage_f32x2*>(stage_meta + 2 * (e0 >> LOGG)) = f32x2{scale, mn + 0.0f};   // -0.0 -> +0.0
+#else
             if ((lane & (LPG - 1)) == 0)
                 *reinterpret_cast<f32x2*>(mw + 2 * (e0 >> LOGG)) = f32x2{scale, mn + 0.0f};   // -0.0 -> +0.0
+#endif
             // a row starts on a multiple of 512 elements = 64 Philox blocks, so adding the
             // lane never carries out of the low counter word
             const uint64_t blk = (uint64_t)(wave_base + r * kRow) >> 3;
             uint32_t w0, w1;
             quantise8<B, STOCH, true>(x[r], mn, inv, kEPL, (uint32_t)blk + lane, (uint32_t)(blk >> 32),
                                       it.seed, it.tensor_id, w0, w1);
+#if FH_COMPRESS_LDS
+            // codes go to the staging area in element order ...
+            uint8_t* sc = stage_codes + (e0 * B >> 3);
+            if constexpr (B == 8) *reinterpret_cast<stage_u32x2*>(sc) = u32x2{w0, w1};
+            else if constexpr (B == 4) *reinterpret_cast<stage_u32*>(sc) = w0;
+            else *reinterpret_cast<stage_u16*>(sc) = (uint16_t)w0;
+#else
             store_codes<B>(pw + (e0 * B >> 3), w0, w1);
+#endif
         }
+#if FH_COMPRESS_LDS
+        // ... and leave as ONE store per wave: lane l takes the 2*B bytes at l*2*B, so the
+        // wave writes its 256 / 512 / 1024 code bytes as one contiguous run.  LDS
+        // operations of one wave complete in order, so the reads see the writes above.
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");    // compiler ordering only: no instruction
+        if constexpr (B == 8) {
+            const u32x4 c = *reinterpret_cast<const stage_u32x4*>(stage_codes + lane * 16);
+            code_store(reinterpret_cast<u32x4*>(pw + lane * 16), c);
+        } else if constexpr (B == 4) {
+            const u32x2 c = *reinterpret_cast<const stage_u32x2*>(stage_codes + lane * 8);
+            code_store(reinterpret_cast<u32x2*>(pw + lane * 8), c);
+        } else {
+            const uint32_t c = *reinterpret_cast<const stage_u32*>(stage_codes + lane * 4);
+            code_store(reinterpret_cast<uint32_t*>(pw + lane * 4), c);
+        }
+        // likewise the span's kWaveSpan / G meta pairs: one 8-byte store from each of the first lanes
+        constexpr uint32_t kGroups = kWaveSpan / G;
+        if (lane < kGroups)
+            *reinterpret_cast<f32x2*>(mw + 2 * lane) = *reinterpret_cast<const stage_f32x2*>(stage_meta + 2 * lane);
+#endif
         return;
     }
 
@@ -272,13 +324,14 @@ __global__ __launch_bounds__(kBlock) void compress_kernel(const CompressBatch ar
     }
     const CompressItem& it = args.item[lo];
     const uint32_t tile = bid - args.tile_start[lo];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[(kBlock / kWave) * kStageDwords];
     switch (it.bits * 2 + it.stochastic) {
-        case 4:  compress_tile<InT, G, 2, false>(it, tile); break;
-        case 5:  compress_tile<InT, G, 2, true >(it, tile); break;
-        case 8:  compress_tile<InT, G, 4, false>(it, tile); break;
-        case 9:  compress_tile<InT, G, 4, true >(it, tile); break;
-        case 16: compress_tile<InT, G, 8, false>(it, tile); break;
-        case 17: compress_tile<InT, G, 8, true >(it, tile); break;
+        case 4:  compress_tile<InT, G, 2, false>(it, tile, stage); break;
+        case 5:  compress_tile<InT, G, 2, true >(it, tile, stage); break;
+        case 8:  compress_tile<InT, G, 4, false>(it, tile, stage); break;
+        case 9:  compress_tile<InT, G, 4, true >(it, tile, stage); break;
+        case 16: compress_tile<InT, G, 8, false>(it, tile, stage); break;
+        case 17: compress_tile<InT, G, 8, true >(it, tile, stage); break;
         default: break;
     }
 }
