@@ -17,6 +17,10 @@ namespace fh {
 
 namespace {
 
+#ifndef FH_COMPRESS_BLOCK
+#define FH_COMPRESS_BLOCK 256
+#endif
+constexpr int kCBlock = FH_COMPRESS_BLOCK;   // threads per workgroup
 constexpr int kEPL = 8;                  // elements per lane
 constexpr int kRow = kWave * kEPL;       // elements one wave covers per row: 512
 #ifndef FH_COMPRESS_ROWS
@@ -24,7 +28,7 @@ constexpr int kRow = kWave * kEPL;       // elements one wave covers per row: 51
 #endif
 constexpr int kRowsPerWave = FH_COMPRESS_ROWS;   // rows whose loads are issued before any is consumed
 constexpr int kWaveSpan = kRowsPerWave * kRow;
-constexpr int kTile = (kBlock / kWave) * kWaveSpan;   // 4096 elements per workgroup
+constexpr int kTile = (kCBlock / kWave) * kWaveSpan;   // 4096 elements per workgroup
 
 // Per-wave LDS staging area: the codes of the wave's span in element order (at most one
 // byte per element) followed by its groups' {scale, zero} pairs (at most span/64).
@@ -532,7 +536,7 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
 }
 
 template <typename InT, int G>
-__global__ __launch_bounds__(kBlock) void compress_kernel(const CompressBatch args)
+__global__ __launch_bounds__(kCBlock) void compress_kernel(const CompressBatch args)
 {
     const uint32_t bid = blockIdx.x;
     int lo = 0, hi = args.count;                              // last item with tile_start <= bid
@@ -542,7 +546,7 @@ __global__ __launch_bounds__(kBlock) void compress_kernel(const CompressBatch ar
     }
     const CompressItem& it = args.item[lo];
     const uint32_t tile = bid - args.tile_start[lo];
-    __shared__ __attribute__((aligned(16))) uint32_t stage[(kBlock / kWave) * kStageDwords];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[(kCBlock / kWave) * kStageDwords];
     switch (it.bits * 2 + it.stochastic) {
         case 4:  compress_tile<InT, G, 2, false>(it, tile, stage); break;
         case 5:  compress_tile<InT, G, 2, true >(it, tile, stage); break;
@@ -562,7 +566,7 @@ hipError_t launch_compress(const CompressBatch& b, int dtype, int group_size, hi
 {
     const uint32_t tiles = b.tile_start[b.count];
     if (tiles == 0) return hipSuccess;
-    const dim3 grid(tiles), block(kBlock);
+    const dim3 grid(tiles), block(kCBlock);
 #define FH_LAUNCH(T, GS) hipLaunchKernelGGL((compress_kernel<T, GS>), grid, block, 0, s, b)
     if (dtype == 0) {
         if (group_size == 64) FH_LAUNCH(float, 64);

@@ -18,8 +18,12 @@ namespace fh {
 namespace {
 
 #ifndef FH_DECOMPRESS_ROWS
-#define FH_DECOMPRESS_ROWS 4
+#define FH_DECOMPRESS_ROWS 2
 #endif
+#ifndef FH_DECOMPRESS_BLOCK
+#define FH_DECOMPRESS_BLOCK 256
+#endif
+constexpr int kDBlock = FH_DECOMPRESS_BLOCK;       // threads per workgroup
 constexpr int kRowsPerWave = FH_DECOMPRESS_ROWS;   // rows whose loads are issued before any store
 
 template <typename OutT> struct OutTraits;
@@ -28,7 +32,7 @@ template <> struct OutTraits<uint16_t> { static constexpr int EPL = 8; };
 
 template <typename OutT> constexpr int tile_elems()
 {
-    return (kBlock / kWave) * kRowsPerWave * kWave * OutTraits<OutT>::EPL;
+    return (kDBlock / kWave) * kRowsPerWave * kWave * OutTraits<OutT>::EPL;
 }
 
 template <int G> struct Log2;
@@ -88,7 +92,7 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
     constexpr int EPL = OutTraits<OutT>::EPL;
     constexpr int ROW = kWave * EPL;
     constexpr int WAVE_SPAN = kRowsPerWave * ROW;
-    constexpr int TILE = (kBlock / kWave) * WAVE_SPAN;
+    constexpr int TILE = (kDBlock / kWave) * WAVE_SPAN;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t numel = it.numel;
@@ -151,7 +155,7 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
 }
 
 template <typename OutT, int G>
-__global__ __launch_bounds__(kBlock) void decompress_kernel(const DecompressBatch args)
+__global__ __launch_bounds__(kDBlock) void decompress_kernel(const DecompressBatch args)
 {
     // Tiles are taken from the end of the set backwards: the backward pass needs the
     // tensors in the reverse of the order the forward pass saved them, and the codes
@@ -187,7 +191,7 @@ hipError_t launch_decompress(const DecompressBatch& b, int out_dtype, int group_
 {
     const uint32_t tiles = b.tile_start[b.count];
     if (tiles == 0) return hipSuccess;
-    const dim3 grid(tiles), block(kBlock);
+    const dim3 grid(tiles), block(kDBlock);
 #define FH_LAUNCH(T, GS) hipLaunchKernelGGL((decompress_kernel<T, GS>), grid, block, 0, s, b)
     if (out_dtype == 0) {
         if (group_size == 64) FH_LAUNCH(float, 64);

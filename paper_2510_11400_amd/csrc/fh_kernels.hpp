@@ -10,7 +10,6 @@
 namespace fh {
 
 constexpr int kMaxItems = 48;
-constexpr int kBlock = 256;            // 4 waves of 64
 
 struct CompressItem {
     const void* x;                     // device, 16-byte aligned
