@@ -17,7 +17,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libfho.so")
-_SRC = os.path.join(_HERE, "fho.c")
+_SRCS = [os.path.join(_HERE, "fho.c"), os.path.join(_HERE, "fho_classify.c")]
 
 F32, BF16 = 0, 1
 NEAREST, STOCHASTIC = 0, 1
@@ -29,9 +29,9 @@ _ROUNDS = {"nearest": NEAREST, "stochastic": STOCHASTIC, NEAREST: NEAREST, STOCH
 def build(force: bool = True) -> str:
     """Compile fho.c into libfho.so with gcc (strict binary32 semantics: no
     contraction, no fast-math)."""
-    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < max(os.path.getmtime(p) for p in _SRCS):
         cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+               "-Wall", "-Wextra", "-o", _SO, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True, cwd=_HERE)
     return _SO
 
@@ -62,6 +62,13 @@ def lib() -> ctypes.CDLL:
         L.fho_decompress.restype = ctypes.c_int
         L.fho_unpack_codes.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
         L.fho_unpack_codes.restype = ctypes.c_int
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.fho_pairwise_moments.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, dp, dp]
+        L.fho_pairwise_moments.restype = None
+        L.fho_classify_channels.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                            ctypes.c_int64, ctypes.c_double, ctypes.c_int64,
+                                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.fho_classify_channels.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -129,3 +136,27 @@ def unpack_codes(packed: np.ndarray, numel: int, bits: int) -> np.ndarray:
     if rc != 0:
         raise ValueError("fho_unpack_codes rejected its arguments")
     return codes
+
+
+def pairwise_moments(x: np.ndarray, dtype="f32") -> Tuple[float, float]:
+    """Pairwise binary64 sums (sum x, sum x*x) in element order."""
+    d = _check_input(x, dtype)
+    s1, s2 = ctypes.c_double(), ctypes.c_double()
+    lib().fho_pairwise_moments(x.ctypes.data, d, int(x.size), ctypes.byref(s1), ctypes.byref(s2))
+    return s1.value, s2.value
+
+
+def classify_channels(x: np.ndarray, outer: int, channels: int, inner: int, k_sigma: float = 3.0,
+                      min_outliers: int = 1, dtype="f32"):
+    """-> (stats float64[4] = {mean, variance, threshold, numel}, counts uint32[C], mask uint8[C])."""
+    d = _check_input(x, dtype)
+    if x.size != outer * channels * inner:
+        raise ValueError("x.size != outer * channels * inner")
+    stats = np.zeros(4, dtype=np.float64)
+    counts = np.zeros(channels, dtype=np.uint32)
+    mask = np.zeros(channels, dtype=np.uint8)
+    rc = lib().fho_classify_channels(x.ctypes.data, d, outer, channels, inner, float(k_sigma), int(min_outliers),
+                                     stats.ctypes.data, counts.ctypes.data, mask.ctypes.data)
+    if rc != 0:
+        raise ValueError("fho_classify_channels rejected its arguments")
+    return stats, counts, mask

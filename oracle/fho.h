@@ -60,6 +60,19 @@ int fho_decompress(const uint8_t *packed, const float *meta, int64_t numel,
 /* The unpacked code of every element (one byte each), for tests that look at codes. */
 int fho_unpack_codes(const uint8_t *packed, int64_t numel, int bits, uint8_t *codes);
 
+/* ---- channel classification (fho_classify.c; Section 4.4.1: 3-sigma rule, salient vs
+ *      normal channels) ---- */
+
+/* Pairwise (balanced binary tree, natural order, zero padded) binary64 sums of x and x*x. */
+void fho_pairwise_moments(const void *x, int dtype, int64_t numel, double *s1_out, double *s2_out);
+
+/* Tensor viewed as [outer][channels][inner].  stats = {mean, variance, threshold, numel};
+ * counts[channels] = outliers per channel; mask[channels] = 1 for salient channels
+ * (count >= min_outliers).  Returns 0, or -1 on a bad argument. */
+int fho_classify_channels(const void *x, int dtype, int64_t outer, int64_t channels, int64_t inner,
+                          double k_sigma, int64_t min_outliers,
+                          double stats[4], uint32_t *counts, uint8_t *mask);
+
 #ifdef __cplusplus
 }
 #endif

@@ -242,3 +242,30 @@ def ablation_set(batch: int = 1, group_size: int = 256, bits: int = 4,
     for tid, (c, h, ww) in enumerate(ABLATION_SHAPES):
         w.tensors.append(TensorSpec(tid, (batch, c, h, ww), F32, "relu", group_size, bits, rounding, seed))
     return w
+
+
+# --------------------------------------------------------------------------
+# Activations with channel-clustered outliers (inputs for channel classification)
+# --------------------------------------------------------------------------
+
+def outlier_channel_tensor(outer: int, channels: int, inner: int, seed: int = 0, dist: str = "gauss",
+                           salient_fraction: float = 0.04, hit_fraction: float = 0.05,
+                           magnitude: float = 81.0, dtype: str = F32):
+    """A [outer][channels][inner] activation whose outliers are sparse and clustered in a few
+    channels, as the paper describes them (Section 4.4.1; magnitudes 81x for CNNs and 347x
+    for Transformers are the figures it quotes).  A seeded subset of about
+    `salient_fraction` of the channels gets `hit_fraction` of its elements multiplied by
+    `magnitude`; every other element follows `dist`.  Returns (flat array, planted channel ids).
+    """
+    rng = np.random.default_rng(np.random.SeedSequence([seed, 0xC1A55, outer, channels, inner]))
+    x = _draw(dist, outer * channels * inner, rng).reshape(outer, channels, inner)
+    k = max(1, int(round(channels * salient_fraction)))
+    planted = np.sort(rng.choice(channels, size=k, replace=False))
+    for c in planted:
+        hit = rng.random((outer, inner)) < hit_fraction
+        block = x[:, c, :]
+        block[hit] = (np.abs(block[hit]) + np.float32(0.5)) * np.float32(magnitude)
+    flat = np.ascontiguousarray(x.reshape(-1))
+    if dtype == BF16:
+        flat = _to_bf16_bits(flat)
+    return flat, planted
