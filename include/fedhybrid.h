@@ -61,7 +61,9 @@ typedef enum fh_status {
     FH_ERR_BUFFER_TOO_SMALL = 7, /* a *_cap is below what the call writes or reads */
     FH_ERR_ALIGNMENT = 8,
     FH_ERR_LAUNCH = 9,           /* the HIP runtime refused the launch */
-    FH_ERR_BAD_COUNT = 10        /* negative item count */
+    FH_ERR_BAD_COUNT = 10,       /* negative item count */
+    FH_ERR_BAD_SHAPE = 11,       /* outer / channels / inner out of range */
+    FH_ERR_BAD_PARAM = 12        /* k_sigma not positive, or min_outliers < 1 */
 } fh_status;
 
 typedef enum fh_dtype { FH_F32 = 0, FH_BF16 = 1 } fh_dtype;
@@ -96,16 +98,16 @@ size_t fh_packed_bytes(int64_t numel, int32_t bits);
 /* 8 * ceil(numel / group_size); 0 for numel <= 0 or group_size <= 0. */
 size_t fh_meta_bytes(int64_t numel, int32_t group_size);
 
-/* Forward side (Section 3: "compresses the training activation during the forward
- * pass"; quantiser of Section 4.4.1).  Reads numel elements of x_dtype at x, writes
+/* Forward side (Section 3: the activation is compressed while the forward pass runs;
+ * quantiser of Section 4.4.1).  Reads numel elements of x_dtype at x, writes
  * fh_packed_bytes() bytes at packed (padding included, zero) and fh_meta_bytes()
  * bytes at meta. */
 fh_status fh_compress(const void *x, fh_dtype x_dtype, int64_t numel, const fh_params *params,
                       void *packed, size_t packed_cap, void *meta, size_t meta_cap, void *stream);
 
-/* Backward side (Section 3: "decompresses the saved activation during
- * backpropagation"; Section 4.4.1: reconstruction of floating-point values from the
- * quantisation codes).  Writes numel elements of out_dtype at out.  params->rounding,
+/* Backward side (Section 3: the saved activation is decompressed when backpropagation
+ * needs it; Section 4.4.1: floating-point values are rebuilt from the quantisation
+ * codes).  Writes numel elements of out_dtype at out.  params->rounding,
  * seed and tensor_id are ignored. */
 fh_status fh_decompress(const void *packed, const void *meta, int64_t numel, const fh_params *params,
                         fh_dtype out_dtype, void *out, size_t out_cap, void *stream);
@@ -129,6 +131,34 @@ fh_status fh_compress_batch(const fh_item *items, int32_t count, void *stream);
 fh_status fh_decompress_batch(const fh_item *items, int32_t count, void *stream);
 fh_status fh_roundtrip_batch(const fh_item *items, int32_t count, void *stream);
 int32_t   fh_batch_capacity(void);
+
+/* ---- channel classification -------------------------------------------------------
+ * Section 4.4.1 finds outliers with the empirical three-sigma rule and sorts channels
+ * into salient (outlier-rich) and normal ones; normal channels are the ones the
+ * quantiser above is meant for.  The paper gives the rule's name only; the definition
+ * used (k and the outlier count that makes a channel salient are inputs):
+ *
+ *   - the tensor is viewed as [outer][channels][inner], row-major (NCHW: outer = N,
+ *     inner = H*W; [tokens][hidden]: inner = 1);
+ *   - S1 = sum x and S2 = sum x*x over all elements in binary64, summed PAIRWISE: the
+ *     sequence in element order, zero-padded to a power of two, reduced by a balanced
+ *     binary tree (this fixes every rounding, whatever the blocking);
+ *   - mean = S1 / N, variance = max(S2 / N - mean*mean, 0), threshold = k*k * variance;
+ *   - x is an outlier iff d*d > threshold, d = (double)x - mean;
+ *   - counts[c] = outliers in channel c; mask[c] = (counts[c] >= min_outliers).
+ *
+ * x: device, 16-byte aligned, outer*channels*inner elements of x_dtype.
+ * workspace: device, 16-byte aligned, >= fh_classify_workspace_bytes(numel) bytes,
+ *   scratch for the partial sums (contents undefined afterwards).
+ * stats: device, 8-byte aligned, 4 doubles {mean, variance, threshold, numel}.
+ * counts: device, uint32[channels].  mask: device, uint8[channels].
+ * 1 <= channels <= 16384, inner >= 1, outer >= 0.  outer == 0 zeroes the outputs.
+ * Everything is enqueued on `stream`; nothing is allocated or synchronised. */
+size_t    fh_classify_workspace_bytes(int64_t numel);
+fh_status fh_classify_channels(const void *x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
+                               double k_sigma, int64_t min_outliers,
+                               void *workspace, size_t workspace_cap,
+                               void *stats, void *counts, void *mask, void *stream);
 
 const char *fh_status_string(fh_status s);
 

@@ -30,7 +30,7 @@ FH_ROUND_NEAREST, FH_ROUND_STOCHASTIC = 0, 1
 
 EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "fh_roundtrip",
            "fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch", "fh_batch_capacity",
-           "fh_status_string")
+           "fh_classify_workspace_bytes", "fh_classify_channels", "fh_status_string")
 
 
 class fh_params(ctypes.Structure):
@@ -65,6 +65,12 @@ _lib.fh_roundtrip.restype = ctypes.c_int
 for _name in ("fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch"):
     getattr(_lib, _name).argtypes = [_P(fh_item), ctypes.c_int32, ctypes.c_void_p]
     getattr(_lib, _name).restype = ctypes.c_int
+_lib.fh_classify_workspace_bytes.argtypes = [ctypes.c_int64]
+_lib.fh_classify_workspace_bytes.restype = ctypes.c_size_t
+_lib.fh_classify_channels.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                      ctypes.c_double, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.fh_classify_channels.restype = ctypes.c_int
 _lib.fh_batch_capacity.argtypes = []
 _lib.fh_batch_capacity.restype = ctypes.c_int32
 _lib.fh_status_string.argtypes = [ctypes.c_int]
@@ -256,3 +262,39 @@ def fh_decompress_batch(batch: Batch, stream=None) -> None:
 
 def fh_roundtrip_batch(batch: Batch, stream=None) -> None:
     batch._call(_lib.fh_roundtrip_batch, stream)
+
+
+def classify_workspace_bytes(numel: int) -> int:
+    return int(_lib.fh_classify_workspace_bytes(numel))
+
+
+def fh_classify_channels(x: torch.Tensor, outer: int, channels: int, inner: int, k_sigma: float = 3.0,
+                         min_outliers: int = 1, workspace: Optional[torch.Tensor] = None,
+                         stats: Optional[torch.Tensor] = None, counts: Optional[torch.Tensor] = None,
+                         mask: Optional[torch.Tensor] = None, stream=None):
+    """Enqueue the channel classification of `x` viewed as [outer][channels][inner];
+    returns device tensors (stats float64[4] = {mean, variance, threshold, numel},
+    counts int32[channels] (bit pattern of uint32), mask uint8[channels])."""
+    _device_tensor(x, "x")
+    if x.numel() != outer * channels * inner:
+        raise ValueError("x.numel() != outer * channels * inner")
+    dev = x.device
+    if workspace is None:
+        workspace = torch.empty(classify_workspace_bytes(x.numel()), dtype=torch.uint8, device=dev)
+    if stats is None:
+        stats = torch.empty(4, dtype=torch.float64, device=dev)
+    if counts is None:
+        counts = torch.empty(channels, dtype=torch.int32, device=dev)
+    if mask is None:
+        mask = torch.empty(channels, dtype=torch.uint8, device=dev)
+    for t, what in ((workspace, "workspace"), (stats, "stats"), (counts, "counts"), (mask, "mask")):
+        _device_tensor(t, what)
+    if stats.numel() * stats.element_size() < 32 or counts.numel() * counts.element_size() < 4 * channels \
+            or mask.numel() * mask.element_size() < channels:
+        raise FedHybridError(7)
+    with torch.cuda.device(dev):
+        _check(_lib.fh_classify_channels(x.data_ptr(), _dtype_code(x), outer, channels, inner, float(k_sigma),
+                                         int(min_outliers), workspace.data_ptr(),
+                                         workspace.numel() * workspace.element_size(),
+                                         stats.data_ptr(), counts.data_ptr(), mask.data_ptr(), _stream_ptr(stream)))
+    return stats, counts, mask

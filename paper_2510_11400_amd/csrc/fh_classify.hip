@@ -1,0 +1,444 @@
+// Channel classification on gfx950: outliers by the k-sigma rule, counted per channel
+// (paper Section 4.4.1: outliers are found with the empirical three-sigma rule and
+// channels are sorted into salient and normal ones).  Contract and definition:
+// include/fedhybrid.h.
+//
+// Two streaming passes over the tensor:
+//   1. moments: pairwise binary64 sums of x and x*x.  The balanced tree of the
+//      definition is walked in 1024-element spans (one per wave): inside a lane over its
+//      consecutive elements, across the 64 lanes by xor 1, 2, 4, ... 32, across the rows of
+//      the span, and then across spans by the same routine applied to the partial sums
+//      (1024 partials per wave) until one pair is left.  Binary64 addition is commutative,
+//      so a butterfly exchange forms exactly the tree's nodes; partial sums of different
+//      rows and of the two moments are spread over the lanes (reduce-scatter) so that
+//      each exchange level handles half of what the level before did.
+//   2. count: d = (double)x - mean, outlier iff d*d > threshold; outliers are rare, so
+//      each lane keeps a bit mask of its 16 elements and only set bits pay for the
+//      channel index (division by invariant integers through multiply-high) and an LDS
+//      histogram increment; the histogram is flushed with one global atomic per
+//      non-zero bin and workgroup.
+#include "../../include/fedhybrid.h"
+
+#include "fh_device.hpp"
+
+#include <limits.h>
+
+namespace fh {
+namespace {
+
+constexpr int kSpan = 1024;              // elements (or partial sums) per wave
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / kWave;
+constexpr int kMaxChannels = 16384;
+
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
+// ---- lane exchanges of a double ------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v)
+{
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)u, CTRL, 0xF, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(u >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+// ds_swizzle in bit-mask mode: lane l reads lane (l & 0x1f) ^ XOR inside its half
+template <int XOR>
+__device__ __forceinline__ double swizzle_f64(double v)
+{
+    constexpr int pattern = (XOR << 10) | 0x1F;
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)u, pattern);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)(u >> 32), pattern);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+template <int XOR>
+__device__ __forceinline__ double from_lane_xor(double v)
+{
+    if constexpr (XOR == 1) return dpp_f64<0xB1>(v);        // quad_perm [1,0,3,2]
+    else if constexpr (XOR == 2) return dpp_f64<0x4E>(v);   // quad_perm [2,3,0,1]
+    else return swizzle_f64<XOR>(v);                          // 4, 8, 16
+}
+// v[l] + v[l ^ 32]: permlane32_swap of two copies returns {lo half, lo half} and
+// {hi half, hi half}; their sum is the same in both halves.
+__device__ __forceinline__ double add_across_halves(double v)
+{
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    uint32_t a0 = (uint32_t)u, a1 = (uint32_t)(u >> 32), b0 = a0, b1 = a1;
+    asm volatile("" : "+v"(b0), "+v"(b1));
+    const u32x2 r0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+    const u32x2 r1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+    const uint32_t f0 = r0.x, s0 = r0.y, f1 = r1.x, s1 = r1.y;
+    const double first = __builtin_bit_cast(double, ((uint64_t)f1 << 32) | f0);
+    const double second = __builtin_bit_cast(double, ((uint64_t)s1 << 32) | s0);
+    return first + second;
+}
+
+// ---- the span tree ---------------------------------------------------------------------
+// In: for each of ROWS rows, the lane's own subtree sums a[r] (of x) and b[r] (of x*x);
+// a row is 64 lanes in element order.  Out (all lanes): the span's two sums.
+// Exchange levels, in the tree's order:
+//   xor 1   keep the rows whose low bit equals the lane's bit 0        (ROWS == 4 only)
+//   xor 2   keep the row whose high bit equals the lane's bit 1 (ROWS == 4), or the row
+//           whose index equals bit 0 moved here (ROWS == 2: done at xor 1)
+//   next    keep one of the two moments
+//   rest    plain butterflies
+// followed by the levels that join the rows.
+template <int ROWS>
+__device__ __forceinline__ void span_tree(const double (&a)[ROWS], const double (&b)[ROWS], uint32_t lane,
+                                          double& s1, double& s2)
+{
+    static_assert(ROWS == 2 || ROWS == 4, "rows per span");
+    const bool b0 = lane & 1u, b1 = lane & 2u, b2 = lane & 4u;
+    double t;          // after the scatter levels: one (row, moment) total per lane
+    if constexpr (ROWS == 4) {
+        // xor 1: rows {b0, b0 + 2} of both moments stay
+        double ka[2], kb[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            ka[j] = (b0 ? a[2 * j + 1] : a[2 * j]) + from_lane_xor<1>(b0 ? a[2 * j] : a[2 * j + 1]);
+            kb[j] = (b0 ? b[2 * j + 1] : b[2 * j]) + from_lane_xor<1>(b0 ? b[2 * j] : b[2 * j + 1]);
+        }
+        // xor 2: row 2 * b1 + b0 stays
+        const double ma = (b1 ? ka[1] : ka[0]) + from_lane_xor<2>(b1 ? ka[0] : ka[1]);
+        const double mb = (b1 ? kb[1] : kb[0]) + from_lane_xor<2>(b1 ? kb[0] : kb[1]);
+        // xor 4: moment b2 stays
+        t = (b2 ? mb : ma) + from_lane_xor<4>(b2 ? ma : mb);
+        t = t + from_lane_xor<8>(t);
+        t = t + from_lane_xor<16>(t);
+        t = add_across_halves(t);
+        // rows: (0 + 1), (2 + 3), then their sum; the row index sits in lane bits 0 and 1
+        t = t + from_lane_xor<1>(t);
+        t = t + from_lane_xor<2>(t);
+        // lanes with bit 2 clear hold the sum of x, the others the sum of x*x
+        const double other = from_lane_xor<4>(t);
+        s1 = b2 ? other : t;
+        s2 = b2 ? t : other;
+    } else {
+        // xor 1: row b0 of both moments stays
+        const double ma = (b0 ? a[1] : a[0]) + from_lane_xor<1>(b0 ? a[0] : a[1]);
+        const double mb = (b0 ? b[1] : b[0]) + from_lane_xor<1>(b0 ? b[0] : b[1]);
+        // xor 2: moment b1 stays
+        t = (b1 ? mb : ma) + from_lane_xor<2>(b1 ? ma : mb);
+        t = t + from_lane_xor<4>(t);
+        t = t + from_lane_xor<8>(t);
+        t = t + from_lane_xor<16>(t);
+        t = add_across_halves(t);
+        t = t + from_lane_xor<1>(t);                          // row 0 + row 1
+        const double other = from_lane_xor<2>(t);
+        s1 = b1 ? other : t;
+        s2 = b1 ? t : other;
+    }
+}
+
+// ---- pass 1a: spans of the tensor ------------------------------------------------------
+template <typename InT> struct Span;
+template <> struct Span<float> {            // 4 rows of 256, 4 consecutive elements per lane
+    static constexpr int ROWS = 4, EPL = 4;
+    __device__ static __forceinline__ void load(const float* p, float (&x)[EPL]) {
+        const f32x4 v = stream_load(reinterpret_cast<const f32x4*>(p));
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    }
+    __device__ static __forceinline__ float one(const float* p) { return *p; }
+};
+template <> struct Span<uint16_t> {         // 2 rows of 512, 8 consecutive elements per lane
+    static constexpr int ROWS = 2, EPL = 8;
+    __device__ static __forceinline__ void load(const uint16_t* p, float (&x)[EPL]) {
+        const u32x4 v = stream_load(reinterpret_cast<const u32x4*>(p));
+        x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
+        x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
+    }
+    __device__ static __forceinline__ float one(const uint16_t* p) {
+        return __builtin_bit_cast(float, (uint32_t)*p << 16);
+    }
+};
+
+// balanced tree over N consecutive values (N a power of two)
+template <int N>
+__device__ __forceinline__ double local_tree(const double (&v)[N])
+{
+    double w[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) w[i] = v[i];
+#pragma unroll
+    for (int n = N; n > 1; n /= 2)
+#pragma unroll
+        for (int i = 0; i < n / 2; ++i) w[i] = w[2 * i] + w[2 * i + 1];
+    return w[0];
+}
+
+template <typename InT>
+__global__ __launch_bounds__(kThreads) void moments_kernel(const InT* __restrict__ x, int64_t numel,
+                                                           f64x2* __restrict__ partial)
+{
+    constexpr int ROWS = Span<InT>::ROWS, EPL = Span<InT>::EPL, ROW = kWave * EPL;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t span = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t base = span * kSpan;
+    if (base >= numel) return;                                // wave-uniform
+    const InT* xs = x + base;
+    double a[ROWS], b[ROWS];
+    const bool interior = base + kSpan <= numel;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        float v[EPL];
+        const uint32_t e0 = r * ROW + lane * EPL;
+        if (interior) {
+            Span<InT>::load(xs + e0, v);
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) v[j] = (base + e0 + j < numel) ? Span<InT>::one(xs + e0 + j) : 0.0f;
+        }
+        double d[EPL], q[EPL];
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) { d[j] = (double)v[j]; q[j] = d[j] * d[j]; }   // the square is exact
+        a[r] = local_tree<EPL>(d);
+        b[r] = local_tree<EPL>(q);
+    }
+    double s1, s2;
+    span_tree<ROWS>(a, b, lane, s1, s2);
+    if (lane == 0) partial[span] = f64x2{s1, s2};
+}
+
+// ---- pass 1b: spans of partial sums (4 rows of 256 pairs, 4 consecutive pairs per lane) --
+__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f64x2* __restrict__ in, int64_t count,
+                                                                   f64x2* __restrict__ out)
+{
+    constexpr int ROWS = 4, EPL = 4, ROW = kWave * EPL;
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t span = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t base = span * kSpan;
+    if (base >= count) return;
+    double a[ROWS], b[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        double d[EPL], q[EPL];
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int64_t i = base + r * ROW + lane * EPL + j;
+            const f64x2 p = i < count ? in[i] : f64x2{0.0, 0.0};
+            d[j] = p.x; q[j] = p.y;
+        }
+        a[r] = local_tree<EPL>(d);
+        b[r] = local_tree<EPL>(q);
+    }
+    double s1, s2;
+    span_tree<ROWS>(a, b, lane, s1, s2);
+    if (lane == 0) out[span] = f64x2{s1, s2};
+}
+
+// ---- pass 1c: mean, variance, threshold; clear the counters -------------------------------
+__global__ __launch_bounds__(kThreads) void finish_moments_kernel(const f64x2* __restrict__ total, int64_t numel,
+                                                                  double k_sigma, double* __restrict__ stats,
+                                                                  uint32_t* __restrict__ counts, int channels)
+{
+    for (int c = threadIdx.x; c < channels; c += kThreads) counts[c] = 0u;
+    if (threadIdx.x == 0) {
+        double mean = 0.0, variance = 0.0;
+        if (numel > 0) {
+            const f64x2 s = total[0];
+            const double n = (double)numel;
+            mean = s.x / n;                                   // IEEE binary64 division
+            const double mean_sq = mean * mean;
+            variance = s.y / n - mean_sq;
+            if (!(variance > 0.0)) variance = 0.0;
+        }
+        stats[0] = mean;
+        stats[1] = variance;
+        stats[2] = (k_sigma * k_sigma) * variance;
+        stats[3] = (double)numel;
+    }
+}
+
+// ---- pass 2: outliers per channel ----------------------------------------------------------
+// floor(n / d) for a divisor fixed on the host.  magic = floor(2^32 / d) + 1 is exact
+// whenever n * d < 2^32; divisors of 2^15 and more are only ever asked for quotients 0 or 1.
+struct Divisor {
+    uint32_t d, magic;
+};
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, Divisor v)
+{
+    if (v.d == 1u) return n;
+    if (v.d >= 32768u) return n >= v.d ? 1u : 0u;
+    return __umulhi(n, v.magic);
+}
+
+struct CountArgs {
+    const void* x;
+    int64_t numel;
+    const double* stats;
+    uint32_t* counts;
+    Divisor inner, channels;
+    int32_t spans_per_wave;                                   // consecutive spans one wave walks
+};
+
+template <typename InT>
+__global__ __launch_bounds__(kThreads) void count_outliers_kernel(const CountArgs args)
+{
+    constexpr int ROWS = Span<InT>::ROWS, EPL = Span<InT>::EPL, ROW = kWave * EPL;
+    extern __shared__ uint32_t hist[];
+    const uint32_t C = args.channels.d;
+    for (uint32_t c = threadIdx.x; c < C; c += kThreads) hist[c] = 0u;
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const double mean = args.stats[0], threshold = args.stats[2];
+    const InT* x = static_cast<const InT*>(args.x);
+    const int64_t numel = args.numel;
+    // this wave's spans: first_span, first_span + 1, ...
+    const int64_t first_span = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * args.spans_per_wave;
+    int64_t base = first_span * kSpan;
+    // position of the span's first element: rem = index inside the channel run, chan = channel
+    uint32_t rem = 0, chan = 0;
+    if (base < numel) {
+        const uint64_t run = (uint64_t)base / args.inner.d;   // once per wave
+        rem = (uint32_t)((uint64_t)base - run * args.inner.d);
+        chan = (uint32_t)(run % C);
+    }
+    for (int s = 0; s < args.spans_per_wave && base < numel; ++s, base += kSpan) {
+        const InT* xs = x + base;
+        const bool interior = base + kSpan <= numel;
+        uint32_t bits = 0u;                                   // bit r * EPL + j: that element is an outlier
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            float v[EPL];
+            const uint32_t e0 = r * ROW + lane * EPL;
+            if (interior) {
+                Span<InT>::load(xs + e0, v);
+            } else {
+#pragma unroll
+                for (int j = 0; j < EPL; ++j)
+                    v[j] = (base + e0 + j < numel) ? Span<InT>::one(xs + e0 + j) : __builtin_bit_cast(float, 0x7fc00000u);
+            }
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) {
+                const double d = (double)v[j] - mean;
+                if (d * d > threshold) bits |= 1u << (r * EPL + j);          // false for the NaN filler
+            }
+        }
+        while (bits) {                                        // rare: about k-sigma tail mass * 16 per lane
+            const uint32_t k = (uint32_t)__builtin_ctz(bits);
+            bits &= bits - 1u;
+            const uint32_t off = (k / EPL) * ROW + lane * EPL + (k % EPL);   // element offset inside the span
+            const uint32_t runs = fast_div(rem + off, args.inner);           // channel runs crossed from `chan`
+            const uint32_t cc = chan + runs;
+            const uint32_t c = cc - fast_div(cc, args.channels) * C;
+            atomicAdd(&hist[c], 1u);
+        }
+        // advance (rem, chan) by one span
+        const uint32_t t = rem + kSpan;
+        const uint32_t runs = fast_div(t, args.inner);
+        rem = t - runs * args.inner.d;
+        const uint32_t cc = chan + runs;
+        chan = cc - fast_div(cc, args.channels) * C;
+    }
+    __syncthreads();
+    for (uint32_t c = threadIdx.x; c < C; c += kThreads) {
+        const uint32_t v = hist[c];
+        if (v) atomicAdd(&args.counts[c], v);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void mask_kernel(const uint32_t* __restrict__ counts, int channels,
+                                                        int64_t min_outliers, uint8_t* __restrict__ mask)
+{
+    const int c = blockIdx.x * kThreads + threadIdx.x;
+    if (c < channels) mask[c] = (int64_t)counts[c] >= min_outliers ? 1 : 0;
+}
+
+Divisor make_divisor(uint32_t d)
+{
+    Divisor v;
+    v.d = d;
+    v.magic = d >= 2u ? (uint32_t)(((uint64_t)1 << 32) / d) + 1u : 0u;
+    return v;
+}
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace
+}  // namespace fh
+
+extern "C" {
+
+size_t fh_classify_workspace_bytes(int64_t numel)
+{
+    // one {sum x, sum x*x} pair per 1024-element span, then per 1024 of those, ... down to one
+    if (numel <= 0) return 16;
+    size_t pairs = 0;
+    int64_t m = fh::ceil_div(numel, fh::kSpan);
+    for (;;) {
+        pairs += (size_t)m;
+        if (m == 1) break;
+        m = fh::ceil_div(m, fh::kSpan);
+    }
+    return pairs * 16;
+}
+
+fh_status fh_classify_channels(const void* x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
+                               double k_sigma, int64_t min_outliers,
+                               void* workspace, size_t workspace_cap,
+                               void* stats, void* counts, void* mask, void* stream)
+{
+    using namespace fh;
+    if (x_dtype != FH_F32 && x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if (outer < 0 || inner < 1 || channels < 1 || channels > kMaxChannels) return FH_ERR_BAD_SHAPE;
+    if (inner > (int64_t)1 << 31 || outer > (int64_t)1 << 40) return FH_ERR_BAD_SHAPE;
+    if (!(k_sigma > 0.0) || min_outliers < 1) return FH_ERR_BAD_PARAM;
+    const double total = (double)outer * (double)channels * (double)inner;
+    if (total > (double)((int64_t)1 << 40)) return FH_ERR_BAD_NUMEL;
+    const int64_t numel = outer * channels * inner;
+    if (!workspace || !stats || !counts || !mask || (numel > 0 && !x)) return FH_ERR_NULL;
+    auto misaligned = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
+    if (misaligned(x, 16) || misaligned(workspace, 16) || misaligned(stats, 8) || misaligned(counts, 4))
+        return FH_ERR_ALIGNMENT;
+    if (workspace_cap < fh_classify_workspace_bytes(numel)) return FH_ERR_BUFFER_TOO_SMALL;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    f64x2* level = static_cast<f64x2*>(workspace);
+    const f64x2* total_pair = level;
+    if (numel > 0) {
+        int64_t m = ceil_div(numel, kSpan);
+        const dim3 grid0((uint32_t)ceil_div(m, kWavesPerBlock)), block(kThreads);
+        if (x_dtype == FH_F32)
+            hipLaunchKernelGGL(moments_kernel<float>, grid0, block, 0, s, static_cast<const float*>(x), numel, level);
+        else
+            hipLaunchKernelGGL(moments_kernel<uint16_t>, grid0, block, 0, s, static_cast<const uint16_t*>(x), numel, level);
+        while (m > 1) {
+            const int64_t next = ceil_div(m, kSpan);
+            f64x2* out = level + m;
+            const dim3 grid((uint32_t)ceil_div(next, kWavesPerBlock));
+            hipLaunchKernelGGL(reduce_partials_kernel, grid, block, 0, s, level, m, out);
+            level = out;
+            m = next;
+        }
+        total_pair = level;
+    }
+    hipLaunchKernelGGL(finish_moments_kernel, dim3(1), dim3(kThreads), 0, s, total_pair, numel, k_sigma,
+                       static_cast<double*>(stats), static_cast<uint32_t*>(counts), (int)channels);
+    if (numel > 0) {
+        CountArgs a;
+        a.x = x;
+        a.numel = numel;
+        a.stats = static_cast<const double*>(stats);
+        a.counts = static_cast<uint32_t*>(counts);
+        a.inner = make_divisor((uint32_t)inner);
+        a.channels = make_divisor((uint32_t)channels);
+        a.spans_per_wave = 8;                                 // 32768 elements per workgroup
+        const int64_t per_block = (int64_t)a.spans_per_wave * kWavesPerBlock * kSpan;
+        const dim3 grid((uint32_t)ceil_div(numel, per_block)), block(kThreads);
+        const size_t lds = (size_t)channels * sizeof(uint32_t);
+        if (x_dtype == FH_F32)
+            hipLaunchKernelGGL(count_outliers_kernel<float>, grid, block, lds, s, a);
+        else
+            hipLaunchKernelGGL(count_outliers_kernel<uint16_t>, grid, block, lds, s, a);
+    }
+    hipLaunchKernelGGL(mask_kernel, dim3((uint32_t)ceil_div(channels, kThreads)), dim3(kThreads), 0, s,
+                       static_cast<const uint32_t*>(counts), (int)channels, min_outliers, static_cast<uint8_t*>(mask));
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+}  // extern "C"

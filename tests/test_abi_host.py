@@ -103,12 +103,43 @@ def test_batch_validates_every_item_before_the_first_launch():
 
 def test_status_strings():
     seen = set()
-    for s in range(0, 11):
+    for s in range(0, 13):
         msg = api.status_string(s)
         assert msg and msg != "unknown status"
         seen.add(msg)
-    assert len(seen) == 11
+    assert len(seen) == 13
     assert api.status_string(99) == "unknown status"
     with pytest.raises(api.FedHybridError) as e:
         api._check(4)
     assert "bits" in str(e.value)
+
+
+def _classify(x=FAKE, dtype=0, outer=4, channels=8, inner=16, k=3.0, min_out=1, ws=FAKE, ws_cap=1 << 20,
+              stats=FAKE, counts=FAKE, mask=FAKE):
+    return api.raw_library().fh_classify_channels(x, dtype, outer, channels, inner, k, min_out, ws, ws_cap,
+                                                   stats, counts, mask, None)
+
+
+def test_classify_rejects_bad_arguments_before_any_launch():
+    assert _classify(dtype=3) == 2
+    assert _classify(outer=-1) == 11 and _classify(inner=0) == 11
+    assert _classify(channels=0) == 11 and _classify(channels=16385) == 11
+    assert _classify(k=0.0) == 12 and _classify(k=-3.0) == 12 and _classify(k=float("nan")) == 12
+    assert _classify(min_out=0) == 12
+    assert _classify(x=None) == 1 and _classify(ws=None) == 1 and _classify(stats=None) == 1
+    assert _classify(counts=None) == 1 and _classify(mask=None) == 1
+    assert _classify(x=FAKE + 8) == 8 and _classify(ws=FAKE + 8) == 8 and _classify(stats=FAKE + 4) == 8
+    assert _classify(ws_cap=15) == 7
+    assert _classify(outer=1 << 30, channels=16384, inner=1 << 20) == 6
+
+
+def test_classify_workspace_size_covers_every_level_of_the_tree():
+    for n in (1, 1023, 1024, 1025, 1 << 20, (1 << 20) + 1, 536870496):
+        pairs, m = 0, -(-n // 1024)
+        while True:
+            pairs += m
+            if m == 1:
+                break
+            m = -(-m // 1024)
+        assert api.classify_workspace_bytes(n) == 16 * pairs
+    assert api.classify_workspace_bytes(0) == 16
