@@ -35,6 +35,72 @@ def algorithmic_bytes(spec, out_itemsize=4):
     return n * spec.itemsize + codes + meta, codes + meta + n * out_itemsize
 
 
+def bench_classify(args, api, W, dev) -> int:
+    """Channel classification (three-sigma outliers, salient channels) over MobileNetV2-style
+    NCHW activations at batch 64 with channel-clustered outliers; one step classifies every
+    tensor of the set once.  Two streaming passes read each tensor twice."""
+    import numpy as np
+    import torch
+
+    shapes = ((64, 32, 112 * 112), (64, 96, 112 * 112), (64, 144, 56 * 56), (64, 192, 28 * 28), (64, 384, 14 * 14))
+    t0 = time.time()
+    host, jobs = [], []
+    for i, (outer, C, inner) in enumerate(shapes):
+        x, _ = W.outlier_channel_tensor(outer, C, inner, seed=i, dist="relu")
+        host.append(x)
+        xd = torch.from_numpy(x).to(dev)
+        ws = torch.empty(api.classify_workspace_bytes(x.size), dtype=torch.uint8, device=dev)
+        stats = torch.empty(4, dtype=torch.float64, device=dev)
+        counts = torch.empty(C, dtype=torch.int32, device=dev)
+        mask = torch.empty(C, dtype=torch.uint8, device=dev)
+        jobs.append((xd, outer, C, inner, outer * inner // 100, ws, stats, counts, mask))
+    torch.cuda.synchronize()
+    nbytes = sum(x.nbytes for x in host)
+    print(f"[bench] classify: {len(jobs)} tensors, {nbytes / 2**20:.1f} MiB resident "
+          f"(generated + uploaded in {time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for xd, outer, C, inner, mo, ws, stats, counts, mask in jobs:
+            api.fh_classify_channels(xd, outer, C, inner, 3.0, mo, workspace=ws, stats=stats, counts=counts,
+                                     mask=mask, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t_start) / args.steps
+    alg = 2 * nbytes                            # each pass reads the tensor once; outputs are negligible
+    result = {
+        "metric": "channel classification GB/s of input and % of HBM peak on 1 MI355X",
+        "value": round(nbytes / elapsed / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "classify_mobilenetv2_b64_outlier_channels", "tensors": len(jobs),
+                   "input_bytes": nbytes, "entry_point": "fh_classify_channels (per tensor)", "k_sigma": 3.0},
+        "roofline": {"bound": "hbm", "kernel": "moments + count passes (whole call)",
+                     "achieved": round(alg / elapsed / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(alg / elapsed / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        t_cpu, done = 0.0, 0
+        for x, (outer, C, inner) in zip(host, shapes):
+            t1 = time.perf_counter()
+            oracle.classify_channels(x, outer, C, inner, 3.0, outer * inner // 100)
+            t_cpu += time.perf_counter() - t1
+            done += x.nbytes
+            if t_cpu > 20.0:
+                break
+        result["cpu_baseline"] = {"value": round(done / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"{done / 2**20:.1f} MiB of the set, whole tensors, {t_cpu:.1f} s"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +111,9 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB device copies before the timed region, so that a "
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE against a known size")
+    ap.add_argument("--op", choices=("roundtrip", "classify"), default="roundtrip",
+                    help="roundtrip (default): compress + decompress of the tensor set; classify: the "
+                         "channel classification step (moments + outlier counts), measured on its own")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()
@@ -68,6 +137,9 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+
+    if args.op == "classify":
+        return bench_classify(args, api, W, dev)
 
     w = W.full_config(args.config)
     t0 = time.time()

@@ -143,7 +143,8 @@ int32_t   fh_batch_capacity(void);
  *   - S1 = sum x and S2 = sum x*x over all elements in binary64, summed PAIRWISE: the
  *     sequence in element order, zero-padded to a power of two, reduced by a balanced
  *     binary tree (this fixes every rounding, whatever the blocking);
- *   - mean = S1 / N, variance = max(S2 / N - mean*mean, 0), threshold = k*k * variance;
+ *   - mean = S1 / N (a total of -0.0 counts as +0.0), variance = max(S2 / N - mean*mean, 0),
+ *     threshold = k*k * variance;
  *   - x is an outlier iff d*d > threshold, d = (double)x - mean;
  *   - counts[c] = outliers in channel c; mask[c] = (counts[c] >= min_outliers).
  *

@@ -16,7 +16,9 @@
  *             balanced binary tree, s[i] = s[2i] + s[2i+1] level by level.  (This fixes
  *             the rounding of every partial sum while leaving a parallel machine free
  *             to form it in any blocking aligned to powers of two.)
- *   spread    mean = S1 / N, variance = max(S2 / N - mean*mean, 0),
+ *   spread    mean = S1 / N (a total of -0.0, which only an all-negative-zero tensor gives and
+ *             whose sign would depend on how far the sequence is padded, counts as +0.0),
+ *             variance = max(S2 / N - mean*mean, 0),
  *             threshold = (k*k) * variance        -- no square root is taken.
  *   outlier   element x is an outlier iff d*d > threshold with d = (double)x - mean,
  *             i.e. |x - mean| > k*sigma up to the rounding of these binary64 steps.
@@ -90,7 +92,7 @@ int fho_classify_channels(const void *x, int dtype, int64_t outer, int64_t chann
     double s1, s2;
     fho_pairwise_moments(x, dtype, numel, &s1, &s2);
     const double n = (double)numel;
-    const double mean = s1 / n;
+    const double mean = (s1 + 0.0) / n;            /* a total of -0.0 counts as +0.0 */
     const double mean_sq = mean * mean;
     double variance = s2 / n - mean_sq;
     if (!(variance > 0.0)) variance = 0.0;

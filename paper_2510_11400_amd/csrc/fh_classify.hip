@@ -229,20 +229,40 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f64x2* 
     if (lane == 0) out[span] = f64x2{s1, s2};
 }
 
-// ---- pass 1c: mean, variance, threshold; clear the counters -------------------------------
-__global__ __launch_bounds__(kThreads) void finish_moments_kernel(const f64x2* __restrict__ total, int64_t numel,
-                                                                  double k_sigma, double* __restrict__ stats,
-                                                                  uint32_t* __restrict__ counts, int channels)
+// ---- pass 1c: last level of the tree (at most 1024 partial sums), then mean, variance and
+//      threshold; clears the counters and the mask ----------------------------------------------
+__global__ __launch_bounds__(kThreads) void finish_moments_kernel(const f64x2* __restrict__ in, int64_t count,
+                                                                  int64_t numel, double k_sigma,
+                                                                  double* __restrict__ stats,
+                                                                  uint32_t* __restrict__ counts,
+                                                                  uint8_t* __restrict__ mask, int channels)
 {
-    for (int c = threadIdx.x; c < channels; c += kThreads) counts[c] = 0u;
-    if (threadIdx.x == 0) {
+    for (int c = threadIdx.x; c < channels; c += kThreads) { counts[c] = 0u; mask[c] = 0; }
+    if (threadIdx.x >= kWave) return;                         // the tree is one wave's work
+    constexpr int ROWS = 4, EPL = 4, ROW = kWave * EPL;
+    const uint32_t lane = threadIdx.x;
+    double a[ROWS], b[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        double d[EPL], q[EPL];
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            const int64_t i = r * ROW + lane * EPL + j;
+            const f64x2 p = i < count ? in[i] : f64x2{0.0, 0.0};
+            d[j] = p.x; q[j] = p.y;
+        }
+        a[r] = local_tree<EPL>(d);
+        b[r] = local_tree<EPL>(q);
+    }
+    double s1, s2;
+    span_tree<ROWS>(a, b, lane, s1, s2);
+    if (lane == 0) {
         double mean = 0.0, variance = 0.0;
         if (numel > 0) {
-            const f64x2 s = total[0];
             const double n = (double)numel;
-            mean = s.x / n;                                   // IEEE binary64 division
+            mean = (s1 + 0.0) / n;                            // a total of -0.0 counts as +0.0; IEEE division
             const double mean_sq = mean * mean;
-            variance = s.y / n - mean_sq;
+            variance = s2 / n - mean_sq;
             if (!(variance > 0.0)) variance = 0.0;
         }
         stats[0] = mean;
@@ -399,15 +419,16 @@ fh_status fh_classify_channels(const void* x, fh_dtype x_dtype, int64_t outer, i
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     f64x2* level = static_cast<f64x2*>(workspace);
-    const f64x2* total_pair = level;
+    const dim3 block(kThreads);
+    int64_t m = 0;
     if (numel > 0) {
-        int64_t m = ceil_div(numel, kSpan);
-        const dim3 grid0((uint32_t)ceil_div(m, kWavesPerBlock)), block(kThreads);
+        m = ceil_div(numel, kSpan);
+        const dim3 grid0((uint32_t)ceil_div(m, kWavesPerBlock));
         if (x_dtype == FH_F32)
             hipLaunchKernelGGL(moments_kernel<float>, grid0, block, 0, s, static_cast<const float*>(x), numel, level);
         else
             hipLaunchKernelGGL(moments_kernel<uint16_t>, grid0, block, 0, s, static_cast<const uint16_t*>(x), numel, level);
-        while (m > 1) {
+        while (m > kSpan) {                                   // the last <= 1024 partials are the finish kernel's
             const int64_t next = ceil_div(m, kSpan);
             f64x2* out = level + m;
             const dim3 grid((uint32_t)ceil_div(next, kWavesPerBlock));
@@ -415,10 +436,10 @@ fh_status fh_classify_channels(const void* x, fh_dtype x_dtype, int64_t outer, i
             level = out;
             m = next;
         }
-        total_pair = level;
     }
-    hipLaunchKernelGGL(finish_moments_kernel, dim3(1), dim3(kThreads), 0, s, total_pair, numel, k_sigma,
-                       static_cast<double*>(stats), static_cast<uint32_t*>(counts), (int)channels);
+    hipLaunchKernelGGL(finish_moments_kernel, dim3(1), block, 0, s, level, m, numel, k_sigma,
+                       static_cast<double*>(stats), static_cast<uint32_t*>(counts), static_cast<uint8_t*>(mask),
+                       (int)channels);
     if (numel > 0) {
         CountArgs a;
         a.x = x;
@@ -427,17 +448,21 @@ fh_status fh_classify_channels(const void* x, fh_dtype x_dtype, int64_t outer, i
         a.counts = static_cast<uint32_t*>(counts);
         a.inner = make_divisor((uint32_t)inner);
         a.channels = make_divisor((uint32_t)channels);
-        a.spans_per_wave = 8;                                 // 32768 elements per workgroup
+        // a workgroup clears and flushes `channels` histogram bins: give it enough elements
+        // to make that cheap, but no more (short workgroups measured faster)
+        a.spans_per_wave = channels <= 512 ? 1 : channels <= 2048 ? 2 : channels <= 8192 ? 4 : 8;
         const int64_t per_block = (int64_t)a.spans_per_wave * kWavesPerBlock * kSpan;
-        const dim3 grid((uint32_t)ceil_div(numel, per_block)), block(kThreads);
+        const dim3 grid((uint32_t)ceil_div(numel, per_block));
         const size_t lds = (size_t)channels * sizeof(uint32_t);
         if (x_dtype == FH_F32)
             hipLaunchKernelGGL(count_outliers_kernel<float>, grid, block, lds, s, a);
         else
             hipLaunchKernelGGL(count_outliers_kernel<uint16_t>, grid, block, lds, s, a);
+        // (an empty tensor has no outliers: the mask the finish kernel cleared stands)
+        hipLaunchKernelGGL(mask_kernel, dim3((uint32_t)ceil_div(channels, kThreads)), block, 0, s,
+                           static_cast<const uint32_t*>(counts), (int)channels, min_outliers,
+                           static_cast<uint8_t*>(mask));
     }
-    hipLaunchKernelGGL(mask_kernel, dim3((uint32_t)ceil_div(channels, kThreads)), dim3(kThreads), 0, s,
-                       static_cast<const uint32_t*>(counts), (int)channels, min_outliers, static_cast<uint8_t*>(mask));
     return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
 }
 

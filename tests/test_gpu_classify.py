@@ -73,6 +73,8 @@ def test_degenerate_inputs(api):
         x = np.full(6 * 10 * 50, value, dtype=f32)
         counts, mask = _check(api, x, 6, 10, 50, name="constant")
         assert not counts.any() and not mask.any()
+    for n in (1, 5, 1024, 1500):                             # negative zeros of any length
+        _check(api, np.full(n, -0.0, dtype=f32), 1, 1, n, name="negative zeros")
     # empty outer: outputs are zeroed, nothing is read
     gs, gc, gm = api.fh_classify_channels(torch.empty(0, device="cuda"), 0, 12, 9)
     torch.cuda.synchronize()

@@ -88,6 +88,10 @@ def test_constant_and_zero_tensors_have_no_outliers():
         stats, counts, mask = oracle.classify_channels(x, 6, 5, 7)
         assert stats[0] == value and stats[1] == 0.0 and stats[2] == 0.0
         assert not counts.any() and not mask.any()
+    # negative zeros: the mean comes out as +0.0 whatever the length (padding must not show)
+    for n in (1, 3, 1024, 1500):
+        stats, counts, _ = oracle.classify_channels(np.full(n, -0.0, dtype=f32), 1, 1, n)
+        assert stats[0] == 0.0 and not np.signbit(stats[0]) and not counts.any()
     stats, counts, mask = oracle.classify_channels(np.zeros(0, dtype=f32), 0, 4, 3)
     assert stats.tolist() == [0.0, 0.0, 0.0, 0.0] and not counts.any()
 
