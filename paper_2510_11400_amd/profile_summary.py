@@ -128,17 +128,43 @@ def read_traffic(path: str) -> Dict[str, float]:
     return out if digest == kernel_source_digest() else {}
 
 
+def summarise_trace_only(trace_dir, bench_json, commands) -> str:
+    """Per-kernel call counts and durations of every library kernel in a kernel trace."""
+    per = defaultdict(lambda: [0, 0, 10 ** 18, 0])
+    with open(_one(os.path.join(trace_dir, "**", "*kernel_trace.csv"))) as fh:
+        for row in csv.DictReader(fh):
+            name = row["Kernel_Name"]
+            if "fh::" not in name:
+                continue
+            short = name.split("fh::(anonymous namespace)::", 1)[1].split("(")[0]
+            d = int(row["End_Timestamp"]) - int(row["Start_Timestamp"])
+            e = per[short]
+            e[0] += 1; e[1] += d; e[2] = min(e[2], d); e[3] = max(e[3], d)
+    bench = json.loads(open(bench_json).read().strip().splitlines()[-1])
+    lines = ["# rocprofv3 summary: " + bench["config"]["workload"],
+             "# commands (each from the repository root, after `cd /tmp && export TMPDIR=/tmp`):"]
+    lines += ["#   " + c for c in commands]
+    lines += ["", f"{'kernel':44s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'total_us':>10s}"]
+    for k, (calls, total, lo, hi) in sorted(per.items(), key=lambda kv: -kv[1][1]):
+        lines.append(f"{k:44s} {calls:6d} {total / calls / 1e3:9.1f} {lo / 1e3:9.1f} {hi / 1e3:9.1f} {total / 1e3:10.1f}")
+    lines += ["", "[bench_line]", json.dumps(bench)]
+    return "\n".join(lines) + "\n"
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--trace", required=True)
-    ap.add_argument("--fetch", required=True)
-    ap.add_argument("--write", required=True)
+    ap.add_argument("--fetch")
+    ap.add_argument("--write")
     ap.add_argument("--bench-json", required=True)
     ap.add_argument("--copy-bytes", type=int, default=1 << 30)
     ap.add_argument("--out", required=True)
     ap.add_argument("--command", action="append", default=[])
     a = ap.parse_args()
-    text = summarise(a.trace, a.fetch, a.write, a.bench_json, a.copy_bytes, a.command)
+    if a.fetch and a.write:
+        text = summarise(a.trace, a.fetch, a.write, a.bench_json, a.copy_bytes, a.command)
+    else:
+        text = summarise_trace_only(a.trace, a.bench_json, a.command)
     with open(a.out, "w") as fh:
         fh.write(text)
     print(text)
