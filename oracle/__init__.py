@@ -17,7 +17,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libfho.so")
-_SRCS = [os.path.join(_HERE, "fho.c"), os.path.join(_HERE, "fho_classify.c")]
+_SRCS = [os.path.join(_HERE, n) for n in ("fho.c", "fho_classify.c", "fho_mixed.c")]
 
 F32, BF16 = 0, 1
 NEAREST, STOCHASTIC = 0, 1
@@ -69,6 +69,18 @@ def lib() -> ctypes.CDLL:
                                             ctypes.c_int64, ctypes.c_double, ctypes.c_int64,
                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.fho_classify_channels.restype = ctypes.c_int
+        L.fho_channel_slots.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
+        L.fho_channel_slots.restype = ctypes.c_int64
+        L.fho_compress_mixed.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                         ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_uint64,
+                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.fho_compress_mixed.restype = ctypes.c_int
+        L.fho_decompress_mixed.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                           ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                           ctypes.c_void_p, ctypes.c_int64,
+                                           ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+        L.fho_decompress_mixed.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -160,3 +172,52 @@ def classify_channels(x: np.ndarray, outer: int, channels: int, inner: int, k_si
     if rc != 0:
         raise ValueError("fho_classify_channels rejected its arguments")
     return stats, counts, mask
+
+
+def channel_slots(mask: np.ndarray, raw_channels: int) -> Tuple[np.ndarray, int]:
+    """-> (slots int16[C]: raw-store row of each kept salient channel, -1 otherwise; slots used)."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    slots = np.empty(mask.size, dtype=np.int16)
+    used = lib().fho_channel_slots(mask.ctypes.data, int(mask.size), int(raw_channels), slots.ctypes.data)
+    if used < 0:
+        raise ValueError("fho_channel_slots rejected its arguments")
+    return slots, int(used)
+
+
+def compress_mixed(x: np.ndarray, outer: int, channels: int, inner: int, slots: np.ndarray, raw_channels: int,
+                   group_size: int, bits: int, rounding="nearest", seed: int = 0, tensor_id: int = 0,
+                   dtype="f32", raw_fill=0):
+    """-> (packed, meta[n_groups, 2], raw[outer * raw_channels * inner] in x's dtype; rows of
+    unused slots keep `raw_fill`)."""
+    d = _check_input(x, dtype)
+    n = outer * channels * inner
+    if x.size != n:
+        raise ValueError("x.size != outer * channels * inner")
+    slots = np.ascontiguousarray(slots, dtype=np.int16)
+    packed = np.empty(packed_bytes(n, bits), dtype=np.uint8)
+    meta = np.empty((meta_bytes(n, group_size) // 8, 2), dtype=np.float32)
+    raw = np.full(outer * raw_channels * inner, raw_fill, dtype=x.dtype)
+    rc = lib().fho_compress_mixed(x.ctypes.data, d, outer, channels, inner, slots.ctypes.data, int(raw_channels),
+                                  group_size, bits, _ROUNDS[rounding], seed, tensor_id,
+                                  packed.ctypes.data, meta.ctypes.data, raw.ctypes.data)
+    if rc != 0:
+        raise ValueError("fho_compress_mixed rejected its arguments")
+    return packed, meta, raw
+
+
+def decompress_mixed(packed: np.ndarray, meta: np.ndarray, raw: np.ndarray, outer: int, channels: int, inner: int,
+                     slots: np.ndarray, raw_channels: int, group_size: int, bits: int,
+                     raw_dtype="f32", out_dtype="f32") -> np.ndarray:
+    rd = _check_input(raw, raw_dtype) if raw.size else _DTYPES[raw_dtype]
+    od = _DTYPES[out_dtype]
+    n = outer * channels * inner
+    out = np.empty(n, dtype=np.float32 if od == F32 else np.uint16)
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    meta = np.ascontiguousarray(meta, dtype=np.float32)
+    slots = np.ascontiguousarray(slots, dtype=np.int16)
+    rc = lib().fho_decompress_mixed(packed.ctypes.data, meta.ctypes.data, raw.ctypes.data, rd,
+                                    outer, channels, inner, slots.ctypes.data, int(raw_channels),
+                                    group_size, bits, od, out.ctypes.data)
+    if rc != 0:
+        raise ValueError("fho_decompress_mixed rejected its arguments")
+    return out

@@ -73,6 +73,25 @@ int fho_classify_channels(const void *x, int dtype, int64_t outer, int64_t chann
                           double k_sigma, int64_t min_outliers,
                           double stats[4], uint32_t *counts, uint8_t *mask);
 
+/* ---- salient channels routed around the quantiser (fho_mixed.c; Section 4.4.1: only normal
+ *      channels are quantised; salient channels are kept verbatim here) ---- */
+
+/* slots[c] = 0, 1, 2, ... for salient channels in channel order while fewer than raw_channels
+ * are in use, -1 for every other channel.  Returns the number of slots used, or -1. */
+int64_t fho_channel_slots(const uint8_t *mask, int64_t channels, int64_t raw_channels, int16_t *slots);
+
+/* Tensor viewed as [outer][channels][inner].  raw: [outer][raw_channels][inner] elements of
+ * `dtype`; rows of unused slots are left untouched.  packed / meta as in fho_compress. */
+int fho_compress_mixed(const void *x, int dtype, int64_t outer, int64_t channels, int64_t inner,
+                       const int16_t *slots, int64_t raw_channels,
+                       int group_size, int bits, int rounding, uint64_t seed, uint64_t tensor_id,
+                       uint8_t *packed, float *meta, void *raw);
+
+int fho_decompress_mixed(const uint8_t *packed, const float *meta, const void *raw, int raw_dtype,
+                         int64_t outer, int64_t channels, int64_t inner,
+                         const int16_t *slots, int64_t raw_channels,
+                         int group_size, int bits, int out_dtype, void *out);
+
 #ifdef __cplusplus
 }
 #endif

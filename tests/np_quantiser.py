@@ -97,3 +97,52 @@ def decompress_np(codes: np.ndarray, meta: np.ndarray, G: int) -> np.ndarray:
     g = np.arange(codes.size) // G
     v = codes.astype(np.float64) * meta[g, 0].astype(np.float64) + meta[g, 1].astype(np.float64)
     return v.astype(np.float32)
+
+
+def compress_mixed_np(x32: np.ndarray, outer: int, channels: int, inner: int, kept: np.ndarray, G: int, B: int,
+                      rounding: str = "nearest", seed: int = 0, tensor_id: int = 0):
+    """The same quantiser when the channels flagged in `kept` (bool[channels]) are routed around
+    it (Section 4.4.1: only normal channels are quantised): their elements are invisible to
+    the group statistics and get code 0.  -> (packed, meta, codes)."""
+    f32 = np.float32
+    n = x32.size
+    assert n == outer * channels * inner
+    normal = np.broadcast_to(~np.asarray(kept, dtype=bool)[None, :, None], (outer, channels, inner)).reshape(n)
+    ng = (n + G - 1) // G
+    L = f32((1 << B) - 1)
+    pad = ng * G - n
+    lo = np.concatenate([np.where(normal, x32, f32(np.inf)), np.full(pad, np.inf, dtype=f32)]).reshape(ng, G)
+    hi = np.concatenate([np.where(normal, x32, f32(-np.inf)), np.full(pad, -np.inf, dtype=f32)]).reshape(ng, G)
+    mn = lo.min(axis=1)
+    mx = hi.max(axis=1)
+    empty = mn > mx
+    mn = np.where(empty, f32(0), mn).astype(f32)
+    mx = np.where(empty, f32(0), mx).astype(f32)
+    rng = (mx - mn).astype(f32)
+    deg = rng < f32(2.0 ** -100)
+    safe = np.where(deg, f32(1), rng).astype(f32)
+    scale = np.where(deg, f32(0), (safe / L).astype(f32)).astype(f32)
+    inv = np.where(deg, f32(0), (L / safe).astype(f32)).astype(f32)
+    zero = (mn + f32(0)).astype(f32)
+    xs = np.concatenate([np.where(normal, x32, f32(0)), np.zeros(pad, dtype=f32)]).reshape(ng, G)
+    with np.errstate(invalid="ignore", over="ignore"):
+        q = ((xs - mn[:, None]).astype(f32) * inv[:, None]).astype(f32)
+    q = np.minimum(np.maximum(q, f32(0)), L).astype(f32)
+    q = np.where(deg[:, None], f32(0), q).ravel()[:n]
+    if rounding == "nearest":
+        codes = np.rint(q).astype(np.uint32)
+    else:
+        k = np.floor(q).astype(f32)
+        frac = (q - k).astype(f32)
+        u = (random16_np(seed, tensor_id, n).astype(f32) * f32(2.0 ** -16)).astype(f32)
+        codes = k.astype(np.uint32) + (u < frac).astype(np.uint32)
+    codes = np.where(normal, codes, np.uint32(0)).astype(np.uint32)
+    per = 8 // B
+    raw = (n * B + 7) // 8
+    total = (raw + 15) // 16 * 16 if n else 0
+    cpad = np.concatenate([codes, np.zeros(raw * per - n, dtype=np.uint32)]).reshape(raw, per)
+    shifts = (np.arange(per, dtype=np.uint32) * np.uint32(B))[None, :]
+    by = np.bitwise_or.reduce(cpad << shifts, axis=1).astype(np.uint8)
+    packed = np.concatenate([by, np.zeros(total - raw, dtype=np.uint8)])
+    meta = np.stack([scale, zero], axis=1).astype(f32)
+    return packed, meta, codes.astype(np.uint8)
