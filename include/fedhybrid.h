@@ -62,7 +62,7 @@ typedef enum fh_status {
     FH_ERR_ALIGNMENT = 8,
     FH_ERR_LAUNCH = 9,           /* the HIP runtime refused the launch */
     FH_ERR_BAD_COUNT = 10,       /* negative item count */
-    FH_ERR_BAD_SHAPE = 11,       /* outer / channels / inner out of range */
+    FH_ERR_BAD_SHAPE = 11,       /* outer / channels / inner / raw_channels out of range */
     FH_ERR_BAD_PARAM = 12        /* k_sigma not positive, or min_outliers < 1 */
 } fh_status;
 
@@ -160,6 +160,45 @@ fh_status fh_classify_channels(const void *x, fh_dtype x_dtype, int64_t outer, i
                                double k_sigma, int64_t min_outliers,
                                void *workspace, size_t workspace_cap,
                                void *stats, void *counts, void *mask, void *stream);
+
+/* ---- salient channels routed around the quantiser ----------------------------------------
+ * Section 4.4.1 quantises only the normal channels, so that the outliers clustered in the
+ * salient channels do not stretch the quantiser's range; the paper stores salient channels
+ * by a sparse / predictive scheme of its own, this library keeps them verbatim ("raw")
+ * beside the quantised stream.  The definition used:
+ *
+ *   - the tensor is viewed as [outer][channels][inner] as above; element i belongs to
+ *     channel (i / inner) mod channels;
+ *   - slots[c] (int16) is the row of the raw store that keeps channel c, 0 <= slot <
+ *     raw_channels; any other value (fh_channel_slots writes -1) means "normal channel";
+ *   - fh_channel_slots numbers the channels whose mask byte is non-zero 0, 1, 2, ... in
+ *     channel order; once raw_channels slots are used the remaining ones stay normal;
+ *   - raw is [outer][raw_channels][inner] in the input's dtype; an element of a kept channel
+ *     is copied bit for bit to raw[(o * raw_channels + slot) * inner + j]; rows of unused
+ *     slots are not written;
+ *   - the quantiser runs over the flattened tensor exactly as in fh_compress (same groups,
+ *     same random bits per element index, same packing), except that elements of kept
+ *     channels are invisible to a group's min / max and get code 0; a group without normal
+ *     elements has scale = zero = 0;
+ *   - fh_decompress_mixed returns fmaf(code, scale, zero) for normal elements and the raw
+ *     value, converted to out_dtype (bf16 -> f32 exact, f32 -> bf16 nearest even), for
+ *     elements of kept channels.
+ *
+ * mask: device, uint8[channels] (as fh_classify_channels writes it).  slots: device, 16-byte
+ * aligned, int16[channels].  raw: device, 16-byte aligned, fh_raw_bytes() bytes.  The other
+ * buffers are as in fh_compress / fh_decompress.  outer * channels * inner <= 2^31,
+ * 0 <= raw_channels <= channels.  With raw_channels == 0 the result equals fh_compress's
+ * and raw may be NULL.  Everything is enqueued on `stream`; nothing is allocated. */
+size_t    fh_raw_bytes(int64_t outer, int64_t raw_channels, int64_t inner, fh_dtype dtype);
+fh_status fh_channel_slots(const void *mask, int64_t channels, int64_t raw_channels, void *slots, void *stream);
+fh_status fh_compress_mixed(const void *x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
+                            const fh_params *params, const void *slots, int64_t raw_channels,
+                            void *packed, size_t packed_cap, void *meta, size_t meta_cap,
+                            void *raw, size_t raw_cap, void *stream);
+fh_status fh_decompress_mixed(const void *packed, const void *meta, const void *raw, fh_dtype raw_dtype,
+                              int64_t outer, int64_t channels, int64_t inner,
+                              const fh_params *params, const void *slots, int64_t raw_channels,
+                              fh_dtype out_dtype, void *out, size_t out_cap, void *stream);
 
 const char *fh_status_string(fh_status s);
 

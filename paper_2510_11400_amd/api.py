@@ -30,7 +30,8 @@ FH_ROUND_NEAREST, FH_ROUND_STOCHASTIC = 0, 1
 
 EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "fh_roundtrip",
            "fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch", "fh_batch_capacity",
-           "fh_classify_workspace_bytes", "fh_classify_channels", "fh_status_string")
+           "fh_classify_workspace_bytes", "fh_classify_channels",
+           "fh_raw_bytes", "fh_channel_slots", "fh_compress_mixed", "fh_decompress_mixed", "fh_status_string")
 
 
 class fh_params(ctypes.Structure):
@@ -71,6 +72,20 @@ _lib.fh_classify_channels.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_in
                                       ctypes.c_double, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.fh_classify_channels.restype = ctypes.c_int
+_lib.fh_raw_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+_lib.fh_raw_bytes.restype = ctypes.c_size_t
+_lib.fh_channel_slots.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+_lib.fh_channel_slots.restype = ctypes.c_int
+_lib.fh_compress_mixed.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                   _P(fh_params), ctypes.c_void_p, ctypes.c_int64,
+                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fh_compress_mixed.restype = ctypes.c_int
+_lib.fh_decompress_mixed.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                     ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                     _P(fh_params), ctypes.c_void_p, ctypes.c_int64,
+                                     ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fh_decompress_mixed.restype = ctypes.c_int
 _lib.fh_batch_capacity.argtypes = []
 _lib.fh_batch_capacity.restype = ctypes.c_int32
 _lib.fh_status_string.argtypes = [ctypes.c_int]
@@ -298,3 +313,80 @@ def fh_classify_channels(x: torch.Tensor, outer: int, channels: int, inner: int,
                                          workspace.numel() * workspace.element_size(),
                                          stats.data_ptr(), counts.data_ptr(), mask.data_ptr(), _stream_ptr(stream)))
     return stats, counts, mask
+
+
+def raw_bytes(outer: int, raw_channels: int, inner: int, dtype) -> int:
+    return int(_lib.fh_raw_bytes(outer, raw_channels, inner, _DT[dtype]))
+
+
+def _nbytes(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None or t.numel() == 0 else t.data_ptr()
+
+
+def fh_channel_slots(mask: torch.Tensor, raw_channels: int, slots: Optional[torch.Tensor] = None,
+                     stream=None) -> torch.Tensor:
+    """Enqueue the numbering of the salient channels in `mask` (uint8[channels]); returns the
+    device tensor slots int16[channels]."""
+    _device_tensor(mask, "mask")
+    channels = mask.numel()
+    if slots is None:
+        slots = torch.empty(channels, dtype=torch.int16, device=mask.device)
+    _device_tensor(slots, "slots")
+    if mask.element_size() != 1 or _nbytes(slots) < 2 * channels:
+        raise FedHybridError(7)
+    with torch.cuda.device(mask.device):
+        _check(_lib.fh_channel_slots(mask.data_ptr(), channels, int(raw_channels), slots.data_ptr(),
+                                     _stream_ptr(stream)))
+    return slots
+
+
+def fh_compress_mixed(x: torch.Tensor, outer: int, channels: int, inner: int, slots: torch.Tensor,
+                      raw_channels: int, group_size: int, bits: int, rounding="nearest", seed: int = 0,
+                      tensor_id: int = 0, packed: Optional[torch.Tensor] = None,
+                      meta: Optional[torch.Tensor] = None, raw: Optional[torch.Tensor] = None, stream=None):
+    """Enqueue compression of `x` viewed as [outer][channels][inner] with the channels that
+    `slots` marks kept verbatim; returns (packed, meta, raw) device tensors."""
+    _device_tensor(x, "x")
+    _device_tensor(slots, "slots")
+    n = x.numel()
+    if n != outer * channels * inner:
+        raise ValueError("x.numel() != outer * channels * inner")
+    if _nbytes(slots) < 2 * channels:
+        raise FedHybridError(7)
+    if packed is None or meta is None:
+        packed, meta = alloc_compressed(n, group_size, bits, x.device)
+    if raw is None:
+        raw = torch.empty(max(0, outer * raw_channels * inner), dtype=x.dtype, device=x.device)
+    p = make_params(group_size, bits, rounding, seed, tensor_id)
+    with torch.cuda.device(x.device):
+        _check(_lib.fh_compress_mixed(x.data_ptr(), _dtype_code(x), outer, channels, inner, ctypes.byref(p),
+                                      slots.data_ptr(), int(raw_channels),
+                                      _ptr(packed), _nbytes(packed), _ptr(meta), _nbytes(meta),
+                                      _ptr(raw), _nbytes(raw), _stream_ptr(stream)))
+    return packed, meta, raw
+
+
+def fh_decompress_mixed(packed: torch.Tensor, meta: torch.Tensor, raw: torch.Tensor, outer: int, channels: int,
+                        inner: int, slots: torch.Tensor, raw_channels: int, group_size: int, bits: int,
+                        out_dtype=torch.float32, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Enqueue the inverse of fh_compress_mixed; returns the flat restored tensor."""
+    for t, what in ((packed, "packed"), (meta, "meta"), (raw, "raw"), (slots, "slots")):
+        _device_tensor(t, what)
+    n = outer * channels * inner
+    if out is None:
+        out = torch.empty(n, dtype=out_dtype, device=packed.device)
+    _device_tensor(out, "out")
+    if _nbytes(packed) < packed_bytes(n, bits) or _nbytes(meta) < meta_bytes(n, group_size) \
+            or _nbytes(slots) < 2 * channels or _nbytes(raw) < raw_bytes(outer, raw_channels, inner, raw.dtype):
+        raise FedHybridError(7)
+    p = make_params(group_size, bits)
+    with torch.cuda.device(packed.device):
+        _check(_lib.fh_decompress_mixed(_ptr(packed), _ptr(meta), _ptr(raw), _dtype_code(raw),
+                                        outer, channels, inner, ctypes.byref(p), slots.data_ptr(),
+                                        int(raw_channels), _dtype_code(out), _ptr(out), _nbytes(out),
+                                        _stream_ptr(stream)))
+    return out

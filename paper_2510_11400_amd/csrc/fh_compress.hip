@@ -14,6 +14,12 @@
 // Follows the paper's Section 4.4.1 (normal channels: linear-scale quantisation;
 // zeros must be preserved) with the parameters the paper leaves open taken from the
 // caller (group size, bits, rounding, seed).
+//
+// The MIXED variants additionally route the channels the caller marks as kept (salient
+// channels, same section) around the quantiser: their elements are copied to a raw store,
+// turned into NaN -- which v_min_f32 / v_max_f32 ignore -- before the statistics, and get
+// code 0.
+#include "fh_channels.hpp"
 #include "fh_device.hpp"
 #include "fh_kernels.hpp"
 
@@ -274,6 +280,32 @@ __device__ __forceinline__ void local_minmax(const float (&x)[N], float& mn, flo
     }
 }
 
+// ---- kept channels (MIXED) ---------------------------------------------------------------
+template <typename InT> struct RawElem;
+template <> struct RawElem<float> {
+    __device__ static __forceinline__ void put(void* raw, uint64_t i, float v) {
+        static_cast<uint32_t*>(raw)[i] = __builtin_bit_cast(uint32_t, v);
+    }
+};
+template <> struct RawElem<uint16_t> {
+    __device__ static __forceinline__ void put(void* raw, uint64_t i, float v) {
+        static_cast<uint16_t*>(raw)[i] = (uint16_t)(__builtin_bit_cast(uint32_t, v) >> 16);   // the original bits
+    }
+};
+
+// Copy the elements flagged in `mask` to the raw store and hide them from the statistics.
+template <typename InT, int N>
+__device__ __forceinline__ void divert_kept(const ChannelMap& cm, const ElemPos& p, uint32_t mask, float (&x)[N])
+{
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        if (mask & (1u << j)) {
+            RawElem<InT>::put(cm.raw, raw_index(cm, p, j), x[j]);
+            x[j] = __builtin_bit_cast(float, 0x7fc00000u);
+        }
+    }
+}
+
 // ---- interior spans: the 4-row layout --------------------------------------------------
 //   * the four rows' min/max are reduce-scattered over each quad (lane xor 1 keeps two
 //     rows, lane xor 2 keeps one), then all-reduced over the quads of the group by
@@ -286,10 +318,11 @@ __device__ __forceinline__ void local_minmax(const float (&x)[N], float& mn, flo
 //   * fp32 (4 elements per lane and row): a Philox block (8 elements) spans a lane pair;
 //     the even lane computes the blocks of rows 0 and 2, the odd lane those of rows 1
 //     and 3, and they trade the halves.  bf16 (8 per lane and row): a block per lane and row.
-template <typename InT, int G, int B, bool STOCH>
+template <typename InT, int G, int B, bool STOCH, bool MIXED>
 __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wave_base, const InT* xw,
                                               uint8_t* pw, float* mw, uint32_t lane,
-                                              uint8_t* stage_codes, float* stage_meta)
+                                              uint8_t* stage_codes, float* stage_meta,
+                                              const ChannelMap* cm, const ElemPos& wave_pos)
 {
     using L = Layout<InT>;
     constexpr int ROWS = 4, EPL = L::EPL, ROW = L::ROW;
@@ -304,6 +337,16 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
     float x[ROWS][EPL];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) Loader<InT>::row(xw + r * ROW + lane * EPL, x[r]);
+
+    uint32_t keptm[ROWS] = {};                                // bit j: element j of the row is kept raw
+    if constexpr (MIXED) {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            const ElemPos p = advance(*cm, wave_pos, r * ROW + lane * EPL);
+            keptm[r] = kept_mask<EPL>(*cm, p);
+            if (keptm[r]) divert_kept<InT, EPL>(*cm, p, keptm[r], x[r]);
+        }
+    }
 
     float mn[ROWS], mx[ROWS];
 #pragma unroll
@@ -333,7 +376,7 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
 
     // one division per lane: even quads range / L, odd quads L / range
     const float range = hi - lo;
-    const bool degenerate = range < 0x1p-100f;
+    const bool degenerate = !(range >= 0x1p-100f);            // also a group without normal elements (NaN)
     const bool odd_quad = lane & 4u;
     const float mine = (odd_quad ? Lf : range) / (odd_quad ? range : Lf);      // IEEE-correct division
     const float other = from_other_quad<RUN>(mine);
@@ -341,8 +384,10 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
     const float inv = degenerate ? 0.0f : (odd_quad ? mine : other);
 
     // the first quad of every group publishes the meta of the four rows (-0.0 -> +0.0)
+    float zero = lo + 0.0f;
+    if constexpr (MIXED) zero = lo == lo ? zero : 0.0f;       // no normal element: {0, 0}
     if ((lane & (LPG - 1)) < 4u)
-        *reinterpret_cast<stage_f32x2*>(stage_meta + 2 * (held * (ROW / G) + lane / LPG)) = f32x2{scale, lo + 0.0f};
+        *reinterpret_cast<stage_f32x2*>(stage_meta + 2 * (held * (ROW / G) + lane / LPG)) = f32x2{scale, zero};
 
     // complemented random words of this lane's elements, per row; a span starts on a
     // multiple of its block count, so the additions below never carry out of the low word
@@ -389,6 +434,12 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
         for (int j = 0; j < EPL; j += 2) {
             e[j] = element_word<B, STOCH, 0>(q[j], nr[r][j >> 1]);
             e[j + 1] = element_word<B, STOCH, 1>(q[j + 1], nr[r][j >> 1]);
+        }
+        if constexpr (MIXED) {
+            if (keptm[r]) {
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) e[j] = (keptm[r] & (1u << j)) ? 0u : e[j];
+            }
         }
         // codes go to the staging area in element order
         uint8_t* sc = stage_codes + r * ROW_CODE_BYTES + lane * (EPL * B / 8);
@@ -461,9 +512,10 @@ __device__ __forceinline__ void store_codes(uint8_t* dst, uint32_t w0, uint32_t 
 
 // The tensor ends inside this wave's span.  All 64 lanes stay active through the
 // reductions; missing elements enter them as +inf / -inf and get code 0.
-template <typename InT, int G, int B, bool STOCH>
+template <typename InT, int G, int B, bool STOCH, bool MIXED>
 __device__ __forceinline__ void compress_edge(const CompressItem& it, int64_t wave_base, int64_t extent,
-                                              const InT* xw, uint8_t* pw, float* mw, uint32_t lane)
+                                              const InT* xw, uint8_t* pw, float* mw, uint32_t lane,
+                                              const ChannelMap* cm, const ElemPos& wave_pos)
 {
     constexpr int LPG = G / kEPL;                             // lanes per group
     constexpr int LOGG = Log2<G>::v;
@@ -478,18 +530,25 @@ __device__ __forceinline__ void compress_edge(const CompressItem& it, int64_t wa
         const int64_t left = numel - i0;
         const int valid = left >= kEPL ? kEPL : (left > 0 ? (int)left : 0);
         float x[kEPL];
+#pragma unroll
+        for (int j = 0; j < kEPL; ++j) x[j] = j < valid ? Loader<InT>::one(xw, e0 + j) : 0.0f;
+        uint32_t keptm = 0u;
+        if constexpr (MIXED) {
+            const ElemPos p = advance(*cm, wave_pos, e0);
+            keptm = kept_mask<kEPL>(*cm, p) & ((1u << valid) - 1u);
+            if (keptm) divert_kept<InT, kEPL>(*cm, p, keptm, x);
+        }
         float mn = 0.0f, mx = 0.0f;
 #pragma unroll
         for (int j = 0; j < kEPL; ++j) {
             const bool ok = j < valid;
-            x[j] = ok ? Loader<InT>::one(xw, e0 + j) : 0.0f;
             const float lo = ok ? x[j] : __builtin_inff();
             const float hi = ok ? x[j] : -__builtin_inff();
             mn = j == 0 ? lo : vmin(mn, lo);
             mx = j == 0 ? hi : vmax(mx, hi);
         }
         group_minmax<LPG>(mn, mx);
-        if (mn > mx) { mn = 0.0f; mx = 0.0f; }                // a run with no element at all
+        if (!(mn <= mx)) { mn = 0.0f; mx = 0.0f; }            // a run with no (normal) element at all
         float scale, inv;
         scale_and_inverse<B>(mx - mn, odd_lane, scale, inv);
         // a group exists iff its first element does
@@ -513,7 +572,7 @@ __device__ __forceinline__ void compress_edge(const CompressItem& it, int64_t wa
             e[j + 1] = element_word<B, STOCH, 1>(t1 * inv, nr[j >> 1]);
         }
 #pragma unroll
-        for (int j = 0; j < kEPL; ++j) e[j] = (j < valid) ? e[j] : 0u;
+        for (int j = 0; j < kEPL; ++j) e[j] = (j < valid && !(keptm & (1u << j))) ? e[j] : 0u;
         uint32_t w0, w1;
         pack8<B, POS>(e, w0, w1);
         // chunks are size-aligned and the padded length is a multiple of 16, so a chunk is
@@ -523,8 +582,9 @@ __device__ __forceinline__ void compress_edge(const CompressItem& it, int64_t wa
     }
 }
 
-template <typename InT, int G, int B, bool STOCH>
-__device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t tile, uint32_t* stage)
+template <typename InT, int G, int B, bool STOCH, bool MIXED = false>
+__device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t tile, uint32_t* stage,
+                                              const ChannelMap* cm = nullptr)
 {
     using L = Layout<InT>;
     const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -540,12 +600,14 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
     const InT* xw = static_cast<const InT*>(it.x) + wave_base;
     uint8_t* pw = it.packed + ((uint64_t)wave_base * B >> 3);
     float* mw = it.meta + 2 * (wave_base >> Log2<G>::v);
+    ElemPos wave_pos = {0u, 0u, 0u};
+    if constexpr (MIXED) wave_pos = locate_base(*cm, (uint32_t)wave_base);
     if (wave_base + L::SPAN <= numel) {
         uint8_t* stage_codes = reinterpret_cast<uint8_t*>(stage + wave * kStageDwords);
         float* stage_meta = reinterpret_cast<float*>(stage_codes + kStageCodeBytes);
-        compress_span<InT, G, B, STOCH>(it, wave_base, xw, pw, mw, lane, stage_codes, stage_meta);
+        compress_span<InT, G, B, STOCH, MIXED>(it, wave_base, xw, pw, mw, lane, stage_codes, stage_meta, cm, wave_pos);
     } else {
-        compress_edge<InT, G, B, STOCH>(it, wave_base, extent, xw, pw, mw, lane);
+        compress_edge<InT, G, B, STOCH, MIXED>(it, wave_base, extent, xw, pw, mw, lane, cm, wave_pos);
     }
 }
 
@@ -572,6 +634,23 @@ __global__ __launch_bounds__(kCBlock) void compress_kernel(const CompressBatch a
     }
 }
 
+// One tensor whose kept channels go to the raw store.
+template <typename InT, int G>
+__global__ __launch_bounds__(kCBlock) void compress_mixed_kernel(const CompressItem it, const ChannelMap cm)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t stage[kWaves * kStageDwords];
+    const uint32_t tile = blockIdx.x;
+    switch (it.bits * 2 + it.stochastic) {
+        case 4:  compress_tile<InT, G, 2, false, true>(it, tile, stage, &cm); break;
+        case 5:  compress_tile<InT, G, 2, true , true>(it, tile, stage, &cm); break;
+        case 8:  compress_tile<InT, G, 4, false, true>(it, tile, stage, &cm); break;
+        case 9:  compress_tile<InT, G, 4, true , true>(it, tile, stage, &cm); break;
+        case 16: compress_tile<InT, G, 8, false, true>(it, tile, stage, &cm); break;
+        case 17: compress_tile<InT, G, 8, true , true>(it, tile, stage, &cm); break;
+        default: break;
+    }
+}
+
 }  // namespace
 
 int compress_tile_elems(int dtype, int) { return dtype == 0 ? Layout<float>::TILE : Layout<uint16_t>::TILE; }
@@ -582,6 +661,26 @@ hipError_t launch_compress(const CompressBatch& b, int dtype, int group_size, hi
     if (tiles == 0) return hipSuccess;
     const dim3 grid(tiles), block(kCBlock);
 #define FH_LAUNCH(T, GS) hipLaunchKernelGGL((compress_kernel<T, GS>), grid, block, 0, s, b)
+    if (dtype == 0) {
+        if (group_size == 64) FH_LAUNCH(float, 64);
+        else if (group_size == 128) FH_LAUNCH(float, 128);
+        else FH_LAUNCH(float, 256);
+    } else {
+        if (group_size == 64) FH_LAUNCH(uint16_t, 64);
+        else if (group_size == 128) FH_LAUNCH(uint16_t, 128);
+        else FH_LAUNCH(uint16_t, 256);
+    }
+#undef FH_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_compress_mixed(const CompressItem& it, const ChannelMap& cm, int dtype, int group_size, hipStream_t s)
+{
+    const int tile = compress_tile_elems(dtype, group_size);
+    const uint32_t tiles = (uint32_t)((it.numel + tile - 1) / tile);
+    if (tiles == 0) return hipSuccess;
+    const dim3 grid(tiles), block(kCBlock);
+#define FH_LAUNCH(T, GS) hipLaunchKernelGGL((compress_mixed_kernel<T, GS>), grid, block, 0, s, it, cm)
     if (dtype == 0) {
         if (group_size == 64) FH_LAUNCH(float, 64);
         else if (group_size == 128) FH_LAUNCH(float, 128);

@@ -10,6 +10,10 @@
 //
 // Reconstruction follows the paper's Section 4.4.1 (floating-point values are rebuilt
 // from the quantisation codes): x^ = fma(code, scale, zero), one rounding.
+//
+// The MIXED variants take the elements of kept (salient) channels from the raw store
+// instead.
+#include "fh_channels.hpp"
 #include "fh_device.hpp"
 #include "fh_kernels.hpp"
 
@@ -86,8 +90,27 @@ __device__ __forceinline__ u32x4 pack_bf16x8(const float (&v)[8])
     return o;
 }
 
-template <typename OutT, int G, int B>
-__device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32_t tile)
+// ---- kept channels (MIXED) ---------------------------------------------------------------
+// Replace the elements flagged in `mask` by their raw values (widened to fp32 when the raw
+// store is bf16; rounding to a bf16 output happens with the rest of the lane's elements).
+template <int N>
+__device__ __forceinline__ void fetch_kept(const ChannelMap& cm, int raw_dtype, const ElemPos& p, uint32_t mask,
+                                           float (&v)[N])
+{
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        if (mask & (1u << j)) {
+            const uint64_t i = raw_index(cm, p, j);
+            const uint32_t bits = raw_dtype == 0 ? static_cast<const uint32_t*>(cm.raw)[i]
+                                                 : (uint32_t) static_cast<const uint16_t*>(cm.raw)[i] << 16;
+            v[j] = __builtin_bit_cast(float, bits);
+        }
+    }
+}
+
+template <typename OutT, int G, int B, bool MIXED = false>
+__device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32_t tile,
+                                                const ChannelMap* cm = nullptr, int raw_dtype = 0)
 {
     constexpr int EPL = OutTraits<OutT>::EPL;
     constexpr int ROW = kWave * EPL;
@@ -98,6 +121,8 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
     const int64_t numel = it.numel;
     const int64_t wave_base = (int64_t)tile * TILE + (int64_t)wave * WAVE_SPAN;
     if (wave_base >= numel) return;
+    ElemPos wave_pos = {0u, 0u, 0u};
+    if constexpr (MIXED) wave_pos = locate_base(*cm, (uint32_t)wave_base);
 
     if (wave_base + WAVE_SPAN <= numel) {
         // ---- interior: all loads first, then one 128-bit store per lane and row ----
@@ -114,6 +139,11 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
             const int64_t i0 = wave_base + r * ROW + lane * EPL;
             float v[EPL];
             restore<EPL, B>(c0[r], c1[r], m[r], v);
+            if constexpr (MIXED) {
+                const ElemPos p = advance(*cm, wave_pos, r * ROW + lane * EPL);
+                const uint32_t keptm = kept_mask<EPL>(*cm, p);
+                if (keptm) fetch_kept<EPL>(*cm, raw_dtype, p, keptm, v);
+            }
             if constexpr (EPL == 4) {
                 stream_store(reinterpret_cast<f32x4*>(static_cast<float*>(it.out) + i0), f32x4{v[0], v[1], v[2], v[3]});
             } else {
@@ -134,6 +164,13 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
         const f32x2 m = *reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v));
         float v[EPL];
         restore<EPL, B>(c0, c1, m, v);
+        if constexpr (MIXED) {
+            const int64_t left = numel - i0;
+            const uint32_t valid = left >= EPL ? (1u << EPL) - 1u : (1u << (int)left) - 1u;
+            const ElemPos p = advance(*cm, wave_pos, r * ROW + lane * EPL);
+            const uint32_t keptm = kept_mask<EPL>(*cm, p) & valid;
+            if (keptm) fetch_kept<EPL>(*cm, raw_dtype, p, keptm, v);
+        }
         if constexpr (EPL == 4) {
             float* dst = static_cast<float*>(it.out) + i0;
             if (i0 + EPL <= numel) {
@@ -180,6 +217,20 @@ __global__ __launch_bounds__(kDBlock) void decompress_kernel(const DecompressBat
     }
 }
 
+// One tensor whose kept channels come from the raw store.
+template <typename OutT, int G>
+__global__ __launch_bounds__(kDBlock) void decompress_mixed_kernel(const DecompressItem it, const ChannelMap cm,
+                                                                   const int raw_dtype)
+{
+    const uint32_t tile = gridDim.x - 1u - blockIdx.x;
+    switch (it.bits) {
+        case 2: decompress_tile<OutT, G, 2, true>(it, tile, &cm, raw_dtype); break;
+        case 4: decompress_tile<OutT, G, 4, true>(it, tile, &cm, raw_dtype); break;
+        case 8: decompress_tile<OutT, G, 8, true>(it, tile, &cm, raw_dtype); break;
+        default: break;
+    }
+}
+
 }  // namespace
 
 int decompress_tile_elems(int out_dtype, int)
@@ -193,6 +244,27 @@ hipError_t launch_decompress(const DecompressBatch& b, int out_dtype, int group_
     if (tiles == 0) return hipSuccess;
     const dim3 grid(tiles), block(kDBlock);
 #define FH_LAUNCH(T, GS) hipLaunchKernelGGL((decompress_kernel<T, GS>), grid, block, 0, s, b)
+    if (out_dtype == 0) {
+        if (group_size == 64) FH_LAUNCH(float, 64);
+        else if (group_size == 128) FH_LAUNCH(float, 128);
+        else FH_LAUNCH(float, 256);
+    } else {
+        if (group_size == 64) FH_LAUNCH(uint16_t, 64);
+        else if (group_size == 128) FH_LAUNCH(uint16_t, 128);
+        else FH_LAUNCH(uint16_t, 256);
+    }
+#undef FH_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_decompress_mixed(const DecompressItem& it, const ChannelMap& cm, int raw_dtype, int out_dtype,
+                                   int group_size, hipStream_t s)
+{
+    const int tile = decompress_tile_elems(out_dtype, group_size);
+    const uint32_t tiles = (uint32_t)((it.numel + tile - 1) / tile);
+    if (tiles == 0) return hipSuccess;
+    const dim3 grid(tiles), block(kDBlock);
+#define FH_LAUNCH(T, GS) hipLaunchKernelGGL((decompress_mixed_kernel<T, GS>), grid, block, 0, s, it, cm, raw_dtype)
     if (out_dtype == 0) {
         if (group_size == 64) FH_LAUNCH(float, 64);
         else if (group_size == 128) FH_LAUNCH(float, 128);

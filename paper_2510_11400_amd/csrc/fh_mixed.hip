@@ -1,0 +1,176 @@
+// Routing salient channels around the quantiser (paper Section 4.4.1, Channel-wise Mix
+// Compression: only normal channels are quantised): the slot table that says which
+// channels are kept verbatim, and the C entry points of the mixed forward / backward
+// calls.  The kernels themselves are the MIXED variants in fh_compress.hip and
+// fh_decompress.hip.
+#include "../../include/fedhybrid.h"
+
+#include "fh_channels.hpp"
+#include "fh_kernels.hpp"
+
+namespace fh {
+namespace {
+
+constexpr int kSlotThreads = 1024;
+constexpr int kSlotPerThread = 16;                 // 1024 * 16 = the largest channel count
+
+// slots[c] = number of salient channels before c, for salient channels while that number is
+// below raw_channels; -1 for every other channel.  One workgroup: each thread owns 16
+// consecutive channels, the per-thread counts are scanned through LDS.
+__global__ __launch_bounds__(kSlotThreads) void channel_slots_kernel(const uint8_t* __restrict__ mask, int channels,
+                                                                      int raw_channels, int16_t* __restrict__ slots)
+{
+    __shared__ int scan[kSlotThreads];
+    const int t = threadIdx.x;
+    const int first = t * kSlotPerThread;
+    int mine = 0;
+    for (int k = 0; k < kSlotPerThread; ++k) {
+        const int c = first + k;
+        if (c < channels && mask[c] != 0) ++mine;
+    }
+    scan[t] = mine;
+    __syncthreads();
+    for (int step = 1; step < kSlotThreads; step <<= 1) {     // inclusive scan, all threads reach every barrier
+        const int add = t >= step ? scan[t - step] : 0;
+        __syncthreads();
+        scan[t] += add;
+        __syncthreads();
+    }
+    int rank = scan[t] - mine;                                // salient channels before this thread's first
+    for (int k = 0; k < kSlotPerThread; ++k) {
+        const int c = first + k;
+        if (c >= channels) break;
+        if (mask[c] != 0 && rank < raw_channels) slots[c] = (int16_t)rank;
+        else slots[c] = (int16_t)-1;
+        if (mask[c] != 0) ++rank;
+    }
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+size_t elem_size(int dtype) { return dtype == FH_F32 ? 4u : 2u; }
+
+constexpr int64_t kMaxMixedElems = (int64_t)1 << 31;
+
+fh_status check_shape(int64_t outer, int64_t channels, int64_t inner, int64_t raw_channels, int64_t* numel)
+{
+    if (outer < 0 || channels < 1 || channels > 16384 || inner < 1) return FH_ERR_BAD_SHAPE;
+    if (raw_channels < 0 || raw_channels > channels) return FH_ERR_BAD_SHAPE;
+    if (inner > kMaxMixedElems) return FH_ERR_BAD_NUMEL;
+    const int64_t per_sample = channels * inner;              // <= 2^45
+    if (per_sample > kMaxMixedElems) return FH_ERR_BAD_NUMEL;
+    if (outer > kMaxMixedElems / per_sample) return FH_ERR_BAD_NUMEL;
+    *numel = outer * per_sample;
+    return FH_OK;
+}
+
+fh_status check_quantiser(const fh_params* p, bool need_round)
+{
+    if (!p) return FH_ERR_NULL;
+    if (p->group_size != 64 && p->group_size != 128 && p->group_size != 256) return FH_ERR_BAD_GROUP;
+    if (p->bits != 2 && p->bits != 4 && p->bits != 8) return FH_ERR_BAD_BITS;
+    if (need_round && p->rounding != FH_ROUND_NEAREST && p->rounding != FH_ROUND_STOCHASTIC) return FH_ERR_BAD_ROUND;
+    return FH_OK;
+}
+
+ChannelMap make_map(const void* slots, void* raw, int64_t channels, int64_t inner, int64_t raw_channels)
+{
+    ChannelMap cm;
+    cm.slots = static_cast<const int16_t*>(slots);
+    cm.raw = raw;
+    cm.raw_channels = (uint32_t)raw_channels;
+    cm.inner_exact = make_exact_div((uint32_t)inner);
+    cm.channels_exact = make_exact_div((uint32_t)channels);
+    cm.inner = make_small_div((uint32_t)inner);
+    cm.channels = make_small_div((uint32_t)channels);
+    return cm;
+}
+
+}  // namespace
+}  // namespace fh
+
+extern "C" {
+
+size_t fh_raw_bytes(int64_t outer, int64_t raw_channels, int64_t inner, fh_dtype dtype)
+{
+    if (outer <= 0 || raw_channels <= 0 || inner <= 0) return 0;
+    if (dtype != FH_F32 && dtype != FH_BF16) return 0;
+    return (size_t)outer * (size_t)raw_channels * (size_t)inner * fh::elem_size(dtype);
+}
+
+fh_status fh_channel_slots(const void* mask, int64_t channels, int64_t raw_channels, void* slots, void* stream)
+{
+    if (channels < 1 || channels > 16384 || raw_channels < 0 || raw_channels > channels) return FH_ERR_BAD_SHAPE;
+    if (!mask || !slots) return FH_ERR_NULL;
+    if (!fh::aligned(slots, 16)) return FH_ERR_ALIGNMENT;
+    hipLaunchKernelGGL(fh::channel_slots_kernel, dim3(1), dim3(fh::kSlotThreads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint8_t*>(mask), (int)channels, (int)raw_channels,
+                       static_cast<int16_t*>(slots));
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+fh_status fh_compress_mixed(const void* x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
+                            const fh_params* params, const void* slots, int64_t raw_channels,
+                            void* packed, size_t packed_cap, void* meta, size_t meta_cap,
+                            void* raw, size_t raw_cap, void* stream)
+{
+    fh_status s;
+    if ((s = fh::check_quantiser(params, true)) != FH_OK) return s;
+    if (x_dtype != FH_F32 && x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    int64_t numel = 0;
+    if ((s = fh::check_shape(outer, channels, inner, raw_channels, &numel)) != FH_OK) return s;
+    if (numel == 0) return FH_OK;
+    if (!x || !slots || !packed || !meta || (raw_channels > 0 && !raw)) return FH_ERR_NULL;
+    if (!fh::aligned(x, 16) || !fh::aligned(packed, 16) || !fh::aligned(meta, 8) || !fh::aligned(slots, 16) ||
+        !fh::aligned(raw, 16))
+        return FH_ERR_ALIGNMENT;
+    if (packed_cap < fh_packed_bytes(numel, params->bits)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (meta_cap < fh_meta_bytes(numel, params->group_size)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (raw_cap < fh_raw_bytes(outer, raw_channels, inner, x_dtype)) return FH_ERR_BUFFER_TOO_SMALL;
+
+    fh::CompressItem it;
+    it.x = x;
+    it.packed = static_cast<uint8_t*>(packed);
+    it.meta = static_cast<float*>(meta);
+    it.numel = numel;
+    it.packed_padded = fh_packed_bytes(numel, params->bits);
+    it.seed = params->seed;
+    it.tensor_id = params->tensor_id;
+    it.bits = params->bits;
+    it.stochastic = params->rounding == FH_ROUND_STOCHASTIC ? 1 : 0;
+    const fh::ChannelMap cm = fh::make_map(slots, raw, channels, inner, raw_channels);
+    return fh::launch_compress_mixed(it, cm, x_dtype, params->group_size, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? FH_OK : FH_ERR_LAUNCH;
+}
+
+fh_status fh_decompress_mixed(const void* packed, const void* meta, const void* raw, fh_dtype raw_dtype,
+                              int64_t outer, int64_t channels, int64_t inner,
+                              const fh_params* params, const void* slots, int64_t raw_channels,
+                              fh_dtype out_dtype, void* out, size_t out_cap, void* stream)
+{
+    fh_status s;
+    if ((s = fh::check_quantiser(params, false)) != FH_OK) return s;
+    if (raw_dtype != FH_F32 && raw_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if (out_dtype != FH_F32 && out_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    int64_t numel = 0;
+    if ((s = fh::check_shape(outer, channels, inner, raw_channels, &numel)) != FH_OK) return s;
+    if (numel == 0) return FH_OK;
+    if (!packed || !meta || !slots || !out || (raw_channels > 0 && !raw)) return FH_ERR_NULL;
+    if (!fh::aligned(packed, 16) || !fh::aligned(out, 16) || !fh::aligned(meta, 8) || !fh::aligned(slots, 16) ||
+        !fh::aligned(raw, 16))
+        return FH_ERR_ALIGNMENT;
+    if (out_cap < (size_t)numel * fh::elem_size(out_dtype)) return FH_ERR_BUFFER_TOO_SMALL;
+
+    fh::DecompressItem it;
+    it.packed = static_cast<const uint8_t*>(packed);
+    it.meta = static_cast<const float*>(meta);
+    it.out = out;
+    it.numel = numel;
+    it.bits = params->bits;
+    it.pad = 0;
+    const fh::ChannelMap cm = fh::make_map(slots, const_cast<void*>(raw), channels, inner, raw_channels);
+    return fh::launch_decompress_mixed(it, cm, raw_dtype, out_dtype, params->group_size,
+                                       static_cast<hipStream_t>(stream)) == hipSuccess
+               ? FH_OK : FH_ERR_LAUNCH;
+}
+
+}  // extern "C"

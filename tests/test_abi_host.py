@@ -143,3 +143,63 @@ def test_classify_workspace_size_covers_every_level_of_the_tree():
             m = -(-m // 1024)
         assert api.classify_workspace_bytes(n) == 16 * pairs
     assert api.classify_workspace_bytes(0) == 16
+
+
+def _params(G=64, B=4, rounding=0):
+    return api.fh_params(G, B, rounding, 0, 0, 0)
+
+
+def _cmixed(x=FAKE, dtype=0, outer=4, channels=8, inner=16, params="default", slots=FAKE, raw_channels=2,
+            packed=FAKE, packed_cap=1 << 20, meta=FAKE, meta_cap=1 << 20, raw=FAKE, raw_cap=1 << 20):
+    p = _params() if params == "default" else params
+    return api.raw_library().fh_compress_mixed(x, dtype, outer, channels, inner,
+                                               ctypes.byref(p) if p is not None else None, slots, raw_channels,
+                                               packed, packed_cap, meta, meta_cap, raw, raw_cap, None)
+
+
+def _dmixed(packed=FAKE, meta=FAKE, raw=FAKE, raw_dtype=0, outer=4, channels=8, inner=16, params="default",
+            slots=FAKE, raw_channels=2, out_dtype=0, out=FAKE, out_cap=1 << 20):
+    p = _params() if params == "default" else params
+    return api.raw_library().fh_decompress_mixed(packed, meta, raw, raw_dtype, outer, channels, inner,
+                                                 ctypes.byref(p) if p is not None else None, slots, raw_channels,
+                                                 out_dtype, out, out_cap, None)
+
+
+def test_mixed_calls_reject_bad_arguments_before_any_launch():
+    assert _cmixed(params=None) == 1 and _dmixed(params=None) == 1
+    assert _cmixed(params=_params(G=32)) == 3 and _cmixed(params=_params(B=3)) == 4
+    assert _cmixed(params=_params(rounding=2)) == 5
+    assert _cmixed(dtype=2) == 2 and _dmixed(raw_dtype=2) == 2 and _dmixed(out_dtype=-1) == 2
+    for call in (_cmixed, _dmixed):
+        assert call(outer=-1) == 11 and call(inner=0) == 11 and call(channels=0) == 11
+        assert call(channels=16385) == 11 and call(raw_channels=9) == 11 and call(raw_channels=-1) == 11
+        assert call(outer=1 << 20, channels=4096, inner=1 << 10) == 6         # more than 2^31 elements
+        assert call(slots=None) == 1 and call(raw=None) == 1
+        assert call(slots=FAKE + 2) == 8 and call(raw=FAKE + 4) == 8
+    assert _cmixed(x=None) == 1 and _cmixed(packed=None) == 1 and _cmixed(meta=None) == 1
+    assert _cmixed(x=FAKE + 4) == 8 and _cmixed(meta=FAKE + 4) == 8
+    n = 4 * 8 * 16
+    assert _cmixed(packed_cap=api.packed_bytes(n, 4) - 1) == 7
+    assert _cmixed(meta_cap=api.meta_bytes(n, 64) - 1) == 7
+    assert _cmixed(raw_cap=4 * 2 * 16 * 4 - 1) == 7
+    assert _dmixed(out=None) == 1 and _dmixed(out_cap=n * 4 - 1) == 7 and _dmixed(out_dtype=1, out_cap=n * 2 - 1) == 7
+    # nothing to do: no pointer is looked at
+    assert _cmixed(outer=0, x=None, packed=None, meta=None, raw=None, slots=None) == 0
+    assert _dmixed(outer=0, packed=None, meta=None, raw=None, slots=None, out=None) == 0
+    # no raw rows: raw may be NULL -- but this would launch, so only the check before it is probed
+    assert _cmixed(raw_channels=0, raw=None, x=None) == 1
+
+
+def test_channel_slots_rejects_bad_arguments_before_any_launch():
+    f = api.raw_library().fh_channel_slots
+    assert f(FAKE, 0, 0, FAKE, None) == 11 and f(FAKE, 16385, 0, FAKE, None) == 11
+    assert f(FAKE, 8, 9, FAKE, None) == 11 and f(FAKE, 8, -1, FAKE, None) == 11
+    assert f(None, 8, 2, FAKE, None) == 1 and f(FAKE, 8, 2, None, None) == 1
+    assert f(FAKE, 8, 2, FAKE + 2, None) == 8
+
+
+def test_raw_store_size():
+    import torch
+    assert api.raw_bytes(4, 3, 50, torch.float32) == 4 * 3 * 50 * 4
+    assert api.raw_bytes(4, 3, 50, torch.bfloat16) == 4 * 3 * 50 * 2
+    assert api.raw_bytes(0, 3, 50, torch.float32) == 0 and api.raw_bytes(4, 0, 50, torch.float32) == 0
