@@ -101,6 +101,106 @@ def bench_classify(args, api, W, dev) -> int:
     return 0
 
 
+def bench_mixed(args, api, W, dev) -> int:
+    """Compress + decompress with salient channels routed around the quantiser, over the same
+    MobileNetV2-style activations with channel-clustered outliers as the classification
+    bench (the planted channels are the kept ones; slot tables are built once, outside the
+    timed region).  One step = every tensor compressed, then every tensor restored."""
+    import numpy as np
+    import torch
+
+    shapes = ((64, 32, 112 * 112), (64, 96, 112 * 112), (64, 144, 56 * 56), (64, 192, 28 * 28), (64, 384, 14 * 14))
+    G, B, rounding = 128, 4, "nearest"
+    t0 = time.time()
+    host, jobs = [], []
+    alg_c = alg_d = 0
+    for i, (outer, C, inner) in enumerate(shapes):
+        x, planted = W.outlier_channel_tensor(outer, C, inner, seed=i, dist="relu")
+        mask = np.zeros(C, np.uint8)
+        mask[planted] = 1
+        cap = len(planted)
+        host.append((x, mask, cap))
+        xd = torch.from_numpy(x).to(dev)
+        slots = api.fh_channel_slots(torch.from_numpy(mask).to(dev), cap)
+        packed, meta = api.alloc_compressed(x.size, G, B, dev)
+        raw = torch.empty(outer * cap * inner, dtype=torch.float32, device=dev)
+        out = torch.empty(x.size, dtype=torch.float32, device=dev)
+        jobs.append((xd, outer, C, inner, slots, cap, packed, meta, raw, out, i))
+        n = x.size
+        side = (n * B + 7) // 8 + 8 * ((n + G - 1) // G) + outer * cap * inner * 4
+        alg_c += n * 4 + side
+        alg_d += side + n * 4
+    torch.cuda.synchronize()
+    nbytes = sum(x.nbytes for x, _, _ in host)
+    print(f"[bench] mixed: {len(jobs)} tensors, {nbytes / 2**20:.1f} MiB resident "
+          f"(generated + uploaded in {time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
+    stream = torch.cuda.current_stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def step(timed=False):
+        if timed:
+            ev[0].record(stream)
+        for xd, outer, C, inner, slots, cap, packed, meta, raw, out, tid in jobs:
+            api.fh_compress_mixed(xd, outer, C, inner, slots, cap, G, B, rounding, 1, tid, packed=packed, meta=meta,
+                                  raw=raw, stream=stream)
+        if timed:
+            ev[1].record(stream)
+        for xd, outer, C, inner, slots, cap, packed, meta, raw, out, tid in reversed(jobs):
+            api.fh_decompress_mixed(packed, meta, raw, outer, C, inner, slots, cap, G, B, out=out, stream=stream)
+        if timed:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t_start) / args.steps
+    ms_c = ms_d = 0.0
+    for _ in range(args.steps):                               # per-direction times, outside the timed region
+        step(timed=True)
+        torch.cuda.synchronize()
+        ms_c += ev[0].elapsed_time(ev[1]) / args.steps
+        ms_d += ev[1].elapsed_time(ev[2]) / args.steps
+    dom = ("compress_mixed_kernel", alg_c, ms_c) if ms_c >= ms_d else ("decompress_mixed_kernel", alg_d, ms_d)
+    result = {
+        "metric": "activation compress+decompress GB/s with salient channels kept raw, on 1 MI355X",
+        "value": round(nbytes / elapsed / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "mixed_mobilenetv2_b64_outlier_channels_g128_b4_nearest", "tensors": len(jobs),
+                   "input_bytes": nbytes, "entry_point": "fh_compress_mixed + fh_decompress_mixed (per tensor)",
+                   "kept_channels": [int(c) for _, _, c in host]},
+        "round_trip_algorithmic_bytes": alg_c + alg_d,
+        "hbm_frac_round_trip": round((alg_c + alg_d) / elapsed / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": {"bound": "hbm", "kernel": dom[0] + " (all launches of a step, event-timed)",
+                     "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},
+        "kernels": {"compress_mixed_kernel": {"ms": round(ms_c, 4), "bytes": alg_c,
+                                              "GBps": round(alg_c / ms_c / 1e6, 1)},
+                    "decompress_mixed_kernel": {"ms": round(ms_d, 4), "bytes": alg_d,
+                                                "GBps": round(alg_d / ms_d / 1e6, 1)}},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        t_cpu, done = 0.0, 0
+        for (x, mask, cap), (outer, C, inner) in zip(host, shapes):
+            t1 = time.perf_counter()
+            slots, _ = oracle.channel_slots(mask, cap)
+            p, m, r = oracle.compress_mixed(x, outer, C, inner, slots, cap, G, B, rounding, 1, 0)
+            oracle.decompress_mixed(p, m, r, outer, C, inner, slots, cap, G, B)
+            t_cpu += time.perf_counter() - t1
+            done += x.nbytes
+            if t_cpu > 20.0:
+                break
+        result["cpu_baseline"] = {"value": round(done / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"{done / 2**20:.1f} MiB of the set, whole tensors, {t_cpu:.1f} s"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -111,9 +211,10 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB device copies before the timed region, so that a "
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE against a known size")
-    ap.add_argument("--op", choices=("roundtrip", "classify"), default="roundtrip",
+    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed"), default="roundtrip",
                     help="roundtrip (default): compress + decompress of the tensor set; classify: the "
-                         "channel classification step (moments + outlier counts), measured on its own")
+                         "channel classification step (moments + outlier counts), measured on its own; "
+                         "mixed: the round trip with salient channels kept raw beside the quantised stream")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()
@@ -140,6 +241,8 @@ def main() -> int:
 
     if args.op == "classify":
         return bench_classify(args, api, W, dev)
+    if args.op == "mixed":
+        return bench_mixed(args, api, W, dev)
 
     w = W.full_config(args.config)
     t0 = time.time()

@@ -99,46 +99,88 @@ __device__ __forceinline__ bool kept(const ChannelMap& cm, int16_t slot)
     return (uint32_t)(int32_t)slot < cm.raw_channels;         // negative slots wrap to huge values
 }
 
-// Bit j set iff element j of the N consecutive elements starting at p belongs to a kept
-// channel.  N = 4 or 8; the first element's index is a multiple of N.
-template <int N>
-__device__ __forceinline__ uint32_t kept_mask(const ChannelMap& cm, const ElemPos& p)
+// What a lane knows about its run of N consecutive elements (N = 4 or 8; the first element's
+// index is a multiple of N).
+template <int N> struct KeptRun {
+    ElemPos  p;                // position of the first element
+    uint32_t mask;             // bit j set iff element j belongs to a kept channel
+    uint32_t slotw[N / 2];     // half-word j: raw-store row of element j (meaningful where bit j is set)
+};
+
+// The runs of one lane in the ROWS rows of a wave's span (row r starts row_stride * r elements
+// after wave_pos; the lane's run starts lane_off into the row).  All table loads are issued
+// before any of them is needed, so a wave pays one memory latency, not one per row.
+template <int ROWS, int N>
+__device__ __forceinline__ void kept_runs(const ChannelMap& cm, const ElemPos& wave_pos, uint32_t lane_off,
+                                          uint32_t row_stride, KeptRun<N> (&run)[ROWS])
 {
-    if (cm.raw_channels == 0u) return 0u;
-    uint32_t mask = 0u;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        run[r].p = advance(cm, wave_pos, r * row_stride + lane_off);
+        run[r].mask = 0u;
+#pragma unroll
+        for (int k = 0; k < N / 2; ++k) run[r].slotw[k] = 0xffffffffu;
+    }
+    if (cm.raw_channels == 0u) return;
     if (cm.inner.d == 1u && (cm.channels.d & (N - 1)) == 0u) {
         // one channel per element, and the N channels of a lane never wrap: one vector load
-        if constexpr (N == 8) {
-            const u32x4 s = *reinterpret_cast<const u32x4*>(cm.slots + p.c);
-            const uint32_t w[4] = {s.x, s.y, s.z, s.w};
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                mask |= kept(cm, (int16_t)(w[j >> 1] >> ((j & 1) * 16))) ? 1u << j : 0u;
-        } else {
-            const u32x2 s = *reinterpret_cast<const u32x2*>(cm.slots + p.c);
-            const uint32_t w[2] = {s.x, s.y};
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                mask |= kept(cm, (int16_t)(w[j >> 1] >> ((j & 1) * 16))) ? 1u << j : 0u;
+        for (int r = 0; r < ROWS; ++r) {
+            if constexpr (N == 8) {
+                const u32x4 s = *reinterpret_cast<const u32x4*>(cm.slots + run[r].p.c);
+                run[r].slotw[0] = s.x; run[r].slotw[1] = s.y; run[r].slotw[2] = s.z; run[r].slotw[3] = s.w;
+            } else {
+                const u32x2 s = *reinterpret_cast<const u32x2*>(cm.slots + run[r].p.c);
+                run[r].slotw[0] = s.x; run[r].slotw[1] = s.y;
+            }
         }
-        return mask;
-    }
-    const bool straddles = p.pos + N > cm.inner.d;
-    if (__builtin_amdgcn_ballot_w64(straddles) == 0ull)       // the usual case for feature maps
-        return kept(cm, cm.slots[p.c]) ? (1u << N) - 1u : 0u;
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-        const ElemPos q = advance(cm, p, j);
-        mask |= kept(cm, cm.slots[q.c]) ? 1u << j : 0u;
+        for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+            for (int j = 0; j < N; ++j)
+                run[r].mask |= kept(cm, (int16_t)(run[r].slotw[j >> 1] >> ((j & 1) * 16))) ? 1u << j : 0u;
+        return;
     }
-    return mask;
+    uint32_t first[ROWS];
+    bool straddles = false;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        first[r] = (uint16_t)cm.slots[run[r].p.c];
+        straddles |= run[r].p.pos + N > cm.inner.d;
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        run[r].mask = kept(cm, (int16_t)first[r]) ? (1u << N) - 1u : 0u;
+#pragma unroll
+        for (int k = 0; k < N / 2; ++k) run[r].slotw[k] = first[r] * 0x10001u;
+    }
+    if (__builtin_amdgcn_ballot_w64(straddles) != 0ull) {     // rare for feature maps
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if (run[r].p.pos + N > cm.inner.d) {              // a channel ends inside this lane's run
+                uint32_t m = 0u;
+#pragma unroll
+                for (int j = 0; j < N; ++j) {
+                    const ElemPos q = advance(cm, run[r].p, j);
+                    const uint32_t s = (uint16_t)cm.slots[q.c];
+                    m |= kept(cm, (int16_t)s) ? 1u << j : 0u;
+                    if (j & 1) run[r].slotw[j >> 1] = (run[r].slotw[j >> 1] & 0xffffu) | (s << 16);
+                    else run[r].slotw[j >> 1] = (run[r].slotw[j >> 1] & 0xffff0000u) | s;
+                }
+                run[r].mask = m;
+            }
+        }
+    }
 }
 
-// index into the raw store of element j after p (whose channel must be kept)
-__device__ __forceinline__ uint64_t raw_index(const ChannelMap& cm, const ElemPos& p, uint32_t j)
+// index into the raw store of element j of the run (whose bit in run.mask must be set)
+template <int N>
+__device__ __forceinline__ uint64_t raw_index(const ChannelMap& cm, const KeptRun<N>& run, uint32_t j)
 {
-    const ElemPos q = advance(cm, p, j);
-    const uint32_t slot = (uint32_t)(int32_t)cm.slots[q.c];
+    const uint32_t slot = (run.slotw[j >> 1] >> ((j & 1u) * 16u)) & 0xffffu;
+    if (cm.inner.d == 1u && (cm.channels.d & (N - 1)) == 0u)  // same sample for the whole run
+        return (uint64_t)run.p.o * cm.raw_channels + slot;
+    const ElemPos q = advance(cm, run.p, j);
     return ((uint64_t)q.o * cm.raw_channels + slot) * cm.inner.d + q.pos;
 }
 

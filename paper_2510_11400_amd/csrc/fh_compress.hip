@@ -293,14 +293,14 @@ template <> struct RawElem<uint16_t> {
     }
 };
 
-// Copy the elements flagged in `mask` to the raw store and hide them from the statistics.
+// Copy the kept elements of a lane's run to the raw store and hide them from the statistics.
 template <typename InT, int N>
-__device__ __forceinline__ void divert_kept(const ChannelMap& cm, const ElemPos& p, uint32_t mask, float (&x)[N])
+__device__ __forceinline__ void divert_kept(const ChannelMap& cm, const KeptRun<N>& run, float (&x)[N])
 {
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-        if (mask & (1u << j)) {
-            RawElem<InT>::put(cm.raw, raw_index(cm, p, j), x[j]);
+        if (run.mask & (1u << j)) {
+            RawElem<InT>::put(cm.raw, raw_index<N>(cm, run, j), x[j]);
             x[j] = __builtin_bit_cast(float, 0x7fc00000u);
         }
     }
@@ -340,11 +340,12 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
 
     uint32_t keptm[ROWS] = {};                                // bit j: element j of the row is kept raw
     if constexpr (MIXED) {
+        KeptRun<EPL> run[ROWS];
+        kept_runs<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            const ElemPos p = advance(*cm, wave_pos, r * ROW + lane * EPL);
-            keptm[r] = kept_mask<EPL>(*cm, p);
-            if (keptm[r]) divert_kept<InT, EPL>(*cm, p, keptm[r], x[r]);
+            keptm[r] = run[r].mask;
+            if (keptm[r]) divert_kept<InT, EPL>(*cm, run[r], x[r]);
         }
     }
 
@@ -534,9 +535,11 @@ __device__ __forceinline__ void compress_edge(const CompressItem& it, int64_t wa
         for (int j = 0; j < kEPL; ++j) x[j] = j < valid ? Loader<InT>::one(xw, e0 + j) : 0.0f;
         uint32_t keptm = 0u;
         if constexpr (MIXED) {
-            const ElemPos p = advance(*cm, wave_pos, e0);
-            keptm = kept_mask<kEPL>(*cm, p) & ((1u << valid) - 1u);
-            if (keptm) divert_kept<InT, kEPL>(*cm, p, keptm, x);
+            KeptRun<kEPL> run[1];
+            kept_runs<1, kEPL>(*cm, wave_pos, e0, 0, run);
+            run[0].mask &= (1u << valid) - 1u;
+            keptm = run[0].mask;
+            if (keptm) divert_kept<InT, kEPL>(*cm, run[0], x);
         }
         float mn = 0.0f, mx = 0.0f;
 #pragma unroll

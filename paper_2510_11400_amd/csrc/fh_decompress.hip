@@ -91,16 +91,15 @@ __device__ __forceinline__ u32x4 pack_bf16x8(const float (&v)[8])
 }
 
 // ---- kept channels (MIXED) ---------------------------------------------------------------
-// Replace the elements flagged in `mask` by their raw values (widened to fp32 when the raw
+// Replace the kept elements of a lane's run by their raw values (widened to fp32 when the raw
 // store is bf16; rounding to a bf16 output happens with the rest of the lane's elements).
 template <int N>
-__device__ __forceinline__ void fetch_kept(const ChannelMap& cm, int raw_dtype, const ElemPos& p, uint32_t mask,
-                                           float (&v)[N])
+__device__ __forceinline__ void fetch_kept(const ChannelMap& cm, int raw_dtype, const KeptRun<N>& run, float (&v)[N])
 {
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-        if (mask & (1u << j)) {
-            const uint64_t i = raw_index(cm, p, j);
+        if (run.mask & (1u << j)) {
+            const uint64_t i = raw_index<N>(cm, run, j);
             const uint32_t bits = raw_dtype == 0 ? static_cast<const uint32_t*>(cm.raw)[i]
                                                  : (uint32_t) static_cast<const uint16_t*>(cm.raw)[i] << 16;
             v[j] = __builtin_bit_cast(float, bits);
@@ -134,15 +133,15 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
             load_codes<EPL, B>(it.packed, i0, c0[r], c1[r]);
             m[r] = *reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v));
         }
+        KeptRun<EPL> run[kRowsPerWave];
+        if constexpr (MIXED) kept_runs<kRowsPerWave, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r) {
             const int64_t i0 = wave_base + r * ROW + lane * EPL;
             float v[EPL];
             restore<EPL, B>(c0[r], c1[r], m[r], v);
             if constexpr (MIXED) {
-                const ElemPos p = advance(*cm, wave_pos, r * ROW + lane * EPL);
-                const uint32_t keptm = kept_mask<EPL>(*cm, p);
-                if (keptm) fetch_kept<EPL>(*cm, raw_dtype, p, keptm, v);
+                if (run[r].mask) fetch_kept<EPL>(*cm, raw_dtype, run[r], v);
             }
             if constexpr (EPL == 4) {
                 stream_store(reinterpret_cast<f32x4*>(static_cast<float*>(it.out) + i0), f32x4{v[0], v[1], v[2], v[3]});
@@ -167,9 +166,10 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
         if constexpr (MIXED) {
             const int64_t left = numel - i0;
             const uint32_t valid = left >= EPL ? (1u << EPL) - 1u : (1u << (int)left) - 1u;
-            const ElemPos p = advance(*cm, wave_pos, r * ROW + lane * EPL);
-            const uint32_t keptm = kept_mask<EPL>(*cm, p) & valid;
-            if (keptm) fetch_kept<EPL>(*cm, raw_dtype, p, keptm, v);
+            KeptRun<EPL> run[1];
+            kept_runs<1, EPL>(*cm, wave_pos, r * ROW + lane * EPL, 0, run);
+            run[0].mask &= valid;
+            if (run[0].mask) fetch_kept<EPL>(*cm, raw_dtype, run[0], v);
         }
         if constexpr (EPL == 4) {
             float* dst = static_cast<float*>(it.out) + i0;
