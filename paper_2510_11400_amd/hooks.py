@@ -1,0 +1,135 @@
+"""Hooking the compressor into a training step, and handing a planner its costs.
+
+`SavedActivations` is the literal "compress in the forward pass, decompress during
+backpropagation" of FedHybrid's local training engine (Section 3, Activation compression):
+a `torch.autograd.graph.saved_tensors_hooks` pair whose pack side calls `fh_compress` and
+whose unpack side calls `fh_decompress`.  Only argument marshalling happens here; every
+byte is produced by the library's kernels.
+
+`mps` is the paper's reward metric (Section 4.3): RW(d) = SM(d) * FLT(d) and
+MPS(d) = RW(d) / (PC(d) + RC(d)), where SM is the memory a technique saves on tensor d, FLT
+the time the tensor would otherwise sit unused, PC the cost of purging it and RC the cost of
+regaining it.  `SavedActivations(record=True)` measures PC (compress time) and RC (decompress
+time) per tensor with events on the stream and reports SM, so that a host-side planner
+(Algorithm 1 compares MPS_compute with MPS_compress per tensor) gets MPS_compress from
+measurement rather than from a model.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import torch
+
+from . import api
+
+
+def mps(saved_bytes: float, freed_lifetime: float, purge_cost: float, regain_cost: float) -> float:
+    """Memory reduced per second (Section 4.3): SM * FLT / (PC + RC)."""
+    cost = purge_cost + regain_cost
+    if cost <= 0.0:
+        raise ValueError("purge cost + regain cost must be positive")
+    return saved_bytes * freed_lifetime / cost
+
+
+def prefer_recompute(mps_compute: float, mps_compress: float) -> bool:
+    """The branch Algorithm 1 takes for the tensor with the largest MPS: evict (and recompute
+    later) when recomputation rewards more than compression, else compress."""
+    return mps_compute > mps_compress
+
+
+@dataclass
+class TensorRecord:
+    """What one compressed activation cost and saved."""
+    tensor_id: int
+    numel: int
+    dtype: torch.dtype
+    input_bytes: int
+    stored_bytes: int                      # codes (padded) + meta
+    _pack: Optional[tuple] = field(default=None, repr=False)
+    _unpack: Optional[tuple] = field(default=None, repr=False)
+
+    @property
+    def saved_bytes(self) -> int:          # SM
+        return self.input_bytes - self.stored_bytes
+
+    @property
+    def purge_cost(self) -> Optional[float]:   # PC, seconds; call after the stream has drained
+        return None if self._pack is None else self._pack[0].elapsed_time(self._pack[1]) * 1e-3
+
+    @property
+    def regain_cost(self) -> Optional[float]:  # RC, seconds
+        return None if self._unpack is None else self._unpack[0].elapsed_time(self._unpack[1]) * 1e-3
+
+    def mps_compress(self, freed_lifetime: float) -> float:
+        if self.purge_cost is None or self.regain_cost is None:
+            raise RuntimeError("costs are known only after the tensor has been compressed and restored "
+                               "with record=True")
+        return mps(self.saved_bytes, freed_lifetime, self.purge_cost, self.regain_cost)
+
+
+class _Packed:
+    __slots__ = ("packed", "meta", "shape", "dtype", "numel", "record")
+
+    def __init__(self, packed, meta, shape, dtype, numel, record):
+        self.packed, self.meta, self.shape, self.dtype, self.numel, self.record = packed, meta, shape, dtype, numel, record
+
+
+class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
+    """Context manager: tensors that autograd saves inside it are stored compressed.
+
+    Eligible: device tensors of float32 / bfloat16 with at least `min_numel` elements that are
+    neither parameters nor listed in `exclude` (weights are saved for backward too, and must
+    stay exact: pass `exclude=model.parameters()`; tensors are recognised by their storage
+    address).  Everything else is saved as it is.  Non-contiguous tensors are made contiguous first (a copy by torch).
+    Stochastic rounding draws its bits from (seed, tensor_id); tensor ids count up from
+    `first_tensor_id` in the order tensors are saved, so a step is reproducible.
+    """
+
+    def __init__(self, group_size: int = 256, bits: int = 4, rounding="nearest", seed: int = 0,
+                 min_numel: int = 4096, first_tensor_id: int = 0, record: bool = False, exclude=()):
+        self.group_size, self.bits, self.rounding, self.seed = group_size, bits, rounding, seed
+        self.min_numel = min_numel
+        self.next_tensor_id = first_tensor_id
+        self.record = record
+        self.records: List[TensorRecord] = []
+        self._exclude = {int(t.data_ptr()) for t in exclude}
+        super().__init__(self._pack, self._unpack)
+
+    def _eligible(self, t: torch.Tensor) -> bool:
+        return (t.is_cuda and t.dtype in (torch.float32, torch.bfloat16) and t.numel() >= self.min_numel
+                and not isinstance(t, torch.nn.Parameter) and int(t.data_ptr()) not in self._exclude)
+
+    def _pack(self, t: torch.Tensor):
+        if not self._eligible(t):
+            return t
+        x = t.detach().contiguous()
+        tid = self.next_tensor_id
+        self.next_tensor_id += 1
+        stream = torch.cuda.current_stream(x.device)
+        rec = None
+        if self.record:
+            ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            ev[0].record(stream)
+        packed, meta = api.fh_compress(x.view(-1), self.group_size, self.bits, self.rounding, self.seed, tid,
+                                       stream=stream)
+        if self.record:
+            ev[1].record(stream)
+            rec = TensorRecord(tid, x.numel(), x.dtype, x.numel() * x.element_size(),
+                               packed.numel() + meta.numel() * meta.element_size(), _pack=ev)
+            self.records.append(rec)
+        return _Packed(packed, meta, t.shape, t.dtype, x.numel(), rec)
+
+    def _unpack(self, h):
+        if not isinstance(h, _Packed):
+            return h
+        stream = torch.cuda.current_stream(h.packed.device)
+        if h.record is not None:
+            ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            ev[0].record(stream)
+        out = api.fh_decompress(h.packed, h.meta, h.numel, self.group_size, self.bits, out_dtype=h.dtype,
+                                stream=stream)
+        if h.record is not None:
+            ev[1].record(stream)
+            h.record._unpack = ev
+        return out.view(h.shape)

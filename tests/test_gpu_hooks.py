@@ -1,0 +1,147 @@
+"""The saved-tensor hooks on the GPU (Section 3: activations are compressed in the forward
+pass and decompressed during backpropagation): what backward sees is bit for bit the
+oracle's round trip of what forward saved, parameters stay exact, and the recorded purge /
+regain costs give the MPS of compression (Section 4.3)."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+import oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def hooks():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a visible MI355X")
+    from paper_2510_11400_amd import hooks as _hooks
+    return _hooks
+
+
+def _oracle_roundtrip(x_host, G, B, rounding, seed, tid, dtype):
+    if dtype == "bf16":
+        bits = x_host.view(torch.int16).numpy().view(np.uint16).reshape(-1)
+        p, m = oracle.compress(bits, G, B, rounding, seed, tid, dtype="bf16")
+        y = oracle.decompress(p, m, bits.size, G, B, out_dtype="bf16")
+        return torch.from_numpy(y.view(np.int16)).view(torch.bfloat16).reshape(x_host.shape)
+    flat = x_host.numpy().reshape(-1)
+    p, m = oracle.compress(flat, G, B, rounding, seed, tid)
+    return torch.from_numpy(oracle.decompress(p, m, flat.size, G, B)).reshape(x_host.shape)
+
+
+class _Probe(torch.autograd.Function):
+    """Saves its input and hands whatever backward gets back to the test."""
+    seen = []
+
+    @staticmethod
+    def forward(ctx, x):
+        ctx.save_for_backward(x)
+        return x * 1.0
+
+    @staticmethod
+    def backward(ctx, g):
+        (x,) = ctx.saved_tensors
+        _Probe.seen.append(x.detach().clone())
+        return g
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("G,B,rounding", [(256, 4, "nearest"), (64, 2, "stochastic"), (128, 8, "stochastic")])
+def test_backward_sees_the_oracles_round_trip(hooks, dtype, G, B, rounding):
+    print(f"[hooks] probe {dtype} G{G} B{B} {rounding}", flush=True)
+    torch.manual_seed(G + B)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    shapes = [(32, 24, 14, 14), (16, 512, 77), (5000,)]
+    _Probe.seen.clear()
+    xs = [torch.randn(s, device="cuda").to(tdt).requires_grad_(True) for s in shapes]
+    ctx = hooks.SavedActivations(G, B, rounding, seed=17, min_numel=1, first_tensor_id=40)
+    with ctx:
+        total = sum(_Probe.apply(x).float().sum() for x in xs)
+    total.backward()
+    torch.cuda.synchronize()
+    assert ctx.next_tensor_id == 43
+    for k, x in enumerate(xs):                             # backward visits them in reverse
+        got = _Probe.seen[len(xs) - 1 - k].cpu()
+        want = _oracle_roundtrip(x.detach().cpu(), G, B, rounding, 17, 40 + k, dtype)
+        assert got.shape == x.shape and got.dtype == x.dtype
+        view = torch.int32 if dtype == "f32" else torch.int16
+        assert torch.equal(got.view(view), want.view(view)), f"tensor {k}"
+
+
+def test_non_contiguous_and_small_tensors_and_parameters(hooks):
+    _Probe.seen.clear()
+    base = torch.randn(64, 96, device="cuda")
+    x = base.t().requires_grad_(True)                      # non-contiguous view
+    small = torch.randn(10, device="cuda", requires_grad=True)
+    w = torch.nn.Parameter(torch.randn(96, 64, device="cuda"))
+    ctx = hooks.SavedActivations(64, 8, min_numel=1000, record=True, exclude=[w])
+    with ctx:
+        y = _Probe.apply(x).sum() + _Probe.apply(small).sum() + _Probe.apply(w).sum()
+    y.backward()
+    torch.cuda.synchronize()
+    assert len(ctx.records) == 1                           # only x was compressed
+    seen_w, seen_small, seen_x = _Probe.seen
+    assert torch.equal(seen_w, w.detach()) and torch.equal(seen_small, small.detach())
+    want = _oracle_roundtrip(x.detach().contiguous().cpu(), 64, 8, "nearest", 0, 0, "f32")
+    assert torch.equal(seen_x.cpu().view(torch.int32), want.view(torch.int32))
+
+
+def test_linear_layer_gradient_uses_the_restored_activation(hooks):
+    torch.manual_seed(3)
+    x = torch.randn(256, 512, device="cuda")
+    lin = torch.nn.Linear(512, 128, bias=False).cuda()
+    gy = torch.randn(256, 128, device="cuda")
+    with hooks.SavedActivations(128, 4, "stochastic", seed=5, min_numel=1, exclude=lin.parameters()):
+        y = lin(x)
+    y.backward(gy)
+    x_hat = _oracle_roundtrip(x.cpu(), 128, 4, "stochastic", 5, 0, "f32").cuda()
+    want = gy.t() @ x_hat                                  # dL/dW = gy^T x_saved
+    assert torch.allclose(lin.weight.grad, want, rtol=1e-4, atol=1e-4)
+    exact = gy.t() @ x
+    assert not torch.allclose(lin.weight.grad, exact, rtol=1e-4, atol=1e-4)   # it really used the lossy copy
+
+
+def test_recorded_costs_give_the_mps_of_compression(hooks):
+    x = torch.randn(64, 96, 56, 56, device="cuda", requires_grad=True)
+    ctx = hooks.SavedActivations(256, 4, record=True)
+    _Probe.seen.clear()
+    with ctx:
+        y = _Probe.apply(x).sum()
+    y.backward()
+    torch.cuda.synchronize()
+    (rec,) = ctx.records
+    n = x.numel()
+    assert rec.input_bytes == 4 * n and rec.stored_bytes == n // 2 + 8 * (n // 256)
+    assert rec.saved_bytes == rec.input_bytes - rec.stored_bytes
+    assert 0 < rec.purge_cost < 0.05 and 0 < rec.regain_cost < 0.05
+    flt = 0.010
+    assert rec.mps_compress(flt) == hooks.mps(rec.saved_bytes, flt, rec.purge_cost, rec.regain_cost)
+
+
+def test_a_small_network_trains_through_the_hooks(hooks):
+    torch.manual_seed(0)
+    net = torch.nn.Sequential(torch.nn.Linear(256, 512), torch.nn.ReLU(), torch.nn.Linear(512, 512), torch.nn.ReLU(),
+                              torch.nn.Linear(512, 10)).cuda()
+    x = torch.randn(512, 256, device="cuda")
+    target = torch.randint(0, 10, (512,), device="cuda")
+    loss_fn = torch.nn.CrossEntropyLoss()
+    loss_fn(net(x), target).backward()
+    ref = [p.grad.clone() for p in net.parameters()]
+    net.zero_grad()
+    ctx = hooks.SavedActivations(256, 8, min_numel=4096, record=True, exclude=net.parameters())
+    with ctx:
+        loss = loss_fn(net(x), target)
+    loss.backward()
+    torch.cuda.synchronize()
+    assert len(ctx.records) >= 3
+    # 8-bit activations.  The error is dominated by ReLU masks taken from the restored tensor:
+    # nearest rounding flushes the ~0.5 % smallest positive activations to zero, and dropping a
+    # fraction f of the terms of a gradient sum costs about sqrt(f) of its norm.
+    for g, p in zip(ref, net.parameters()):
+        rel = (p.grad - g).norm() / g.norm()
+        cos = torch.nn.functional.cosine_similarity(p.grad.flatten(), g.flatten(), dim=0)
+        assert rel < 0.2 and cos > 0.98, (float(rel), float(cos))
