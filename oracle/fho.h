@@ -92,6 +92,22 @@ int fho_decompress_mixed(const uint8_t *packed, const float *meta, const void *r
                          const int16_t *slots, int64_t raw_channels,
                          int group_size, int bits, int out_dtype, void *out);
 
+/* ---- sparse-block storage of salient-channel feature maps (fho_sparse.c; Section 4.4.1:
+ *      non-zero mask, n x n average pooling against a threshold tau, sparse blocks as CSR) ---- */
+
+/* maps * ceil(h/n) * ceil(w/n), or -1. */
+int64_t fho_sparse_blocks(int64_t maps, int64_t h, int64_t w, int n);
+
+/* x: [maps][h][w] elements of dtype.  info: one byte per block.  values: room for maps*h*w
+ * elements.  indices: room for blocks*(n+1) + maps*h*w bytes.  totals = {values written, index
+ * bytes written, sparse blocks, dense blocks}.  Returns 0, or -1 on a bad argument. */
+int fho_sparse_encode(const void *x, int dtype, int64_t maps, int64_t h, int64_t w, int n, float tau,
+                      uint8_t *info, void *values, uint8_t *indices, uint64_t totals[4]);
+
+/* out: [maps][h][w].  Returns 0, -1 on a bad argument, -2 on an inconsistent stream. */
+int fho_sparse_decode(const uint8_t *info, const void *values, const uint8_t *indices, int dtype,
+                      int64_t maps, int64_t h, int64_t w, int n, void *out);
+
 #ifdef __cplusplus
 }
 #endif

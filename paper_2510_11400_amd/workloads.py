@@ -269,3 +269,25 @@ def outlier_channel_tensor(outer: int, channels: int, inner: int, seed: int = 0,
     if dtype == BF16:
         flat = _to_bf16_bits(flat)
     return flat, planted
+
+
+def salient_feature_maps(maps: int, h: int, w: int, seed: int = 0, zero_level: float = 0.3,
+                         outlier_fraction: float = 0.02, magnitude: float = 81.0, dtype: str = F32) -> np.ndarray:
+    """[maps][h][w] feature maps of outlier-rich channels as the paper describes them (Section
+    4.4.1): many zeros, locally clustered (post-ReLU responses are spatially smooth), and a
+    sprinkle of large outliers.  A coarse random field (one value per 8 x 8 patch, so zeros come
+    in patches) plus fine noise goes through ReLU; `zero_level` shifts the field down (more
+    zeros); `outlier_fraction` of the surviving values is multiplied by `magnitude`.  Returns the
+    flat array (float32, or bf16 bit patterns)."""
+    rng = np.random.default_rng(np.random.SeedSequence([seed, 0x5AC5E, maps, h, w]))
+    ch, cw = (h + 7) // 8, (w + 7) // 8
+    coarse = rng.standard_normal((maps, ch, cw), dtype=np.float32)
+    field = np.repeat(np.repeat(coarse, 8, axis=1), 8, axis=2)[:, :h, :w]
+    x = field + np.float32(0.35) * rng.standard_normal((maps, h, w), dtype=np.float32) - np.float32(zero_level)
+    np.maximum(x, np.float32(0.0), out=x)
+    hit = (rng.random((maps, h, w), dtype=np.float32) < np.float32(outlier_fraction)) & (x > 0)
+    x[hit] *= np.float32(magnitude)
+    flat = np.ascontiguousarray(x.reshape(-1))
+    if dtype == BF16:
+        flat = _to_bf16_bits(flat)
+    return flat
