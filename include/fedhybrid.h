@@ -63,7 +63,7 @@ typedef enum fh_status {
     FH_ERR_LAUNCH = 9,           /* the HIP runtime refused the launch */
     FH_ERR_BAD_COUNT = 10,       /* negative item count */
     FH_ERR_BAD_SHAPE = 11,       /* outer / channels / inner / raw_channels out of range */
-    FH_ERR_BAD_PARAM = 12        /* k_sigma not positive, or min_outliers < 1 */
+    FH_ERR_BAD_PARAM = 12        /* k_sigma not positive, min_outliers < 1, or a pooling window other than 2, 4, 8 */
 } fh_status;
 
 typedef enum fh_dtype { FH_F32 = 0, FH_BF16 = 1 } fh_dtype;
@@ -199,6 +199,47 @@ fh_status fh_decompress_mixed(const void *packed, const void *meta, const void *
                               int64_t outer, int64_t channels, int64_t inner,
                               const fh_params *params, const void *slots, int64_t raw_channels,
                               fh_dtype out_dtype, void *out, size_t out_cap, void *stream);
+
+/* ---- sparse-block storage of salient-channel feature maps -----------------------------------
+ * Section 4.4.1 stores an outlier-rich channel block-wise: a binary mask marks the non-zero
+ * values of the h x w map, average pooling with an n x n window turns it into a density per
+ * block, blocks whose density does not exceed a threshold tau are sparse and are stored in
+ * Compressed Sparse Row format; zeros must come back exactly.  Dense blocks (which the paper
+ * hands to a predictive coder) are stored verbatim here.  The paper gives neither n, tau, the
+ * pooling stride nor a layout; the definition used:
+ *
+ *   - input: `maps` maps of h x w elements, row-major, contiguous (for instance the raw store
+ *     of fh_compress_mixed with maps = outer * raw_channels, h * w = inner);
+ *   - pooling is non-overlapping: a map is cut into ceil(h/n) x ceil(w/n) blocks, edge blocks
+ *     are smaller; blocks are numbered map-major, then row-major; n is 2, 4 or 8;
+ *   - an element is non-zero iff its bit pattern is not all zero (-0.0 is a value);
+ *     density = (float)nnz / (float)area (binary32 division), sparse iff density <= tau;
+ *   - info: one byte per block, bit 7 = dense, bits 0..6 = nnz (sparse) or area (dense);
+ *   - values: one stream in block order -- the non-zeros of a sparse block in row-major order,
+ *     all elements of a dense block in row-major order;
+ *   - indices: one byte stream in block order -- per sparse block row_ptr[0..rows] (non-zeros in
+ *     the block's rows before r) followed by the column inside the block of each non-zero;
+ *   - totals: uint64[4] = {values written, index bytes written, sparse blocks, dense blocks};
+ *   - decoding restores the input bit for bit.
+ *
+ * All pointers are device pointers; x, values, out 4-byte aligned, totals and workspace 8-byte
+ * aligned.  Stream sizes depend on the data, so the encoder wants room for the worst case:
+ * info_cap >= fh_sparse_info_bytes(), values_cap >= maps*h*w elements, indices_cap >=
+ * fh_sparse_index_bytes(); what was used is in totals (device memory, valid once the stream
+ * has reached it).  The decoder is given the valid prefix of each stream; blocks that would
+ * reach past it are zero-filled rather than read.  maps*h*w <= 2^31.  workspace:
+ * fh_sparse_workspace_bytes() bytes of scratch.  Nothing is allocated or synchronised. */
+size_t    fh_sparse_info_bytes(int64_t maps, int64_t h, int64_t w, int32_t n);
+size_t    fh_sparse_index_bytes(int64_t maps, int64_t h, int64_t w, int32_t n);
+size_t    fh_sparse_workspace_bytes(int64_t maps, int64_t h, int64_t w, int32_t n);
+fh_status fh_sparse_encode(const void *x, fh_dtype dtype, int64_t maps, int64_t h, int64_t w, int32_t n, float tau,
+                           void *info, size_t info_cap, void *values, size_t values_cap,
+                           void *indices, size_t indices_cap, void *totals,
+                           void *workspace, size_t workspace_cap, void *stream);
+fh_status fh_sparse_decode(const void *info, const void *values, size_t values_bytes,
+                           const void *indices, size_t indices_bytes, fh_dtype dtype,
+                           int64_t maps, int64_t h, int64_t w, int32_t n,
+                           void *out, size_t out_cap, void *workspace, size_t workspace_cap, void *stream);
 
 const char *fh_status_string(fh_status s);
 

@@ -31,7 +31,9 @@ FH_ROUND_NEAREST, FH_ROUND_STOCHASTIC = 0, 1
 EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "fh_roundtrip",
            "fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch", "fh_batch_capacity",
            "fh_classify_workspace_bytes", "fh_classify_channels",
-           "fh_raw_bytes", "fh_channel_slots", "fh_compress_mixed", "fh_decompress_mixed", "fh_status_string")
+           "fh_raw_bytes", "fh_channel_slots", "fh_compress_mixed", "fh_decompress_mixed",
+           "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
+           "fh_sparse_decode", "fh_status_string")
 
 
 class fh_params(ctypes.Structure):
@@ -86,6 +88,18 @@ _lib.fh_decompress_mixed.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_
                                      _P(fh_params), ctypes.c_void_p, ctypes.c_int64,
                                      ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fh_decompress_mixed.restype = ctypes.c_int
+for _name in ("fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes"):
+    getattr(_lib, _name).argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
+    getattr(_lib, _name).restype = ctypes.c_size_t
+_lib.fh_sparse_encode.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                  ctypes.c_int32, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t,
+                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fh_sparse_encode.restype = ctypes.c_int
+_lib.fh_sparse_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                                  ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                  ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fh_sparse_decode.restype = ctypes.c_int
 _lib.fh_batch_capacity.argtypes = []
 _lib.fh_batch_capacity.restype = ctypes.c_int32
 _lib.fh_status_string.argtypes = [ctypes.c_int]
@@ -389,4 +403,79 @@ def fh_decompress_mixed(packed: torch.Tensor, meta: torch.Tensor, raw: torch.Ten
                                         outer, channels, inner, ctypes.byref(p), slots.data_ptr(),
                                         int(raw_channels), _dtype_code(out), _ptr(out), _nbytes(out),
                                         _stream_ptr(stream)))
+    return out
+
+
+def sparse_info_bytes(maps: int, h: int, w: int, n: int) -> int:
+    return int(_lib.fh_sparse_info_bytes(maps, h, w, n))
+
+
+def sparse_index_bytes(maps: int, h: int, w: int, n: int) -> int:
+    return int(_lib.fh_sparse_index_bytes(maps, h, w, n))
+
+
+def sparse_workspace_bytes(maps: int, h: int, w: int, n: int) -> int:
+    return int(_lib.fh_sparse_workspace_bytes(maps, h, w, n))
+
+
+@dataclass
+class SparseBuffers:
+    """Worst-case sized device buffers of one fh_sparse_encode call; `totals` (uint64[4] as
+    int64: values written, index bytes written, sparse blocks, dense blocks) says how much of
+    `values` and `indices` is in use."""
+    info: torch.Tensor
+    values: torch.Tensor
+    indices: torch.Tensor
+    totals: torch.Tensor
+    workspace: torch.Tensor
+
+
+def alloc_sparse(maps: int, h: int, w: int, n: int, dtype, device) -> SparseBuffers:
+    return SparseBuffers(
+        info=torch.empty(max(1, sparse_info_bytes(maps, h, w, n)), dtype=torch.uint8, device=device),
+        values=torch.empty(max(1, maps * h * w), dtype=dtype, device=device),
+        indices=torch.empty(max(1, sparse_index_bytes(maps, h, w, n)), dtype=torch.uint8, device=device),
+        totals=torch.zeros(4, dtype=torch.int64, device=device),
+        workspace=torch.empty(max(8, sparse_workspace_bytes(maps, h, w, n)), dtype=torch.uint8, device=device))
+
+
+def fh_sparse_encode(x: torch.Tensor, maps: int, h: int, w: int, n: int, tau: float,
+                     buffers: Optional[SparseBuffers] = None, stream=None) -> SparseBuffers:
+    """Enqueue the block-wise sparse storage of `x` viewed as [maps][h][w]."""
+    _device_tensor(x, "x")
+    if x.numel() != maps * h * w:
+        raise ValueError("x.numel() != maps * h * w")
+    b = buffers if buffers is not None else alloc_sparse(maps, h, w, n, x.dtype, x.device)
+    for t, what in ((b.info, "info"), (b.values, "values"), (b.indices, "indices"), (b.totals, "totals"),
+                    (b.workspace, "workspace")):
+        _device_tensor(t, what)
+    if b.values.dtype != x.dtype or _nbytes(b.totals) < 32:
+        raise FedHybridError(7)
+    with torch.cuda.device(x.device):
+        _check(_lib.fh_sparse_encode(_ptr(x), _dtype_code(x), maps, h, w, int(n), float(tau),
+                                     b.info.data_ptr(), _nbytes(b.info), b.values.data_ptr(), _nbytes(b.values),
+                                     b.indices.data_ptr(), _nbytes(b.indices), b.totals.data_ptr(),
+                                     b.workspace.data_ptr(), _nbytes(b.workspace), _stream_ptr(stream)))
+    return b
+
+
+def fh_sparse_decode(info: torch.Tensor, values: torch.Tensor, indices: torch.Tensor, maps: int, h: int, w: int,
+                     n: int, out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                     stream=None) -> torch.Tensor:
+    """Enqueue the inverse; `values` and `indices` are the valid prefixes of the two streams
+    (their sizes bound what the kernel reads).  Returns the flat [maps][h][w] tensor."""
+    for t, what in ((info, "info"), (values, "values"), (indices, "indices")):
+        _device_tensor(t, what)
+    if out is None:
+        out = torch.empty(maps * h * w, dtype=values.dtype, device=info.device)
+    if workspace is None:
+        workspace = torch.empty(max(8, sparse_workspace_bytes(maps, h, w, n)), dtype=torch.uint8, device=info.device)
+    _device_tensor(out, "out")
+    _device_tensor(workspace, "workspace")
+    if _nbytes(info) < sparse_info_bytes(maps, h, w, n) or out.dtype != values.dtype:
+        raise FedHybridError(7)
+    with torch.cuda.device(info.device):
+        _check(_lib.fh_sparse_decode(_ptr(info), _ptr(values), _nbytes(values), _ptr(indices), _nbytes(indices),
+                                     _dtype_code(out), maps, h, w, int(n), _ptr(out), _nbytes(out),
+                                     workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)))
     return out

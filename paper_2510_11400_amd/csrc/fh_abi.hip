@@ -251,8 +251,8 @@ const char* fh_status_string(fh_status s)
         case FH_ERR_ALIGNMENT: return "x, packed and out must be 16-byte aligned, meta 8-byte aligned";
         case FH_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
         case FH_ERR_BAD_COUNT: return "item count is negative";
-        case FH_ERR_BAD_SHAPE: return "outer must be >= 0, inner >= 1, channels in 1..16384";
-        case FH_ERR_BAD_PARAM: return "k_sigma must be positive and min_outliers at least 1";
+        case FH_ERR_BAD_SHAPE: return "outer / maps must be >= 0, inner / h / w >= 1, channels in 1..16384, raw_channels in 0..channels";
+        case FH_ERR_BAD_PARAM: return "k_sigma must be positive, min_outliers at least 1, the pooling window 2, 4 or 8";
     }
     return "unknown status";
 }

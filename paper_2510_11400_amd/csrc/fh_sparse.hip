@@ -1,0 +1,431 @@
+// Sparse-block storage of salient-channel feature maps on gfx950 (paper Section 4.4.1: a
+// binary non-zero mask is mean-filtered by n x n average pooling and compared with a
+// threshold tau; sparse blocks are stored in Compressed Sparse Row format, dense blocks are
+// kept as they are; zeros come back exactly).
+//
+// The pooling windows ("tiles" below, to keep them apart from GPU workgroups) are independent,
+// and what each contributes to the two output streams is known from one byte of information,
+// so the streams are laid out by a prefix sum over tiles -- stream compaction:
+//   pass 1  one thread per tile: count non-zeros, decide sparse / dense, write the tile's info
+//           byte; each workgroup adds up what its 256 tiles will write;
+//   pass 2  one workgroup turns the per-workgroup sums into exclusive offsets (and totals);
+//   pass 3  one thread per tile: offsets inside the workgroup by a scan through LDS, then the
+//           tile's values and CSR structure go to their final place.
+// Restoring runs the same three passes with the info bytes as the only input of pass 1.
+// Everything here is integer and byte work; results do not depend on launch geometry.
+#include "../../include/fedhybrid.h"
+
+#include "fh_channels.hpp"
+
+namespace fh {
+namespace {
+
+constexpr int kTileThreads = 256;                  // tiles per workgroup
+constexpr int kScanThreads = 1024;
+
+struct Sums {                                      // what a run of tiles writes
+    uint64_t values, index_bytes, sparse_tiles;
+};
+__device__ __forceinline__ Sums operator+(const Sums& a, const Sums& b)
+{
+    return Sums{a.values + b.values, a.index_bytes + b.index_bytes, a.sparse_tiles + b.sparse_tiles};
+}
+
+struct MapShape {
+    const void* x;             // [maps][h][w] (encode: input; decode: output)
+    uint32_t h, w, n;
+    uint32_t tiles;            // maps * BH * BW
+    ExactDiv bw, bh;           // tile index -> (map, tile row, tile column)
+    uint32_t BW, BH;
+};
+
+struct TilePos {
+    uint64_t origin;           // element index of the tile's first element
+    uint32_t rows, cols;
+};
+__device__ __forceinline__ TilePos tile_pos(const MapShape& s, uint32_t b)
+{
+    const uint32_t row_of_tiles = div_exact(b, s.bw);         // m * BH + bi
+    const uint32_t bj = b - row_of_tiles * s.BW;
+    const uint32_t m = div_exact(row_of_tiles, s.bh);
+    const uint32_t bi = row_of_tiles - m * s.BH;
+    const uint32_t r0 = bi * s.n, c0 = bj * s.n;
+    TilePos t;
+    t.rows = s.h - r0 < s.n ? s.h - r0 : s.n;
+    t.cols = s.w - c0 < s.n ? s.w - c0 : s.n;
+    t.origin = ((uint64_t)m * s.h + r0) * s.w + c0;
+    return t;
+}
+
+// what a tile with this info byte adds to the streams
+__device__ __forceinline__ Sums tile_sums(uint32_t info, uint32_t rows)
+{
+    const uint32_t count = info & 0x7fu;
+    const bool dense = info & 0x80u;
+    return Sums{count, dense ? 0u : rows + 1u + count, dense ? 0u : 1u};
+}
+
+template <typename T> __device__ __forceinline__ uint32_t bits_of(T v);
+template <> __device__ __forceinline__ uint32_t bits_of<uint32_t>(uint32_t v) { return v; }
+template <> __device__ __forceinline__ uint32_t bits_of<uint16_t>(uint16_t v) { return v; }
+
+// Sum of `mine` over the workgroup, to thread 0's caller through LDS; every thread gets the
+// exclusive prefix of its own value.
+__device__ __forceinline__ Sums workgroup_exclusive_scan(Sums mine, Sums* lds /* [kTileThreads] */, Sums* total)
+{
+    const int t = threadIdx.x;
+    lds[t] = mine;
+    __syncthreads();
+    for (int step = 1; step < kTileThreads; step <<= 1) {
+        Sums add = {0, 0, 0};
+        if (t >= step) add = lds[t - step];
+        __syncthreads();
+        lds[t] = lds[t] + add;
+        __syncthreads();
+    }
+    const Sums inclusive = lds[t];
+    *total = lds[kTileThreads - 1];
+    return Sums{inclusive.values - mine.values, inclusive.index_bytes - mine.index_bytes,
+                inclusive.sparse_tiles - mine.sparse_tiles};
+}
+
+// ---- pass 1 (encode): non-zero count, density, info byte, workgroup sums ---------------------
+template <typename Bits, int N>
+__global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const MapShape s, const float tau,
+                                                                    uint8_t* __restrict__ info,
+                                                                    Sums* __restrict__ wg_sums)
+{
+    __shared__ Sums lds[kTileThreads];
+    const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
+    Sums mine = {0, 0, 0};
+    if (b < s.tiles) {
+        const TilePos t = tile_pos(s, b);
+        const Bits* x = static_cast<const Bits*>(s.x) + t.origin;
+        uint32_t nnz = 0;
+#pragma unroll
+        for (int r = 0; r < N; ++r)
+#pragma unroll
+            for (int c = 0; c < N; ++c)
+                if (r < (int)t.rows && c < (int)t.cols) nnz += bits_of<Bits>(x[(uint64_t)r * s.w + c]) != 0u ? 1u : 0u;
+        const uint32_t area = t.rows * t.cols;
+        const float density = (float)nnz / (float)area;       // IEEE division: average pooling of the mask
+        const uint32_t byte = density <= tau ? nnz : (0x80u | area);
+        info[b] = (uint8_t)byte;
+        mine = tile_sums(byte, t.rows);
+    }
+    Sums total;
+    workgroup_exclusive_scan(mine, lds, &total);
+    if (threadIdx.x == 0) wg_sums[blockIdx.x] = total;
+}
+
+// ---- pass 1 (decode): workgroup sums from the info bytes --------------------------------------
+__global__ __launch_bounds__(kTileThreads) void sparse_sums_kernel(const MapShape s, const uint8_t* __restrict__ info,
+                                                                   Sums* __restrict__ wg_sums)
+{
+    __shared__ Sums lds[kTileThreads];
+    const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
+    Sums mine = {0, 0, 0};
+    if (b < s.tiles) mine = tile_sums(info[b], tile_pos(s, b).rows);
+    Sums total;
+    workgroup_exclusive_scan(mine, lds, &total);
+    if (threadIdx.x == 0) wg_sums[blockIdx.x] = total;
+}
+
+// ---- pass 2: exclusive scan of the workgroup sums, in place; totals -----------------------------
+__global__ __launch_bounds__(kScanThreads) void sparse_scan_kernel(Sums* __restrict__ wg_sums, uint32_t count,
+                                                                   uint32_t tiles, uint64_t* __restrict__ totals)
+{
+    __shared__ Sums lds[kScanThreads];
+    const int t = threadIdx.x;
+    Sums carry = {0, 0, 0};
+    for (uint32_t base = 0; base < count; base += kScanThreads) {     // every thread walks every chunk
+        const uint32_t i = base + t;
+        const Sums mine = i < count ? wg_sums[i] : Sums{0, 0, 0};
+        lds[t] = mine;
+        __syncthreads();
+        for (int step = 1; step < kScanThreads; step <<= 1) {
+            Sums add = {0, 0, 0};
+            if (t >= step) add = lds[t - step];
+            __syncthreads();
+            lds[t] = lds[t] + add;
+            __syncthreads();
+        }
+        const Sums inclusive = lds[t];
+        const Sums chunk = lds[kScanThreads - 1];
+        if (i < count)
+            wg_sums[i] = Sums{carry.values + inclusive.values - mine.values,
+                              carry.index_bytes + inclusive.index_bytes - mine.index_bytes,
+                              carry.sparse_tiles + inclusive.sparse_tiles - mine.sparse_tiles};
+        carry = carry + chunk;
+        __syncthreads();
+    }
+    if (t == 0 && totals) {
+        totals[0] = carry.values;
+        totals[1] = carry.index_bytes;
+        totals[2] = carry.sparse_tiles;
+        totals[3] = (uint64_t)tiles - carry.sparse_tiles;
+    }
+}
+
+// ---- pass 3 (encode): values and CSR structure to their place ---------------------------------------
+template <typename Bits, int N>
+__global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapShape s, const uint8_t* __restrict__ info,
+                                                                    const Sums* __restrict__ wg_base,
+                                                                    Bits* __restrict__ values,
+                                                                    uint8_t* __restrict__ indices)
+{
+    __shared__ Sums lds[kTileThreads];
+    const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
+    const bool live = b < s.tiles;
+    TilePos t = {0, 0, 0};
+    uint32_t byte = 0x80u;
+    Sums mine = {0, 0, 0};
+    if (live) {
+        t = tile_pos(s, b);
+        byte = info[b];
+        mine = tile_sums(byte, t.rows);
+    }
+    Sums total;
+    const Sums before = workgroup_exclusive_scan(mine, lds, &total);
+    if (!live) return;
+    const Sums base = wg_base[blockIdx.x];
+    const Bits* x = static_cast<const Bits*>(s.x) + t.origin;
+    Bits* v = values + base.values + before.values;
+    if (byte & 0x80u) {                                       // dense: the tile, row-major
+        uint32_t k = 0;
+#pragma unroll
+        for (int r = 0; r < N; ++r)
+#pragma unroll
+            for (int c = 0; c < N; ++c)
+                if (r < (int)t.rows && c < (int)t.cols) v[k++] = x[(uint64_t)r * s.w + c];
+    } else {                                                  // sparse: row_ptr, then columns; values alongside
+        uint8_t* row_ptr = indices + base.index_bytes + before.index_bytes;
+        uint8_t* col = row_ptr + t.rows + 1;
+        uint32_t k = 0;
+#pragma unroll
+        for (int r = 0; r < N; ++r) {
+            if (r < (int)t.rows) {
+                row_ptr[r] = (uint8_t)k;
+#pragma unroll
+                for (int c = 0; c < N; ++c) {
+                    if (c < (int)t.cols) {
+                        const Bits e = x[(uint64_t)r * s.w + c];
+                        if (bits_of<Bits>(e) != 0u) {
+                            v[k] = e;
+                            col[k] = (uint8_t)c;
+                            ++k;
+                        }
+                    }
+                }
+            }
+        }
+        row_ptr[t.rows] = (uint8_t)k;
+    }
+}
+
+// ---- pass 3 (decode): tiles back from the streams -------------------------------------------------
+// A stream this library did not write must not make the kernel read or write out of bounds:
+// a tile whose slice would leave a stream is zero-filled, entries outside the tile are dropped.
+template <typename Bits, int N>
+__global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShape s, const uint8_t* __restrict__ info,
+                                                                   const Sums* __restrict__ wg_base,
+                                                                   const Bits* __restrict__ values, uint64_t value_count,
+                                                                   const uint8_t* __restrict__ indices,
+                                                                   uint64_t index_count)
+{
+    __shared__ Sums lds[kTileThreads];
+    const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
+    const bool live = b < s.tiles;
+    TilePos t = {0, 0, 0};
+    uint32_t byte = 0x80u;
+    Sums mine = {0, 0, 0};
+    if (live) {
+        t = tile_pos(s, b);
+        byte = info[b];
+        mine = tile_sums(byte, t.rows);
+    }
+    Sums total;
+    const Sums before = workgroup_exclusive_scan(mine, lds, &total);
+    if (!live) return;
+    const Sums base = wg_base[blockIdx.x];
+    Bits* out = static_cast<Bits*>(const_cast<void*>(s.x)) + t.origin;
+    const uint64_t v0 = base.values + before.values, i0 = base.index_bytes + before.index_bytes;
+    const uint32_t count = byte & 0x7fu;
+    const bool in_bounds = v0 + mine.values <= value_count && i0 + mine.index_bytes <= index_count;
+    const Bits* v = values + v0;
+    if ((byte & 0x80u) && in_bounds && count == t.rows * t.cols) {
+        uint32_t k = 0;
+#pragma unroll
+        for (int r = 0; r < N; ++r)
+#pragma unroll
+            for (int c = 0; c < N; ++c)
+                if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = v[k++];
+        return;
+    }
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+#pragma unroll
+        for (int c = 0; c < N; ++c)
+            if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = (Bits)0;
+    if ((byte & 0x80u) || !in_bounds) return;
+    const uint8_t* row_ptr = indices + i0;
+    const uint8_t* col = row_ptr + t.rows + 1;
+    for (uint32_t r = 0; r < t.rows; ++r) {
+        uint32_t k = row_ptr[r], end = row_ptr[r + 1];
+        if (end > count) end = count;
+        for (; k < end; ++k) {
+            const uint32_t c = col[k];
+            if (c < t.cols) out[(uint64_t)r * s.w + c] = v[k];
+        }
+    }
+}
+
+// ---- host side ------------------------------------------------------------------------------------
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+size_t elem_size(int dtype) { return dtype == FH_F32 ? 4u : 2u; }
+
+constexpr int64_t kMaxElems = (int64_t)1 << 31;
+
+// tiles of the whole input, or -1 when the shape is not served
+int64_t tile_count(int64_t maps, int64_t h, int64_t w, int64_t n)
+{
+    if (maps < 0 || h < 1 || w < 1 || (n != 2 && n != 4 && n != 8)) return -1;
+    if (h > kMaxElems || w > kMaxElems || h * w > kMaxElems) return -1;
+    if (maps > kMaxElems / (h * w)) return -1;
+    return maps * ((h + n - 1) / n) * ((w + n - 1) / n);
+}
+
+uint32_t workgroups(int64_t tiles) { return (uint32_t)((tiles + kTileThreads - 1) / kTileThreads); }
+
+MapShape make_shape(const void* x, int64_t h, int64_t w, int n, int64_t tiles)
+{
+    MapShape s;
+    s.x = x;
+    s.h = (uint32_t)h; s.w = (uint32_t)w; s.n = (uint32_t)n;
+    s.tiles = (uint32_t)tiles;
+    s.BH = (uint32_t)((h + n - 1) / n);
+    s.BW = (uint32_t)((w + n - 1) / n);
+    s.bw = make_exact_div(s.BW);
+    s.bh = make_exact_div(s.BH);
+    return s;
+}
+
+fh_status check_shape(int64_t maps, int64_t h, int64_t w, int32_t n, int64_t* tiles)
+{
+    if (n != 2 && n != 4 && n != 8) return FH_ERR_BAD_PARAM;
+    if (maps < 0 || h < 1 || w < 1) return FH_ERR_BAD_SHAPE;
+    *tiles = tile_count(maps, h, w, n);
+    return *tiles < 0 ? FH_ERR_BAD_NUMEL : FH_OK;
+}
+
+}  // namespace
+}  // namespace fh
+
+extern "C" {
+
+size_t fh_sparse_info_bytes(int64_t maps, int64_t h, int64_t w, int32_t n)
+{
+    const int64_t t = fh::tile_count(maps, h, w, n);
+    return t < 0 ? 0 : (size_t)t;
+}
+
+size_t fh_sparse_index_bytes(int64_t maps, int64_t h, int64_t w, int32_t n)
+{
+    const int64_t t = fh::tile_count(maps, h, w, n);
+    return t < 0 ? 0 : (size_t)t * (size_t)(n + 1) + (size_t)(maps * h * w);
+}
+
+size_t fh_sparse_workspace_bytes(int64_t maps, int64_t h, int64_t w, int32_t n)
+{
+    const int64_t t = fh::tile_count(maps, h, w, n);
+    if (t < 0) return 0;
+    return sizeof(fh::Sums) * (size_t)(fh::workgroups(t) > 0 ? fh::workgroups(t) : 1);
+}
+
+fh_status fh_sparse_encode(const void* x, fh_dtype dtype, int64_t maps, int64_t h, int64_t w, int32_t n, float tau,
+                           void* info, size_t info_cap, void* values, size_t values_cap,
+                           void* indices, size_t indices_cap, void* totals,
+                           void* workspace, size_t workspace_cap, void* stream)
+{
+    using namespace fh;
+    if (dtype != FH_F32 && dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    int64_t tiles = 0;
+    const fh_status st = check_shape(maps, h, w, n, &tiles);
+    if (st != FH_OK) return st;
+    if (!totals || !workspace) return FH_ERR_NULL;
+    if (!aligned(totals, 8) || !aligned(workspace, 8)) return FH_ERR_ALIGNMENT;
+    if (workspace_cap < fh_sparse_workspace_bytes(maps, h, w, n)) return FH_ERR_BUFFER_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Sums* wg = static_cast<Sums*>(workspace);
+    if (tiles == 0) {                                         // nothing to store: totals are all zero
+        hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, 0u, 0u,
+                           static_cast<uint64_t*>(totals));
+        return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+    }
+    if (!x || !info || !values || !indices) return FH_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(values, 4)) return FH_ERR_ALIGNMENT;
+    if (info_cap < (size_t)tiles || values_cap < (size_t)(maps * h * w) * elem_size(dtype) ||
+        indices_cap < fh_sparse_index_bytes(maps, h, w, n))
+        return FH_ERR_BUFFER_TOO_SMALL;
+
+    const MapShape shape = make_shape(x, h, w, n, tiles);
+    const dim3 grid(workgroups(tiles)), block(kTileThreads);
+    uint8_t* inf = static_cast<uint8_t*>(info);
+    uint8_t* idx = static_cast<uint8_t*>(indices);
+#define FH_SPARSE_ENCODE(BITS, NN)                                                                              \
+    do {                                                                                                        \
+        hipLaunchKernelGGL((sparse_count_kernel<BITS, NN>), grid, block, 0, s, shape, tau, inf, wg);            \
+        hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, grid.x, (uint32_t)tiles,  \
+                           static_cast<uint64_t*>(totals));                                                     \
+        hipLaunchKernelGGL((sparse_write_kernel<BITS, NN>), grid, block, 0, s, shape, inf, wg,                  \
+                           static_cast<BITS*>(values), idx);                                                    \
+    } while (0)
+    if (dtype == FH_F32) {
+        if (n == 2) FH_SPARSE_ENCODE(uint32_t, 2); else if (n == 4) FH_SPARSE_ENCODE(uint32_t, 4); else FH_SPARSE_ENCODE(uint32_t, 8);
+    } else {
+        if (n == 2) FH_SPARSE_ENCODE(uint16_t, 2); else if (n == 4) FH_SPARSE_ENCODE(uint16_t, 4); else FH_SPARSE_ENCODE(uint16_t, 8);
+    }
+#undef FH_SPARSE_ENCODE
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+fh_status fh_sparse_decode(const void* info, const void* values, size_t values_bytes,
+                           const void* indices, size_t indices_bytes, fh_dtype dtype,
+                           int64_t maps, int64_t h, int64_t w, int32_t n,
+                           void* out, size_t out_cap, void* workspace, size_t workspace_cap, void* stream)
+{
+    using namespace fh;
+    if (dtype != FH_F32 && dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    int64_t tiles = 0;
+    const fh_status st = check_shape(maps, h, w, n, &tiles);
+    if (st != FH_OK) return st;
+    if (tiles == 0) return FH_OK;
+    if (!info || !out || !workspace) return FH_ERR_NULL;
+    if ((values_bytes > 0 && !values) || (indices_bytes > 0 && !indices)) return FH_ERR_NULL;
+    if (!aligned(out, 4) || !aligned(values, 4) || !aligned(workspace, 8)) return FH_ERR_ALIGNMENT;
+    if (workspace_cap < fh_sparse_workspace_bytes(maps, h, w, n)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (out_cap < (size_t)(maps * h * w) * elem_size(dtype)) return FH_ERR_BUFFER_TOO_SMALL;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Sums* wg = static_cast<Sums*>(workspace);
+    const MapShape shape = make_shape(out, h, w, n, tiles);
+    const dim3 grid(workgroups(tiles)), block(kTileThreads);
+    const uint8_t* inf = static_cast<const uint8_t*>(info);
+    const uint8_t* idx = static_cast<const uint8_t*>(indices);
+    const uint64_t nvals = values_bytes / elem_size(dtype);
+    hipLaunchKernelGGL(sparse_sums_kernel, grid, block, 0, s, shape, inf, wg);
+    hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, grid.x, (uint32_t)tiles,
+                       static_cast<uint64_t*>(nullptr));
+#define FH_SPARSE_DECODE(BITS, NN)                                                                        \
+    hipLaunchKernelGGL((sparse_read_kernel<BITS, NN>), grid, block, 0, s, shape, inf, wg,                 \
+                       static_cast<const BITS*>(values), nvals, idx, (uint64_t)indices_bytes)
+    if (dtype == FH_F32) {
+        if (n == 2) FH_SPARSE_DECODE(uint32_t, 2); else if (n == 4) FH_SPARSE_DECODE(uint32_t, 4); else FH_SPARSE_DECODE(uint32_t, 8);
+    } else {
+        if (n == 2) FH_SPARSE_DECODE(uint16_t, 2); else if (n == 4) FH_SPARSE_DECODE(uint16_t, 4); else FH_SPARSE_DECODE(uint16_t, 8);
+    }
+#undef FH_SPARSE_DECODE
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+}  // extern "C"

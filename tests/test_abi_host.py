@@ -203,3 +203,42 @@ def test_raw_store_size():
     assert api.raw_bytes(4, 3, 50, torch.float32) == 4 * 3 * 50 * 4
     assert api.raw_bytes(4, 3, 50, torch.bfloat16) == 4 * 3 * 50 * 2
     assert api.raw_bytes(0, 3, 50, torch.float32) == 0 and api.raw_bytes(4, 0, 50, torch.float32) == 0
+
+
+def _sencode(x=FAKE, dtype=0, maps=4, h=10, w=10, n=4, tau=0.5, info=FAKE, info_cap=1 << 20, values=FAKE,
+             values_cap=1 << 20, indices=FAKE, indices_cap=1 << 20, totals=FAKE, ws=FAKE, ws_cap=1 << 20):
+    return api.raw_library().fh_sparse_encode(x, dtype, maps, h, w, n, tau, info, info_cap, values, values_cap,
+                                              indices, indices_cap, totals, ws, ws_cap, None)
+
+
+def _sdecode(info=FAKE, values=FAKE, values_bytes=1 << 20, indices=FAKE, indices_bytes=1 << 20, dtype=0, maps=4,
+             h=10, w=10, n=4, out=FAKE, out_cap=1 << 20, ws=FAKE, ws_cap=1 << 20):
+    return api.raw_library().fh_sparse_decode(info, values, values_bytes, indices, indices_bytes, dtype, maps, h, w, n,
+                                              out, out_cap, ws, ws_cap, None)
+
+
+def test_sparse_calls_reject_bad_arguments_before_any_launch():
+    for call in (_sencode, _sdecode):
+        assert call(dtype=2) == 2
+        assert call(n=3) == 12 and call(n=16) == 12 and call(n=0) == 12
+        assert call(maps=-1) == 11 and call(h=0) == 11 and call(w=0) == 11
+        assert call(maps=1 << 20, h=1 << 10, w=1 << 10) == 6              # more than 2^31 elements
+        assert call(ws=None) == 1 and call(info=None) == 1
+        assert call(ws=FAKE + 4) == 8
+        assert call(ws_cap=23) == 7
+    assert _sencode(x=None) == 1 and _sencode(values=None) == 1 and _sencode(indices=None) == 1
+    assert _sencode(totals=None) == 1 and _sencode(totals=FAKE + 4) == 8 and _sencode(x=FAKE + 2) == 8
+    assert _sencode(info_cap=4 * 9 - 1) == 7 and _sencode(values_cap=4 * 100 * 4 - 1) == 7
+    assert _sencode(indices_cap=api.sparse_index_bytes(4, 10, 10, 4) - 1) == 7
+    assert _sdecode(out=None) == 1 and _sdecode(out_cap=4 * 100 * 4 - 1) == 7 and _sdecode(out=FAKE + 2) == 8
+    assert _sdecode(values=None) == 1 and _sdecode(indices=None) == 1
+    assert _sdecode(maps=0, info=None, values=None, indices=None, out=None, ws=None) == 0
+
+
+def test_sparse_size_helpers():
+    # 4 maps of 10 x 10 with 4 x 4 windows: 3 x 3 blocks per map
+    assert api.sparse_info_bytes(4, 10, 10, 4) == 36 == oracle.sparse_blocks(4, 10, 10, 4)
+    assert api.sparse_index_bytes(4, 10, 10, 4) == 36 * 5 + 400
+    assert api.sparse_workspace_bytes(4, 10, 10, 4) == 24
+    assert api.sparse_workspace_bytes(1000, 16, 16, 2) == 24 * -(-64000 // 256)
+    assert api.sparse_info_bytes(4, 10, 10, 3) == 0 and api.sparse_info_bytes(0, 10, 10, 4) == 0

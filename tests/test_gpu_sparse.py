@@ -1,0 +1,190 @@
+"""Parity of the HIP sparse-block storage with the CPU oracle (Section 4.4.1: non-zero mask,
+n x n average pooling against tau, sparse blocks in CSR form, zeros preserved).  Bar: the info
+bytes, both streams up to the reported totals, the totals and the restored maps all bit-exact."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_11400_amd import workloads as W
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def api():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a visible MI355X")
+    from paper_2510_11400_amd import api as _api
+    return _api
+
+
+def _device(x, dtype):
+    t = torch.from_numpy(x.view(np.int16) if dtype == "bf16" else x).cuda()
+    return t.view(torch.bfloat16) if dtype == "bf16" else t
+
+
+def _host(t, dtype):
+    t = t.cpu()
+    return t.view(torch.int16).numpy().view(np.uint16) if dtype == "bf16" else t.numpy()
+
+
+def _bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def _check(api, x, maps, h, w, n, tau, dtype="f32", name=""):
+    print(f"[sparse] {name} {dtype} [{maps}][{h}][{w}] n={n} tau={tau}", flush=True)
+    info, v, idx, totals = oracle.sparse_encode(x, maps, h, w, n, tau, dtype=dtype)
+    dx = _device(x, dtype)
+    b = api.fh_sparse_encode(dx, maps, h, w, n, tau)
+    torch.cuda.synchronize()
+    gt = b.totals.cpu().numpy().view(np.uint64)
+    assert np.array_equal(gt, totals), f"{name}: totals {gt} vs {totals}"
+    nb = oracle.sparse_blocks(maps, h, w, n)
+    assert np.array_equal(b.info.cpu().numpy()[:nb], info), f"{name}: info bytes differ"
+    gv = _host(b.values, dtype)[:int(totals[0])]
+    assert np.array_equal(_bits(gv), _bits(v)), f"{name}: value stream differs"
+    gi = b.indices.cpu().numpy()[:int(totals[1])]
+    assert np.array_equal(gi, idx), f"{name}: index stream differs"
+    out = api.fh_sparse_decode(b.info, b.values[:int(totals[0])], b.indices[:int(totals[1])], maps, h, w, n)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(_host(out, dtype)), _bits(x)), f"{name}: round trip is not lossless"
+    return totals
+
+
+SHAPES = [(1, 1, 1), (3, 7, 7), (8, 14, 14), (5, 28, 28), (2, 56, 56), (4, 13, 29), (1, 1, 700), (2, 300, 1),
+          (600, 7, 7), (3, 57, 31), (1, 112, 112), (257, 9, 10)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("n", [2, 4, 8])
+def test_shapes_and_windows(api, shape, n):
+    maps, h, w = shape
+    x = W.salient_feature_maps(maps, h, w, seed=h + w + n)
+    _check(api, x, maps, h, w, n, 0.5, name="shape")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("tau", [-1.0, 0.0, 0.2, 0.3, 0.75, 1.0, float("nan")])
+def test_thresholds_and_dtypes(api, dtype, tau):
+    maps, h, w = 24, 27, 22
+    x = W.salient_feature_maps(maps, h, w, seed=int(0 if tau != tau else abs(tau) * 10) + 3, dtype=dtype)
+    rng = np.random.default_rng(1)
+    x[rng.integers(0, x.size, 40)] = 0x8000 if dtype == "bf16" else -0.0       # negative zeros are values
+    for n in (2, 4, 8):
+        t = _check(api, x, maps, h, w, n, tau, dtype=dtype, name="tau")
+        if tau != tau or tau < 0:
+            assert t[2] == 0
+        if tau >= 1:
+            assert t[3] == 0
+
+
+def test_all_zero_and_all_dense_maps(api):
+    z = np.zeros(6 * 20 * 20, f32)
+    t = _check(api, z, 6, 20, 20, 4, 0.5, name="zeros")
+    assert t.tolist() == [0, 150 * 5, 150, 0]
+    d = np.arange(1, 6 * 20 * 20 + 1, dtype=f32)
+    t = _check(api, d, 6, 20, 20, 4, 0.5, name="dense")
+    assert t.tolist() == [2400, 0, 0, 150]
+    t = _check(api, d, 6, 20, 20, 4, 1.0, name="dense stored as CSR")
+    assert t.tolist() == [2400, 150 * 5 + 2400, 150, 0]
+
+
+def test_more_tiles_than_one_scan_chunk(api):
+    # 1024 workgroups of 256 tiles fill one chunk of the middle pass; this needs three
+    maps, h, w, n = 9000, 16, 16, 2                         # 576000 tiles -> 2250 workgroups
+    x = W.salient_feature_maps(maps, h, w, seed=77)
+    _check(api, x, maps, h, w, n, 0.5, name="scan chunks")
+
+
+def test_full_size_salient_channels_of_a_layer(api):
+    # 4 kept channels of the 112 x 112 expanded feature map at batch 64
+    maps, h, w = 64 * 4, 112, 112
+    for dtype in ("f32", "bf16"):
+        x = W.salient_feature_maps(maps, h, w, seed=5, dtype=dtype)
+        _check(api, x, maps, h, w, 8, 0.5, dtype=dtype, name="layer")
+
+
+def test_buffers_can_be_reused_and_empty_input_is_fine(api):
+    maps, h, w, n = 10, 30, 30, 4
+    bufs = api.alloc_sparse(maps, h, w, n, torch.float32, "cuda")
+    for seed in (1, 2):
+        x = W.salient_feature_maps(maps, h, w, seed=seed, zero_level=0.2 * seed)
+        info, v, idx, totals = oracle.sparse_encode(x, maps, h, w, n, 0.4)
+        api.fh_sparse_encode(torch.from_numpy(x).cuda(), maps, h, w, n, 0.4, buffers=bufs)
+        torch.cuda.synchronize()
+        assert np.array_equal(bufs.totals.cpu().numpy().view(np.uint64), totals)
+        assert np.array_equal(bufs.values.cpu().numpy()[:int(totals[0])].view(np.uint32), v.view(np.uint32))
+    b = api.fh_sparse_encode(torch.empty(0, device="cuda"), 0, 5, 5, 4, 0.5)
+    torch.cuda.synchronize()
+    assert b.totals.cpu().tolist() == [0, 0, 0, 0]
+
+
+def test_decoder_stays_inside_truncated_or_foreign_streams(api):
+    """The decoder bounds every read by the sizes it is given: a block whose slice would leave a
+    stream is zero-filled, entries pointing outside a block are dropped.  The kernels run to
+    completion; only the restored values are (defined) garbage."""
+    maps, h, w, n = 8, 24, 24, 4
+    x = W.salient_feature_maps(maps, h, w, seed=3)
+    b = api.fh_sparse_encode(torch.from_numpy(x).cuda(), maps, h, w, n, 0.5)
+    torch.cuda.synchronize()
+    nv, ni = (int(v) for v in b.totals.cpu().tolist()[:2])
+    # truncated streams: the blocks that still fit come back exactly, the others as zeros
+    out = api.fh_sparse_decode(b.info, b.values[:nv // 2], b.indices[:ni // 2], maps, h, w, n)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    same = got == x
+    assert same[: x.size // 4].all() and ((got == 0) | same).all() and not same.all()
+    # foreign info bytes (random): must simply finish
+    junk = torch.randint(0, 256, (b.info.numel(),), dtype=torch.uint8, device="cuda")
+    out = api.fh_sparse_decode(junk, b.values[:nv], b.indices[:ni], maps, h, w, n)
+    torch.cuda.synchronize()
+    assert out.numel() == x.size
+    # foreign index bytes
+    junk_idx = torch.randint(0, 256, (ni,), dtype=torch.uint8, device="cuda")
+    out = api.fh_sparse_decode(b.info, b.values[:nv], junk_idx, maps, h, w, n)
+    torch.cuda.synchronize()
+    assert out.numel() == x.size
+
+
+def test_salient_channels_end_to_end(api):
+    """mixed compress -> sparse storage of the raw store -> back -> mixed restore, against the
+    oracle's mixed round trip (the sparse stage is lossless, so it must not show)."""
+    outer, C, hh, ww = 8, 48, 28, 28
+    inner = hh * ww
+    x, planted = W.outlier_channel_tensor(outer, C, inner, seed=21, dist="relu", salient_fraction=0.08)
+    mask = np.zeros(C, np.uint8)
+    mask[planted] = 1
+    cap = len(planted)
+    dx = torch.from_numpy(x).cuda()
+    d_slots = api.fh_channel_slots(torch.from_numpy(mask).cuda(), cap)
+    gp, gm, graw = api.fh_compress_mixed(dx, outer, C, inner, d_slots, cap, 128, 4, "stochastic", 4, 2)
+    b = api.fh_sparse_encode(graw, outer * cap, hh, ww, 4, 0.6)
+    torch.cuda.synchronize()
+    nv, ni, ns, nd = (int(v) for v in b.totals.cpu().tolist())
+    assert ns > 0 and nd > 0
+    raw_back = api.fh_sparse_decode(b.info, b.values[:nv], b.indices[:ni], outer * cap, hh, ww, 4)
+    got = api.fh_decompress_mixed(gp, gm, raw_back, outer, C, inner, d_slots, cap, 128, 4)
+    torch.cuda.synchronize()
+    slots, _ = oracle.channel_slots(mask, cap)
+    p, m, raw = oracle.compress_mixed(x, outer, C, inner, slots, cap, 128, 4, "stochastic", 4, 2)
+    want = oracle.decompress_mixed(p, m, raw, outer, C, inner, slots, cap, 128, 4)
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    stored = nv * 4 + ni + b.info.numel()
+    assert stored < raw.nbytes                               # post-ReLU salient channels do shrink
+
+
+def test_argument_errors_reach_the_caller(api):
+    x = torch.zeros(2 * 8 * 8, device="cuda")
+    with pytest.raises(api.FedHybridError) as e:
+        api.fh_sparse_encode(x, 2, 8, 8, 3, 0.5)
+    assert e.value.status == 12
+    bufs = api.alloc_sparse(2, 8, 8, 4, torch.float32, "cuda")
+    bufs.indices = bufs.indices[:10]
+    with pytest.raises(api.FedHybridError) as e:
+        api.fh_sparse_encode(x, 2, 8, 8, 4, 0.5, buffers=bufs)
+    assert e.value.status == 7
