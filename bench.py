@@ -201,6 +201,101 @@ def bench_mixed(args, api, W, dev) -> int:
     return 0
 
 
+def bench_sparse(args, api, W, dev) -> int:
+    """Sparse-block storage of salient-channel feature maps (non-zero mask, n x n average
+    pooling against tau, CSR for sparse blocks): the kept channels (4 %) of the MobileNetV2-style
+    set at batch 64, post-ReLU with clustered zeros.  One step = every map set encoded, then
+    every one decoded."""
+    import numpy as np
+    import torch
+
+    layers = ((64 * 1, 112, 112), (64 * 4, 112, 112), (64 * 6, 56, 56), (64 * 8, 28, 28), (64 * 15, 14, 14))
+    n, tau = 4, 0.5
+    t0 = time.time()
+    host, jobs = [], []
+    for i, (maps, h, w) in enumerate(layers):
+        x = W.salient_feature_maps(maps, h, w, seed=i)
+        host.append(x)
+        xd = torch.from_numpy(x).to(dev)
+        bufs = api.alloc_sparse(maps, h, w, n, torch.float32, dev)
+        out = torch.empty(x.size, dtype=torch.float32, device=dev)
+        jobs.append([xd, maps, h, w, bufs, out, None])
+    stream = torch.cuda.current_stream()
+    for job in jobs:                                          # stream sizes (fixed: the input is)
+        xd, maps, h, w, bufs, out, _ = job
+        api.fh_sparse_encode(xd, maps, h, w, n, tau, buffers=bufs, stream=stream)
+    torch.cuda.synchronize()
+    stored = 0
+    for job in jobs:
+        nv, ni, ns, nd = (int(v) for v in job[4].totals.cpu().tolist())
+        job[6] = (job[4].values[:nv], job[4].indices[:ni])
+        stored += nv * 4 + ni + job[4].info.numel()
+    nbytes = sum(x.nbytes for x in host)
+    print(f"[bench] sparse: {len(jobs)} map sets, {nbytes / 2**20:.1f} MiB resident, stored {stored / 2**20:.1f} MiB "
+          f"(generated + uploaded in {time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def step(timed=False):
+        if timed:
+            ev[0].record(stream)
+        for xd, maps, h, w, bufs, out, _ in jobs:
+            api.fh_sparse_encode(xd, maps, h, w, n, tau, buffers=bufs, stream=stream)
+        if timed:
+            ev[1].record(stream)
+        for xd, maps, h, w, bufs, out, (vals, idx) in jobs:
+            api.fh_sparse_decode(bufs.info, vals, idx, maps, h, w, n, out=out, workspace=bufs.workspace, stream=stream)
+        if timed:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t_start) / args.steps
+    ms_e = ms_d = 0.0
+    for _ in range(args.steps):
+        step(timed=True)
+        torch.cuda.synchronize()
+        ms_e += ev[0].elapsed_time(ev[1]) / args.steps
+        ms_d += ev[1].elapsed_time(ev[2]) / args.steps
+    info_bytes = sum(job[4].info.numel() for job in jobs)
+    alg_e = 2 * nbytes + stored + info_bytes                  # two passes over the input, info re-read, streams written
+    alg_d = 2 * info_bytes + stored + nbytes                  # info read twice, streams read, maps written
+    dom = ("encode (count + scan + write)", alg_e, ms_e) if ms_e >= ms_d else ("decode (sums + scan + read)", alg_d, ms_d)
+    result = {
+        "metric": "sparse-block storage of salient-channel maps, encode+decode GB/s of input on 1 MI355X",
+        "value": round(nbytes / elapsed / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "sparse_mobilenetv2_b64_kept_channels_n4_tau0.5", "map_sets": len(jobs),
+                   "input_bytes": nbytes, "stored_bytes": stored, "entry_point": "fh_sparse_encode + fh_sparse_decode",
+                   "window": n, "tau": tau},
+        "roofline": {"bound": "hbm", "kernel": dom[0] + ", all launches of a step, event-timed",
+                     "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},
+        "kernels": {"encode": {"ms": round(ms_e, 4), "bytes": alg_e, "GBps": round(alg_e / ms_e / 1e6, 1)},
+                    "decode": {"ms": round(ms_d, 4), "bytes": alg_d, "GBps": round(alg_d / ms_d / 1e6, 1)}},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        t_cpu, done = 0.0, 0
+        for x, (maps, h, w) in zip(host, layers):
+            t1 = time.perf_counter()
+            info, v, idx, _ = oracle.sparse_encode(x, maps, h, w, n, tau)
+            oracle.sparse_decode(info, v, idx, maps, h, w, n)
+            t_cpu += time.perf_counter() - t1
+            done += x.nbytes
+            if t_cpu > 20.0:
+                break
+        result["cpu_baseline"] = {"value": round(done / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"{done / 2**20:.1f} MiB of the set, whole map sets, {t_cpu:.1f} s"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -211,10 +306,11 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB device copies before the timed region, so that a "
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE against a known size")
-    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed"), default="roundtrip",
+    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed", "sparse"), default="roundtrip",
                     help="roundtrip (default): compress + decompress of the tensor set; classify: the "
                          "channel classification step (moments + outlier counts), measured on its own; "
-                         "mixed: the round trip with salient channels kept raw beside the quantised stream")
+                         "mixed: the round trip with salient channels kept raw beside the quantised stream; "
+                         "sparse: block-wise sparse storage of the kept channels' maps")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()
@@ -243,6 +339,8 @@ def main() -> int:
         return bench_classify(args, api, W, dev)
     if args.op == "mixed":
         return bench_mixed(args, api, W, dev)
+    if args.op == "sparse":
+        return bench_sparse(args, api, W, dev)
 
     w = W.full_config(args.config)
     t0 = time.time()

@@ -8,10 +8,13 @@
 // so the streams are laid out by a prefix sum over tiles -- stream compaction:
 //   pass 1  one thread per tile: count non-zeros, decide sparse / dense, write the tile's info
 //           byte; each workgroup adds up what its 256 tiles will write;
-//   pass 2  one workgroup turns the per-workgroup sums into exclusive offsets (and totals);
-//   pass 3  one thread per tile: offsets inside the workgroup by a scan through LDS, then the
-//           tile's values and CSR structure go to their final place.
-// Restoring runs the same three passes with the info bytes as the only input of pass 1.
+//   pass 2  one thread per tile: the workgroup's base is the sum of the sums before it (each
+//           workgroup adds them up itself while there are few; a scan kernel in between does
+//           it once there are many), offsets inside the workgroup come from a scan through
+//           LDS, then the tile's values and CSR structure go to their final place.
+// Restoring runs the same passes with the info bytes as the only input of pass 1.
+// A thread reads its whole tile with unconditional loads (addresses clamped into the tile) before
+// it looks at any value, so it waits for memory once, not once per element.
 // Everything here is integer and byte work; results do not depend on launch geometry.
 #include "../../include/fedhybrid.h"
 
@@ -22,6 +25,7 @@ namespace {
 
 constexpr int kTileThreads = 256;                  // tiles per workgroup
 constexpr int kScanThreads = 1024;
+constexpr uint32_t kSelfScanLimit = 2048;          // up to this many workgroups each adds up the sums before it
 
 struct Sums {                                      // what a run of tiles writes
     uint64_t values, index_bytes, sparse_tiles;
@@ -69,24 +73,93 @@ template <typename T> __device__ __forceinline__ uint32_t bits_of(T v);
 template <> __device__ __forceinline__ uint32_t bits_of<uint32_t>(uint32_t v) { return v; }
 template <> __device__ __forceinline__ uint32_t bits_of<uint16_t>(uint16_t v) { return v; }
 
-// Sum of `mine` over the workgroup, to thread 0's caller through LDS; every thread gets the
-// exclusive prefix of its own value.
-__device__ __forceinline__ Sums workgroup_exclusive_scan(Sums mine, Sums* lds /* [kTileThreads] */, Sums* total)
+// Workgroup-wide exclusive scan of what each thread's tile writes.  A tile writes at most 127
+// values and 73 index bytes, so a workgroup's running sums fit 20-bit fields of one 64-bit
+// word: lanes scan that word with wave shuffles, and the four wave totals meet in LDS.
+constexpr int kTileWaves = kTileThreads / 64;
+__device__ __forceinline__ uint64_t pack_sums(const Sums& s)
 {
-    const int t = threadIdx.x;
-    lds[t] = mine;
-    __syncthreads();
-    for (int step = 1; step < kTileThreads; step <<= 1) {
-        Sums add = {0, 0, 0};
-        if (t >= step) add = lds[t - step];
-        __syncthreads();
-        lds[t] = lds[t] + add;
-        __syncthreads();
+    return s.values | (s.index_bytes << 20) | (s.sparse_tiles << 40);
+}
+__device__ __forceinline__ Sums unpack_sums(uint64_t p)
+{
+    return Sums{p & 0xfffffu, (p >> 20) & 0xfffffu, p >> 40};
+}
+__device__ __forceinline__ Sums workgroup_exclusive_scan(Sums mine, uint64_t* lds /* [kTileWaves] */, Sums* total)
+{
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint64_t own = pack_sums(mine);
+    uint64_t inc = own;
+#pragma unroll
+    for (int step = 1; step < 64; step <<= 1) {
+        const uint64_t up = __shfl_up(inc, step, 64);
+        if (lane >= (uint32_t)step) inc += up;
     }
-    const Sums inclusive = lds[t];
-    *total = lds[kTileThreads - 1];
-    return Sums{inclusive.values - mine.values, inclusive.index_bytes - mine.index_bytes,
-                inclusive.sparse_tiles - mine.sparse_tiles};
+    if (lane == 63u) lds[wave] = inc;
+    __syncthreads();
+    uint64_t before = 0, all = 0;
+#pragma unroll
+    for (int v = 0; v < kTileWaves; ++v) {
+        const uint64_t t = lds[v];
+        if ((uint32_t)v < wave) before += t;
+        all += t;
+    }
+    __syncthreads();                                          // lds may be reused right away
+    *total = unpack_sums(all);
+    return unpack_sums(before + inc - own);
+}
+
+// Workgroup-wide sum of full-width sums.
+__device__ __forceinline__ Sums workgroup_sum(Sums part, uint64_t* lds /* [3 * kTileWaves] */)
+{
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    uint64_t a = part.values, b = part.index_bytes, c = part.sparse_tiles;
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1) {
+        a += __shfl_xor(a, step, 64);
+        b += __shfl_xor(b, step, 64);
+        c += __shfl_xor(c, step, 64);
+    }
+    if (lane == 0u) { lds[3 * wave] = a; lds[3 * wave + 1] = b; lds[3 * wave + 2] = c; }
+    __syncthreads();
+    Sums total = {0, 0, 0};
+#pragma unroll
+    for (int v = 0; v < kTileWaves; ++v) total = total + Sums{lds[3 * v], lds[3 * v + 1], lds[3 * v + 2]};
+    __syncthreads();
+    return total;
+}
+
+// The tile's elements, row-major, zeros where the tile has no element.  Every load is
+// unconditional -- out-of-tile positions read a clamped in-tile address -- so all N*N loads
+// are in flight together.
+template <typename Bits, int N>
+__device__ __forceinline__ void load_tile(const Bits* x, const TilePos& t, uint32_t w, Bits (&e)[N][N])
+{
+#pragma unroll
+    for (int r = 0; r < N; ++r) {
+        const uint32_t rr = r < (int)t.rows ? r : t.rows - 1;
+#pragma unroll
+        for (int c = 0; c < N; ++c) {
+            const uint32_t cc = c < (int)t.cols ? c : t.cols - 1;
+            e[r][c] = x[(uint64_t)rr * w + cc];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+#pragma unroll
+        for (int c = 0; c < N; ++c)
+            if (!(r < (int)t.rows && c < (int)t.cols)) e[r][c] = (Bits)0;
+}
+
+// What the tiles of all earlier workgroups write.  `scanned`: wg[] already holds exclusive
+// prefixes (the scan kernel ran); otherwise it holds per-workgroup sums and they are added up
+// here, 256 at a time.
+__device__ __forceinline__ Sums workgroup_base(const Sums* __restrict__ wg, bool scanned, uint64_t* lds)
+{
+    if (scanned) return wg[blockIdx.x];
+    Sums part = {0, 0, 0};
+    for (uint32_t i = threadIdx.x; i < blockIdx.x; i += kTileThreads) part = part + wg[i];
+    return workgroup_sum(part, lds);
 }
 
 // ---- pass 1 (encode): non-zero count, density, info byte, workgroup sums ---------------------
@@ -95,18 +168,18 @@ __global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const MapSha
                                                                     uint8_t* __restrict__ info,
                                                                     Sums* __restrict__ wg_sums)
 {
-    __shared__ Sums lds[kTileThreads];
+    __shared__ uint64_t lds[3 * kTileWaves];
     const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
     Sums mine = {0, 0, 0};
     if (b < s.tiles) {
         const TilePos t = tile_pos(s, b);
-        const Bits* x = static_cast<const Bits*>(s.x) + t.origin;
+        Bits e[N][N];
+        load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, e);
         uint32_t nnz = 0;
 #pragma unroll
         for (int r = 0; r < N; ++r)
 #pragma unroll
-            for (int c = 0; c < N; ++c)
-                if (r < (int)t.rows && c < (int)t.cols) nnz += bits_of<Bits>(x[(uint64_t)r * s.w + c]) != 0u ? 1u : 0u;
+            for (int c = 0; c < N; ++c) nnz += bits_of<Bits>(e[r][c]) != 0u ? 1u : 0u;   // padding is zero
         const uint32_t area = t.rows * t.cols;
         const float density = (float)nnz / (float)area;       // IEEE division: average pooling of the mask
         const uint32_t byte = density <= tau ? nnz : (0x80u | area);
@@ -122,7 +195,7 @@ __global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const MapSha
 __global__ __launch_bounds__(kTileThreads) void sparse_sums_kernel(const MapShape s, const uint8_t* __restrict__ info,
                                                                    Sums* __restrict__ wg_sums)
 {
-    __shared__ Sums lds[kTileThreads];
+    __shared__ uint64_t lds[3 * kTileWaves];
     const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
     Sums mine = {0, 0, 0};
     if (b < s.tiles) mine = tile_sums(info[b], tile_pos(s, b).rows);
@@ -170,56 +243,58 @@ __global__ __launch_bounds__(kScanThreads) void sparse_scan_kernel(Sums* __restr
 // ---- pass 3 (encode): values and CSR structure to their place ---------------------------------------
 template <typename Bits, int N>
 __global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapShape s, const uint8_t* __restrict__ info,
-                                                                    const Sums* __restrict__ wg_base,
+                                                                    const Sums* __restrict__ wg, const bool scanned,
                                                                     Bits* __restrict__ values,
-                                                                    uint8_t* __restrict__ indices)
+                                                                    uint8_t* __restrict__ indices,
+                                                                    uint64_t* __restrict__ totals)
 {
-    __shared__ Sums lds[kTileThreads];
+    __shared__ uint64_t lds[3 * kTileWaves];
     const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
     const bool live = b < s.tiles;
-    TilePos t = {0, 0, 0};
+    TilePos t = {0, 1, 1};
     uint32_t byte = 0x80u;
     Sums mine = {0, 0, 0};
+    Bits e[N][N];
     if (live) {
         t = tile_pos(s, b);
         byte = info[b];
         mine = tile_sums(byte, t.rows);
+        load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, e);
     }
+    const Sums base = workgroup_base(wg, scanned, lds);
     Sums total;
     const Sums before = workgroup_exclusive_scan(mine, lds, &total);
+    if (!scanned && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        totals[0] = base.values + total.values;
+        totals[1] = base.index_bytes + total.index_bytes;
+        totals[2] = base.sparse_tiles + total.sparse_tiles;
+        totals[3] = (uint64_t)s.tiles - totals[2];
+    }
     if (!live) return;
-    const Sums base = wg_base[blockIdx.x];
-    const Bits* x = static_cast<const Bits*>(s.x) + t.origin;
     Bits* v = values + base.values + before.values;
     if (byte & 0x80u) {                                       // dense: the tile, row-major
-        uint32_t k = 0;
 #pragma unroll
         for (int r = 0; r < N; ++r)
 #pragma unroll
             for (int c = 0; c < N; ++c)
-                if (r < (int)t.rows && c < (int)t.cols) v[k++] = x[(uint64_t)r * s.w + c];
+                if (r < (int)t.rows && c < (int)t.cols) v[r * t.cols + c] = e[r][c];
     } else {                                                  // sparse: row_ptr, then columns; values alongside
         uint8_t* row_ptr = indices + base.index_bytes + before.index_bytes;
         uint8_t* col = row_ptr + t.rows + 1;
         uint32_t k = 0;
 #pragma unroll
         for (int r = 0; r < N; ++r) {
-            if (r < (int)t.rows) {
-                row_ptr[r] = (uint8_t)k;
+            if (r <= (int)t.rows) row_ptr[r] = (uint8_t)k;    // r == rows: the closing entry
 #pragma unroll
-                for (int c = 0; c < N; ++c) {
-                    if (c < (int)t.cols) {
-                        const Bits e = x[(uint64_t)r * s.w + c];
-                        if (bits_of<Bits>(e) != 0u) {
-                            v[k] = e;
-                            col[k] = (uint8_t)c;
-                            ++k;
-                        }
-                    }
+            for (int c = 0; c < N; ++c) {
+                if (bits_of<Bits>(e[r][c]) != 0u) {           // padding is zero, so it never gets here
+                    v[k] = e[r][c];
+                    col[k] = (uint8_t)c;
+                    ++k;
                 }
             }
         }
-        row_ptr[t.rows] = (uint8_t)k;
+        if ((int)t.rows == N) row_ptr[N] = (uint8_t)k;
     }
 }
 
@@ -228,15 +303,15 @@ __global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapSha
 // a tile whose slice would leave a stream is zero-filled, entries outside the tile are dropped.
 template <typename Bits, int N>
 __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShape s, const uint8_t* __restrict__ info,
-                                                                   const Sums* __restrict__ wg_base,
+                                                                   const Sums* __restrict__ wg, const bool scanned,
                                                                    const Bits* __restrict__ values, uint64_t value_count,
                                                                    const uint8_t* __restrict__ indices,
                                                                    uint64_t index_count)
 {
-    __shared__ Sums lds[kTileThreads];
+    __shared__ uint64_t lds[3 * kTileWaves];
     const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
     const bool live = b < s.tiles;
-    TilePos t = {0, 0, 0};
+    TilePos t = {0, 1, 1};
     uint32_t byte = 0x80u;
     Sums mine = {0, 0, 0};
     if (live) {
@@ -244,22 +319,29 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
         byte = info[b];
         mine = tile_sums(byte, t.rows);
     }
+    const Sums base = workgroup_base(wg, scanned, lds);
     Sums total;
     const Sums before = workgroup_exclusive_scan(mine, lds, &total);
     if (!live) return;
-    const Sums base = wg_base[blockIdx.x];
     Bits* out = static_cast<Bits*>(const_cast<void*>(s.x)) + t.origin;
     const uint64_t v0 = base.values + before.values, i0 = base.index_bytes + before.index_bytes;
     const uint32_t count = byte & 0x7fu;
     const bool in_bounds = v0 + mine.values <= value_count && i0 + mine.index_bytes <= index_count;
     const Bits* v = values + v0;
     if ((byte & 0x80u) && in_bounds && count == t.rows * t.cols) {
-        uint32_t k = 0;
+        Bits e[N][N];                                         // all loads first (clamped), then the stores
+#pragma unroll
+        for (int r = 0; r < N; ++r)
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                const uint32_t rr = r < (int)t.rows ? r : t.rows - 1, cc = c < (int)t.cols ? c : t.cols - 1;
+                e[r][c] = v[rr * t.cols + cc];
+            }
 #pragma unroll
         for (int r = 0; r < N; ++r)
 #pragma unroll
             for (int c = 0; c < N; ++c)
-                if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = v[k++];
+                if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = e[r][c];
         return;
     }
 #pragma unroll
@@ -267,15 +349,30 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
 #pragma unroll
         for (int c = 0; c < N; ++c)
             if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = (Bits)0;
-    if ((byte & 0x80u) || !in_bounds) return;
+    if ((byte & 0x80u) || !in_bounds || count == 0u) return;
     const uint8_t* row_ptr = indices + i0;
     const uint8_t* col = row_ptr + t.rows + 1;
-    for (uint32_t r = 0; r < t.rows; ++r) {
-        uint32_t k = row_ptr[r], end = row_ptr[r + 1];
-        if (end > count) end = count;
-        for (; k < end; ++k) {
-            const uint32_t c = col[k];
-            if (c < t.cols) out[(uint64_t)r * s.w + c] = v[k];
+    uint32_t rp[N + 1];                                       // row_ptr[1..rows], clamped reads
+#pragma unroll
+    for (int r = 1; r <= N; ++r) rp[r] = row_ptr[r <= (int)t.rows ? r : t.rows];
+    // entries in chunks of 8, each chunk's loads issued together; the row of entry k is the
+    // number of rows that end at or before k
+    for (uint32_t k0 = 0; k0 < count; k0 += 8) {
+        uint32_t cc[8];
+        Bits vv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t k = k0 + j < count ? k0 + j : count - 1;
+            cc[j] = col[k];
+            vv[j] = v[k];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t k = k0 + j;
+            uint32_t r = 0;
+#pragma unroll
+            for (int q = 1; q <= N; ++q) r += (q <= (int)t.rows && rp[q] <= k) ? 1u : 0u;
+            if (k < count && r < t.rows && cc[j] < t.cols) out[(uint64_t)r * s.w + cc[j]] = vv[j];
         }
     }
 }
@@ -372,13 +469,15 @@ fh_status fh_sparse_encode(const void* x, fh_dtype dtype, int64_t maps, int64_t 
     const dim3 grid(workgroups(tiles)), block(kTileThreads);
     uint8_t* inf = static_cast<uint8_t*>(info);
     uint8_t* idx = static_cast<uint8_t*>(indices);
+    const bool scan = grid.x > kSelfScanLimit;
 #define FH_SPARSE_ENCODE(BITS, NN)                                                                              \
     do {                                                                                                        \
         hipLaunchKernelGGL((sparse_count_kernel<BITS, NN>), grid, block, 0, s, shape, tau, inf, wg);            \
-        hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, grid.x, (uint32_t)tiles,  \
-                           static_cast<uint64_t*>(totals));                                                     \
-        hipLaunchKernelGGL((sparse_write_kernel<BITS, NN>), grid, block, 0, s, shape, inf, wg,                  \
-                           static_cast<BITS*>(values), idx);                                                    \
+        if (scan)                                                                                               \
+            hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, grid.x,               \
+                               (uint32_t)tiles, static_cast<uint64_t*>(totals));                                \
+        hipLaunchKernelGGL((sparse_write_kernel<BITS, NN>), grid, block, 0, s, shape, inf, wg, scan,            \
+                           static_cast<BITS*>(values), idx, static_cast<uint64_t*>(totals));                    \
     } while (0)
     if (dtype == FH_F32) {
         if (n == 2) FH_SPARSE_ENCODE(uint32_t, 2); else if (n == 4) FH_SPARSE_ENCODE(uint32_t, 4); else FH_SPARSE_ENCODE(uint32_t, 8);
@@ -413,11 +512,13 @@ fh_status fh_sparse_decode(const void* info, const void* values, size_t values_b
     const uint8_t* inf = static_cast<const uint8_t*>(info);
     const uint8_t* idx = static_cast<const uint8_t*>(indices);
     const uint64_t nvals = values_bytes / elem_size(dtype);
+    const bool scan = grid.x > kSelfScanLimit;
     hipLaunchKernelGGL(sparse_sums_kernel, grid, block, 0, s, shape, inf, wg);
-    hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, grid.x, (uint32_t)tiles,
-                       static_cast<uint64_t*>(nullptr));
+    if (scan)
+        hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, grid.x, (uint32_t)tiles,
+                           static_cast<uint64_t*>(nullptr));
 #define FH_SPARSE_DECODE(BITS, NN)                                                                        \
-    hipLaunchKernelGGL((sparse_read_kernel<BITS, NN>), grid, block, 0, s, shape, inf, wg,                 \
+    hipLaunchKernelGGL((sparse_read_kernel<BITS, NN>), grid, block, 0, s, shape, inf, wg, scan,           \
                        static_cast<const BITS*>(values), nvals, idx, (uint64_t)indices_bytes)
     if (dtype == FH_F32) {
         if (n == 2) FH_SPARSE_DECODE(uint32_t, 2); else if (n == 4) FH_SPARSE_DECODE(uint32_t, 4); else FH_SPARSE_DECODE(uint32_t, 8);
