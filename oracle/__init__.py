@@ -84,11 +84,12 @@ def lib() -> ctypes.CDLL:
         L.fho_sparse_blocks.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
         L.fho_sparse_blocks.restype = ctypes.c_int64
         L.fho_sparse_encode.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
-                                        ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_int, ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_void_p]
         L.fho_sparse_encode.restype = ctypes.c_int
         L.fho_sparse_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
-                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_float,
+                                        ctypes.c_void_p]
         L.fho_sparse_decode.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -236,9 +237,10 @@ def sparse_blocks(maps: int, h: int, w: int, n: int) -> int:
     return int(lib().fho_sparse_blocks(maps, h, w, n))
 
 
-def sparse_encode(x: np.ndarray, maps: int, h: int, w: int, n: int, tau: float, dtype="f32"):
+def sparse_encode(x: np.ndarray, maps: int, h: int, w: int, n: int, tau: float, dtype="f32", eps: float = 0.0):
     """-> (info uint8[blocks], values (trimmed to what was written), indices uint8 (trimmed),
-    totals uint64[4] = {values, index bytes, sparse blocks, dense blocks})."""
+    totals uint64[4] = {values, index bytes, sparse blocks, dense blocks}).  eps > 0 stores
+    dense blocks by Lorenzo prediction within that error bound."""
     d = _check_input(x, dtype)
     if x.size != maps * h * w:
         raise ValueError("x.size != maps * h * w")
@@ -249,22 +251,22 @@ def sparse_encode(x: np.ndarray, maps: int, h: int, w: int, n: int, tau: float, 
     values = np.zeros(max(1, x.size), dtype=x.dtype)
     indices = np.zeros(max(1, nb * (n + 1) + x.size), dtype=np.uint8)
     totals = np.zeros(4, dtype=np.uint64)
-    rc = lib().fho_sparse_encode(x.ctypes.data, d, maps, h, w, n, float(tau), info.ctypes.data, values.ctypes.data,
-                                 indices.ctypes.data, totals.ctypes.data)
+    rc = lib().fho_sparse_encode(x.ctypes.data, d, maps, h, w, n, float(tau), float(eps), info.ctypes.data,
+                                 values.ctypes.data, indices.ctypes.data, totals.ctypes.data)
     if rc != 0:
         raise ValueError("fho_sparse_encode rejected its arguments")
     return info, values[:int(totals[0])].copy(), indices[:int(totals[1])].copy(), totals
 
 
 def sparse_decode(info: np.ndarray, values: np.ndarray, indices: np.ndarray, maps: int, h: int, w: int, n: int,
-                  dtype="f32") -> np.ndarray:
+                  dtype="f32", eps: float = 0.0) -> np.ndarray:
     d = _DTYPES[dtype]
     out = np.empty(maps * h * w, dtype=np.float32 if d == F32 else np.uint16)
     info = np.ascontiguousarray(info, dtype=np.uint8)
     values = np.ascontiguousarray(np.concatenate([values, np.zeros(1, values.dtype)]))
     indices = np.ascontiguousarray(np.concatenate([indices.astype(np.uint8), np.zeros(1, np.uint8)]))
     rc = lib().fho_sparse_decode(info.ctypes.data, values.ctypes.data, indices.ctypes.data, d, maps, h, w, n,
-                                 out.ctypes.data)
+                                 float(eps), out.ctypes.data)
     if rc != 0:
         raise ValueError(f"fho_sparse_decode failed ({rc})")
     return out

@@ -100,13 +100,15 @@ int64_t fho_sparse_blocks(int64_t maps, int64_t h, int64_t w, int n);
 
 /* x: [maps][h][w] elements of dtype.  info: one byte per block.  values: room for maps*h*w
  * elements.  indices: room for blocks*(n+1) + maps*h*w bytes.  totals = {values written, index
- * bytes written, sparse blocks, dense blocks}.  Returns 0, or -1 on a bad argument. */
-int fho_sparse_encode(const void *x, int dtype, int64_t maps, int64_t h, int64_t w, int n, float tau,
+ * bytes written, sparse blocks, dense blocks}.  eps > 0: dense blocks are stored by Lorenzo
+ * prediction with error bound eps (outliers intact) instead of verbatim.  Returns 0, or -1 on
+ * a bad argument. */
+int fho_sparse_encode(const void *x, int dtype, int64_t maps, int64_t h, int64_t w, int n, float tau, float eps,
                       uint8_t *info, void *values, uint8_t *indices, uint64_t totals[4]);
 
 /* out: [maps][h][w].  Returns 0, -1 on a bad argument, -2 on an inconsistent stream. */
 int fho_sparse_decode(const uint8_t *info, const void *values, const uint8_t *indices, int dtype,
-                      int64_t maps, int64_t h, int64_t w, int n, void *out);
+                      int64_t maps, int64_t h, int64_t w, int n, float eps, void *out);
 
 #ifdef __cplusplus
 }
