@@ -220,7 +220,18 @@ fh_status fh_decompress_mixed(const void *packed, const void *meta, const void *
  *   - indices: one byte stream in block order -- per sparse block row_ptr[0..rows] (non-zeros in
  *     the block's rows before r) followed by the column inside the block of each non-zero;
  *   - totals: uint64[4] = {values written, index bytes written, sparse blocks, dense blocks};
- *   - decoding restores the input bit for bit.
+ *   - decoding restores the input bit for bit;
+ *   - with eps > 0 (the same value on both calls) dense blocks take the section's predictive
+ *     form instead of the verbatim one: on the lattice q = rint(x / (2 eps)) (binary32 division;
+ *     an element with |x / (2 eps)| >= 2^22, NaN or infinite has no lattice point and counts as
+ *     0) each element is predicted by first-order Lorenzo inside its block,
+ *     p = q(left) + q(up) - q(up-left) with zeros outside the block; an element with a lattice
+ *     point and |q - p| < 128 becomes the code byte q - p + 128, any other element is an
+ *     outlier: code byte 0 and its original bits in the value stream.  info = 0x80 | outliers,
+ *     the index stream gets the block's code bytes row-major.  Restoring returns outliers
+ *     unchanged and (float)q * (2 eps) otherwise (rounded to bf16 for bf16 maps), i.e. within
+ *     eps of the input up to two roundings.  eps <= 0 or NaN means verbatim.  The Huffman stage
+ *     the paper puts after this is not part of the library.
  *
  * All pointers are device pointers; x, values, out 4-byte aligned, totals and workspace 8-byte
  * aligned.  Stream sizes depend on the data, so the encoder wants room for the worst case:
@@ -233,12 +244,12 @@ size_t    fh_sparse_info_bytes(int64_t maps, int64_t h, int64_t w, int32_t n);
 size_t    fh_sparse_index_bytes(int64_t maps, int64_t h, int64_t w, int32_t n);
 size_t    fh_sparse_workspace_bytes(int64_t maps, int64_t h, int64_t w, int32_t n);
 fh_status fh_sparse_encode(const void *x, fh_dtype dtype, int64_t maps, int64_t h, int64_t w, int32_t n, float tau,
-                           void *info, size_t info_cap, void *values, size_t values_cap,
+                           float eps, void *info, size_t info_cap, void *values, size_t values_cap,
                            void *indices, size_t indices_cap, void *totals,
                            void *workspace, size_t workspace_cap, void *stream);
 fh_status fh_sparse_decode(const void *info, const void *values, size_t values_bytes,
                            const void *indices, size_t indices_bytes, fh_dtype dtype,
-                           int64_t maps, int64_t h, int64_t w, int32_t n,
+                           int64_t maps, int64_t h, int64_t w, int32_t n, float eps,
                            void *out, size_t out_cap, void *workspace, size_t workspace_cap, void *stream);
 
 const char *fh_status_string(fh_status s);

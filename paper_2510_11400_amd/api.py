@@ -92,12 +92,13 @@ for _name in ("fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_worksp
     getattr(_lib, _name).argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
     getattr(_lib, _name).restype = ctypes.c_size_t
 _lib.fh_sparse_encode.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
-                                  ctypes.c_int32, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t,
+                                  ctypes.c_int32, ctypes.c_float, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t,
                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fh_sparse_encode.restype = ctypes.c_int
 _lib.fh_sparse_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
                                   ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                  ctypes.c_float,
                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fh_sparse_decode.restype = ctypes.c_int
 _lib.fh_batch_capacity.argtypes = []
@@ -440,8 +441,9 @@ def alloc_sparse(maps: int, h: int, w: int, n: int, dtype, device) -> SparseBuff
 
 
 def fh_sparse_encode(x: torch.Tensor, maps: int, h: int, w: int, n: int, tau: float,
-                     buffers: Optional[SparseBuffers] = None, stream=None) -> SparseBuffers:
-    """Enqueue the block-wise sparse storage of `x` viewed as [maps][h][w]."""
+                     buffers: Optional[SparseBuffers] = None, stream=None, eps: float = 0.0) -> SparseBuffers:
+    """Enqueue the block-wise sparse storage of `x` viewed as [maps][h][w]; eps > 0 stores dense
+    blocks by Lorenzo prediction within that error bound instead of verbatim."""
     _device_tensor(x, "x")
     if x.numel() != maps * h * w:
         raise ValueError("x.numel() != maps * h * w")
@@ -452,7 +454,7 @@ def fh_sparse_encode(x: torch.Tensor, maps: int, h: int, w: int, n: int, tau: fl
     if b.values.dtype != x.dtype or _nbytes(b.totals) < 32:
         raise FedHybridError(7)
     with torch.cuda.device(x.device):
-        _check(_lib.fh_sparse_encode(_ptr(x), _dtype_code(x), maps, h, w, int(n), float(tau),
+        _check(_lib.fh_sparse_encode(_ptr(x), _dtype_code(x), maps, h, w, int(n), float(tau), float(eps),
                                      b.info.data_ptr(), _nbytes(b.info), b.values.data_ptr(), _nbytes(b.values),
                                      b.indices.data_ptr(), _nbytes(b.indices), b.totals.data_ptr(),
                                      b.workspace.data_ptr(), _nbytes(b.workspace), _stream_ptr(stream)))
@@ -461,7 +463,7 @@ def fh_sparse_encode(x: torch.Tensor, maps: int, h: int, w: int, n: int, tau: fl
 
 def fh_sparse_decode(info: torch.Tensor, values: torch.Tensor, indices: torch.Tensor, maps: int, h: int, w: int,
                      n: int, out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                     stream=None) -> torch.Tensor:
+                     stream=None, eps: float = 0.0) -> torch.Tensor:
     """Enqueue the inverse; `values` and `indices` are the valid prefixes of the two streams
     (their sizes bound what the kernel reads).  Returns the flat [maps][h][w] tensor."""
     for t, what in ((info, "info"), (values, "values"), (indices, "indices")):
@@ -476,6 +478,6 @@ def fh_sparse_decode(info: torch.Tensor, values: torch.Tensor, indices: torch.Te
         raise FedHybridError(7)
     with torch.cuda.device(info.device):
         _check(_lib.fh_sparse_decode(_ptr(info), _ptr(values), _nbytes(values), _ptr(indices), _nbytes(indices),
-                                     _dtype_code(out), maps, h, w, int(n), _ptr(out), _nbytes(out),
+                                     _dtype_code(out), maps, h, w, int(n), float(eps), _ptr(out), _nbytes(out),
                                      workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)))
     return out

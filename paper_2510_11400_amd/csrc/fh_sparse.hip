@@ -15,7 +15,12 @@
 // Restoring runs the same passes with the info bytes as the only input of pass 1.
 // A thread reads its whole tile with unconditional loads (addresses clamped into the tile) before
 // it looks at any value, so it waits for memory once, not once per element.
-// Everything here is integer and byte work; results do not depend on launch geometry.
+// With an error bound, dense blocks are stored by first-order Lorenzo prediction on the lattice
+// of step 2*eps (same section: prediction from decompressed neighbours, errors within the bound
+// quantised to a byte, outliers kept intact) instead of verbatim; a thread runs the recurrence
+// of its block in registers.
+// Apart from one division and one multiplication per element in that mode, everything here is
+// integer and byte work; results do not depend on launch geometry.
 #include "../../include/fedhybrid.h"
 
 #include "fh_channels.hpp"
@@ -41,6 +46,7 @@ struct MapShape {
     uint32_t tiles;            // maps * BH * BW
     ExactDiv bw, bh;           // tile index -> (map, tile row, tile column)
     uint32_t BW, BH;
+    float two_eps;             // lattice step of the predictive form of dense tiles; 0 = verbatim
 };
 
 struct TilePos {
@@ -62,16 +68,58 @@ __device__ __forceinline__ TilePos tile_pos(const MapShape& s, uint32_t b)
 }
 
 // what a tile with this info byte adds to the streams
-__device__ __forceinline__ Sums tile_sums(uint32_t info, uint32_t rows)
+__device__ __forceinline__ Sums tile_sums(uint32_t info, const TilePos& t, bool predictive)
 {
-    const uint32_t count = info & 0x7fu;
-    const bool dense = info & 0x80u;
-    return Sums{count, dense ? 0u : rows + 1u + count, dense ? 0u : 1u};
+    const uint32_t count = info & 0x7fu;                      // non-zeros | elements | outliers
+    if (info & 0x80u) return Sums{count, predictive ? t.rows * t.cols : 0u, 0u};
+    return Sums{count, t.rows + 1u + count, 1u};
 }
 
 template <typename T> __device__ __forceinline__ uint32_t bits_of(T v);
 template <> __device__ __forceinline__ uint32_t bits_of<uint32_t>(uint32_t v) { return v; }
 template <> __device__ __forceinline__ uint32_t bits_of<uint16_t>(uint16_t v) { return v; }
+
+// ---- the predictive form of a dense tile -----------------------------------------------------
+template <typename Bits> __device__ __forceinline__ float value_of(Bits b);
+template <> __device__ __forceinline__ float value_of<uint32_t>(uint32_t b) { return __builtin_bit_cast(float, b); }
+template <> __device__ __forceinline__ float value_of<uint16_t>(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
+template <typename Bits> __device__ __forceinline__ Bits stored_of(float f);
+template <> __device__ __forceinline__ uint32_t stored_of<uint32_t>(float f) { return __builtin_bit_cast(uint32_t, f); }
+template <> __device__ __forceinline__ uint16_t stored_of<uint16_t>(float f) { return (uint16_t)bf16_bits(f); }
+
+// the lattice point of x (0 when it has none) and whether it has one
+__device__ __forceinline__ int32_t lattice(float x, float two_eps, bool& ok)
+{
+    const float t = x / two_eps;                              // IEEE division
+    ok = __builtin_fabsf(t) < 0x1p22f;                        // false for NaN and infinities
+    return ok ? (int32_t)__builtin_rintf(t) : 0;
+}
+
+// Code bytes of a tile (0 = outlier) and the number of outliers; elements outside the tile
+// (zero padding) are never counted.  q(r,c) is predicted by q(r,c-1) + q(r-1,c) - q(r-1,c-1)
+// with zeros outside the tile.
+template <typename Bits, int N>
+__device__ __forceinline__ uint32_t lorenzo_codes(const Bits (&e)[N][N], const TilePos& t, float two_eps,
+                                                  uint8_t (&code)[N][N])
+{
+    int32_t q[N][N];
+    uint32_t outliers = 0;
+#pragma unroll
+    for (int r = 0; r < N; ++r) {
+#pragma unroll
+        for (int c = 0; c < N; ++c) {
+            bool ok;
+            q[r][c] = lattice(value_of<Bits>(e[r][c]), two_eps, ok);
+            const int32_t left = c > 0 ? q[r][c - 1] : 0, up = r > 0 ? q[r - 1][c] : 0;
+            const int32_t diag = (r > 0 && c > 0) ? q[r - 1][c - 1] : 0;
+            const int32_t d = q[r][c] - (left + up - diag);
+            const bool coded = ok && d > -128 && d < 128;
+            code[r][c] = coded ? (uint8_t)(d + 128) : (uint8_t)0;
+            if (!coded && r < (int)t.rows && c < (int)t.cols) ++outliers;
+        }
+    }
+    return outliers;
+}
 
 // Workgroup-wide exclusive scan of what each thread's tile writes.  A tile writes at most 127
 // values and 73 index bytes, so a workgroup's running sums fit 20-bit fields of one 64-bit
@@ -182,9 +230,13 @@ __global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const MapSha
             for (int c = 0; c < N; ++c) nnz += bits_of<Bits>(e[r][c]) != 0u ? 1u : 0u;   // padding is zero
         const uint32_t area = t.rows * t.cols;
         const float density = (float)nnz / (float)area;       // IEEE division: average pooling of the mask
-        const uint32_t byte = density <= tau ? nnz : (0x80u | area);
+        uint32_t byte = density <= tau ? nnz : (0x80u | area);
+        if ((byte & 0x80u) && s.two_eps > 0.0f) {             // dense, within the error bound: count the outliers
+            uint8_t code[N][N];
+            byte = 0x80u | lorenzo_codes<Bits, N>(e, t, s.two_eps, code);
+        }
         info[b] = (uint8_t)byte;
-        mine = tile_sums(byte, t.rows);
+        mine = tile_sums(byte, t, s.two_eps > 0.0f);
     }
     Sums total;
     workgroup_exclusive_scan(mine, lds, &total);
@@ -198,7 +250,7 @@ __global__ __launch_bounds__(kTileThreads) void sparse_sums_kernel(const MapShap
     __shared__ uint64_t lds[3 * kTileWaves];
     const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
     Sums mine = {0, 0, 0};
-    if (b < s.tiles) mine = tile_sums(info[b], tile_pos(s, b).rows);
+    if (b < s.tiles) mine = tile_sums(info[b], tile_pos(s, b), s.two_eps > 0.0f);
     Sums total;
     workgroup_exclusive_scan(mine, lds, &total);
     if (threadIdx.x == 0) wg_sums[blockIdx.x] = total;
@@ -258,7 +310,7 @@ __global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapSha
     if (live) {
         t = tile_pos(s, b);
         byte = info[b];
-        mine = tile_sums(byte, t.rows);
+        mine = tile_sums(byte, t, s.two_eps > 0.0f);
         load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, e);
     }
     const Sums base = workgroup_base(wg, scanned, lds);
@@ -272,7 +324,20 @@ __global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapSha
     }
     if (!live) return;
     Bits* v = values + base.values + before.values;
-    if (byte & 0x80u) {                                       // dense: the tile, row-major
+    if ((byte & 0x80u) && s.two_eps > 0.0f) {                 // dense, predictive: code bytes + outliers
+        uint8_t code[N][N];
+        lorenzo_codes<Bits, N>(e, t, s.two_eps, code);
+        uint8_t* codes = indices + base.index_bytes + before.index_bytes;
+        uint32_t k = 0;
+#pragma unroll
+        for (int r = 0; r < N; ++r)
+#pragma unroll
+            for (int c = 0; c < N; ++c)
+                if (r < (int)t.rows && c < (int)t.cols) {
+                    codes[r * t.cols + c] = code[r][c];
+                    if (code[r][c] == 0) v[k++] = e[r][c];
+                }
+    } else if (byte & 0x80u) {                                // dense: the tile, row-major
 #pragma unroll
         for (int r = 0; r < N; ++r)
 #pragma unroll
@@ -317,7 +382,7 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
     if (live) {
         t = tile_pos(s, b);
         byte = info[b];
-        mine = tile_sums(byte, t.rows);
+        mine = tile_sums(byte, t, s.two_eps > 0.0f);
     }
     const Sums base = workgroup_base(wg, scanned, lds);
     Sums total;
@@ -328,6 +393,50 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
     const uint32_t count = byte & 0x7fu;
     const bool in_bounds = v0 + mine.values <= value_count && i0 + mine.index_bytes <= index_count;
     const Bits* v = values + v0;
+    if ((byte & 0x80u) && s.two_eps > 0.0f) {                 // dense, predictive
+        if (!in_bounds) {
+#pragma unroll
+            for (int r = 0; r < N; ++r)
+#pragma unroll
+                for (int c = 0; c < N; ++c)
+                    if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = (Bits)0;
+            return;
+        }
+        const uint8_t* codes = indices + i0;
+        uint8_t code[N][N];                                   // all code bytes first (clamped addresses)
+#pragma unroll
+        for (int r = 0; r < N; ++r)
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                const uint32_t rr = r < (int)t.rows ? r : t.rows - 1, cc = c < (int)t.cols ? c : t.cols - 1;
+                code[r][c] = codes[rr * t.cols + cc];
+            }
+        int32_t q[N][N];
+        uint32_t used = 0;
+#pragma unroll
+        for (int r = 0; r < N; ++r) {
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                const int32_t left = c > 0 ? q[r][c - 1] : 0, up = r > 0 ? q[r - 1][c] : 0;
+                const int32_t diag = (r > 0 && c > 0) ? q[r - 1][c - 1] : 0;
+                q[r][c] = 0;
+                if (r < (int)t.rows && c < (int)t.cols) {
+                    Bits restored;
+                    if (code[r][c] == 0) {                    // an outlier: unchanged, and back on the lattice
+                        restored = used < count ? v[used] : (Bits)0;
+                        ++used;
+                        bool ok;
+                        q[r][c] = lattice(value_of<Bits>(restored), s.two_eps, ok);
+                    } else {
+                        q[r][c] = left + up - diag + ((int32_t)code[r][c] - 128);
+                        restored = stored_of<Bits>((float)q[r][c] * s.two_eps);
+                    }
+                    out[(uint64_t)r * s.w + c] = restored;
+                }
+            }
+        }
+        return;
+    }
     if ((byte & 0x80u) && in_bounds && count == t.rows * t.cols) {
         Bits e[N][N];                                         // all loads first (clamped), then the stores
 #pragma unroll
@@ -394,10 +503,11 @@ int64_t tile_count(int64_t maps, int64_t h, int64_t w, int64_t n)
 
 uint32_t workgroups(int64_t tiles) { return (uint32_t)((tiles + kTileThreads - 1) / kTileThreads); }
 
-MapShape make_shape(const void* x, int64_t h, int64_t w, int n, int64_t tiles)
+MapShape make_shape(const void* x, int64_t h, int64_t w, int n, int64_t tiles, float eps)
 {
     MapShape s;
     s.x = x;
+    s.two_eps = eps > 0.0f ? eps + eps : 0.0f;                // also 0 for NaN
     s.h = (uint32_t)h; s.w = (uint32_t)w; s.n = (uint32_t)n;
     s.tiles = (uint32_t)tiles;
     s.BH = (uint32_t)((h + n - 1) / n);
@@ -440,7 +550,7 @@ size_t fh_sparse_workspace_bytes(int64_t maps, int64_t h, int64_t w, int32_t n)
 }
 
 fh_status fh_sparse_encode(const void* x, fh_dtype dtype, int64_t maps, int64_t h, int64_t w, int32_t n, float tau,
-                           void* info, size_t info_cap, void* values, size_t values_cap,
+                           float eps, void* info, size_t info_cap, void* values, size_t values_cap,
                            void* indices, size_t indices_cap, void* totals,
                            void* workspace, size_t workspace_cap, void* stream)
 {
@@ -465,7 +575,7 @@ fh_status fh_sparse_encode(const void* x, fh_dtype dtype, int64_t maps, int64_t 
         indices_cap < fh_sparse_index_bytes(maps, h, w, n))
         return FH_ERR_BUFFER_TOO_SMALL;
 
-    const MapShape shape = make_shape(x, h, w, n, tiles);
+    const MapShape shape = make_shape(x, h, w, n, tiles, eps);
     const dim3 grid(workgroups(tiles)), block(kTileThreads);
     uint8_t* inf = static_cast<uint8_t*>(info);
     uint8_t* idx = static_cast<uint8_t*>(indices);
@@ -490,7 +600,7 @@ fh_status fh_sparse_encode(const void* x, fh_dtype dtype, int64_t maps, int64_t 
 
 fh_status fh_sparse_decode(const void* info, const void* values, size_t values_bytes,
                            const void* indices, size_t indices_bytes, fh_dtype dtype,
-                           int64_t maps, int64_t h, int64_t w, int32_t n,
+                           int64_t maps, int64_t h, int64_t w, int32_t n, float eps,
                            void* out, size_t out_cap, void* workspace, size_t workspace_cap, void* stream)
 {
     using namespace fh;
@@ -507,7 +617,7 @@ fh_status fh_sparse_decode(const void* info, const void* values, size_t values_b
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     Sums* wg = static_cast<Sums*>(workspace);
-    const MapShape shape = make_shape(out, h, w, n, tiles);
+    const MapShape shape = make_shape(out, h, w, n, tiles, eps);
     const dim3 grid(workgroups(tiles)), block(kTileThreads);
     const uint8_t* inf = static_cast<const uint8_t*>(info);
     const uint8_t* idx = static_cast<const uint8_t*>(indices);

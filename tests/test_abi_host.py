@@ -207,14 +207,14 @@ def test_raw_store_size():
 
 def _sencode(x=FAKE, dtype=0, maps=4, h=10, w=10, n=4, tau=0.5, info=FAKE, info_cap=1 << 20, values=FAKE,
              values_cap=1 << 20, indices=FAKE, indices_cap=1 << 20, totals=FAKE, ws=FAKE, ws_cap=1 << 20):
-    return api.raw_library().fh_sparse_encode(x, dtype, maps, h, w, n, tau, info, info_cap, values, values_cap,
+    return api.raw_library().fh_sparse_encode(x, dtype, maps, h, w, n, tau, 0.0, info, info_cap, values, values_cap,
                                               indices, indices_cap, totals, ws, ws_cap, None)
 
 
 def _sdecode(info=FAKE, values=FAKE, values_bytes=1 << 20, indices=FAKE, indices_bytes=1 << 20, dtype=0, maps=4,
              h=10, w=10, n=4, out=FAKE, out_cap=1 << 20, ws=FAKE, ws_cap=1 << 20):
     return api.raw_library().fh_sparse_decode(info, values, values_bytes, indices, indices_bytes, dtype, maps, h, w, n,
-                                              out, out_cap, ws, ws_cap, None)
+                                              0.0, out, out_cap, ws, ws_cap, None)
 
 
 def test_sparse_calls_reject_bad_arguments_before_any_launch():

@@ -36,11 +36,11 @@ def _bits(a):
     return a.view(np.uint32) if a.dtype == np.float32 else a
 
 
-def _check(api, x, maps, h, w, n, tau, dtype="f32", name=""):
-    print(f"[sparse] {name} {dtype} [{maps}][{h}][{w}] n={n} tau={tau}", flush=True)
-    info, v, idx, totals = oracle.sparse_encode(x, maps, h, w, n, tau, dtype=dtype)
+def _check(api, x, maps, h, w, n, tau, dtype="f32", name="", eps=0.0):
+    print(f"[sparse] {name} {dtype} [{maps}][{h}][{w}] n={n} tau={tau} eps={eps}", flush=True)
+    info, v, idx, totals = oracle.sparse_encode(x, maps, h, w, n, tau, dtype=dtype, eps=eps)
     dx = _device(x, dtype)
-    b = api.fh_sparse_encode(dx, maps, h, w, n, tau)
+    b = api.fh_sparse_encode(dx, maps, h, w, n, tau, eps=eps)
     torch.cuda.synchronize()
     gt = b.totals.cpu().numpy().view(np.uint64)
     assert np.array_equal(gt, totals), f"{name}: totals {gt} vs {totals}"
@@ -50,9 +50,10 @@ def _check(api, x, maps, h, w, n, tau, dtype="f32", name=""):
     assert np.array_equal(_bits(gv), _bits(v)), f"{name}: value stream differs"
     gi = b.indices.cpu().numpy()[:int(totals[1])]
     assert np.array_equal(gi, idx), f"{name}: index stream differs"
-    out = api.fh_sparse_decode(b.info, b.values[:int(totals[0])], b.indices[:int(totals[1])], maps, h, w, n)
+    out = api.fh_sparse_decode(b.info, b.values[:int(totals[0])], b.indices[:int(totals[1])], maps, h, w, n, eps=eps)
     torch.cuda.synchronize()
-    assert np.array_equal(_bits(_host(out, dtype)), _bits(x)), f"{name}: round trip is not lossless"
+    want = x if not eps > 0 else oracle.sparse_decode(info, v, idx, maps, h, w, n, dtype=dtype, eps=eps)
+    assert np.array_equal(_bits(_host(out, dtype)), _bits(want)), f"{name}: restored maps differ"
     return totals
 
 
@@ -188,3 +189,64 @@ def test_argument_errors_reach_the_caller(api):
     with pytest.raises(api.FedHybridError) as e:
         api.fh_sparse_encode(x, 2, 8, 8, 4, 0.5, buffers=bufs)
     assert e.value.status == 7
+
+
+# ---- dense blocks within an error bound (Lorenzo prediction, outliers intact) ------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 8])
+@pytest.mark.parametrize("eps", [1e-4, 0.02, 0.5])
+def test_predictive_dense_blocks(api, dtype, n, eps):
+    for (maps, h, w) in ((6, 27, 22), (3, 56, 56), (40, 7, 7)):
+        x = W.salient_feature_maps(maps, h, w, seed=n + maps, zero_level=0.1, dtype=dtype)
+        _check(api, x, maps, h, w, n, 0.4, dtype=dtype, name="predictive", eps=eps)
+        _check(api, x, maps, h, w, n, -1.0, dtype=dtype, name="predictive, all dense", eps=eps)
+
+
+def test_predictive_blocks_with_values_off_the_lattice(api):
+    rng = np.random.default_rng(4)
+    maps, h, w = 4, 24, 24
+    x = W.salient_feature_maps(maps, h, w, seed=8, zero_level=-0.5)
+    x[rng.integers(0, x.size, 30)] = np.inf
+    x[rng.integers(0, x.size, 30)] = -3.0e9
+    x[rng.integers(0, x.size, 30)] = np.nan
+    x[rng.integers(0, x.size, 30)] = f32(2.0 ** 22 * 0.02)                  # exactly at the end of the lattice
+    for n in (2, 4, 8):
+        info, v, idx, totals = oracle.sparse_encode(x, maps, h, w, n, 0.3, eps=0.01)
+        b = api.fh_sparse_encode(torch.from_numpy(x).cuda(), maps, h, w, n, 0.3, eps=0.01)
+        torch.cuda.synchronize()
+        assert np.array_equal(b.totals.cpu().numpy().view(np.uint64), totals)
+        assert np.array_equal(b.info.cpu().numpy()[:info.size], info)
+        assert np.array_equal(b.values.cpu().numpy()[:v.size].view(np.uint32), v.view(np.uint32))
+        assert np.array_equal(b.indices.cpu().numpy()[:idx.size], idx)
+        out = api.fh_sparse_decode(b.info, b.values[:v.size], b.indices[:idx.size], maps, h, w, n, eps=0.01)
+        torch.cuda.synchronize()
+        want = oracle.sparse_decode(info, v, idx, maps, h, w, n, eps=0.01)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_predictive_full_size_layer_meets_the_bound(api):
+    maps, h, w, n, eps = 64 * 4, 112, 112, 8, 0.05
+    x = W.salient_feature_maps(maps, h, w, seed=6, zero_level=0.0)
+    t = _check(api, x, maps, h, w, n, 0.4, name="predictive layer", eps=eps)
+    b = api.fh_sparse_encode(torch.from_numpy(x).cuda(), maps, h, w, n, 0.4, eps=eps)
+    torch.cuda.synchronize()
+    nv, ni = int(t[0]), int(t[1])
+    out = api.fh_sparse_decode(b.info, b.values[:nv], b.indices[:ni], maps, h, w, n, eps=eps).cpu().numpy()
+    assert np.abs(out.astype(np.float64) - x).max() <= eps * (1 + 1e-6) + np.abs(x).max() * 2.0 ** -22
+    assert nv * 4 + ni + b.info.numel() < 0.45 * x.nbytes                 # and it does pay
+
+
+def test_predictive_decoder_stays_inside_truncated_or_foreign_streams(api):
+    maps, h, w, n, eps = 8, 24, 24, 4, 0.02
+    x = W.salient_feature_maps(maps, h, w, seed=3, zero_level=0.0)
+    b = api.fh_sparse_encode(torch.from_numpy(x).cuda(), maps, h, w, n, 0.3, eps=eps)
+    torch.cuda.synchronize()
+    nv, ni = (int(v) for v in b.totals.cpu().tolist()[:2])
+    for info, vals, idx in ((b.info, b.values[:nv // 2], b.indices[:ni // 2]),
+                            (torch.randint(0, 256, (b.info.numel(),), dtype=torch.uint8, device="cuda"),
+                             b.values[:nv], b.indices[:ni]),
+                            (b.info, b.values[:nv], torch.randint(0, 256, (ni,), dtype=torch.uint8, device="cuda"))):
+        out = api.fh_sparse_decode(info, vals, idx, maps, h, w, n, eps=eps)
+        torch.cuda.synchronize()
+        assert out.numel() == x.size
