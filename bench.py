@@ -210,7 +210,7 @@ def bench_sparse(args, api, W, dev) -> int:
     import torch
 
     layers = ((64 * 1, 112, 112), (64 * 4, 112, 112), (64 * 6, 56, 56), (64 * 8, 28, 28), (64 * 15, 14, 14))
-    n, tau = 4, 0.5
+    n, tau, eps = 4, 0.5, args.eps
     t0 = time.time()
     host, jobs = [], []
     for i, (maps, h, w) in enumerate(layers):
@@ -223,7 +223,7 @@ def bench_sparse(args, api, W, dev) -> int:
     stream = torch.cuda.current_stream()
     for job in jobs:                                          # stream sizes (fixed: the input is)
         xd, maps, h, w, bufs, out, _ = job
-        api.fh_sparse_encode(xd, maps, h, w, n, tau, buffers=bufs, stream=stream)
+        api.fh_sparse_encode(xd, maps, h, w, n, tau, buffers=bufs, stream=stream, eps=eps)
     torch.cuda.synchronize()
     stored = 0
     for job in jobs:
@@ -239,11 +239,12 @@ def bench_sparse(args, api, W, dev) -> int:
         if timed:
             ev[0].record(stream)
         for xd, maps, h, w, bufs, out, _ in jobs:
-            api.fh_sparse_encode(xd, maps, h, w, n, tau, buffers=bufs, stream=stream)
+            api.fh_sparse_encode(xd, maps, h, w, n, tau, buffers=bufs, stream=stream, eps=eps)
         if timed:
             ev[1].record(stream)
         for xd, maps, h, w, bufs, out, (vals, idx) in jobs:
-            api.fh_sparse_decode(bufs.info, vals, idx, maps, h, w, n, out=out, workspace=bufs.workspace, stream=stream)
+            api.fh_sparse_decode(bufs.info, vals, idx, maps, h, w, n, out=out, workspace=bufs.workspace, stream=stream,
+                                 eps=eps)
         if timed:
             ev[2].record(stream)
 
@@ -270,9 +271,9 @@ def bench_sparse(args, api, W, dev) -> int:
         "value": round(nbytes / elapsed / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-        "config": {"workload": "sparse_mobilenetv2_b64_kept_channels_n4_tau0.5", "map_sets": len(jobs),
-                   "input_bytes": nbytes, "stored_bytes": stored, "entry_point": "fh_sparse_encode + fh_sparse_decode",
-                   "window": n, "tau": tau},
+        "config": {"workload": "sparse_mobilenetv2_b64_kept_channels_n4_tau0.5" + (f"_eps{eps:g}" if eps > 0 else ""),
+                   "map_sets": len(jobs), "input_bytes": nbytes, "stored_bytes": stored,
+                   "entry_point": "fh_sparse_encode + fh_sparse_decode", "window": n, "tau": tau, "eps": eps},
         "roofline": {"bound": "hbm", "kernel": dom[0] + ", all launches of a step, event-timed",
                      "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},
@@ -284,8 +285,8 @@ def bench_sparse(args, api, W, dev) -> int:
         t_cpu, done = 0.0, 0
         for x, (maps, h, w) in zip(host, layers):
             t1 = time.perf_counter()
-            info, v, idx, _ = oracle.sparse_encode(x, maps, h, w, n, tau)
-            oracle.sparse_decode(info, v, idx, maps, h, w, n)
+            info, v, idx, _ = oracle.sparse_encode(x, maps, h, w, n, tau, eps=eps)
+            oracle.sparse_decode(info, v, idx, maps, h, w, n, eps=eps)
             t_cpu += time.perf_counter() - t1
             done += x.nbytes
             if t_cpu > 20.0:
@@ -311,6 +312,8 @@ def main() -> int:
                          "channel classification step (moments + outlier counts), measured on its own; "
                          "mixed: the round trip with salient channels kept raw beside the quantised stream; "
                          "sparse: block-wise sparse storage of the kept channels' maps")
+    ap.add_argument("--eps", type=float, default=0.0,
+                    help="--op sparse: error bound of the predictive form of dense blocks (0 = verbatim)")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()
