@@ -250,3 +250,73 @@ def test_predictive_decoder_stays_inside_truncated_or_foreign_streams(api):
         out = api.fh_sparse_decode(info, vals, idx, maps, h, w, n, eps=eps)
         torch.cuda.synchronize()
         assert out.numel() == x.size
+
+
+def test_the_whole_channel_wise_chain_can_be_captured_in_a_graph_and_replayed(api):
+    """classify -> slots -> mixed compress -> sparse storage of the raw store -> back -> mixed
+    restore, captured once and replayed on new inputs: no call allocates, clears memory with a
+    memset or synchronises, so every replay must reproduce what the oracle computes."""
+    outer, C, hh, ww, cap, n, tau, eps = 6, 40, 28, 28, 3, 4, 0.5, 0.02
+    inner = hh * ww
+    G, B = 128, 4
+    dev = "cuda"
+    xd = torch.empty(outer * C * inner, device=dev)
+    ws = torch.empty(api.classify_workspace_bytes(xd.numel()), dtype=torch.uint8, device=dev)
+    stats = torch.empty(4, dtype=torch.float64, device=dev)
+    counts = torch.empty(C, dtype=torch.int32, device=dev)
+    mask = torch.empty(C, dtype=torch.uint8, device=dev)
+    slots = torch.empty(C, dtype=torch.int16, device=dev)
+    packed, meta = api.alloc_compressed(xd.numel(), G, B, dev)
+    raw = torch.zeros(outer * cap * inner, device=dev)
+    bufs = api.alloc_sparse(outer * cap, hh, ww, n, torch.float32, dev)
+    raw_back = torch.empty_like(raw)
+    out = torch.empty_like(xd)
+    min_out = outer * inner // 100
+
+    def chain(stream):
+        api.fh_classify_channels(xd, outer, C, inner, 3.0, min_out, workspace=ws, stats=stats, counts=counts,
+                                 mask=mask, stream=stream)
+        api.fh_channel_slots(mask, cap, slots=slots, stream=stream)
+        api.fh_compress_mixed(xd, outer, C, inner, slots, cap, G, B, "stochastic", 5, 1, packed=packed, meta=meta,
+                              raw=raw, stream=stream)
+        api.fh_sparse_encode(raw, outer * cap, hh, ww, n, tau, buffers=bufs, stream=stream, eps=eps)
+        # the valid prefixes are only known on the device: the decoder is given the whole buffers,
+        # it reads no further than the info bytes say
+        api.fh_sparse_decode(bufs.info, bufs.values, bufs.indices, outer * cap, hh, ww, n, out=raw_back,
+                             workspace=bufs.workspace, stream=stream, eps=eps)
+        api.fh_decompress_mixed(packed, meta, raw_back, outer, C, inner, slots, cap, G, B, out=out, stream=stream)
+
+    def expected(x):
+        _, _, omask = oracle.classify_channels(x, outer, C, inner, 3.0, min_out)
+        oslots, used = oracle.channel_slots(omask, cap)
+        p, m, oraw = oracle.compress_mixed(x, outer, C, inner, oslots, cap, G, B, "stochastic", 5, 1)
+        # rows of unused slots are not written by the compressor: they keep what the buffer held
+        # (zeros here), and go through the sparse stage like the others
+        info, v, idx, _ = oracle.sparse_encode(oraw, outer * cap, hh, ww, n, tau, eps=eps)
+        back = oracle.sparse_decode(info, v, idx, outer * cap, hh, ww, n, eps=eps)
+        return oslots, p, m, oracle.decompress_mixed(p, m, back, outer, C, inner, oslots, cap, G, B)
+
+    x0, _ = W.outlier_channel_tensor(outer, C, inner, seed=1, dist="relu", salient_fraction=0.05)
+    xd.copy_(torch.from_numpy(x0))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain(side)                                          # warm-up outside capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        chain(torch.cuda.current_stream())
+    for rep in range(3):
+        x, _ = W.outlier_channel_tensor(outer, C, inner, seed=10 + rep, dist="relu", salient_fraction=0.05 + 0.02 * rep)
+        xd.copy_(torch.from_numpy(x))
+        out.fill_(float("nan"))
+        raw.zero_()
+        packed.fill_(0x5A)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        oslots, p, m, want = expected(x)
+        assert np.array_equal(slots.cpu().numpy(), oslots), f"replay {rep}: slots"
+        assert np.array_equal(packed.cpu().numpy(), p), f"replay {rep}: codes"
+        assert np.array_equal(meta.cpu().numpy().view(np.uint32), m.view(np.uint32)), f"replay {rep}: meta"
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32)), f"replay {rep}: restored"

@@ -1,6 +1,6 @@
 """Pins for the oracle of salient-channel routing (Section 4.4.1, Channel-wise Mix
 Compression: only normal channels go through the linear-scale quantiser, so that outliers
-do not stretch its range; salient channels are kept verbatim by this build).  The paper
+do not stretch its range; salient channels are kept verbatim by this library).  The paper
 prints no worked example; the pins are reductions to the already pinned plain quantiser,
 explicit index arithmetic, error bounds that only hold when salient values are excluded
 from the statistics, brute force on tiny tensors, and an independent numpy twin."""
