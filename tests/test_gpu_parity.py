@@ -340,3 +340,43 @@ def test_batched_round_trip_can_be_captured_in_a_graph_and_replayed(api):
             p, m, o = _oracle_roundtrip(x, spec)
             _assert_same(f"graph replay {rep}/t{spec.tensor_id}", spec.group_size,
                          _host(e.packed), _host(e.meta), _host(e.out), p, m, o)
+
+
+# ------------------------------------------------------ beyond 32-bit element indices ----
+
+def test_a_tensor_with_more_than_two_to_the_32_elements(api):
+    """Element indices, byte offsets and group numbers beyond 2^32: one bf16 tensor of
+    2^32 + 70001 elements, checked against the oracle on windows that sit on the 2^31 and 2^32
+    boundaries, at the start and on the ragged end.  Nearest rounding makes every group a pure
+    function of its own elements, so the oracle can be run on a window that starts on a group
+    boundary."""
+    G, B = 256, 2
+    n = (1 << 32) + 70001
+    print(f"[parity] large tensor: {n} bf16 elements, G{G} B{B} nearest", flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    x = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    step = 1 << 28
+    for start in range(0, n, step):                          # filled in pieces: no 16 GiB fp32 temporary
+        stop = min(n, start + step)
+        x[start:stop] = torch.randn(stop - start, device="cuda", generator=gen).to(torch.bfloat16)
+    packed, meta = api.fh_compress(x, G, B, "nearest")
+    out = api.fh_decompress(packed, meta, n, G, B, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    win = 8 * 8192 + 3 * G                                   # a few compress tiles and a group-aligned tail
+    starts = [0, (1 << 31) - 4 * 8192, (1 << 32) - 4 * 8192, (1 << 32) + 8192, (n - win) // G * G]
+    for s0 in starts:
+        s1 = min(n, s0 + win)
+        xs = x[s0:s1].view(torch.int16).cpu().numpy().view(np.uint16)
+        p, m = oracle.compress(xs, G, B, "nearest", dtype="bf16")
+        o = oracle.decompress(p, m, xs.size, G, B, out_dtype="bf16")
+        nbytes = (xs.size * B + 7) // 8
+        gp = packed[s0 * B // 8: s0 * B // 8 + nbytes].cpu().numpy()
+        gm = meta[s0 // G: s0 // G + m.shape[0]].cpu().numpy()
+        go = out[s0:s1].view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(gm.view(np.uint32), m.view(np.uint32)), f"meta differs in the window at {s0}"
+        assert np.array_equal(gp, p[:nbytes]), f"codes differ in the window at {s0}"
+        assert np.array_equal(go, o), f"restored values differ in the window at {s0}"
+    # the padding behind the last code byte is zero
+    raw = (n * B + 7) // 8
+    assert packed.numel() == (raw + 15) // 16 * 16 and not packed[raw:].any().item()
