@@ -38,7 +38,8 @@ def algorithmic_bytes(spec, out_itemsize=4):
 def bench_classify(args, api, W, dev) -> int:
     """Channel classification (three-sigma outliers, salient channels) over MobileNetV2-style
     NCHW activations at batch 64 with channel-clustered outliers; one step classifies every
-    tensor of the set once.  Two streaming passes read each tensor twice."""
+    tensor of the set once (one batched call; --per-tensor: one call per tensor).  Two streaming
+    passes read each tensor twice."""
     import numpy as np
     import torch
 
@@ -60,10 +61,16 @@ def bench_classify(args, api, W, dev) -> int:
           f"(generated + uploaded in {time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
     stream = torch.cuda.current_stream()
 
+    batch = api.ClassifyBatch([api.ClassifyEntry(xd, outer, C, inner, 3.0, mo, ws, stats, counts, mask)
+                               for xd, outer, C, inner, mo, ws, stats, counts, mask in jobs])
+
     def step():
-        for xd, outer, C, inner, mo, ws, stats, counts, mask in jobs:
-            api.fh_classify_channels(xd, outer, C, inner, 3.0, mo, workspace=ws, stats=stats, counts=counts,
-                                     mask=mask, stream=stream)
+        if args.per_tensor:
+            for xd, outer, C, inner, mo, ws, stats, counts, mask in jobs:
+                api.fh_classify_channels(xd, outer, C, inner, 3.0, mo, workspace=ws, stats=stats, counts=counts,
+                                         mask=mask, stream=stream)
+        else:
+            api.fh_classify_channels_batch(batch, stream)
 
     for _ in range(args.warmup):
         step()
@@ -80,7 +87,8 @@ def bench_classify(args, api, W, dev) -> int:
         "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": "classify_mobilenetv2_b64_outlier_channels", "tensors": len(jobs),
-                   "input_bytes": nbytes, "entry_point": "fh_classify_channels (per tensor)", "k_sigma": 3.0},
+                   "input_bytes": nbytes, "k_sigma": 3.0,
+                   "entry_point": "fh_classify_channels (per tensor)" if args.per_tensor else "fh_classify_channels_batch"},
         "roofline": {"bound": "hbm", "kernel": "moments + count passes (whole call)",
                      "achieved": round(alg / elapsed / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(alg / elapsed / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},

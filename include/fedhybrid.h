@@ -252,6 +252,21 @@ fh_status fh_sparse_decode(const void *info, const void *values, size_t values_b
                            int64_t maps, int64_t h, int64_t w, int32_t n, float eps,
                            void *out, size_t out_cap, void *workspace, size_t workspace_cap, void *stream);
 
+/* The same for several tensors, as a plan classifies every compressible activation of a model:
+ * each kind of kernel is launched once per run of up to fh_classify_batch_capacity() items of
+ * one dtype, so small tensors do not each pay five launches.  All items are checked before the
+ * first launch; results are identical to calling fh_classify_channels item by item.  The
+ * items' outputs and workspaces must not overlap. */
+typedef struct fh_classify_item {
+    const void *x;          int32_t x_dtype;   int32_t reserved;    /* fh_dtype; 0 */
+    int64_t     outer, channels, inner;
+    double      k_sigma;    int64_t min_outliers;
+    void       *workspace;  size_t workspace_cap;
+    void       *stats;      void *counts;      void *mask;
+} fh_classify_item;
+fh_status fh_classify_channels_batch(const fh_classify_item *items, int32_t count, void *stream);
+int32_t   fh_classify_batch_capacity(void);
+
 const char *fh_status_string(fh_status s);
 
 #ifdef __cplusplus

@@ -30,7 +30,8 @@ FH_ROUND_NEAREST, FH_ROUND_STOCHASTIC = 0, 1
 
 EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "fh_roundtrip",
            "fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch", "fh_batch_capacity",
-           "fh_classify_workspace_bytes", "fh_classify_channels",
+           "fh_classify_workspace_bytes", "fh_classify_channels", "fh_classify_channels_batch",
+           "fh_classify_batch_capacity",
            "fh_raw_bytes", "fh_channel_slots", "fh_compress_mixed", "fh_decompress_mixed",
            "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
            "fh_sparse_decode", "fh_status_string")
@@ -48,6 +49,14 @@ class fh_item(ctypes.Structure):
                 ("meta", ctypes.c_void_p), ("meta_cap", ctypes.c_size_t),
                 ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t),
                 ("params", fh_params)]
+
+
+class fh_classify_item(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("x_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("outer", ctypes.c_int64), ("channels", ctypes.c_int64), ("inner", ctypes.c_int64),
+                ("k_sigma", ctypes.c_double), ("min_outliers", ctypes.c_int64),
+                ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t),
+                ("stats", ctypes.c_void_p), ("counts", ctypes.c_void_p), ("mask", ctypes.c_void_p)]
 
 
 _P = ctypes.POINTER
@@ -74,6 +83,10 @@ _lib.fh_classify_channels.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_in
                                       ctypes.c_double, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.fh_classify_channels.restype = ctypes.c_int
+_lib.fh_classify_channels_batch.argtypes = [_P(fh_classify_item), ctypes.c_int32, ctypes.c_void_p]
+_lib.fh_classify_channels_batch.restype = ctypes.c_int
+_lib.fh_classify_batch_capacity.argtypes = []
+_lib.fh_classify_batch_capacity.restype = ctypes.c_int32
 _lib.fh_raw_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
 _lib.fh_raw_bytes.restype = ctypes.c_size_t
 _lib.fh_channel_slots.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
@@ -481,3 +494,64 @@ def fh_sparse_decode(info: torch.Tensor, values: torch.Tensor, indices: torch.Te
                                      _dtype_code(out), maps, h, w, int(n), float(eps), _ptr(out), _nbytes(out),
                                      workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)))
     return out
+
+
+@dataclass
+class ClassifyEntry:
+    """One tensor of a batched classification; buffers left None are allocated."""
+    x: torch.Tensor
+    outer: int
+    channels: int
+    inner: int
+    k_sigma: float = 3.0
+    min_outliers: int = 1
+    workspace: Optional[torch.Tensor] = None
+    stats: Optional[torch.Tensor] = None
+    counts: Optional[torch.Tensor] = None
+    mask: Optional[torch.Tensor] = None
+
+
+class ClassifyBatch:
+    """A marshalled fh_classify_item array, reusable across calls (the buffers are fixed)."""
+
+    def __init__(self, entries: Sequence[ClassifyEntry]):
+        self.entries: List[ClassifyEntry] = list(entries)
+        self.count = len(self.entries)
+        self.items = (fh_classify_item * max(1, self.count))()
+        self.device = None
+        for it, e in zip(self.items, self.entries):
+            _device_tensor(e.x, "x")
+            if e.x.numel() != e.outer * e.channels * e.inner:
+                raise ValueError("x.numel() != outer * channels * inner")
+            dev = e.x.device
+            self.device = self.device or dev
+            if e.workspace is None:
+                e.workspace = torch.empty(classify_workspace_bytes(e.x.numel()), dtype=torch.uint8, device=dev)
+            if e.stats is None:
+                e.stats = torch.empty(4, dtype=torch.float64, device=dev)
+            if e.counts is None:
+                e.counts = torch.empty(e.channels, dtype=torch.int32, device=dev)
+            if e.mask is None:
+                e.mask = torch.empty(e.channels, dtype=torch.uint8, device=dev)
+            for t, what in ((e.workspace, "workspace"), (e.stats, "stats"), (e.counts, "counts"), (e.mask, "mask")):
+                _device_tensor(t, what)
+            if _nbytes(e.stats) < 32 or _nbytes(e.counts) < 4 * e.channels or _nbytes(e.mask) < e.channels:
+                raise FedHybridError(7)
+            it.x, it.x_dtype, it.reserved = _ptr(e.x), _dtype_code(e.x), 0
+            it.outer, it.channels, it.inner = e.outer, e.channels, e.inner
+            it.k_sigma, it.min_outliers = float(e.k_sigma), int(e.min_outliers)
+            it.workspace, it.workspace_cap = e.workspace.data_ptr(), _nbytes(e.workspace)
+            it.stats, it.counts, it.mask = e.stats.data_ptr(), e.counts.data_ptr(), e.mask.data_ptr()
+
+
+def classify_batch_capacity() -> int:
+    return int(_lib.fh_classify_batch_capacity())
+
+
+def fh_classify_channels_batch(batch: ClassifyBatch, stream=None) -> None:
+    """Enqueue the classification of every tensor of the batch; results are in the entries'
+    stats / counts / mask tensors."""
+    if batch.count == 0:
+        return
+    with torch.cuda.device(batch.device):
+        _check(_lib.fh_classify_channels_batch(batch.items, batch.count, _stream_ptr(stream)))

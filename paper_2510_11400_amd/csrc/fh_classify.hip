@@ -19,6 +19,7 @@
 //      non-zero bin and workgroup.
 #include "../../include/fedhybrid.h"
 
+#include "fh_channels.hpp"
 #include "fh_device.hpp"
 
 #include <limits.h>
@@ -131,6 +132,38 @@ __device__ __forceinline__ void span_tree(const double (&a)[ROWS], const double 
     }
 }
 
+// ---- batches -----------------------------------------------------------------------------
+// Every kernel serves up to kBatch tensors per launch: descriptors travel by value in the
+// kernel-argument segment and a workgroup finds its tensor by a scalar search over the
+// exclusive prefix sums of the tensors' workgroup counts (entries past the last tensor repeat
+// the total).
+constexpr int kBatch = 16;
+
+template <typename Item> struct Batch {
+    int32_t  count;
+    uint32_t block_start[kBatch + 1];
+    Item     item[kBatch];
+};
+template <typename Item>
+__device__ __forceinline__ int batch_item(const Batch<Item>& b, uint32_t bid, uint32_t& local)
+{
+    int lo = 0, hi = b.count;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (b.block_start[mid] <= bid) lo = mid; else hi = mid;
+    }
+    local = bid - b.block_start[lo];
+    return lo;
+}
+
+struct MomentsItem { const void* x; int64_t numel; f64x2* partial; };
+struct ReduceItem  { const f64x2* in; int64_t count; f64x2* out; };
+struct FinishItem  {
+    const f64x2* in; int64_t count; int64_t numel; double k_sigma;
+    double* stats; uint32_t* counts; uint8_t* mask; int32_t channels;
+};
+struct MaskItem    { const uint32_t* counts; uint8_t* mask; int64_t min_outliers; int32_t channels; };
+
 // ---- pass 1a: spans of the tensor ------------------------------------------------------
 template <typename InT> struct Span;
 template <> struct Span<float> {            // 4 rows of 256, 4 consecutive elements per lane
@@ -168,13 +201,17 @@ __device__ __forceinline__ double local_tree(const double (&v)[N])
 }
 
 template <typename InT>
-__global__ __launch_bounds__(kThreads) void moments_kernel(const InT* __restrict__ x, int64_t numel,
-                                                           f64x2* __restrict__ partial)
+__global__ __launch_bounds__(kThreads) void moments_kernel(const Batch<MomentsItem> args)
 {
     constexpr int ROWS = Span<InT>::ROWS, EPL = Span<InT>::EPL, ROW = kWave * EPL;
+    uint32_t block;
+    const MomentsItem& it = args.item[batch_item(args, blockIdx.x, block)];
+    const InT* x = static_cast<const InT*>(it.x);
+    const int64_t numel = it.numel;
+    f64x2* partial = it.partial;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t span = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t span = (int64_t)block * kWavesPerBlock + wave;
     const int64_t base = span * kSpan;
     if (base >= numel) return;                                // wave-uniform
     const InT* xs = x + base;
@@ -202,13 +239,17 @@ __global__ __launch_bounds__(kThreads) void moments_kernel(const InT* __restrict
 }
 
 // ---- pass 1b: spans of partial sums (4 rows of 256 pairs, 4 consecutive pairs per lane) --
-__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f64x2* __restrict__ in, int64_t count,
-                                                                   f64x2* __restrict__ out)
+__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const Batch<ReduceItem> args)
 {
     constexpr int ROWS = 4, EPL = 4, ROW = kWave * EPL;
+    uint32_t block;
+    const ReduceItem& it = args.item[batch_item(args, blockIdx.x, block)];
+    const f64x2* in = it.in;
+    const int64_t count = it.count;
+    f64x2* out = it.out;
     const uint32_t lane = threadIdx.x & (kWave - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t span = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t span = (int64_t)block * kWavesPerBlock + wave;
     const int64_t base = span * kSpan;
     if (base >= count) return;
     double a[ROWS], b[ROWS];
@@ -231,12 +272,17 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const f64x2* 
 
 // ---- pass 1c: last level of the tree (at most 1024 partial sums), then mean, variance and
 //      threshold; clears the counters and the mask ----------------------------------------------
-__global__ __launch_bounds__(kThreads) void finish_moments_kernel(const f64x2* __restrict__ in, int64_t count,
-                                                                  int64_t numel, double k_sigma,
-                                                                  double* __restrict__ stats,
-                                                                  uint32_t* __restrict__ counts,
-                                                                  uint8_t* __restrict__ mask, int channels)
+struct FinishBatch { FinishItem item[kBatch]; };           // one workgroup per tensor
+__global__ __launch_bounds__(kThreads) void finish_moments_kernel(const FinishBatch args)
 {
+    const FinishItem& it = args.item[blockIdx.x];
+    const f64x2* in = it.in;
+    const int64_t count = it.count, numel = it.numel;
+    const double k_sigma = it.k_sigma;
+    double* stats = it.stats;
+    uint32_t* counts = it.counts;
+    uint8_t* mask = it.mask;
+    const int channels = it.channels;
     for (int c = threadIdx.x; c < channels; c += kThreads) { counts[c] = 0u; mask[c] = 0; }
     if (threadIdx.x >= kWave) return;                         // the tree is one wave's work
     constexpr int ROWS = 4, EPL = 4, ROW = kWave * EPL;
@@ -273,32 +319,24 @@ __global__ __launch_bounds__(kThreads) void finish_moments_kernel(const f64x2* _
 }
 
 // ---- pass 2: outliers per channel ----------------------------------------------------------
-// floor(n / d) for a divisor fixed on the host.  magic = floor(2^32 / d) + 1 is exact
-// whenever n * d < 2^32; divisors of 2^15 and more are only ever asked for quotients 0 or 1.
-struct Divisor {
-    uint32_t d, magic;
-};
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, Divisor v)
-{
-    if (v.d == 1u) return n;
-    if (v.d >= 32768u) return n >= v.d ? 1u : 0u;
-    return __umulhi(n, v.magic);
-}
-
+// Channel of an outlier: division by `inner` and `channels` through the small-dividend
+// divider of fh_channels.hpp (dividends stay below divisor + 2 * 1024 here).
 struct CountArgs {
     const void* x;
     int64_t numel;
     const double* stats;
     uint32_t* counts;
-    Divisor inner, channels;
+    SmallDiv inner, channels;
     int32_t spans_per_wave;                                   // consecutive spans one wave walks
 };
 
 template <typename InT>
-__global__ __launch_bounds__(kThreads) void count_outliers_kernel(const CountArgs args)
+__global__ __launch_bounds__(kThreads) void count_outliers_kernel(const Batch<CountArgs> batch)
 {
     constexpr int ROWS = Span<InT>::ROWS, EPL = Span<InT>::EPL, ROW = kWave * EPL;
     extern __shared__ uint32_t hist[];
+    uint32_t block;
+    const CountArgs& args = batch.item[batch_item(batch, blockIdx.x, block)];
     const uint32_t C = args.channels.d;
     for (uint32_t c = threadIdx.x; c < C; c += kThreads) hist[c] = 0u;
     __syncthreads();
@@ -309,7 +347,7 @@ __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const CountArg
     const InT* x = static_cast<const InT*>(args.x);
     const int64_t numel = args.numel;
     // this wave's spans: first_span, first_span + 1, ...
-    const int64_t first_span = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * args.spans_per_wave;
+    const int64_t first_span = ((int64_t)block * kWavesPerBlock + wave) * args.spans_per_wave;
     int64_t base = first_span * kSpan;
     // position of the span's first element: rem = index inside the channel run, chan = channel
     uint32_t rem = 0, chan = 0;
@@ -343,17 +381,17 @@ __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const CountArg
             const uint32_t k = (uint32_t)__builtin_ctz(bits);
             bits &= bits - 1u;
             const uint32_t off = (k / EPL) * ROW + lane * EPL + (k % EPL);   // element offset inside the span
-            const uint32_t runs = fast_div(rem + off, args.inner);           // channel runs crossed from `chan`
+            const uint32_t runs = div_small(rem + off, args.inner);           // channel runs crossed from `chan`
             const uint32_t cc = chan + runs;
-            const uint32_t c = cc - fast_div(cc, args.channels) * C;
+            const uint32_t c = cc - div_small(cc, args.channels) * C;
             atomicAdd(&hist[c], 1u);
         }
         // advance (rem, chan) by one span
         const uint32_t t = rem + kSpan;
-        const uint32_t runs = fast_div(t, args.inner);
+        const uint32_t runs = div_small(t, args.inner);
         rem = t - runs * args.inner.d;
         const uint32_t cc = chan + runs;
-        chan = cc - fast_div(cc, args.channels) * C;
+        chan = cc - div_small(cc, args.channels) * C;
     }
     __syncthreads();
     for (uint32_t c = threadIdx.x; c < C; c += kThreads) {
@@ -362,19 +400,12 @@ __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const CountArg
     }
 }
 
-__global__ __launch_bounds__(kThreads) void mask_kernel(const uint32_t* __restrict__ counts, int channels,
-                                                        int64_t min_outliers, uint8_t* __restrict__ mask)
+__global__ __launch_bounds__(kThreads) void mask_kernel(const Batch<MaskItem> args)
 {
-    const int c = blockIdx.x * kThreads + threadIdx.x;
-    if (c < channels) mask[c] = (int64_t)counts[c] >= min_outliers ? 1 : 0;
-}
-
-Divisor make_divisor(uint32_t d)
-{
-    Divisor v;
-    v.d = d;
-    v.magic = d >= 2u ? (uint32_t)(((uint64_t)1 << 32) / d) + 1u : 0u;
-    return v;
+    uint32_t block;
+    const MaskItem& it = args.item[batch_item(args, blockIdx.x, block)];
+    const int c = block * kThreads + threadIdx.x;
+    if (c < it.channels) it.mask[c] = (int64_t)it.counts[c] >= it.min_outliers ? 1 : 0;
 }
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -398,72 +429,170 @@ size_t fh_classify_workspace_bytes(int64_t numel)
     return pairs * 16;
 }
 
+}  // extern "C"
+
+namespace {
+
+using namespace fh;
+
+fh_status check_item(const fh_classify_item& it, int64_t* numel_out)
+{
+    if (it.x_dtype != FH_F32 && it.x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if (it.outer < 0 || it.inner < 1 || it.channels < 1 || it.channels > kMaxChannels) return FH_ERR_BAD_SHAPE;
+    if (it.inner > (int64_t)1 << 31 || it.outer > (int64_t)1 << 40) return FH_ERR_BAD_SHAPE;
+    if (!(it.k_sigma > 0.0) || it.min_outliers < 1) return FH_ERR_BAD_PARAM;
+    const double total = (double)it.outer * (double)it.channels * (double)it.inner;
+    if (total > (double)((int64_t)1 << 40)) return FH_ERR_BAD_NUMEL;
+    const int64_t numel = it.outer * it.channels * it.inner;
+    if (!it.workspace || !it.stats || !it.counts || !it.mask || (numel > 0 && !it.x)) return FH_ERR_NULL;
+    auto misaligned = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
+    if (misaligned(it.x, 16) || misaligned(it.workspace, 16) || misaligned(it.stats, 8) || misaligned(it.counts, 4))
+        return FH_ERR_ALIGNMENT;
+    if (it.workspace_cap < fh_classify_workspace_bytes(numel)) return FH_ERR_BUFFER_TOO_SMALL;
+    *numel_out = numel;
+    return FH_OK;
+}
+
+// Append an item that needs `blocks` workgroups; false when the launch is full.
+template <typename Item>
+bool push(Batch<Item>& b, const Item& item, int64_t blocks)
+{
+    if (b.count == kBatch || (uint64_t)b.block_start[b.count] + (uint64_t)blocks > (uint64_t)INT_MAX) return false;
+    b.item[b.count] = item;
+    b.block_start[b.count + 1] = b.block_start[b.count] + (uint32_t)blocks;
+    ++b.count;
+    return true;
+}
+template <typename Item> void seal(Batch<Item>& b)
+{
+    for (int k = b.count + 1; k <= kBatch; ++k) b.block_start[k] = b.block_start[b.count];
+}
+template <typename Item> void reset(Batch<Item>& b) { b.count = 0; b.block_start[0] = 0; }
+
+// One run of up to kBatch tensors of one dtype: five kinds of launches, each covering all of them.
+fh_status run_classify(const fh_classify_item* items, const int64_t* numels, int n, hipStream_t s)
+{
+    const dim3 block(kThreads);
+    const int dtype = items[0].x_dtype;
+    f64x2* level[kBatch];
+    int64_t m[kBatch];
+
+    Batch<MomentsItem> mb;
+    reset(mb);
+    for (int i = 0; i < n; ++i) {
+        level[i] = static_cast<f64x2*>(items[i].workspace);
+        m[i] = numels[i] > 0 ? ceil_div(numels[i], kSpan) : 0;
+        if (numels[i] > 0 && !push(mb, MomentsItem{items[i].x, numels[i], level[i]}, ceil_div(m[i], kWavesPerBlock)))
+            return FH_ERR_BAD_NUMEL;
+    }
+    if (mb.count > 0) {
+        seal(mb);
+        const dim3 grid(mb.block_start[mb.count]);
+        if (dtype == FH_F32) hipLaunchKernelGGL(moments_kernel<float>, grid, block, 0, s, mb);
+        else hipLaunchKernelGGL(moments_kernel<uint16_t>, grid, block, 0, s, mb);
+    }
+    for (;;) {                                                // tree levels above the first, where needed
+        Batch<ReduceItem> rb;
+        reset(rb);
+        for (int i = 0; i < n; ++i) {
+            if (m[i] <= kSpan) continue;                      // the last <= 1024 partials are the finish kernel's
+            const int64_t next = ceil_div(m[i], kSpan);
+            f64x2* out = level[i] + m[i];
+            push(rb, ReduceItem{level[i], m[i], out}, ceil_div(next, kWavesPerBlock));
+            level[i] = out;
+            m[i] = next;
+        }
+        if (rb.count == 0) break;
+        seal(rb);
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3(rb.block_start[rb.count]), block, 0, s, rb);
+    }
+    FinishBatch fb;
+    for (int i = 0; i < n; ++i)
+        fb.item[i] = FinishItem{level[i], m[i], numels[i], items[i].k_sigma, static_cast<double*>(items[i].stats),
+                                static_cast<uint32_t*>(items[i].counts), static_cast<uint8_t*>(items[i].mask),
+                                (int32_t)items[i].channels};
+    for (int i = n; i < kBatch; ++i) fb.item[i] = fb.item[0];
+    hipLaunchKernelGGL(finish_moments_kernel, dim3(n), block, 0, s, fb);
+
+    Batch<CountArgs> cb;
+    Batch<MaskItem> kb;
+    reset(cb);
+    reset(kb);
+    size_t lds = 0;
+    for (int i = 0; i < n; ++i) {
+        if (numels[i] == 0) continue;                         // no outliers: the cleared mask stands
+        CountArgs a;
+        a.x = items[i].x;
+        a.numel = numels[i];
+        a.stats = static_cast<const double*>(items[i].stats);
+        a.counts = static_cast<uint32_t*>(items[i].counts);
+        a.inner = make_small_div((uint32_t)items[i].inner);
+        a.channels = make_small_div((uint32_t)items[i].channels);
+        // a workgroup clears and flushes `channels` histogram bins: give it enough elements
+        // to make that cheap, but no more (short workgroups measured faster)
+        const int64_t ch = items[i].channels;
+        a.spans_per_wave = ch <= 512 ? 1 : ch <= 2048 ? 2 : ch <= 8192 ? 4 : 8;
+        const int64_t per_block = (int64_t)a.spans_per_wave * kWavesPerBlock * kSpan;
+        if (!push(cb, a, ceil_div(numels[i], per_block))) return FH_ERR_BAD_NUMEL;
+        push(kb, MaskItem{a.counts, static_cast<uint8_t*>(items[i].mask), items[i].min_outliers, (int32_t)ch},
+             ceil_div(ch, kThreads));
+        if ((size_t)ch * sizeof(uint32_t) > lds) lds = (size_t)ch * sizeof(uint32_t);
+    }
+    if (cb.count > 0) {
+        seal(cb);
+        seal(kb);
+        const dim3 grid(cb.block_start[cb.count]);
+        if (dtype == FH_F32) hipLaunchKernelGGL(count_outliers_kernel<float>, grid, block, lds, s, cb);
+        else hipLaunchKernelGGL(count_outliers_kernel<uint16_t>, grid, block, lds, s, cb);
+        hipLaunchKernelGGL(mask_kernel, dim3(kb.block_start[kb.count]), block, 0, s, kb);
+    }
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t fh_classify_batch_capacity(void) { return fh::kBatch; }
+
+fh_status fh_classify_channels_batch(const fh_classify_item* items, int32_t count, void* stream)
+{
+    if (count < 0) return FH_ERR_BAD_COUNT;
+    if (count > 0 && !items) return FH_ERR_NULL;
+    // all items are checked before the first launch
+    for (int32_t i = 0; i < count; ++i) {
+        int64_t numel;
+        const fh_status st = check_item(items[i], &numel);
+        if (st != FH_OK) return st;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t i = 0;
+    while (i < count) {                                       // runs of one dtype, at most kBatch long
+        int64_t numels[fh::kBatch];
+        int n = 0;
+        while (i + n < count && n < fh::kBatch && items[i + n].x_dtype == items[i].x_dtype) {
+            check_item(items[i + n], &numels[n]);
+            ++n;
+        }
+        const fh_status st = run_classify(items + i, numels, n, s);
+        if (st != FH_OK) return st;
+        i += n;
+    }
+    return FH_OK;
+}
+
 fh_status fh_classify_channels(const void* x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
                                double k_sigma, int64_t min_outliers,
                                void* workspace, size_t workspace_cap,
                                void* stats, void* counts, void* mask, void* stream)
 {
-    using namespace fh;
-    if (x_dtype != FH_F32 && x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
-    if (outer < 0 || inner < 1 || channels < 1 || channels > kMaxChannels) return FH_ERR_BAD_SHAPE;
-    if (inner > (int64_t)1 << 31 || outer > (int64_t)1 << 40) return FH_ERR_BAD_SHAPE;
-    if (!(k_sigma > 0.0) || min_outliers < 1) return FH_ERR_BAD_PARAM;
-    const double total = (double)outer * (double)channels * (double)inner;
-    if (total > (double)((int64_t)1 << 40)) return FH_ERR_BAD_NUMEL;
-    const int64_t numel = outer * channels * inner;
-    if (!workspace || !stats || !counts || !mask || (numel > 0 && !x)) return FH_ERR_NULL;
-    auto misaligned = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
-    if (misaligned(x, 16) || misaligned(workspace, 16) || misaligned(stats, 8) || misaligned(counts, 4))
-        return FH_ERR_ALIGNMENT;
-    if (workspace_cap < fh_classify_workspace_bytes(numel)) return FH_ERR_BUFFER_TOO_SMALL;
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    f64x2* level = static_cast<f64x2*>(workspace);
-    const dim3 block(kThreads);
-    int64_t m = 0;
-    if (numel > 0) {
-        m = ceil_div(numel, kSpan);
-        const dim3 grid0((uint32_t)ceil_div(m, kWavesPerBlock));
-        if (x_dtype == FH_F32)
-            hipLaunchKernelGGL(moments_kernel<float>, grid0, block, 0, s, static_cast<const float*>(x), numel, level);
-        else
-            hipLaunchKernelGGL(moments_kernel<uint16_t>, grid0, block, 0, s, static_cast<const uint16_t*>(x), numel, level);
-        while (m > kSpan) {                                   // the last <= 1024 partials are the finish kernel's
-            const int64_t next = ceil_div(m, kSpan);
-            f64x2* out = level + m;
-            const dim3 grid((uint32_t)ceil_div(next, kWavesPerBlock));
-            hipLaunchKernelGGL(reduce_partials_kernel, grid, block, 0, s, level, m, out);
-            level = out;
-            m = next;
-        }
-    }
-    hipLaunchKernelGGL(finish_moments_kernel, dim3(1), block, 0, s, level, m, numel, k_sigma,
-                       static_cast<double*>(stats), static_cast<uint32_t*>(counts), static_cast<uint8_t*>(mask),
-                       (int)channels);
-    if (numel > 0) {
-        CountArgs a;
-        a.x = x;
-        a.numel = numel;
-        a.stats = static_cast<const double*>(stats);
-        a.counts = static_cast<uint32_t*>(counts);
-        a.inner = make_divisor((uint32_t)inner);
-        a.channels = make_divisor((uint32_t)channels);
-        // a workgroup clears and flushes `channels` histogram bins: give it enough elements
-        // to make that cheap, but no more (short workgroups measured faster)
-        a.spans_per_wave = channels <= 512 ? 1 : channels <= 2048 ? 2 : channels <= 8192 ? 4 : 8;
-        const int64_t per_block = (int64_t)a.spans_per_wave * kWavesPerBlock * kSpan;
-        const dim3 grid((uint32_t)ceil_div(numel, per_block));
-        const size_t lds = (size_t)channels * sizeof(uint32_t);
-        if (x_dtype == FH_F32)
-            hipLaunchKernelGGL(count_outliers_kernel<float>, grid, block, lds, s, a);
-        else
-            hipLaunchKernelGGL(count_outliers_kernel<uint16_t>, grid, block, lds, s, a);
-        // (an empty tensor has no outliers: the mask the finish kernel cleared stands)
-        hipLaunchKernelGGL(mask_kernel, dim3((uint32_t)ceil_div(channels, kThreads)), block, 0, s,
-                           static_cast<const uint32_t*>(counts), (int)channels, min_outliers,
-                           static_cast<uint8_t*>(mask));
-    }
-    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+    fh_classify_item it;
+    it.x = x; it.x_dtype = x_dtype; it.reserved = 0;
+    it.outer = outer; it.channels = channels; it.inner = inner;
+    it.k_sigma = k_sigma; it.min_outliers = min_outliers;
+    it.workspace = workspace; it.workspace_cap = workspace_cap;
+    it.stats = stats; it.counts = counts; it.mask = mask;
+    return fh_classify_channels_batch(&it, 1, stream);
 }
 
 }  // extern "C"

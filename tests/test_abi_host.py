@@ -242,3 +242,28 @@ def test_sparse_size_helpers():
     assert api.sparse_workspace_bytes(4, 10, 10, 4) == 24
     assert api.sparse_workspace_bytes(1000, 16, 16, 2) == 24 * -(-64000 // 256)
     assert api.sparse_info_bytes(4, 10, 10, 3) == 0 and api.sparse_info_bytes(0, 10, 10, 4) == 0
+
+
+def test_classify_item_layout_and_batch_argument_checks():
+    # the C struct: pointer, two int32, three int64, double, int64, pointer + size, three pointers
+    assert ctypes.sizeof(api.fh_classify_item) == 8 + 8 + 24 + 16 + 16 + 24 == 96
+    assert api.fh_classify_item.outer.offset == 16 and api.fh_classify_item.k_sigma.offset == 40
+    assert api.fh_classify_item.workspace.offset == 56 and api.fh_classify_item.mask.offset == 88
+    assert api.classify_batch_capacity() == 16
+    f = api.raw_library().fh_classify_channels_batch
+    assert f(None, 0, None) == 0 and f(None, 1, None) == 1 and f(None, -1, None) == 10
+
+    def item(**kw):
+        it = api.fh_classify_item(FAKE, 0, 0, 4, 8, 16, 3.0, 1, FAKE, 1 << 20, FAKE, FAKE, FAKE)
+        for k, v in kw.items():
+            setattr(it, k, v)
+        return it
+
+    arr = (api.fh_classify_item * 3)(item(), item(), item(channels=0))
+    assert f(arr, 3, None) == 11                             # the bad third item is found before any launch
+    arr = (api.fh_classify_item * 2)(item(), item(k_sigma=-1.0))
+    assert f(arr, 2, None) == 12
+    arr = (api.fh_classify_item * 2)(item(x_dtype=5), item())
+    assert f(arr, 2, None) == 2
+    arr = (api.fh_classify_item * 1)(item(workspace_cap=8))
+    assert f(arr, 1, None) == 7

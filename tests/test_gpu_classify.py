@@ -106,3 +106,52 @@ def test_paper_sized_activation_set(api):
         x, planted = W.outlier_channel_tensor(64, C, h * w, seed=100 + i, dist="relu")
         counts, mask = _check(api, x, 64, C, h * w, 3.0, 64 * h * w // 100, name="ablation")
         assert set(int(c) for c in planted) <= set(np.flatnonzero(mask))
+
+
+# ---- the batched call --------------------------------------------------------------------------
+
+def test_batched_call_matches_the_oracle_for_every_item(api):
+    """More items than one launch holds, both dtypes (so several runs), an empty tensor, a tensor
+    whose partial sums need a second tree level, very different channel counts."""
+    shapes = [(4, 16, 196, "f32"), (2, 7, 49, "f32"), (300, 768, 1, "bf16"), (0, 12, 9, "f32"), (1, 3, 1_100_000, "f32"),
+              (5, 16384, 3, "f32"), (64, 32, 49, "bf16")] + [(3, 5 + i, 100 + 7 * i, "f32") for i in range(14)]
+    entries, host = [], []
+    for i, (outer, C, inner, dtype) in enumerate(shapes):
+        x, _ = W.outlier_channel_tensor(max(outer, 1), C, inner, seed=100 + i, salient_fraction=0.1, dtype=dtype)
+        x = x[: outer * C * inner]
+        host.append(x)
+        k, mo = (3.0, max(1, outer * inner // 50)) if i % 2 == 0 else (2.0, 3)
+        entries.append(api.ClassifyEntry(_device(x, dtype) if x.size else torch.empty(0, device="cuda"),
+                                         outer, C, inner, k, mo))
+    assert len(entries) > api.classify_batch_capacity()
+    batch = api.ClassifyBatch(entries)
+    print(f"[classify] batch of {len(entries)} tensors", flush=True)
+    api.fh_classify_channels_batch(batch)
+    torch.cuda.synchronize()
+    for i, ((outer, C, inner, dtype), x, e) in enumerate(zip(shapes, host, entries)):
+        stats, counts, mask = oracle.classify_channels(x, outer, C, inner, e.k_sigma, e.min_outliers, dtype=dtype)
+        assert np.array_equal(e.stats.cpu().numpy().view(np.uint64), stats.view(np.uint64)), f"item {i}: stats"
+        assert np.array_equal(e.counts.cpu().numpy().view(np.uint32), counts), f"item {i}: counts"
+        assert np.array_equal(e.mask.cpu().numpy(), mask), f"item {i}: mask"
+    # a second call on the same batch (buffers reused) gives the same answers
+    api.fh_classify_channels_batch(batch)
+    torch.cuda.synchronize()
+    for (outer, C, inner, dtype), x, e in zip(shapes, host, entries):
+        _, counts, _ = oracle.classify_channels(x, outer, C, inner, e.k_sigma, e.min_outliers, dtype=dtype)
+        assert np.array_equal(e.counts.cpu().numpy().view(np.uint32), counts)
+
+
+def test_batched_call_on_the_full_size_set(api):
+    shapes = ((64, 32, 112 * 112), (64, 96, 112 * 112), (64, 144, 56 * 56), (64, 192, 28 * 28), (64, 384, 14 * 14))
+    entries, host = [], []
+    for i, (outer, C, inner) in enumerate(shapes):
+        x, _ = W.outlier_channel_tensor(outer, C, inner, seed=i, dist="relu")
+        host.append(x)
+        entries.append(api.ClassifyEntry(torch.from_numpy(x).cuda(), outer, C, inner, 3.0, outer * inner // 100))
+    api.fh_classify_channels_batch(api.ClassifyBatch(entries))
+    torch.cuda.synchronize()
+    for (outer, C, inner), x, e in zip(shapes, host, entries):
+        stats, counts, mask = oracle.classify_channels(x, outer, C, inner, 3.0, outer * inner // 100)
+        assert np.array_equal(e.stats.cpu().numpy().view(np.uint64), stats.view(np.uint64))
+        assert np.array_equal(e.counts.cpu().numpy().view(np.uint32), counts)
+        assert np.array_equal(e.mask.cpu().numpy(), mask)
