@@ -202,12 +202,8 @@ __global__ __launch_bounds__(kDBlock) void decompress_kernel(const DecompressBat
 #else
     const uint32_t bid = blockIdx.x;
 #endif
-    int lo = 0, hi = args.count;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (args.tile_start[mid] <= bid) lo = mid; else hi = mid;
-    }
-    const DecompressItem& it = args.item[lo];
+    const int lo = find_item(args.tile_start, bid);
+    const DecompressItem it = args.item[lo];                  // by value: one batch of scalar loads
     const uint32_t tile = bid - args.tile_start[lo];
     switch (it.bits) {
         case 2: decompress_tile<OutT, G, 2>(it, tile); break;

@@ -47,6 +47,24 @@ struct DecompressBatch {
 static_assert(sizeof(CompressBatch) <= 4096, "kernel arguments must fit the 4 KiB segment");
 static_assert(sizeof(DecompressBatch) <= 4096, "kernel arguments must fit the 4 KiB segment");
 
+// The item a workgroup's tile belongs to: the last one whose first tile is <= bid.  Entries
+// past the last item repeat the total (> bid), so every entry may be compared.  Two rounds of
+// independent scalar loads -- every 8th entry, then the entries inside that run -- instead of a
+// binary search's chain of six dependent ones: a wave cannot issue its first data load before
+// this is done.
+static_assert(kMaxItems == 48, "find_item walks 6 runs of 8");
+__device__ __forceinline__ int find_item(const uint32_t (&tile_start)[kMaxItems + 1], uint32_t bid)
+{
+    int run = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxItems / 8; ++k) run += tile_start[8 * k] <= bid ? 1 : 0;
+    const int first = 8 * run;
+    int lo = first;
+#pragma unroll
+    for (int i = 1; i < 8; ++i) lo += tile_start[first + i] <= bid ? 1 : 0;
+    return lo;
+}
+
 // Elements one workgroup covers (same for every bit width, so tile_start[] can be
 // built on the host without knowing which variant a tile dispatches to).
 int compress_tile_elems(int dtype, int group_size);

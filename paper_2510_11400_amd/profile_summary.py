@@ -73,7 +73,33 @@ def _counter(pmc_dir: str, counter: str) -> Dict[str, float]:
     return {k: sum(v) / len(v) for k, v in acc.items()}
 
 
-def summarise(trace_dir, fetch_dir, write_dir, bench_json, copy_bytes, commands) -> str:
+SQ_COUNTERS = ("SQ_WAVES", "SQ_BUSY_CYCLES", "SQ_WAIT_INST_ANY", "SQ_INSTS_VALU", "SQ_INSTS_SALU", "SQ_INSTS_LDS",
+               "SQ_ACTIVE_INST_LDS", "SQ_LDS_BANK_CONFLICT")
+
+
+def _sq_section(sq_dir: str) -> list:
+    """Per-launch means of the shader-sequencer counters of a --pmc run, per kernel."""
+    vals = {c: _counter(sq_dir, c) for c in SQ_COUNTERS}
+    lines = []
+    for k in KERNELS:
+        if k not in vals["SQ_WAVES"]:
+            continue
+        lines.append(f"[{k}.sq]")
+        for c in SQ_COUNTERS:
+            lines.append(f"{c} = {vals[c].get(k, float('nan')):.0f}")
+        lds_active = vals["SQ_ACTIVE_INST_LDS"].get(k, 0.0)
+        if lds_active > 0:
+            lines.append(f"lds_bank_conflict_over_lds_active_cycles = "
+                         f"{vals['SQ_LDS_BANK_CONFLICT'].get(k, 0.0) / lds_active:.4f}")
+        waves = vals["SQ_WAVES"][k]
+        lines.append(f"valu_instructions_per_wave = {vals['SQ_INSTS_VALU'].get(k, 0.0) / waves:.1f}")
+        lines.append(f"salu_instructions_per_wave = {vals['SQ_INSTS_SALU'].get(k, 0.0) / waves:.1f}")
+        lines.append(f"lds_instructions_per_wave = {vals['SQ_INSTS_LDS'].get(k, 0.0) / waves:.1f}")
+        lines.append("")
+    return lines
+
+
+def summarise(trace_dir, fetch_dir, write_dir, bench_json, copy_bytes, commands, sq_dir=None) -> str:
     dur = _durations(trace_dir)
     fetch = _counter(fetch_dir, "FETCH_SIZE")
     write = _counter(write_dir, "WRITE_SIZE")
@@ -107,6 +133,8 @@ def summarise(trace_dir, fetch_dir, write_dir, bench_json, copy_bytes, commands)
                   f"traffic_over_algorithmic = {(fb + wb) / alg:.4f}",
                   f"achieved_GBps_algorithmic = {alg / avg_us / 1e3:.1f}",
                   ""]
+    if sq_dir:
+        lines += _sq_section(sq_dir)
     lines += ["[bench_line]", json.dumps(bench)]
     return "\n".join(lines) + "\n"
 
@@ -156,13 +184,14 @@ def main() -> None:
     ap.add_argument("--trace", required=True)
     ap.add_argument("--fetch")
     ap.add_argument("--write")
+    ap.add_argument("--sq", help="a --pmc run of the SQ counters (waves, instructions, LDS bank conflicts)")
     ap.add_argument("--bench-json", required=True)
     ap.add_argument("--copy-bytes", type=int, default=1 << 30)
     ap.add_argument("--out", required=True)
     ap.add_argument("--command", action="append", default=[])
     a = ap.parse_args()
     if a.fetch and a.write:
-        text = summarise(a.trace, a.fetch, a.write, a.bench_json, a.copy_bytes, a.command)
+        text = summarise(a.trace, a.fetch, a.write, a.bench_json, a.copy_bytes, a.command, a.sq)
     else:
         text = summarise_trace_only(a.trace, a.bench_json, a.command)
     with open(a.out, "w") as fh:
