@@ -47,6 +47,8 @@ struct MapShape {
     ExactDiv bw, bh;           // tile index -> (map, tile row, tile column)
     uint32_t BW, BH;
     float two_eps;             // lattice step of the predictive form of dense tiles; 0 = verbatim
+    uint32_t rows_are_vectors; // w is a multiple of n and the maps are 16-byte aligned: a tile row is one
+                               // aligned vector of n elements (every tile is n wide)
 };
 
 struct TilePos {
@@ -180,9 +182,25 @@ __device__ __forceinline__ Sums workgroup_sum(Sums part, uint64_t* lds /* [3 * k
 // The tile's elements, row-major, zeros where the tile has no element.  Every load is
 // unconditional -- out-of-tile positions read a clamped in-tile address -- so all N*N loads
 // are in flight together.
+template <typename Bits, int N> struct RowVec {               // N elements of Bits as one vector
+    typedef Bits type __attribute__((ext_vector_type(N)));
+};
+
 template <typename Bits, int N>
-__device__ __forceinline__ void load_tile(const Bits* x, const TilePos& t, uint32_t w, Bits (&e)[N][N])
+__device__ __forceinline__ void load_tile(const Bits* x, const TilePos& t, uint32_t w, bool rows_are_vectors,
+                                          Bits (&e)[N][N])
 {
+    if (rows_are_vectors) {                                   // wave-uniform
+        typedef typename RowVec<Bits, N>::type vec;
+#pragma unroll
+        for (int r = 0; r < N; ++r) {
+            const uint32_t rr = r < (int)t.rows ? r : t.rows - 1;
+            const vec v = *reinterpret_cast<const vec*>(x + (uint64_t)rr * w);
+#pragma unroll
+            for (int c = 0; c < N; ++c) e[r][c] = r < (int)t.rows ? v[c] : (Bits)0;
+        }
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < N; ++r) {
         const uint32_t rr = r < (int)t.rows ? r : t.rows - 1;
@@ -197,6 +215,31 @@ __device__ __forceinline__ void load_tile(const Bits* x, const TilePos& t, uint3
 #pragma unroll
         for (int c = 0; c < N; ++c)
             if (!(r < (int)t.rows && c < (int)t.cols)) e[r][c] = (Bits)0;
+}
+
+// The tile back to the map (only elements that exist).
+template <typename Bits, int N>
+__device__ __forceinline__ void store_tile(Bits* out, const TilePos& t, uint32_t w, bool rows_are_vectors,
+                                           const Bits (&e)[N][N])
+{
+    if (rows_are_vectors) {
+        typedef typename RowVec<Bits, N>::type vec;
+#pragma unroll
+        for (int r = 0; r < N; ++r) {
+            if (r < (int)t.rows) {
+                vec v;
+#pragma unroll
+                for (int c = 0; c < N; ++c) v[c] = e[r][c];
+                *reinterpret_cast<vec*>(out + (uint64_t)r * w) = v;
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+#pragma unroll
+        for (int c = 0; c < N; ++c)
+            if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * w + c] = e[r][c];
 }
 
 // What the tiles of all earlier workgroups write.  `scanned`: wg[] already holds exclusive
@@ -222,7 +265,7 @@ __global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const MapSha
     if (b < s.tiles) {
         const TilePos t = tile_pos(s, b);
         Bits e[N][N];
-        load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, e);
+        load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, s.rows_are_vectors != 0u, e);
         uint32_t nnz = 0;
 #pragma unroll
         for (int r = 0; r < N; ++r)
@@ -311,7 +354,7 @@ __global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapSha
         t = tile_pos(s, b);
         byte = info[b];
         mine = tile_sums(byte, t, s.two_eps > 0.0f);
-        load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, e);
+        load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, s.rows_are_vectors != 0u, e);
     }
     const Sums base = workgroup_base(wg, scanned, lds);
     Sums total;
@@ -395,11 +438,8 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
     const Bits* v = values + v0;
     if ((byte & 0x80u) && s.two_eps > 0.0f) {                 // dense, predictive
         if (!in_bounds) {
-#pragma unroll
-            for (int r = 0; r < N; ++r)
-#pragma unroll
-                for (int c = 0; c < N; ++c)
-                    if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = (Bits)0;
+            const Bits zeros[N][N] = {};
+            store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, zeros);
             return;
         }
         const uint8_t* codes = indices + i0;
@@ -412,6 +452,7 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
                 code[r][c] = codes[rr * t.cols + cc];
             }
         int32_t q[N][N];
+        Bits e[N][N];
         uint32_t used = 0;
 #pragma unroll
         for (int r = 0; r < N; ++r) {
@@ -420,21 +461,21 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
                 const int32_t left = c > 0 ? q[r][c - 1] : 0, up = r > 0 ? q[r - 1][c] : 0;
                 const int32_t diag = (r > 0 && c > 0) ? q[r - 1][c - 1] : 0;
                 q[r][c] = 0;
+                e[r][c] = (Bits)0;
                 if (r < (int)t.rows && c < (int)t.cols) {
-                    Bits restored;
                     if (code[r][c] == 0) {                    // an outlier: unchanged, and back on the lattice
-                        restored = used < count ? v[used] : (Bits)0;
+                        e[r][c] = used < count ? v[used] : (Bits)0;
                         ++used;
                         bool ok;
-                        q[r][c] = lattice(value_of<Bits>(restored), s.two_eps, ok);
+                        q[r][c] = lattice(value_of<Bits>(e[r][c]), s.two_eps, ok);
                     } else {
                         q[r][c] = left + up - diag + ((int32_t)code[r][c] - 128);
-                        restored = stored_of<Bits>((float)q[r][c] * s.two_eps);
+                        e[r][c] = stored_of<Bits>((float)q[r][c] * s.two_eps);
                     }
-                    out[(uint64_t)r * s.w + c] = restored;
                 }
             }
         }
+        store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, e);
         return;
     }
     if ((byte & 0x80u) && in_bounds && count == t.rows * t.cols) {
@@ -446,18 +487,13 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
                 const uint32_t rr = r < (int)t.rows ? r : t.rows - 1, cc = c < (int)t.cols ? c : t.cols - 1;
                 e[r][c] = v[rr * t.cols + cc];
             }
-#pragma unroll
-        for (int r = 0; r < N; ++r)
-#pragma unroll
-            for (int c = 0; c < N; ++c)
-                if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = e[r][c];
+        store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, e);
         return;
     }
-#pragma unroll
-    for (int r = 0; r < N; ++r)
-#pragma unroll
-        for (int c = 0; c < N; ++c)
-            if (r < (int)t.rows && c < (int)t.cols) out[(uint64_t)r * s.w + c] = (Bits)0;
+    {
+        const Bits zeros[N][N] = {};
+        store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, zeros);
+    }
     if ((byte & 0x80u) || !in_bounds || count == 0u) return;
     const uint8_t* row_ptr = indices + i0;
     const uint8_t* col = row_ptr + t.rows + 1;
@@ -508,6 +544,7 @@ MapShape make_shape(const void* x, int64_t h, int64_t w, int n, int64_t tiles, f
     MapShape s;
     s.x = x;
     s.two_eps = eps > 0.0f ? eps + eps : 0.0f;                // also 0 for NaN
+    s.rows_are_vectors = (w % n == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0u) ? 1u : 0u;
     s.h = (uint32_t)h; s.w = (uint32_t)w; s.n = (uint32_t)n;
     s.tiles = (uint32_t)tiles;
     s.BH = (uint32_t)((h + n - 1) / n);
