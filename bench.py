@@ -243,16 +243,25 @@ def bench_sparse(args, api, W, dev) -> int:
           f"(generated + uploaded in {time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
+    batch = api.SparseBatch([api.SparseEntry(maps, h, w, n, tau, eps, x=xd, buffers=bufs, values=vals, indices=idx,
+                                             out=out) for xd, maps, h, w, bufs, out, (vals, idx) in jobs])
+
     def step(timed=False):
         if timed:
             ev[0].record(stream)
-        for xd, maps, h, w, bufs, out, _ in jobs:
-            api.fh_sparse_encode(xd, maps, h, w, n, tau, buffers=bufs, stream=stream, eps=eps)
+        if args.per_tensor:
+            for xd, maps, h, w, bufs, out, _ in jobs:
+                api.fh_sparse_encode(xd, maps, h, w, n, tau, buffers=bufs, stream=stream, eps=eps)
+        else:
+            api.fh_sparse_encode_batch(batch, stream)
         if timed:
             ev[1].record(stream)
-        for xd, maps, h, w, bufs, out, (vals, idx) in jobs:
-            api.fh_sparse_decode(bufs.info, vals, idx, maps, h, w, n, out=out, workspace=bufs.workspace, stream=stream,
-                                 eps=eps)
+        if args.per_tensor:
+            for xd, maps, h, w, bufs, out, (vals, idx) in jobs:
+                api.fh_sparse_decode(bufs.info, vals, idx, maps, h, w, n, out=out, workspace=bufs.workspace,
+                                     stream=stream, eps=eps)
+        else:
+            api.fh_sparse_decode_batch(batch, stream)
         if timed:
             ev[2].record(stream)
 
@@ -281,7 +290,9 @@ def bench_sparse(args, api, W, dev) -> int:
         "vs_baseline": None, "dtype": "u32", "data": "synthetic",
         "config": {"workload": "sparse_mobilenetv2_b64_kept_channels_n4_tau0.5" + (f"_eps{eps:g}" if eps > 0 else ""),
                    "map_sets": len(jobs), "input_bytes": nbytes, "stored_bytes": stored,
-                   "entry_point": "fh_sparse_encode + fh_sparse_decode", "window": n, "tau": tau, "eps": eps},
+                   "entry_point": ("fh_sparse_encode + fh_sparse_decode (per set)" if args.per_tensor
+                                   else "fh_sparse_encode_batch + fh_sparse_decode_batch"),
+                   "window": n, "tau": tau, "eps": eps},
         "roofline": {"bound": "hbm", "kernel": dom[0] + ", all launches of a step, event-timed",
                      "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},

@@ -267,6 +267,34 @@ typedef struct fh_classify_item {
 fh_status fh_classify_channels_batch(const fh_classify_item *items, int32_t count, void *stream);
 int32_t   fh_classify_batch_capacity(void);
 
+/* The same for several sets of maps (the kept channels of every layer of a model): each pass is
+ * launched once per run of up to fh_sparse_batch_capacity() items that share dtype and window.
+ * All items are checked before the first launch; results are identical to the single calls.
+ * The items' buffers must not overlap. */
+typedef struct fh_sparse_encode_item {
+    const void *x;        int32_t dtype;    int32_t n;             /* fh_dtype; window 2 | 4 | 8 */
+    int64_t     maps, h, w;
+    float       tau, eps;
+    void       *info;     size_t info_cap;
+    void       *values;   size_t values_cap;
+    void       *indices;  size_t indices_cap;
+    void       *totals;
+    void       *workspace; size_t workspace_cap;
+} fh_sparse_encode_item;
+typedef struct fh_sparse_decode_item {
+    const void *info;
+    const void *values;   size_t values_bytes;
+    const void *indices;  size_t indices_bytes;
+    int32_t     dtype;    int32_t n;
+    int64_t     maps, h, w;
+    float       eps;      int32_t reserved;                        /* 0 */
+    void       *out;      size_t out_cap;
+    void       *workspace; size_t workspace_cap;
+} fh_sparse_decode_item;
+fh_status fh_sparse_encode_batch(const fh_sparse_encode_item *items, int32_t count, void *stream);
+fh_status fh_sparse_decode_batch(const fh_sparse_decode_item *items, int32_t count, void *stream);
+int32_t   fh_sparse_batch_capacity(void);
+
 const char *fh_status_string(fh_status s);
 
 #ifdef __cplusplus

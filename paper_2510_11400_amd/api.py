@@ -34,7 +34,8 @@ EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "
            "fh_classify_batch_capacity",
            "fh_raw_bytes", "fh_channel_slots", "fh_compress_mixed", "fh_decompress_mixed",
            "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
-           "fh_sparse_decode", "fh_status_string")
+           "fh_sparse_decode", "fh_sparse_encode_batch", "fh_sparse_decode_batch", "fh_sparse_batch_capacity",
+           "fh_status_string")
 
 
 class fh_params(ctypes.Structure):
@@ -57,6 +58,26 @@ class fh_classify_item(ctypes.Structure):
                 ("k_sigma", ctypes.c_double), ("min_outliers", ctypes.c_int64),
                 ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t),
                 ("stats", ctypes.c_void_p), ("counts", ctypes.c_void_p), ("mask", ctypes.c_void_p)]
+
+
+class fh_sparse_encode_item(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("maps", ctypes.c_int64), ("h", ctypes.c_int64), ("w", ctypes.c_int64),
+                ("tau", ctypes.c_float), ("eps", ctypes.c_float),
+                ("info", ctypes.c_void_p), ("info_cap", ctypes.c_size_t),
+                ("values", ctypes.c_void_p), ("values_cap", ctypes.c_size_t),
+                ("indices", ctypes.c_void_p), ("indices_cap", ctypes.c_size_t),
+                ("totals", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t)]
+
+
+class fh_sparse_decode_item(ctypes.Structure):
+    _fields_ = [("info", ctypes.c_void_p), ("values", ctypes.c_void_p), ("values_bytes", ctypes.c_size_t),
+                ("indices", ctypes.c_void_p), ("indices_bytes", ctypes.c_size_t),
+                ("dtype", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("maps", ctypes.c_int64), ("h", ctypes.c_int64), ("w", ctypes.c_int64),
+                ("eps", ctypes.c_float), ("reserved", ctypes.c_int32),
+                ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t),
+                ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t)]
 
 
 _P = ctypes.POINTER
@@ -114,6 +135,12 @@ _lib.fh_sparse_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_siz
                                   ctypes.c_float,
                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fh_sparse_decode.restype = ctypes.c_int
+_lib.fh_sparse_encode_batch.argtypes = [_P(fh_sparse_encode_item), ctypes.c_int32, ctypes.c_void_p]
+_lib.fh_sparse_encode_batch.restype = ctypes.c_int
+_lib.fh_sparse_decode_batch.argtypes = [_P(fh_sparse_decode_item), ctypes.c_int32, ctypes.c_void_p]
+_lib.fh_sparse_decode_batch.restype = ctypes.c_int
+_lib.fh_sparse_batch_capacity.argtypes = []
+_lib.fh_sparse_batch_capacity.restype = ctypes.c_int32
 _lib.fh_batch_capacity.argtypes = []
 _lib.fh_batch_capacity.restype = ctypes.c_int32
 _lib.fh_status_string.argtypes = [ctypes.c_int]
@@ -555,3 +582,84 @@ def fh_classify_channels_batch(batch: ClassifyBatch, stream=None) -> None:
         return
     with torch.cuda.device(batch.device):
         _check(_lib.fh_classify_channels_batch(batch.items, batch.count, _stream_ptr(stream)))
+
+
+@dataclass
+class SparseEntry:
+    """One set of maps of a batched sparse encode / decode.  `buffers` are allocated when left
+    None; for decoding, `values` / `indices` are the valid prefixes of the two streams (default:
+    the whole buffers, which is safe -- the decoder reads no further than the info bytes say)."""
+    maps: int
+    h: int
+    w: int
+    n: int
+    tau: float = 0.5
+    eps: float = 0.0
+    x: Optional[torch.Tensor] = None
+    buffers: Optional[SparseBuffers] = None
+    values: Optional[torch.Tensor] = None
+    indices: Optional[torch.Tensor] = None
+    out: Optional[torch.Tensor] = None
+
+
+def sparse_batch_capacity() -> int:
+    return int(_lib.fh_sparse_batch_capacity())
+
+
+class SparseBatch:
+    """Marshalled fh_sparse_encode_item / fh_sparse_decode_item arrays, reusable across calls."""
+
+    def __init__(self, entries: Sequence[SparseEntry]):
+        self.entries: List[SparseEntry] = list(entries)
+        self.count = len(self.entries)
+        self.device = None
+        self.enc = (fh_sparse_encode_item * max(1, self.count))()
+        self.dec = (fh_sparse_decode_item * max(1, self.count))()
+        for e in self.entries:
+            ref = e.x if e.x is not None else (e.out if e.out is not None else e.buffers.values)
+            self.device = self.device or ref.device
+            if e.buffers is None:
+                e.buffers = alloc_sparse(e.maps, e.h, e.w, e.n, ref.dtype, ref.device)
+        self.refresh()
+
+    def refresh(self) -> None:
+        """Re-marshal after entries' tensors (x, out, stream prefixes) were replaced."""
+        for enc, dec, e in zip(self.enc, self.dec, self.entries):
+            b = e.buffers
+            if e.x is not None:
+                _device_tensor(e.x, "x")
+                if e.x.numel() != e.maps * e.h * e.w or e.x.dtype != b.values.dtype:
+                    raise ValueError("x does not match maps * h * w or the buffers' dtype")
+                enc.x, enc.dtype = _ptr(e.x), _dtype_code(e.x)
+            else:
+                enc.x, enc.dtype = None, _dtype_code(b.values)
+            enc.n, enc.maps, enc.h, enc.w, enc.tau, enc.eps = int(e.n), e.maps, e.h, e.w, float(e.tau), float(e.eps)
+            enc.info, enc.info_cap = b.info.data_ptr(), _nbytes(b.info)
+            enc.values, enc.values_cap = b.values.data_ptr(), _nbytes(b.values)
+            enc.indices, enc.indices_cap = b.indices.data_ptr(), _nbytes(b.indices)
+            enc.totals, enc.workspace, enc.workspace_cap = b.totals.data_ptr(), b.workspace.data_ptr(), _nbytes(b.workspace)
+            vals = e.values if e.values is not None else b.values
+            idx = e.indices if e.indices is not None else b.indices
+            dec.info = b.info.data_ptr()
+            dec.values, dec.values_bytes = _ptr(vals), _nbytes(vals)
+            dec.indices, dec.indices_bytes = _ptr(idx), _nbytes(idx)
+            dec.dtype, dec.n, dec.maps, dec.h, dec.w = _dtype_code(b.values), int(e.n), e.maps, e.h, e.w
+            dec.eps, dec.reserved = float(e.eps), 0
+            if e.out is not None:
+                _device_tensor(e.out, "out")
+                dec.out, dec.out_cap = _ptr(e.out), _nbytes(e.out)
+            else:
+                dec.out, dec.out_cap = None, 0
+            dec.workspace, dec.workspace_cap = b.workspace.data_ptr(), _nbytes(b.workspace)
+
+
+def fh_sparse_encode_batch(batch: SparseBatch, stream=None) -> None:
+    if batch.count:
+        with torch.cuda.device(batch.device):
+            _check(_lib.fh_sparse_encode_batch(batch.enc, batch.count, _stream_ptr(stream)))
+
+
+def fh_sparse_decode_batch(batch: SparseBatch, stream=None) -> None:
+    if batch.count:
+        with torch.cuda.device(batch.device):
+            _check(_lib.fh_sparse_decode_batch(batch.dec, batch.count, _stream_ptr(stream)))

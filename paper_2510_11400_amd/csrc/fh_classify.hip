@@ -19,6 +19,7 @@
 //      non-zero bin and workgroup.
 #include "../../include/fedhybrid.h"
 
+#include "fh_batch.hpp"
 #include "fh_channels.hpp"
 #include "fh_device.hpp"
 
@@ -132,30 +133,7 @@ __device__ __forceinline__ void span_tree(const double (&a)[ROWS], const double 
     }
 }
 
-// ---- batches -----------------------------------------------------------------------------
-// Every kernel serves up to kBatch tensors per launch: descriptors travel by value in the
-// kernel-argument segment and a workgroup finds its tensor by a scalar search over the
-// exclusive prefix sums of the tensors' workgroup counts (entries past the last tensor repeat
-// the total).
-constexpr int kBatch = 16;
-
-template <typename Item> struct Batch {
-    int32_t  count;
-    uint32_t block_start[kBatch + 1];
-    Item     item[kBatch];
-};
-template <typename Item>
-__device__ __forceinline__ int batch_item(const Batch<Item>& b, uint32_t bid, uint32_t& local)
-{
-    int lo = 0, hi = b.count;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (b.block_start[mid] <= bid) lo = mid; else hi = mid;
-    }
-    local = bid - b.block_start[lo];
-    return lo;
-}
-
+// ---- per-kernel descriptors (fh_batch.hpp: up to kBatch tensors per launch) ----------------
 struct MomentsItem { const void* x; int64_t numel; f64x2* partial; };
 struct ReduceItem  { const f64x2* in; int64_t count; f64x2* out; };
 struct FinishItem  {
@@ -452,22 +430,6 @@ fh_status check_item(const fh_classify_item& it, int64_t* numel_out)
     *numel_out = numel;
     return FH_OK;
 }
-
-// Append an item that needs `blocks` workgroups; false when the launch is full.
-template <typename Item>
-bool push(Batch<Item>& b, const Item& item, int64_t blocks)
-{
-    if (b.count == kBatch || (uint64_t)b.block_start[b.count] + (uint64_t)blocks > (uint64_t)INT_MAX) return false;
-    b.item[b.count] = item;
-    b.block_start[b.count + 1] = b.block_start[b.count] + (uint32_t)blocks;
-    ++b.count;
-    return true;
-}
-template <typename Item> void seal(Batch<Item>& b)
-{
-    for (int k = b.count + 1; k <= kBatch; ++k) b.block_start[k] = b.block_start[b.count];
-}
-template <typename Item> void reset(Batch<Item>& b) { b.count = 0; b.block_start[0] = 0; }
 
 // One run of up to kBatch tensors of one dtype: five kinds of launches, each covering all of them.
 fh_status run_classify(const fh_classify_item* items, const int64_t* numels, int n, hipStream_t s)

@@ -23,6 +23,7 @@
 // integer and byte work; results do not depend on launch geometry.
 #include "../../include/fedhybrid.h"
 
+#include "fh_batch.hpp"
 #include "fh_channels.hpp"
 
 namespace fh {
@@ -68,6 +69,21 @@ __device__ __forceinline__ TilePos tile_pos(const MapShape& s, uint32_t b)
     t.origin = ((uint64_t)m * s.h + r0) * s.w + c0;
     return t;
 }
+
+// One set of maps in a launch (fh_batch.hpp: a launch serves up to kBatch of them).
+struct Job {
+    MapShape  shape;           // x: the maps (encode: input; decode: output)
+    uint8_t*  info;            // one byte per tile (encode: written; decode: read)
+    Sums*     wg;              // per-workgroup sums, or their exclusive prefixes once `scanned`
+    void*     values;          // the two streams (encode: written; decode: read)
+    uint8_t*  indices;
+    uint64_t* totals;          // encode: {values, index bytes, sparse tiles, dense tiles}; may be null
+    uint64_t  value_count;     // decode: valid prefix of the streams
+    uint64_t  index_count;
+    float     tau;
+    uint32_t  scanned;         // this set has so many workgroups that a scan kernel runs between the passes
+    uint32_t  wg_count;
+};
 
 // what a tile with this info byte adds to the streams
 __device__ __forceinline__ Sums tile_sums(uint32_t info, const TilePos& t, bool predictive)
@@ -245,22 +261,27 @@ __device__ __forceinline__ void store_tile(Bits* out, const TilePos& t, uint32_t
 // What the tiles of all earlier workgroups write.  `scanned`: wg[] already holds exclusive
 // prefixes (the scan kernel ran); otherwise it holds per-workgroup sums and they are added up
 // here, 256 at a time.
-__device__ __forceinline__ Sums workgroup_base(const Sums* __restrict__ wg, bool scanned, uint64_t* lds)
+__device__ __forceinline__ Sums workgroup_base(const Sums* __restrict__ wg, bool scanned, uint32_t block,
+                                               uint64_t* lds)
 {
-    if (scanned) return wg[blockIdx.x];
+    if (scanned) return wg[block];
     Sums part = {0, 0, 0};
-    for (uint32_t i = threadIdx.x; i < blockIdx.x; i += kTileThreads) part = part + wg[i];
+    for (uint32_t i = threadIdx.x; i < block; i += kTileThreads) part = part + wg[i];
     return workgroup_sum(part, lds);
 }
 
 // ---- pass 1 (encode): non-zero count, density, info byte, workgroup sums ---------------------
 template <typename Bits, int N>
-__global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const MapShape s, const float tau,
-                                                                    uint8_t* __restrict__ info,
-                                                                    Sums* __restrict__ wg_sums)
+__global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const Batch<Job> batch)
 {
     __shared__ uint64_t lds[3 * kTileWaves];
-    const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
+    uint32_t block;
+    const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
+    const MapShape& s = job.shape;
+    const float tau = job.tau;
+    uint8_t* info = job.info;
+    Sums* wg_sums = job.wg;
+    const uint32_t b = block * kTileThreads + threadIdx.x;
     Sums mine = {0, 0, 0};
     if (b < s.tiles) {
         const TilePos t = tile_pos(s, b);
@@ -283,26 +304,33 @@ __global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const MapSha
     }
     Sums total;
     workgroup_exclusive_scan(mine, lds, &total);
-    if (threadIdx.x == 0) wg_sums[blockIdx.x] = total;
+    if (threadIdx.x == 0) wg_sums[block] = total;
 }
 
 // ---- pass 1 (decode): workgroup sums from the info bytes --------------------------------------
-__global__ __launch_bounds__(kTileThreads) void sparse_sums_kernel(const MapShape s, const uint8_t* __restrict__ info,
-                                                                   Sums* __restrict__ wg_sums)
+__global__ __launch_bounds__(kTileThreads) void sparse_sums_kernel(const Batch<Job> batch)
 {
     __shared__ uint64_t lds[3 * kTileWaves];
-    const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
+    uint32_t block;
+    const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
+    const MapShape& s = job.shape;
+    const uint32_t b = block * kTileThreads + threadIdx.x;
     Sums mine = {0, 0, 0};
-    if (b < s.tiles) mine = tile_sums(info[b], tile_pos(s, b), s.two_eps > 0.0f);
+    if (b < s.tiles) mine = tile_sums(job.info[b], tile_pos(s, b), s.two_eps > 0.0f);
     Sums total;
     workgroup_exclusive_scan(mine, lds, &total);
-    if (threadIdx.x == 0) wg_sums[blockIdx.x] = total;
+    if (threadIdx.x == 0) job.wg[block] = total;
 }
 
 // ---- pass 2: exclusive scan of the workgroup sums, in place; totals -----------------------------
-__global__ __launch_bounds__(kScanThreads) void sparse_scan_kernel(Sums* __restrict__ wg_sums, uint32_t count,
-                                                                   uint32_t tiles, uint64_t* __restrict__ totals)
+// one workgroup per set; sets with few workgroups skip it (their workgroups add up the sums themselves)
+__global__ __launch_bounds__(kScanThreads) void sparse_scan_kernel(const Batch<Job> batch)
 {
+    const Job& job = batch.item[blockIdx.x];
+    if (!job.scanned) return;                                 // workgroup-uniform
+    Sums* wg_sums = job.wg;
+    const uint32_t count = job.wg_count, tiles = job.shape.tiles;
+    uint64_t* totals = job.totals;
     __shared__ Sums lds[kScanThreads];
     const int t = threadIdx.x;
     Sums carry = {0, 0, 0};
@@ -337,14 +365,19 @@ __global__ __launch_bounds__(kScanThreads) void sparse_scan_kernel(Sums* __restr
 
 // ---- pass 3 (encode): values and CSR structure to their place ---------------------------------------
 template <typename Bits, int N>
-__global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapShape s, const uint8_t* __restrict__ info,
-                                                                    const Sums* __restrict__ wg, const bool scanned,
-                                                                    Bits* __restrict__ values,
-                                                                    uint8_t* __restrict__ indices,
-                                                                    uint64_t* __restrict__ totals)
+__global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const Batch<Job> batch)
 {
     __shared__ uint64_t lds[3 * kTileWaves];
-    const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
+    uint32_t block;
+    const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
+    const MapShape& s = job.shape;
+    const uint8_t* info = job.info;
+    const Sums* wg = job.wg;
+    const bool scanned = job.scanned != 0u;
+    Bits* values = static_cast<Bits*>(job.values);
+    uint8_t* indices = job.indices;
+    uint64_t* totals = job.totals;
+    const uint32_t b = block * kTileThreads + threadIdx.x;
     const bool live = b < s.tiles;
     TilePos t = {0, 1, 1};
     uint32_t byte = 0x80u;
@@ -356,10 +389,10 @@ __global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapSha
         mine = tile_sums(byte, t, s.two_eps > 0.0f);
         load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, s.rows_are_vectors != 0u, e);
     }
-    const Sums base = workgroup_base(wg, scanned, lds);
+    const Sums base = workgroup_base(wg, scanned, block, lds);
     Sums total;
     const Sums before = workgroup_exclusive_scan(mine, lds, &total);
-    if (!scanned && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+    if (!scanned && totals && block == job.wg_count - 1 && threadIdx.x == 0) {
         totals[0] = base.values + total.values;
         totals[1] = base.index_bytes + total.index_bytes;
         totals[2] = base.sparse_tiles + total.sparse_tiles;
@@ -410,14 +443,19 @@ __global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const MapSha
 // A stream this library did not write must not make the kernel read or write out of bounds:
 // a tile whose slice would leave a stream is zero-filled, entries outside the tile are dropped.
 template <typename Bits, int N>
-__global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShape s, const uint8_t* __restrict__ info,
-                                                                   const Sums* __restrict__ wg, const bool scanned,
-                                                                   const Bits* __restrict__ values, uint64_t value_count,
-                                                                   const uint8_t* __restrict__ indices,
-                                                                   uint64_t index_count)
+__global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const Batch<Job> batch)
 {
     __shared__ uint64_t lds[3 * kTileWaves];
-    const uint32_t b = blockIdx.x * kTileThreads + threadIdx.x;
+    uint32_t block;
+    const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
+    const MapShape& s = job.shape;
+    const uint8_t* info = job.info;
+    const Sums* wg = job.wg;
+    const bool scanned = job.scanned != 0u;
+    const Bits* values = static_cast<const Bits*>(job.values);
+    const uint64_t value_count = job.value_count, index_count = job.index_count;
+    const uint8_t* indices = job.indices;
+    const uint32_t b = block * kTileThreads + threadIdx.x;
     const bool live = b < s.tiles;
     TilePos t = {0, 1, 1};
     uint32_t byte = 0x80u;
@@ -427,7 +465,7 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const MapShap
         byte = info[b];
         mine = tile_sums(byte, t, s.two_eps > 0.0f);
     }
-    const Sums base = workgroup_base(wg, scanned, lds);
+    const Sums base = workgroup_base(wg, scanned, block, lds);
     Sums total;
     const Sums before = workgroup_exclusive_scan(mine, lds, &total);
     if (!live) return;
@@ -586,53 +624,189 @@ size_t fh_sparse_workspace_bytes(int64_t maps, int64_t h, int64_t w, int32_t n)
     return sizeof(fh::Sums) * (size_t)(fh::workgroups(t) > 0 ? fh::workgroups(t) : 1);
 }
 
+}  // extern "C"
+
+namespace {
+
+using namespace fh;
+
+fh_status check_encode(const fh_sparse_encode_item& it, int64_t* tiles)
+{
+    if (it.dtype != FH_F32 && it.dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    const fh_status st = check_shape(it.maps, it.h, it.w, it.n, tiles);
+    if (st != FH_OK) return st;
+    if (!it.totals || !it.workspace) return FH_ERR_NULL;
+    if (!aligned(it.totals, 8) || !aligned(it.workspace, 8)) return FH_ERR_ALIGNMENT;
+    if (it.workspace_cap < fh_sparse_workspace_bytes(it.maps, it.h, it.w, it.n)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (*tiles == 0) return FH_OK;
+    if (!it.x || !it.info || !it.values || !it.indices) return FH_ERR_NULL;
+    if (!aligned(it.x, 4) || !aligned(it.values, 4)) return FH_ERR_ALIGNMENT;
+    if (it.info_cap < (size_t)*tiles || it.values_cap < (size_t)(it.maps * it.h * it.w) * elem_size(it.dtype) ||
+        it.indices_cap < fh_sparse_index_bytes(it.maps, it.h, it.w, it.n))
+        return FH_ERR_BUFFER_TOO_SMALL;
+    return FH_OK;
+}
+
+fh_status check_decode(const fh_sparse_decode_item& it, int64_t* tiles)
+{
+    if (it.dtype != FH_F32 && it.dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    const fh_status st = check_shape(it.maps, it.h, it.w, it.n, tiles);
+    if (st != FH_OK) return st;
+    if (*tiles == 0) return FH_OK;
+    if (!it.info || !it.out || !it.workspace) return FH_ERR_NULL;
+    if ((it.values_bytes > 0 && !it.values) || (it.indices_bytes > 0 && !it.indices)) return FH_ERR_NULL;
+    if (!aligned(it.out, 4) || !aligned(it.values, 4) || !aligned(it.workspace, 8)) return FH_ERR_ALIGNMENT;
+    if (it.workspace_cap < fh_sparse_workspace_bytes(it.maps, it.h, it.w, it.n)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (it.out_cap < (size_t)(it.maps * it.h * it.w) * elem_size(it.dtype)) return FH_ERR_BUFFER_TOO_SMALL;
+    return FH_OK;
+}
+
+template <typename Kernel>
+void launch_tiles(Kernel kernel, const Batch<Job>& b, hipStream_t s)
+{
+    if (b.count > 0) hipLaunchKernelGGL(kernel, dim3(b.block_start[b.count]), dim3(kTileThreads), 0, s, b);
+}
+
+// the (dtype, window) instantiation of a templated pass
+#define FH_SPARSE_PICK(KERNEL, DTYPE, NN)                                                         \
+    ((DTYPE) == FH_F32 ? ((NN) == 2 ? KERNEL<uint32_t, 2> : (NN) == 4 ? KERNEL<uint32_t, 4> : KERNEL<uint32_t, 8>)  \
+                       : ((NN) == 2 ? KERNEL<uint16_t, 2> : (NN) == 4 ? KERNEL<uint16_t, 4> : KERNEL<uint16_t, 8>))
+
+// jobs of one run (same dtype and window): every set with tiles in `tiled`, all sets in `all`
+struct Run {
+    Batch<Job> tiled, all;
+    bool any_scan;
+};
+
+void add_job(Run& run, Job job, int64_t tiles)
+{
+    job.wg_count = workgroups(tiles);
+    job.scanned = (tiles == 0 || job.wg_count > kSelfScanLimit) ? 1u : 0u;   // an empty set: the scan kernel writes its totals
+    if (job.scanned) run.any_scan = true;
+    if (tiles > 0) push(run.tiled, job, job.wg_count);
+    push(run.all, job, 1);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t fh_sparse_batch_capacity(void) { return fh::kBatch; }
+
+fh_status fh_sparse_encode_batch(const fh_sparse_encode_item* items, int32_t count, void* stream)
+{
+    if (count < 0) return FH_ERR_BAD_COUNT;
+    if (count > 0 && !items) return FH_ERR_NULL;
+    for (int32_t i = 0; i < count; ++i) {                     // everything is checked before the first launch
+        int64_t tiles;
+        const fh_status st = check_encode(items[i], &tiles);
+        if (st != FH_OK) return st;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    bool launched = false;
+    int32_t i = 0;
+    while (i < count) {                                       // runs of one dtype and window, at most kBatch long
+        Run run;
+        reset(run.tiled);
+        reset(run.all);
+        run.any_scan = false;
+        const int dtype = items[i].dtype, n = items[i].n;
+        while (i < count && run.all.count < kBatch && items[i].dtype == dtype && items[i].n == n) {
+            const fh_sparse_encode_item& it = items[i];
+            int64_t tiles;
+            check_encode(it, &tiles);
+            if ((uint64_t)run.tiled.block_start[run.tiled.count] + workgroups(tiles) > (uint64_t)INT_MAX) {
+                if (run.all.count == 0) return FH_ERR_BAD_NUMEL;
+                break;
+            }
+            Job job;
+            job.shape = make_shape(it.x, it.h, it.w, it.n, tiles, it.eps);
+            job.info = static_cast<uint8_t*>(it.info);
+            job.wg = static_cast<Sums*>(it.workspace);
+            job.values = it.values;
+            job.indices = static_cast<uint8_t*>(it.indices);
+            job.totals = static_cast<uint64_t*>(it.totals);
+            job.value_count = job.index_count = 0;
+            job.tau = it.tau;
+            add_job(run, job, tiles);
+            ++i;
+        }
+        launched = true;
+        seal(run.tiled);
+        seal(run.all);
+        launch_tiles(FH_SPARSE_PICK(sparse_count_kernel, dtype, n), run.tiled, s);
+        if (run.any_scan)
+            hipLaunchKernelGGL(sparse_scan_kernel, dim3(run.all.count), dim3(kScanThreads), 0, s, run.all);
+        launch_tiles(FH_SPARSE_PICK(sparse_write_kernel, dtype, n), run.tiled, s);
+    }
+    if (!launched) return FH_OK;
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+fh_status fh_sparse_decode_batch(const fh_sparse_decode_item* items, int32_t count, void* stream)
+{
+    if (count < 0) return FH_ERR_BAD_COUNT;
+    if (count > 0 && !items) return FH_ERR_NULL;
+    for (int32_t i = 0; i < count; ++i) {
+        int64_t tiles;
+        const fh_status st = check_decode(items[i], &tiles);
+        if (st != FH_OK) return st;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    bool launched = false;
+    int32_t i = 0;
+    while (i < count) {
+        Run run;
+        reset(run.tiled);
+        reset(run.all);
+        run.any_scan = false;
+        const int dtype = items[i].dtype, n = items[i].n;
+        while (i < count && run.all.count < kBatch && items[i].dtype == dtype && items[i].n == n) {
+            const fh_sparse_decode_item& it = items[i];
+            int64_t tiles;
+            check_decode(it, &tiles);
+            if (tiles == 0) { ++i; continue; }                // nothing to restore
+            if ((uint64_t)run.tiled.block_start[run.tiled.count] + workgroups(tiles) > (uint64_t)INT_MAX) {
+                if (run.all.count == 0) return FH_ERR_BAD_NUMEL;
+                break;
+            }
+            Job job;
+            job.shape = make_shape(it.out, it.h, it.w, it.n, tiles, it.eps);
+            job.info = const_cast<uint8_t*>(static_cast<const uint8_t*>(it.info));
+            job.wg = static_cast<Sums*>(it.workspace);
+            job.values = const_cast<void*>(it.values);
+            job.indices = const_cast<uint8_t*>(static_cast<const uint8_t*>(it.indices));
+            job.totals = nullptr;
+            job.value_count = it.values_bytes / elem_size(it.dtype);
+            job.index_count = it.indices_bytes;
+            job.tau = 0.0f;
+            add_job(run, job, tiles);
+            ++i;
+        }
+        if (run.tiled.count == 0) continue;                   // only empty sets in this run
+        launched = true;
+        seal(run.tiled);
+        seal(run.all);
+        launch_tiles(sparse_sums_kernel, run.tiled, s);
+        if (run.any_scan)
+            hipLaunchKernelGGL(sparse_scan_kernel, dim3(run.all.count), dim3(kScanThreads), 0, s, run.all);
+        launch_tiles(FH_SPARSE_PICK(sparse_read_kernel, dtype, n), run.tiled, s);
+    }
+    if (!launched) return FH_OK;
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
 fh_status fh_sparse_encode(const void* x, fh_dtype dtype, int64_t maps, int64_t h, int64_t w, int32_t n, float tau,
                            float eps, void* info, size_t info_cap, void* values, size_t values_cap,
                            void* indices, size_t indices_cap, void* totals,
                            void* workspace, size_t workspace_cap, void* stream)
 {
-    using namespace fh;
-    if (dtype != FH_F32 && dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
-    int64_t tiles = 0;
-    const fh_status st = check_shape(maps, h, w, n, &tiles);
-    if (st != FH_OK) return st;
-    if (!totals || !workspace) return FH_ERR_NULL;
-    if (!aligned(totals, 8) || !aligned(workspace, 8)) return FH_ERR_ALIGNMENT;
-    if (workspace_cap < fh_sparse_workspace_bytes(maps, h, w, n)) return FH_ERR_BUFFER_TOO_SMALL;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    Sums* wg = static_cast<Sums*>(workspace);
-    if (tiles == 0) {                                         // nothing to store: totals are all zero
-        hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, 0u, 0u,
-                           static_cast<uint64_t*>(totals));
-        return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
-    }
-    if (!x || !info || !values || !indices) return FH_ERR_NULL;
-    if (!aligned(x, 4) || !aligned(values, 4)) return FH_ERR_ALIGNMENT;
-    if (info_cap < (size_t)tiles || values_cap < (size_t)(maps * h * w) * elem_size(dtype) ||
-        indices_cap < fh_sparse_index_bytes(maps, h, w, n))
-        return FH_ERR_BUFFER_TOO_SMALL;
-
-    const MapShape shape = make_shape(x, h, w, n, tiles, eps);
-    const dim3 grid(workgroups(tiles)), block(kTileThreads);
-    uint8_t* inf = static_cast<uint8_t*>(info);
-    uint8_t* idx = static_cast<uint8_t*>(indices);
-    const bool scan = grid.x > kSelfScanLimit;
-#define FH_SPARSE_ENCODE(BITS, NN)                                                                              \
-    do {                                                                                                        \
-        hipLaunchKernelGGL((sparse_count_kernel<BITS, NN>), grid, block, 0, s, shape, tau, inf, wg);            \
-        if (scan)                                                                                               \
-            hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, grid.x,               \
-                               (uint32_t)tiles, static_cast<uint64_t*>(totals));                                \
-        hipLaunchKernelGGL((sparse_write_kernel<BITS, NN>), grid, block, 0, s, shape, inf, wg, scan,            \
-                           static_cast<BITS*>(values), idx, static_cast<uint64_t*>(totals));                    \
-    } while (0)
-    if (dtype == FH_F32) {
-        if (n == 2) FH_SPARSE_ENCODE(uint32_t, 2); else if (n == 4) FH_SPARSE_ENCODE(uint32_t, 4); else FH_SPARSE_ENCODE(uint32_t, 8);
-    } else {
-        if (n == 2) FH_SPARSE_ENCODE(uint16_t, 2); else if (n == 4) FH_SPARSE_ENCODE(uint16_t, 4); else FH_SPARSE_ENCODE(uint16_t, 8);
-    }
-#undef FH_SPARSE_ENCODE
-    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+    fh_sparse_encode_item it;
+    it.x = x; it.dtype = dtype; it.n = n; it.maps = maps; it.h = h; it.w = w; it.tau = tau; it.eps = eps;
+    it.info = info; it.info_cap = info_cap; it.values = values; it.values_cap = values_cap;
+    it.indices = indices; it.indices_cap = indices_cap; it.totals = totals;
+    it.workspace = workspace; it.workspace_cap = workspace_cap;
+    return fh_sparse_encode_batch(&it, 1, stream);
 }
 
 fh_status fh_sparse_decode(const void* info, const void* values, size_t values_bytes,
@@ -640,40 +814,12 @@ fh_status fh_sparse_decode(const void* info, const void* values, size_t values_b
                            int64_t maps, int64_t h, int64_t w, int32_t n, float eps,
                            void* out, size_t out_cap, void* workspace, size_t workspace_cap, void* stream)
 {
-    using namespace fh;
-    if (dtype != FH_F32 && dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
-    int64_t tiles = 0;
-    const fh_status st = check_shape(maps, h, w, n, &tiles);
-    if (st != FH_OK) return st;
-    if (tiles == 0) return FH_OK;
-    if (!info || !out || !workspace) return FH_ERR_NULL;
-    if ((values_bytes > 0 && !values) || (indices_bytes > 0 && !indices)) return FH_ERR_NULL;
-    if (!aligned(out, 4) || !aligned(values, 4) || !aligned(workspace, 8)) return FH_ERR_ALIGNMENT;
-    if (workspace_cap < fh_sparse_workspace_bytes(maps, h, w, n)) return FH_ERR_BUFFER_TOO_SMALL;
-    if (out_cap < (size_t)(maps * h * w) * elem_size(dtype)) return FH_ERR_BUFFER_TOO_SMALL;
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    Sums* wg = static_cast<Sums*>(workspace);
-    const MapShape shape = make_shape(out, h, w, n, tiles, eps);
-    const dim3 grid(workgroups(tiles)), block(kTileThreads);
-    const uint8_t* inf = static_cast<const uint8_t*>(info);
-    const uint8_t* idx = static_cast<const uint8_t*>(indices);
-    const uint64_t nvals = values_bytes / elem_size(dtype);
-    const bool scan = grid.x > kSelfScanLimit;
-    hipLaunchKernelGGL(sparse_sums_kernel, grid, block, 0, s, shape, inf, wg);
-    if (scan)
-        hipLaunchKernelGGL(sparse_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, wg, grid.x, (uint32_t)tiles,
-                           static_cast<uint64_t*>(nullptr));
-#define FH_SPARSE_DECODE(BITS, NN)                                                                        \
-    hipLaunchKernelGGL((sparse_read_kernel<BITS, NN>), grid, block, 0, s, shape, inf, wg, scan,           \
-                       static_cast<const BITS*>(values), nvals, idx, (uint64_t)indices_bytes)
-    if (dtype == FH_F32) {
-        if (n == 2) FH_SPARSE_DECODE(uint32_t, 2); else if (n == 4) FH_SPARSE_DECODE(uint32_t, 4); else FH_SPARSE_DECODE(uint32_t, 8);
-    } else {
-        if (n == 2) FH_SPARSE_DECODE(uint16_t, 2); else if (n == 4) FH_SPARSE_DECODE(uint16_t, 4); else FH_SPARSE_DECODE(uint16_t, 8);
-    }
-#undef FH_SPARSE_DECODE
-    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+    fh_sparse_decode_item it;
+    it.info = info; it.values = values; it.values_bytes = values_bytes;
+    it.indices = indices; it.indices_bytes = indices_bytes;
+    it.dtype = dtype; it.n = n; it.maps = maps; it.h = h; it.w = w; it.eps = eps; it.reserved = 0;
+    it.out = out; it.out_cap = out_cap; it.workspace = workspace; it.workspace_cap = workspace_cap;
+    return fh_sparse_decode_batch(&it, 1, stream);
 }
 
 }  // extern "C"

@@ -267,3 +267,22 @@ def test_classify_item_layout_and_batch_argument_checks():
     assert f(arr, 2, None) == 2
     arr = (api.fh_classify_item * 1)(item(workspace_cap=8))
     assert f(arr, 1, None) == 7
+
+
+def test_sparse_item_layouts_and_batch_argument_checks():
+    assert ctypes.sizeof(api.fh_sparse_encode_item) == 8 + 8 + 24 + 8 + 6 * 8 + 8 + 16 == 120
+    assert api.fh_sparse_encode_item.tau.offset == 40 and api.fh_sparse_encode_item.info.offset == 48
+    assert api.fh_sparse_encode_item.totals.offset == 96 and api.fh_sparse_encode_item.workspace_cap.offset == 112
+    assert ctypes.sizeof(api.fh_sparse_decode_item) == 5 * 8 + 8 + 24 + 8 + 4 * 8 == 112
+    assert api.fh_sparse_decode_item.dtype.offset == 40 and api.fh_sparse_decode_item.eps.offset == 72
+    assert api.fh_sparse_decode_item.out.offset == 80
+    assert api.sparse_batch_capacity() == 16
+    lib = api.raw_library()
+    for f in (lib.fh_sparse_encode_batch, lib.fh_sparse_decode_batch):
+        assert f(None, 0, None) == 0 and f(None, 2, None) == 1 and f(None, -1, None) == 10
+    good = api.fh_sparse_encode_item(FAKE, 0, 4, 4, 10, 10, 0.5, 0.0, FAKE, 1 << 20, FAKE, 1 << 20, FAKE, 1 << 20,
+                                     FAKE, FAKE, 1 << 20)
+    bad = api.fh_sparse_encode_item(FAKE, 0, 3, 4, 10, 10, 0.5, 0.0, FAKE, 1 << 20, FAKE, 1 << 20, FAKE, 1 << 20,
+                                    FAKE, FAKE, 1 << 20)
+    arr = (api.fh_sparse_encode_item * 2)(good, bad)
+    assert lib.fh_sparse_encode_batch(arr, 2, None) == 12          # found before any launch

@@ -320,3 +320,34 @@ def test_the_whole_channel_wise_chain_can_be_captured_in_a_graph_and_replayed(ap
         assert np.array_equal(packed.cpu().numpy(), p), f"replay {rep}: codes"
         assert np.array_equal(meta.cpu().numpy().view(np.uint32), m.view(np.uint32)), f"replay {rep}: meta"
         assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32)), f"replay {rep}: restored"
+
+
+# ---- the batched calls ---------------------------------------------------------------------------
+
+def test_batched_calls_match_the_oracle_for_every_set(api):
+    """More sets than one launch holds, both dtypes and all windows (several runs), an empty set,
+    a set large enough for the scan kernel, with and without an error bound."""
+    specs = [(3, 28, 28, 4, "f32", 0.0), (5, 14, 14, 4, "f32", 0.02), (0, 9, 9, 4, "f32", 0.0), (2, 56, 56, 8, "f32", 0.05),
+             (4, 13, 29, 2, "bf16", 0.0), (9000, 16, 16, 2, "f32", 0.0), (7, 7, 7, 8, "bf16", 0.1)]
+    specs += [(2 + i, 10 + i, 12 + 2 * i, 4, "f32", 0.01 * (i % 3)) for i in range(14)]
+    entries, host = [], []
+    for i, (maps, h, w, n, dtype, eps) in enumerate(specs):
+        x = W.salient_feature_maps(max(maps, 1), h, w, seed=50 + i, zero_level=0.2, dtype=dtype)[: maps * h * w]
+        host.append(x)
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        xd = _device(x, dtype) if x.size else torch.empty(0, dtype=tdt, device="cuda")
+        entries.append(api.SparseEntry(maps, h, w, n, 0.45, eps, x=xd, out=torch.empty(x.size, dtype=tdt, device="cuda")))
+    assert len(entries) > api.sparse_batch_capacity()
+    batch = api.SparseBatch(entries)
+    print(f"[sparse] batch of {len(entries)} map sets", flush=True)
+    api.fh_sparse_encode_batch(batch)
+    api.fh_sparse_decode_batch(batch)                         # whole buffers as streams: bounded by the info bytes
+    torch.cuda.synchronize()
+    for i, ((maps, h, w, n, dtype, eps), x, e) in enumerate(zip(specs, host, entries)):
+        info, v, idx, totals = oracle.sparse_encode(x, maps, h, w, n, 0.45, dtype=dtype, eps=eps)
+        assert np.array_equal(e.buffers.totals.cpu().numpy().view(np.uint64), totals), f"set {i}: totals"
+        assert np.array_equal(e.buffers.info.cpu().numpy()[:info.size], info), f"set {i}: info"
+        assert np.array_equal(_bits(_host(e.buffers.values, dtype)[:v.size]), _bits(v)), f"set {i}: values"
+        assert np.array_equal(e.buffers.indices.cpu().numpy()[:idx.size], idx), f"set {i}: indices"
+        want = oracle.sparse_decode(info, v, idx, maps, h, w, n, dtype=dtype, eps=eps)
+        assert np.array_equal(_bits(_host(e.out, dtype)), _bits(want)), f"set {i}: restored"
