@@ -145,16 +145,26 @@ def bench_mixed(args, api, W, dev) -> int:
     stream = torch.cuda.current_stream()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
+    batch = api.MixedBatch([api.MixedEntry(outer, C, inner, slots, cap, G, B, rounding, 1, tid, x=xd, packed=packed,
+                                           meta=meta, raw=raw, out=out)
+                            for xd, outer, C, inner, slots, cap, packed, meta, raw, out, tid in jobs])
+
     def step(timed=False):
         if timed:
             ev[0].record(stream)
-        for xd, outer, C, inner, slots, cap, packed, meta, raw, out, tid in jobs:
-            api.fh_compress_mixed(xd, outer, C, inner, slots, cap, G, B, rounding, 1, tid, packed=packed, meta=meta,
-                                  raw=raw, stream=stream)
+        if args.per_tensor:
+            for xd, outer, C, inner, slots, cap, packed, meta, raw, out, tid in jobs:
+                api.fh_compress_mixed(xd, outer, C, inner, slots, cap, G, B, rounding, 1, tid, packed=packed,
+                                      meta=meta, raw=raw, stream=stream)
+        else:
+            api.fh_compress_mixed_batch(batch, stream)
         if timed:
             ev[1].record(stream)
-        for xd, outer, C, inner, slots, cap, packed, meta, raw, out, tid in reversed(jobs):
-            api.fh_decompress_mixed(packed, meta, raw, outer, C, inner, slots, cap, G, B, out=out, stream=stream)
+        if args.per_tensor:
+            for xd, outer, C, inner, slots, cap, packed, meta, raw, out, tid in reversed(jobs):
+                api.fh_decompress_mixed(packed, meta, raw, outer, C, inner, slots, cap, G, B, out=out, stream=stream)
+        else:
+            api.fh_decompress_mixed_batch(batch, stream)
         if timed:
             ev[2].record(stream)
 
@@ -179,11 +189,13 @@ def bench_mixed(args, api, W, dev) -> int:
         "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "mixed_mobilenetv2_b64_outlier_channels_g128_b4_nearest", "tensors": len(jobs),
-                   "input_bytes": nbytes, "entry_point": "fh_compress_mixed + fh_decompress_mixed (per tensor)",
+                   "input_bytes": nbytes,
+                   "entry_point": ("fh_compress_mixed + fh_decompress_mixed (per tensor)" if args.per_tensor
+                                   else "fh_compress_mixed_batch + fh_decompress_mixed_batch"),
                    "kept_channels": [int(c) for _, _, c in host]},
         "round_trip_algorithmic_bytes": alg_c + alg_d,
         "hbm_frac_round_trip": round((alg_c + alg_d) / elapsed / 1e9 / HBM_PEAK_GBS, 4),
-        "roofline": {"bound": "hbm", "kernel": dom[0] + " (all launches of a step, event-timed)",
+        "roofline": {"bound": "hbm", "kernel": dom[0] + " (event-timed)",
                      "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},
         "kernels": {"compress_mixed_kernel": {"ms": round(ms_c, 4), "bytes": alg_c,

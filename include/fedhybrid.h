@@ -200,6 +200,26 @@ fh_status fh_decompress_mixed(const void *packed, const void *meta, const void *
                               const fh_params *params, const void *slots, int64_t raw_channels,
                               fh_dtype out_dtype, void *out, size_t out_cap, void *stream);
 
+/* The same two calls for several tensors (one launch per run of up to fh_mixed_batch_capacity()
+ * items that share dtype and group size; items with no element are skipped; everything is
+ * checked before the first launch; results identical to the single calls).  Compression uses
+ * x, x_dtype, the shape, slots, raw_channels, packed, meta, raw (whose dtype is x_dtype) and
+ * params; decompression uses packed, meta, raw, raw_dtype, the shape, slots, raw_channels, out,
+ * out_dtype and params. */
+typedef struct fh_mixed_item {
+    const void *x;          int32_t x_dtype;   int32_t out_dtype;   /* fh_dtype */
+    int64_t     outer, channels, inner;
+    const void *slots;      int64_t raw_channels;
+    void       *packed;     size_t packed_cap;
+    void       *meta;       size_t meta_cap;
+    void       *raw;        size_t raw_cap;    int32_t raw_dtype;   int32_t reserved;
+    void       *out;        size_t out_cap;
+    fh_params   params;
+} fh_mixed_item;
+fh_status fh_compress_mixed_batch(const fh_mixed_item *items, int32_t count, void *stream);
+fh_status fh_decompress_mixed_batch(const fh_mixed_item *items, int32_t count, void *stream);
+int32_t   fh_mixed_batch_capacity(void);
+
 /* ---- sparse-block storage of salient-channel feature maps -----------------------------------
  * Section 4.4.1 stores an outlier-rich channel block-wise: a binary mask marks the non-zero
  * values of the h x w map, average pooling with an n x n window turns it into a density per

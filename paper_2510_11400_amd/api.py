@@ -33,6 +33,7 @@ EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "
            "fh_classify_workspace_bytes", "fh_classify_channels", "fh_classify_channels_batch",
            "fh_classify_batch_capacity",
            "fh_raw_bytes", "fh_channel_slots", "fh_compress_mixed", "fh_decompress_mixed",
+           "fh_compress_mixed_batch", "fh_decompress_mixed_batch", "fh_mixed_batch_capacity",
            "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
            "fh_sparse_decode", "fh_sparse_encode_batch", "fh_sparse_decode_batch", "fh_sparse_batch_capacity",
            "fh_status_string")
@@ -58,6 +59,18 @@ class fh_classify_item(ctypes.Structure):
                 ("k_sigma", ctypes.c_double), ("min_outliers", ctypes.c_int64),
                 ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t),
                 ("stats", ctypes.c_void_p), ("counts", ctypes.c_void_p), ("mask", ctypes.c_void_p)]
+
+
+class fh_mixed_item(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("x_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("outer", ctypes.c_int64), ("channels", ctypes.c_int64), ("inner", ctypes.c_int64),
+                ("slots", ctypes.c_void_p), ("raw_channels", ctypes.c_int64),
+                ("packed", ctypes.c_void_p), ("packed_cap", ctypes.c_size_t),
+                ("meta", ctypes.c_void_p), ("meta_cap", ctypes.c_size_t),
+                ("raw", ctypes.c_void_p), ("raw_cap", ctypes.c_size_t),
+                ("raw_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t),
+                ("params", fh_params)]
 
 
 class fh_sparse_encode_item(ctypes.Structure):
@@ -135,6 +148,11 @@ _lib.fh_sparse_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_siz
                                   ctypes.c_float,
                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.fh_sparse_decode.restype = ctypes.c_int
+for _name in ("fh_compress_mixed_batch", "fh_decompress_mixed_batch"):
+    getattr(_lib, _name).argtypes = [_P(fh_mixed_item), ctypes.c_int32, ctypes.c_void_p]
+    getattr(_lib, _name).restype = ctypes.c_int
+_lib.fh_mixed_batch_capacity.argtypes = []
+_lib.fh_mixed_batch_capacity.restype = ctypes.c_int32
 _lib.fh_sparse_encode_batch.argtypes = [_P(fh_sparse_encode_item), ctypes.c_int32, ctypes.c_void_p]
 _lib.fh_sparse_encode_batch.restype = ctypes.c_int
 _lib.fh_sparse_decode_batch.argtypes = [_P(fh_sparse_decode_item), ctypes.c_int32, ctypes.c_void_p]
@@ -663,3 +681,78 @@ def fh_sparse_decode_batch(batch: SparseBatch, stream=None) -> None:
     if batch.count:
         with torch.cuda.device(batch.device):
             _check(_lib.fh_sparse_decode_batch(batch.dec, batch.count, _stream_ptr(stream)))
+
+
+@dataclass
+class MixedEntry:
+    """One tensor of a batched mixed compress / decompress; buffers left None are allocated."""
+    outer: int
+    channels: int
+    inner: int
+    slots: torch.Tensor
+    raw_channels: int
+    group_size: int
+    bits: int
+    rounding: object = "nearest"
+    seed: int = 0
+    tensor_id: int = 0
+    x: Optional[torch.Tensor] = None
+    packed: Optional[torch.Tensor] = None
+    meta: Optional[torch.Tensor] = None
+    raw: Optional[torch.Tensor] = None
+    out: Optional[torch.Tensor] = None
+
+
+def mixed_batch_capacity() -> int:
+    return int(_lib.fh_mixed_batch_capacity())
+
+
+class MixedBatch:
+    """A marshalled fh_mixed_item array, reusable across calls (the buffers are fixed)."""
+
+    def __init__(self, entries: Sequence[MixedEntry]):
+        self.entries: List[MixedEntry] = list(entries)
+        self.count = len(self.entries)
+        self.items = (fh_mixed_item * max(1, self.count))()
+        self.device = None
+        for it, e in zip(self.items, self.entries):
+            n = e.outer * e.channels * e.inner
+            ref = e.x if e.x is not None else e.raw
+            if ref is None:
+                raise ValueError("a mixed entry needs x (to compress) or raw (to restore)")
+            dev = ref.device
+            self.device = self.device or dev
+            if e.packed is None or e.meta is None:
+                e.packed, e.meta = alloc_compressed(n, e.group_size, e.bits, dev)
+            if e.raw is None:
+                e.raw = torch.empty(max(0, e.outer * e.raw_channels * e.inner), dtype=ref.dtype, device=dev)
+            for t, what in ((e.slots, "slots"), (e.packed, "packed"), (e.meta, "meta"), (e.raw, "raw")):
+                _device_tensor(t, what)
+            if _nbytes(e.slots) < 2 * e.channels:
+                raise FedHybridError(7)
+            it.outer, it.channels, it.inner = e.outer, e.channels, e.inner
+            it.slots, it.raw_channels = e.slots.data_ptr(), int(e.raw_channels)
+            it.packed, it.packed_cap = _ptr(e.packed), _nbytes(e.packed)
+            it.meta, it.meta_cap = _ptr(e.meta), _nbytes(e.meta)
+            it.raw, it.raw_cap, it.raw_dtype = _ptr(e.raw), _nbytes(e.raw), _dtype_code(e.raw)
+            it.params = make_params(e.group_size, e.bits, e.rounding, e.seed, e.tensor_id)
+            if e.x is not None:
+                _device_tensor(e.x, "x")
+                if e.x.numel() != n:
+                    raise ValueError("x.numel() != outer * channels * inner")
+                it.x, it.x_dtype = _ptr(e.x), _dtype_code(e.x)
+            if e.out is not None:
+                _device_tensor(e.out, "out")
+                it.out, it.out_dtype, it.out_cap = _ptr(e.out), _dtype_code(e.out), _nbytes(e.out)
+
+
+def fh_compress_mixed_batch(batch: MixedBatch, stream=None) -> None:
+    if batch.count:
+        with torch.cuda.device(batch.device):
+            _check(_lib.fh_compress_mixed_batch(batch.items, batch.count, _stream_ptr(stream)))
+
+
+def fh_decompress_mixed_batch(batch: MixedBatch, stream=None) -> None:
+    if batch.count:
+        with torch.cuda.device(batch.device):
+            _check(_lib.fh_decompress_mixed_batch(batch.items, batch.count, _stream_ptr(stream)))

@@ -637,12 +637,15 @@ __global__ __launch_bounds__(kCBlock) void compress_kernel(const CompressBatch a
     }
 }
 
-// One tensor whose kept channels go to the raw store.
+// Tensors whose kept channels go to the raw store.
 template <typename InT, int G>
-__global__ __launch_bounds__(kCBlock) void compress_mixed_kernel(const CompressItem it, const ChannelMap cm)
+__global__ __launch_bounds__(kCBlock) void compress_mixed_kernel(const Batch<MixedCompressJob> batch)
 {
     __shared__ __attribute__((aligned(16))) uint32_t stage[kWaves * kStageDwords];
-    const uint32_t tile = blockIdx.x;
+    uint32_t tile;
+    const MixedCompressJob& job = batch.item[batch_item(batch, blockIdx.x, tile)];
+    const CompressItem& it = job.it;
+    const ChannelMap& cm = job.cm;
     switch (it.bits * 2 + it.stochastic) {
         case 4:  compress_tile<InT, G, 2, false, true>(it, tile, stage, &cm); break;
         case 5:  compress_tile<InT, G, 2, true , true>(it, tile, stage, &cm); break;
@@ -677,13 +680,12 @@ hipError_t launch_compress(const CompressBatch& b, int dtype, int group_size, hi
     return hipGetLastError();
 }
 
-hipError_t launch_compress_mixed(const CompressItem& it, const ChannelMap& cm, int dtype, int group_size, hipStream_t s)
+hipError_t launch_compress_mixed(const Batch<MixedCompressJob>& b, int dtype, int group_size, hipStream_t s)
 {
-    const int tile = compress_tile_elems(dtype, group_size);
-    const uint32_t tiles = (uint32_t)((it.numel + tile - 1) / tile);
+    const uint32_t tiles = b.block_start[b.count];
     if (tiles == 0) return hipSuccess;
     const dim3 grid(tiles), block(kCBlock);
-#define FH_LAUNCH(T, GS) hipLaunchKernelGGL((compress_mixed_kernel<T, GS>), grid, block, 0, s, it, cm)
+#define FH_LAUNCH(T, GS) hipLaunchKernelGGL((compress_mixed_kernel<T, GS>), grid, block, 0, s, b)
     if (dtype == 0) {
         if (group_size == 64) FH_LAUNCH(float, 64);
         else if (group_size == 128) FH_LAUNCH(float, 128);

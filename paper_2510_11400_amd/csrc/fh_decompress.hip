@@ -213,12 +213,15 @@ __global__ __launch_bounds__(kDBlock) void decompress_kernel(const DecompressBat
     }
 }
 
-// One tensor whose kept channels come from the raw store.
+// Tensors whose kept channels come from the raw store.
 template <typename OutT, int G>
-__global__ __launch_bounds__(kDBlock) void decompress_mixed_kernel(const DecompressItem it, const ChannelMap cm,
-                                                                   const int raw_dtype)
+__global__ __launch_bounds__(kDBlock) void decompress_mixed_kernel(const Batch<MixedDecompressJob> batch)
 {
-    const uint32_t tile = gridDim.x - 1u - blockIdx.x;
+    uint32_t tile;
+    const MixedDecompressJob& job = batch.item[batch_item(batch, gridDim.x - 1u - blockIdx.x, tile)];
+    const DecompressItem& it = job.it;
+    const ChannelMap& cm = job.cm;
+    const int raw_dtype = job.raw_dtype;
     switch (it.bits) {
         case 2: decompress_tile<OutT, G, 2, true>(it, tile, &cm, raw_dtype); break;
         case 4: decompress_tile<OutT, G, 4, true>(it, tile, &cm, raw_dtype); break;
@@ -253,14 +256,12 @@ hipError_t launch_decompress(const DecompressBatch& b, int out_dtype, int group_
     return hipGetLastError();
 }
 
-hipError_t launch_decompress_mixed(const DecompressItem& it, const ChannelMap& cm, int raw_dtype, int out_dtype,
-                                   int group_size, hipStream_t s)
+hipError_t launch_decompress_mixed(const Batch<MixedDecompressJob>& b, int out_dtype, int group_size, hipStream_t s)
 {
-    const int tile = decompress_tile_elems(out_dtype, group_size);
-    const uint32_t tiles = (uint32_t)((it.numel + tile - 1) / tile);
+    const uint32_t tiles = b.block_start[b.count];
     if (tiles == 0) return hipSuccess;
     const dim3 grid(tiles), block(kDBlock);
-#define FH_LAUNCH(T, GS) hipLaunchKernelGGL((decompress_mixed_kernel<T, GS>), grid, block, 0, s, it, cm, raw_dtype)
+#define FH_LAUNCH(T, GS) hipLaunchKernelGGL((decompress_mixed_kernel<T, GS>), grid, block, 0, s, b)
     if (out_dtype == 0) {
         if (group_size == 64) FH_LAUNCH(float, 64);
         else if (group_size == 128) FH_LAUNCH(float, 128);

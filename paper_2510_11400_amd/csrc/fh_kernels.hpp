@@ -7,6 +7,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fh_batch.hpp"
+#include "fh_channels.hpp"
+
 namespace fh {
 
 constexpr int kMaxItems = 48;
@@ -74,11 +77,19 @@ int decompress_tile_elems(int out_dtype, int group_size);
 hipError_t launch_compress(const CompressBatch& b, int dtype, int group_size, hipStream_t s);
 hipError_t launch_decompress(const DecompressBatch& b, int out_dtype, int group_size, hipStream_t s);
 
-// The same for one [outer][channels][inner] tensor some of whose channels are kept verbatim
-// in a raw store instead of being quantised (at most 2^31 elements).
-struct ChannelMap;
-hipError_t launch_compress_mixed(const CompressItem& it, const ChannelMap& cm, int dtype, int group_size, hipStream_t s);
-hipError_t launch_decompress_mixed(const DecompressItem& it, const ChannelMap& cm, int raw_dtype, int out_dtype,
-                                   int group_size, hipStream_t s);
+// The same for [outer][channels][inner] tensors some of whose channels are kept verbatim in a raw
+// store instead of being quantised (at most 2^31 elements each; up to kBatch tensors per launch).
+struct MixedCompressJob {
+    CompressItem it;
+    ChannelMap   cm;
+};
+struct MixedDecompressJob {
+    DecompressItem it;
+    ChannelMap     cm;
+    int32_t        raw_dtype;
+    int32_t        pad;
+};
+hipError_t launch_compress_mixed(const Batch<MixedCompressJob>& b, int dtype, int group_size, hipStream_t s);
+hipError_t launch_decompress_mixed(const Batch<MixedDecompressJob>& b, int out_dtype, int group_size, hipStream_t s);
 
 }  // namespace fh

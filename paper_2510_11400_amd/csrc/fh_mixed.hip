@@ -108,38 +108,153 @@ fh_status fh_channel_slots(const void* mask, int64_t channels, int64_t raw_chann
     return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
 }
 
+}  // extern "C"
+
+namespace {
+
+using namespace fh;
+
+fh_status check_compress(const fh_mixed_item& it, int64_t* numel)
+{
+    fh_status s;
+    if ((s = check_quantiser(&it.params, true)) != FH_OK) return s;
+    if (it.x_dtype != FH_F32 && it.x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if ((s = check_shape(it.outer, it.channels, it.inner, it.raw_channels, numel)) != FH_OK) return s;
+    if (*numel == 0) return FH_OK;
+    if (!it.x || !it.slots || !it.packed || !it.meta || (it.raw_channels > 0 && !it.raw)) return FH_ERR_NULL;
+    if (!aligned(it.x, 16) || !aligned(it.packed, 16) || !aligned(it.meta, 8) || !aligned(it.slots, 16) ||
+        !aligned(it.raw, 16))
+        return FH_ERR_ALIGNMENT;
+    if (it.packed_cap < fh_packed_bytes(*numel, it.params.bits)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (it.meta_cap < fh_meta_bytes(*numel, it.params.group_size)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (it.raw_cap < fh_raw_bytes(it.outer, it.raw_channels, it.inner, (fh_dtype)it.x_dtype)) return FH_ERR_BUFFER_TOO_SMALL;
+    return FH_OK;
+}
+
+fh_status check_decompress(const fh_mixed_item& it, int64_t* numel)
+{
+    fh_status s;
+    if ((s = check_quantiser(&it.params, false)) != FH_OK) return s;
+    if (it.raw_dtype != FH_F32 && it.raw_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if (it.out_dtype != FH_F32 && it.out_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if ((s = check_shape(it.outer, it.channels, it.inner, it.raw_channels, numel)) != FH_OK) return s;
+    if (*numel == 0) return FH_OK;
+    if (!it.packed || !it.meta || !it.slots || !it.out || (it.raw_channels > 0 && !it.raw)) return FH_ERR_NULL;
+    if (!aligned(it.packed, 16) || !aligned(it.out, 16) || !aligned(it.meta, 8) || !aligned(it.slots, 16) ||
+        !aligned(it.raw, 16))
+        return FH_ERR_ALIGNMENT;
+    if (it.packed_cap < fh_packed_bytes(*numel, it.params.bits)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (it.meta_cap < fh_meta_bytes(*numel, it.params.group_size)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (it.raw_cap < fh_raw_bytes(it.outer, it.raw_channels, it.inner, (fh_dtype)it.raw_dtype)) return FH_ERR_BUFFER_TOO_SMALL;
+    if (it.out_cap < (size_t)*numel * elem_size(it.out_dtype)) return FH_ERR_BUFFER_TOO_SMALL;
+    return FH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t fh_mixed_batch_capacity(void) { return fh::kBatch; }
+
+fh_status fh_compress_mixed_batch(const fh_mixed_item* items, int32_t count, void* stream)
+{
+    using namespace fh;
+    if (count < 0) return FH_ERR_BAD_COUNT;
+    if (count > 0 && !items) return FH_ERR_NULL;
+    for (int32_t i = 0; i < count; ++i) {                     // everything is checked before the first launch
+        int64_t numel;
+        const fh_status st = check_compress(items[i], &numel);
+        if (st != FH_OK) return st;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t i = 0;
+    while (i < count) {                                       // runs of one dtype and group size
+        Batch<MixedCompressJob> b;
+        reset(b);
+        const int dtype = items[i].x_dtype, G = items[i].params.group_size;
+        const int tile = compress_tile_elems(dtype, G);
+        while (i < count && items[i].x_dtype == dtype && items[i].params.group_size == G) {
+            const fh_mixed_item& it = items[i];
+            int64_t numel;
+            check_compress(it, &numel);
+            if (numel == 0) { ++i; continue; }
+            MixedCompressJob job;
+            job.it.x = it.x;
+            job.it.packed = static_cast<uint8_t*>(it.packed);
+            job.it.meta = static_cast<float*>(it.meta);
+            job.it.numel = numel;
+            job.it.packed_padded = fh_packed_bytes(numel, it.params.bits);
+            job.it.seed = it.params.seed;
+            job.it.tensor_id = it.params.tensor_id;
+            job.it.bits = it.params.bits;
+            job.it.stochastic = it.params.rounding == FH_ROUND_STOCHASTIC ? 1 : 0;
+            job.cm = make_map(it.slots, it.raw, it.channels, it.inner, it.raw_channels);
+            if (!push(b, job, (numel + tile - 1) / tile)) break;      // launch what is there, go on with this item
+            ++i;
+        }
+        if (b.count == 0) continue;
+        seal(b);
+        if (launch_compress_mixed(b, dtype, G, s) != hipSuccess) return FH_ERR_LAUNCH;
+    }
+    return FH_OK;
+}
+
+fh_status fh_decompress_mixed_batch(const fh_mixed_item* items, int32_t count, void* stream)
+{
+    using namespace fh;
+    if (count < 0) return FH_ERR_BAD_COUNT;
+    if (count > 0 && !items) return FH_ERR_NULL;
+    for (int32_t i = 0; i < count; ++i) {
+        int64_t numel;
+        const fh_status st = check_decompress(items[i], &numel);
+        if (st != FH_OK) return st;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t i = 0;
+    while (i < count) {
+        Batch<MixedDecompressJob> b;
+        reset(b);
+        const int dtype = items[i].out_dtype, G = items[i].params.group_size;
+        const int tile = decompress_tile_elems(dtype, G);
+        while (i < count && items[i].out_dtype == dtype && items[i].params.group_size == G) {
+            const fh_mixed_item& it = items[i];
+            int64_t numel;
+            check_decompress(it, &numel);
+            if (numel == 0) { ++i; continue; }
+            MixedDecompressJob job;
+            job.it.packed = static_cast<const uint8_t*>(it.packed);
+            job.it.meta = static_cast<const float*>(it.meta);
+            job.it.out = it.out;
+            job.it.numel = numel;
+            job.it.bits = it.params.bits;
+            job.it.pad = 0;
+            job.cm = make_map(it.slots, it.raw, it.channels, it.inner, it.raw_channels);
+            job.raw_dtype = it.raw_dtype;
+            job.pad = 0;
+            if (!push(b, job, (numel + tile - 1) / tile)) break;
+            ++i;
+        }
+        if (b.count == 0) continue;
+        seal(b);
+        if (launch_decompress_mixed(b, dtype, G, s) != hipSuccess) return FH_ERR_LAUNCH;
+    }
+    return FH_OK;
+}
+
 fh_status fh_compress_mixed(const void* x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
                             const fh_params* params, const void* slots, int64_t raw_channels,
                             void* packed, size_t packed_cap, void* meta, size_t meta_cap,
                             void* raw, size_t raw_cap, void* stream)
 {
-    fh_status s;
-    if ((s = fh::check_quantiser(params, true)) != FH_OK) return s;
-    if (x_dtype != FH_F32 && x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
-    int64_t numel = 0;
-    if ((s = fh::check_shape(outer, channels, inner, raw_channels, &numel)) != FH_OK) return s;
-    if (numel == 0) return FH_OK;
-    if (!x || !slots || !packed || !meta || (raw_channels > 0 && !raw)) return FH_ERR_NULL;
-    if (!fh::aligned(x, 16) || !fh::aligned(packed, 16) || !fh::aligned(meta, 8) || !fh::aligned(slots, 16) ||
-        !fh::aligned(raw, 16))
-        return FH_ERR_ALIGNMENT;
-    if (packed_cap < fh_packed_bytes(numel, params->bits)) return FH_ERR_BUFFER_TOO_SMALL;
-    if (meta_cap < fh_meta_bytes(numel, params->group_size)) return FH_ERR_BUFFER_TOO_SMALL;
-    if (raw_cap < fh_raw_bytes(outer, raw_channels, inner, x_dtype)) return FH_ERR_BUFFER_TOO_SMALL;
-
-    fh::CompressItem it;
-    it.x = x;
-    it.packed = static_cast<uint8_t*>(packed);
-    it.meta = static_cast<float*>(meta);
-    it.numel = numel;
-    it.packed_padded = fh_packed_bytes(numel, params->bits);
-    it.seed = params->seed;
-    it.tensor_id = params->tensor_id;
-    it.bits = params->bits;
-    it.stochastic = params->rounding == FH_ROUND_STOCHASTIC ? 1 : 0;
-    const fh::ChannelMap cm = fh::make_map(slots, raw, channels, inner, raw_channels);
-    return fh::launch_compress_mixed(it, cm, x_dtype, params->group_size, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? FH_OK : FH_ERR_LAUNCH;
+    if (!params) return FH_ERR_NULL;
+    fh_mixed_item it = {};
+    it.x = x; it.x_dtype = x_dtype; it.out_dtype = FH_F32;
+    it.outer = outer; it.channels = channels; it.inner = inner;
+    it.slots = slots; it.raw_channels = raw_channels;
+    it.packed = packed; it.packed_cap = packed_cap; it.meta = meta; it.meta_cap = meta_cap;
+    it.raw = raw; it.raw_cap = raw_cap; it.raw_dtype = x_dtype;
+    it.params = *params;
+    return fh_compress_mixed_batch(&it, 1, stream);
 }
 
 fh_status fh_decompress_mixed(const void* packed, const void* meta, const void* raw, fh_dtype raw_dtype,
@@ -147,30 +262,24 @@ fh_status fh_decompress_mixed(const void* packed, const void* meta, const void* 
                               const fh_params* params, const void* slots, int64_t raw_channels,
                               fh_dtype out_dtype, void* out, size_t out_cap, void* stream)
 {
-    fh_status s;
-    if ((s = fh::check_quantiser(params, false)) != FH_OK) return s;
-    if (raw_dtype != FH_F32 && raw_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
-    if (out_dtype != FH_F32 && out_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if (!params) return FH_ERR_NULL;
+    fh_mixed_item it = {};
+    it.x_dtype = FH_F32; it.out_dtype = out_dtype;
+    it.outer = outer; it.channels = channels; it.inner = inner;
+    it.slots = slots; it.raw_channels = raw_channels;
+    it.packed = const_cast<void*>(packed); it.meta = const_cast<void*>(meta);
+    it.raw = const_cast<void*>(raw); it.raw_dtype = raw_dtype;
+    it.out = out; it.out_cap = out_cap;
+    it.params = *params;
+    // the single call takes no capacities for its inputs: they are what the shape implies
     int64_t numel = 0;
-    if ((s = fh::check_shape(outer, channels, inner, raw_channels, &numel)) != FH_OK) return s;
-    if (numel == 0) return FH_OK;
-    if (!packed || !meta || !slots || !out || (raw_channels > 0 && !raw)) return FH_ERR_NULL;
-    if (!fh::aligned(packed, 16) || !fh::aligned(out, 16) || !fh::aligned(meta, 8) || !fh::aligned(slots, 16) ||
-        !fh::aligned(raw, 16))
-        return FH_ERR_ALIGNMENT;
-    if (out_cap < (size_t)numel * fh::elem_size(out_dtype)) return FH_ERR_BUFFER_TOO_SMALL;
-
-    fh::DecompressItem it;
-    it.packed = static_cast<const uint8_t*>(packed);
-    it.meta = static_cast<const float*>(meta);
-    it.out = out;
-    it.numel = numel;
-    it.bits = params->bits;
-    it.pad = 0;
-    const fh::ChannelMap cm = fh::make_map(slots, const_cast<void*>(raw), channels, inner, raw_channels);
-    return fh::launch_decompress_mixed(it, cm, raw_dtype, out_dtype, params->group_size,
-                                       static_cast<hipStream_t>(stream)) == hipSuccess
-               ? FH_OK : FH_ERR_LAUNCH;
+    if (fh::check_shape(outer, channels, inner, raw_channels, &numel) == FH_OK && numel > 0 &&
+        (raw_dtype == FH_F32 || raw_dtype == FH_BF16)) {
+        it.packed_cap = fh_packed_bytes(numel, params->bits);
+        it.meta_cap = fh_meta_bytes(numel, params->group_size);
+        it.raw_cap = fh_raw_bytes(outer, raw_channels, inner, raw_dtype);
+    }
+    return fh_decompress_mixed_batch(&it, 1, stream);
 }
 
 }  // extern "C"

@@ -286,3 +286,24 @@ def test_sparse_item_layouts_and_batch_argument_checks():
                                     FAKE, FAKE, 1 << 20)
     arr = (api.fh_sparse_encode_item * 2)(good, bad)
     assert lib.fh_sparse_encode_batch(arr, 2, None) == 12          # found before any launch
+
+
+def test_mixed_item_layout_and_batch_argument_checks():
+    assert ctypes.sizeof(api.fh_mixed_item) == 16 + 24 + 16 + 3 * 16 + 8 + 16 + 32 == 160
+    assert api.fh_mixed_item.slots.offset == 40 and api.fh_mixed_item.raw_dtype.offset == 104
+    assert api.fh_mixed_item.out.offset == 112 and api.fh_mixed_item.params.offset == 128
+    assert api.mixed_batch_capacity() == 16
+    lib = api.raw_library()
+    for f in (lib.fh_compress_mixed_batch, lib.fh_decompress_mixed_batch):
+        assert f(None, 0, None) == 0 and f(None, 2, None) == 1 and f(None, -1, None) == 10
+    arr = (api.fh_mixed_item * 2)()
+    for it in arr:
+        it.x, it.outer, it.channels, it.inner, it.slots, it.raw_channels = FAKE, 4, 8, 16, FAKE, 2
+        it.packed, it.packed_cap, it.meta, it.meta_cap, it.raw, it.raw_cap = FAKE, 1 << 20, FAKE, 1 << 20, FAKE, 1 << 20
+        it.out, it.out_cap = FAKE, 1 << 20
+        it.params = api.make_params(64, 4)
+    arr[1].params.bits = 3
+    assert lib.fh_compress_mixed_batch(arr, 2, None) == 4 and lib.fh_decompress_mixed_batch(arr, 2, None) == 4
+    arr[1].params.bits = 4
+    arr[1].raw_cap = 4 * 2 * 16 * 4 - 1
+    assert lib.fh_compress_mixed_batch(arr, 2, None) == 7 and lib.fh_decompress_mixed_batch(arr, 2, None) == 7

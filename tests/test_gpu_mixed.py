@@ -214,3 +214,42 @@ def test_argument_errors_reach_the_caller(api):
     # an empty tensor is fine and launches nothing
     p, m, r = api.fh_compress_mixed(torch.empty(0, device="cuda"), 0, 8, 64, slots, 2, 64, 4)
     assert p.numel() == 0 and m.numel() == 0 and r.numel() == 0
+
+
+# ---- the batched calls ---------------------------------------------------------------------------
+
+def test_batched_calls_match_the_oracle_for_every_tensor(api):
+    """More tensors than one launch holds, both dtypes and several group sizes (several runs),
+    an empty tensor, capacities below and above the salient count."""
+    specs = [(8, 32, 196, "f32", 128, 4, "nearest"), (64, 768, 1, "bf16", 64, 2, "stochastic"), (0, 12, 9, "f32", 128, 4, "nearest"),
+             (3, 16, 4097, "f32", 256, 8, "stochastic"), (5, 100, 1, "bf16", 64, 4, "nearest"), (2, 10, 7, "f32", 64, 8, "nearest")]
+    specs += [(2 + i % 3, 8 + i, 50 + 13 * i, "f32", 128, 4, "stochastic") for i in range(16)]
+    entries, host = [], []
+    for i, (outer, C, inner, dtype, G, B, rounding) in enumerate(specs):
+        x, _ = W.outlier_channel_tensor(max(outer, 1), C, inner, seed=70 + i, salient_fraction=0.1, dtype=dtype)
+        x = x[: outer * C * inner]
+        mask = _mask(C, 0.2, i)
+        mask[0] = 1
+        cap = max(1, int(mask.sum()) - (i % 2))              # every other tensor: one salient channel too many
+        slots, used = oracle.channel_slots(mask, cap)
+        host.append((x, slots, cap))
+        tdt = _tdtype(dtype)
+        xd = _device(x, dtype) if x.size else torch.empty(0, dtype=tdt, device="cuda")
+        entries.append(api.MixedEntry(outer, C, inner, torch.from_numpy(slots).cuda(), cap, G, B, rounding, 3, 100 + i,
+                                      x=xd, out=torch.empty(x.size, dtype=torch.float32, device="cuda")))
+    assert len(entries) > api.mixed_batch_capacity()
+    batch = api.MixedBatch(entries)
+    print(f"[mixed] batch of {len(entries)} tensors", flush=True)
+    api.fh_compress_mixed_batch(batch)
+    api.fh_decompress_mixed_batch(batch)
+    torch.cuda.synchronize()
+    for i, ((outer, C, inner, dtype, G, B, rounding), (x, slots, cap), e) in enumerate(zip(specs, host, entries)):
+        p, m, raw = oracle.compress_mixed(x, outer, C, inner, slots, cap, G, B, rounding, 3, 100 + i, dtype=dtype)
+        used = int((slots >= 0).sum())
+        assert np.array_equal(e.packed.cpu().numpy(), p), f"tensor {i}: codes"
+        assert np.array_equal(e.meta.cpu().numpy().view(np.uint32), m.view(np.uint32)), f"tensor {i}: meta"
+        got_raw = _host(e.raw, dtype).reshape(outer, cap, inner)[:, :used]
+        assert np.array_equal(_bits(got_raw), _bits(raw.reshape(outer, cap, inner)[:, :used])), f"tensor {i}: raw"
+        # restore with the oracle's raw store where unused rows are zero: kept rows are what matter
+        want = oracle.decompress_mixed(p, m, raw, outer, C, inner, slots, cap, G, B, raw_dtype=dtype, out_dtype="f32")
+        assert np.array_equal(e.out.cpu().numpy().view(np.uint32), want.view(np.uint32)), f"tensor {i}: restored"
