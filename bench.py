@@ -230,6 +230,7 @@ def bench_sparse(args, api, W, dev) -> int:
     import torch
 
     layers = ((64 * 1, 112, 112), (64 * 4, 112, 112), (64 * 6, 56, 56), (64 * 8, 28, 28), (64 * 15, 14, 14))
+    layers = tuple((maps * args.maps_scale, h, w) for maps, h, w in layers)
     n, tau, eps = 4, 0.5, args.eps
     t0 = time.time()
     host, jobs = [], []
@@ -300,7 +301,8 @@ def bench_sparse(args, api, W, dev) -> int:
         "value": round(nbytes / elapsed / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-        "config": {"workload": "sparse_mobilenetv2_b64_kept_channels_n4_tau0.5" + (f"_eps{eps:g}" if eps > 0 else ""),
+        "config": {"workload": "sparse_mobilenetv2_b64_kept_channels_n4_tau0.5" + (f"_eps{eps:g}" if eps > 0 else "")
+                   + (f"_x{args.maps_scale}" if args.maps_scale != 1 else ""),
                    "map_sets": len(jobs), "input_bytes": nbytes, "stored_bytes": stored,
                    "entry_point": ("fh_sparse_encode + fh_sparse_decode (per set)" if args.per_tensor
                                    else "fh_sparse_encode_batch + fh_sparse_decode_batch"),
@@ -345,6 +347,8 @@ def main() -> int:
                          "sparse: block-wise sparse storage of the kept channels' maps")
     ap.add_argument("--eps", type=float, default=0.0,
                     help="--op sparse: error bound of the predictive form of dense blocks (0 = verbatim)")
+    ap.add_argument("--maps-scale", type=int, default=1, metavar="K",
+                    help="--op sparse: K times as many maps per set (the kernels at a bandwidth-bound size)")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()

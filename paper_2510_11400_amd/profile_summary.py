@@ -19,7 +19,7 @@ from collections import defaultdict
 from typing import Dict, Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-KERNEL_SOURCES = ("fh_device.hpp", "fh_kernels.hpp", "fh_channels.hpp", "fh_compress.hip", "fh_decompress.hip")   # device code
+KERNEL_SOURCES = ("fh_device.hpp", "fh_kernels.hpp", "fh_batch.hpp", "fh_channels.hpp", "fh_compress.hip", "fh_decompress.hip")   # device code
 KERNELS = {"compress_kernel": "::compress_kernel<", "decompress_kernel": "::decompress_kernel<"}
 COPY_MARKERS = ("copyBuffer", "copy_kernel", "CopyKernel")
 
