@@ -10,9 +10,13 @@
 //           byte; each workgroup adds up what its 256 tiles will write;
 //   pass 2  one thread per tile: the workgroup's base is the sum of the sums before it (each
 //           workgroup adds them up itself while there are few; a scan kernel in between does
-//           it once there are many), offsets inside the workgroup come from a scan through
-//           LDS, then the tile's values and CSR structure go to their final place.
-// Restoring runs the same passes with the info bytes as the only input of pass 1.
+//           it once there are many), offsets inside the workgroup come from a wave-shuffle
+//           scan, then the tile's values and CSR structure go to their final place.
+// What a workgroup's tiles write is one contiguous slice of each stream, so the threads put
+// their pieces together in LDS and the workgroup moves the slice with aligned 16-byte
+// vectors (thread-per-tile stores would touch every cache line of the slice once per element).
+// Restoring runs the same passes with the info bytes as the only input of pass 1; the slices
+// come into LDS the same way and every thread rebuilds its tile from there.
 // A thread reads its whole tile with unconditional loads (addresses clamped into the tile) before
 // it looks at any value, so it waits for memory once, not once per element.
 // With an error bound, dense blocks are stored by first-order Lorenzo prediction on the lattice
@@ -29,8 +33,13 @@
 namespace fh {
 namespace {
 
-constexpr int kTileThreads = 256;                  // tiles per workgroup
-constexpr int kScanThreads = 1024;
+// tiles (threads) per workgroup: fewer for the largest window, whose slices are four times as long
+template <int N> struct Group {
+    static constexpr int kTiles = N == 8 ? 128 : 256;
+    static constexpr int kWaves = kTiles / 64;
+};
+constexpr int kMaxWaves = 4;
+constexpr int kScanThreads = 512;
 constexpr uint32_t kSelfScanLimit = 2048;          // up to this many workgroups each adds up the sums before it
 
 struct Sums {                                      // what a run of tiles writes
@@ -139,65 +148,90 @@ __device__ __forceinline__ uint32_t lorenzo_codes(const Bits (&e)[N][N], const T
     return outliers;
 }
 
-// Workgroup-wide exclusive scan of what each thread's tile writes.  A tile writes at most 127
-// values and 73 index bytes, so a workgroup's running sums fit 20-bit fields of one 64-bit
-// word: lanes scan that word with wave shuffles, and the four wave totals meet in LDS.
-constexpr int kTileWaves = kTileThreads / 64;
-__device__ __forceinline__ uint64_t pack_sums(const Sums& s)
+// ---- sums over a wave and a workgroup -----------------------------------------------------------
+// Inside a wave every running sum here stays below 2^32 (a wave covers at most 64 groups of
+// 256 tiles, a tile writes at most 127 values and 73 index bytes), so lanes scan three 32-bit
+// words with data-parallel-primitive adds on the vector ALU: four shifts inside each row of 16
+// lanes, then the last lane of rows 0 and 2 onto rows 1 and 3, then lane 31 onto rows 2 and 3.
+// Across waves and workgroups the sums are 64 bits wide and meet in LDS.
+struct Sums32 {
+    uint32_t values, index_bytes, sparse_tiles;
+};
+__device__ __forceinline__ Sums32 narrow(const Sums& s)
 {
-    return s.values | (s.index_bytes << 20) | (s.sparse_tiles << 40);
-}
-__device__ __forceinline__ Sums unpack_sums(uint64_t p)
-{
-    return Sums{p & 0xfffffu, (p >> 20) & 0xfffffu, p >> 40};
-}
-__device__ __forceinline__ Sums workgroup_exclusive_scan(Sums mine, uint64_t* lds /* [kTileWaves] */, Sums* total)
-{
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint64_t own = pack_sums(mine);
-    uint64_t inc = own;
-#pragma unroll
-    for (int step = 1; step < 64; step <<= 1) {
-        const uint64_t up = __shfl_up(inc, step, 64);
-        if (lane >= (uint32_t)step) inc += up;
-    }
-    if (lane == 63u) lds[wave] = inc;
-    __syncthreads();
-    uint64_t before = 0, all = 0;
-#pragma unroll
-    for (int v = 0; v < kTileWaves; ++v) {
-        const uint64_t t = lds[v];
-        if ((uint32_t)v < wave) before += t;
-        all += t;
-    }
-    __syncthreads();                                          // lds may be reused right away
-    *total = unpack_sums(all);
-    return unpack_sums(before + inc - own);
+    return Sums32{(uint32_t)s.values, (uint32_t)s.index_bytes, (uint32_t)s.sparse_tiles};
 }
 
-// Workgroup-wide sum of full-width sums.
-__device__ __forceinline__ Sums workgroup_sum(Sums part, uint64_t* lds /* [3 * kTileWaves] */)
+// v + (the lane the control word names, 0 where there is none or the row is masked out)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t v)
+{
+    return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+    v = dpp_add<0x111, 0xf>(v);                               // row_shr:1
+    v = dpp_add<0x112, 0xf>(v);                               // row_shr:2
+    v = dpp_add<0x114, 0xf>(v);                               // row_shr:4
+    v = dpp_add<0x118, 0xf>(v);                               // row_shr:8
+    v = dpp_add<0x142, 0xa>(v);                               // row_bcast:15 onto rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);                               // row_bcast:31 onto rows 2 and 3
+    return v;
+}
+__device__ __forceinline__ Sums32 wave_inclusive_scan(const Sums32& s)
+{
+    return Sums32{wave_inclusive_scan(s.values), wave_inclusive_scan(s.index_bytes), wave_inclusive_scan(s.sparse_tiles)};
+}
+// the wave's total, from the inclusive sums: lane 63's, in scalar registers
+__device__ __forceinline__ Sums wave_total(const Sums32& inclusive)
+{
+    return Sums{(uint32_t)__builtin_amdgcn_readlane((int)inclusive.values, 63),
+                (uint32_t)__builtin_amdgcn_readlane((int)inclusive.index_bytes, 63),
+                (uint32_t)__builtin_amdgcn_readlane((int)inclusive.sparse_tiles, 63)};
+}
+
+// the waves' totals through LDS: what the waves before this one add up to, and all of them
+template <int WAVES>
+__device__ __forceinline__ Sums across_waves(const Sums& wave_sum, uint64_t* lds /* [3 * WAVES] */, Sums* all)
 {
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    uint64_t a = part.values, b = part.index_bytes, c = part.sparse_tiles;
+    if (lane == 0u) { lds[3 * wave] = wave_sum.values; lds[3 * wave + 1] = wave_sum.index_bytes; lds[3 * wave + 2] = wave_sum.sparse_tiles; }
+    __syncthreads();
+    Sums before = {0, 0, 0}, total = {0, 0, 0};
 #pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) {
-        a += __shfl_xor(a, step, 64);
-        b += __shfl_xor(b, step, 64);
-        c += __shfl_xor(c, step, 64);
+    for (int v = 0; v < WAVES; ++v) {
+        const Sums w = {lds[3 * v], lds[3 * v + 1], lds[3 * v + 2]};
+        if ((uint32_t)v < wave) before = before + w;
+        total = total + w;
     }
-    if (lane == 0u) { lds[3 * wave] = a; lds[3 * wave + 1] = b; lds[3 * wave + 2] = c; }
-    __syncthreads();
-    Sums total = {0, 0, 0};
-#pragma unroll
-    for (int v = 0; v < kTileWaves; ++v) total = total + Sums{lds[3 * v], lds[3 * v + 1], lds[3 * v + 2]};
-    __syncthreads();
+    __syncthreads();                                          // lds may be reused right away
+    *all = total;
+    return before;
+}
+
+// Workgroup-wide exclusive scan of what each thread's tile writes.
+template <int WAVES>
+__device__ __forceinline__ Sums workgroup_exclusive_scan(Sums mine, uint64_t* lds /* [3 * WAVES] */, Sums* total)
+{
+    const Sums32 own = narrow(mine), inc = wave_inclusive_scan(own);
+    const Sums before = across_waves<WAVES>(wave_total(inc), lds, total);
+    return Sums{before.values + inc.values - own.values, before.index_bytes + inc.index_bytes - own.index_bytes,
+                before.sparse_tiles + inc.sparse_tiles - own.sparse_tiles};
+}
+
+// Workgroup-wide sum; a thread's part is below 2^32 / 64.
+template <int WAVES>
+__device__ __forceinline__ Sums workgroup_sum(Sums part, uint64_t* lds /* [3 * WAVES] */)
+{
+    Sums total;
+    across_waves<WAVES>(wave_total(wave_inclusive_scan(narrow(part))), lds, &total);
     return total;
 }
 
 // The tile's elements, row-major, zeros where the tile has no element.  Every load is
 // unconditional -- out-of-tile positions read a clamped in-tile address -- so all N*N loads
-// are in flight together.
+// are in flight together.  Plain loads on purpose: the second pass over the maps finds in the
+// memory-side cache what the first one read whenever a layer's kept channels fit there.
 template <typename Bits, int N> struct RowVec {               // N elements of Bits as one vector
     typedef Bits type __attribute__((ext_vector_type(N)));
 };
@@ -260,28 +294,130 @@ __device__ __forceinline__ void store_tile(Bits* out, const TilePos& t, uint32_t
 
 // What the tiles of all earlier workgroups write.  `scanned`: wg[] already holds exclusive
 // prefixes (the scan kernel ran); otherwise it holds per-workgroup sums and they are added up
-// here, 256 at a time.
+// here, a workgroup's width at a time.
+template <int WAVES>
 __device__ __forceinline__ Sums workgroup_base(const Sums* __restrict__ wg, bool scanned, uint32_t block,
                                                uint64_t* lds)
 {
     if (scanned) return wg[block];
     Sums part = {0, 0, 0};
-    for (uint32_t i = threadIdx.x; i < block; i += kTileThreads) part = part + wg[i];
-    return workgroup_sum(part, lds);
+    for (uint32_t i = threadIdx.x; i < block; i += WAVES * 64) part = part + wg[i];
+    return workgroup_sum<WAVES>(part, lds);
 }
 
-// ---- pass 1 (encode): non-zero count, density, info byte, workgroup sums ---------------------
-template <typename Bits, int N>
-__global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const Batch<Job> batch)
+// ---- a workgroup's slice of a stream, staged in LDS --------------------------------------------
+// Byte i of the slice sits at stage[phase + i], phase = the slice's address mod 16, so 16-byte
+// chunks of LDS and of the stream line up: whole chunks move as one vector per thread, the
+// (at most 15 + 15) bytes before the first and after the last whole chunk byte by byte.
+// Neighbouring workgroups' slices may share a chunk; each writes only its own bytes of it.
+typedef uint32_t chunk16 __attribute__((ext_vector_type(4), may_alias));
+template <typename T> struct Alias { typedef T __attribute__((may_alias)) type; };
+
+__device__ __forceinline__ uint32_t phase_of(const void* p) { return (uint32_t)(reinterpret_cast<uintptr_t>(p) & 15u); }
+
+template <int THREADS>
+__device__ __forceinline__ void stage_to_stream(const uint8_t* stage, uint8_t* dst, uint32_t nbytes)
 {
-    __shared__ uint64_t lds[3 * kTileWaves];
+    const uint32_t phase = phase_of(dst), end = phase + nbytes;
+    uint8_t* g0 = dst - phase;                                // 16-byte aligned
+    const uint32_t first = (phase + 15u) >> 4, last = end >> 4;       // whole chunks [first, last)
+    for (uint32_t c = first + threadIdx.x; c < last; c += THREADS)
+        *reinterpret_cast<chunk16*>(g0 + 16u * c) = *reinterpret_cast<const chunk16*>(stage + 16u * c);
+    const uint32_t head_end = first * 16u < end ? first * 16u : end;
+    const uint32_t tail = last * 16u > head_end ? last * 16u : head_end;
+    uint32_t i = phase + threadIdx.x;
+    if (i < head_end) g0[i] = stage[i];
+    i = tail + threadIdx.x;
+    if (i < end) g0[i] = stage[i];
+}
+
+template <int THREADS>
+__device__ __forceinline__ void stream_to_stage(uint8_t* stage, const uint8_t* src, uint32_t nbytes)
+{
+    const uint32_t phase = phase_of(src), end = phase + nbytes;
+    const uint8_t* g0 = src - phase;
+    const uint32_t first = (phase + 15u) >> 4, last = end >> 4;
+    for (uint32_t c = first + threadIdx.x; c < last; c += THREADS)
+        *reinterpret_cast<chunk16*>(stage + 16u * c) = *reinterpret_cast<const chunk16*>(g0 + 16u * c);
+    const uint32_t head_end = first * 16u < end ? first * 16u : end;
+    const uint32_t tail = last * 16u > head_end ? last * 16u : head_end;
+    uint32_t i = phase + threadIdx.x;
+    if (i < head_end) stage[i] = g0[i];
+    i = tail + threadIdx.x;
+    if (i < end) stage[i] = g0[i];
+}
+
+// LDS of a workgroup: a tile puts at most N*N values and N*N + N + 1 index bytes into the streams
+// (a sparse tile whose every element is a non-zero: tau >= 1).  16 bytes for the phase; the
+// decoder may read up to N bytes / one value past a tile's piece (and discards them).
+template <typename Bits, int N> struct Stage {
+    static constexpr int kValueBytes = Group<N>::kTiles * N * N * (int)sizeof(Bits) + 32;
+    static constexpr int kIndexBytes = Group<N>::kTiles * (N * N + N + 1) + 32;
+};
+
+// occupancy of a tile, bit r*N + c for element (r, c)
+template <int N> struct TileMask { typedef uint32_t type; };
+template <> struct TileMask<8> { typedef uint64_t type; };
+__device__ __forceinline__ uint32_t popcount(uint32_t m) { return (uint32_t)__builtin_popcount(m); }
+__device__ __forceinline__ uint32_t popcount(uint64_t m) { return (uint32_t)__builtin_popcountll(m); }
+
+// the elements a tile has (edge tiles are smaller than the window)
+template <int N>
+__device__ __forceinline__ typename TileMask<N>::type valid_mask(const TilePos& t)
+{
+    typedef typename TileMask<N>::type M;
+    const uint32_t row = (1u << t.cols) - 1u;
+    M m = 0;
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+        if (r < (int)t.rows) m |= (M)row << (r * N);
+    return m;
+}
+
+// The occupancy a sparse tile's CSR structure describes: row r owns entries
+// [row_ptr[r], row_ptr[r+1]), their column bytes ascending (as the encoder writes them), so
+// entry k is the k-th set bit.  Bytes that do not describe a tile (a foreign stream) yield some
+// mask; nothing outside the tile's piece plus N bytes is read.
+template <int N>
+__device__ __forceinline__ typename TileMask<N>::type csr_mask(const uint8_t* si, const TilePos& t, uint32_t count)
+{
+    typedef typename TileMask<N>::type M;
+    uint32_t rp[N + 1];
+#pragma unroll
+    for (int r = 0; r <= N; ++r) rp[r] = si[r <= (int)t.rows ? r : t.rows];
+    const uint8_t* col = si + t.rows + 1;
+    M m = 0;
+#pragma unroll
+    for (int r = 0; r < N; ++r) {
+        const uint32_t start = rp[r] < count ? rp[r] : count;
+        const uint32_t len = rp[r + 1] > rp[r] ? rp[r + 1] - rp[r] : 0u;
+        uint32_t cols[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) cols[j] = col[start + j];
+        uint32_t row = 0;
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if ((uint32_t)j < len && start + j < count && cols[j] < t.cols) row |= 1u << cols[j];
+        if (r < (int)t.rows) m |= (M)row << (r * N);
+    }
+    return m;
+}
+
+// ---- pass 1: what each group of tiles (a workgroup of pass 3) will write -------------------------
+constexpr int kGroupsPerWorkgroup = 4;             // decode: waves of a pass-1 workgroup, a group each
+
+// encode: non-zero count, density, info byte; one thread per tile, one workgroup per group
+template <typename Bits, int N>
+__global__ __launch_bounds__(Group<N>::kTiles) void sparse_count_kernel(const Batch<Job> batch)
+{
+    constexpr int T = Group<N>::kTiles, WAVES = Group<N>::kWaves;
+    __shared__ uint64_t lds[3 * kMaxWaves];
     uint32_t block;
     const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
     const MapShape& s = job.shape;
     const float tau = job.tau;
     uint8_t* info = job.info;
-    Sums* wg_sums = job.wg;
-    const uint32_t b = block * kTileThreads + threadIdx.x;
+    const uint32_t b = block * T + threadIdx.x;
     Sums mine = {0, 0, 0};
     if (b < s.tiles) {
         const TilePos t = tile_pos(s, b);
@@ -302,59 +438,102 @@ __global__ __launch_bounds__(kTileThreads) void sparse_count_kernel(const Batch<
         info[b] = (uint8_t)byte;
         mine = tile_sums(byte, t, s.two_eps > 0.0f);
     }
-    Sums total;
-    workgroup_exclusive_scan(mine, lds, &total);
-    if (threadIdx.x == 0) wg_sums[block] = total;
-}
-
-// ---- pass 1 (decode): workgroup sums from the info bytes --------------------------------------
-__global__ __launch_bounds__(kTileThreads) void sparse_sums_kernel(const Batch<Job> batch)
-{
-    __shared__ uint64_t lds[3 * kTileWaves];
-    uint32_t block;
-    const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
-    const MapShape& s = job.shape;
-    const uint32_t b = block * kTileThreads + threadIdx.x;
-    Sums mine = {0, 0, 0};
-    if (b < s.tiles) mine = tile_sums(job.info[b], tile_pos(s, b), s.two_eps > 0.0f);
-    Sums total;
-    workgroup_exclusive_scan(mine, lds, &total);
+    const Sums total = workgroup_sum<WAVES>(mine, lds);
     if (threadIdx.x == 0) job.wg[block] = total;
 }
 
-// ---- pass 2: exclusive scan of the workgroup sums, in place; totals -----------------------------
-// one workgroup per set; sets with few workgroups skip it (their workgroups add up the sums themselves)
+// decode: the same sums from the info bytes.  A wave owns a group: a lane takes the tiles lane,
+// lane + 64, ... of it and the group's sums are a wave reduction with no barrier.
+template <int N>
+__global__ __launch_bounds__(64 * kGroupsPerWorkgroup) void sparse_sums_kernel(const Batch<Job> batch)
+{
+    constexpr int T = Group<N>::kTiles, PER_LANE = T / 64;
+    uint32_t block;
+    const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
+    const MapShape& s = job.shape;
+    const uint32_t lane = threadIdx.x & 63u, group = block * kGroupsPerWorkgroup + (threadIdx.x >> 6);
+    if (group >= job.wg_count) return;
+    uint32_t byte[PER_LANE];
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) {
+        const uint32_t b = group * T + j * 64 + lane;
+        byte[j] = job.info[b < s.tiles ? b : s.tiles - 1u];
+    }
+    Sums mine = {0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) {
+        const uint32_t b = group * T + j * 64 + lane;
+        if (b < s.tiles) mine = mine + tile_sums(byte[j], tile_pos(s, b), s.two_eps > 0.0f);
+    }
+    const Sums total = wave_total(wave_inclusive_scan(narrow(mine)));
+    if (lane == 0u) job.wg[group] = total;
+}
+
+// ---- pass 2: exclusive scan of the group sums, in place; totals -----------------------------------
+// One workgroup per set; sets with few groups skip it (pass 3 adds up the sums itself).  A
+// round covers kScanRows rows of kScanThreads consecutive groups, thread t taking the t-th
+// group of every row (contiguous loads and stores; the next round's loads are in flight while
+// this one is scanned).  Each row is scanned inside the waves; the (row, wave) totals of the
+// round -- 32 numbers per field, still below 2^32 together -- are scanned by the first wave
+// in row-major order and handed back through LDS; a 64-bit carry links the rounds.
+constexpr int kScanRows = 4;
+
 __global__ __launch_bounds__(kScanThreads) void sparse_scan_kernel(const Batch<Job> batch)
 {
+    constexpr int WAVES = kScanThreads / 64, CELLS = kScanRows * WAVES;
+    constexpr uint32_t ROUND = kScanThreads * kScanRows;
+    static_assert(CELLS < 64, "one wave scans a round's (row, wave) totals");
     const Job& job = batch.item[blockIdx.x];
     if (!job.scanned) return;                                 // workgroup-uniform
     Sums* wg_sums = job.wg;
     const uint32_t count = job.wg_count, tiles = job.shape.tiles;
-    uint64_t* totals = job.totals;
-    __shared__ Sums lds[kScanThreads];
-    const int t = threadIdx.x;
+    __shared__ Sums32 cell_total[CELLS];                      // inclusive end of wave w's part of row j, at [j * WAVES + w]
+    __shared__ Sums32 cell_before[CELLS + 1];                 // what precedes a cell in its round; [CELLS]: the whole round
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     Sums carry = {0, 0, 0};
-    for (uint32_t base = 0; base < count; base += kScanThreads) {     // every thread walks every chunk
-        const uint32_t i = base + t;
-        const Sums mine = i < count ? wg_sums[i] : Sums{0, 0, 0};
-        lds[t] = mine;
-        __syncthreads();
-        for (int step = 1; step < kScanThreads; step <<= 1) {
-            Sums add = {0, 0, 0};
-            if (t >= step) add = lds[t - step];
-            __syncthreads();
-            lds[t] = lds[t] + add;
-            __syncthreads();
-        }
-        const Sums inclusive = lds[t];
-        const Sums chunk = lds[kScanThreads - 1];
-        if (i < count)
-            wg_sums[i] = Sums{carry.values + inclusive.values - mine.values,
-                              carry.index_bytes + inclusive.index_bytes - mine.index_bytes,
-                              carry.sparse_tiles + inclusive.sparse_tiles - mine.sparse_tiles};
-        carry = carry + chunk;
-        __syncthreads();
+    Sums next[kScanRows];
+#pragma unroll
+    for (int j = 0; j < kScanRows; ++j) {
+        const uint32_t i = j * kScanThreads + t;
+        next[j] = i < count ? wg_sums[i] : Sums{0, 0, 0};
     }
+#pragma nounroll
+    for (uint32_t base = 0; base < count; base += ROUND) {    // workgroup-uniform trip count
+        Sums32 own[kScanRows], inc[kScanRows];
+#pragma unroll
+        for (int j = 0; j < kScanRows; ++j) {
+            const uint32_t i = base + ROUND + j * kScanThreads + t;
+            own[j] = narrow(next[j]);
+            next[j] = i < count ? wg_sums[i] : Sums{0, 0, 0};
+        }
+#pragma unroll
+        for (int j = 0; j < kScanRows; ++j) {
+            inc[j] = wave_inclusive_scan(own[j]);
+            if (lane == 63u) cell_total[j * WAVES + wave] = inc[j];
+        }
+        __syncthreads();
+        if (wave == 0u) {
+            const Sums32 mine = lane < (uint32_t)CELLS ? cell_total[lane] : Sums32{0, 0, 0};
+            const Sums32 upto = wave_inclusive_scan(mine);
+            if (lane < (uint32_t)CELLS)
+                cell_before[lane] = Sums32{upto.values - mine.values, upto.index_bytes - mine.index_bytes,
+                                           upto.sparse_tiles - mine.sparse_tiles};
+            if (lane == (uint32_t)CELLS - 1u) cell_before[CELLS] = upto;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kScanRows; ++j) {
+            const uint32_t i = base + j * kScanThreads + t;
+            const Sums32 before = cell_before[j * WAVES + wave];
+            if (i < count)
+                wg_sums[i] = Sums{carry.values + before.values + inc[j].values - own[j].values,
+                                  carry.index_bytes + before.index_bytes + inc[j].index_bytes - own[j].index_bytes,
+                                  carry.sparse_tiles + before.sparse_tiles + inc[j].sparse_tiles - own[j].sparse_tiles};
+        }
+        const Sums32 round = cell_before[CELLS];
+        carry = carry + Sums{round.values, round.index_bytes, round.sparse_tiles};
+    }
+    uint64_t* totals = job.totals;
     if (t == 0 && totals) {
         totals[0] = carry.values;
         totals[1] = carry.index_bytes;
@@ -365,19 +544,21 @@ __global__ __launch_bounds__(kScanThreads) void sparse_scan_kernel(const Batch<J
 
 // ---- pass 3 (encode): values and CSR structure to their place ---------------------------------------
 template <typename Bits, int N>
-__global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const Batch<Job> batch)
+__global__ __launch_bounds__(Group<N>::kTiles) void sparse_write_kernel(const Batch<Job> batch)
 {
-    __shared__ uint64_t lds[3 * kTileWaves];
+    constexpr int T = Group<N>::kTiles, WAVES = Group<N>::kWaves;
+    typedef typename Alias<Bits>::type StagedBits;
+    __shared__ uint64_t lds[3 * kMaxWaves];
+    __shared__ __attribute__((aligned(16))) uint8_t stage_v[Stage<Bits, N>::kValueBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t stage_i[Stage<Bits, N>::kIndexBytes];
     uint32_t block;
     const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
     const MapShape& s = job.shape;
     const uint8_t* info = job.info;
     const Sums* wg = job.wg;
     const bool scanned = job.scanned != 0u;
-    Bits* values = static_cast<Bits*>(job.values);
-    uint8_t* indices = job.indices;
     uint64_t* totals = job.totals;
-    const uint32_t b = block * kTileThreads + threadIdx.x;
+    const uint32_t b = block * T + threadIdx.x;
     const bool live = b < s.tiles;
     TilePos t = {0, 1, 1};
     uint32_t byte = 0x80u;
@@ -389,73 +570,84 @@ __global__ __launch_bounds__(kTileThreads) void sparse_write_kernel(const Batch<
         mine = tile_sums(byte, t, s.two_eps > 0.0f);
         load_tile<Bits, N>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, s.rows_are_vectors != 0u, e);
     }
-    const Sums base = workgroup_base(wg, scanned, block, lds);
+    const Sums base = workgroup_base<WAVES>(wg, scanned, block, lds);
     Sums total;
-    const Sums before = workgroup_exclusive_scan(mine, lds, &total);
+    const Sums before = workgroup_exclusive_scan<WAVES>(mine, lds, &total);
     if (!scanned && totals && block == job.wg_count - 1 && threadIdx.x == 0) {
         totals[0] = base.values + total.values;
         totals[1] = base.index_bytes + total.index_bytes;
         totals[2] = base.sparse_tiles + total.sparse_tiles;
         totals[3] = (uint64_t)s.tiles - totals[2];
     }
-    if (!live) return;
-    Bits* v = values + base.values + before.values;
-    if ((byte & 0x80u) && s.two_eps > 0.0f) {                 // dense, predictive: code bytes + outliers
-        uint8_t code[N][N];
-        lorenzo_codes<Bits, N>(e, t, s.two_eps, code);
-        uint8_t* codes = indices + base.index_bytes + before.index_bytes;
-        uint32_t k = 0;
+    // this workgroup's slices of the two streams
+    Bits* value_slice = static_cast<Bits*>(job.values) + base.values;
+    uint8_t* index_slice = job.indices + base.index_bytes;
+    if (live) {
+        StagedBits* v = reinterpret_cast<StagedBits*>(stage_v + phase_of(value_slice)) + before.values;
+        uint8_t* idx = stage_i + phase_of(index_slice) + before.index_bytes;
+        if ((byte & 0x80u) && s.two_eps > 0.0f) {             // dense, predictive: code bytes + outliers
+            uint8_t code[N][N];
+            lorenzo_codes<Bits, N>(e, t, s.two_eps, code);
+            uint32_t k = 0;
 #pragma unroll
-        for (int r = 0; r < N; ++r)
+            for (int r = 0; r < N; ++r)
 #pragma unroll
-            for (int c = 0; c < N; ++c)
-                if (r < (int)t.rows && c < (int)t.cols) {
-                    codes[r * t.cols + c] = code[r][c];
-                    if (code[r][c] == 0) v[k++] = e[r][c];
-                }
-    } else if (byte & 0x80u) {                                // dense: the tile, row-major
+                for (int c = 0; c < N; ++c)
+                    if (r < (int)t.rows && c < (int)t.cols) {
+                        idx[r * t.cols + c] = code[r][c];
+                        if (code[r][c] == 0) v[k++] = e[r][c];
+                    }
+        } else if (byte & 0x80u) {                            // dense: the tile, row-major
 #pragma unroll
-        for (int r = 0; r < N; ++r)
+            for (int r = 0; r < N; ++r)
 #pragma unroll
-            for (int c = 0; c < N; ++c)
-                if (r < (int)t.rows && c < (int)t.cols) v[r * t.cols + c] = e[r][c];
-    } else {                                                  // sparse: row_ptr, then columns; values alongside
-        uint8_t* row_ptr = indices + base.index_bytes + before.index_bytes;
-        uint8_t* col = row_ptr + t.rows + 1;
-        uint32_t k = 0;
+                for (int c = 0; c < N; ++c)
+                    if (r < (int)t.rows && c < (int)t.cols) v[r * t.cols + c] = e[r][c];
+        } else {                                              // sparse: row_ptr, then columns; values alongside
+            uint8_t* col = idx + t.rows + 1;
+            uint32_t k = 0;
 #pragma unroll
-        for (int r = 0; r < N; ++r) {
-            if (r <= (int)t.rows) row_ptr[r] = (uint8_t)k;    // r == rows: the closing entry
+            for (int r = 0; r < N; ++r) {
+                if (r <= (int)t.rows) idx[r] = (uint8_t)k;    // r == rows: the closing entry
 #pragma unroll
-            for (int c = 0; c < N; ++c) {
-                if (bits_of<Bits>(e[r][c]) != 0u) {           // padding is zero, so it never gets here
-                    v[k] = e[r][c];
-                    col[k] = (uint8_t)c;
-                    ++k;
+                for (int c = 0; c < N; ++c) {
+                    if (bits_of<Bits>(e[r][c]) != 0u) {       // padding is zero, so it never gets here
+                        v[k] = e[r][c];
+                        col[k] = (uint8_t)c;
+                        ++k;
+                    }
                 }
             }
+            if ((int)t.rows == N) idx[N] = (uint8_t)k;
         }
-        if ((int)t.rows == N) row_ptr[N] = (uint8_t)k;
     }
+    __syncthreads();
+    stage_to_stream<T>(stage_v, reinterpret_cast<uint8_t*>(value_slice), (uint32_t)total.values * (uint32_t)sizeof(Bits));
+    stage_to_stream<T>(stage_i, index_slice, (uint32_t)total.index_bytes);
 }
 
 // ---- pass 3 (decode): tiles back from the streams -------------------------------------------------
 // A stream this library did not write must not make the kernel read or write out of bounds:
-// a tile whose slice would leave a stream is zero-filled, entries outside the tile are dropped.
+// only the part of a slice that lies inside the stream is staged, a tile whose piece would
+// leave the stream is zero-filled, and whatever the staged bytes say, a thread reads no further
+// than N bytes / one value past its own piece.
 template <typename Bits, int N>
-__global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const Batch<Job> batch)
+__global__ __launch_bounds__(Group<N>::kTiles) void sparse_read_kernel(const Batch<Job> batch)
 {
-    __shared__ uint64_t lds[3 * kTileWaves];
+    constexpr int T = Group<N>::kTiles, WAVES = Group<N>::kWaves;
+    typedef typename Alias<Bits>::type StagedBits;
+    typedef typename TileMask<N>::type Mask;
+    __shared__ uint64_t lds[3 * kMaxWaves];
+    __shared__ __attribute__((aligned(16))) uint8_t stage_v[Stage<Bits, N>::kValueBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t stage_i[Stage<Bits, N>::kIndexBytes];
     uint32_t block;
     const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
     const MapShape& s = job.shape;
     const uint8_t* info = job.info;
     const Sums* wg = job.wg;
     const bool scanned = job.scanned != 0u;
-    const Bits* values = static_cast<const Bits*>(job.values);
     const uint64_t value_count = job.value_count, index_count = job.index_count;
-    const uint8_t* indices = job.indices;
-    const uint32_t b = block * kTileThreads + threadIdx.x;
+    const uint32_t b = block * T + threadIdx.x;
     const bool live = b < s.tiles;
     TilePos t = {0, 1, 1};
     uint32_t byte = 0x80u;
@@ -465,32 +657,44 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const Batch<J
         byte = info[b];
         mine = tile_sums(byte, t, s.two_eps > 0.0f);
     }
-    const Sums base = workgroup_base(wg, scanned, block, lds);
+    const Sums base = workgroup_base<WAVES>(wg, scanned, block, lds);
     Sums total;
-    const Sums before = workgroup_exclusive_scan(mine, lds, &total);
+    const Sums before = workgroup_exclusive_scan<WAVES>(mine, lds, &total);
+
+    // what the streams hold of this workgroup's slices
+    const Bits* value_slice = static_cast<const Bits*>(job.values) + base.values;
+    const uint8_t* index_slice = job.indices + base.index_bytes;
+    uint64_t have_v = base.values < value_count ? value_count - base.values : 0u;
+    uint64_t have_i = base.index_bytes < index_count ? index_count - base.index_bytes : 0u;
+    if (have_v > total.values) have_v = total.values;
+    if (have_i > total.index_bytes) have_i = total.index_bytes;
+    stream_to_stage<T>(stage_v, reinterpret_cast<const uint8_t*>(value_slice), (uint32_t)have_v * (uint32_t)sizeof(Bits));
+    stream_to_stage<T>(stage_i, index_slice, (uint32_t)have_i);
+    __syncthreads();
     if (!live) return;
-    Bits* out = static_cast<Bits*>(const_cast<void*>(s.x)) + t.origin;
-    const uint64_t v0 = base.values + before.values, i0 = base.index_bytes + before.index_bytes;
+
+    const StagedBits* v = reinterpret_cast<const StagedBits*>(stage_v + phase_of(value_slice)) + before.values;
+    const uint8_t* idx = stage_i + phase_of(index_slice) + before.index_bytes;
     const uint32_t count = byte & 0x7fu;
-    const bool in_bounds = v0 + mine.values <= value_count && i0 + mine.index_bytes <= index_count;
-    const Bits* v = values + v0;
-    if ((byte & 0x80u) && s.two_eps > 0.0f) {                 // dense, predictive
-        if (!in_bounds) {
-            const Bits zeros[N][N] = {};
-            store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, zeros);
-            return;
-        }
-        const uint8_t* codes = indices + i0;
+    const uint32_t last = count > 0u ? count - 1u : 0u;       // reads of values are clamped to the tile's piece
+    const bool in_bounds = before.values + mine.values <= have_v && before.index_bytes + mine.index_bytes <= have_i;
+    Bits* out = static_cast<Bits*>(const_cast<void*>(s.x)) + t.origin;
+    Bits e[N][N];
+#pragma unroll
+    for (int r = 0; r < N; ++r)
+#pragma unroll
+        for (int c = 0; c < N; ++c) e[r][c] = (Bits)0;
+
+    if (in_bounds && (byte & 0x80u) && s.two_eps > 0.0f) {    // dense, predictive
         uint8_t code[N][N];                                   // all code bytes first (clamped addresses)
 #pragma unroll
         for (int r = 0; r < N; ++r)
 #pragma unroll
             for (int c = 0; c < N; ++c) {
                 const uint32_t rr = r < (int)t.rows ? r : t.rows - 1, cc = c < (int)t.cols ? c : t.cols - 1;
-                code[r][c] = codes[rr * t.cols + cc];
+                code[r][c] = idx[rr * t.cols + cc];
             }
         int32_t q[N][N];
-        Bits e[N][N];
         uint32_t used = 0;
 #pragma unroll
         for (int r = 0; r < N; ++r) {
@@ -499,10 +703,9 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const Batch<J
                 const int32_t left = c > 0 ? q[r][c - 1] : 0, up = r > 0 ? q[r - 1][c] : 0;
                 const int32_t diag = (r > 0 && c > 0) ? q[r - 1][c - 1] : 0;
                 q[r][c] = 0;
-                e[r][c] = (Bits)0;
                 if (r < (int)t.rows && c < (int)t.cols) {
                     if (code[r][c] == 0) {                    // an outlier: unchanged, and back on the lattice
-                        e[r][c] = used < count ? v[used] : (Bits)0;
+                        e[r][c] = used < count ? (Bits)v[used] : (Bits)0;
                         ++used;
                         bool ok;
                         q[r][c] = lattice(value_of<Bits>(e[r][c]), s.two_eps, ok);
@@ -513,51 +716,25 @@ __global__ __launch_bounds__(kTileThreads) void sparse_read_kernel(const Batch<J
                 }
             }
         }
-        store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, e);
-        return;
-    }
-    if ((byte & 0x80u) && in_bounds && count == t.rows * t.cols) {
-        Bits e[N][N];                                         // all loads first (clamped), then the stores
+    } else if (in_bounds) {
+        // verbatim: a dense tile holds every element it has, a sparse one those its CSR structure
+        // names; either way the k-th set bit of the occupancy is the k-th value of the piece
+        Mask m = 0;
+        if (byte & 0x80u) {
+            if (count == t.rows * t.cols) m = valid_mask<N>(t);
+        } else if (count > 0u) {
+            m = csr_mask<N>(idx, t, count);
+        }
 #pragma unroll
         for (int r = 0; r < N; ++r)
 #pragma unroll
             for (int c = 0; c < N; ++c) {
-                const uint32_t rr = r < (int)t.rows ? r : t.rows - 1, cc = c < (int)t.cols ? c : t.cols - 1;
-                e[r][c] = v[rr * t.cols + cc];
+                const int p = r * N + c;
+                const uint32_t rank = popcount((Mask)(m & (((Mask)1 << p) - 1)));
+                if ((m >> p) & 1) e[r][c] = (Bits)v[rank < last ? rank : last];
             }
-        store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, e);
-        return;
     }
-    {
-        const Bits zeros[N][N] = {};
-        store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, zeros);
-    }
-    if ((byte & 0x80u) || !in_bounds || count == 0u) return;
-    const uint8_t* row_ptr = indices + i0;
-    const uint8_t* col = row_ptr + t.rows + 1;
-    uint32_t rp[N + 1];                                       // row_ptr[1..rows], clamped reads
-#pragma unroll
-    for (int r = 1; r <= N; ++r) rp[r] = row_ptr[r <= (int)t.rows ? r : t.rows];
-    // entries in chunks of 8, each chunk's loads issued together; the row of entry k is the
-    // number of rows that end at or before k
-    for (uint32_t k0 = 0; k0 < count; k0 += 8) {
-        uint32_t cc[8];
-        Bits vv[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t k = k0 + j < count ? k0 + j : count - 1;
-            cc[j] = col[k];
-            vv[j] = v[k];
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t k = k0 + j;
-            uint32_t r = 0;
-#pragma unroll
-            for (int q = 1; q <= N; ++q) r += (q <= (int)t.rows && rp[q] <= k) ? 1u : 0u;
-            if (k < count && r < t.rows && cc[j] < t.cols) out[(uint64_t)r * s.w + cc[j]] = vv[j];
-        }
-    }
+    store_tile<Bits, N>(out, t, s.w, s.rows_are_vectors != 0u, e);
 }
 
 // ---- host side ------------------------------------------------------------------------------------
@@ -575,7 +752,8 @@ int64_t tile_count(int64_t maps, int64_t h, int64_t w, int64_t n)
     return maps * ((h + n - 1) / n) * ((w + n - 1) / n);
 }
 
-uint32_t workgroups(int64_t tiles) { return (uint32_t)((tiles + kTileThreads - 1) / kTileThreads); }
+int tiles_per_workgroup(int n) { return n == 8 ? Group<8>::kTiles : Group<4>::kTiles; }
+uint32_t workgroups(int64_t tiles, int n) { return (uint32_t)((tiles + tiles_per_workgroup(n) - 1) / tiles_per_workgroup(n)); }
 
 MapShape make_shape(const void* x, int64_t h, int64_t w, int n, int64_t tiles, float eps)
 {
@@ -621,7 +799,7 @@ size_t fh_sparse_workspace_bytes(int64_t maps, int64_t h, int64_t w, int32_t n)
 {
     const int64_t t = fh::tile_count(maps, h, w, n);
     if (t < 0) return 0;
-    return sizeof(fh::Sums) * (size_t)(fh::workgroups(t) > 0 ? fh::workgroups(t) : 1);
+    return sizeof(fh::Sums) * (size_t)(fh::workgroups(t, n) > 0 ? fh::workgroups(t, n) : 1);
 }
 
 }  // extern "C"
@@ -662,9 +840,9 @@ fh_status check_decode(const fh_sparse_decode_item& it, int64_t* tiles)
 }
 
 template <typename Kernel>
-void launch_tiles(Kernel kernel, const Batch<Job>& b, hipStream_t s)
+void launch_tiles(Kernel kernel, const Batch<Job>& b, int threads, hipStream_t s)
 {
-    if (b.count > 0) hipLaunchKernelGGL(kernel, dim3(b.block_start[b.count]), dim3(kTileThreads), 0, s, b);
+    if (b.count > 0) hipLaunchKernelGGL(kernel, dim3(b.block_start[b.count]), dim3(threads), 0, s, b);
 }
 
 // the (dtype, window) instantiation of a templated pass
@@ -674,16 +852,19 @@ void launch_tiles(Kernel kernel, const Batch<Job>& b, hipStream_t s)
 
 // jobs of one run (same dtype and window): every set with tiles in `tiled`, all sets in `all`
 struct Run {
-    Batch<Job> tiled, all;
+    Batch<Job> tiled, grouped, all;                // pass 3 | pass 1 (several groups per workgroup) | scan
     bool any_scan;
 };
 
 void add_job(Run& run, Job job, int64_t tiles)
 {
-    job.wg_count = workgroups(tiles);
+    job.wg_count = workgroups(tiles, (int)job.shape.n);
     job.scanned = (tiles == 0 || job.wg_count > kSelfScanLimit) ? 1u : 0u;   // an empty set: the scan kernel writes its totals
     if (job.scanned) run.any_scan = true;
-    if (tiles > 0) push(run.tiled, job, job.wg_count);
+    if (tiles > 0) {
+        push(run.tiled, job, job.wg_count);
+        push(run.grouped, job, (job.wg_count + kGroupsPerWorkgroup - 1) / kGroupsPerWorkgroup);
+    }
     push(run.all, job, 1);
 }
 
@@ -708,6 +889,7 @@ fh_status fh_sparse_encode_batch(const fh_sparse_encode_item* items, int32_t cou
     while (i < count) {                                       // runs of one dtype and window, at most kBatch long
         Run run;
         reset(run.tiled);
+        reset(run.grouped);
         reset(run.all);
         run.any_scan = false;
         const int dtype = items[i].dtype, n = items[i].n;
@@ -715,7 +897,7 @@ fh_status fh_sparse_encode_batch(const fh_sparse_encode_item* items, int32_t cou
             const fh_sparse_encode_item& it = items[i];
             int64_t tiles;
             check_encode(it, &tiles);
-            if ((uint64_t)run.tiled.block_start[run.tiled.count] + workgroups(tiles) > (uint64_t)INT_MAX) {
+            if ((uint64_t)run.tiled.block_start[run.tiled.count] + workgroups(tiles, n) > (uint64_t)INT_MAX) {
                 if (run.all.count == 0) return FH_ERR_BAD_NUMEL;
                 break;
             }
@@ -733,11 +915,12 @@ fh_status fh_sparse_encode_batch(const fh_sparse_encode_item* items, int32_t cou
         }
         launched = true;
         seal(run.tiled);
+        seal(run.grouped);
         seal(run.all);
-        launch_tiles(FH_SPARSE_PICK(sparse_count_kernel, dtype, n), run.tiled, s);
+        launch_tiles(FH_SPARSE_PICK(sparse_count_kernel, dtype, n), run.tiled, tiles_per_workgroup(n), s);
         if (run.any_scan)
             hipLaunchKernelGGL(sparse_scan_kernel, dim3(run.all.count), dim3(kScanThreads), 0, s, run.all);
-        launch_tiles(FH_SPARSE_PICK(sparse_write_kernel, dtype, n), run.tiled, s);
+        launch_tiles(FH_SPARSE_PICK(sparse_write_kernel, dtype, n), run.tiled, tiles_per_workgroup(n), s);
     }
     if (!launched) return FH_OK;
     return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
@@ -758,6 +941,7 @@ fh_status fh_sparse_decode_batch(const fh_sparse_decode_item* items, int32_t cou
     while (i < count) {
         Run run;
         reset(run.tiled);
+        reset(run.grouped);
         reset(run.all);
         run.any_scan = false;
         const int dtype = items[i].dtype, n = items[i].n;
@@ -766,7 +950,7 @@ fh_status fh_sparse_decode_batch(const fh_sparse_decode_item* items, int32_t cou
             int64_t tiles;
             check_decode(it, &tiles);
             if (tiles == 0) { ++i; continue; }                // nothing to restore
-            if ((uint64_t)run.tiled.block_start[run.tiled.count] + workgroups(tiles) > (uint64_t)INT_MAX) {
+            if ((uint64_t)run.tiled.block_start[run.tiled.count] + workgroups(tiles, n) > (uint64_t)INT_MAX) {
                 if (run.all.count == 0) return FH_ERR_BAD_NUMEL;
                 break;
             }
@@ -786,11 +970,13 @@ fh_status fh_sparse_decode_batch(const fh_sparse_decode_item* items, int32_t cou
         if (run.tiled.count == 0) continue;                   // only empty sets in this run
         launched = true;
         seal(run.tiled);
+        seal(run.grouped);
         seal(run.all);
-        launch_tiles(sparse_sums_kernel, run.tiled, s);
+        launch_tiles(n == 2 ? sparse_sums_kernel<2> : n == 4 ? sparse_sums_kernel<4> : sparse_sums_kernel<8>, run.grouped,
+                     64 * kGroupsPerWorkgroup, s);
         if (run.any_scan)
             hipLaunchKernelGGL(sparse_scan_kernel, dim3(run.all.count), dim3(kScanThreads), 0, s, run.all);
-        launch_tiles(FH_SPARSE_PICK(sparse_read_kernel, dtype, n), run.tiled, s);
+        launch_tiles(FH_SPARSE_PICK(sparse_read_kernel, dtype, n), run.tiled, tiles_per_workgroup(n), s);
     }
     if (!launched) return FH_OK;
     return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;

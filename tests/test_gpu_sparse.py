@@ -95,11 +95,19 @@ def test_all_zero_and_all_dense_maps(api):
     assert t.tolist() == [2400, 150 * 5 + 2400, 150, 0]
 
 
-def test_more_tiles_than_one_scan_chunk(api):
-    # 1024 workgroups of 256 tiles fill one chunk of the middle pass; this needs three
-    maps, h, w, n = 9000, 16, 16, 2                         # 576000 tiles -> 2250 workgroups
+def test_more_groups_than_the_write_pass_adds_up_itself(api):
+    # beyond 2048 groups of 256 tiles the scan kernel runs between the passes
+    maps, h, w, n = 9000, 16, 16, 2                         # 576000 tiles -> 2250 groups
     x = W.salient_feature_maps(maps, h, w, seed=77)
-    _check(api, x, maps, h, w, n, 0.5, name="scan chunks")
+    _check(api, x, maps, h, w, n, 0.5, name="scan kernel")
+
+
+def test_many_rows_of_the_scan_kernel(api):
+    # a row of the scan kernel covers 512 groups; this set needs 17, the last one ragged
+    maps, h, w, n = 700, 112, 112, 2                        # 2 195 200 tiles -> 8575 groups
+    x = W.salient_feature_maps(maps, h, w, seed=78)
+    _check(api, x, maps, h, w, n, 0.5, name="scan rounds")
+    _check(api, x, maps, h, w, n, 0.5, name="scan rounds, predictive", eps=0.05)
 
 
 def test_full_size_salient_channels_of_a_layer(api):
