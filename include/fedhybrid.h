@@ -238,7 +238,8 @@ int32_t   fh_mixed_batch_capacity(void);
  *   - values: one stream in block order -- the non-zeros of a sparse block in row-major order,
  *     all elements of a dense block in row-major order;
  *   - indices: one byte stream in block order -- per sparse block row_ptr[0..rows] (non-zeros in
- *     the block's rows before r) followed by the column inside the block of each non-zero;
+ *     the block's rows before r) followed by the column inside the block of each non-zero, in
+ *     row-major order (columns ascending inside a row; the decoder relies on that order);
  *   - totals: uint64[4] = {values written, index bytes written, sparse blocks, dense blocks};
  *   - decoding restores the input bit for bit;
  *   - with eps > 0 (the same value on both calls) dense blocks take the section's predictive
