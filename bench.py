@@ -112,32 +112,43 @@ def bench_classify(args, api, W, dev) -> int:
 def bench_mixed(args, api, W, dev) -> int:
     """Compress + decompress with salient channels routed around the quantiser, over the same
     MobileNetV2-style activations with channel-clustered outliers as the classification
-    bench (the planted channels are the kept ones; slot tables are built once, outside the
+    bench, or (--config 4) over the transformer set with outliers planted in 4 % of the hidden
+    channels (the planted channels are the kept ones; slot tables are built once, outside the
     timed region).  One step = every tensor compressed, then every tensor restored."""
     import numpy as np
     import torch
 
-    shapes = ((64, 32, 112 * 112), (64, 96, 112 * 112), (64, 144, 56 * 56), (64, 192, 28 * 28), (64, 384, 14 * 14))
-    G, B, rounding = 128, 4, "nearest"
+    if args.config == 4:                                      # transformer activations, one channel per element
+        shapes = tuple(s for _ in range(12) for s in ((16 * 512, 768, 1), (16 * 512, 3072, 1)))
+        G, B, rounding, dtype, dist = 64, 2, "stochastic", "bf16", ("gauss", "gelu")
+        workload = "mixed_transformer_l12_b16_s512_bf16_outlier_channels_g64_b2_stochastic"
+    else:
+        shapes = ((64, 32, 112 * 112), (64, 96, 112 * 112), (64, 144, 56 * 56), (64, 192, 28 * 28), (64, 384, 14 * 14))
+        G, B, rounding, dtype, dist = 128, 4, "nearest", "f32", ("relu", "relu")
+        workload = "mixed_mobilenetv2_b64_outlier_channels_g128_b4_nearest"
+    tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+    esize = 2 if dtype == "bf16" else 4
     t0 = time.time()
     host, jobs = [], []
     alg_c = alg_d = 0
     for i, (outer, C, inner) in enumerate(shapes):
-        x, planted = W.outlier_channel_tensor(outer, C, inner, seed=i, dist="relu")
+        x, planted = W.outlier_channel_tensor(outer, C, inner, seed=i, dist=dist[i % 2], dtype=dtype)
         mask = np.zeros(C, np.uint8)
         mask[planted] = 1
         cap = len(planted)
         host.append((x, mask, cap))
-        xd = torch.from_numpy(x).to(dev)
+        xd = torch.from_numpy(x.view(np.int16) if dtype == "bf16" else x).to(dev)
+        if dtype == "bf16":
+            xd = xd.view(torch.bfloat16)
         slots = api.fh_channel_slots(torch.from_numpy(mask).to(dev), cap)
         packed, meta = api.alloc_compressed(x.size, G, B, dev)
-        raw = torch.empty(outer * cap * inner, dtype=torch.float32, device=dev)
-        out = torch.empty(x.size, dtype=torch.float32, device=dev)
+        raw = torch.empty(outer * cap * inner, dtype=tdtype, device=dev)
+        out = torch.empty(x.size, dtype=tdtype, device=dev)
         jobs.append((xd, outer, C, inner, slots, cap, packed, meta, raw, out, i))
         n = x.size
-        side = (n * B + 7) // 8 + 8 * ((n + G - 1) // G) + outer * cap * inner * 4
-        alg_c += n * 4 + side
-        alg_d += side + n * 4
+        side = (n * B + 7) // 8 + 8 * ((n + G - 1) // G) + outer * cap * inner * esize
+        alg_c += n * esize + side
+        alg_d += side + n * esize
     torch.cuda.synchronize()
     nbytes = sum(x.nbytes for x, _, _ in host)
     print(f"[bench] mixed: {len(jobs)} tensors, {nbytes / 2**20:.1f} MiB resident "
@@ -187,8 +198,8 @@ def bench_mixed(args, api, W, dev) -> int:
         "metric": "activation compress+decompress GB/s with salient channels kept raw, on 1 MI355X",
         "value": round(nbytes / elapsed / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "mixed_mobilenetv2_b64_outlier_channels_g128_b4_nearest", "tensors": len(jobs),
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": workload, "tensors": len(jobs),
                    "input_bytes": nbytes,
                    "entry_point": ("fh_compress_mixed + fh_decompress_mixed (per tensor)" if args.per_tensor
                                    else "fh_compress_mixed_batch + fh_decompress_mixed_batch"),
@@ -209,8 +220,8 @@ def bench_mixed(args, api, W, dev) -> int:
         for (x, mask, cap), (outer, C, inner) in zip(host, shapes):
             t1 = time.perf_counter()
             slots, _ = oracle.channel_slots(mask, cap)
-            p, m, r = oracle.compress_mixed(x, outer, C, inner, slots, cap, G, B, rounding, 1, 0)
-            oracle.decompress_mixed(p, m, r, outer, C, inner, slots, cap, G, B)
+            p, m, r = oracle.compress_mixed(x, outer, C, inner, slots, cap, G, B, rounding, 1, 0, dtype=dtype)
+            oracle.decompress_mixed(p, m, r, outer, C, inner, slots, cap, G, B, raw_dtype=dtype, out_dtype=dtype)
             t_cpu += time.perf_counter() - t1
             done += x.nbytes
             if t_cpu > 20.0:

@@ -173,6 +173,75 @@ __device__ __forceinline__ void kept_runs(const ChannelMap& cm, const ElemPos& w
     }
 }
 
+// ---- one channel per element --------------------------------------------------------------
+// With inner == 1, channels a multiple of N and at most 16384 raw-store rows, the N channels of
+// a lane's run never wrap and their table entries are one vector load; what the lane needs then
+// comes out of packed 16-bit arithmetic on the entry pairs, with no branch and no per-element
+// compare: an entry s names a row iff 0 <= s < raw_channels, i.e. iff bit 15 of ~s & (s - raw_channels)
+// is set (s - raw_channels cannot wrap: both are below 2^15 in magnitude).
+typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
+
+template <int N> struct KeptVector {
+    uint32_t keep[N / 2];      // half-word j: 0xffff iff element j belongs to a kept channel
+    uint32_t slot[N / 2];      // half-word j: that channel's raw-store row, 0 for a normal channel
+    uint32_t row;              // raw-store index of (the run's sample, row 0), counted from the wave's first sample
+};
+
+template <int N>
+__device__ __forceinline__ bool one_channel_per_element(const ChannelMap& cm)
+{
+    return cm.inner.d == 1u && (cm.channels.d & (N - 1)) == 0u && cm.raw_channels - 1u < 16384u;
+}
+
+template <int ROWS, int N>
+__device__ __forceinline__ void kept_vectors(const ChannelMap& cm, const ElemPos& wave_pos, uint32_t lane_off,
+                                             uint32_t row_stride, KeptVector<N> (&kv)[ROWS])
+{
+    uint32_t w[ROWS][N / 2];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {                          // all table loads first
+        const ElemPos p = advance(cm, wave_pos, r * row_stride + lane_off);
+        kv[r].row = (p.o - wave_pos.o) * cm.raw_channels;
+        if constexpr (N == 8) {
+            const u32x4 s = *reinterpret_cast<const u32x4*>(cm.slots + p.c);
+            w[r][0] = s.x; w[r][1] = s.y; w[r][2] = s.z; w[r][3] = s.w;
+        } else {
+            const u32x2 s = *reinterpret_cast<const u32x2*>(cm.slots + p.c);
+            w[r][0] = s.x; w[r][1] = s.y;
+        }
+    }
+    const int16_t rows = (int16_t)cm.raw_channels;
+    const i16x2 limit = {rows, rows};
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+        for (int k = 0; k < N / 2; ++k) {
+            const i16x2 s = __builtin_bit_cast(i16x2, w[r][k]);
+            const i16x2 keep = (~s & (s - limit)) >> 15;      // arithmetic shift: 0xffff or 0 per half
+            kv[r].keep[k] = __builtin_bit_cast(uint32_t, keep);
+            kv[r].slot[k] = w[r][k] & kv[r].keep[k];
+        }
+}
+
+// byte offset, from the raw-store row of the wave's first sample, of the entry element j of the run reads or writes
+// (a normal element gets row 0 of its sample, which exists: raw_channels >= 1)
+template <int N, int ELEM_BYTES>
+__device__ __forceinline__ uint32_t raw_offset(const KeptVector<N>& kv, int j)
+{
+    const uint32_t slot = (j & 1) ? kv.slot[j >> 1] >> 16 : kv.slot[j >> 1] & 0xffffu;
+    return slot * ELEM_BYTES + kv.row * ELEM_BYTES;
+}
+
+// does any lane of the wave hold a kept element in this run? (a wave-uniform answer keeps the branch scalar)
+template <int N>
+__device__ __forceinline__ bool any_kept(const KeptVector<N>& kv)
+{
+    uint32_t any = 0;
+#pragma unroll
+    for (int k = 0; k < N / 2; ++k) any |= kv.keep[k];
+    return __builtin_amdgcn_ballot_w64(any != 0u) != 0ull;
+}
+
 // index into the raw store of element j of the run (whose bit in run.mask must be set)
 template <int N>
 __device__ __forceinline__ uint64_t raw_index(const ChannelMap& cm, const KeptRun<N>& run, uint32_t j)

@@ -306,6 +306,29 @@ __device__ __forceinline__ void divert_kept(const ChannelMap& cm, const KeptRun<
     }
 }
 
+// The same for one channel per element (fh_channels.hpp).  A kept element becomes a quiet NaN by
+// setting its exponent and top mantissa bit; further down the clamp of the quantiser
+// (v_med3_f32, which returns the minimum of the other two operands for a NaN) turns it into
+// code 0, so nothing else has to know about it.  (Gathering a row's kept elements in LDS to
+// store them with one instruction per 64 was measured: the gather costs more than the sparse
+// stores it replaces.)
+template <typename InT, int N>
+__device__ __forceinline__ void divert_kept_vector(uint8_t* base, const KeptVector<N>& kv, float (&x)[N])
+{
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const uint32_t keep = kv.keep[j >> 1];
+        const uint32_t bits = __builtin_bit_cast(uint32_t, x[j]);
+        if (keep & ((j & 1) ? 0xffff0000u : 0x0000ffffu)) {
+            uint8_t* p = base + raw_offset<N, (int)sizeof(InT)>(kv, j);
+            if constexpr (sizeof(InT) == 4) *reinterpret_cast<uint32_t*>(p) = bits;
+            else *reinterpret_cast<uint16_t*>(p) = (uint16_t)(bits >> 16);        // the original bits
+        }
+        const uint32_t nan = ((j & 1) ? keep : keep << 16) & 0x7fc00000u;
+        x[j] = __builtin_bit_cast(float, bits | nan);
+    }
+}
+
 // ---- interior spans: the 4-row layout --------------------------------------------------
 //   * the four rows' min/max are reduce-scattered over each quad (lane xor 1 keeps two
 //     rows, lane xor 2 keeps one), then all-reduced over the quads of the group by
@@ -340,12 +363,21 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
 
     uint32_t keptm[ROWS] = {};                                // bit j: element j of the row is kept raw
     if constexpr (MIXED) {
-        KeptRun<EPL> run[ROWS];
-        kept_runs<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
+        if (one_channel_per_element<EPL>(*cm)) {              // wave-uniform; keptm stays 0: see divert_kept_vector
+            KeptVector<EPL> kv[ROWS];
+            kept_vectors<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, kv);
+            uint8_t* base = static_cast<uint8_t*>(cm->raw) + (uint64_t)wave_pos.o * cm->raw_channels * sizeof(InT);
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
-            keptm[r] = run[r].mask;
-            if (keptm[r]) divert_kept<InT, EPL>(*cm, run[r], x[r]);
+            for (int r = 0; r < ROWS; ++r)
+                if (any_kept<EPL>(kv[r])) divert_kept_vector<InT, EPL>(base, kv[r], x[r]);
+        } else {
+            KeptRun<EPL> run[ROWS];
+            kept_runs<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                keptm[r] = run[r].mask;
+                if (keptm[r]) divert_kept<InT, EPL>(*cm, run[r], x[r]);
+            }
         }
     }
 

@@ -107,6 +107,36 @@ __device__ __forceinline__ void fetch_kept(const ChannelMap& cm, int raw_dtype, 
     }
 }
 
+// The same for one channel per element (fh_channels.hpp): every lane loads an entry per element
+// -- normal elements a harmless one -- and the kept ones are merged in by their masks.
+// `base`: the raw-store row of the wave's first sample (wave-uniform).
+template <int N, typename RawT>
+__device__ __forceinline__ void merge_kept(const uint8_t* base, const KeptVector<N>& kv, float (&v)[N])
+{
+    uint32_t bits[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const RawT e = *reinterpret_cast<const RawT*>(base + raw_offset<N, (int)sizeof(RawT)>(kv, j));
+        bits[j] = sizeof(RawT) == 4 ? (uint32_t)e : (uint32_t)e << 16;
+    }
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const int32_t pair = (int32_t)kv.keep[j >> 1];
+        const uint32_t m = (uint32_t)((j & 1) ? pair >> 16 : (pair << 16) >> 16);     // all ones iff kept
+        v[j] = __builtin_bit_cast(float, (bits[j] & m) | (__builtin_bit_cast(uint32_t, v[j]) & ~m));
+    }
+}
+// bf16 raw store into a bf16 tensor: the kept halves of each output word are the raw bits
+__device__ __forceinline__ u32x4 merge_kept_bf16(const uint8_t* base, const KeptVector<8>& kv, u32x4 o)
+{
+    uint32_t e[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) e[j] = *reinterpret_cast<const uint16_t*>(base + raw_offset<8, 2>(kv, j));
+    uint32_t out[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) out[k] = ((e[2 * k] | (e[2 * k + 1] << 16)) & kv.keep[k]) | (out[k] & ~kv.keep[k]);
+    return u32x4{out[0], out[1], out[2], out[3]};
+}
 template <typename OutT, int G, int B, bool MIXED = false>
 __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32_t tile,
                                                 const ChannelMap* cm = nullptr, int raw_dtype = 0)
@@ -132,6 +162,34 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
             const int64_t i0 = wave_base + r * ROW + lane * EPL;
             load_codes<EPL, B>(it.packed, i0, c0[r], c1[r]);
             m[r] = *reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v));
+        }
+        if constexpr (MIXED) {
+            if (one_channel_per_element<EPL>(*cm)) {          // wave-uniform
+                KeptVector<EPL> kv[kRowsPerWave];
+                kept_vectors<kRowsPerWave, EPL>(*cm, wave_pos, lane * EPL, ROW, kv);
+                const uint8_t* base = static_cast<const uint8_t*>(cm->raw) +
+                                      (uint64_t)wave_pos.o * cm->raw_channels * (raw_dtype == 0 ? 4u : 2u);
+#pragma unroll
+                for (int r = 0; r < kRowsPerWave; ++r) {
+                    const int64_t i0 = wave_base + r * ROW + lane * EPL;
+                    float v[EPL];
+                    restore<EPL, B>(c0[r], c1[r], m[r], v);
+                    const bool any = any_kept<EPL>(kv[r]);
+                    if constexpr (EPL == 4) {
+                        if (any) {
+                            if (raw_dtype == 0) merge_kept<EPL, uint32_t>(base, kv[r], v);
+                            else merge_kept<EPL, uint16_t>(base, kv[r], v);
+                        }
+                        stream_store(reinterpret_cast<f32x4*>(static_cast<float*>(it.out) + i0), f32x4{v[0], v[1], v[2], v[3]});
+                    } else {
+                        if (any && raw_dtype == 0) merge_kept<EPL, uint32_t>(base, kv[r], v);
+                        u32x4 o = pack_bf16x8(v);
+                        if (any && raw_dtype != 0) o = merge_kept_bf16(base, kv[r], o);
+                        stream_store(reinterpret_cast<u32x4*>(static_cast<uint16_t*>(it.out) + i0), o);
+                    }
+                }
+                return;
+            }
         }
         KeptRun<EPL> run[kRowsPerWave];
         if constexpr (MIXED) kept_runs<kRowsPerWave, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
