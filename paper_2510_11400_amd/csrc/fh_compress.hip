@@ -293,7 +293,9 @@ template <> struct RawElem<uint16_t> {
     }
 };
 
-// Copy the kept elements of a lane's run to the raw store and hide them from the statistics.
+// Copy the kept elements of a lane's run to the raw store and hide them from the statistics:
+// a kept element becomes a quiet NaN, which v_min_f32 / v_max_f32 pass over and which the
+// quantiser's clamp (v_med3_f32: the minimum of the other two operands for a NaN) turns into code 0.
 template <typename InT, int N>
 __device__ __forceinline__ void divert_kept(const ChannelMap& cm, const KeptRun<N>& run, float (&x)[N])
 {
@@ -361,9 +363,8 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) Loader<InT>::row(xw + r * ROW + lane * EPL, x[r]);
 
-    uint32_t keptm[ROWS] = {};                                // bit j: element j of the row is kept raw
     if constexpr (MIXED) {
-        if (one_channel_per_element<EPL>(*cm)) {              // wave-uniform; keptm stays 0: see divert_kept_vector
+        if (one_channel_per_element<EPL>(*cm)) {              // wave-uniform
             KeptVector<EPL> kv[ROWS];
             kept_vectors<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, kv);
             uint8_t* base = static_cast<uint8_t*>(cm->raw) + (uint64_t)wave_pos.o * cm->raw_channels * sizeof(InT);
@@ -374,10 +375,8 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
             KeptRun<EPL> run[ROWS];
             kept_runs<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
 #pragma unroll
-            for (int r = 0; r < ROWS; ++r) {
-                keptm[r] = run[r].mask;
-                if (keptm[r]) divert_kept<InT, EPL>(*cm, run[r], x[r]);
-            }
+            for (int r = 0; r < ROWS; ++r)
+                if (run[r].mask) divert_kept<InT, EPL>(*cm, run[r], x[r]);
         }
     }
 
@@ -467,12 +466,6 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
         for (int j = 0; j < EPL; j += 2) {
             e[j] = element_word<B, STOCH, 0>(q[j], nr[r][j >> 1]);
             e[j + 1] = element_word<B, STOCH, 1>(q[j + 1], nr[r][j >> 1]);
-        }
-        if constexpr (MIXED) {
-            if (keptm[r]) {
-#pragma unroll
-                for (int j = 0; j < EPL; ++j) e[j] = (keptm[r] & (1u << j)) ? 0u : e[j];
-            }
         }
         // codes go to the staging area in element order
         uint8_t* sc = stage_codes + r * ROW_CODE_BYTES + lane * (EPL * B / 8);
