@@ -341,6 +341,92 @@ def bench_sparse(args, api, W, dev) -> int:
     return 0
 
 
+def bench_hooks(args, api, W, dev) -> int:
+    """A training step with the compressor hooked into autograd (saved_tensors_hooks): the
+    feed-forward half of a 12-layer transformer encoder at configuration 4's shapes (batch 16,
+    sequence 512, hidden 768 / 3072, bf16; LayerNorm outputs and GELU inputs are what autograd
+    saves), G64 / 2-bit / stochastic.  Reported: step time and peak memory with and without
+    the hooks, and per-tensor SM / PC / RC / FLT with the resulting MPS (Section 4.3).  The
+    layers themselves are torch's; only the pack / unpack calls are this library's."""
+    import torch
+    from paper_2510_11400_amd import hooks
+
+    torch.manual_seed(0)
+    layers, hidden, inner, tokens = 12, 768, 3072, 16 * 512
+    G, B, rounding = 64, 2, "stochastic"
+
+    class Block(torch.nn.Module):
+        def __init__(self):
+            super().__init__()
+            self.norm = torch.nn.LayerNorm(hidden)
+            self.up = torch.nn.Linear(hidden, inner)
+            self.down = torch.nn.Linear(inner, hidden)
+
+        def forward(self, x):
+            return x + self.down(torch.nn.functional.gelu(self.up(self.norm(x))))
+
+    model = torch.nn.Sequential(*[Block() for _ in range(layers)]).to(dev, torch.bfloat16)
+    x = torch.randn(tokens, hidden, device=dev, dtype=torch.bfloat16)
+    params = list(model.parameters())
+
+    def step(ctx):
+        for p in params:
+            p.grad = None
+        with ctx:
+            y = model(x)
+            loss = y.float().square().mean()
+        loss.backward()
+
+    import contextlib
+
+    def measure(make_ctx):
+        for _ in range(args.warmup):
+            step(make_ctx())
+        torch.cuda.synchronize()
+        torch.cuda.reset_peak_memory_stats()
+        base = torch.cuda.memory_allocated()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(make_ctx())
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps, torch.cuda.max_memory_allocated() - base
+
+    plain_s, plain_peak = measure(contextlib.nullcontext)
+    make = lambda record=False: hooks.SavedActivations(G, B, rounding, seed=1, record=record, exclude=params)
+    hooked_s, hooked_peak = measure(make)
+    ctx = make(record=True)                                   # one more step, with events around every call
+    step(ctx)
+    torch.cuda.synchronize()
+    recs = [r for r in ctx.records if r.purge_cost is not None and r.regain_cost is not None]
+    sm = sum(r.saved_bytes for r in recs)
+    pc = sum(r.purge_cost for r in recs)
+    rc = sum(r.regain_cost for r in recs)
+    flt = [r._pack[1].elapsed_time(r._unpack[0]) * 1e-3 for r in recs]      # freed lifetime: stored -> needed again
+    mps_each = [hooks.mps(r.saved_bytes, f, r.purge_cost, r.regain_cost) for r, f in zip(recs, flt)]
+    in_bytes = sum(r.input_bytes for r in recs)
+    result = {
+        "metric": "training step with activations stored compressed (saved_tensors_hooks), on 1 MI355X",
+        "value": round(in_bytes / (pc + rc) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(hooked_s * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "hooks_transformer_ffn_l12_b16_s512_bf16_g64_b2_stochastic", "layers": layers,
+                   "tensors_compressed": len(recs), "input_bytes": in_bytes,
+                   "entry_point": "fh_compress / fh_decompress from autograd's pack / unpack hooks"},
+        "step_ms_without_hooks": round(plain_s * 1e3, 4),
+        "peak_activation_bytes_without_hooks": int(plain_peak), "peak_activation_bytes_with_hooks": int(hooked_peak),
+        "saved_bytes": int(sm), "purge_cost_ms": round(pc * 1e3, 4), "regain_cost_ms": round(rc * 1e3, 4),
+        "freed_lifetime_ms_mean": round(1e3 * sum(flt) / max(len(flt), 1), 4),
+        "mps_compress_byte_seconds_per_second": {"min": min(mps_each), "median": sorted(mps_each)[len(mps_each) // 2],
+                                                 "max": max(mps_each)} if mps_each else None,
+        "roofline": {"bound": "hbm", "kernel": "per-tensor compress + decompress calls (event-timed, launch-inclusive)",
+                     "achieved": round((in_bytes * 2 + 2 * (in_bytes - sm)) / (pc + rc) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round((in_bytes * 2 + 2 * (in_bytes - sm)) / (pc + rc) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None},
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -351,11 +437,12 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB device copies before the timed region, so that a "
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE against a known size")
-    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed", "sparse"), default="roundtrip",
+    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed", "sparse", "hooks"), default="roundtrip",
                     help="roundtrip (default): compress + decompress of the tensor set; classify: the "
                          "channel classification step (moments + outlier counts), measured on its own; "
                          "mixed: the round trip with salient channels kept raw beside the quantised stream; "
-                         "sparse: block-wise sparse storage of the kept channels' maps")
+                         "sparse: block-wise sparse storage of the kept channels' maps; hooks: a training "
+                         "step with the compressor in autograd's saved-tensor hooks")
     ap.add_argument("--eps", type=float, default=0.0,
                     help="--op sparse: error bound of the predictive form of dense blocks (0 = verbatim)")
     ap.add_argument("--maps-scale", type=int, default=1, metavar="K",
@@ -390,6 +477,8 @@ def main() -> int:
         return bench_mixed(args, api, W, dev)
     if args.op == "sparse":
         return bench_sparse(args, api, W, dev)
+    if args.op == "hooks":
+        return bench_hooks(args, api, W, dev)
 
     w = W.full_config(args.config)
     t0 = time.time()
