@@ -201,8 +201,9 @@ fh_status fh_decompress_mixed(const void *packed, const void *meta, const void *
                               fh_dtype out_dtype, void *out, size_t out_cap, void *stream);
 
 /* The same two calls for several tensors (one launch per run of up to fh_mixed_batch_capacity()
- * items that share dtype and group size; items with no element are skipped; everything is
- * checked before the first launch; results identical to the single calls).  Compression uses
+ * items that share dtype and group size; items with no element are skipped, items with
+ * raw_channels == 0 are served by the plain quantiser's kernels; everything is checked before
+ * the first launch; results identical to the single calls).  Compression uses
  * x, x_dtype, the shape, slots, raw_channels, packed, meta, raw (whose dtype is x_dtype) and
  * params; decompression uses packed, meta, raw, raw_dtype, the shape, slots, raw_channels, out,
  * out_dtype and params. */

@@ -166,6 +166,25 @@ fh_status fh_compress_mixed_batch(const fh_mixed_item* items, int32_t count, voi
         const fh_status st = check_compress(items[i], &numel);
         if (st != FH_OK) return st;
     }
+    // a tensor that keeps nothing is the plain quantiser's: its kernels do not look at channels at all
+    fh_item plain[kBatch];
+    int32_t plain_count = 0;
+    for (int32_t k = 0; k <= count; ++k) {
+        if (k < count && items[k].raw_channels == 0) {
+            const fh_mixed_item& it = items[k];
+            fh_item& p = plain[plain_count++];
+            p = fh_item{};
+            p.x = it.x; p.x_dtype = it.x_dtype; p.out_dtype = FH_F32;
+            p.numel = it.outer * it.channels * it.inner;
+            p.packed = it.packed; p.packed_cap = it.packed_cap; p.meta = it.meta; p.meta_cap = it.meta_cap;
+            p.params = it.params;
+        }
+        if (plain_count == kBatch || (k == count && plain_count > 0)) {
+            const fh_status st = fh_compress_batch(plain, plain_count, stream);
+            if (st != FH_OK) return st;
+            plain_count = 0;
+        }
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t i = 0;
     while (i < count) {                                       // runs of one dtype and group size
@@ -177,7 +196,7 @@ fh_status fh_compress_mixed_batch(const fh_mixed_item* items, int32_t count, voi
             const fh_mixed_item& it = items[i];
             int64_t numel;
             check_compress(it, &numel);
-            if (numel == 0) { ++i; continue; }
+            if (numel == 0 || it.raw_channels == 0) { ++i; continue; }
             MixedCompressJob job;
             job.it.x = it.x;
             job.it.packed = static_cast<uint8_t*>(it.packed);
@@ -209,6 +228,25 @@ fh_status fh_decompress_mixed_batch(const fh_mixed_item* items, int32_t count, v
         const fh_status st = check_decompress(items[i], &numel);
         if (st != FH_OK) return st;
     }
+    fh_item plain[kBatch];                                    // tensors that kept nothing: the plain kernels
+    int32_t plain_count = 0;
+    for (int32_t k = 0; k <= count; ++k) {
+        if (k < count && items[k].raw_channels == 0) {
+            const fh_mixed_item& it = items[k];
+            fh_item& p = plain[plain_count++];
+            p = fh_item{};
+            p.x_dtype = FH_F32; p.out_dtype = it.out_dtype;
+            p.numel = it.outer * it.channels * it.inner;
+            p.packed = it.packed; p.packed_cap = it.packed_cap; p.meta = it.meta; p.meta_cap = it.meta_cap;
+            p.out = it.out; p.out_cap = it.out_cap;
+            p.params = it.params;
+        }
+        if (plain_count == kBatch || (k == count && plain_count > 0)) {
+            const fh_status st = fh_decompress_batch(plain, plain_count, stream);
+            if (st != FH_OK) return st;
+            plain_count = 0;
+        }
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t i = 0;
     while (i < count) {
@@ -220,7 +258,7 @@ fh_status fh_decompress_mixed_batch(const fh_mixed_item* items, int32_t count, v
             const fh_mixed_item& it = items[i];
             int64_t numel;
             check_decompress(it, &numel);
-            if (numel == 0) { ++i; continue; }
+            if (numel == 0 || it.raw_channels == 0) { ++i; continue; }
             MixedDecompressJob job;
             job.it.packed = static_cast<const uint8_t*>(it.packed);
             job.it.meta = static_cast<const float*>(it.meta);

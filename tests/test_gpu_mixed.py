@@ -231,6 +231,8 @@ def test_batched_calls_match_the_oracle_for_every_tensor(api):
         mask = _mask(C, 0.2, i)
         mask[0] = 1
         cap = max(1, int(mask.sum()) - (i % 2))              # every other tensor: one salient channel too many
+        if i in (3, 9):
+            cap = 0                                           # nothing kept: served by the plain kernels
         slots, used = oracle.channel_slots(mask, cap)
         host.append((x, slots, cap))
         tdt = _tdtype(dtype)
