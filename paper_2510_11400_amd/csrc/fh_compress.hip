@@ -311,9 +311,9 @@ __device__ __forceinline__ void divert_kept(const ChannelMap& cm, const KeptRun<
 // The same for one channel per element (fh_channels.hpp).  A kept element becomes a quiet NaN by
 // setting its exponent and top mantissa bit; further down the clamp of the quantiser
 // (v_med3_f32, which returns the minimum of the other two operands for a NaN) turns it into
-// code 0, so nothing else has to know about it.  (Gathering a row's kept elements in LDS to
-// store them with one instruction per 64 was measured: the gather costs more than the sparse
-// stores it replaces.)
+// code 0, so nothing else has to know about it.  (Gathering a row's kept elements in LDS -- in
+// the wave's staging area, free at this point -- to store them with one instruction per 64
+// was measured twice: the gather costs more than the sparse stores it replaces.)
 template <typename InT, int N>
 __device__ __forceinline__ void divert_kept_vector(uint8_t* base, const KeptVector<N>& kv, float (&x)[N])
 {
