@@ -392,8 +392,10 @@ def bench_hooks(args, api, W, dev) -> int:
         return (time.perf_counter() - t0) / args.steps, torch.cuda.max_memory_allocated() - base
 
     plain_s, plain_peak = measure(contextlib.nullcontext)
-    make = lambda record=False: hooks.SavedActivations(G, B, rounding, seed=1, record=record, exclude=params)
+    extra = {"channel_dim": -1} if args.channel_wise else {}
+    make = lambda record=False: hooks.SavedActivations(G, B, rounding, seed=1, record=record, exclude=params, **extra)
     hooked_s, hooked_peak = measure(make)
+    step(make(record=True))                                   # events are created lazily: once untimed
     ctx = make(record=True)                                   # one more step, with events around every call
     step(ctx)
     torch.cuda.synchronize()
@@ -409,9 +411,11 @@ def bench_hooks(args, api, W, dev) -> int:
         "value": round(in_bytes / (pc + rc) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(hooked_s * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "hooks_transformer_ffn_l12_b16_s512_bf16_g64_b2_stochastic", "layers": layers,
+        "config": {"workload": "hooks_transformer_ffn_l12_b16_s512_bf16_g64_b2_stochastic" + ("_channel_wise" if args.channel_wise else ""),
+                   "layers": layers,
                    "tensors_compressed": len(recs), "input_bytes": in_bytes,
-                   "entry_point": "fh_compress / fh_decompress from autograd's pack / unpack hooks"},
+                   "entry_point": ("fh_classify_channels + fh_channel_slots + fh_compress_mixed / fh_decompress_mixed"
+                                   if args.channel_wise else "fh_compress / fh_decompress") + " from autograd's pack / unpack hooks"},
         "step_ms_without_hooks": round(plain_s * 1e3, 4),
         "peak_activation_bytes_without_hooks": int(plain_peak), "peak_activation_bytes_with_hooks": int(hooked_peak),
         "saved_bytes": int(sm), "purge_cost_ms": round(pc * 1e3, 4), "regain_cost_ms": round(rc * 1e3, 4),
@@ -447,6 +451,8 @@ def main() -> int:
                     help="--op sparse: error bound of the predictive form of dense blocks (0 = verbatim)")
     ap.add_argument("--maps-scale", type=int, default=1, metavar="K",
                     help="--op sparse: K times as many maps per set (the kernels at a bandwidth-bound size)")
+    ap.add_argument("--channel-wise", action="store_true",
+                    help="--op hooks: classify every saved tensor's hidden channels and keep the salient ones raw")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()

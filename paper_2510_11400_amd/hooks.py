@@ -69,10 +69,11 @@ class TensorRecord:
 
 
 class _Packed:
-    __slots__ = ("packed", "meta", "shape", "dtype", "numel", "record")
+    __slots__ = ("packed", "meta", "shape", "dtype", "numel", "record", "mixed")
 
-    def __init__(self, packed, meta, shape, dtype, numel, record):
+    def __init__(self, packed, meta, shape, dtype, numel, record, mixed=None):
         self.packed, self.meta, self.shape, self.dtype, self.numel, self.record = packed, meta, shape, dtype, numel, record
+        self.mixed = mixed                 # (outer, channels, inner, slots, raw_channels, raw) on the channel-wise path
 
 
 class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
@@ -84,12 +85,23 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
     address).  Everything else is saved as it is.  Non-contiguous tensors are made contiguous first (a copy by torch).
     Stochastic rounding draws its bits from (seed, tensor_id); tensor ids count up from
     `first_tensor_id` in the order tensors are saved, so a step is reproducible.
+
+    With `channel_dim` set, every tensor takes the channel-wise mix of Section 4.4.1: its
+    channels (dimension `channel_dim`, at most 16384 of them) are classified by the 3-sigma rule
+    -- salient where more than `outlier_share` of a channel's elements lie beyond `k_sigma`
+    standard deviations of the tensor -- and up to `raw_share` of the channels, the salient
+    ones, are kept verbatim beside the quantised stream, so that their outliers do not stretch
+    the range of the groups they sit in.  All of it is enqueued on the stream; nothing waits
+    for the classification's result.
     """
 
     def __init__(self, group_size: int = 256, bits: int = 4, rounding="nearest", seed: int = 0,
-                 min_numel: int = 4096, first_tensor_id: int = 0, record: bool = False, exclude=()):
+                 min_numel: int = 4096, first_tensor_id: int = 0, record: bool = False, exclude=(),
+                 channel_dim: Optional[int] = None, k_sigma: float = 3.0, outlier_share: float = 0.01,
+                 raw_share: float = 1.0 / 16.0):
         self.group_size, self.bits, self.rounding, self.seed = group_size, bits, rounding, seed
         self.min_numel = min_numel
+        self.channel_dim, self.k_sigma, self.outlier_share, self.raw_share = channel_dim, k_sigma, outlier_share, raw_share
         self.next_tensor_id = first_tensor_id
         self.record = record
         self.records: List[TensorRecord] = []
@@ -111,14 +123,41 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
         if self.record:
             ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
             ev[0].record(stream)
-        packed, meta = api.fh_compress(x.view(-1), self.group_size, self.bits, self.rounding, self.seed, tid,
-                                       stream=stream)
+        mixed, extra = self._split(x), 0
+        if mixed is None:
+            packed, meta = api.fh_compress(x.view(-1), self.group_size, self.bits, self.rounding, self.seed, tid,
+                                           stream=stream)
+        else:
+            outer, channels, inner, raw_channels = mixed
+            min_outliers = max(1, int(outer * inner * self.outlier_share))
+            _, _, mask = api.fh_classify_channels(x.view(-1), outer, channels, inner, self.k_sigma, min_outliers,
+                                                  stream=stream)
+            slots = api.fh_channel_slots(mask, raw_channels, stream=stream)
+            packed, meta, raw = api.fh_compress_mixed(x.view(-1), outer, channels, inner, slots, raw_channels,
+                                                      self.group_size, self.bits, self.rounding, self.seed, tid,
+                                                      stream=stream)
+            mixed = (outer, channels, inner, slots, raw_channels, raw)
+            extra = raw.numel() * raw.element_size() + slots.numel() * slots.element_size()
         if self.record:
             ev[1].record(stream)
             rec = TensorRecord(tid, x.numel(), x.dtype, x.numel() * x.element_size(),
-                               packed.numel() + meta.numel() * meta.element_size(), _pack=ev)
+                               packed.numel() + meta.numel() * meta.element_size() + extra, _pack=ev)
             self.records.append(rec)
-        return _Packed(packed, meta, t.shape, t.dtype, x.numel(), rec)
+        return _Packed(packed, meta, t.shape, t.dtype, x.numel(), rec, mixed)
+
+    def _split(self, x: torch.Tensor):
+        """(outer, channels, inner, raw_channels) of the channel-wise path, or None for the plain one."""
+        if self.channel_dim is None or x.dim() == 0 or x.numel() > 2 ** 31:
+            return None
+        d = self.channel_dim % x.dim()
+        channels = x.shape[d]
+        if not 1 <= channels <= 16384:
+            return None
+        outer = 1
+        for n in x.shape[:d]:
+            outer *= n
+        inner = x.numel() // (outer * channels)
+        return outer, channels, inner, max(1, min(channels, int(channels * self.raw_share + 0.5)))
 
     def _unpack(self, h):
         if not isinstance(h, _Packed):
@@ -127,8 +166,13 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
         if h.record is not None:
             ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
             ev[0].record(stream)
-        out = api.fh_decompress(h.packed, h.meta, h.numel, self.group_size, self.bits, out_dtype=h.dtype,
-                                stream=stream)
+        if h.mixed is None:
+            out = api.fh_decompress(h.packed, h.meta, h.numel, self.group_size, self.bits, out_dtype=h.dtype,
+                                    stream=stream)
+        else:
+            outer, channels, inner, slots, raw_channels, raw = h.mixed
+            out = api.fh_decompress_mixed(h.packed, h.meta, raw, outer, channels, inner, slots, raw_channels,
+                                          self.group_size, self.bits, out_dtype=h.dtype, stream=stream)
         if h.record is not None:
             ev[1].record(stream)
             h.record._unpack = ev

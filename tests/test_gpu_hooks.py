@@ -145,3 +145,77 @@ def test_a_small_network_trains_through_the_hooks(hooks):
         rel = (p.grad - g).norm() / g.norm()
         cos = torch.nn.functional.cosine_similarity(p.grad.flatten(), g.flatten(), dim=0)
         assert rel < 0.2 and cos > 0.98, (float(rel), float(cos))
+
+
+# ---- the channel-wise mix inside the hooks (Section 4.4.1) ------------------------------------------
+
+def _oracle_channel_wise(x_host, outer, C, inner, G, B, rounding, seed, tid, dtype, k_sigma, share, raw_share):
+    bits = x_host.view(torch.int16).numpy().view(np.uint16).reshape(-1) if dtype == "bf16" else x_host.numpy().reshape(-1)
+    min_outliers = max(1, int(outer * inner * share))
+    _, _, mask = oracle.classify_channels(bits, outer, C, inner, k_sigma, min_outliers, dtype=dtype)
+    cap = max(1, min(C, int(C * raw_share + 0.5)))
+    slots, used = oracle.channel_slots(mask, cap)
+    p, m, raw = oracle.compress_mixed(bits, outer, C, inner, slots, cap, G, B, rounding, seed, tid, dtype=dtype)
+    y = oracle.decompress_mixed(p, m, raw, outer, C, inner, slots, cap, G, B, raw_dtype=dtype, out_dtype=dtype)
+    if dtype == "bf16":
+        return torch.from_numpy(y.view(np.int16)).view(torch.bfloat16).reshape(x_host.shape), used
+    return torch.from_numpy(y).reshape(x_host.shape), used
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,channel_dim", [((24, 48, 14, 14), 1), ((6, 200, 768), -1), ((40, 96), 1)])
+def test_channel_wise_hooks_give_backward_the_oracles_chain(hooks, dtype, shape, channel_dim):
+    """classify -> slots -> mixed compress in the pack hook, mixed restore in the unpack hook:
+    bit for bit the oracle's chain, and the planted channels come back exactly."""
+    from paper_2510_11400_amd import workloads as W
+    print(f"[hooks] channel-wise {dtype} {shape} dim {channel_dim}", flush=True)
+    d = channel_dim % len(shape)
+    outer = int(np.prod(shape[:d])) if d else 1
+    C = shape[d]
+    inner = int(np.prod(shape[d + 1:])) if d + 1 < len(shape) else 1
+    x_np, planted = W.outlier_channel_tensor(outer, C, inner, seed=C, dist="gauss", salient_fraction=0.05, dtype=dtype)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    x_host = (torch.from_numpy(x_np.view(np.int16)).view(torch.bfloat16) if dtype == "bf16" else torch.from_numpy(x_np)).reshape(shape)
+    x = x_host.cuda().requires_grad_(True)
+    G, B, rounding, seed = 64, 4, "stochastic", 5
+    _Probe.seen.clear()
+    ctx = hooks.SavedActivations(G, B, rounding, seed=seed, min_numel=1, first_tensor_id=9, channel_dim=channel_dim,
+                                 record=True)
+    with ctx:
+        y = _Probe.apply(x)
+    y.sum().backward()
+    torch.cuda.synchronize()
+    want, used = _oracle_channel_wise(x_host, outer, C, inner, G, B, rounding, seed, 9, dtype, 3.0, 0.01, 1.0 / 16.0)
+    got = _Probe.seen[0].cpu()
+    assert got.shape == x_host.shape and got.dtype == tdt
+    same = got.view(torch.int16 if dtype == "bf16" else torch.int32) == want.view(torch.int16 if dtype == "bf16" else torch.int32)
+    assert bool(same.all())
+    moved = [slice(None)] * len(shape)
+    kept_exact = 0
+    for c in planted:                                          # the planted channels were found, got a row, and are exact
+        moved[d] = int(c)
+        kept_exact += bool((got[tuple(moved)] == x_host[tuple(moved)]).all())
+    assert used == len(planted) and kept_exact == len(planted)
+    assert ctx.records[0].stored_bytes < ctx.records[0].input_bytes
+
+
+def test_channel_wise_hooks_shrink_the_error_of_the_normal_channels(hooks):
+    """With 81x outliers in a few channels the plain quantiser's error follows the outliers'
+    range; with those channels kept aside it follows the normal channels' own range."""
+    from paper_2510_11400_amd import workloads as W
+    outer, C, inner = 32, 64, 400
+    x_np, planted = W.outlier_channel_tensor(outer, C, inner, seed=3, dist="gauss", salient_fraction=0.05, magnitude=81.0)
+    x_host = torch.from_numpy(x_np).reshape(outer, C, inner)
+    normal = np.setdiff1d(np.arange(C), planted)
+    errs = {}
+    for name, kw in (("plain", {}), ("channel-wise", {"channel_dim": 1})):
+        _Probe.seen.clear()
+        x = x_host.cuda().requires_grad_(True)
+        with hooks.SavedActivations(256, 4, "nearest", min_numel=1, **kw):
+            y = _Probe.apply(x)
+        y.sum().backward()
+        torch.cuda.synchronize()
+        got = _Probe.seen[0].cpu()
+        errs[name] = float((got[:, normal] - x_host[:, normal]).abs().max())
+    print(f"[hooks] max error on normal channels: {errs}", flush=True)
+    assert errs["channel-wise"] < errs["plain"] / 8
