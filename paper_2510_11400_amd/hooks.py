@@ -3,8 +3,9 @@
 `SavedActivations` is the literal "compress in the forward pass, decompress during
 backpropagation" of FedHybrid's local training engine (Section 3, Activation compression):
 a `torch.autograd.graph.saved_tensors_hooks` pair whose pack side calls `fh_compress` and
-whose unpack side calls `fh_decompress`.  Only argument marshalling happens here; every
-byte is produced by the library's kernels.
+whose unpack side calls `fh_decompress` -- or, with a channel dimension given, the channel-wise
+mix of Section 4.4.1 (classification, slot numbering, mixed compress / restore).  Only argument
+marshalling happens here; every byte is produced by the library's kernels.
 
 `mps` is the paper's reward metric (Section 4.3): RW(d) = SM(d) * FLT(d) and
 MPS(d) = RW(d) / (PC(d) + RC(d)), where SM is the memory a technique saves on tensor d, FLT
