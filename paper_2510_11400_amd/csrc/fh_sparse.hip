@@ -7,11 +7,12 @@
 // and what each contributes to the two output streams is known from one byte of information,
 // so the streams are laid out by a prefix sum over tiles -- stream compaction:
 //   pass 1  one thread per tile: count non-zeros, decide sparse / dense, write the tile's info
-//           byte; each workgroup adds up what its 256 tiles will write;
-//   pass 2  one thread per tile: the workgroup's base is the sum of the sums before it (each
+//           byte; the tiles of a workgroup (256, or 128 for the largest window) form a group,
+//           whose sums are added up;
+//   pass 2  one thread per tile: the group's base is the sum of the sums before it (each
 //           workgroup adds them up itself while there are few; a scan kernel in between does
-//           it once there are many), offsets inside the workgroup come from a wave-shuffle
-//           scan, then the tile's values and CSR structure go to their final place.
+//           it once there are many), offsets inside the group come from a scan over the
+//           workgroup, then the tile's values and CSR structure go to their final place.
 // What a workgroup's tiles write is one contiguous slice of each stream, so the threads put
 // their pieces together in LDS and the workgroup moves the slice with aligned 16-byte
 // vectors (thread-per-tile stores would touch every cache line of the slice once per element).
