@@ -180,11 +180,12 @@ __device__ __forceinline__ void kept_runs(const ChannelMap& cm, const ElemPos& w
 // compare: an entry s names a row iff 0 <= s < raw_channels, i.e. iff bit 15 of ~s & (s - raw_channels)
 // is set (s - raw_channels cannot wrap: both are below 2^15 in magnitude).
 typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
 
 template <int N> struct KeptVector {
     uint32_t keep[N / 2];      // half-word j: 0xffff iff element j belongs to a kept channel
-    uint32_t slot[N / 2];      // half-word j: that channel's raw-store row, 0 for a normal channel
-    uint32_t row;              // raw-store index of (the run's sample, row 0), counted from the wave's first sample
+    uint32_t slot[N / 2];      // half-word j: that channel's raw-store row times the element size, 0 for a normal channel
+    uint32_t row;              // byte offset of (the run's sample, row 0) from the row 0 of the wave's first sample
 };
 
 template <int N>
@@ -193,15 +194,16 @@ __device__ __forceinline__ bool one_channel_per_element(const ChannelMap& cm)
     return cm.inner.d == 1u && (cm.channels.d & (N - 1)) == 0u && cm.raw_channels - 1u < 16384u;
 }
 
+// elem_shift: log2 of the raw store's element size (1 or 2; rows < 2^14, so the scaled rows fit 16 bits)
 template <int ROWS, int N>
 __device__ __forceinline__ void kept_vectors(const ChannelMap& cm, const ElemPos& wave_pos, uint32_t lane_off,
-                                             uint32_t row_stride, KeptVector<N> (&kv)[ROWS])
+                                             uint32_t row_stride, uint32_t elem_shift, KeptVector<N> (&kv)[ROWS])
 {
     uint32_t w[ROWS][N / 2];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {                          // all table loads first
         const ElemPos p = advance(cm, wave_pos, r * row_stride + lane_off);
-        kv[r].row = (p.o - wave_pos.o) * cm.raw_channels;
+        kv[r].row = ((p.o - wave_pos.o) * cm.raw_channels) << elem_shift;
         if constexpr (N == 8) {
             const u32x4 s = *reinterpret_cast<const u32x4*>(cm.slots + p.c);
             w[r][0] = s.x; w[r][1] = s.y; w[r][2] = s.z; w[r][3] = s.w;
@@ -219,17 +221,17 @@ __device__ __forceinline__ void kept_vectors(const ChannelMap& cm, const ElemPos
             const i16x2 s = __builtin_bit_cast(i16x2, w[r][k]);
             const i16x2 keep = (~s & (s - limit)) >> 15;      // arithmetic shift: 0xffff or 0 per half
             kv[r].keep[k] = __builtin_bit_cast(uint32_t, keep);
-            kv[r].slot[k] = w[r][k] & kv[r].keep[k];
+            const u16x2 scaled = __builtin_bit_cast(u16x2, w[r][k] & kv[r].keep[k]) << (uint16_t)elem_shift;
+            kv[r].slot[k] = __builtin_bit_cast(uint32_t, scaled);
         }
 }
 
 // byte offset, from the raw-store row of the wave's first sample, of the entry element j of the run reads or writes
 // (a normal element gets row 0 of its sample, which exists: raw_channels >= 1)
-template <int N, int ELEM_BYTES>
+template <int N>
 __device__ __forceinline__ uint32_t raw_offset(const KeptVector<N>& kv, int j)
 {
-    const uint32_t slot = (j & 1) ? kv.slot[j >> 1] >> 16 : kv.slot[j >> 1] & 0xffffu;
-    return slot * ELEM_BYTES + kv.row * ELEM_BYTES;
+    return ((j & 1) ? kv.slot[j >> 1] >> 16 : kv.slot[j >> 1] & 0xffffu) + kv.row;
 }
 
 // does any lane of the wave hold a kept element in this run? (a wave-uniform answer keeps the branch scalar)

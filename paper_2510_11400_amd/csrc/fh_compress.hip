@@ -322,7 +322,7 @@ __device__ __forceinline__ void divert_kept_vector(uint8_t* base, const KeptVect
         const uint32_t keep = kv.keep[j >> 1];
         const uint32_t bits = __builtin_bit_cast(uint32_t, x[j]);
         if (keep & ((j & 1) ? 0xffff0000u : 0x0000ffffu)) {
-            uint8_t* p = base + raw_offset<N, (int)sizeof(InT)>(kv, j);
+            uint8_t* p = base + raw_offset<N>(kv, j);
             if constexpr (sizeof(InT) == 4) *reinterpret_cast<uint32_t*>(p) = bits;
             else *reinterpret_cast<uint16_t*>(p) = (uint16_t)(bits >> 16);        // the original bits
         }
@@ -366,7 +366,7 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
     if constexpr (MIXED) {
         if (one_channel_per_element<EPL>(*cm)) {              // wave-uniform
             KeptVector<EPL> kv[ROWS];
-            kept_vectors<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, kv);
+            kept_vectors<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, sizeof(InT) == 4 ? 2u : 1u, kv);
             uint8_t* base = static_cast<uint8_t*>(cm->raw) + (uint64_t)wave_pos.o * cm->raw_channels * sizeof(InT);
 #pragma unroll
             for (int r = 0; r < ROWS; ++r)

@@ -116,7 +116,7 @@ __device__ __forceinline__ void merge_kept(const uint8_t* base, const KeptVector
     uint32_t bits[N];
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-        const RawT e = *reinterpret_cast<const RawT*>(base + raw_offset<N, (int)sizeof(RawT)>(kv, j));
+        const RawT e = *reinterpret_cast<const RawT*>(base + raw_offset<N>(kv, j));
         bits[j] = sizeof(RawT) == 4 ? (uint32_t)e : (uint32_t)e << 16;
     }
 #pragma unroll
@@ -131,7 +131,7 @@ __device__ __forceinline__ u32x4 merge_kept_bf16(const uint8_t* base, const Kept
 {
     uint32_t e[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) e[j] = *reinterpret_cast<const uint16_t*>(base + raw_offset<8, 2>(kv, j));
+    for (int j = 0; j < 8; ++j) e[j] = *reinterpret_cast<const uint16_t*>(base + raw_offset<8>(kv, j));
     uint32_t out[4] = {o.x, o.y, o.z, o.w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) out[k] = ((e[2 * k] | (e[2 * k + 1] << 16)) & kv.keep[k]) | (out[k] & ~kv.keep[k]);
@@ -166,7 +166,7 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
         if constexpr (MIXED) {
             if (one_channel_per_element<EPL>(*cm)) {          // wave-uniform
                 KeptVector<EPL> kv[kRowsPerWave];
-                kept_vectors<kRowsPerWave, EPL>(*cm, wave_pos, lane * EPL, ROW, kv);
+                kept_vectors<kRowsPerWave, EPL>(*cm, wave_pos, lane * EPL, ROW, raw_dtype == 0 ? 2u : 1u, kv);
                 const uint8_t* base = static_cast<const uint8_t*>(cm->raw) +
                                       (uint64_t)wave_pos.o * cm->raw_channels * (raw_dtype == 0 ? 4u : 2u);
 #pragma unroll
