@@ -451,6 +451,8 @@ def main() -> int:
                     help="--op sparse: error bound of the predictive form of dense blocks (0 = verbatim)")
     ap.add_argument("--maps-scale", type=int, default=1, metavar="K",
                     help="--op sparse: K times as many maps per set (the kernels at a bandwidth-bound size)")
+    ap.add_argument("--same-dtype-out", action="store_true",
+                    help="restore bf16 tensors to bf16 instead of fp32 (configuration 4's second figure)")
     ap.add_argument("--channel-wise", action="store_true",
                     help="--op hooks: classify every saved tensor's hidden channels and keep the salient ones raw")
     ap.add_argument("--per-tensor", action="store_true",
@@ -496,7 +498,8 @@ def main() -> int:
         if spec.dtype == "bf16":
             xd = xd.view(torch.bfloat16)
         pk, mt = api.alloc_compressed(x.size, spec.group_size, spec.bits, dev)
-        out = torch.empty(x.size, dtype=torch.float32, device=dev)
+        out_dtype = torch.bfloat16 if (args.same_dtype_out and spec.dtype == "bf16") else torch.float32
+        out = torch.empty(x.size, dtype=out_dtype, device=dev)
         entries.append(api.BatchEntry(spec.group_size, spec.bits, spec.rounding, spec.seed, spec.tensor_id,
                                       x=xd, packed=pk, meta=mt, out=out))
     batch = api.Batch(entries)
@@ -505,7 +508,7 @@ def main() -> int:
           f"(generated + uploaded in {time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
 
     cbytes = sum(algorithmic_bytes(s)[0] for s in w.tensors)
-    dbytes = sum(algorithmic_bytes(s)[1] for s in w.tensors)
+    dbytes = sum(algorithmic_bytes(s, 2 if (args.same_dtype_out and s.dtype == "bf16") else 4)[1] for s in w.tensors)
     launches_c = launches_d = 1
     stream = torch.cuda.current_stream()
 
@@ -554,6 +557,7 @@ def main() -> int:
         "config": {"workload": w.name, "tensors": len(w.tensors), "input_bytes": w.nbytes,
                    "entry_point": "fh_roundtrip (per tensor)" if args.per_tensor
                    else "fh_compress_batch + fh_decompress_batch",
+                   "restored_dtype": "bf16" if (args.same_dtype_out and w.tensors[0].dtype == "bf16") else "f32",
                    "group_size": w.tensors[0].group_size,
                    "bits": sorted({t.bits for t in w.tensors}),
                    "rounding": sorted({t.rounding for t in w.tensors})},
@@ -572,7 +576,8 @@ def main() -> int:
         # measured HBM bytes per launch of that kernel, from the committed counter summary of
         # this workload; None when there is none or the kernel sources changed since
         from paper_2510_11400_amd.profile_summary import read_traffic
-        traffic = read_traffic(os.path.join(ROOT, "profiles", f"compress_decompress_{w.name}.txt")).get(dom)
+        traffic = None if args.same_dtype_out else \
+            read_traffic(os.path.join(ROOT, "profiles", f"compress_decompress_{w.name}.txt")).get(dom)
         result["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": round(kern[dom]["GBps"] / HBM_PEAK_GBS, 4),
                               "traffic": traffic}
