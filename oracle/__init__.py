@@ -17,7 +17,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libfho.so")
-_SRCS = [os.path.join(_HERE, n) for n in ("fho.c", "fho_classify.c", "fho_mixed.c", "fho_sparse.c")]
+_SRCS = [os.path.join(_HERE, n) for n in ("fho.c", "fho_classify.c", "fho_mixed.c", "fho_sparse.c", "fho_huffman.c")]
 
 F32, BF16 = 0, 1
 NEAREST, STOCHASTIC = 0, 1
@@ -91,6 +91,16 @@ def lib() -> ctypes.CDLL:
                                         ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_float,
                                         ctypes.c_void_p]
         L.fho_sparse_decode.restype = ctypes.c_int
+        L.fho_huffman_lengths.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        L.fho_huffman_lengths.restype = None
+        L.fho_huffman_codes.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        L.fho_huffman_codes.restype = None
+        L.fho_huffman_stream_bytes.argtypes = [ctypes.c_uint64]
+        L.fho_huffman_stream_bytes.restype = ctypes.c_size_t
+        L.fho_huffman_encode.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
+        L.fho_huffman_encode.restype = ctypes.c_int
+        L.fho_huffman_decode.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_void_p]
+        L.fho_huffman_decode.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -269,4 +279,41 @@ def sparse_decode(info: np.ndarray, values: np.ndarray, indices: np.ndarray, map
                                  float(eps), out.ctypes.data)
     if rc != 0:
         raise ValueError(f"fho_sparse_decode failed ({rc})")
+    return out
+
+
+def huffman_lengths(hist) -> np.ndarray:
+    """Code length of every byte value for the histogram `hist` (256 counts) -> uint8[256]."""
+    h = np.ascontiguousarray(hist, dtype=np.uint64)
+    if h.size != 256:
+        raise ValueError("a histogram has 256 counts")
+    out = np.zeros(256, dtype=np.uint8)
+    lib().fho_huffman_lengths(h.ctypes.data, out.ctypes.data)
+    return out
+
+
+def huffman_codes(lengths) -> np.ndarray:
+    """Canonical codes for the lengths -> uint32[256] (0 where the length is 0)."""
+    l = np.ascontiguousarray(lengths, dtype=np.uint8)
+    out = np.zeros(256, dtype=np.uint32)
+    lib().fho_huffman_codes(l.ctypes.data, out.ctypes.data)
+    return out
+
+
+def huffman_encode(data: np.ndarray):
+    """-> (stream uint8[used], payload bits)."""
+    d = np.ascontiguousarray(data, dtype=np.uint8).reshape(-1)
+    stream = np.zeros(lib().fho_huffman_stream_bytes(d.size), dtype=np.uint8)
+    totals = np.zeros(2, dtype=np.uint64)
+    if lib().fho_huffman_encode(d.ctypes.data, d.size, stream.ctypes.data, totals.ctypes.data) != 0:
+        raise ValueError("fho_huffman_encode rejected its arguments")
+    return stream[: int(totals[0])].copy(), int(totals[1])
+
+
+def huffman_decode(stream: np.ndarray, n: int) -> np.ndarray:
+    s = np.ascontiguousarray(stream, dtype=np.uint8).reshape(-1)
+    out = np.zeros(n, dtype=np.uint8)
+    rc = lib().fho_huffman_decode(s.ctypes.data, s.size, n, out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"fho_huffman_decode failed ({rc})")
     return out

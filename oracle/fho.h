@@ -110,6 +110,24 @@ int fho_sparse_encode(const void *x, int dtype, int64_t maps, int64_t h, int64_t
 int fho_sparse_decode(const uint8_t *info, const void *values, const uint8_t *indices, int dtype,
                       int64_t maps, int64_t h, int64_t w, int n, float eps, void *out);
 
+/* ---- Huffman coding of a byte stream (fho_huffman.c; Section 4.4.1: the quantisation codes of
+ *      the predictive form are encoded with Huffman coding, and restored by Huffman decoding) ----
+ * Code lengths: Huffman's algorithm on the byte histogram (leaves sorted by (count, symbol),
+ * two queues, a leaf preferred to an internal node of equal weight); unused symbols have
+ * length 0, a single used symbol length 1; while the longest code exceeds 24 bits every
+ * non-zero count c becomes (c + 1) >> 1 and the construction is repeated.  Codes: canonical, by
+ * increasing (length, symbol).  Stream: len[256] bytes, then uint32 offsets[chunks + 1]
+ * (chunks of 256 symbols; offsets in 32-bit words into the payload), then the payload: each
+ * chunk's codes written first bit first from bit 31 of its first word downwards, zero-padded
+ * to a whole word. */
+void   fho_huffman_lengths(const uint64_t hist[256], uint8_t len[256]);
+void   fho_huffman_codes(const uint8_t len[256], uint32_t code[256]);
+size_t fho_huffman_stream_bytes(uint64_t n);        /* room the encoder wants for n symbols */
+/* totals = {stream bytes used, payload bits}.  Returns 0, or -1 on a bad argument. */
+int    fho_huffman_encode(const uint8_t *in, uint64_t n, uint8_t *stream, uint64_t totals[2]);
+/* Returns 0, -1 on a bad argument, -2 on a stream that does not decode to n symbols. */
+int    fho_huffman_decode(const uint8_t *stream, uint64_t stream_bytes, uint64_t n, uint8_t *out);
+
 #ifdef __cplusplus
 }
 #endif
