@@ -317,6 +317,38 @@ fh_status fh_sparse_encode_batch(const fh_sparse_encode_item *items, int32_t cou
 fh_status fh_sparse_decode_batch(const fh_sparse_decode_item *items, int32_t count, void *stream);
 int32_t   fh_sparse_batch_capacity(void);
 
+/* ---- Huffman coding of a byte stream -----------------------------------------------------------
+ * Section 4.4.1 ends the predictive form of dense blocks with an entropy stage: the
+ * quantisation codes are encoded with Huffman coding, and restoring starts with Huffman
+ * decoding.  These two calls code any device byte buffer (for instance the index stream
+ * fh_sparse_encode writes with eps > 0, whose code bytes cluster around 128).  The paper names
+ * the coder only; the definition used:
+ *
+ *   - code lengths: Huffman's algorithm on the histogram of the n bytes -- the used byte values
+ *     sorted by (count, value), two queues, a leaf preferred to an internal node of equal
+ *     weight; unused values get length 0, a single used value length 1; while the longest code
+ *     exceeds 24 bits every non-zero count c becomes (c + 1) >> 1 and the construction is
+ *     repeated;
+ *   - codes: canonical, by increasing (length, value);
+ *   - stream: 256 length bytes; then uint32 offsets[chunks + 1], chunks = ceil(n / 256); then
+ *     the payload, 32-bit words: the codes of chunk c (symbols 256 c ...) start at word
+ *     offsets[c], first bit first from bit 31 of a word downwards, zero-padded to a whole word;
+ *     offsets[chunks] = words in all;
+ *   - totals: uint64[2] = {stream bytes used, payload bits};
+ *   - decoding restores the bytes exactly.
+ *
+ * All pointers are device pointers, 16-byte aligned (totals 8); n < 2^32.  The encoder wants
+ * stream_cap >= fh_huffman_stream_bytes(n) (the worst case) and fh_huffman_workspace_bytes(n)
+ * bytes of scratch; what was used is in totals once the stream has reached it.  The decoder is
+ * given the valid prefix of the stream (at least the lengths and the offsets, else
+ * FH_ERR_BUFFER_TOO_SMALL); words past it read as zero.  Nothing is allocated or synchronised. */
+size_t    fh_huffman_stream_bytes(uint64_t n);
+size_t    fh_huffman_workspace_bytes(uint64_t n);
+fh_status fh_huffman_encode(const void *bytes, uint64_t n, void *stream_out, size_t stream_cap, void *totals,
+                            void *workspace, size_t workspace_cap, void *stream);
+fh_status fh_huffman_decode(const void *stream_in, size_t stream_bytes, uint64_t n, void *out, size_t out_cap,
+                            void *stream);
+
 const char *fh_status_string(fh_status s);
 
 #ifdef __cplusplus

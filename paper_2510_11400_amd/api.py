@@ -36,6 +36,7 @@ EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "
            "fh_compress_mixed_batch", "fh_decompress_mixed_batch", "fh_mixed_batch_capacity",
            "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
            "fh_sparse_decode", "fh_sparse_encode_batch", "fh_sparse_decode_batch", "fh_sparse_batch_capacity",
+           "fh_huffman_stream_bytes", "fh_huffman_workspace_bytes", "fh_huffman_encode", "fh_huffman_decode",
            "fh_status_string")
 
 
@@ -161,6 +162,15 @@ _lib.fh_sparse_batch_capacity.argtypes = []
 _lib.fh_sparse_batch_capacity.restype = ctypes.c_int32
 _lib.fh_batch_capacity.argtypes = []
 _lib.fh_batch_capacity.restype = ctypes.c_int32
+for _name in ("fh_huffman_stream_bytes", "fh_huffman_workspace_bytes"):
+    getattr(_lib, _name).argtypes = [ctypes.c_uint64]
+    getattr(_lib, _name).restype = ctypes.c_size_t
+_lib.fh_huffman_encode.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.fh_huffman_encode.restype = ctypes.c_int
+_lib.fh_huffman_decode.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t,
+                                   ctypes.c_void_p]
+_lib.fh_huffman_decode.restype = ctypes.c_int
 _lib.fh_status_string.argtypes = [ctypes.c_int]
 _lib.fh_status_string.restype = ctypes.c_char_p
 
@@ -538,6 +548,52 @@ def fh_sparse_decode(info: torch.Tensor, values: torch.Tensor, indices: torch.Te
         _check(_lib.fh_sparse_decode(_ptr(info), _ptr(values), _nbytes(values), _ptr(indices), _nbytes(indices),
                                      _dtype_code(out), maps, h, w, int(n), float(eps), _ptr(out), _nbytes(out),
                                      workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)))
+    return out
+
+
+def huffman_stream_bytes(n: int) -> int:
+    return int(_lib.fh_huffman_stream_bytes(n))
+
+
+def huffman_workspace_bytes(n: int) -> int:
+    return int(_lib.fh_huffman_workspace_bytes(n))
+
+
+def fh_huffman_encode(data: torch.Tensor, stream_out: Optional[torch.Tensor] = None,
+                      totals: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """Enqueue Huffman coding of the bytes of `data` (a device uint8 tensor); returns
+    (stream_out, totals): a worst-case sized uint8 tensor and int64[2] = {stream bytes in use,
+    payload bits}, valid once the stream has reached them."""
+    _device_tensor(data, "data")
+    if data.dtype != torch.uint8:
+        raise ValueError("data must be uint8")
+    n = data.numel()
+    if stream_out is None:
+        stream_out = torch.empty(huffman_stream_bytes(n), dtype=torch.uint8, device=data.device)
+    if totals is None:
+        totals = torch.zeros(2, dtype=torch.int64, device=data.device)
+    if workspace is None:
+        workspace = torch.empty(huffman_workspace_bytes(n), dtype=torch.uint8, device=data.device)
+    for t, what in ((stream_out, "stream_out"), (totals, "totals"), (workspace, "workspace")):
+        _device_tensor(t, what)
+    if _nbytes(totals) < 16:
+        raise FedHybridError(7)
+    with torch.cuda.device(data.device):
+        _check(_lib.fh_huffman_encode(_ptr(data), n, stream_out.data_ptr(), _nbytes(stream_out), totals.data_ptr(),
+                                      workspace.data_ptr(), _nbytes(workspace), _stream_ptr(stream)))
+    return stream_out, totals
+
+
+def fh_huffman_decode(stream_in: torch.Tensor, n: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Enqueue the inverse; `stream_in` is the valid prefix of an encoded stream (its size bounds
+    what the kernel reads).  Returns the n restored bytes."""
+    _device_tensor(stream_in, "stream_in")
+    if out is None:
+        out = torch.empty(n, dtype=torch.uint8, device=stream_in.device)
+    _device_tensor(out, "out")
+    with torch.cuda.device(stream_in.device):
+        _check(_lib.fh_huffman_decode(_ptr(stream_in), _nbytes(stream_in), n, _ptr(out), _nbytes(out),
+                                      _stream_ptr(stream)))
     return out
 
 

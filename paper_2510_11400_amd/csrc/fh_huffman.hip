@@ -1,0 +1,473 @@
+// Huffman coding of a byte stream on gfx950 (paper Section 4.4.1: the quantisation codes of
+// the predictive form are encoded with Huffman coding; restoring starts with Huffman
+// decoding).  The paper names the coder only; the definition used (tie-breaks, 24-bit limit,
+// canonical codes, layout) is the one in include/fedhybrid.h.
+//
+// A variable-length code is sequential per symbol, so the stream is cut into chunks of 256
+// symbols that start on a 32-bit word; a thread owns a chunk.  Encoding is stream compaction
+// again:
+//   histogram   LDS counters (eight copies, by lane, so that a dominant symbol does not
+//               serialise the wave), added to the global histogram at the end;
+//   code        one workgroup: the used symbols are ranked by (count, symbol) in parallel, one
+//               lane runs the two-queue construction over the ranked leaves (at most 255
+//               merges) and walks the tree for the depths; counts are halved and the
+//               construction repeated while a code would exceed 24 bits; canonical codes;
+//   count       a thread adds up the code lengths of its chunk: its length in words;
+//   scan        the sums of groups of 256 chunks (a workgroup of the count pass) are scanned by
+//               one workgroup;
+//   write       a thread turns its chunk's word count into its offset (group base + a scan
+//               over the workgroup) and writes its words.
+// Decoding needs no pass but one: the offsets are part of the stream.  Every workgroup
+// rebuilds the canonical tables from the 256 lengths (a 10-bit lookup table for the short
+// codes, first-code / count comparisons for the longer ones).
+// Everything here is integer work; results do not depend on launch geometry.
+#include "../../include/fedhybrid.h"
+
+#include "fh_scan.hpp"
+
+namespace fh {
+namespace {
+
+constexpr int kChunk = 256;                        // symbols per chunk (= per thread)
+constexpr int kThreads = 256;                      // chunks per workgroup: a group
+constexpr int kMaxLen = 24;
+constexpr int kChunkWordsMax = kChunk * kMaxLen / 32;
+constexpr int kHistCopies = 8;
+constexpr int kFastBits = 10;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct Layout {                                    // where things are in the stream and in the workspace
+    uint8_t*  len;                                 // [256]
+    uint32_t* offsets;                             // [chunks + 1]
+    uint32_t* payload;
+    uint32_t* hist;                                // workspace: [256]
+    uint32_t* table;                               // workspace: [256], code << 8 | length
+    uint32_t* group_sums;                          // workspace: [groups]
+    uint64_t* totals;                              // {stream bytes used, payload bits}
+    const uint8_t* in;
+    uint64_t  n;
+    uint32_t  chunks, groups;
+};
+
+__global__ __launch_bounds__(256) void huffman_clear_kernel(uint32_t* hist) { hist[threadIdx.x] = 0u; }
+
+// ---- histogram ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void huffman_histogram_kernel(const uint8_t* __restrict__ in, uint64_t n,
+                                                                uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t local[kHistCopies][256];
+    for (int i = threadIdx.x; i < kHistCopies * 256; i += 256) (&local[0][0])[i] = 0u;
+    __syncthreads();
+    uint32_t* mine = local[threadIdx.x & (kHistCopies - 1)];
+    const uint64_t vectors = n >> 4;                          // `in` is 16-byte aligned
+    for (uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x; v < vectors; v += (uint64_t)gridDim.x * 256) {
+        const u32x4 w = reinterpret_cast<const u32x4*>(in)[v];
+        const uint32_t word[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) atomicAdd(&mine[(word[k] >> (8 * b)) & 0xffu], 1u);
+    }
+    if (blockIdx.x == 0) {                                    // the bytes after the last whole vector
+        const uint64_t i = (vectors << 4) + threadIdx.x;
+        if (threadIdx.x < 16 && i < n) atomicAdd(&mine[in[i]], 1u);
+    }
+    __syncthreads();
+    uint32_t total = 0;
+#pragma unroll
+    for (int c = 0; c < kHistCopies; ++c) total += local[c][threadIdx.x];
+    if (total) atomicAdd(&hist[threadIdx.x], total);
+}
+
+// ---- code lengths and canonical codes ---------------------------------------------------------------
+// One workgroup of 256 threads, thread s = symbol s.
+__global__ __launch_bounds__(256) void huffman_code_kernel(const Layout lay)
+{
+    __shared__ uint64_t count[256];                           // this round's counts, by symbol
+    __shared__ uint64_t weight[511];                          // leaves in rank order, then internal nodes as made
+    __shared__ uint16_t parent[511];
+    __shared__ uint16_t depth[511];
+    __shared__ uint8_t  leaf_symbol[256];
+    __shared__ uint8_t  length[256];
+    __shared__ uint32_t code_of[256];
+    __shared__ uint32_t used, deepest;
+    const uint32_t s = threadIdx.x;
+    const uint64_t original = lay.hist[s];
+    uint64_t c = original;
+    for (;;) {                                                // workgroup-uniform; counts halve, so it ends
+        count[s] = c;
+        length[s] = 0;
+        if (s == 0) used = 0u;
+        __syncthreads();
+        uint32_t rank = 0;                                    // used symbols before this one by (count, symbol)
+        for (int t = 0; t < 256; ++t) {
+            const uint64_t o = count[t];
+            rank += (o != 0 && (o < c || (o == c && (uint32_t)t < s))) ? 1u : 0u;
+        }
+        if (c != 0) {
+            weight[rank] = c;
+            leaf_symbol[rank] = (uint8_t)s;
+            atomicAdd(&used, 1u);
+        }
+        __syncthreads();
+        if (s == 0) {
+            const int m = (int)used;
+            int deep = 0;
+            if (m == 1) {
+                length[leaf_symbol[0]] = 1;
+                deep = 1;
+            } else if (m > 1) {
+                int next_leaf = 0, next_internal = m, made = m;
+                while (made < 2 * m - 1) {                    // at most 255 merges
+                    int pick[2];
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        const bool have_leaf = next_leaf < m, have_internal = next_internal < made;
+                        // a leaf is preferred to an internal node of equal weight
+                        if (have_leaf && (!have_internal || weight[next_leaf] <= weight[next_internal])) pick[k] = next_leaf++;
+                        else pick[k] = next_internal++;
+                    }
+                    weight[made] = weight[pick[0]] + weight[pick[1]];
+                    parent[pick[0]] = (uint16_t)made;
+                    parent[pick[1]] = (uint16_t)made;
+                    ++made;
+                }
+                depth[2 * m - 2] = 0;
+                for (int i = 2 * m - 3; i >= 0; --i) depth[i] = (uint16_t)(depth[parent[i]] + 1);   // parents are made later
+                for (int i = 0; i < m; ++i) {
+                    length[leaf_symbol[i]] = (uint8_t)(depth[i] < 255 ? depth[i] : 255);
+                    deep = depth[i] > deep ? depth[i] : deep;
+                }
+            }
+            deepest = (uint32_t)deep;
+        }
+        __syncthreads();
+        if (deepest <= (uint32_t)kMaxLen) break;
+        if (c != 0) c = (c + 1) >> 1;
+        __syncthreads();                                      // everyone has read `deepest` before it is written again
+    }
+    // canonical codes: by increasing (length, symbol); few symbols, one lane
+    if (s == 0) {
+        uint32_t per_length[kMaxLen + 2], next[kMaxLen + 2];
+        for (int l = 0; l <= kMaxLen + 1; ++l) per_length[l] = 0u;
+        for (int t = 0; t < 256; ++t) ++per_length[length[t]];
+        next[0] = next[1] = 0u;
+        for (int l = 2; l <= kMaxLen; ++l) next[l] = (next[l - 1] + per_length[l - 1]) << 1;
+        for (int t = 0; t < 256; ++t) {
+            const uint32_t l = length[t];
+            code_of[t] = l ? next[l]++ : 0u;
+        }
+    }
+    __syncthreads();
+    lay.len[s] = length[s];
+    lay.table[s] = (code_of[s] << 8) | length[s];
+    // payload bits: every symbol's count times its length (the counts as they were)
+    __shared__ uint64_t bit_sum[256];
+    bit_sum[s] = original * length[s];
+    __syncthreads();
+    for (int step = 128; step >= 1; step >>= 1) {
+        if (s < (uint32_t)step) bit_sum[s] += bit_sum[s + step];
+        __syncthreads();
+    }
+    if (s == 0) lay.totals[1] = bit_sum[0];
+}
+
+// the symbols of a chunk, 16 at a time; `valid` of them exist
+__device__ __forceinline__ void load_symbols(const uint8_t* in, uint64_t first, uint32_t valid, uint32_t (&word)[4])
+{
+    if (valid >= 16u) {
+        const u32x4 w = *reinterpret_cast<const u32x4*>(in + first);
+        word[0] = w.x; word[1] = w.y; word[2] = w.z; word[3] = w.w;
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        word[k] = 0u;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            if ((uint32_t)(4 * k + b) < valid) word[k] |= (uint32_t)in[first + 4 * k + b] << (8 * b);
+    }
+}
+
+// exclusive prefix over the workgroup of one value per thread; all = the workgroup's total
+__device__ __forceinline__ uint32_t workgroup_exclusive_scan(uint32_t mine, uint32_t* lds /* [4] */, uint32_t* all)
+{
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t inc = wave_inclusive_scan(mine);
+    if (lane == 63u) lds[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int v = 0; v < kThreads / 64; ++v) {
+        const uint32_t t = lds[v];
+        if ((uint32_t)v < wave) before += t;
+        total += t;
+    }
+    __syncthreads();
+    *all = total;
+    return before + inc - mine;
+}
+
+// ---- count: words per chunk, sums per group -------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Layout lay)
+{
+    __shared__ uint8_t len[256];
+    __shared__ uint32_t lds[4];
+    len[threadIdx.x] = (uint8_t)(lay.table[threadIdx.x] & 0xffu);
+    __syncthreads();
+    const uint32_t chunk = blockIdx.x * kThreads + threadIdx.x;
+    uint32_t words = 0;
+    if (chunk < lay.chunks) {
+        const uint64_t first = (uint64_t)chunk * kChunk;
+        const uint32_t valid = lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
+        uint32_t bits = 0;
+        for (uint32_t i = 0; i < valid; i += 16) {            // at most 16 rounds
+            uint32_t word[4];
+            load_symbols(lay.in, first + i, valid - i, word);
+            const uint32_t here = valid - i < 16u ? valid - i : 16u;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    if ((uint32_t)(4 * k + b) < here) bits += len[(word[k] >> (8 * b)) & 0xffu];
+        }
+        words = (bits + 31u) >> 5;
+        lay.offsets[chunk] = words;                           // becomes the chunk's offset in the write pass
+    }
+    uint32_t total;
+    workgroup_exclusive_scan(words, lds, &total);
+    if (threadIdx.x == 0) lay.group_sums[blockIdx.x] = total;
+}
+
+// ---- scan of the group sums (in place, exclusive); the stream's size --------------------------------
+__global__ __launch_bounds__(kThreads) void huffman_scan_kernel(const Layout lay)
+{
+    __shared__ uint32_t lds[4];
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < lay.groups; base += kThreads) {         // workgroup-uniform trip count
+        const uint32_t i = base + threadIdx.x;
+        const uint32_t mine = i < lay.groups ? lay.group_sums[i] : 0u;
+        uint32_t total;
+        const uint32_t before = workgroup_exclusive_scan(mine, lds, &total);
+        if (i < lay.groups) lay.group_sums[i] = carry + before;
+        carry += total;
+    }
+    if (threadIdx.x == 0) {
+        lay.offsets[lay.chunks] = carry;
+        lay.totals[0] = 256u + 4ull * (lay.chunks + 1ull) + 4ull * carry;
+    }
+}
+
+// ---- write: offsets and payload -------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Layout lay)
+{
+    __shared__ uint32_t table[256];
+    __shared__ uint32_t lds[4];
+    table[threadIdx.x] = lay.table[threadIdx.x];
+    const uint32_t chunk = blockIdx.x * kThreads + threadIdx.x;
+    const bool live = chunk < lay.chunks;
+    const uint32_t words = live ? lay.offsets[chunk] : 0u;
+    uint32_t total;
+    const uint32_t offset = lay.group_sums[blockIdx.x] + workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
+    if (!live) return;
+    lay.offsets[chunk] = offset;
+    const uint64_t first = (uint64_t)chunk * kChunk;
+    const uint32_t valid = lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
+    uint32_t* out = lay.payload + offset;
+    uint64_t acc = 0;                                         // the low `filled` bits are pending, oldest on top
+    uint32_t filled = 0, written = 0;
+    for (uint32_t i = 0; i < valid; i += 16) {
+        uint32_t word[4];
+        load_symbols(lay.in, first + i, valid - i, word);
+        const uint32_t here = valid - i < 16u ? valid - i : 16u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if ((uint32_t)(4 * k + b) < here) {
+                    const uint32_t e = table[(word[k] >> (8 * b)) & 0xffu];
+                    const uint32_t l = e & 0xffu;
+                    acc = (acc << l) | (e >> 8);
+                    filled += l;
+                    if (filled >= 32u) {                      // filled < 32 + 24 before this
+                        filled -= 32u;
+                        if (written < words) out[written] = (uint32_t)(acc >> filled);
+                        ++written;
+                    }
+                }
+            }
+    }
+    if (filled && written < words) out[written] = (uint32_t)(acc << (32u - filled));   // zero-padded to a whole word
+}
+
+// ---- decode -------------------------------------------------------------------------------------------
+// The stream may be foreign: the tables are built from whatever the 256 length bytes say
+// (lengths above 24 count as unused), reads of payload words are bounded by the stream's size
+// (words outside read as zero), and every loop is bounded by the symbol count.
+__global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const uint8_t* __restrict__ len_in,
+                                                                  const uint32_t* __restrict__ offsets,
+                                                                  const uint32_t* __restrict__ payload,
+                                                                  uint32_t payload_words, uint64_t n, uint32_t chunks,
+                                                                  uint8_t* __restrict__ out)
+{
+    __shared__ uint8_t  len[256];
+    __shared__ uint8_t  sorted[256];                          // symbols by (length, symbol)
+    __shared__ uint32_t per_length[kMaxLen + 2], first[kMaxLen + 2], start[kMaxLen + 2];
+    __shared__ uint16_t fast[1 << kFastBits];                 // next kFastBits bits -> symbol | length << 8; 0: longer code
+    const uint32_t s = threadIdx.x;
+    {
+        const uint32_t l = len_in[s];
+        len[s] = l <= (uint32_t)kMaxLen ? (uint8_t)l : (uint8_t)0;
+    }
+    for (int i = s; i < (1 << kFastBits); i += kThreads) fast[i] = 0;
+    if (s < (uint32_t)kMaxLen + 2u) per_length[s] = 0u;
+    __syncthreads();
+    const uint32_t l = len[s];
+    if (l) atomicAdd(&per_length[l], 1u);
+    __syncthreads();
+    if (s == 0) {
+        first[0] = first[1] = 0u;
+        start[0] = start[1] = 0u;
+        for (int k = 2; k <= kMaxLen; ++k) {
+            first[k] = (first[k - 1] + per_length[k - 1]) << 1;
+            start[k] = start[k - 1] + per_length[k - 1];
+        }
+    }
+    __syncthreads();
+    if (l) {
+        uint32_t before = 0;                                  // symbols of the same length below this one
+        for (uint32_t t = 0; t < s; ++t) before += len[t] == l ? 1u : 0u;
+        sorted[start[l] + before] = (uint8_t)s;
+        const uint32_t code = first[l] + before;
+        if (l <= (uint32_t)kFastBits && (code >> l) == 0u) {  // a code that does not fit its length: a foreign table
+            const uint32_t lo = code << (kFastBits - l), span = 1u << (kFastBits - l);
+            for (uint32_t k = 0; k < span; ++k) fast[lo + k] = (uint16_t)(s | (l << 8));
+        }
+    }
+    __syncthreads();
+
+    const uint32_t chunk = blockIdx.x * kThreads + threadIdx.x;
+    if (chunk >= chunks) return;
+    const uint64_t base = (uint64_t)chunk * kChunk;
+    const uint32_t valid = n - base < (uint64_t)kChunk ? (uint32_t)(n - base) : (uint32_t)kChunk;
+    uint32_t next_word = offsets[chunk];
+    uint64_t buf = 0;                                         // pending bits, the next one on top
+    uint32_t have = 0;
+    uint8_t* dst = out + base;
+    for (uint32_t i = 0; i < valid; i += 4) {
+        uint32_t four = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if (have <= 32u) {
+                const uint32_t w = next_word < payload_words ? payload[next_word] : 0u;
+                ++next_word;
+                buf |= (uint64_t)w << (32u - have);
+                have += 32u;
+            }
+            uint32_t symbol = 0, used_bits = 1;
+            const uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
+            if (e) {
+                symbol = e & 0xffu;
+                used_bits = e >> 8;
+            } else {
+                for (int k = kFastBits + 1; k <= kMaxLen; ++k) {
+                    const uint32_t code = (uint32_t)(buf >> (64 - k));
+                    if (per_length[k] && code >= first[k] && code - first[k] < per_length[k]) {
+                        symbol = sorted[start[k] + code - first[k]];
+                        used_bits = (uint32_t)k;
+                        break;
+                    }
+                }
+            }
+            buf <<= used_bits;
+            have -= used_bits;
+            four |= symbol << (8 * b);
+        }
+        if (i + 4 <= valid) {
+            *reinterpret_cast<uint32_t*>(dst + i) = four;     // out is 4-byte aligned, chunks are 256 bytes
+        } else {
+            for (uint32_t b = 0; i + b < valid; ++b) dst[i + b] = (uint8_t)(four >> (8 * b));
+        }
+    }
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+uint64_t chunks_of(uint64_t n) { return (n + kChunk - 1) / kChunk; }
+uint64_t groups_of(uint64_t n) { return (chunks_of(n) + kThreads - 1) / kThreads; }
+constexpr uint64_t kMaxSymbols = ((uint64_t)1 << 32) - 1;
+
+}  // namespace
+}  // namespace fh
+
+extern "C" {
+
+size_t fh_huffman_stream_bytes(uint64_t n)
+{
+    if (n > fh::kMaxSymbols) return 0;
+    return (size_t)(256u + 4u * (fh::chunks_of(n) + 1u) + 4u * (uint64_t)fh::kChunkWordsMax * fh::chunks_of(n));
+}
+
+size_t fh_huffman_workspace_bytes(uint64_t n)
+{
+    if (n > fh::kMaxSymbols) return 0;
+    return (size_t)(4u * (256u + 256u + (fh::groups_of(n) > 0 ? fh::groups_of(n) : 1u)));
+}
+
+fh_status fh_huffman_encode(const void* bytes, uint64_t n, void* stream_out, size_t stream_cap, void* totals,
+                            void* workspace, size_t workspace_cap, void* stream)
+{
+    using namespace fh;
+    if (n > kMaxSymbols) return FH_ERR_BAD_NUMEL;
+    if (!stream_out || !totals || !workspace || (n > 0 && !bytes)) return FH_ERR_NULL;
+    if (!aligned(bytes, 16) || !aligned(stream_out, 16) || !aligned(totals, 8) || !aligned(workspace, 16)) return FH_ERR_ALIGNMENT;
+    if (stream_cap < fh_huffman_stream_bytes(n) || workspace_cap < fh_huffman_workspace_bytes(n)) return FH_ERR_BUFFER_TOO_SMALL;
+    Layout lay;
+    lay.chunks = (uint32_t)chunks_of(n);
+    lay.groups = (uint32_t)groups_of(n);
+    lay.len = static_cast<uint8_t*>(stream_out);
+    lay.offsets = reinterpret_cast<uint32_t*>(lay.len + 256);
+    lay.payload = lay.offsets + lay.chunks + 1;
+    lay.hist = static_cast<uint32_t*>(workspace);
+    lay.table = lay.hist + 256;
+    lay.group_sums = lay.table + 256;
+    lay.totals = static_cast<uint64_t*>(totals);
+    lay.in = static_cast<const uint8_t*>(bytes);
+    lay.n = n;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(huffman_clear_kernel, dim3(1), dim3(256), 0, s, lay.hist);
+    if (n > 0) {
+        const uint64_t want = (n / 16 + 255) / 256 / 8 + 1;   // about eight vectors per thread
+        const uint32_t grid = (uint32_t)(want < 4096 ? want : 4096);
+        hipLaunchKernelGGL(huffman_histogram_kernel, dim3(grid), dim3(256), 0, s, lay.in, n, lay.hist);
+    }
+    hipLaunchKernelGGL(huffman_code_kernel, dim3(1), dim3(256), 0, s, lay);
+    if (lay.groups > 0) hipLaunchKernelGGL(huffman_count_kernel, dim3(lay.groups), dim3(kThreads), 0, s, lay);
+    hipLaunchKernelGGL(huffman_scan_kernel, dim3(1), dim3(kThreads), 0, s, lay);
+    if (lay.groups > 0) hipLaunchKernelGGL(huffman_write_kernel, dim3(lay.groups), dim3(kThreads), 0, s, lay);
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+fh_status fh_huffman_decode(const void* stream_in, size_t stream_bytes, uint64_t n, void* out, size_t out_cap,
+                            void* stream)
+{
+    using namespace fh;
+    if (n > kMaxSymbols) return FH_ERR_BAD_NUMEL;
+    if (n == 0) return FH_OK;
+    if (!stream_in || !out) return FH_ERR_NULL;
+    if (!aligned(stream_in, 16) || !aligned(out, 16)) return FH_ERR_ALIGNMENT;
+    if (out_cap < n) return FH_ERR_BUFFER_TOO_SMALL;
+    const uint64_t chunks = chunks_of(n);
+    const uint64_t header = 256u + 4u * (chunks + 1u);
+    if (stream_bytes < header) return FH_ERR_BUFFER_TOO_SMALL;    // not even the lengths and the offsets
+    const uint64_t words = (stream_bytes - header) / 4u;
+    const uint8_t* base = static_cast<const uint8_t*>(stream_in);
+    const uint32_t* offsets = reinterpret_cast<const uint32_t*>(base + 256);
+    hipLaunchKernelGGL(huffman_decode_kernel, dim3((uint32_t)groups_of(n)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), base, offsets, offsets + chunks + 1,
+                       (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu), n, (uint32_t)chunks,
+                       static_cast<uint8_t*>(out));
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -30,6 +30,7 @@
 
 #include "fh_batch.hpp"
 #include "fh_channels.hpp"
+#include "fh_scan.hpp"
 
 namespace fh {
 namespace {
@@ -163,23 +164,7 @@ __device__ __forceinline__ Sums32 narrow(const Sums& s)
     return Sums32{(uint32_t)s.values, (uint32_t)s.index_bytes, (uint32_t)s.sparse_tiles};
 }
 
-// v + (the lane the control word names, 0 where there is none or the row is masked out)
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ uint32_t dpp_add(uint32_t v)
-{
-    return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
-}
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
-{
-    v = dpp_add<0x111, 0xf>(v);                               // row_shr:1
-    v = dpp_add<0x112, 0xf>(v);                               // row_shr:2
-    v = dpp_add<0x114, 0xf>(v);                               // row_shr:4
-    v = dpp_add<0x118, 0xf>(v);                               // row_shr:8
-    v = dpp_add<0x142, 0xa>(v);                               // row_bcast:15 onto rows 1 and 3
-    v = dpp_add<0x143, 0xc>(v);                               // row_bcast:31 onto rows 2 and 3
-    return v;
-}
-__device__ __forceinline__ Sums32 wave_inclusive_scan(const Sums32& s)
+__device__ __forceinline__ Sums32 wave_inclusive_scans(const Sums32& s)
 {
     return Sums32{wave_inclusive_scan(s.values), wave_inclusive_scan(s.index_bytes), wave_inclusive_scan(s.sparse_tiles)};
 }
@@ -214,7 +199,7 @@ __device__ __forceinline__ Sums across_waves(const Sums& wave_sum, uint64_t* lds
 template <int WAVES>
 __device__ __forceinline__ Sums workgroup_exclusive_scan(Sums mine, uint64_t* lds /* [3 * WAVES] */, Sums* total)
 {
-    const Sums32 own = narrow(mine), inc = wave_inclusive_scan(own);
+    const Sums32 own = narrow(mine), inc = wave_inclusive_scans(own);
     const Sums before = across_waves<WAVES>(wave_total(inc), lds, total);
     return Sums{before.values + inc.values - own.values, before.index_bytes + inc.index_bytes - own.index_bytes,
                 before.sparse_tiles + inc.sparse_tiles - own.sparse_tiles};
@@ -225,7 +210,7 @@ template <int WAVES>
 __device__ __forceinline__ Sums workgroup_sum(Sums part, uint64_t* lds /* [3 * WAVES] */)
 {
     Sums total;
-    across_waves<WAVES>(wave_total(wave_inclusive_scan(narrow(part))), lds, &total);
+    across_waves<WAVES>(wave_total(wave_inclusive_scans(narrow(part))), lds, &total);
     return total;
 }
 
@@ -466,7 +451,7 @@ __global__ __launch_bounds__(64 * kGroupsPerWorkgroup) void sparse_sums_kernel(c
         const uint32_t b = group * T + j * 64 + lane;
         if (b < s.tiles) mine = mine + tile_sums(byte[j], tile_pos(s, b), s.two_eps > 0.0f);
     }
-    const Sums total = wave_total(wave_inclusive_scan(narrow(mine)));
+    const Sums total = wave_total(wave_inclusive_scans(narrow(mine)));
     if (lane == 0u) job.wg[group] = total;
 }
 
@@ -509,13 +494,13 @@ __global__ __launch_bounds__(kScanThreads) void sparse_scan_kernel(const Batch<J
         }
 #pragma unroll
         for (int j = 0; j < kScanRows; ++j) {
-            inc[j] = wave_inclusive_scan(own[j]);
+            inc[j] = wave_inclusive_scans(own[j]);
             if (lane == 63u) cell_total[j * WAVES + wave] = inc[j];
         }
         __syncthreads();
         if (wave == 0u) {
             const Sums32 mine = lane < (uint32_t)CELLS ? cell_total[lane] : Sums32{0, 0, 0};
-            const Sums32 upto = wave_inclusive_scan(mine);
+            const Sums32 upto = wave_inclusive_scans(mine);
             if (lane < (uint32_t)CELLS)
                 cell_before[lane] = Sums32{upto.values - mine.values, upto.index_bytes - mine.index_bytes,
                                            upto.sparse_tiles - mine.sparse_tiles};

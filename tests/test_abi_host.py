@@ -307,3 +307,26 @@ def test_mixed_item_layout_and_batch_argument_checks():
     arr[1].params.bits = 4
     arr[1].raw_cap = 4 * 2 * 16 * 4 - 1
     assert lib.fh_compress_mixed_batch(arr, 2, None) == 7 and lib.fh_decompress_mixed_batch(arr, 2, None) == 7
+
+
+def test_huffman_sizes_and_argument_checks():
+    lib = api.raw_library()
+    assert api.huffman_stream_bytes(0) == 256 + 4
+    assert api.huffman_stream_bytes(1) == 256 + 8 + 768
+    assert api.huffman_stream_bytes(257) == 256 + 12 + 2 * 768          # 256 symbols of 24 bits = 192 words a chunk
+    assert api.huffman_workspace_bytes(0) == 4 * 513 and api.huffman_workspace_bytes(65537) == 4 * 514
+    assert api.huffman_stream_bytes(1 << 32) == 0                       # n < 2^32
+    fake = ctypes.c_void_p(0x10000)
+    enc = lambda data, n, out, cap, tot, ws, wcap: lib.fh_huffman_encode(data, n, out, cap, tot, ws, wcap, None)
+    assert enc(fake, 1 << 32, fake, 1 << 40, fake, fake, 1 << 20) == 6          # FH_ERR_BAD_NUMEL
+    assert enc(None, 100, fake, 1 << 20, fake, fake, 1 << 20) == 1              # FH_ERR_NULL
+    assert enc(fake, 100, fake, 1 << 20, None, fake, 1 << 20) == 1
+    assert enc(ctypes.c_void_p(0x10004), 100, fake, 1 << 20, fake, fake, 1 << 20) == 8   # FH_ERR_ALIGNMENT
+    assert enc(fake, 100, fake, 100, fake, fake, 1 << 20) == 7                  # FH_ERR_BUFFER_TOO_SMALL
+    assert enc(fake, 100, fake, 1 << 20, fake, fake, 16) == 7
+    dec = lambda s, sb, n, out, cap: lib.fh_huffman_decode(s, sb, n, out, cap, None)
+    assert dec(None, 0, 0, None, 0) == 0                                        # nothing to restore
+    assert dec(None, 1000, 10, fake, 10) == 1
+    assert dec(fake, 1000, 10, fake, 9) == 7
+    assert dec(fake, 200, 10, fake, 10) == 7                                    # not even the lengths and the offsets
+    assert dec(fake, 1000, 1 << 32, fake, 1 << 33) == 6
