@@ -341,6 +341,106 @@ def bench_sparse(args, api, W, dev) -> int:
     return 0
 
 
+def bench_huffman(args, api, W, dev) -> int:
+    """The entropy stage of the predictive form (Section 4.4.1: Huffman coding of the quantisation
+    codes): the index streams -- code bytes of dense blocks, CSR bytes of sparse ones -- that
+    fh_sparse_encode writes for the sparse bench's map sets with an error bound (--eps, default
+    0.02 here; --maps-scale K times as many maps).  One step = every stream encoded, then every
+    one decoded."""
+    import numpy as np
+    import torch
+
+    layers = ((64 * 1, 112, 112), (64 * 4, 112, 112), (64 * 6, 56, 56), (64 * 8, 28, 28), (64 * 15, 14, 14))
+    layers = tuple((maps * args.maps_scale, h, w) for maps, h, w in layers)
+    n, tau, eps = 4, 0.5, (args.eps if args.eps > 0 else 0.02)
+    stream = torch.cuda.current_stream()
+    jobs, host = [], []
+    for i, (maps, h, w) in enumerate(layers):
+        x = torch.from_numpy(W.salient_feature_maps(maps, h, w, seed=i)).to(dev)
+        bufs = api.fh_sparse_encode(x, maps, h, w, n, tau, stream=stream, eps=eps)
+        torch.cuda.synchronize()
+        ni = int(bufs.totals[1])
+        data = bufs.indices[:ni].clone()
+        host.append(data.cpu().numpy())
+        out = torch.empty(api.huffman_stream_bytes(ni), dtype=torch.uint8, device=dev)
+        totals = torch.zeros(2, dtype=torch.int64, device=dev)
+        ws = torch.empty(api.huffman_workspace_bytes(ni), dtype=torch.uint8, device=dev)
+        api.fh_huffman_encode(data, stream_out=out, totals=totals, workspace=ws, stream=stream)
+        torch.cuda.synchronize()
+        used = int(totals[0])
+        jobs.append((data, ni, out, totals, ws, used, torch.empty(ni, dtype=torch.uint8, device=dev)))
+        del x, bufs
+    nbytes = sum(j[1] for j in jobs)
+    stored = sum(j[5] for j in jobs)
+    print(f"[bench] huffman: {len(jobs)} streams, {nbytes / 2**20:.1f} MiB of index bytes, stored {stored / 2**20:.1f} MiB",
+          file=sys.stderr, flush=True)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def step(timed=False):
+        if timed:
+            ev[0].record(stream)
+        for data, ni, out, totals, ws, used, back in jobs:
+            api.fh_huffman_encode(data, stream_out=out, totals=totals, workspace=ws, stream=stream)
+        if timed:
+            ev[1].record(stream)
+        for data, ni, out, totals, ws, used, back in jobs:
+            api.fh_huffman_decode(out[:used], ni, out=back, stream=stream)
+        if timed:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t_start) / args.steps
+    ms_e = ms_d = 0.0
+    for _ in range(args.steps):
+        step(timed=True)
+        torch.cuda.synchronize()
+        ms_e += ev[0].elapsed_time(ev[1]) / args.steps
+        ms_d += ev[1].elapsed_time(ev[2]) / args.steps
+    for data, ni, out, totals, ws, used, back in jobs:
+        if not torch.equal(back, data):
+            print("bench.py: the Huffman round trip did not restore its input", file=sys.stderr)
+            return 1
+    alg_e = 3 * nbytes + stored                               # histogram, count and write passes read the bytes
+    alg_d = stored + nbytes
+    dom = ("encode (histogram + code + count + scan + write)", alg_e, ms_e) if ms_e >= ms_d else ("decode", alg_d, ms_d)
+    result = {
+        "metric": "Huffman coding of the predictive form's index streams, encode+decode GB/s of input on 1 MI355X",
+        "value": round(nbytes / elapsed / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"huffman_index_streams_mobilenetv2_b64_kept_channels_n4_tau0.5_eps{eps:g}_x{args.maps_scale}",
+                   "streams": len(jobs), "input_bytes": nbytes, "stored_bytes": stored,
+                   "entry_point": "fh_huffman_encode + fh_huffman_decode (per stream)"},
+        "roofline": {"bound": "hbm", "kernel": dom[0] + ", all launches of a step, event-timed",
+                     "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},
+        "kernels": {"encode": {"ms": round(ms_e, 4), "bytes": alg_e, "GBps": round(alg_e / ms_e / 1e6, 1)},
+                    "decode": {"ms": round(ms_d, 4), "bytes": alg_d, "GBps": round(alg_d / ms_d / 1e6, 1)}},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        t_cpu, done = 0.0, 0
+        for data in host:
+            sample = data[: 1 << 24]
+            t1 = time.perf_counter()
+            st, _ = oracle.huffman_encode(sample)
+            oracle.huffman_decode(st, sample.size)
+            t_cpu += time.perf_counter() - t1
+            done += sample.size
+            if t_cpu > 20.0:
+                break
+        result["cpu_baseline"] = {"value": round(done / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"leading {done / 2**20:.1f} MiB of the streams, {t_cpu:.1f} s"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def bench_hooks(args, api, W, dev) -> int:
     """A training step with the compressor hooked into autograd (saved_tensors_hooks): the
     feed-forward half of a 12-layer transformer encoder at configuration 4's shapes (batch 16,
@@ -441,12 +541,13 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB device copies before the timed region, so that a "
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE against a known size")
-    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed", "sparse", "hooks"), default="roundtrip",
+    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed", "sparse", "hooks", "huffman"), default="roundtrip",
                     help="roundtrip (default): compress + decompress of the tensor set; classify: the "
                          "channel classification step (moments + outlier counts), measured on its own; "
                          "mixed: the round trip with salient channels kept raw beside the quantised stream; "
                          "sparse: block-wise sparse storage of the kept channels' maps; hooks: a training "
-                         "step with the compressor in autograd's saved-tensor hooks")
+                         "step with the compressor in autograd's saved-tensor hooks; huffman: the entropy "
+                         "stage over the predictive form's index streams")
     ap.add_argument("--eps", type=float, default=0.0,
                     help="--op sparse: error bound of the predictive form of dense blocks (0 = verbatim)")
     ap.add_argument("--maps-scale", type=int, default=1, metavar="K",
@@ -487,6 +588,8 @@ def main() -> int:
         return bench_sparse(args, api, W, dev)
     if args.op == "hooks":
         return bench_hooks(args, api, W, dev)
+    if args.op == "huffman":
+        return bench_huffman(args, api, W, dev)
 
     w = W.full_config(args.config)
     t0 = time.time()

@@ -18,7 +18,7 @@
 //   write       a thread turns its chunk's word count into its offset (group base + a scan
 //               over the workgroup) and writes its words.
 // Decoding needs no pass but one: the offsets are part of the stream.  Every workgroup
-// rebuilds the canonical tables from the 256 lengths (a 10-bit lookup table for the short
+// rebuilds the canonical tables from the 256 lengths (a 12-bit lookup table for the short
 // codes, first-code / count comparisons for the longer ones).
 // Everything here is integer work; results do not depend on launch geometry.
 #include "../../include/fedhybrid.h"
@@ -33,7 +33,7 @@ constexpr int kThreads = 256;                      // chunks per workgroup: a gr
 constexpr int kMaxLen = 24;
 constexpr int kChunkWordsMax = kChunk * kMaxLen / 32;
 constexpr int kHistCopies = 8;
-constexpr int kFastBits = 10;
+constexpr int kFastBits = 12;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -87,7 +87,6 @@ __global__ __launch_bounds__(256) void huffman_code_kernel(const Layout lay)
     __shared__ uint64_t count[256];                           // this round's counts, by symbol
     __shared__ uint64_t weight[511];                          // leaves in rank order, then internal nodes as made
     __shared__ uint16_t parent[511];
-    __shared__ uint16_t depth[511];
     __shared__ uint8_t  leaf_symbol[256];
     __shared__ uint8_t  length[256];
     __shared__ uint32_t code_of[256];
@@ -111,53 +110,68 @@ __global__ __launch_bounds__(256) void huffman_code_kernel(const Layout lay)
             atomicAdd(&used, 1u);
         }
         __syncthreads();
+        const int m = (int)used;
         if (s == 0) {
-            const int m = (int)used;
-            int deep = 0;
-            if (m == 1) {
-                length[leaf_symbol[0]] = 1;
-                deep = 1;
-            } else if (m > 1) {
+            deepest = 0u;
+            if (m > 1) {
+                // the fronts of the two queues stay in registers; LDS is read once per node taken
                 int next_leaf = 0, next_internal = m, made = m;
+                uint64_t leaf_front = weight[0], internal_front = 0;
                 while (made < 2 * m - 1) {                    // at most 255 merges
-                    int pick[2];
+                    uint64_t sum = 0;
 #pragma unroll
                     for (int k = 0; k < 2; ++k) {
                         const bool have_leaf = next_leaf < m, have_internal = next_internal < made;
                         // a leaf is preferred to an internal node of equal weight
-                        if (have_leaf && (!have_internal || weight[next_leaf] <= weight[next_internal])) pick[k] = next_leaf++;
-                        else pick[k] = next_internal++;
+                        if (have_leaf && (!have_internal || leaf_front <= internal_front)) {
+                            sum += leaf_front;
+                            parent[next_leaf] = (uint16_t)made;
+                            ++next_leaf;
+                            if (next_leaf < m) leaf_front = weight[next_leaf];
+                        } else {
+                            sum += internal_front;
+                            parent[next_internal] = (uint16_t)made;
+                            ++next_internal;
+                            if (next_internal < made) internal_front = weight[next_internal];
+                        }
                     }
-                    weight[made] = weight[pick[0]] + weight[pick[1]];
-                    parent[pick[0]] = (uint16_t)made;
-                    parent[pick[1]] = (uint16_t)made;
+                    weight[made] = sum;
+                    if (next_internal == made) internal_front = sum;   // the new node is the queue's front
                     ++made;
                 }
-                depth[2 * m - 2] = 0;
-                for (int i = 2 * m - 3; i >= 0; --i) depth[i] = (uint16_t)(depth[parent[i]] + 1);   // parents are made later
-                for (int i = 0; i < m; ++i) {
-                    length[leaf_symbol[i]] = (uint8_t)(depth[i] < 255 ? depth[i] : 255);
-                    deep = depth[i] > deep ? depth[i] : deep;
-                }
             }
-            deepest = (uint32_t)deep;
+        }
+        __syncthreads();
+        if (c != 0) {                                         // every leaf walks up to the root: its depth
+            uint32_t d = 1;
+            if (m > 1) {
+                d = 0;
+                for (uint32_t node = rank; node != (uint32_t)(2 * m - 2) && d < 256u; ++d) node = parent[node];
+            }
+            length[s] = (uint8_t)(d < 255u ? d : 255u);
+            atomicMax(&deepest, d);
         }
         __syncthreads();
         if (deepest <= (uint32_t)kMaxLen) break;
         if (c != 0) c = (c + 1) >> 1;
         __syncthreads();                                      // everyone has read `deepest` before it is written again
     }
-    // canonical codes: by increasing (length, symbol); few symbols, one lane
+    // canonical codes: by increasing (length, symbol)
+    __shared__ uint32_t per_length[kMaxLen + 2], first_code[kMaxLen + 2];
+    if (s < (uint32_t)kMaxLen + 2u) per_length[s] = 0u;
+    __syncthreads();
+    const uint32_t my_length = length[s];
+    if (my_length) atomicAdd(&per_length[my_length], 1u);
+    __syncthreads();
     if (s == 0) {
-        uint32_t per_length[kMaxLen + 2], next[kMaxLen + 2];
-        for (int l = 0; l <= kMaxLen + 1; ++l) per_length[l] = 0u;
-        for (int t = 0; t < 256; ++t) ++per_length[length[t]];
-        next[0] = next[1] = 0u;
-        for (int l = 2; l <= kMaxLen; ++l) next[l] = (next[l - 1] + per_length[l - 1]) << 1;
-        for (int t = 0; t < 256; ++t) {
-            const uint32_t l = length[t];
-            code_of[t] = l ? next[l]++ : 0u;
-        }
+        first_code[0] = first_code[1] = 0u;
+        for (int l = 2; l <= kMaxLen; ++l) first_code[l] = (first_code[l - 1] + per_length[l - 1]) << 1;
+    }
+    __syncthreads();
+    {
+        uint32_t before = 0;                                  // symbols of the same length below this one
+        for (uint32_t t = 0; t < s; ++t) before += length[t] == my_length ? 1u : 0u;
+        code_of[s] = my_length ? first_code[my_length] + before : 0u;
     }
     __syncthreads();
     lay.len[s] = length[s];
@@ -222,15 +236,29 @@ __global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Layout la
         const uint64_t first = (uint64_t)chunk * kChunk;
         const uint32_t valid = lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
         uint32_t bits = 0;
-        for (uint32_t i = 0; i < valid; i += 16) {            // at most 16 rounds
-            uint32_t word[4];
-            load_symbols(lay.in, first + i, valid - i, word);
-            const uint32_t here = valid - i < 16u ? valid - i : 16u;
+        if (valid == (uint32_t)kChunk) {                      // all sixteen loads in flight together
+            u32x4 v[kChunk / 16];
 #pragma unroll
-            for (int k = 0; k < 4; ++k)
+            for (int i = 0; i < kChunk / 16; ++i) v[i] = reinterpret_cast<const u32x4*>(lay.in + first)[i];
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    if ((uint32_t)(4 * k + b) < here) bits += len[(word[k] >> (8 * b)) & 0xffu];
+            for (int i = 0; i < kChunk / 16; ++i) {
+                const uint32_t word[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) bits += len[(word[k] >> (8 * b)) & 0xffu];
+            }
+        } else {
+            for (uint32_t i = 0; i < valid; i += 16) {        // the last chunk: at most 16 rounds
+                uint32_t word[4];
+                load_symbols(lay.in, first + i, valid - i, word);
+                const uint32_t here = valid - i < 16u ? valid - i : 16u;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        if ((uint32_t)(4 * k + b) < here) bits += len[(word[k] >> (8 * b)) & 0xffu];
+            }
         }
         words = (bits + 31u) >> 5;
         lay.offsets[chunk] = words;                           // becomes the chunk's offset in the write pass
@@ -277,9 +305,12 @@ __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Layout la
     uint32_t* out = lay.payload + offset;
     uint64_t acc = 0;                                         // the low `filled` bits are pending, oldest on top
     uint32_t filled = 0, written = 0;
+    uint32_t word[4], ahead[4];
+    load_symbols(lay.in, first, valid, ahead);
     for (uint32_t i = 0; i < valid; i += 16) {
-        uint32_t word[4];
-        load_symbols(lay.in, first + i, valid - i, word);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) word[k] = ahead[k];
+        if (i + 16 < valid) load_symbols(lay.in, first + i + 16, valid - i - 16, ahead);   // in flight while this vector is coded
         const uint32_t here = valid - i < 16u ? valid - i : 16u;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
@@ -315,12 +346,12 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const uint8_t*
     __shared__ uint8_t  sorted[256];                          // symbols by (length, symbol)
     __shared__ uint32_t per_length[kMaxLen + 2], first[kMaxLen + 2], start[kMaxLen + 2];
     __shared__ uint16_t fast[1 << kFastBits];                 // next kFastBits bits -> symbol | length << 8; 0: longer code
+    __shared__ uint32_t ring[8 * kThreads];
     const uint32_t s = threadIdx.x;
     {
         const uint32_t l = len_in[s];
         len[s] = l <= (uint32_t)kMaxLen ? (uint8_t)l : (uint8_t)0;
     }
-    for (int i = s; i < (1 << kFastBits); i += kThreads) fast[i] = 0;
     if (s < (uint32_t)kMaxLen + 2u) per_length[s] = 0u;
     __syncthreads();
     const uint32_t l = len[s];
@@ -339,11 +370,21 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const uint8_t*
         uint32_t before = 0;                                  // symbols of the same length below this one
         for (uint32_t t = 0; t < s; ++t) before += len[t] == l ? 1u : 0u;
         sorted[start[l] + before] = (uint8_t)s;
-        const uint32_t code = first[l] + before;
-        if (l <= (uint32_t)kFastBits && (code >> l) == 0u) {  // a code that does not fit its length: a foreign table
-            const uint32_t lo = code << (kFastBits - l), span = 1u << (kFastBits - l);
-            for (uint32_t k = 0; k < span; ++k) fast[lo + k] = (uint16_t)(s | (l << 8));
+    }
+    __syncthreads();
+    // the tables of this stream, in registers (the same in every thread)
+    uint32_t count_of[kMaxLen + 1], first_of[kMaxLen + 1], start_of[kMaxLen + 1];
+#pragma unroll
+    for (int k = 1; k <= kMaxLen; ++k) { count_of[k] = per_length[k]; first_of[k] = first[k]; start_of[k] = start[k]; }
+    for (uint32_t i = s; i < (1u << kFastBits); i += kThreads) {      // the short codes: what the next kFastBits bits decode to
+        uint32_t e = 0;
+#pragma unroll
+        for (int k = kFastBits; k >= 1; --k) {
+            const uint32_t code = i >> (kFastBits - k);
+            if (count_of[k] && code >= first_of[k] && code - first_of[k] < count_of[k])
+                e = sorted[start_of[k] + code - first_of[k]] | ((uint32_t)k << 8);   // at most one length matches a prefix code
         }
+        fast[i] = (uint16_t)e;
     }
     __syncthreads();
 
@@ -351,43 +392,67 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const uint8_t*
     if (chunk >= chunks) return;
     const uint64_t base = (uint64_t)chunk * kChunk;
     const uint32_t valid = n - base < (uint64_t)kChunk ? (uint32_t)(n - base) : (uint32_t)kChunk;
-    uint32_t next_word = offsets[chunk];
+    // The chunk's words come through a ring of eight in LDS: when four have been consumed, the
+    // four loaded at the previous refill take their place and the next four are requested, so a
+    // load has the time of four words' decoding to arrive.
+    uint32_t* mine = ring + threadIdx.x;                      // word k of the ring at mine[(k & 7) * kThreads]
+    const uint32_t first_word = offsets[chunk];
+    uint32_t pending[4];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) mine[k * kThreads] = first_word + k < payload_words ? payload[first_word + k] : 0u;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) pending[k] = first_word + 8 + k < payload_words ? payload[first_word + 8 + k] : 0u;
+    uint32_t taken = 0;                                       // words moved from the ring into `buf`
     uint64_t buf = 0;                                         // pending bits, the next one on top
     uint32_t have = 0;
     uint8_t* dst = out + base;
-    for (uint32_t i = 0; i < valid; i += 4) {
-        uint32_t four = 0;
+    for (uint32_t i = 0; i < valid; i += 16) {
+        uint32_t sixteen[4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            if (have <= 32u) {
-                const uint32_t w = next_word < payload_words ? payload[next_word] : 0u;
-                ++next_word;
-                buf |= (uint64_t)w << (32u - have);
-                have += 32u;
-            }
-            uint32_t symbol = 0, used_bits = 1;
-            const uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
-            if (e) {
-                symbol = e & 0xffu;
-                used_bits = e >> 8;
-            } else {
-                for (int k = kFastBits + 1; k <= kMaxLen; ++k) {
-                    const uint32_t code = (uint32_t)(buf >> (64 - k));
-                    if (per_length[k] && code >= first[k] && code - first[k] < per_length[k]) {
-                        symbol = sorted[start[k] + code - first[k]];
-                        used_bits = (uint32_t)k;
-                        break;
+        for (int q = 0; q < 4; ++q) {
+            uint32_t four = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (have <= 32u) {
+                    if ((taken & 3u) == 0u && taken != 0u) {  // a block of four used up: refill the half of the ring just freed
+                        const uint32_t slot = (taken + 4u) & 7u;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) mine[((slot + k) & 7u) * kThreads] = pending[k];
+                        const uint32_t at = first_word + taken + 8u;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) pending[k] = at + k < payload_words ? payload[at + k] : 0u;
                     }
+                    const uint32_t w = mine[(taken & 7u) * kThreads];
+                    ++taken;
+                    buf |= (uint64_t)w << (32u - have);
+                    have += 32u;
                 }
+                uint32_t symbol = 0, used_bits = 1;
+                const uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
+                if (e) {
+                    symbol = e & 0xffu;
+                    used_bits = e >> 8;
+                } else {
+#pragma unroll
+                    for (int k = kMaxLen; k > kFastBits; --k) {       // no LDS until the length is known
+                        const uint32_t code = (uint32_t)(buf >> (64 - k));
+                        if (count_of[k] && code >= first_of[k] && code - first_of[k] < count_of[k]) {
+                            symbol = start_of[k] + code - first_of[k];
+                            used_bits = (uint32_t)k;
+                        }
+                    }
+                    if (used_bits > (uint32_t)kFastBits) symbol = sorted[symbol & 0xffu];
+                }
+                buf <<= used_bits;
+                have -= used_bits;
+                four |= symbol << (8 * b);
             }
-            buf <<= used_bits;
-            have -= used_bits;
-            four |= symbol << (8 * b);
+            sixteen[q] = four;
         }
-        if (i + 4 <= valid) {
-            *reinterpret_cast<uint32_t*>(dst + i) = four;     // out is 4-byte aligned, chunks are 256 bytes
+        if (i + 16 <= valid) {
+            *reinterpret_cast<u32x4*>(dst + i) = u32x4{sixteen[0], sixteen[1], sixteen[2], sixteen[3]};   // out is 16-byte aligned
         } else {
-            for (uint32_t b = 0; i + b < valid; ++b) dst[i + b] = (uint8_t)(four >> (8 * b));
+            for (uint32_t b = 0; i + b < valid; ++b) dst[i + b] = (uint8_t)(sixteen[b >> 2] >> (8 * (b & 3u)));
         }
     }
 }
