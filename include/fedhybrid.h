@@ -253,7 +253,7 @@ int32_t   fh_mixed_batch_capacity(void);
  *     the index stream gets the block's code bytes row-major.  Restoring returns outliers
  *     unchanged and (float)q * (2 eps) otherwise (rounded to bf16 for bf16 maps), i.e. within
  *     eps of the input up to two roundings.  eps <= 0 or NaN means verbatim.  The Huffman stage
- *     the paper puts after this is not part of the library.
+ *     the paper puts after this is a call of its own on the index stream: fh_huffman_encode.
  *
  * All pointers are device pointers; x, values, out 4-byte aligned, totals and workspace 8-byte
  * aligned.  Stream sizes depend on the data, so the encoder wants room for the worst case:

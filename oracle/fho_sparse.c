@@ -59,7 +59,8 @@
  *   restore   row-major: a code byte 0 takes the next outlier, returns it unchanged and
  *             re-derives its q as above; any other code gives q = p + code - 128 and returns
  *             (float)q * two_eps (rounded to bf16, nearest even, for bf16 maps).
- *   Huffman coding of the code bytes, which the paper applies last, is not done.
+ *   Huffman coding of the code bytes, which the paper applies last, is a separate step on the
+ *   index stream (fho_huffman.c).
  */
 #include "fho.h"
 

@@ -34,6 +34,7 @@ constexpr int kMaxLen = 24;
 constexpr int kChunkWordsMax = kChunk * kMaxLen / 32;
 constexpr int kHistCopies = 8;
 constexpr int kFastBits = 12;
+constexpr int kStageWords = 13312;                 // decode: LDS for a workgroup's payload slice (256 chunks of 52 words)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -332,6 +333,58 @@ __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Layout la
     if (filled && written < words) out[written] = (uint32_t)(acc << (32u - filled));   // zero-padded to a whole word
 }
 
+// One chunk: `valid` symbols from the words next_word(0), next_word(1), ... to dst (16-byte aligned).
+template <typename NextWord>
+__device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const uint16_t* fast, const uint8_t* sorted,
+                                             const uint32_t (&count_of)[kMaxLen + 1], const uint32_t (&first_of)[kMaxLen + 1],
+                                             const uint32_t (&start_of)[kMaxLen + 1], NextWord next_word)
+{
+    uint32_t taken = 0;                                       // words moved into `buf`
+    uint64_t buf = 0;                                         // pending bits, the next one on top
+    uint32_t have = 0;
+    for (uint32_t i = 0; i < valid; i += 16) {
+        uint32_t sixteen[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t four = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (have <= 32u) {
+                    const uint32_t w = next_word(taken);
+                    ++taken;
+                    buf |= (uint64_t)w << (32u - have);
+                    have += 32u;
+                }
+                uint32_t symbol = 0, used_bits = 1;
+                const uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
+                if (e) {
+                    symbol = e & 0xffu;
+                    used_bits = e >> 8;
+                } else {
+#pragma unroll
+                    for (int k = kMaxLen; k > kFastBits; --k) {       // no LDS until the length is known
+                        const uint32_t code = (uint32_t)(buf >> (64 - k));
+                        if (count_of[k] && code >= first_of[k] && code - first_of[k] < count_of[k]) {
+                            symbol = start_of[k] + code - first_of[k];
+                            used_bits = (uint32_t)k;
+                        }
+                    }
+                    if (used_bits > (uint32_t)kFastBits) symbol = sorted[symbol & 0xffu];
+                }
+                buf <<= used_bits;
+                have -= used_bits;
+                four |= symbol << (8 * b);
+            }
+            sixteen[q] = four;
+        }
+        if (i + 16 <= valid) {
+            *reinterpret_cast<u32x4*>(dst + i) = u32x4{sixteen[0], sixteen[1], sixteen[2], sixteen[3]};
+        } else {
+            for (uint32_t b = 0; i + b < valid; ++b) dst[i + b] = (uint8_t)(sixteen[b >> 2] >> (8 * (b & 3u)));
+        }
+    }
+}
+
 // ---- decode -------------------------------------------------------------------------------------------
 // The stream may be foreign: the tables are built from whatever the 256 length bytes say
 // (lengths above 24 count as unused), reads of payload words are bounded by the stream's size
@@ -346,7 +399,7 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const uint8_t*
     __shared__ uint8_t  sorted[256];                          // symbols by (length, symbol)
     __shared__ uint32_t per_length[kMaxLen + 2], first[kMaxLen + 2], start[kMaxLen + 2];
     __shared__ uint16_t fast[1 << kFastBits];                 // next kFastBits bits -> symbol | length << 8; 0: longer code
-    __shared__ uint32_t ring[8 * kThreads];
+    __shared__ uint32_t stage[kStageWords];                   // the workgroup's slice of the payload, or the rings
     const uint32_t s = threadIdx.x;
     {
         const uint32_t l = len_in[s];
@@ -388,73 +441,50 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const uint8_t*
     }
     __syncthreads();
 
-    const uint32_t chunk = blockIdx.x * kThreads + threadIdx.x;
-    if (chunk >= chunks) return;
+    // The payload words of the workgroup's 256 chunks are one contiguous slice.  When it fits it
+    // is brought into LDS with contiguous loads and the threads read their words from there
+    // (a thread walking its chunk in memory would fetch a cache line per word); a longer slice,
+    // or offsets that do not describe one, go through per-thread rings instead.
+    const uint32_t chunk0 = blockIdx.x * kThreads;
+    const uint32_t chunk1 = chunk0 + kThreads < chunks ? chunk0 + kThreads : chunks;
+    const uint32_t slice_at = offsets[chunk0], slice_end = offsets[chunk1];
+    const bool staged = slice_end >= slice_at && slice_end - slice_at <= (uint32_t)kStageWords && slice_end <= payload_words;
+    const uint32_t chunk = chunk0 + threadIdx.x;
+    const bool live = chunk < chunks;
     const uint64_t base = (uint64_t)chunk * kChunk;
-    const uint32_t valid = n - base < (uint64_t)kChunk ? (uint32_t)(n - base) : (uint32_t)kChunk;
-    // The chunk's words come through a ring of eight in LDS: when four have been consumed, the
-    // four loaded at the previous refill take their place and the next four are requested, so a
-    // load has the time of four words' decoding to arrive.
-    uint32_t* mine = ring + threadIdx.x;                      // word k of the ring at mine[(k & 7) * kThreads]
-    const uint32_t first_word = offsets[chunk];
+    const uint32_t valid = !live ? 0u : n - base < (uint64_t)kChunk ? (uint32_t)(n - base) : (uint32_t)kChunk;
+    const uint32_t first_word = live ? offsets[chunk] : 0u;
+    uint8_t* dst = out + base;
+    if (staged) {                                             // workgroup-uniform
+        const uint32_t slice_words = slice_end - slice_at;
+        for (uint32_t i = threadIdx.x; i < slice_words; i += kThreads) stage[i] = payload[slice_at + i];
+        __syncthreads();
+        const uint32_t at = first_word - slice_at;            // anything at all for a foreign stream: reads are bounded
+        decode_chunk(valid, dst, fast, sorted, count_of, first_of, start_of,
+                     [&](uint32_t k) { return at + k < slice_words ? stage[at + k] : 0u; });
+        return;
+    }
+    if (!live) return;
+    // a ring of eight words per thread: when four have been consumed, the four loaded at the
+    // previous refill take their place and the next four are requested, so a load has the time
+    // of four words' decoding to arrive
+    uint32_t* mine = stage + threadIdx.x;                     // word k of the ring at mine[(k & 7) * kThreads]
     uint32_t pending[4];
 #pragma unroll
     for (int k = 0; k < 8; ++k) mine[k * kThreads] = first_word + k < payload_words ? payload[first_word + k] : 0u;
 #pragma unroll
     for (int k = 0; k < 4; ++k) pending[k] = first_word + 8 + k < payload_words ? payload[first_word + 8 + k] : 0u;
-    uint32_t taken = 0;                                       // words moved from the ring into `buf`
-    uint64_t buf = 0;                                         // pending bits, the next one on top
-    uint32_t have = 0;
-    uint8_t* dst = out + base;
-    for (uint32_t i = 0; i < valid; i += 16) {
-        uint32_t sixteen[4];
+    decode_chunk(valid, dst, fast, sorted, count_of, first_of, start_of, [&](uint32_t taken) {
+        if ((taken & 3u) == 0u && taken != 0u) {              // a block of four used up: refill the half of the ring just freed
+            const uint32_t slot = (taken + 4u) & 7u;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            uint32_t four = 0;
+            for (int k = 0; k < 4; ++k) mine[((slot + k) & 7u) * kThreads] = pending[k];
+            const uint32_t at = first_word + taken + 8u;
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (have <= 32u) {
-                    if ((taken & 3u) == 0u && taken != 0u) {  // a block of four used up: refill the half of the ring just freed
-                        const uint32_t slot = (taken + 4u) & 7u;
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) mine[((slot + k) & 7u) * kThreads] = pending[k];
-                        const uint32_t at = first_word + taken + 8u;
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) pending[k] = at + k < payload_words ? payload[at + k] : 0u;
-                    }
-                    const uint32_t w = mine[(taken & 7u) * kThreads];
-                    ++taken;
-                    buf |= (uint64_t)w << (32u - have);
-                    have += 32u;
-                }
-                uint32_t symbol = 0, used_bits = 1;
-                const uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
-                if (e) {
-                    symbol = e & 0xffu;
-                    used_bits = e >> 8;
-                } else {
-#pragma unroll
-                    for (int k = kMaxLen; k > kFastBits; --k) {       // no LDS until the length is known
-                        const uint32_t code = (uint32_t)(buf >> (64 - k));
-                        if (count_of[k] && code >= first_of[k] && code - first_of[k] < count_of[k]) {
-                            symbol = start_of[k] + code - first_of[k];
-                            used_bits = (uint32_t)k;
-                        }
-                    }
-                    if (used_bits > (uint32_t)kFastBits) symbol = sorted[symbol & 0xffu];
-                }
-                buf <<= used_bits;
-                have -= used_bits;
-                four |= symbol << (8 * b);
-            }
-            sixteen[q] = four;
+            for (int k = 0; k < 4; ++k) pending[k] = at + k < payload_words ? payload[at + k] : 0u;
         }
-        if (i + 16 <= valid) {
-            *reinterpret_cast<u32x4*>(dst + i) = u32x4{sixteen[0], sixteen[1], sixteen[2], sixteen[3]};   // out is 16-byte aligned
-        } else {
-            for (uint32_t b = 0; i + b < valid; ++b) dst[i + b] = (uint8_t)(sixteen[b >> 2] >> (8 * (b & 3u)));
-        }
-    }
+        return mine[(taken & 7u) * kThreads];
+    });
 }
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
