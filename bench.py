@@ -376,15 +376,26 @@ def bench_huffman(args, api, W, dev) -> int:
           file=sys.stderr, flush=True)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
+    batch = api.HuffmanBatch([j[0] for j in jobs])
+    api.fh_huffman_encode_batch(batch, stream)
+    torch.cuda.synchronize()
+    batch.refresh()                                           # stream sizes (fixed: the input is)
+
     def step(timed=False):
         if timed:
             ev[0].record(stream)
-        for data, ni, out, totals, ws, used, back in jobs:
-            api.fh_huffman_encode(data, stream_out=out, totals=totals, workspace=ws, stream=stream)
+        if args.per_tensor:
+            for data, ni, out, totals, ws, used, back in jobs:
+                api.fh_huffman_encode(data, stream_out=out, totals=totals, workspace=ws, stream=stream)
+        else:
+            api.fh_huffman_encode_batch(batch, stream)
         if timed:
             ev[1].record(stream)
-        for data, ni, out, totals, ws, used, back in jobs:
-            api.fh_huffman_decode(out[:used], ni, out=back, stream=stream)
+        if args.per_tensor:
+            for data, ni, out, totals, ws, used, back in jobs:
+                api.fh_huffman_decode(out[:used], ni, out=back, stream=stream)
+        else:
+            api.fh_huffman_decode_batch(batch, stream)
         if timed:
             ev[2].record(stream)
 
@@ -402,8 +413,8 @@ def bench_huffman(args, api, W, dev) -> int:
         torch.cuda.synchronize()
         ms_e += ev[0].elapsed_time(ev[1]) / args.steps
         ms_d += ev[1].elapsed_time(ev[2]) / args.steps
-    for data, ni, out, totals, ws, used, back in jobs:
-        if not torch.equal(back, data):
+    for k, (data, ni, out, totals, ws, used, back) in enumerate(jobs):
+        if not torch.equal(back if args.per_tensor else batch.out[k], data):
             print("bench.py: the Huffman round trip did not restore its input", file=sys.stderr)
             return 1
     alg_e = 3 * nbytes + stored                               # histogram, count and write passes read the bytes
@@ -416,7 +427,8 @@ def bench_huffman(args, api, W, dev) -> int:
         "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"huffman_index_streams_mobilenetv2_b64_kept_channels_n4_tau0.5_eps{eps:g}_x{args.maps_scale}",
                    "streams": len(jobs), "input_bytes": nbytes, "stored_bytes": stored,
-                   "entry_point": "fh_huffman_encode + fh_huffman_decode (per stream)"},
+                   "entry_point": ("fh_huffman_encode + fh_huffman_decode (per stream)" if args.per_tensor
+                                   else "fh_huffman_encode_batch + fh_huffman_decode_batch")},
         "roofline": {"bound": "hbm", "kernel": dom[0] + ", all launches of a step, event-timed",
                      "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},

@@ -349,6 +349,25 @@ fh_status fh_huffman_encode(const void *bytes, uint64_t n, void *stream_out, siz
 fh_status fh_huffman_decode(const void *stream_in, size_t stream_bytes, uint64_t n, void *out, size_t out_cap,
                             void *stream);
 
+/* The same two calls for several byte buffers: every pass is launched once per run of up to
+ * fh_huffman_batch_capacity() items (the code construction, a single workgroup's work per
+ * buffer, then runs for all of them side by side).  Everything is checked before the first
+ * launch; results identical to the single calls. */
+typedef struct fh_huffman_encode_item {
+    const void *bytes;      uint64_t n;
+    void       *stream_out; size_t stream_cap;
+    void       *totals;
+    void       *workspace;  size_t workspace_cap;
+} fh_huffman_encode_item;
+typedef struct fh_huffman_decode_item {
+    const void *stream_in;  size_t stream_bytes;
+    uint64_t    n;
+    void       *out;        size_t out_cap;
+} fh_huffman_decode_item;
+fh_status fh_huffman_encode_batch(const fh_huffman_encode_item *items, int32_t count, void *stream);
+fh_status fh_huffman_decode_batch(const fh_huffman_decode_item *items, int32_t count, void *stream);
+int32_t   fh_huffman_batch_capacity(void);
+
 const char *fh_status_string(fh_status s);
 
 #ifdef __cplusplus

@@ -37,6 +37,7 @@ EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "
            "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
            "fh_sparse_decode", "fh_sparse_encode_batch", "fh_sparse_decode_batch", "fh_sparse_batch_capacity",
            "fh_huffman_stream_bytes", "fh_huffman_workspace_bytes", "fh_huffman_encode", "fh_huffman_decode",
+           "fh_huffman_encode_batch", "fh_huffman_decode_batch", "fh_huffman_batch_capacity",
            "fh_status_string")
 
 
@@ -173,6 +174,26 @@ _lib.fh_huffman_decode.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_ui
 _lib.fh_huffman_decode.restype = ctypes.c_int
 _lib.fh_status_string.argtypes = [ctypes.c_int]
 _lib.fh_status_string.restype = ctypes.c_char_p
+
+
+class fh_huffman_encode_item(ctypes.Structure):
+    _fields_ = [("bytes", ctypes.c_void_p), ("n", ctypes.c_uint64),
+                ("stream_out", ctypes.c_void_p), ("stream_cap", ctypes.c_size_t),
+                ("totals", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t)]
+
+
+class fh_huffman_decode_item(ctypes.Structure):
+    _fields_ = [("stream_in", ctypes.c_void_p), ("stream_bytes", ctypes.c_size_t), ("n", ctypes.c_uint64),
+                ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t)]
+
+
+_lib.fh_huffman_encode_batch.argtypes = [_P(fh_huffman_encode_item), ctypes.c_int32, ctypes.c_void_p]
+_lib.fh_huffman_encode_batch.restype = ctypes.c_int
+_lib.fh_huffman_decode_batch.argtypes = [_P(fh_huffman_decode_item), ctypes.c_int32, ctypes.c_void_p]
+_lib.fh_huffman_decode_batch.restype = ctypes.c_int
+_lib.fh_huffman_batch_capacity.argtypes = []
+_lib.fh_huffman_batch_capacity.restype = ctypes.c_int32
 
 
 class FedHybridError(RuntimeError):
@@ -595,6 +616,60 @@ def fh_huffman_decode(stream_in: torch.Tensor, n: int, out: Optional[torch.Tenso
         _check(_lib.fh_huffman_decode(_ptr(stream_in), _nbytes(stream_in), n, _ptr(out), _nbytes(out),
                                       _stream_ptr(stream)))
     return out
+
+
+def huffman_batch_capacity() -> int:
+    return int(_lib.fh_huffman_batch_capacity())
+
+
+class HuffmanBatch:
+    """Several byte buffers coded with one call each way.  `data`: device uint8 tensors; the
+    worst-case sized streams, the totals (int64[2] each: stream bytes in use, payload bits) and
+    the scratch are allocated here once.  After an encode has finished, `refresh()` reads the
+    totals back (a synchronising copy) so that decode is given the valid prefixes."""
+
+    def __init__(self, data):
+        self.data = list(data)
+        for d in self.data:
+            _device_tensor(d, "data")
+            if d.dtype != torch.uint8:
+                raise ValueError("data must be uint8")
+        self.device = self.data[0].device if self.data else None
+        self.count = len(self.data)
+        self.streams = [torch.empty(huffman_stream_bytes(d.numel()), dtype=torch.uint8, device=d.device) for d in self.data]
+        self.totals = torch.zeros((max(self.count, 1), 2), dtype=torch.int64, device=self.device)
+        self.workspaces = [torch.empty(huffman_workspace_bytes(d.numel()), dtype=torch.uint8, device=d.device)
+                           for d in self.data]
+        self.out = [torch.empty(d.numel(), dtype=torch.uint8, device=d.device) for d in self.data]
+        self.enc = (fh_huffman_encode_item * max(self.count, 1))()
+        self.dec = (fh_huffman_decode_item * max(self.count, 1))()
+        for i, d in enumerate(self.data):
+            e = self.enc[i]
+            e.bytes, e.n = _ptr(d), d.numel()
+            e.stream_out, e.stream_cap = self.streams[i].data_ptr(), _nbytes(self.streams[i])
+            e.totals = self.totals[i].data_ptr()
+            e.workspace, e.workspace_cap = self.workspaces[i].data_ptr(), _nbytes(self.workspaces[i])
+            q = self.dec[i]
+            q.stream_in, q.stream_bytes, q.n = self.streams[i].data_ptr(), _nbytes(self.streams[i]), d.numel()
+            q.out, q.out_cap = _ptr(self.out[i]), _nbytes(self.out[i])
+
+    def refresh(self):
+        used = self.totals.cpu()[:, 0].tolist()
+        for i in range(self.count):
+            self.dec[i].stream_bytes = int(used[i])
+        return used[: self.count]
+
+
+def fh_huffman_encode_batch(batch: HuffmanBatch, stream=None) -> None:
+    if batch.count:
+        with torch.cuda.device(batch.device):
+            _check(_lib.fh_huffman_encode_batch(batch.enc, batch.count, _stream_ptr(stream)))
+
+
+def fh_huffman_decode_batch(batch: HuffmanBatch, stream=None) -> None:
+    if batch.count:
+        with torch.cuda.device(batch.device):
+            _check(_lib.fh_huffman_decode_batch(batch.dec, batch.count, _stream_ptr(stream)))
 
 
 @dataclass

@@ -23,6 +23,7 @@
 // Everything here is integer work; results do not depend on launch geometry.
 #include "../../include/fedhybrid.h"
 
+#include "fh_batch.hpp"
 #include "fh_scan.hpp"
 
 namespace fh {
@@ -49,20 +50,35 @@ struct Layout {                                    // where things are in the st
     const uint8_t* in;
     uint64_t  n;
     uint32_t  chunks, groups;
+    uint32_t  hist_blocks;                         // workgroups of the histogram pass
 };
 
-__global__ __launch_bounds__(256) void huffman_clear_kernel(uint32_t* hist) { hist[threadIdx.x] = 0u; }
+struct DecodeJob {
+    const uint8_t*  len;
+    const uint32_t* offsets;
+    const uint32_t* payload;
+    uint8_t*        out;
+    uint64_t        n;
+    uint32_t        payload_words, chunks;
+};
+
+// Every pass serves up to kBatch streams (fh_batch.hpp); the per-stream passes take a workgroup per stream.
+__global__ __launch_bounds__(256) void huffman_clear_kernel(const Batch<Layout> batch) { batch.item[blockIdx.x].hist[threadIdx.x] = 0u; }
 
 // ---- histogram ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void huffman_histogram_kernel(const uint8_t* __restrict__ in, uint64_t n,
-                                                                uint32_t* __restrict__ hist)
+__global__ __launch_bounds__(256) void huffman_histogram_kernel(const Batch<Layout> batch)
 {
+    uint32_t block;
+    const Layout& lay = batch.item[batch_item(batch, blockIdx.x, block)];
+    const uint8_t* in = lay.in;
+    const uint64_t n = lay.n;
+    uint32_t* hist = lay.hist;
     __shared__ uint32_t local[kHistCopies][256];
     for (int i = threadIdx.x; i < kHistCopies * 256; i += 256) (&local[0][0])[i] = 0u;
     __syncthreads();
     uint32_t* mine = local[threadIdx.x & (kHistCopies - 1)];
     const uint64_t vectors = n >> 4;                          // `in` is 16-byte aligned
-    for (uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x; v < vectors; v += (uint64_t)gridDim.x * 256) {
+    for (uint64_t v = (uint64_t)block * 256 + threadIdx.x; v < vectors; v += (uint64_t)lay.hist_blocks * 256) {
         const u32x4 w = reinterpret_cast<const u32x4*>(in)[v];
         const uint32_t word[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
@@ -70,7 +86,7 @@ __global__ __launch_bounds__(256) void huffman_histogram_kernel(const uint8_t* _
 #pragma unroll
             for (int b = 0; b < 4; ++b) atomicAdd(&mine[(word[k] >> (8 * b)) & 0xffu], 1u);
     }
-    if (blockIdx.x == 0) {                                    // the bytes after the last whole vector
+    if (block == 0) {                                         // the bytes after the last whole vector
         const uint64_t i = (vectors << 4) + threadIdx.x;
         if (threadIdx.x < 16 && i < n) atomicAdd(&mine[in[i]], 1u);
     }
@@ -83,8 +99,9 @@ __global__ __launch_bounds__(256) void huffman_histogram_kernel(const uint8_t* _
 
 // ---- code lengths and canonical codes ---------------------------------------------------------------
 // One workgroup of 256 threads, thread s = symbol s.
-__global__ __launch_bounds__(256) void huffman_code_kernel(const Layout lay)
+__global__ __launch_bounds__(256) void huffman_code_kernel(const Batch<Layout> batch)
 {
+    const Layout& lay = batch.item[blockIdx.x];
     __shared__ uint64_t count[256];                           // this round's counts, by symbol
     __shared__ uint64_t weight[511];                          // leaves in rank order, then internal nodes as made
     __shared__ uint16_t parent[511];
@@ -225,13 +242,15 @@ __device__ __forceinline__ uint32_t workgroup_exclusive_scan(uint32_t mine, uint
 }
 
 // ---- count: words per chunk, sums per group -------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Layout lay)
+__global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Batch<Layout> batch)
 {
+    uint32_t group;
+    const Layout& lay = batch.item[batch_item(batch, blockIdx.x, group)];
     __shared__ uint8_t len[256];
     __shared__ uint32_t lds[4];
     len[threadIdx.x] = (uint8_t)(lay.table[threadIdx.x] & 0xffu);
     __syncthreads();
-    const uint32_t chunk = blockIdx.x * kThreads + threadIdx.x;
+    const uint32_t chunk = group * kThreads + threadIdx.x;
     uint32_t words = 0;
     if (chunk < lay.chunks) {
         const uint64_t first = (uint64_t)chunk * kChunk;
@@ -266,12 +285,13 @@ __global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Layout la
     }
     uint32_t total;
     workgroup_exclusive_scan(words, lds, &total);
-    if (threadIdx.x == 0) lay.group_sums[blockIdx.x] = total;
+    if (threadIdx.x == 0) lay.group_sums[group] = total;
 }
 
 // ---- scan of the group sums (in place, exclusive); the stream's size --------------------------------
-__global__ __launch_bounds__(kThreads) void huffman_scan_kernel(const Layout lay)
+__global__ __launch_bounds__(kThreads) void huffman_scan_kernel(const Batch<Layout> batch)
 {
+    const Layout& lay = batch.item[blockIdx.x];
     __shared__ uint32_t lds[4];
     uint32_t carry = 0;
     for (uint32_t base = 0; base < lay.groups; base += kThreads) {         // workgroup-uniform trip count
@@ -289,16 +309,18 @@ __global__ __launch_bounds__(kThreads) void huffman_scan_kernel(const Layout lay
 }
 
 // ---- write: offsets and payload -------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Layout lay)
+__global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Layout> batch)
 {
+    uint32_t group;
+    const Layout& lay = batch.item[batch_item(batch, blockIdx.x, group)];
     __shared__ uint32_t table[256];
     __shared__ uint32_t lds[4];
     table[threadIdx.x] = lay.table[threadIdx.x];
-    const uint32_t chunk = blockIdx.x * kThreads + threadIdx.x;
+    const uint32_t chunk = group * kThreads + threadIdx.x;
     const bool live = chunk < lay.chunks;
     const uint32_t words = live ? lay.offsets[chunk] : 0u;
     uint32_t total;
-    const uint32_t offset = lay.group_sums[blockIdx.x] + workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
+    const uint32_t offset = lay.group_sums[group] + workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
     if (!live) return;
     lay.offsets[chunk] = offset;
     const uint64_t first = (uint64_t)chunk * kChunk;
@@ -389,12 +411,16 @@ __device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const
 // The stream may be foreign: the tables are built from whatever the 256 length bytes say
 // (lengths above 24 count as unused), reads of payload words are bounded by the stream's size
 // (words outside read as zero), and every loop is bounded by the symbol count.
-__global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const uint8_t* __restrict__ len_in,
-                                                                  const uint32_t* __restrict__ offsets,
-                                                                  const uint32_t* __restrict__ payload,
-                                                                  uint32_t payload_words, uint64_t n, uint32_t chunks,
-                                                                  uint8_t* __restrict__ out)
+__global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<DecodeJob> batch)
 {
+    uint32_t group;
+    const DecodeJob& job = batch.item[batch_item(batch, blockIdx.x, group)];
+    const uint8_t* len_in = job.len;
+    const uint32_t* offsets = job.offsets;
+    const uint32_t* payload = job.payload;
+    const uint32_t payload_words = job.payload_words, chunks = job.chunks;
+    const uint64_t n = job.n;
+    uint8_t* out = job.out;
     __shared__ uint8_t  len[256];
     __shared__ uint8_t  sorted[256];                          // symbols by (length, symbol)
     __shared__ uint32_t per_length[kMaxLen + 2], first[kMaxLen + 2], start[kMaxLen + 2];
@@ -445,7 +471,7 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const uint8_t*
     // is brought into LDS with contiguous loads and the threads read their words from there
     // (a thread walking its chunk in memory would fetch a cache line per word); a longer slice,
     // or offsets that do not describe one, go through per-thread rings instead.
-    const uint32_t chunk0 = blockIdx.x * kThreads;
+    const uint32_t chunk0 = group * kThreads;
     const uint32_t chunk1 = chunk0 + kThreads < chunks ? chunk0 + kThreads : chunks;
     const uint32_t slice_at = offsets[chunk0], slice_end = offsets[chunk1];
     const bool staged = slice_end >= slice_at && slice_end - slice_at <= (uint32_t)kStageWords && slice_end <= payload_words;
@@ -509,60 +535,153 @@ size_t fh_huffman_workspace_bytes(uint64_t n)
     return (size_t)(4u * (256u + 256u + (fh::groups_of(n) > 0 ? fh::groups_of(n) : 1u)));
 }
 
+int32_t fh_huffman_batch_capacity(void) { return fh::kBatch; }
+
+}  // extern "C"
+
+namespace {
+
+using namespace fh;
+
+fh_status check_encode(const fh_huffman_encode_item& it)
+{
+    if (it.n > kMaxSymbols) return FH_ERR_BAD_NUMEL;
+    if (!it.stream_out || !it.totals || !it.workspace || (it.n > 0 && !it.bytes)) return FH_ERR_NULL;
+    if (!aligned(it.bytes, 16) || !aligned(it.stream_out, 16) || !aligned(it.totals, 8) || !aligned(it.workspace, 16))
+        return FH_ERR_ALIGNMENT;
+    if (it.stream_cap < fh_huffman_stream_bytes(it.n) || it.workspace_cap < fh_huffman_workspace_bytes(it.n))
+        return FH_ERR_BUFFER_TOO_SMALL;
+    return FH_OK;
+}
+
+fh_status check_decode(const fh_huffman_decode_item& it)
+{
+    if (it.n > kMaxSymbols) return FH_ERR_BAD_NUMEL;
+    if (it.n == 0) return FH_OK;
+    if (!it.stream_in || !it.out) return FH_ERR_NULL;
+    if (!aligned(it.stream_in, 16) || !aligned(it.out, 16)) return FH_ERR_ALIGNMENT;
+    if (it.out_cap < it.n) return FH_ERR_BUFFER_TOO_SMALL;
+    if (it.stream_bytes < 256u + 4u * (chunks_of(it.n) + 1u)) return FH_ERR_BUFFER_TOO_SMALL;   // not even the lengths and the offsets
+    return FH_OK;
+}
+
+template <typename Kernel, typename Item>
+void launch(Kernel kernel, const Batch<Item>& b, uint32_t grid, hipStream_t s)
+{
+    if (grid > 0) hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, s, b);
+}
+
+}  // namespace
+
+extern "C" {
+
+fh_status fh_huffman_encode_batch(const fh_huffman_encode_item* items, int32_t count, void* stream)
+{
+    if (count < 0) return FH_ERR_BAD_COUNT;
+    if (count > 0 && !items) return FH_ERR_NULL;
+    for (int32_t i = 0; i < count; ++i) {                     // everything is checked before the first launch
+        const fh_status st = check_encode(items[i]);
+        if (st != FH_OK) return st;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int32_t i = 0; i < count;) {
+        // the same streams three times: a workgroup each | by histogram workgroups | by groups of chunks
+        Batch<Layout> each, hist, grouped;
+        reset(each); reset(hist); reset(grouped);
+        while (i < count && each.count < kBatch) {
+            const fh_huffman_encode_item& it = items[i];
+            Layout lay;
+            lay.chunks = (uint32_t)chunks_of(it.n);
+            lay.groups = (uint32_t)groups_of(it.n);
+            lay.len = static_cast<uint8_t*>(it.stream_out);
+            lay.offsets = reinterpret_cast<uint32_t*>(lay.len + 256);
+            lay.payload = lay.offsets + lay.chunks + 1;
+            lay.hist = static_cast<uint32_t*>(it.workspace);
+            lay.table = lay.hist + 256;
+            lay.group_sums = lay.table + 256;
+            lay.totals = static_cast<uint64_t*>(it.totals);
+            lay.in = static_cast<const uint8_t*>(it.bytes);
+            lay.n = it.n;
+            const uint64_t want = it.n == 0 ? 0 : (it.n / 16 + 255) / 256 / 8 + 1;     // about eight vectors per thread
+            lay.hist_blocks = (uint32_t)(want < 4096 ? want : 4096);
+            if ((uint64_t)grouped.block_start[grouped.count] + lay.groups > (uint64_t)INT_MAX) {
+                if (each.count == 0) return FH_ERR_BAD_NUMEL;
+                break;
+            }
+            push(each, lay, 1);
+            push(hist, lay, lay.hist_blocks);
+            push(grouped, lay, lay.groups);
+            ++i;
+        }
+        seal(each); seal(hist); seal(grouped);
+        launch(huffman_clear_kernel, each, (uint32_t)each.count, s);
+        launch(huffman_histogram_kernel, hist, hist.block_start[hist.count], s);
+        launch(huffman_code_kernel, each, (uint32_t)each.count, s);
+        launch(huffman_count_kernel, grouped, grouped.block_start[grouped.count], s);
+        launch(huffman_scan_kernel, each, (uint32_t)each.count, s);
+        launch(huffman_write_kernel, grouped, grouped.block_start[grouped.count], s);
+    }
+    if (count == 0) return FH_OK;
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t count, void* stream)
+{
+    if (count < 0) return FH_ERR_BAD_COUNT;
+    if (count > 0 && !items) return FH_ERR_NULL;
+    for (int32_t i = 0; i < count; ++i) {
+        const fh_status st = check_decode(items[i]);
+        if (st != FH_OK) return st;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    bool launched = false;
+    for (int32_t i = 0; i < count;) {
+        Batch<DecodeJob> b;
+        reset(b);
+        while (i < count && b.count < kBatch) {
+            const fh_huffman_decode_item& it = items[i];
+            if (it.n == 0) { ++i; continue; }                 // nothing to restore
+            const uint64_t chunks = chunks_of(it.n);
+            const uint64_t words = (it.stream_bytes - (256u + 4u * (chunks + 1u))) / 4u;
+            DecodeJob job;
+            job.len = static_cast<const uint8_t*>(it.stream_in);
+            job.offsets = reinterpret_cast<const uint32_t*>(job.len + 256);
+            job.payload = job.offsets + chunks + 1;
+            job.out = static_cast<uint8_t*>(it.out);
+            job.n = it.n;
+            job.payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
+            job.chunks = (uint32_t)chunks;
+            if (!push(b, job, (int64_t)groups_of(it.n))) {
+                if (b.count == 0) return FH_ERR_BAD_NUMEL;
+                break;
+            }
+            ++i;
+        }
+        seal(b);
+        if (b.count > 0) {
+            launch(huffman_decode_kernel, b, b.block_start[b.count], s);
+            launched = true;
+        }
+    }
+    if (!launched) return FH_OK;
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
 fh_status fh_huffman_encode(const void* bytes, uint64_t n, void* stream_out, size_t stream_cap, void* totals,
                             void* workspace, size_t workspace_cap, void* stream)
 {
-    using namespace fh;
-    if (n > kMaxSymbols) return FH_ERR_BAD_NUMEL;
-    if (!stream_out || !totals || !workspace || (n > 0 && !bytes)) return FH_ERR_NULL;
-    if (!aligned(bytes, 16) || !aligned(stream_out, 16) || !aligned(totals, 8) || !aligned(workspace, 16)) return FH_ERR_ALIGNMENT;
-    if (stream_cap < fh_huffman_stream_bytes(n) || workspace_cap < fh_huffman_workspace_bytes(n)) return FH_ERR_BUFFER_TOO_SMALL;
-    Layout lay;
-    lay.chunks = (uint32_t)chunks_of(n);
-    lay.groups = (uint32_t)groups_of(n);
-    lay.len = static_cast<uint8_t*>(stream_out);
-    lay.offsets = reinterpret_cast<uint32_t*>(lay.len + 256);
-    lay.payload = lay.offsets + lay.chunks + 1;
-    lay.hist = static_cast<uint32_t*>(workspace);
-    lay.table = lay.hist + 256;
-    lay.group_sums = lay.table + 256;
-    lay.totals = static_cast<uint64_t*>(totals);
-    lay.in = static_cast<const uint8_t*>(bytes);
-    lay.n = n;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(huffman_clear_kernel, dim3(1), dim3(256), 0, s, lay.hist);
-    if (n > 0) {
-        const uint64_t want = (n / 16 + 255) / 256 / 8 + 1;   // about eight vectors per thread
-        const uint32_t grid = (uint32_t)(want < 4096 ? want : 4096);
-        hipLaunchKernelGGL(huffman_histogram_kernel, dim3(grid), dim3(256), 0, s, lay.in, n, lay.hist);
-    }
-    hipLaunchKernelGGL(huffman_code_kernel, dim3(1), dim3(256), 0, s, lay);
-    if (lay.groups > 0) hipLaunchKernelGGL(huffman_count_kernel, dim3(lay.groups), dim3(kThreads), 0, s, lay);
-    hipLaunchKernelGGL(huffman_scan_kernel, dim3(1), dim3(kThreads), 0, s, lay);
-    if (lay.groups > 0) hipLaunchKernelGGL(huffman_write_kernel, dim3(lay.groups), dim3(kThreads), 0, s, lay);
-    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+    fh_huffman_encode_item it;
+    it.bytes = bytes; it.n = n; it.stream_out = stream_out; it.stream_cap = stream_cap; it.totals = totals;
+    it.workspace = workspace; it.workspace_cap = workspace_cap;
+    return fh_huffman_encode_batch(&it, 1, stream);
 }
 
 fh_status fh_huffman_decode(const void* stream_in, size_t stream_bytes, uint64_t n, void* out, size_t out_cap,
                             void* stream)
 {
-    using namespace fh;
-    if (n > kMaxSymbols) return FH_ERR_BAD_NUMEL;
-    if (n == 0) return FH_OK;
-    if (!stream_in || !out) return FH_ERR_NULL;
-    if (!aligned(stream_in, 16) || !aligned(out, 16)) return FH_ERR_ALIGNMENT;
-    if (out_cap < n) return FH_ERR_BUFFER_TOO_SMALL;
-    const uint64_t chunks = chunks_of(n);
-    const uint64_t header = 256u + 4u * (chunks + 1u);
-    if (stream_bytes < header) return FH_ERR_BUFFER_TOO_SMALL;    // not even the lengths and the offsets
-    const uint64_t words = (stream_bytes - header) / 4u;
-    const uint8_t* base = static_cast<const uint8_t*>(stream_in);
-    const uint32_t* offsets = reinterpret_cast<const uint32_t*>(base + 256);
-    hipLaunchKernelGGL(huffman_decode_kernel, dim3((uint32_t)groups_of(n)), dim3(kThreads), 0,
-                       static_cast<hipStream_t>(stream), base, offsets, offsets + chunks + 1,
-                       (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu), n, (uint32_t)chunks,
-                       static_cast<uint8_t*>(out));
-    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+    fh_huffman_decode_item it;
+    it.stream_in = stream_in; it.stream_bytes = stream_bytes; it.n = n; it.out = out; it.out_cap = out_cap;
+    return fh_huffman_decode_batch(&it, 1, stream);
 }
 
 }  // extern "C"

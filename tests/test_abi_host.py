@@ -330,3 +330,22 @@ def test_huffman_sizes_and_argument_checks():
     assert dec(fake, 1000, 10, fake, 9) == 7
     assert dec(fake, 200, 10, fake, 10) == 7                                    # not even the lengths and the offsets
     assert dec(fake, 1000, 1 << 32, fake, 1 << 33) == 6
+
+
+def test_huffman_item_layouts_and_batch_argument_checks():
+    assert ctypes.sizeof(api.fh_huffman_encode_item) == 56 and ctypes.sizeof(api.fh_huffman_decode_item) == 40
+    assert api.fh_huffman_encode_item.workspace_cap.offset == 48 and api.fh_huffman_decode_item.out.offset == 24
+    lib = api.raw_library()
+    assert api.huffman_batch_capacity() == 16
+    assert lib.fh_huffman_encode_batch(None, 0, None) == 0 and lib.fh_huffman_decode_batch(None, 0, None) == 0
+    assert lib.fh_huffman_encode_batch(None, 2, None) == 1 and lib.fh_huffman_decode_batch(None, -1, None) != 0
+    items = (api.fh_huffman_encode_item * 2)()
+    for it in items:
+        it.bytes = it.stream_out = it.totals = it.workspace = 0x10000
+        it.n, it.stream_cap, it.workspace_cap = 100, 1 << 20, 1 << 20
+    items[1].stream_cap = 10                                   # the second item is bad: nothing may be launched
+    assert lib.fh_huffman_encode_batch(items, 2, None) == 7
+    dec = (api.fh_huffman_decode_item * 1)()
+    dec[0].stream_in = dec[0].out = 0x10000
+    dec[0].n, dec[0].stream_bytes, dec[0].out_cap = 100, 100, 100
+    assert lib.fh_huffman_decode_batch(dec, 1, None) == 7

@@ -136,3 +136,27 @@ def test_buffers_can_be_reused_and_errors_reach_the_caller(api):
         api.fh_huffman_encode(torch.from_numpy(a).cuda(), stream_out=out[:1000], totals=tot, workspace=ws)
     with pytest.raises(api.FedHybridError):
         api.fh_huffman_encode(torch.from_numpy(a).cuda()[1:], stream_out=out, totals=tot, workspace=ws)   # misaligned
+
+
+def test_batched_calls_match_the_oracle_for_every_stream(api):
+    """More streams than one launch holds, an empty one among them, sizes from one symbol to a few groups."""
+    rng = np.random.default_rng(9)
+    sizes = [1, 0, 300, 65536, 200001, 77] + [1000 + 4099 * i for i in range(14)]
+    datas = []
+    for i, n in enumerate(sizes):
+        spread = 1.0 + (i % 5) * 3.0
+        datas.append(np.clip(np.rint(rng.normal(128, spread, n)), 0, 255).astype(np.uint8))
+    assert len(datas) > api.huffman_batch_capacity()
+    dev = [torch.from_numpy(d).cuda() if d.size else torch.empty(0, dtype=torch.uint8, device="cuda") for d in datas]
+    batch = api.HuffmanBatch(dev)
+    api.fh_huffman_encode_batch(batch)
+    torch.cuda.synchronize()
+    used = batch.refresh()
+    api.fh_huffman_decode_batch(batch)
+    torch.cuda.synchronize()
+    totals = batch.totals.cpu().tolist()
+    for i, d in enumerate(datas):
+        want, bits = oracle.huffman_encode(d)
+        assert totals[i] == [want.size, bits], f"stream {i}: totals"
+        assert np.array_equal(batch.streams[i].cpu().numpy()[: used[i]], want), f"stream {i}: bytes"
+        assert np.array_equal(batch.out[i].cpu().numpy(), d), f"stream {i}: decoded"
