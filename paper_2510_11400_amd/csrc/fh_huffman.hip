@@ -33,9 +33,13 @@ constexpr int kChunk = 256;                        // symbols per chunk (= per t
 constexpr int kThreads = 256;                      // chunks per workgroup: a group
 constexpr int kMaxLen = 24;
 constexpr int kChunkWordsMax = kChunk * kMaxLen / 32;
-constexpr int kHistCopies = 8;
+constexpr int kHistCopies = 32;                     // one per LDS bank
 constexpr int kFastBits = 12;
-constexpr int kStageWords = 13312;                 // decode: LDS for a workgroup's payload slice (256 chunks of 52 words)
+constexpr int kDecodeBlocksWanted = 128;            // decode: workgroups a stream is cut into before a workgroup takes several groups
+constexpr int kDecodeGroupsMax = 8;
+constexpr int kBurst = 8;                          // decode: 16-byte output vectors held back and stored together
+constexpr int kWriteStageWords = 12288;            // encode: LDS for a workgroup's payload slice (256 chunks of 48 words)
+constexpr int kStageWords = 13056;                 // decode: LDS for a workgroup's payload slice (256 chunks of 51 words)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -60,6 +64,7 @@ struct DecodeJob {
     uint8_t*        out;
     uint64_t        n;
     uint32_t        payload_words, chunks;
+    uint32_t        groups_per_block;                         // groups of 256 chunks a workgroup decodes with one set of tables
 };
 
 // Every pass serves up to kBatch streams (fh_batch.hpp); the per-stream passes take a workgroup per stream.
@@ -73,27 +78,34 @@ __global__ __launch_bounds__(256) void huffman_histogram_kernel(const Batch<Layo
     const uint8_t* in = lay.in;
     const uint64_t n = lay.n;
     uint32_t* hist = lay.hist;
-    __shared__ uint32_t local[kHistCopies][256];
+    // One copy of the histogram per LDS bank, the copies interleaved so that copy c of every bin lies in bank c:
+    // lane l counts in copy l mod 32, and whatever the bytes are no two lanes of a half-wave meet in a bank
+    // (bytes clustered around one value would otherwise serialise on the few bins they share).
+    __shared__ uint32_t local[256][kHistCopies];
     for (int i = threadIdx.x; i < kHistCopies * 256; i += 256) (&local[0][0])[i] = 0u;
     __syncthreads();
-    uint32_t* mine = local[threadIdx.x & (kHistCopies - 1)];
+    uint32_t* mine = &local[0][threadIdx.x & (kHistCopies - 1)];
     const uint64_t vectors = n >> 4;                          // `in` is 16-byte aligned
-    for (uint64_t v = (uint64_t)block * 256 + threadIdx.x; v < vectors; v += (uint64_t)lay.hist_blocks * 256) {
-        const u32x4 w = reinterpret_cast<const u32x4*>(in)[v];
+    const uint64_t stride = (uint64_t)lay.hist_blocks * 256;
+    uint64_t v = (uint64_t)block * 256 + threadIdx.x;
+    u32x4 ahead = v < vectors ? reinterpret_cast<const u32x4*>(in)[v] : u32x4{0u, 0u, 0u, 0u};
+    for (; v < vectors; v += stride) {
+        const u32x4 w = ahead;
+        if (v + stride < vectors) ahead = reinterpret_cast<const u32x4*>(in)[v + stride];   // in flight during the counting
         const uint32_t word[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int k = 0; k < 4; ++k)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) atomicAdd(&mine[(word[k] >> (8 * b)) & 0xffu], 1u);
+            for (int b = 0; b < 4; ++b) atomicAdd(&mine[((word[k] >> (8 * b)) & 0xffu) * kHistCopies], 1u);
     }
     if (block == 0) {                                         // the bytes after the last whole vector
         const uint64_t i = (vectors << 4) + threadIdx.x;
-        if (threadIdx.x < 16 && i < n) atomicAdd(&mine[in[i]], 1u);
+        if (threadIdx.x < 16 && i < n) atomicAdd(&mine[(uint32_t)in[i] * kHistCopies], 1u);
     }
     __syncthreads();
     uint32_t total = 0;
 #pragma unroll
-    for (int c = 0; c < kHistCopies; ++c) total += local[c][threadIdx.x];
+    for (int c = 0; c < kHistCopies; ++c) total += local[threadIdx.x][(c + threadIdx.x) & (kHistCopies - 1)];   // a bank per lane
     if (total) atomicAdd(&hist[threadIdx.x], total);
 }
 
@@ -320,20 +332,26 @@ __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Lay
     const bool live = chunk < lay.chunks;
     const uint32_t words = live ? lay.offsets[chunk] : 0u;
     uint32_t total;
-    const uint32_t offset = lay.group_sums[group] + workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
-    if (!live) return;
-    lay.offsets[chunk] = offset;
+    const uint32_t before = workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
+    const uint32_t base = lay.group_sums[group];
+    if (live) lay.offsets[chunk] = base + before;
+    // The workgroup's chunks are one contiguous slice of the payload. It is put together in LDS and copied out
+    // with consecutive lanes on consecutive words; word by word from each thread the stores would be 4 bytes
+    // every ~100 bytes. A slice too long for the LDS (more than 6 bits per symbol on average) goes out directly.
+    __shared__ uint32_t stage[kWriteStageWords];
+    const bool staged = total <= (uint32_t)kWriteStageWords;
+    uint32_t* out = staged ? stage + before : lay.payload + base + before;
     const uint64_t first = (uint64_t)chunk * kChunk;
-    const uint32_t valid = lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
-    uint32_t* out = lay.payload + offset;
+    const uint32_t valid = !live ? 0u : lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
     uint64_t acc = 0;                                         // the low `filled` bits are pending, oldest on top
     uint32_t filled = 0, written = 0;
     uint32_t word[4], ahead[4];
-    load_symbols(lay.in, first, valid, ahead);
+    if (valid) load_symbols(lay.in, first, valid, ahead);
     for (uint32_t i = 0; i < valid; i += 16) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) word[k] = ahead[k];
-        if (i + 16 < valid) load_symbols(lay.in, first + i + 16, valid - i - 16, ahead);   // in flight while this vector is coded
+        // in flight while this vector is coded (all sixteen requested at once were measured slower)
+        if (i + 16 < valid) load_symbols(lay.in, first + i + 16, valid - i - 16, ahead);
         const uint32_t here = valid - i < 16u ? valid - i : 16u;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
@@ -353,56 +371,128 @@ __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Lay
             }
     }
     if (filled && written < words) out[written] = (uint32_t)(acc << (32u - filled));   // zero-padded to a whole word
+    if (!staged) return;                                      // the same decision in every thread
+    __syncthreads();
+    uint32_t* slice = lay.payload + base;
+    for (uint32_t w = threadIdx.x; w < total; w += kThreads) slice[w] = stage[w];
 }
 
 // One chunk: `valid` symbols from the words next_word(0), next_word(1), ... to dst (16-byte aligned).
+// The per-length tables of a stream, in LDS: what a code longer than the fast table's index is decoded with.
+struct LongCodes {
+    uint32_t per_length[kMaxLen + 2];                         // [k]: codes of length k
+    uint32_t first[kMaxLen + 2];                              // [k]: the first (smallest) code of length k
+    uint32_t start[kMaxLen + 2];                              // [k]: position in `sorted` of that code's symbol
+    uint8_t  sorted[256];                                     // symbols by (length, symbol)
+};
+
+// The symbol whose code, longer than kFastBits, is on top of `window`, as symbol | length << 8 like an entry of the
+// fast table.  Such codes belong to symbols rarer than one in 2^kFastBits, so this is a call of a rolled loop that
+// reads LDS: the code of the common path around it stays short.  The shortest matching length wins and no match
+// consumes one bit (only a stream that no encoder wrote can have either).
+__device__ __noinline__ uint32_t decode_long(uint64_t window, const LongCodes* t)
+{
+#pragma unroll 1
+    for (int k = kFastBits + 1; k <= kMaxLen; ++k) {
+        const uint32_t code = (uint32_t)(window >> (64 - k)), count = t->per_length[k], first = t->first[k];
+        if (count && code >= first && code - first < count)
+            return t->sorted[(t->start[k] + code - first) & 0xffu] | ((uint32_t)k << 8);
+    }
+    return 1u << 8;
+}
+
 template <typename NextWord>
-__device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const uint16_t* fast, const uint8_t* sorted,
-                                             const uint32_t (&count_of)[kMaxLen + 1], const uint32_t (&first_of)[kMaxLen + 1],
-                                             const uint32_t (&start_of)[kMaxLen + 1], NextWord next_word)
+__device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const uint16_t* fast, const LongCodes* tables,
+                                             NextWord next_word)
 {
     uint32_t taken = 0;                                       // words moved into `buf`
     uint64_t buf = 0;                                         // pending bits, the next one on top
     uint32_t have = 0;
-    for (uint32_t i = 0; i < valid; i += 16) {
-        uint32_t sixteen[4];
+    for (uint32_t half = 0; half < valid; half += 16 * kBurst) {
+        u32x4 piece[kBurst];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            uint32_t four = 0;
+        for (int v = 0; v < kBurst; ++v) {
+            uint32_t sixteen[4];
+            if (half + 16u * v >= valid) { piece[v] = u32x4{0u, 0u, 0u, 0u}; continue; }
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if (have <= 32u) {
-                    const uint32_t w = next_word(taken);
-                    ++taken;
-                    buf |= (uint64_t)w << (32u - have);
-                    have += 32u;
-                }
-                uint32_t symbol = 0, used_bits = 1;
-                const uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
-                if (e) {
-                    symbol = e & 0xffu;
-                    used_bits = e >> 8;
-                } else {
+            for (int q = 0; q < 4; ++q) {
+                uint32_t four = 0;
 #pragma unroll
-                    for (int k = kMaxLen; k > kFastBits; --k) {       // no LDS until the length is known
-                        const uint32_t code = (uint32_t)(buf >> (64 - k));
-                        if (count_of[k] && code >= first_of[k] && code - first_of[k] < count_of[k]) {
-                            symbol = start_of[k] + code - first_of[k];
-                            used_bits = (uint32_t)k;
-                        }
+                for (int b = 0; b < 4; ++b) {
+                    if (have <= 32u) {
+                        const uint32_t w = next_word(taken);
+                        ++taken;
+                        buf |= (uint64_t)w << (32u - have);
+                        have += 32u;
                     }
-                    if (used_bits > (uint32_t)kFastBits) symbol = sorted[symbol & 0xffu];
+                    uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
+                    if (!e) e = decode_long(buf, tables);
+                    const uint32_t symbol = e & 0xffu, used_bits = e >> 8;
+                    buf <<= used_bits;
+                    have -= used_bits;
+                    four |= symbol << (8 * b);
                 }
-                buf <<= used_bits;
-                have -= used_bits;
-                four |= symbol << (8 * b);
+                sixteen[q] = four;
             }
-            sixteen[q] = four;
+            piece[v] = u32x4{sixteen[0], sixteen[1], sixteen[2], sixteen[3]};
         }
-        if (i + 16 <= valid) {
-            *reinterpret_cast<u32x4*>(dst + i) = u32x4{sixteen[0], sixteen[1], sixteen[2], sixteen[3]};
-        } else {
-            for (uint32_t b = 0; i + b < valid; ++b) dst[i + b] = (uint8_t)(sixteen[b >> 2] >> (8 * (b & 3u)));
+        // a whole cache line's worth of stores back to back: the line is complete in the L2 before it can be evicted
+#pragma unroll
+        for (int v = 0; v < kBurst; ++v) {
+            const uint32_t i = half + 16u * v;
+            if (i + 16 <= valid) {
+                *reinterpret_cast<u32x4*>(dst + i) = piece[v];
+            } else if (i < valid) {
+                const uint32_t w[4] = {piece[v].x, piece[v].y, piece[v].z, piece[v].w};
+                for (uint32_t b = 0; i + b < valid; ++b) dst[i + b] = (uint8_t)(w[b >> 2] >> (8 * (b & 3u)));
+            }
+        }
+    }
+}
+
+// The same from words in LDS: no bit buffer to refill (lanes would diverge on when) -- every
+// symbol reads the two words its bits start in and shifts them into place, so a step is two
+// dependent LDS reads and nothing data-dependent in the control flow.
+__device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst, const uint16_t* fast, const LongCodes* tables,
+                                                    const uint32_t* words)
+{
+    // the next 33 bits or more of the chunk from bit `pos` on, the first one on top
+    const auto window_at = [&](uint32_t pos) {
+        const uint32_t w = pos >> 5;
+        return (((uint64_t)words[w] << 32) | words[w + 1]) << (pos & 31u);
+    };
+    uint32_t pos = 0;                                         // bits of the chunk consumed
+    for (uint32_t half = 0; half < valid; half += 16 * kBurst) {
+        u32x4 piece[kBurst];
+#pragma unroll
+        for (int v = 0; v < kBurst; ++v) {
+            uint32_t sixteen[4];
+            if (half + 16u * v >= valid) { piece[v] = u32x4{0u, 0u, 0u, 0u}; continue; }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t four = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint64_t window = window_at(pos);
+                    uint32_t e = fast[(uint32_t)(window >> (64 - kFastBits))];
+                    if (!e) e = decode_long(window, tables);  // rare (one test for four symbols was measured slower)
+                    four |= (e & 0xffu) << (8 * b);
+                    pos += e >> 8;
+                }
+                sixteen[q] = four;
+            }
+            piece[v] = u32x4{sixteen[0], sixteen[1], sixteen[2], sixteen[3]};
+        }
+        // a whole cache line's worth of stores back to back: the line is complete in the L2 before it can be evicted
+#pragma unroll
+        for (int v = 0; v < kBurst; ++v) {
+            const uint32_t i = half + 16u * v;
+            if (i + 16 <= valid) {
+                *reinterpret_cast<u32x4*>(dst + i) = piece[v];
+            } else if (i < valid) {
+                const uint32_t w[4] = {piece[v].x, piece[v].y, piece[v].z, piece[v].w};
+                for (uint32_t b = 0; i + b < valid; ++b) dst[i + b] = (uint8_t)(w[b >> 2] >> (8 * (b & 3u)));
+            }
         }
     }
 }
@@ -413,104 +503,152 @@ __device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const
 // (words outside read as zero), and every loop is bounded by the symbol count.
 __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<DecodeJob> batch)
 {
-    uint32_t group;
-    const DecodeJob& job = batch.item[batch_item(batch, blockIdx.x, group)];
+    uint32_t block;
+    const DecodeJob& job = batch.item[batch_item(batch, blockIdx.x, block)];
     const uint8_t* len_in = job.len;
     const uint32_t* offsets = job.offsets;
     const uint32_t* payload = job.payload;
     const uint32_t payload_words = job.payload_words, chunks = job.chunks;
     const uint64_t n = job.n;
     uint8_t* out = job.out;
-    __shared__ uint8_t  len[256];
-    __shared__ uint8_t  sorted[256];                          // symbols by (length, symbol)
-    __shared__ uint32_t per_length[kMaxLen + 2], first[kMaxLen + 2], start[kMaxLen + 2];
+    __shared__ LongCodes tables;
+    uint32_t (&per_length)[kMaxLen + 2] = tables.per_length, (&first)[kMaxLen + 2] = tables.first, (&start)[kMaxLen + 2] = tables.start;
+    uint8_t (&sorted)[256] = tables.sorted;
+    __shared__ uint32_t in_wave[kThreads / 64][kMaxLen + 2];  // [w][k]: symbols of length k among wave w's 64
     __shared__ uint16_t fast[1 << kFastBits];                 // next kFastBits bits -> symbol | length << 8; 0: longer code
-    __shared__ uint32_t stage[kStageWords];                   // the workgroup's slice of the payload, or the rings
-    const uint32_t s = threadIdx.x;
-    {
-        const uint32_t l = len_in[s];
-        len[s] = l <= (uint32_t)kMaxLen ? (uint8_t)l : (uint8_t)0;
+    __shared__ __align__(16) uint32_t stage[kStageWords + kChunkWordsMax + 8];   // the workgroup's slice of the payload, or the rings
+    const uint32_t s = threadIdx.x, wave = s >> 6, lane = s & 63u;
+    uint32_t l = len_in[s];
+    if (l > (uint32_t)kMaxLen) l = 0u;
+    // thread s is symbol s: its rank among the symbols of its length, by lane masks inside the wave ...
+    uint32_t before = 0;
+#pragma unroll
+    for (int k = 1; k <= kMaxLen; ++k) {
+        const uint64_t same = __ballot(l == (uint32_t)k);
+        if (l == (uint32_t)k) before = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
+        if (lane == 0) in_wave[wave][k] = (uint32_t)__popcll(same);
     }
-    if (s < (uint32_t)kMaxLen + 2u) per_length[s] = 0u;
     __syncthreads();
-    const uint32_t l = len[s];
-    if (l) atomicAdd(&per_length[l], 1u);
+    if (s < (uint32_t)kMaxLen + 2u) {
+        uint32_t total = 0;
+        if (s >= 1u && s <= (uint32_t)kMaxLen)
+            for (int w = 0; w < kThreads / 64; ++w) total += in_wave[w][s];
+        per_length[s] = total;
+    }
     __syncthreads();
     if (s == 0) {
+        uint32_t count[kMaxLen + 1];
+#pragma unroll
+        for (int k = 1; k <= kMaxLen; ++k) count[k] = per_length[k];
+        uint32_t code = 0, at = 0;
         first[0] = first[1] = 0u;
         start[0] = start[1] = 0u;
+#pragma unroll
         for (int k = 2; k <= kMaxLen; ++k) {
-            first[k] = (first[k - 1] + per_length[k - 1]) << 1;
-            start[k] = start[k - 1] + per_length[k - 1];
+            code = (code + count[k - 1]) << 1;
+            at += count[k - 1];
+            first[k] = code;
+            start[k] = at;
         }
     }
     __syncthreads();
-    if (l) {
-        uint32_t before = 0;                                  // symbols of the same length below this one
-        for (uint32_t t = 0; t < s; ++t) before += len[t] == l ? 1u : 0u;
-        sorted[start[l] + before] = (uint8_t)s;
+    if (l) {                                                  // ... plus those in the waves below
+        for (uint32_t w = 0; w < wave; ++w) before += in_wave[w][l];
+        sorted[(start[l] + before) & 0xffu] = (uint8_t)s;
     }
     __syncthreads();
-    // the tables of this stream, in registers (the same in every thread)
-    uint32_t count_of[kMaxLen + 1], first_of[kMaxLen + 1], start_of[kMaxLen + 1];
+    {
+        // the short lengths' tables in registers (the same in every thread)
+        uint32_t count_of[kFastBits + 1], first_of[kFastBits + 1], start_of[kFastBits + 1];
 #pragma unroll
-    for (int k = 1; k <= kMaxLen; ++k) { count_of[k] = per_length[k]; first_of[k] = first[k]; start_of[k] = start[k]; }
-    for (uint32_t i = s; i < (1u << kFastBits); i += kThreads) {      // the short codes: what the next kFastBits bits decode to
-        uint32_t e = 0;
+        for (int k = 1; k <= kFastBits; ++k) { count_of[k] = per_length[k]; first_of[k] = first[k]; start_of[k] = start[k]; }
+        for (uint32_t i = s; i < (1u << kFastBits); i += kThreads) {  // the short codes: what the next kFastBits bits decode to
+            uint32_t at = 0, length = 0;
 #pragma unroll
-        for (int k = kFastBits; k >= 1; --k) {
-            const uint32_t code = i >> (kFastBits - k);
-            if (count_of[k] && code >= first_of[k] && code - first_of[k] < count_of[k])
-                e = sorted[start_of[k] + code - first_of[k]] | ((uint32_t)k << 8);   // at most one length matches a prefix code
+            for (int k = kFastBits; k >= 1; --k) {                   // at most one length matches a prefix code
+                const uint32_t code = i >> (kFastBits - k);
+                if (count_of[k] && code >= first_of[k] && code - first_of[k] < count_of[k]) {
+                    at = start_of[k] + code - first_of[k];
+                    length = (uint32_t)k;
+                }
+            }
+            fast[i] = length ? (uint16_t)(sorted[at & 0xffu] | (length << 8)) : (uint16_t)0;
         }
-        fast[i] = (uint16_t)e;
     }
     __syncthreads();
 
-    // The payload words of the workgroup's 256 chunks are one contiguous slice.  When it fits it
-    // is brought into LDS with contiguous loads and the threads read their words from there
-    // (a thread walking its chunk in memory would fetch a cache line per word); a longer slice,
-    // or offsets that do not describe one, go through per-thread rings instead.
-    const uint32_t chunk0 = group * kThreads;
-    const uint32_t chunk1 = chunk0 + kThreads < chunks ? chunk0 + kThreads : chunks;
-    const uint32_t slice_at = offsets[chunk0], slice_end = offsets[chunk1];
-    const bool staged = slice_end >= slice_at && slice_end - slice_at <= (uint32_t)kStageWords && slice_end <= payload_words;
-    const uint32_t chunk = chunk0 + threadIdx.x;
-    const bool live = chunk < chunks;
-    const uint64_t base = (uint64_t)chunk * kChunk;
-    const uint32_t valid = !live ? 0u : n - base < (uint64_t)kChunk ? (uint32_t)(n - base) : (uint32_t)kChunk;
-    const uint32_t first_word = live ? offsets[chunk] : 0u;
-    uint8_t* dst = out + base;
-    if (staged) {                                             // workgroup-uniform
-        const uint32_t slice_words = slice_end - slice_at;
-        for (uint32_t i = threadIdx.x; i < slice_words; i += kThreads) stage[i] = payload[slice_at + i];
-        __syncthreads();
-        const uint32_t at = first_word - slice_at;            // anything at all for a foreign stream: reads are bounded
-        decode_chunk(valid, dst, fast, sorted, count_of, first_of, start_of,
-                     [&](uint32_t k) { return at + k < slice_words ? stage[at + k] : 0u; });
-        return;
-    }
-    if (!live) return;
-    // a ring of eight words per thread: when four have been consumed, the four loaded at the
-    // previous refill take their place and the next four are requested, so a load has the time
-    // of four words' decoding to arrive
-    uint32_t* mine = stage + threadIdx.x;                     // word k of the ring at mine[(k & 7) * kThreads]
-    uint32_t pending[4];
+    // These tables serve `groups_per_block` groups of 256 chunks, one after the other.  The payload words of
+    // a group's chunks are one contiguous slice.  When it fits it is brought into LDS with contiguous loads and the
+    // threads read their words from there (a thread walking its chunk in memory would fetch a cache line per
+    // word); a longer slice, or offsets that do not describe one, go through per-thread rings instead.
+    const uint32_t groups = (chunks + kThreads - 1) / kThreads;
+    const uint32_t group_end = (block + 1u) * job.groups_per_block < groups ? (block + 1u) * job.groups_per_block : groups;
+    for (uint32_t group = block * job.groups_per_block; group < group_end; ++group) {
+        const uint32_t chunk0 = group * kThreads;
+        const uint32_t chunk1 = chunk0 + kThreads < chunks ? chunk0 + kThreads : chunks;
+        const uint32_t slice_at = offsets[chunk0], slice_end = offsets[chunk1];
+        const bool staged = slice_end >= slice_at && slice_end - slice_at <= (uint32_t)kStageWords && slice_end <= payload_words;
+        const uint32_t chunk = chunk0 + threadIdx.x;
+        const bool live = chunk < chunks;
+        const uint64_t base = (uint64_t)chunk * kChunk;
+        const uint32_t valid = !live ? 0u : n - base < (uint64_t)kChunk ? (uint32_t)(n - base) : (uint32_t)kChunk;
+        const uint32_t first_word = live ? offsets[chunk] : 0u;
+        uint8_t* dst = out + base;
+        if (staged) {                                         // workgroup-uniform
+            // 16 bytes per load, eight loads of a thread in flight: one at a time, a slice of ~50 words per thread
+            // would cost as many memory latencies.  The stage starts at the 16-byte boundary at or below the
+            // slice's first word (`phase` words earlier); what the vectors cover beyond the payload's ends is
+            // read as zero.
+            const uint32_t slice_words = slice_end - slice_at;
+            const uint32_t phase = (uint32_t)(reinterpret_cast<uintptr_t>(payload + slice_at) >> 2) & 3u;
+            const uint32_t vectors = (slice_words + phase + 3u) / 4u;
+            for (uint32_t v0 = 0; v0 < vectors; v0 += 8u * kThreads) {
+                u32x4 got[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) mine[k * kThreads] = first_word + k < payload_words ? payload[first_word + k] : 0u;
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t v = v0 + k * kThreads + threadIdx.x;
+                    const int64_t w = (int64_t)slice_at + 4 * (int64_t)v - phase;  // below zero in the first vector at most
+                    const auto word_at = [&](int64_t g) { return g >= 0 && g < (int64_t)payload_words ? payload[g] : 0u; };
+                    got[k] = u32x4{0u, 0u, 0u, 0u};
+                    if (v < vectors) {
+                        if (w >= 0 && w + 3 < (int64_t)payload_words) got[k] = *reinterpret_cast<const u32x4*>(payload + w);
+                        else got[k] = u32x4{word_at(w), word_at(w + 1), word_at(w + 2), word_at(w + 3)};
+                    }
+                }
 #pragma unroll
-    for (int k = 0; k < 4; ++k) pending[k] = first_word + 8 + k < payload_words ? payload[first_word + 8 + k] : 0u;
-    decode_chunk(valid, dst, fast, sorted, count_of, first_of, start_of, [&](uint32_t taken) {
-        if ((taken & 3u) == 0u && taken != 0u) {              // a block of four used up: refill the half of the ring just freed
-            const uint32_t slot = (taken + 4u) & 7u;
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t v = v0 + k * kThreads + threadIdx.x;
+                    if (v < vectors) *reinterpret_cast<u32x4*>(stage + 4u * v) = got[k];
+                }
+            }
+            __syncthreads();
+            // anything at all for a foreign stream: clamped, the reads stay inside the array (a chunk is at most 192 words)
+            const uint32_t at = first_word - slice_at < slice_words ? first_word - slice_at : slice_words;
+            decode_chunk_staged(valid, dst, fast, &tables, stage + phase + at);
+        } else if (live) {
+            // a ring of eight words per thread: when four have been consumed, the four loaded at the
+            // previous refill take their place and the next four are requested, so a load has the time
+            // of four words' decoding to arrive
+            uint32_t* mine = stage + threadIdx.x;             // word k of the ring at mine[(k & 7) * kThreads]
+            uint32_t pending[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) mine[((slot + k) & 7u) * kThreads] = pending[k];
-            const uint32_t at = first_word + taken + 8u;
+            for (int k = 0; k < 8; ++k) mine[k * kThreads] = first_word + k < payload_words ? payload[first_word + k] : 0u;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) pending[k] = at + k < payload_words ? payload[at + k] : 0u;
+            for (int k = 0; k < 4; ++k) pending[k] = first_word + 8 + k < payload_words ? payload[first_word + 8 + k] : 0u;
+            decode_chunk(valid, dst, fast, &tables, [&](uint32_t taken) {
+                if ((taken & 3u) == 0u && taken != 0u) {      // a block of four used up: refill the half of the ring just freed
+                    const uint32_t slot = (taken + 4u) & 7u;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) mine[((slot + k) & 7u) * kThreads] = pending[k];
+                    const uint32_t at = first_word + taken + 8u;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) pending[k] = at + k < payload_words ? payload[at + k] : 0u;
+                }
+                return mine[(taken & 7u) * kThreads];
+            });
         }
-        return mine[(taken & 7u) * kThreads];
-    });
+        __syncthreads();                                      // the stage is the next group's
+    }
 }
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -651,7 +789,13 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
             job.n = it.n;
             job.payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
             job.chunks = (uint32_t)chunks;
-            if (!push(b, job, (int64_t)groups_of(it.n))) {
+            // a workgroup builds the stream's tables once for all its groups: several groups each when the
+            // stream has enough of them to fill the chip many times over anyway
+            const uint64_t groups = groups_of(it.n);
+            job.groups_per_block = (uint32_t)(groups / kDecodeBlocksWanted < 1u ? 1u
+                                              : groups / kDecodeBlocksWanted > (uint64_t)kDecodeGroupsMax ? (uint64_t)kDecodeGroupsMax
+                                              : groups / kDecodeBlocksWanted);
+            if (!push(b, job, (int64_t)((groups + job.groups_per_block - 1u) / job.groups_per_block))) {
                 if (b.count == 0) return FH_ERR_BAD_NUMEL;
                 break;
             }

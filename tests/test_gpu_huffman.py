@@ -50,6 +50,17 @@ def test_sizes_around_vectors_chunks_and_groups(api, n):
     _check(api, data, "normal around 128")
 
 
+@pytest.mark.parametrize("spread", [2.5, 14.0, 0.0])
+def test_streams_long_enough_that_a_workgroup_decodes_several_groups(api, spread):
+    # 301 groups of 256 chunks and a ragged tail: two groups per decoding workgroup, the last workgroup with one.
+    # spread 14: codes longer than the decoder's fast table occur; 0: uniform bytes, whose 64 words per chunk do
+    # not fit the LDS stage of either side (the direct payload stores and the per-thread rings)
+    n = 256 * 256 * 301 + 77
+    rng = np.random.default_rng(int(spread * 10))
+    data = (np.clip(np.rint(rng.normal(128, spread, n)), 0, 255) if spread else rng.integers(0, 256, n)).astype(np.uint8)
+    _check(api, data, f"spread {spread}")
+
+
 @pytest.mark.parametrize("kind", ["uniform", "one", "two", "geometric", "all-once", "ties"])
 def test_distributions(api, kind):
     rng = np.random.default_rng(1)
