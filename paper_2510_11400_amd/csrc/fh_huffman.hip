@@ -6,8 +6,9 @@
 // A variable-length code is sequential per symbol, so the stream is cut into chunks of 256
 // symbols that start on a 32-bit word; a thread owns a chunk.  Encoding is stream compaction
 // again:
-//   histogram   LDS counters (eight copies, by lane, so that a dominant symbol does not
-//               serialise the wave), added to the global histogram at the end;
+//   histogram   LDS counters, one copy per bank and the copies interleaved, so that no two lanes
+//               of a half-wave meet in a bank whatever the bytes are; added to the global
+//               histogram at the end;
 //   code        one workgroup: the used symbols are ranked by (count, symbol) in parallel, one
 //               lane runs the two-queue construction over the ranked leaves (at most 255
 //               merges) and walks the tree for the depths; counts are halved and the
@@ -16,10 +17,12 @@
 //   scan        the sums of groups of 256 chunks (a workgroup of the count pass) are scanned by
 //               one workgroup;
 //   write       a thread turns its chunk's word count into its offset (group base + a scan
-//               over the workgroup) and writes its words.
-// Decoding needs no pass but one: the offsets are part of the stream.  Every workgroup
-// rebuilds the canonical tables from the 256 lengths (a 12-bit lookup table for the short
-// codes, first-code / count comparisons for the longer ones).
+//               over the workgroup) and produces its words; the workgroup's words, a contiguous
+//               slice, are collected in LDS and stored with consecutive lanes on consecutive words.
+// Decoding needs no pass but one: the offsets are part of the stream.  A workgroup rebuilds the
+// canonical tables from the 256 lengths (a 12-bit lookup table for the short codes, first-code /
+// count comparisons for the longer ones), stages the payload slice of 256 chunks in LDS, and a
+// thread decodes its chunk from there; the tables serve several such groups in long streams.
 // Everything here is integer work; results do not depend on launch geometry.
 #include "../../include/fedhybrid.h"
 
