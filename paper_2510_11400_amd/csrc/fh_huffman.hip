@@ -117,59 +117,72 @@ __global__ __launch_bounds__(256) void huffman_histogram_kernel(const Batch<Layo
 __global__ __launch_bounds__(256) void huffman_code_kernel(const Batch<Layout> batch)
 {
     const Layout& lay = batch.item[blockIdx.x];
-    __shared__ uint64_t count[256];                           // this round's counts, by symbol
-    __shared__ uint64_t weight[511];                          // leaves in rank order, then internal nodes as made
+    // counts and weights are sums of at most 2^32 - 1 symbols: 32 bits hold them
+    __shared__ __align__(16) uint32_t count[256];             // this round's counts, by symbol
+    __shared__ uint32_t weight[511];                          // leaves in rank order, then internal nodes as made
     __shared__ uint16_t parent[511];
-    __shared__ uint8_t  leaf_symbol[256];
     __shared__ uint8_t  length[256];
     __shared__ uint32_t code_of[256];
-    __shared__ uint32_t used, deepest;
-    const uint32_t s = threadIdx.x;
-    const uint64_t original = lay.hist[s];
-    uint64_t c = original;
+    __shared__ uint32_t in_wave[4][kMaxLen + 2];              // [w][k]: wave w's symbols that are unused (k = 0) / of length k
+    __shared__ uint32_t deepest;
+    const uint32_t s = threadIdx.x, wave = s >> 6, lane = s & 63u;
+    const uint32_t original = lay.hist[s];
+    uint32_t c = original;
     for (;;) {                                                // workgroup-uniform; counts halve, so it ends
         count[s] = c;
         length[s] = 0;
-        if (s == 0) used = 0u;
-        __syncthreads();
-        uint32_t rank = 0;                                    // used symbols before this one by (count, symbol)
-        for (int t = 0; t < 256; ++t) {
-            const uint64_t o = count[t];
-            rank += (o != 0 && (o < c || (o == c && (uint32_t)t < s))) ? 1u : 0u;
-        }
-        if (c != 0) {
-            weight[rank] = c;
-            leaf_symbol[rank] = (uint8_t)s;
-            atomicAdd(&used, 1u);
+        {
+            const uint64_t unused = __ballot(c == 0u);
+            if (lane == 0) in_wave[wave][0] = (uint32_t)__popcll(unused);
         }
         __syncthreads();
-        const int m = (int)used;
+        const int m = 256 - (int)(in_wave[0][0] + in_wave[1][0] + in_wave[2][0] + in_wave[3][0]);   // used symbols
+        // used symbols before this one by (count, symbol): those with a smaller count, the unused ones taken off
+        // again, plus those of the same count and a smaller value
+        uint32_t rank = 0;
+#pragma unroll 4
+        for (int t = 0; t < 256; t += 4) {
+            const u32x4 four = *reinterpret_cast<const u32x4*>(&count[t]);
+            const uint32_t o[4] = {four.x, four.y, four.z, four.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) rank += (o[k] < c ? 1u : 0u) + ((o[k] == c && (uint32_t)(t + k) < s) ? 1u : 0u);
+        }
+        rank -= 256u - (uint32_t)m;
+        if (c != 0) weight[rank] = c;
+        __syncthreads();
         if (s == 0) {
             deepest = 0u;
             if (m > 1) {
-                // the fronts of the two queues stay in registers; LDS is read once per node taken
+                // The first two nodes of either queue stay in registers, so that taking a node starts the LDS
+                // read of the one after next and nothing waits for it until a further node has been taken.
+                // kNone stands for a node that does not exist (yet): only the root can weigh 2^32 - 1, and the
+                // root is never compared.  One of the fronts always exists: before a merge the queues hold two
+                // nodes or more.
+                constexpr uint32_t kNone = ~(uint32_t)0;
                 int next_leaf = 0, next_internal = m, made = m;
-                uint64_t leaf_front = weight[0], internal_front = 0;
+                uint32_t leaf0 = weight[0], leaf1 = weight[1];        // leaves next_leaf and next_leaf + 1
+                uint32_t node0 = kNone, node1 = kNone;                // internal nodes next_internal and next_internal + 1
                 while (made < 2 * m - 1) {                    // at most 255 merges
-                    uint64_t sum = 0;
+                    uint32_t sum = 0;
 #pragma unroll
                     for (int k = 0; k < 2; ++k) {
-                        const bool have_leaf = next_leaf < m, have_internal = next_internal < made;
-                        // a leaf is preferred to an internal node of equal weight
-                        if (have_leaf && (!have_internal || leaf_front <= internal_front)) {
-                            sum += leaf_front;
+                        if (leaf0 <= node0) {                 // a leaf is preferred to an internal node of equal weight
+                            sum += leaf0;
                             parent[next_leaf] = (uint16_t)made;
                             ++next_leaf;
-                            if (next_leaf < m) leaf_front = weight[next_leaf];
+                            leaf0 = leaf1;
+                            leaf1 = next_leaf + 1 < m ? weight[next_leaf + 1] : kNone;
                         } else {
-                            sum += internal_front;
+                            sum += node0;
                             parent[next_internal] = (uint16_t)made;
                             ++next_internal;
-                            if (next_internal < made) internal_front = weight[next_internal];
+                            node0 = node1;
+                            node1 = next_internal + 1 < made ? weight[next_internal + 1] : kNone;
                         }
                     }
                     weight[made] = sum;
-                    if (next_internal == made) internal_front = sum;   // the new node is the queue's front
+                    if (made == next_internal) node0 = sum;           // the new node is the queue's front,
+                    else if (made == next_internal + 1) node1 = sum;  // or the one behind it
                     ++made;
                 }
             }
@@ -189,29 +202,36 @@ __global__ __launch_bounds__(256) void huffman_code_kernel(const Batch<Layout> b
         if (c != 0) c = (c + 1) >> 1;
         __syncthreads();                                      // everyone has read `deepest` before it is written again
     }
-    // canonical codes: by increasing (length, symbol)
-    __shared__ uint32_t per_length[kMaxLen + 2], first_code[kMaxLen + 2];
-    if (s < (uint32_t)kMaxLen + 2u) per_length[s] = 0u;
-    __syncthreads();
+    // canonical codes: by increasing (length, symbol); a symbol's place among those of its length from lane masks
+    // inside the wave plus the counts of the waves below
+    __shared__ uint32_t first_code[kMaxLen + 2];
     const uint32_t my_length = length[s];
-    if (my_length) atomicAdd(&per_length[my_length], 1u);
+    uint32_t before = 0;
+#pragma unroll
+    for (int k = 1; k <= kMaxLen; ++k) {
+        const uint64_t same = __ballot(my_length == (uint32_t)k);
+        if (my_length == (uint32_t)k) before = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
+        if (lane == 0) in_wave[wave][k] = (uint32_t)__popcll(same);
+    }
     __syncthreads();
     if (s == 0) {
+        uint32_t code = 0;
         first_code[0] = first_code[1] = 0u;
-        for (int l = 2; l <= kMaxLen; ++l) first_code[l] = (first_code[l - 1] + per_length[l - 1]) << 1;
+#pragma unroll
+        for (int l = 2; l <= kMaxLen; ++l) {
+            code = (code + in_wave[0][l - 1] + in_wave[1][l - 1] + in_wave[2][l - 1] + in_wave[3][l - 1]) << 1;
+            first_code[l] = code;
+        }
     }
     __syncthreads();
-    {
-        uint32_t before = 0;                                  // symbols of the same length below this one
-        for (uint32_t t = 0; t < s; ++t) before += length[t] == my_length ? 1u : 0u;
-        code_of[s] = my_length ? first_code[my_length] + before : 0u;
-    }
+    if (my_length) for (uint32_t w = 0; w < wave; ++w) before += in_wave[w][my_length];
+    code_of[s] = my_length ? first_code[my_length] + before : 0u;
     __syncthreads();
     lay.len[s] = length[s];
     lay.table[s] = (code_of[s] << 8) | length[s];
     // payload bits: every symbol's count times its length (the counts as they were)
     __shared__ uint64_t bit_sum[256];
-    bit_sum[s] = original * length[s];
+    bit_sum[s] = (uint64_t)original * length[s];
     __syncthreads();
     for (int step = 128; step >= 1; step >>= 1) {
         if (s < (uint32_t)step) bit_sum[s] += bit_sum[s + step];
