@@ -344,37 +344,21 @@ __global__ __launch_bounds__(kThreads) void huffman_scan_kernel(const Batch<Layo
 }
 
 // ---- write: offsets and payload -------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Layout> batch)
+// The code words of one chunk (symbols in[first .. first + valid)), MSB first, to out[0 .. words): `out` is LDS or
+// global memory, and the function is compiled once for each so that the LDS case uses LDS stores.
+template <typename Out>
+__device__ __forceinline__ void encode_chunk(const uint8_t* in, uint64_t first, uint32_t valid, const uint32_t* table,
+                                             uint32_t words, Out out)
 {
-    uint32_t group;
-    const Layout& lay = batch.item[batch_item(batch, blockIdx.x, group)];
-    __shared__ uint32_t table[256];
-    __shared__ uint32_t lds[4];
-    table[threadIdx.x] = lay.table[threadIdx.x];
-    const uint32_t chunk = group * kThreads + threadIdx.x;
-    const bool live = chunk < lay.chunks;
-    const uint32_t words = live ? lay.offsets[chunk] : 0u;
-    uint32_t total;
-    const uint32_t before = workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
-    const uint32_t base = lay.group_sums[group];
-    if (live) lay.offsets[chunk] = base + before;
-    // The workgroup's chunks are one contiguous slice of the payload. It is put together in LDS and copied out
-    // with consecutive lanes on consecutive words; word by word from each thread the stores would be 4 bytes
-    // every ~100 bytes. A slice too long for the LDS (more than 6 bits per symbol on average) goes out directly.
-    __shared__ uint32_t stage[kWriteStageWords];
-    const bool staged = total <= (uint32_t)kWriteStageWords;
-    uint32_t* out = staged ? stage + before : lay.payload + base + before;
-    const uint64_t first = (uint64_t)chunk * kChunk;
-    const uint32_t valid = !live ? 0u : lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
     uint64_t acc = 0;                                         // the low `filled` bits are pending, oldest on top
     uint32_t filled = 0, written = 0;
     uint32_t word[4], ahead[4];
-    if (valid) load_symbols(lay.in, first, valid, ahead);
+    if (valid) load_symbols(in, first, valid, ahead);
     for (uint32_t i = 0; i < valid; i += 16) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) word[k] = ahead[k];
-        // in flight while this vector is coded (all sixteen requested at once were measured slower)
-        if (i + 16 < valid) load_symbols(lay.in, first + i + 16, valid - i - 16, ahead);
+        // in flight while this vector is coded (four ahead, and all sixteen at once, were measured no faster)
+        if (i + 16 < valid) load_symbols(in, first + i + 16, valid - i - 16, ahead);
         const uint32_t here = valid - i < 16u ? valid - i : 16u;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
@@ -394,7 +378,33 @@ __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Lay
             }
     }
     if (filled && written < words) out[written] = (uint32_t)(acc << (32u - filled));   // zero-padded to a whole word
-    if (!staged) return;                                      // the same decision in every thread
+}
+
+__global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Layout> batch)
+{
+    uint32_t group;
+    const Layout& lay = batch.item[batch_item(batch, blockIdx.x, group)];
+    __shared__ uint32_t table[256];
+    __shared__ uint32_t lds[4];
+    table[threadIdx.x] = lay.table[threadIdx.x];
+    const uint32_t chunk = group * kThreads + threadIdx.x;
+    const bool live = chunk < lay.chunks;
+    const uint32_t words = live ? lay.offsets[chunk] : 0u;
+    uint32_t total;
+    const uint32_t before = workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
+    const uint32_t base = lay.group_sums[group];
+    if (live) lay.offsets[chunk] = base + before;
+    const uint64_t first = (uint64_t)chunk * kChunk;
+    const uint32_t valid = !live ? 0u : lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
+    // The workgroup's chunks are one contiguous slice of the payload. It is put together in LDS and copied out
+    // with consecutive lanes on consecutive words; word by word from each thread the stores would be 4 bytes
+    // every ~100 bytes. A slice too long for the LDS (more than 6 bits per symbol on average) goes out directly.
+    __shared__ uint32_t stage[kWriteStageWords];
+    if (total > (uint32_t)kWriteStageWords) {                 // the same decision in every thread
+        encode_chunk(lay.in, first, valid, table, words, lay.payload + base + before);
+        return;
+    }
+    encode_chunk(lay.in, first, valid, table, words, &stage[before]);
     __syncthreads();
     uint32_t* slice = lay.payload + base;
     for (uint32_t w = threadIdx.x; w < total; w += kThreads) slice[w] = stage[w];
