@@ -37,6 +37,7 @@ constexpr int kThreads = 256;                      // chunks per workgroup: a gr
 constexpr int kMaxLen = 24;
 constexpr int kChunkWordsMax = kChunk * kMaxLen / 32;
 constexpr int kHistCopies = 32;                     // one per LDS bank
+constexpr int kHistBlocksMax = 640;                // histogram workgroups per stream: 2.5 per compute unit
 constexpr int kFastBits = 12;
 constexpr int kDecodeBlocksWanted = 128;            // decode: workgroups a stream is cut into before a workgroup takes several groups
 constexpr int kDecodeGroupsMax = 8;
@@ -773,8 +774,10 @@ fh_status fh_huffman_encode_batch(const fh_huffman_encode_item* items, int32_t c
             lay.totals = static_cast<uint64_t*>(it.totals);
             lay.in = static_cast<const uint8_t*>(it.bytes);
             lay.n = it.n;
-            const uint64_t want = it.n == 0 ? 0 : (it.n / 16 + 255) / 256 / 8 + 1;     // about eight vectors per thread
-            lay.hist_blocks = (uint32_t)(want < 4096 ? want : 4096);
+            // about eight vectors per thread, more in long streams: a workgroup clears and adds up 32 KiB of
+            // counters and sends 256 atomics to the stream's histogram whatever it counts
+            const uint64_t want = it.n == 0 ? 0 : (it.n / 16 + 255) / 256 / 8 + 1;
+            lay.hist_blocks = (uint32_t)(want < (uint64_t)kHistBlocksMax ? want : (uint64_t)kHistBlocksMax);
             if ((uint64_t)grouped.block_start[grouped.count] + lay.groups > (uint64_t)INT_MAX) {
                 if (each.count == 0) return FH_ERR_BAD_NUMEL;
                 break;
