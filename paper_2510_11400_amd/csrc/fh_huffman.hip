@@ -490,12 +490,12 @@ __device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const
 __device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst, const uint16_t* fast, const LongCodes* tables,
                                                     const uint32_t* words)
 {
-    // the next 33 bits or more of the chunk from bit `pos` on, the first one on top
-    const auto window_at = [&](uint32_t pos) {
-        const uint32_t w = pos >> 5;
-        return (((uint64_t)words[w] << 32) | words[w + 1]) << (pos & 31u);
-    };
-    uint32_t pos = 0;                                         // bits of the chunk consumed
+    // Three words of the chunk stay in registers: w0 holds bit `pos`, w1 follows, w2 is the word after that.  A
+    // symbol advances by at most 24 bits, one word, so after it the registers move up by one at most, and w2 is
+    // read again for the new position: that read is needed one symbol later, so that a symbol waits for one LDS
+    // access in a row (the table) rather than two (words, then table).
+    uint32_t pos = 0, at = 0;                                 // bits of the chunk consumed; at = pos / 32
+    uint32_t w0 = words[0], w1 = words[1], w2 = words[2];
     for (uint32_t half = 0; half < valid; half += 16 * kBurst) {
         u32x4 piece[kBurst];
 #pragma unroll
@@ -507,11 +507,16 @@ __device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst
                 uint32_t four = 0;
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
-                    const uint64_t window = window_at(pos);
-                    uint32_t e = fast[(uint32_t)(window >> (64 - kFastBits))];
-                    if (!e) e = decode_long(window, tables);  // rare (one test for four symbols was measured slower)
+                    const uint32_t top = (uint32_t)(((((uint64_t)w0 << 32) | w1) << (pos & 31u)) >> 32);   // the next 32 bits
+                    uint32_t e = fast[top >> (32 - kFastBits)];
+                    if (!e) e = decode_long((uint64_t)top << 32, tables);   // rare (one test for four symbols was measured slower)
                     four |= (e & 0xffu) << (8 * b);
                     pos += e >> 8;
+                    const bool crossed = (pos >> 5) != at;
+                    w0 = crossed ? w1 : w0;
+                    w1 = crossed ? w2 : w1;
+                    at = pos >> 5;
+                    w2 = words[at + 2];
                 }
                 sixteen[q] = four;
             }
