@@ -39,8 +39,6 @@ constexpr int kChunkWordsMax = kChunk * kMaxLen / 32;
 constexpr int kHistCopies = 32;                     // one per LDS bank
 constexpr int kHistBlocksMax = 640;                // histogram workgroups per stream: 2.5 per compute unit
 constexpr int kFastBits = 12;
-constexpr int kDecodeBlocksWanted = 128;            // decode: workgroups a stream is cut into before a workgroup takes several groups
-constexpr int kDecodeGroupsMax = 8;
 constexpr int kBurst = 8;                          // decode: 16-byte output vectors held back and stored together
 constexpr int kWriteStageWords = 12288;            // encode: LDS for a workgroup's payload slice (256 chunks of 48 words)
 constexpr int kStageWords = 13056;                 // decode: LDS for a workgroup's payload slice (256 chunks of 51 words)
@@ -748,6 +746,23 @@ void launch(Kernel kernel, const Batch<Item>& b, uint32_t grid, hipStream_t s)
     if (grid > 0) hipLaunchKernelGGL(kernel, dim3(grid), dim3(kThreads), 0, s, b);
 }
 
+
+// workgroups of the decode kernel that the current device holds at once (two per compute unit with its LDS)
+int decode_slots()
+{
+    static int cached[64] = {0};
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return 512;
+    if (cached[device] == 0) {
+        int per_unit = 0, units = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, huffman_decode_kernel, kThreads, 0) != hipSuccess || per_unit < 1)
+            per_unit = 1;
+        if (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || units < 1) units = 256;
+        cached[device] = per_unit * units;
+    }
+    return cached[device];
+}
+
 }  // namespace
 
 extern "C" {
@@ -813,34 +828,41 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
         if (st != FH_OK) return st;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t slots = (uint64_t)decode_slots();
     bool launched = false;
     for (int32_t i = 0; i < count;) {
-        Batch<DecodeJob> b;
-        reset(b);
-        while (i < count && b.count < kBatch) {
+        DecodeJob job[kBatch];
+        uint64_t groups[kBatch], total = 0;
+        int jobs = 0;
+        for (; i < count && jobs < kBatch; ++i) {
             const fh_huffman_decode_item& it = items[i];
-            if (it.n == 0) { ++i; continue; }                 // nothing to restore
+            if (it.n == 0) continue;                          // nothing to restore
             const uint64_t chunks = chunks_of(it.n);
             const uint64_t words = (it.stream_bytes - (256u + 4u * (chunks + 1u))) / 4u;
-            DecodeJob job;
-            job.len = static_cast<const uint8_t*>(it.stream_in);
-            job.offsets = reinterpret_cast<const uint32_t*>(job.len + 256);
-            job.payload = job.offsets + chunks + 1;
-            job.out = static_cast<uint8_t*>(it.out);
-            job.n = it.n;
-            job.payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
-            job.chunks = (uint32_t)chunks;
-            // a workgroup builds the stream's tables once for all its groups: several groups each when the
-            // stream has enough of them to fill the chip many times over anyway
-            const uint64_t groups = groups_of(it.n);
-            job.groups_per_block = (uint32_t)(groups / kDecodeBlocksWanted < 1u ? 1u
-                                              : groups / kDecodeBlocksWanted > (uint64_t)kDecodeGroupsMax ? (uint64_t)kDecodeGroupsMax
-                                              : groups / kDecodeBlocksWanted);
-            if (!push(b, job, (int64_t)((groups + job.groups_per_block - 1u) / job.groups_per_block))) {
-                if (b.count == 0) return FH_ERR_BAD_NUMEL;
-                break;
-            }
-            ++i;
+            DecodeJob& j = job[jobs];
+            j.len = static_cast<const uint8_t*>(it.stream_in);
+            j.offsets = reinterpret_cast<const uint32_t*>(j.len + 256);
+            j.payload = j.offsets + chunks + 1;
+            j.out = static_cast<uint8_t*>(it.out);
+            j.n = it.n;
+            j.payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
+            j.chunks = (uint32_t)chunks;
+            groups[jobs] = groups_of(it.n);
+            total += groups[jobs];
+            ++jobs;
+        }
+        // A workgroup builds a stream's tables once and then decodes `groups_per_block` groups of 256 chunks.  With
+        // more groups in the launch than workgroups fit on the device at once, every stream gets its share of
+        // that many workgroups: all of them are resident from the start and finish together, whereas a launch of
+        // 1.4 times as many would run a second, mostly empty round.
+        Batch<DecodeJob> b;
+        reset(b);
+        for (int k = 0; k < jobs; ++k) {
+            uint64_t blocks = total <= slots ? groups[k] : groups[k] * slots / total;
+            if (blocks < 1u) blocks = 1u;
+            job[k].groups_per_block = (uint32_t)((groups[k] + blocks - 1u) / blocks);
+            if (!push(b, job[k], (int64_t)((groups[k] + job[k].groups_per_block - 1u) / job[k].groups_per_block)))
+                return FH_ERR_BAD_NUMEL;                      // cannot happen: a stream has at most 2^16 groups
         }
         seal(b);
         if (b.count > 0) {
