@@ -21,8 +21,9 @@
 //               slice, are collected in LDS and stored with consecutive lanes on consecutive words.
 // Decoding needs no pass but one: the offsets are part of the stream.  A workgroup rebuilds the
 // canonical tables from the 256 lengths (a 12-bit lookup table for the short codes, first-code /
-// count comparisons for the longer ones), stages the payload slice of 256 chunks in LDS, and a
-// thread decodes its chunk from there; the tables serve several such groups in long streams.
+// count comparisons for the longer ones), stages the payload slice of 768 chunks in LDS (150 of
+// the compute unit's 160 KiB: one workgroup of twelve waves each), and a thread decodes its chunk
+// from there; the tables serve several such groups in long streams.
 // Everything here is integer work; results do not depend on launch geometry.
 #include "../../include/fedhybrid.h"
 
@@ -41,7 +42,11 @@ constexpr int kHistBlocksMax = 640;                // histogram workgroups per s
 constexpr int kFastBits = 12;
 constexpr int kBurst = 8;                          // decode: 16-byte output vectors held back and stored together
 constexpr int kWriteStageWords = 12288;            // encode: LDS for a workgroup's payload slice (256 chunks of 48 words)
-constexpr int kStageWords = 13056;                 // decode: LDS for a workgroup's payload slice (256 chunks of 51 words)
+// decode: chunks per workgroup.  The payload slice in LDS is what limits the chunks in flight on a compute unit,
+// and the decode waits on dependent instructions, not on a unit: one workgroup with the whole LDS holds 768
+// chunks (twelve waves) where workgroups of 256 with their own tables held 512.
+constexpr int kDecodeThreads = 768;
+constexpr int kStageWords = kDecodeThreads * 48;   // decode: LDS for a workgroup's payload slice (48 words per chunk: 6 bits per symbol)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -66,7 +71,7 @@ struct DecodeJob {
     uint8_t*        out;
     uint64_t        n;
     uint32_t        payload_words, chunks;
-    uint32_t        groups_per_block;                         // groups of 256 chunks a workgroup decodes with one set of tables
+    uint32_t        groups_per_block;                         // groups of 768 chunks a workgroup decodes with one set of tables
 };
 
 // Every pass serves up to kBatch streams (fh_batch.hpp); the per-stream passes take a workgroup per stream.
@@ -538,7 +543,7 @@ __device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst
 // The stream may be foreign: the tables are built from whatever the 256 length bytes say
 // (lengths above 24 count as unused), reads of payload words are bounded by the stream's size
 // (words outside read as zero), and every loop is bounded by the symbol count.
-__global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<DecodeJob> batch)
+__global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Batch<DecodeJob> batch)
 {
     uint32_t block;
     const DecodeJob& job = batch.item[batch_item(batch, blockIdx.x, block)];
@@ -554,8 +559,10 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<De
     __shared__ uint32_t in_wave[kThreads / 64][kMaxLen + 2];  // [w][k]: symbols of length k among wave w's 64
     __shared__ uint16_t fast[1 << kFastBits];                 // next kFastBits bits -> symbol | length << 8; 0: longer code
     __shared__ __align__(16) uint32_t stage[kStageWords + kChunkWordsMax + 8];   // the workgroup's slice of the payload, or the rings
+    // threads 0..255 stand for the 256 symbols while the tables are built; the others only fill and wait
     const uint32_t s = threadIdx.x, wave = s >> 6, lane = s & 63u;
-    uint32_t l = len_in[s];
+    const bool symbol = s < 256u;
+    uint32_t l = symbol ? len_in[s] : 0u;
     if (l > (uint32_t)kMaxLen) l = 0u;
     // thread s is symbol s: its rank among the symbols of its length, by lane masks inside the wave ...
     uint32_t before = 0;
@@ -563,7 +570,7 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<De
     for (int k = 1; k <= kMaxLen; ++k) {
         const uint64_t same = __ballot(l == (uint32_t)k);
         if (l == (uint32_t)k) before = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
-        if (lane == 0) in_wave[wave][k] = (uint32_t)__popcll(same);
+        if (lane == 0 && symbol) in_wave[wave][k] = (uint32_t)__popcll(same);
     }
     __syncthreads();
     if (s < (uint32_t)kMaxLen + 2u) {
@@ -599,7 +606,7 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<De
         uint32_t count_of[kFastBits + 1], first_of[kFastBits + 1], start_of[kFastBits + 1];
 #pragma unroll
         for (int k = 1; k <= kFastBits; ++k) { count_of[k] = per_length[k]; first_of[k] = first[k]; start_of[k] = start[k]; }
-        for (uint32_t i = s; i < (1u << kFastBits); i += kThreads) {  // the short codes: what the next kFastBits bits decode to
+        for (uint32_t i = s; i < (1u << kFastBits); i += kDecodeThreads) {  // the short codes: what the next kFastBits bits decode to
             uint32_t at = 0, length = 0;
 #pragma unroll
             for (int k = kFastBits; k >= 1; --k) {                   // at most one length matches a prefix code
@@ -614,15 +621,15 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<De
     }
     __syncthreads();
 
-    // These tables serve `groups_per_block` groups of 256 chunks, one after the other.  The payload words of
+    // These tables serve `groups_per_block` groups of 768 chunks, one after the other.  The payload words of
     // a group's chunks are one contiguous slice.  When it fits it is brought into LDS with contiguous loads and the
     // threads read their words from there (a thread walking its chunk in memory would fetch a cache line per
     // word); a longer slice, or offsets that do not describe one, go through per-thread rings instead.
-    const uint32_t groups = (chunks + kThreads - 1) / kThreads;
+    const uint32_t groups = (chunks + kDecodeThreads - 1) / kDecodeThreads;
     const uint32_t group_end = (block + 1u) * job.groups_per_block < groups ? (block + 1u) * job.groups_per_block : groups;
     for (uint32_t group = block * job.groups_per_block; group < group_end; ++group) {
-        const uint32_t chunk0 = group * kThreads;
-        const uint32_t chunk1 = chunk0 + kThreads < chunks ? chunk0 + kThreads : chunks;
+        const uint32_t chunk0 = group * kDecodeThreads;
+        const uint32_t chunk1 = chunk0 + kDecodeThreads < chunks ? chunk0 + kDecodeThreads : chunks;
         const uint32_t slice_at = offsets[chunk0], slice_end = offsets[chunk1];
         const bool staged = slice_end >= slice_at && slice_end - slice_at <= (uint32_t)kStageWords && slice_end <= payload_words;
         const uint32_t chunk = chunk0 + threadIdx.x;
@@ -639,11 +646,11 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<De
             const uint32_t slice_words = slice_end - slice_at;
             const uint32_t phase = (uint32_t)(reinterpret_cast<uintptr_t>(payload + slice_at) >> 2) & 3u;
             const uint32_t vectors = (slice_words + phase + 3u) / 4u;
-            for (uint32_t v0 = 0; v0 < vectors; v0 += 8u * kThreads) {
+            for (uint32_t v0 = 0; v0 < vectors; v0 += 8u * kDecodeThreads) {
                 u32x4 got[8];
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    const uint32_t v = v0 + k * kThreads + threadIdx.x;
+                    const uint32_t v = v0 + k * kDecodeThreads + threadIdx.x;
                     const int64_t w = (int64_t)slice_at + 4 * (int64_t)v - phase;  // below zero in the first vector at most
                     const auto word_at = [&](int64_t g) { return g >= 0 && g < (int64_t)payload_words ? payload[g] : 0u; };
                     got[k] = u32x4{0u, 0u, 0u, 0u};
@@ -654,7 +661,7 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<De
                 }
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    const uint32_t v = v0 + k * kThreads + threadIdx.x;
+                    const uint32_t v = v0 + k * kDecodeThreads + threadIdx.x;
                     if (v < vectors) *reinterpret_cast<u32x4*>(stage + 4u * v) = got[k];
                 }
             }
@@ -666,22 +673,22 @@ __global__ __launch_bounds__(kThreads) void huffman_decode_kernel(const Batch<De
             // a ring of eight words per thread: when four have been consumed, the four loaded at the
             // previous refill take their place and the next four are requested, so a load has the time
             // of four words' decoding to arrive
-            uint32_t* mine = stage + threadIdx.x;             // word k of the ring at mine[(k & 7) * kThreads]
+            uint32_t* mine = stage + threadIdx.x;             // word k of the ring at mine[(k & 7) * kDecodeThreads]
             uint32_t pending[4];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) mine[k * kThreads] = first_word + k < payload_words ? payload[first_word + k] : 0u;
+            for (int k = 0; k < 8; ++k) mine[k * kDecodeThreads] = first_word + k < payload_words ? payload[first_word + k] : 0u;
 #pragma unroll
             for (int k = 0; k < 4; ++k) pending[k] = first_word + 8 + k < payload_words ? payload[first_word + 8 + k] : 0u;
             decode_chunk(valid, dst, fast, &tables, [&](uint32_t taken) {
                 if ((taken & 3u) == 0u && taken != 0u) {      // a block of four used up: refill the half of the ring just freed
                     const uint32_t slot = (taken + 4u) & 7u;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) mine[((slot + k) & 7u) * kThreads] = pending[k];
+                    for (int k = 0; k < 4; ++k) mine[((slot + k) & 7u) * kDecodeThreads] = pending[k];
                     const uint32_t at = first_word + taken + 8u;
 #pragma unroll
                     for (int k = 0; k < 4; ++k) pending[k] = at + k < payload_words ? payload[at + k] : 0u;
                 }
-                return mine[(taken & 7u) * kThreads];
+                return mine[(taken & 7u) * kDecodeThreads];
             });
         }
         __syncthreads();                                      // the stage is the next group's
@@ -747,7 +754,7 @@ void launch(Kernel kernel, const Batch<Item>& b, uint32_t grid, hipStream_t s)
 }
 
 
-// workgroups of the decode kernel that the current device holds at once (two per compute unit with its LDS)
+// workgroups of the decode kernel that the current device holds at once (one per compute unit with its LDS)
 int decode_slots()
 {
     static int cached[64] = {0};
@@ -755,7 +762,7 @@ int decode_slots()
     if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return 512;
     if (cached[device] == 0) {
         int per_unit = 0, units = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, huffman_decode_kernel, kThreads, 0) != hipSuccess || per_unit < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, huffman_decode_kernel, kDecodeThreads, 0) != hipSuccess || per_unit < 1)
             per_unit = 1;
         if (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || units < 1) units = 256;
         cached[device] = per_unit * units;
@@ -847,11 +854,11 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
             j.n = it.n;
             j.payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
             j.chunks = (uint32_t)chunks;
-            groups[jobs] = groups_of(it.n);
+            groups[jobs] = (chunks + kDecodeThreads - 1) / kDecodeThreads;   // the decoder's own groups
             total += groups[jobs];
             ++jobs;
         }
-        // A workgroup builds a stream's tables once and then decodes `groups_per_block` groups of 256 chunks.  With
+        // A workgroup builds a stream's tables once and then decodes `groups_per_block` groups of 768 chunks.  With
         // more groups in the launch than workgroups fit on the device at once, every stream gets its share of
         // that many workgroups: all of them are resident from the start and finish together, whereas a launch of
         // 1.4 times as many would run a second, mostly empty round.
@@ -866,7 +873,7 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
         }
         seal(b);
         if (b.count > 0) {
-            launch(huffman_decode_kernel, b, b.block_start[b.count], s);
+            hipLaunchKernelGGL(huffman_decode_kernel, dim3(b.block_start[b.count]), dim3(kDecodeThreads), 0, s, b);
             launched = true;
         }
     }

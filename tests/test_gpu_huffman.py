@@ -52,11 +52,11 @@ def test_sizes_around_vectors_chunks_and_groups(api, n):
 
 @pytest.mark.parametrize("spread", [2.5, 14.0, 0.0])
 def test_streams_long_enough_that_a_workgroup_decodes_several_groups(api, spread):
-    # 600 groups of 256 chunks and a ragged tail: more groups than decoding workgroups fit on the device at once
-    # (two per compute unit), so a workgroup takes two and the last one the ragged one.
+    # The decoder takes 768 chunks per workgroup and one workgroup per compute unit: 300 such groups and a ragged
+    # tail are more than the device holds at once, so a workgroup takes two and the last one the ragged one.
     # spread 14: codes longer than the decoder's fast table occur; 0: uniform bytes, whose 64 words per chunk do
     # not fit the LDS stage of either side (the direct payload stores and the per-thread rings)
-    n = 256 * 256 * 600 + 77
+    n = 256 * 768 * 300 + 77
     rng = np.random.default_rng(int(spread * 10))
     data = (np.clip(np.rint(rng.normal(128, spread, n)), 0, 255) if spread else rng.integers(0, 256, n)).astype(np.uint8)
     _check(api, data, f"spread {spread}")
