@@ -356,30 +356,34 @@ __device__ __forceinline__ void encode_chunk(const uint8_t* in, uint64_t first, 
 {
     uint64_t acc = 0;                                         // the low `filled` bits are pending, oldest on top
     uint32_t filled = 0, written = 0;
+    const auto put = [&](uint32_t e) {                        // e = code << 8 | length
+        const uint32_t l = e & 0xffu;
+        acc = (acc << l) | (e >> 8);
+        filled += l;
+        if (filled >= 32u) {                                  // filled < 32 + 24 before this
+            filled -= 32u;
+            if (written < words) out[written] = (uint32_t)(acc >> filled);
+            ++written;
+        }
+    };
     uint32_t word[4], ahead[4];
     if (valid) load_symbols(in, first, valid, ahead);
-    for (uint32_t i = 0; i < valid; i += 16) {
+    uint32_t i = 0;
+    for (; i + 16 <= valid; i += 16) {                        // whole vectors: sixteen table reads, then the serial part
 #pragma unroll
         for (int k = 0; k < 4; ++k) word[k] = ahead[k];
         // in flight while this vector is coded (four ahead, and all sixteen at once, were measured no faster)
         if (i + 16 < valid) load_symbols(in, first + i + 16, valid - i - 16, ahead);
-        const uint32_t here = valid - i < 16u ? valid - i : 16u;
+        uint32_t e[16];
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+        for (int k = 0; k < 16; ++k) e[k] = table[(word[k >> 2] >> (8 * (k & 3))) & 0xffu];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                if ((uint32_t)(4 * k + b) < here) {
-                    const uint32_t e = table[(word[k] >> (8 * b)) & 0xffu];
-                    const uint32_t l = e & 0xffu;
-                    acc = (acc << l) | (e >> 8);
-                    filled += l;
-                    if (filled >= 32u) {                      // filled < 32 + 24 before this
-                        filled -= 32u;
-                        if (written < words) out[written] = (uint32_t)(acc >> filled);
-                        ++written;
-                    }
-                }
-            }
+        for (int k = 0; k < 16; ++k) put(e[k]);
+    }
+    if (i < valid) {                                          // the stream's last chunk may end inside a vector
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (i + k < valid) put(table[(ahead[k >> 2] >> (8 * (k & 3))) & 0xffu]);
     }
     if (filled && written < words) out[written] = (uint32_t)(acc << (32u - filled));   // zero-padded to a whole word
 }
