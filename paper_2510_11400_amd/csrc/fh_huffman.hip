@@ -154,19 +154,25 @@ __global__ __launch_bounds__(256) void huffman_code_kernel(const Batch<Layout> b
         rank -= 256u - (uint32_t)m;
         if (c != 0) weight[rank] = c;
         __syncthreads();
-        if (s == 0) {
-            deepest = 0u;
-            if (m > 1) {
-                // The first two nodes of either queue stay in registers, so that taking a node starts the LDS
-                // read of the one after next and nothing waits for it until a further node has been taken.
-                // kNone stands for a node that does not exist (yet): only the root can weigh 2^32 - 1, and the
-                // root is never compared.  One of the fronts always exists: before a merge the queues hold two
-                // nodes or more.
+        if (wave == 0) {
+            // The merges are one chain of dependent steps.  The whole first wave runs it with every value the same
+            // in all lanes and made known as such (readfirstlane), so that counters, comparisons and branches are
+            // scalar instructions; the lanes' LDS stores write one value to one address.
+            if (lane == 0) deepest = 0u;
+            const uint32_t mm = (uint32_t)__builtin_amdgcn_readfirstlane(m);
+            if (mm > 1u) {
+                // The first two nodes of either queue are at hand -- the front as a scalar, the one behind it
+                // requested from LDS when the front was taken -- so that nothing waits for LDS until a further
+                // node has been taken.  kNone stands for a node that does not exist (yet): only the root can
+                // weigh 2^32 - 1, and the root is never compared.  One of the fronts always exists: before a
+                // merge the queues hold two nodes or more.
                 constexpr uint32_t kNone = ~(uint32_t)0;
-                int next_leaf = 0, next_internal = m, made = m;
-                uint32_t leaf0 = weight[0], leaf1 = weight[1];        // leaves next_leaf and next_leaf + 1
-                uint32_t node0 = kNone, node1 = kNone;                // internal nodes next_internal and next_internal + 1
-                while (made < 2 * m - 1) {                    // at most 255 merges
+                uint32_t next_leaf = 0, next_internal = mm, made = mm;
+                uint32_t leaf0 = (uint32_t)__builtin_amdgcn_readfirstlane(weight[0]);     // leaf next_leaf
+                uint32_t leaf1 = weight[1];                                             // leaf next_leaf + 1, in flight
+                uint32_t node0 = kNone;                                                 // internal node next_internal
+                uint32_t node1 = kNone;                                                 // internal node next_internal + 1
+                while (made < 2u * mm - 1u) {                 // at most 255 merges
                     uint32_t sum = 0;
 #pragma unroll
                     for (int k = 0; k < 2; ++k) {
@@ -174,19 +180,19 @@ __global__ __launch_bounds__(256) void huffman_code_kernel(const Batch<Layout> b
                             sum += leaf0;
                             parent[next_leaf] = (uint16_t)made;
                             ++next_leaf;
-                            leaf0 = leaf1;
-                            leaf1 = next_leaf + 1 < m ? weight[next_leaf + 1] : kNone;
+                            leaf0 = (uint32_t)__builtin_amdgcn_readfirstlane(leaf1);
+                            leaf1 = next_leaf + 1u < mm ? weight[next_leaf + 1u] : kNone;
                         } else {
                             sum += node0;
                             parent[next_internal] = (uint16_t)made;
                             ++next_internal;
-                            node0 = node1;
-                            node1 = next_internal + 1 < made ? weight[next_internal + 1] : kNone;
+                            node0 = (uint32_t)__builtin_amdgcn_readfirstlane(node1);
+                            node1 = next_internal + 1u < made ? weight[next_internal + 1u] : kNone;
                         }
                     }
                     weight[made] = sum;
                     if (made == next_internal) node0 = sum;           // the new node is the queue's front,
-                    else if (made == next_internal + 1) node1 = sum;  // or the one behind it
+                    else if (made == next_internal + 1u) node1 = sum; // or the one behind it
                     ++made;
                 }
             }
