@@ -63,7 +63,8 @@ typedef enum fh_status {
     FH_ERR_LAUNCH = 9,           /* the HIP runtime refused the launch */
     FH_ERR_BAD_COUNT = 10,       /* negative item count */
     FH_ERR_BAD_SHAPE = 11,       /* outer / channels / inner / raw_channels out of range */
-    FH_ERR_BAD_PARAM = 12        /* k_sigma not positive, min_outliers < 1, or a pooling window other than 2, 4, 8 */
+    FH_ERR_BAD_PARAM = 12        /* k_sigma not positive, min_outliers < 1, a pooling window other than 2, 4, 8,
+                                    or a reserved field that is not 0 */
 } fh_status;
 
 typedef enum fh_dtype { FH_F32 = 0, FH_BF16 = 1 } fh_dtype;

@@ -253,6 +253,16 @@ def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
     return int(s.cuda_stream)
 
 
+def _scratch(nbytes: int, device, stream: Optional[torch.cuda.Stream]) -> torch.Tensor:
+    """A temporary device buffer for work enqueued on `stream`.  The caching allocator hands a
+    freed block to the next allocation on the stream it was allocated on (the current one), so a
+    buffer a kernel on ANOTHER stream still uses is marked as in use there before it is dropped."""
+    t = torch.empty(max(16, int(nbytes)), dtype=torch.uint8, device=device)
+    if stream is not None:
+        t.record_stream(stream)
+    return t
+
+
 def make_params(group_size: int, bits: int, rounding="nearest", seed: int = 0, tensor_id: int = 0) -> fh_params:
     return fh_params(int(group_size), int(bits), _ROUND[rounding], 0,
                      int(seed) & 0xFFFFFFFFFFFFFFFF, int(tensor_id) & 0xFFFFFFFFFFFFFFFF)
@@ -399,7 +409,7 @@ def fh_classify_channels(x: torch.Tensor, outer: int, channels: int, inner: int,
         raise ValueError("x.numel() != outer * channels * inner")
     dev = x.device
     if workspace is None:
-        workspace = torch.empty(classify_workspace_bytes(x.numel()), dtype=torch.uint8, device=dev)
+        workspace = _scratch(classify_workspace_bytes(x.numel()), dev, stream)
     if stats is None:
         stats = torch.empty(4, dtype=torch.float64, device=dev)
     if counts is None:
@@ -560,7 +570,7 @@ def fh_sparse_decode(info: torch.Tensor, values: torch.Tensor, indices: torch.Te
     if out is None:
         out = torch.empty(maps * h * w, dtype=values.dtype, device=info.device)
     if workspace is None:
-        workspace = torch.empty(max(8, sparse_workspace_bytes(maps, h, w, n)), dtype=torch.uint8, device=info.device)
+        workspace = _scratch(sparse_workspace_bytes(maps, h, w, n), info.device, stream)
     _device_tensor(out, "out")
     _device_tensor(workspace, "workspace")
     if _nbytes(info) < sparse_info_bytes(maps, h, w, n) or out.dtype != values.dtype:
@@ -594,7 +604,7 @@ def fh_huffman_encode(data: torch.Tensor, stream_out: Optional[torch.Tensor] = N
     if totals is None:
         totals = torch.zeros(2, dtype=torch.int64, device=data.device)
     if workspace is None:
-        workspace = torch.empty(huffman_workspace_bytes(n), dtype=torch.uint8, device=data.device)
+        workspace = _scratch(huffman_workspace_bytes(n), data.device, stream)
     for t, what in ((stream_out, "stream_out"), (totals, "totals"), (workspace, "workspace")):
         _device_tensor(t, what)
     if _nbytes(totals) < 16:

@@ -22,6 +22,7 @@ fh_status check_params(const fh_params* p, bool need_round)
     if (p->bits != 2 && p->bits != 4 && p->bits != 8) return FH_ERR_BAD_BITS;
     if (need_round && p->rounding != FH_ROUND_NEAREST && p->rounding != FH_ROUND_STOCHASTIC)
         return FH_ERR_BAD_ROUND;
+    if (p->reserved != 0) return FH_ERR_BAD_PARAM;
     return FH_OK;
 }
 
@@ -252,7 +253,7 @@ const char* fh_status_string(fh_status s)
         case FH_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
         case FH_ERR_BAD_COUNT: return "item count is negative";
         case FH_ERR_BAD_SHAPE: return "outer / maps must be >= 0, inner / h / w >= 1, channels in 1..16384, raw_channels in 0..channels";
-        case FH_ERR_BAD_PARAM: return "k_sigma must be positive, min_outliers at least 1, the pooling window 2, 4 or 8";
+        case FH_ERR_BAD_PARAM: return "k_sigma must be positive, min_outliers at least 1, the pooling window 2, 4 or 8, every reserved field 0";
     }
     return "unknown status";
 }

@@ -416,6 +416,7 @@ using namespace fh;
 fh_status check_item(const fh_classify_item& it, int64_t* numel_out)
 {
     if (it.x_dtype != FH_F32 && it.x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if (it.reserved != 0) return FH_ERR_BAD_PARAM;
     if (it.outer < 0 || it.inner < 1 || it.channels < 1 || it.channels > kMaxChannels) return FH_ERR_BAD_SHAPE;
     if (it.inner > (int64_t)1 << 31 || it.outer > (int64_t)1 << 40) return FH_ERR_BAD_SHAPE;
     if (!(it.k_sigma > 0.0) || it.min_outliers < 1) return FH_ERR_BAD_PARAM;

@@ -69,6 +69,7 @@ fh_status check_quantiser(const fh_params* p, bool need_round)
     if (p->group_size != 64 && p->group_size != 128 && p->group_size != 256) return FH_ERR_BAD_GROUP;
     if (p->bits != 2 && p->bits != 4 && p->bits != 8) return FH_ERR_BAD_BITS;
     if (need_round && p->rounding != FH_ROUND_NEAREST && p->rounding != FH_ROUND_STOCHASTIC) return FH_ERR_BAD_ROUND;
+    if (p->reserved != 0) return FH_ERR_BAD_PARAM;
     return FH_OK;
 }
 
@@ -118,6 +119,7 @@ fh_status check_compress(const fh_mixed_item& it, int64_t* numel)
 {
     fh_status s;
     if ((s = check_quantiser(&it.params, true)) != FH_OK) return s;
+    if (it.reserved != 0) return FH_ERR_BAD_PARAM;
     if (it.x_dtype != FH_F32 && it.x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
     if ((s = check_shape(it.outer, it.channels, it.inner, it.raw_channels, numel)) != FH_OK) return s;
     if (*numel == 0) return FH_OK;
@@ -135,6 +137,7 @@ fh_status check_decompress(const fh_mixed_item& it, int64_t* numel)
 {
     fh_status s;
     if ((s = check_quantiser(&it.params, false)) != FH_OK) return s;
+    if (it.reserved != 0) return FH_ERR_BAD_PARAM;
     if (it.raw_dtype != FH_F32 && it.raw_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
     if (it.out_dtype != FH_F32 && it.out_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
     if ((s = check_shape(it.outer, it.channels, it.inner, it.raw_channels, numel)) != FH_OK) return s;

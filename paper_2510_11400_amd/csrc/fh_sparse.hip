@@ -814,6 +814,7 @@ fh_status check_encode(const fh_sparse_encode_item& it, int64_t* tiles)
 fh_status check_decode(const fh_sparse_decode_item& it, int64_t* tiles)
 {
     if (it.dtype != FH_F32 && it.dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
+    if (it.reserved != 0) return FH_ERR_BAD_PARAM;
     const fh_status st = check_shape(it.maps, it.h, it.w, it.n, tiles);
     if (st != FH_OK) return st;
     if (*tiles == 0) return FH_OK;

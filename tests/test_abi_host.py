@@ -349,3 +349,30 @@ def test_huffman_item_layouts_and_batch_argument_checks():
     dec[0].stream_in = dec[0].out = 0x10000
     dec[0].n, dec[0].stream_bytes, dec[0].out_cap = 100, 100, 100
     assert lib.fh_huffman_decode_batch(dec, 1, None) == 7
+
+
+def test_reserved_fields_must_be_zero():
+    lib = api.raw_library()
+    p = api.fh_params(256, 4, 0, 1, 0, 0)                      # reserved = 1
+    assert lib.fh_compress(FAKE, 0, 1024, ctypes.byref(p), FAKE, 1 << 20, FAKE, 1 << 20, None) == 12
+    assert lib.fh_decompress(FAKE, FAKE, 1024, ctypes.byref(p), 0, FAKE, 1 << 20, None) == 12
+    assert lib.fh_roundtrip(FAKE, 0, 1024, ctypes.byref(p), FAKE, 1 << 20, FAKE, 1 << 20, 0, FAKE, 1 << 20, None) == 12
+    it = api.fh_classify_item(FAKE, 0, 7, 4, 8, 16, 3.0, 1, FAKE, 1 << 20, FAKE, FAKE, FAKE)
+    assert lib.fh_classify_channels_batch((api.fh_classify_item * 1)(it), 1, None) == 12
+    arr = (api.fh_mixed_item * 1)()
+    m = arr[0]
+    m.x, m.outer, m.channels, m.inner, m.slots, m.raw_channels = FAKE, 4, 8, 16, FAKE, 2
+    m.packed, m.packed_cap, m.meta, m.meta_cap, m.raw, m.raw_cap = FAKE, 1 << 20, FAKE, 1 << 20, FAKE, 1 << 20
+    m.out, m.out_cap = FAKE, 1 << 20
+    m.params = api.make_params(64, 4)
+    m.reserved = 3
+    assert lib.fh_compress_mixed_batch(arr, 1, None) == 12 and lib.fh_decompress_mixed_batch(arr, 1, None) == 12
+    m.reserved = 0
+    m.params.reserved = 1
+    assert lib.fh_compress_mixed_batch(arr, 1, None) == 12 and lib.fh_decompress_mixed_batch(arr, 1, None) == 12
+    dec = (api.fh_sparse_decode_item * 1)()
+    d = dec[0]
+    d.info = d.values = d.indices = d.out = d.workspace = FAKE
+    d.values_bytes = d.indices_bytes = d.out_cap = d.workspace_cap = 1 << 20
+    d.dtype, d.n, d.maps, d.h, d.w, d.eps, d.reserved = 0, 4, 4, 10, 10, 0.0, 9
+    assert lib.fh_sparse_decode_batch(dec, 1, None) == 12
