@@ -592,6 +592,9 @@ def main() -> int:
     ap.add_argument("--warm", action="store_true",
                     help="--op roundtrip: time compress and decompress back to back (codes still in the "
                          "memory-side cache) instead of the cold protocol")
+    ap.add_argument("--displace", choices=("read", "write"), default="read",
+                    help="--op roundtrip, cold protocol: what the untimed pass that displaces the memory-side "
+                         "cache does with its 1 GiB buffer")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()
@@ -652,25 +655,34 @@ def main() -> int:
     cold = not (args.warm or args.per_tensor)
     # The forward pass saves a tensor long before the backward pass restores it, so nothing a
     # compress call wrote is still in the memory-side cache (256 MB) when its decompress call
-    # runs.  The cold protocol reproduces that: an untimed 1 GiB device write on the same stream
-    # displaces the cache before each of the two calls; the calls are timed by their own events.
-    scrub = torch.empty(1 << 30, dtype=torch.uint8, device=dev) if cold else None
+    # runs.  The cold protocol reproduces that: an untimed pass over a 1 GiB buffer on the same
+    # stream displaces the cache before each of the two calls; the calls are timed by their own
+    # events.  The pass READS the buffer (--displace read): a pass that writes leaves 256 MB of
+    # modified lines behind, whose write-back to HBM then happens inside the timed call although
+    # it is the displacing pass's traffic (--displace write measures exactly that).
+    scrub = torch.zeros(1 << 28, dtype=torch.int32, device=dev) if cold else None
 
-    def step(events=None, displace=False):
+    def displace_cache(how):
+        if how == "write":
+            scrub.fill_(1)
+        else:
+            torch.amax(scrub)
+
+    def step(events=None, displace=None):
         if args.per_tensor:
             for e in entries:
                 api.fh_roundtrip(e.x, e.group_size, e.bits, e.rounding, e.seed, e.tensor_id,
                                  packed=e.packed, meta=e.meta, out=e.out, stream=stream)
             return
         if displace:
-            scrub.fill_(1)
+            displace_cache(displace)
         if events is not None:
             events[0].record(stream)
         api.fh_compress_batch(batch, stream)
         if events is not None:
             events[1].record(stream)
         if displace:
-            scrub.fill_(2)
+            displace_cache(displace)
         if events is not None:
             events[2].record(stream)
         api.fh_decompress_batch(batch, stream)
@@ -678,7 +690,7 @@ def main() -> int:
             events[3].record(stream)
 
     for _ in range(args.warmup):
-        step(displace=cold)
+        step(displace=args.displace if cold else None)
     torch.cuda.synchronize()
 
     if args.copy_calibration > 0:
@@ -703,7 +715,7 @@ def main() -> int:
         d_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
         return wall, c_ms, d_ms
 
-    wall, c_ms, d_ms = timed_loop(cold)
+    wall, c_ms, d_ms = timed_loop(args.displace if cold else None)
     # cold: a step's time is that of its two calls (the displacing writes lie outside both
     # event intervals); otherwise the wall clock over the back-to-back steps
     step_s = (c_ms + d_ms) * 1e-3 if cold else wall
@@ -719,14 +731,14 @@ def main() -> int:
                    "group_size": w.tensors[0].group_size,
                    "bits": sorted({t.bits for t in w.tensors}),
                    "rounding": sorted({t.rounding for t in w.tensors}),
-                   "protocol": ("cold: memory-side cache displaced by an untimed 1 GiB write before compress and "
-                                "before decompress; step time = event-timed compress + decompress") if cold
+                   "protocol": (f"cold: memory-side cache displaced by an untimed 1 GiB {args.displace} pass before "
+                                "compress and before decompress; step time = event-timed compress + decompress") if cold
                    else "warm: compress and decompress back to back, wall clock"},
         "round_trip_algorithmic_bytes": cbytes + dbytes,
         "hbm_frac_round_trip": round((cbytes + dbytes) / step_s / 1e9 / HBM_PEAK_GBS, 4),
     }
     if cold:
-        result["wall_ms_per_step_with_displacing_writes"] = round(wall * 1e3, 4)
+        result["wall_ms_per_step_with_displacing_passes"] = round(wall * 1e3, 4)
 
     def kernel_block(c_ms, d_ms):
         return {"compress_kernel": {"ms": round(c_ms, 4), "bytes": cbytes, "GBps": round(cbytes / c_ms / 1e6, 1)},
@@ -747,10 +759,17 @@ def main() -> int:
     if cold:
         # the same steps back to back, where the backward side finds the most recently written
         # codes in the memory-side cache
-        wall_w, cw_ms, dw_ms = timed_loop(False)
+        wall_w, cw_ms, dw_ms = timed_loop(None)
         result["warm_codes"] = {"ms_per_step": round(wall_w * 1e3, 4), "value": round(w.nbytes / wall_w / 1e9, 2),
                                 "hbm_frac_round_trip": round((cbytes + dbytes) / wall_w / 1e9 / HBM_PEAK_GBS, 4),
                                 "kernels": kernel_block(cw_ms, dw_ms)}
+        # and with the other kind of displacing pass (see the comment above)
+        other = "write" if args.displace == "read" else "read"
+        _, co_ms, do_ms = timed_loop(other)
+        result["cold_after_" + other + "_pass"] = {
+            "ms_per_step": round(co_ms + do_ms, 4),
+            "hbm_frac_round_trip": round((cbytes + dbytes) / (co_ms + do_ms) / 1e6 / HBM_PEAK_GBS, 4),
+            "kernels": kernel_block(co_ms, do_ms)}
     del scrub
 
     if not args.no_cpu_baseline:

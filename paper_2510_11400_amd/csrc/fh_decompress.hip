@@ -21,14 +21,8 @@ namespace fh {
 
 namespace {
 
-#ifndef FH_DECOMPRESS_ROWS
-#define FH_DECOMPRESS_ROWS 2
-#endif
-#ifndef FH_DECOMPRESS_BLOCK
-#define FH_DECOMPRESS_BLOCK 256
-#endif
-constexpr int kDBlock = FH_DECOMPRESS_BLOCK;       // threads per workgroup
-constexpr int kRowsPerWave = FH_DECOMPRESS_ROWS;   // rows whose loads are issued before any store
+constexpr int kDBlock = 256;                       // threads per workgroup
+constexpr int kRowsPerWave = 2;                    // rows whose loads are issued before any store (1 and 4 measure slower)
 
 template <typename OutT> struct OutTraits;
 template <> struct OutTraits<float>    { static constexpr int EPL = 4; };
@@ -53,12 +47,12 @@ __device__ __forceinline__ void load_codes(const uint8_t* packed, int64_t i0, ui
     const uint64_t off = (uint64_t)i0 * B / 8;                // byte offset, multiple of NBITS/8
     c1 = 0u;
     if constexpr (NBITS == 64) {
-        const u32x2 w = *reinterpret_cast<const u32x2*>(packed + off);
+        const u32x2 w = code_load(reinterpret_cast<const u32x2*>(packed + off));
         c0 = w.x; c1 = w.y;
     } else if constexpr (NBITS == 32) {
-        c0 = *reinterpret_cast<const uint32_t*>(packed + off);
+        c0 = code_load(reinterpret_cast<const uint32_t*>(packed + off));
     } else {                                                  // 16 or 8 bits inside an aligned word
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(packed + (off & ~(uint64_t)3));
+        const uint32_t w = code_load(reinterpret_cast<const uint32_t*>(packed + (off & ~(uint64_t)3)));
         c0 = (w >> (((uint32_t)off & 3u) * 8u)) & ((1u << NBITS) - 1u);
     }
 }
@@ -161,7 +155,7 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
         for (int r = 0; r < kRowsPerWave; ++r) {
             const int64_t i0 = wave_base + r * ROW + lane * EPL;
             load_codes<EPL, B>(it.packed, i0, c0[r], c1[r]);
-            m[r] = *reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v));
+            m[r] = code_load(reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v)));
         }
         if constexpr (MIXED) {
             if (one_channel_per_element<EPL>(*cm)) {          // wave-uniform
@@ -255,11 +249,7 @@ __global__ __launch_bounds__(kDBlock) void decompress_kernel(const DecompressBat
     // Tiles are taken from the end of the set backwards: the backward pass needs the
     // tensors in the reverse of the order the forward pass saved them, and the codes
     // written last are the ones most likely still held by the memory-side cache.
-#ifndef FH_DECOMPRESS_FORWARD
     const uint32_t bid = gridDim.x - 1u - blockIdx.x;
-#else
-    const uint32_t bid = blockIdx.x;
-#endif
     const int lo = find_item(args.tile_start, bid);
     const DecompressItem it = args.item[lo];                  // by value: one batch of scalar loads
     const uint32_t tile = bid - args.tile_start[lo];

@@ -16,46 +16,23 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float    f32x2 __attribute__((ext_vector_type(2)));
 
 // ---- streaming memory access --------------------------------------------------------
-// The activation, the code stream and the restored tensor are each touched once per
-// call, so they are loaded and stored with the non-temporal hint where that measures
-// faster (FH_NT_LOAD / FH_NT_STORE, decided by measurement on MI355X).
-#ifndef FH_NT_LOAD
-#define FH_NT_LOAD 1
-#endif
-#ifndef FH_NT_STORE
-#define FH_NT_STORE 1
-#endif
+// The activation and the restored tensor are each touched once per call and are far larger
+// than any cache: they are loaded and stored with the non-temporal hint (measured on MI355X:
+// ordinary loads of the activation evict the code stream from the memory-side cache and cost
+// the round trip 15 %).
 template <typename T>
-__device__ __forceinline__ T stream_load(const T* p)
-{
-#if FH_NT_LOAD
-    return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
-}
-#ifndef FH_NT_CODE_STORE
-#define FH_NT_CODE_STORE 0
-#endif
-// The code stream is small and is read back by the backward side.
+__device__ __forceinline__ T stream_load(const T* p) { return __builtin_nontemporal_load(p); }
 template <typename T>
-__device__ __forceinline__ void code_store(T* p, T v)
-{
-#if FH_NT_CODE_STORE
-    __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
-}
+__device__ __forceinline__ void stream_store(T* p, T v) { __builtin_nontemporal_store(v, p); }
+// The code stream and the meta pairs are small and are read back by the backward side: ordinary
+// stores and loads.  Measured with the memory-side cache displaced between the two sides
+// (2 GiB mixed set): non-temporal code stores cost the forward side 3 %, non-temporal code
+// loads the backward side 8 % (lanes share the words they read); with the two sides back to
+// back, ordinary accesses let the backward side find the latest codes in that cache.
 template <typename T>
-__device__ __forceinline__ void stream_store(T* p, T v)
-{
-#if FH_NT_STORE
-    __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
-}
+__device__ __forceinline__ void code_store(T* p, T v) { *p = v; }
+template <typename T>
+__device__ __forceinline__ T code_load(const T* p) { return *p; }
 
 // ---- min / max ---------------------------------------------------------------------
 // Written as the machine instructions themselves.  The inputs are finite by contract,
