@@ -63,8 +63,9 @@ typedef enum fh_status {
     FH_ERR_LAUNCH = 9,           /* the HIP runtime refused the launch */
     FH_ERR_BAD_COUNT = 10,       /* negative item count */
     FH_ERR_BAD_SHAPE = 11,       /* outer / channels / inner / raw_channels out of range */
-    FH_ERR_BAD_PARAM = 12        /* k_sigma not positive, min_outliers < 1, a pooling window other than 2, 4, 8,
+    FH_ERR_BAD_PARAM = 12,       /* k_sigma not positive, min_outliers < 1, a pooling window other than 2, 4, 8,
                                     or a reserved field that is not 0 */
+    FH_ERR_SCRATCH_LIMIT = 13    /* the tensor needs more scratch than the library's static buffer holds */
 } fh_status;
 
 typedef enum fh_dtype { FH_F32 = 0, FH_BF16 = 1 } fh_dtype;
@@ -161,6 +162,22 @@ fh_status fh_classify_channels(const void *x, fh_dtype x_dtype, int64_t outer, i
                                double k_sigma, int64_t min_outliers,
                                void *workspace, size_t workspace_cap,
                                void *stats, void *counts, void *mask, void *stream);
+
+/* fh_classify_channels for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid allocation.
+ * The partial sums go to a buffer that is part of the library itself (a device array of
+ * fh_classify_static_scratch_bytes() = 4 MiB, held by every GPU the library runs on until the
+ * process ends), so the call allocates nothing; inputs and outputs are still the caller's.
+ * Results are identical to fh_classify_channels.  A tensor whose
+ * fh_classify_workspace_bytes() exceeds that size (more than about 2.68e8 elements) is refused
+ * with FH_ERR_SCRATCH_LIMIT before anything is launched.  All calls on one GPU share the
+ * buffer: calls that may overlap on one GPU (different streams, different host threads) race;
+ * calls on one stream are ordered and safe.  The device is the current one, and `stream` must
+ * belong to it. */
+size_t    fh_classify_static_scratch_bytes(void);
+fh_status fh_classify_channels_static(const void *x, fh_dtype x_dtype, int64_t outer, int64_t channels,
+                                      int64_t inner, double k_sigma, int64_t min_outliers,
+                                      void *stats, void *counts, void *mask, void *stream);
 
 /* ---- salient channels routed around the quantiser ----------------------------------------
  * Section 4.4.1 quantises only the normal channels, so that the outliers clustered in the

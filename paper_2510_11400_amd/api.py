@@ -31,7 +31,7 @@ FH_ROUND_NEAREST, FH_ROUND_STOCHASTIC = 0, 1
 EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "fh_roundtrip",
            "fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch", "fh_batch_capacity",
            "fh_classify_workspace_bytes", "fh_classify_channels", "fh_classify_channels_batch",
-           "fh_classify_batch_capacity",
+           "fh_classify_batch_capacity", "fh_classify_static_scratch_bytes", "fh_classify_channels_static",
            "fh_raw_bytes", "fh_channel_slots", "fh_compress_mixed", "fh_decompress_mixed",
            "fh_compress_mixed_batch", "fh_decompress_mixed_batch", "fh_mixed_batch_capacity",
            "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
@@ -119,6 +119,12 @@ _lib.fh_classify_channels.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_in
                                       ctypes.c_double, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.fh_classify_channels.restype = ctypes.c_int
+_lib.fh_classify_static_scratch_bytes.argtypes = []
+_lib.fh_classify_static_scratch_bytes.restype = ctypes.c_size_t
+_lib.fh_classify_channels_static.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                             ctypes.c_int64, ctypes.c_double, ctypes.c_int64,
+                                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.fh_classify_channels_static.restype = ctypes.c_int
 _lib.fh_classify_channels_batch.argtypes = [_P(fh_classify_item), ctypes.c_int32, ctypes.c_void_p]
 _lib.fh_classify_channels_batch.restype = ctypes.c_int
 _lib.fh_classify_batch_capacity.argtypes = []
@@ -427,6 +433,28 @@ def fh_classify_channels(x: torch.Tensor, outer: int, channels: int, inner: int,
                                          workspace.numel() * workspace.element_size(),
                                          stats.data_ptr(), counts.data_ptr(), mask.data_ptr(), _stream_ptr(stream)))
     return stats, counts, mask
+
+
+def classify_static_scratch_bytes() -> int:
+    return int(_lib.fh_classify_static_scratch_bytes())
+
+
+def fh_classify_channels_static(x: torch.Tensor, outer: int, channels: int, inner: int, k_sigma: float,
+                                min_outliers: int, stats: torch.Tensor, counts: torch.Tensor, mask: torch.Tensor,
+                                stream=None) -> None:
+    """fh_classify_channels with the partial sums in the library's own static device buffer: the
+    call allocates nothing, so every output is the caller's (stats float64[4], counts int32
+    [channels], mask uint8[channels])."""
+    for t, what in ((x, "x"), (stats, "stats"), (counts, "counts"), (mask, "mask")):
+        _device_tensor(t, what)
+    if x.numel() != outer * channels * inner:
+        raise ValueError("x.numel() != outer * channels * inner")
+    if _nbytes(stats) < 32 or _nbytes(counts) < 4 * channels or _nbytes(mask) < channels:
+        raise FedHybridError(7)
+    with torch.cuda.device(x.device):
+        _check(_lib.fh_classify_channels_static(x.data_ptr(), _dtype_code(x), outer, channels, inner,
+                                                float(k_sigma), int(min_outliers), stats.data_ptr(),
+                                                counts.data_ptr(), mask.data_ptr(), _stream_ptr(stream)))
 
 
 def raw_bytes(outer: int, raw_channels: int, inner: int, dtype) -> int:

@@ -254,6 +254,7 @@ const char* fh_status_string(fh_status s)
         case FH_ERR_BAD_COUNT: return "item count is negative";
         case FH_ERR_BAD_SHAPE: return "outer / maps must be >= 0, inner / h / w >= 1, channels in 1..16384, raw_channels in 0..channels";
         case FH_ERR_BAD_PARAM: return "k_sigma must be positive, min_outliers at least 1, the pooling window 2, 4 or 8, every reserved field 0";
+        case FH_ERR_SCRATCH_LIMIT: return "the tensor needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }

@@ -25,6 +25,8 @@
 
 #include <limits.h>
 
+#include <mutex>
+
 namespace fh {
 namespace {
 
@@ -409,9 +411,39 @@ size_t fh_classify_workspace_bytes(int64_t numel)
 
 }  // extern "C"
 
+// ---- partial sums in a buffer of the library's own -------------------------------------------
+// For callers that cannot allocate (HIP graph capture, serving loops, harnesses that forbid it):
+// the workspace of the partial-sum tree as a device array that is part of the code object.  Each
+// GPU the library runs on holds its own copy at its own address until the process ends; every
+// call on a GPU shares it, so calls that overlap on one GPU race.  Nothing in it has to start
+// at zero: every level of the tree is written in full before it is read.
+constexpr size_t kScratchBytes = (size_t)4 << 20;           // serves up to 2^28 - 2^18 elements
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 using namespace fh;
+
+// The device address of `scratch` on the current device.  In host code the array's name is only
+// a handle for hipGetSymbolAddress, never an address a kernel may be given; the address is
+// asked for once per device, with that device current, and kept.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+fh_status scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FH_ERR_LAUNCH;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FH_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FH_OK;
+}
 
 fh_status check_item(const fh_classify_item& it, int64_t* numel_out)
 {
@@ -556,6 +588,26 @@ fh_status fh_classify_channels(const void* x, fh_dtype x_dtype, int64_t outer, i
     it.workspace = workspace; it.workspace_cap = workspace_cap;
     it.stats = stats; it.counts = counts; it.mask = mask;
     return fh_classify_channels_batch(&it, 1, stream);
+}
+
+size_t fh_classify_static_scratch_bytes(void) { return kScratchBytes; }
+
+fh_status fh_classify_channels_static(const void* x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
+                                      double k_sigma, int64_t min_outliers,
+                                      void* stats, void* counts, void* mask, void* stream)
+{
+    // the size check comes first: a tensor the static buffer cannot serve is refused before
+    // anything else is looked at, and before the buffer's address is asked for
+    if (outer >= 0 && channels >= 1 && inner >= 1) {
+        const double total = (double)outer * (double)channels * (double)inner;
+        if (total > (double)((int64_t)1 << 40)) return FH_ERR_BAD_NUMEL;
+        if (fh_classify_workspace_bytes(outer * channels * inner) > kScratchBytes) return FH_ERR_SCRATCH_LIMIT;
+    }
+    void* ws = nullptr;
+    const fh_status st = scratch_of_current_device(&ws);
+    if (st != FH_OK) return st;
+    return fh_classify_channels(x, x_dtype, outer, channels, inner, k_sigma, min_outliers, ws, kScratchBytes,
+                                stats, counts, mask, stream);
 }
 
 }  // extern "C"

@@ -376,3 +376,15 @@ def test_reserved_fields_must_be_zero():
     d.values_bytes = d.indices_bytes = d.out_cap = d.workspace_cap = 1 << 20
     d.dtype, d.n, d.maps, d.h, d.w, d.eps, d.reserved = 0, 4, 4, 10, 10, 0.0, 9
     assert lib.fh_sparse_decode_batch(dec, 1, None) == 12
+
+
+def test_static_scratch_entry_point_refuses_oversized_tensors_on_the_host():
+    lib = api.raw_library()
+    limit = api.classify_static_scratch_bytes()
+    assert limit == 4 << 20
+    n_ok = 261_887 * 1024                        # 261887 + 256 + 1 partial-sum pairs of 16 bytes = 4 MiB
+    assert api.classify_workspace_bytes(n_ok) == limit < api.classify_workspace_bytes(n_ok + 1)
+    # refused before the device is even asked for the buffer's address (no GPU needed here)
+    assert lib.fh_classify_channels_static(FAKE, 0, 1, 1, n_ok + 1, 3.0, 1, FAKE, FAKE, FAKE, None) == 13
+    assert lib.fh_classify_channels_static(FAKE, 0, 4, 1024, 1 << 20, 3.0, 1, FAKE, FAKE, FAKE, None) == 13
+    assert "static buffer" in api.status_string(13)
