@@ -371,17 +371,27 @@ fh_status fh_huffman_decode(const void *stream_in, size_t stream_bytes, uint64_t
 /* The same two calls for several byte buffers: every pass is launched once per run of up to
  * fh_huffman_batch_capacity() items (the code construction, a single workgroup's work per
  * buffer, then runs for all of them side by side).  Everything is checked before the first
- * launch; results identical to the single calls. */
+ * launch; results identical to the single calls.
+ *
+ * n_device: NULL, or a device pointer (8-byte aligned) to a uint64 that holds the symbol count
+ * by the time the stream reaches the call -- for a buffer whose length is itself the output of
+ * an earlier call on the same stream (the index-byte total of fh_sparse_encode), so that the
+ * whole chain can be enqueued without the host reading anything back.  `n` is then an upper
+ * bound: buffers, capacities and launches are sized for it, and the count used is
+ * min(*n_device, n).  The decoder's stream_bytes may then be the capacity of the stream buffer
+ * (at least the size the encoder reported). */
 typedef struct fh_huffman_encode_item {
     const void *bytes;      uint64_t n;
     void       *stream_out; size_t stream_cap;
     void       *totals;
     void       *workspace;  size_t workspace_cap;
+    const void *n_device;
 } fh_huffman_encode_item;
 typedef struct fh_huffman_decode_item {
     const void *stream_in;  size_t stream_bytes;
     uint64_t    n;
     void       *out;        size_t out_cap;
+    const void *n_device;
 } fh_huffman_decode_item;
 fh_status fh_huffman_encode_batch(const fh_huffman_encode_item *items, int32_t count, void *stream);
 fh_status fh_huffman_decode_batch(const fh_huffman_decode_item *items, int32_t count, void *stream);

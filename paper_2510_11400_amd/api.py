@@ -186,12 +186,13 @@ class fh_huffman_encode_item(ctypes.Structure):
     _fields_ = [("bytes", ctypes.c_void_p), ("n", ctypes.c_uint64),
                 ("stream_out", ctypes.c_void_p), ("stream_cap", ctypes.c_size_t),
                 ("totals", ctypes.c_void_p),
-                ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t)]
+                ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t),
+                ("n_device", ctypes.c_void_p)]
 
 
 class fh_huffman_decode_item(ctypes.Structure):
     _fields_ = [("stream_in", ctypes.c_void_p), ("stream_bytes", ctypes.c_size_t), ("n", ctypes.c_uint64),
-                ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t)]
+                ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t), ("n_device", ctypes.c_void_p)]
 
 
 _lib.fh_huffman_encode_batch.argtypes = [_P(fh_huffman_encode_item), ctypes.c_int32, ctypes.c_void_p]
@@ -664,10 +665,14 @@ class HuffmanBatch:
     """Several byte buffers coded with one call each way.  `data`: device uint8 tensors; the
     worst-case sized streams, the totals (int64[2] each: stream bytes in use, payload bits) and
     the scratch are allocated here once.  After an encode has finished, `refresh()` reads the
-    totals back (a synchronising copy) so that decode is given the valid prefixes."""
+    totals back (a synchronising copy) so that decode is given the valid prefixes.
+    `n_device`: per buffer None or a device int64 tensor whose first element holds the number of
+    bytes of `data` that count (the buffer's size is then only the upper bound); with it, decode
+    needs no refresh: the stream's capacity bounds what it reads."""
 
-    def __init__(self, data):
+    def __init__(self, data, n_device=None):
         self.data = list(data)
+        self.n_device = list(n_device) if n_device is not None else [None] * len(self.data)
         for d in self.data:
             _device_tensor(d, "data")
             if d.dtype != torch.uint8:
@@ -690,6 +695,9 @@ class HuffmanBatch:
             q = self.dec[i]
             q.stream_in, q.stream_bytes, q.n = self.streams[i].data_ptr(), _nbytes(self.streams[i]), d.numel()
             q.out, q.out_cap = _ptr(self.out[i]), _nbytes(self.out[i])
+            if self.n_device[i] is not None:
+                _device_tensor(self.n_device[i], "n_device")
+                e.n_device = q.n_device = self.n_device[i].data_ptr()
 
     def refresh(self):
         used = self.totals.cpu()[:, 0].tolist()

@@ -59,17 +59,39 @@ struct Layout {                                    // where things are in the st
     uint32_t* group_sums;                          // workspace: [groups]
     uint64_t* totals;                              // {stream bytes used, payload bits}
     const uint8_t* in;
-    uint64_t  n;
+    uint64_t  n;                                   // symbols (an upper bound when n_dev is set)
+    const uint64_t* n_dev;                         // device: the symbol count, known only on the stream; or null
     uint32_t  chunks, groups;
     uint32_t  hist_blocks;                         // workgroups of the histogram pass
 };
+
+__device__ __forceinline__ uint64_t chunks_for(uint64_t n) { return (n + 255u) >> 8; }
+
+// The layout a kernel works with.  When the symbol count lives in device memory (it is the
+// output of an earlier call on the same stream), the host has sized buffers and grids for an
+// upper bound; the count itself, and what follows from it -- chunks, groups, where the payload
+// starts -- is settled here, and workgroups beyond the real extent find nothing to do.
+__device__ __forceinline__ Layout resolved(const Layout& given)
+{
+    Layout lay = given;
+    if (given.n_dev) {
+        const uint64_t there = *given.n_dev;
+        lay.n = there < given.n ? there : given.n;
+        lay.chunks = (uint32_t)chunks_for(lay.n);
+        lay.groups = (lay.chunks + 255u) >> 8;
+        lay.payload = lay.offsets + lay.chunks + 1;
+    }
+    return lay;
+}
 
 struct DecodeJob {
     const uint8_t*  len;
     const uint32_t* offsets;
     const uint32_t* payload;
     uint8_t*        out;
-    uint64_t        n;
+    uint64_t        n;                                        // symbols (an upper bound when n_dev is set)
+    const uint64_t* n_dev;                                    // device: the symbol count; or null
+    uint64_t        stream_bytes;                             // the valid prefix of the stream
     uint32_t        payload_words, chunks;
     uint32_t        groups_per_block;                         // groups of 768 chunks a workgroup decodes with one set of tables
 };
@@ -81,7 +103,7 @@ __global__ __launch_bounds__(256) void huffman_clear_kernel(const Batch<Layout> 
 __global__ __launch_bounds__(256) void huffman_histogram_kernel(const Batch<Layout> batch)
 {
     uint32_t block;
-    const Layout& lay = batch.item[batch_item(batch, blockIdx.x, block)];
+    const Layout lay = resolved(batch.item[batch_item(batch, blockIdx.x, block)]);
     const uint8_t* in = lay.in;
     const uint64_t n = lay.n;
     uint32_t* hist = lay.hist;
@@ -290,7 +312,8 @@ __device__ __forceinline__ uint32_t workgroup_exclusive_scan(uint32_t mine, uint
 __global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Batch<Layout> batch)
 {
     uint32_t group;
-    const Layout& lay = batch.item[batch_item(batch, blockIdx.x, group)];
+    const Layout lay = resolved(batch.item[batch_item(batch, blockIdx.x, group)]);
+    if (group >= lay.groups) return;                          // workgroup-uniform: past the real extent
     __shared__ uint8_t len[256];
     __shared__ uint32_t lds[4];
     len[threadIdx.x] = (uint8_t)(lay.table[threadIdx.x] & 0xffu);
@@ -336,7 +359,7 @@ __global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Batch<Lay
 // ---- scan of the group sums (in place, exclusive); the stream's size --------------------------------
 __global__ __launch_bounds__(kThreads) void huffman_scan_kernel(const Batch<Layout> batch)
 {
-    const Layout& lay = batch.item[blockIdx.x];
+    const Layout lay = resolved(batch.item[blockIdx.x]);
     __shared__ uint32_t lds[4];
     uint32_t carry = 0;
     for (uint32_t base = 0; base < lay.groups; base += kThreads) {         // workgroup-uniform trip count
@@ -397,7 +420,8 @@ __device__ __forceinline__ void encode_chunk(const uint8_t* in, uint64_t first, 
 __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Layout> batch)
 {
     uint32_t group;
-    const Layout& lay = batch.item[batch_item(batch, blockIdx.x, group)];
+    const Layout lay = resolved(batch.item[batch_item(batch, blockIdx.x, group)]);
+    if (group >= lay.groups) return;                          // workgroup-uniform: past the real extent
     __shared__ uint32_t table[256];
     __shared__ uint32_t lds[4];
     table[threadIdx.x] = lay.table[threadIdx.x];
@@ -560,8 +584,17 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
     const uint8_t* len_in = job.len;
     const uint32_t* offsets = job.offsets;
     const uint32_t* payload = job.payload;
-    const uint32_t payload_words = job.payload_words, chunks = job.chunks;
-    const uint64_t n = job.n;
+    uint32_t payload_words = job.payload_words, chunks = job.chunks;
+    uint64_t n = job.n;
+    if (job.n_dev) {                                          // the count is on the stream: settle what follows from it
+        const uint64_t there = *job.n_dev;
+        n = there < job.n ? there : job.n;
+        chunks = (uint32_t)chunks_for(n);
+        payload = offsets + chunks + 1;
+        const uint64_t head = 256u + 4u * ((uint64_t)chunks + 1u);
+        const uint64_t words = job.stream_bytes > head ? (job.stream_bytes - head) / 4u : 0u;
+        payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
+    }
     uint8_t* out = job.out;
     __shared__ LongCodes tables;
     uint32_t (&per_length)[kMaxLen + 2] = tables.per_length, (&first)[kMaxLen + 2] = tables.first, (&start)[kMaxLen + 2] = tables.start;
@@ -739,7 +772,8 @@ fh_status check_encode(const fh_huffman_encode_item& it)
 {
     if (it.n > kMaxSymbols) return FH_ERR_BAD_NUMEL;
     if (!it.stream_out || !it.totals || !it.workspace || (it.n > 0 && !it.bytes)) return FH_ERR_NULL;
-    if (!aligned(it.bytes, 16) || !aligned(it.stream_out, 16) || !aligned(it.totals, 8) || !aligned(it.workspace, 16))
+    if (!aligned(it.bytes, 16) || !aligned(it.stream_out, 16) || !aligned(it.totals, 8) || !aligned(it.workspace, 16) ||
+        !aligned(it.n_device, 8))
         return FH_ERR_ALIGNMENT;
     if (it.stream_cap < fh_huffman_stream_bytes(it.n) || it.workspace_cap < fh_huffman_workspace_bytes(it.n))
         return FH_ERR_BUFFER_TOO_SMALL;
@@ -751,9 +785,10 @@ fh_status check_decode(const fh_huffman_decode_item& it)
     if (it.n > kMaxSymbols) return FH_ERR_BAD_NUMEL;
     if (it.n == 0) return FH_OK;
     if (!it.stream_in || !it.out) return FH_ERR_NULL;
-    if (!aligned(it.stream_in, 16) || !aligned(it.out, 16)) return FH_ERR_ALIGNMENT;
+    if (!aligned(it.stream_in, 16) || !aligned(it.out, 16) || !aligned(it.n_device, 8)) return FH_ERR_ALIGNMENT;
     if (it.out_cap < it.n) return FH_ERR_BUFFER_TOO_SMALL;
-    if (it.stream_bytes < 256u + 4u * (chunks_of(it.n) + 1u)) return FH_ERR_BUFFER_TOO_SMALL;   // not even the lengths and the offsets
+    // not even the lengths and the offsets (with the count on the device: of the largest stream it may describe)
+    if (it.stream_bytes < 256u + 4u * (chunks_of(it.n) + 1u)) return FH_ERR_BUFFER_TOO_SMALL;
     return FH_OK;
 }
 
@@ -811,6 +846,7 @@ fh_status fh_huffman_encode_batch(const fh_huffman_encode_item* items, int32_t c
             lay.totals = static_cast<uint64_t*>(it.totals);
             lay.in = static_cast<const uint8_t*>(it.bytes);
             lay.n = it.n;
+            lay.n_dev = static_cast<const uint64_t*>(it.n_device);
             // about eight vectors per thread, more in long streams: a workgroup clears and adds up 32 KiB of
             // counters and sends 256 atomics to the stream's histogram whatever it counts
             const uint64_t want = it.n == 0 ? 0 : (it.n / 16 + 255) / 256 / 8 + 1;
@@ -862,6 +898,8 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
             j.payload = j.offsets + chunks + 1;
             j.out = static_cast<uint8_t*>(it.out);
             j.n = it.n;
+            j.n_dev = static_cast<const uint64_t*>(it.n_device);
+            j.stream_bytes = it.stream_bytes;
             j.payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
             j.chunks = (uint32_t)chunks;
             groups[jobs] = (chunks + kDecodeThreads - 1) / kDecodeThreads;   // the decoder's own groups
@@ -895,6 +933,7 @@ fh_status fh_huffman_encode(const void* bytes, uint64_t n, void* stream_out, siz
                             void* workspace, size_t workspace_cap, void* stream)
 {
     fh_huffman_encode_item it;
+    it.n_device = nullptr;
     it.bytes = bytes; it.n = n; it.stream_out = stream_out; it.stream_cap = stream_cap; it.totals = totals;
     it.workspace = workspace; it.workspace_cap = workspace_cap;
     return fh_huffman_encode_batch(&it, 1, stream);
@@ -904,6 +943,7 @@ fh_status fh_huffman_decode(const void* stream_in, size_t stream_bytes, uint64_t
                             void* stream)
 {
     fh_huffman_decode_item it;
+    it.n_device = nullptr;
     it.stream_in = stream_in; it.stream_bytes = stream_bytes; it.n = n; it.out = out; it.out_cap = out_cap;
     return fh_huffman_decode_batch(&it, 1, stream);
 }

@@ -333,7 +333,8 @@ def test_huffman_sizes_and_argument_checks():
 
 
 def test_huffman_item_layouts_and_batch_argument_checks():
-    assert ctypes.sizeof(api.fh_huffman_encode_item) == 56 and ctypes.sizeof(api.fh_huffman_decode_item) == 40
+    assert ctypes.sizeof(api.fh_huffman_encode_item) == 64 and ctypes.sizeof(api.fh_huffman_decode_item) == 48
+    assert api.fh_huffman_encode_item.n_device.offset == 56 and api.fh_huffman_decode_item.n_device.offset == 40
     assert api.fh_huffman_encode_item.workspace_cap.offset == 48 and api.fh_huffman_decode_item.out.offset == 24
     lib = api.raw_library()
     assert api.huffman_batch_capacity() == 16

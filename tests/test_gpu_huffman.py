@@ -172,3 +172,32 @@ def test_batched_calls_match_the_oracle_for_every_stream(api):
         assert totals[i] == [want.size, bits], f"stream {i}: totals"
         assert np.array_equal(batch.streams[i].cpu().numpy()[: used[i]], want), f"stream {i}: bytes"
         assert np.array_equal(batch.out[i].cpu().numpy(), d), f"stream {i}: decoded"
+
+
+def test_symbol_count_taken_from_device_memory(api):
+    """The buffer's length is the output of an earlier call on the stream: buffers and launches are
+    sized for an upper bound, the count comes from device memory, and nothing is read back between
+    encode and decode."""
+    rng = np.random.default_rng(5)
+    cap = 300_000
+    full = np.clip(np.rint(rng.normal(128.0, 5.0, cap)), 0, 255).astype(np.uint8)
+    counts = [0, 1, 255, 256, 257, 65_536, 65_537, 200_001, cap, cap + 999]        # the last: clipped to the bound
+    data = [torch.from_numpy(full.copy()).cuda() for _ in counts]
+    n_dev = [torch.tensor([c], dtype=torch.int64, device="cuda") for c in counts]
+    batch = api.HuffmanBatch(data, n_device=n_dev)
+    for o in batch.out:
+        o.fill_(0xEE)
+    torch.cuda.synchronize()
+    api.fh_huffman_encode_batch(batch)
+    api.fh_huffman_decode_batch(batch)                       # no refresh: stream capacities bound the reads
+    torch.cuda.synchronize()
+    totals = batch.totals.cpu().numpy()
+    for k, c in enumerate(counts):
+        n = min(c, cap)
+        print(f"[huffman] device count {c} of capacity {cap}", flush=True)
+        want, bits = oracle.huffman_encode(full[:n])
+        assert (int(totals[k, 0]), int(totals[k, 1])) == (want.size, bits)
+        assert np.array_equal(batch.streams[k].cpu().numpy()[:want.size], want)
+        back = batch.out[k].cpu().numpy()
+        assert np.array_equal(back[:n], full[:n])
+        assert np.all(back[-(-n // 16) * 16:] == 0xEE)          # nothing written past the count's last 16-byte vector
