@@ -397,6 +397,72 @@ fh_status fh_huffman_encode_batch(const fh_huffman_encode_item *items, int32_t c
 fh_status fh_huffman_decode_batch(const fh_huffman_decode_item *items, int32_t count, void *stream);
 int32_t   fh_huffman_batch_capacity(void);
 
+/* ---- the channel-wise mix compressor as one call each way ------------------------------------------
+ * Section 4.4.1 describes ONE compressor -- classify channels by the three-sigma rule, quantise
+ * the normal ones, store the salient ones block-wise (sparse blocks as CSR, dense blocks by
+ * Lorenzo prediction within an error bound, their codes Huffman-coded) -- and Algorithm 1 knows
+ * two actions, compress and decompress.  These calls enqueue that whole chain, built from the
+ * calls above, on one stream without the host reading anything back:
+ *
+ *   fh_mix_compress    fh_classify_channels -> slots as fh_channel_slots numbers them -> the raw
+ *                      store cleared (rows of unused slots are zero) -> fh_compress_mixed ->
+ *                      fh_sparse_encode of the raw store viewed as `maps` maps of h x w ->
+ *                      (entropy = 1) fh_huffman_encode of the index stream;
+ *   fh_mix_decompress  (entropy = 1) fh_huffman_decode -> fh_sparse_decode -> fh_decompress_mixed.
+ *
+ * Results are identical to making those calls one by one with the same parameters.  The
+ * caller owns two device buffers per tensor, both 256-byte aligned: `store`, which holds the
+ * stored form from compress until decompress, and `workspace`, scratch that either call may
+ * overwrite and that is free again once the call's work has run.  fh_mix_layout says how large
+ * they must be (sizes for the worst case: how much of the value, index and Huffman streams is
+ * in use depends on the data) and where each part lies:
+ *   store      header (uint64[8]: [0..3] the sparse stage's totals {values, index bytes, sparse
+ *              blocks, dense blocks}, [4..5] the Huffman stage's totals {stream bytes, payload
+ *              bits}, [6] bytes the stored form occupies -- header, codes, meta and, when
+ *              channels are kept, slots, info bytes, the values in use and the index or Huffman
+ *              stream in use --, [7] raw-store rows in use), slots, packed, meta, info, values,
+ *              then indices (entropy = 0) or the Huffman stream (entropy = 1);
+ *   workspace  stats, counts, mask (as fh_classify_channels writes them), the classification's
+ *              partial sums, the raw store, the sparse stage's scratch, and with entropy = 1 the
+ *              plain index stream and the Huffman stage's scratch.
+ * maps * h * w must equal outer * raw_channels * inner (feature maps: maps = outer *
+ * raw_channels, h * w = inner; [tokens][hidden]: one map of h = tokens, w = raw_channels); with
+ * raw_channels == 0 the chain is the classification followed by the plain quantiser and maps, h,
+ * w, window, tau, eps and entropy are ignored.  At most 2^31 elements per tensor.  decompress
+ * reads the same fields as compress (shape, parameters, store, workspace) plus out, out_dtype,
+ * out_cap.  The batched calls run every stage once for all items (in runs of that stage's
+ * batch capacity); everything is checked before the first launch; nothing is allocated on the
+ * device or synchronised. */
+typedef struct fh_mix_item {
+    const void *x;          int32_t x_dtype;   int32_t out_dtype;   /* fh_dtype */
+    int64_t     outer, channels, inner;
+    int64_t     maps, h, w;                     /* the raw store as feature maps */
+    fh_params   quant;                          /* quantiser of the normal channels */
+    double      k_sigma;    int64_t min_outliers;                   /* classification */
+    int64_t     raw_channels;                   /* rows of the raw store: salient channels beyond it are quantised */
+    int32_t     window;     int32_t entropy;    /* pooling window 2 | 4 | 8; 1: Huffman-code the index stream */
+    float       tau, eps;                       /* sparsity threshold; error bound of dense blocks (<= 0: verbatim) */
+    int64_t     reserved;                       /* 0 */
+    void       *store;      size_t store_cap;
+    void       *workspace;  size_t workspace_cap;
+    void       *out;        size_t out_cap;
+} fh_mix_item;
+typedef struct fh_mix_regions {
+    size_t store_bytes, workspace_bytes;
+    /* offsets into store (indices is 0 and unused when entropy = 1, huffman when entropy = 0) */
+    size_t header, slots, packed, meta, info, values, indices, huffman;
+    /* offsets into workspace */
+    size_t stats, counts, mask, classify_ws, raw, sparse_ws, indices_ws, huffman_ws;
+    /* sizes of the parts: exact for slots, packed, meta, info, raw; capacities for the streams */
+    size_t slots_bytes, packed_bytes, meta_bytes, info_bytes, values_cap, indices_cap, huffman_cap, raw_bytes,
+           classify_ws_bytes, sparse_ws_bytes, huffman_ws_bytes;
+} fh_mix_regions;
+fh_status fh_mix_layout(const fh_mix_item *item, fh_mix_regions *regions);   /* host only; reads shape and parameters */
+fh_status fh_mix_compress(const fh_mix_item *item, void *stream);
+fh_status fh_mix_decompress(const fh_mix_item *item, void *stream);
+fh_status fh_mix_compress_batch(const fh_mix_item *items, int32_t count, void *stream);
+fh_status fh_mix_decompress_batch(const fh_mix_item *items, int32_t count, void *stream);
+
 const char *fh_status_string(fh_status s);
 
 #ifdef __cplusplus

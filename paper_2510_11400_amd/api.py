@@ -38,6 +38,7 @@ EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "
            "fh_sparse_decode", "fh_sparse_encode_batch", "fh_sparse_decode_batch", "fh_sparse_batch_capacity",
            "fh_huffman_stream_bytes", "fh_huffman_workspace_bytes", "fh_huffman_encode", "fh_huffman_decode",
            "fh_huffman_encode_batch", "fh_huffman_decode_batch", "fh_huffman_batch_capacity",
+           "fh_mix_layout", "fh_mix_compress", "fh_mix_decompress", "fh_mix_compress_batch", "fh_mix_decompress_batch",
            "fh_status_string")
 
 
@@ -201,6 +202,42 @@ _lib.fh_huffman_decode_batch.argtypes = [_P(fh_huffman_decode_item), ctypes.c_in
 _lib.fh_huffman_decode_batch.restype = ctypes.c_int
 _lib.fh_huffman_batch_capacity.argtypes = []
 _lib.fh_huffman_batch_capacity.restype = ctypes.c_int32
+
+
+class fh_mix_item(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("x_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("outer", ctypes.c_int64), ("channels", ctypes.c_int64), ("inner", ctypes.c_int64),
+                ("maps", ctypes.c_int64), ("h", ctypes.c_int64), ("w", ctypes.c_int64),
+                ("quant", fh_params),
+                ("k_sigma", ctypes.c_double), ("min_outliers", ctypes.c_int64),
+                ("raw_channels", ctypes.c_int64),
+                ("window", ctypes.c_int32), ("entropy", ctypes.c_int32),
+                ("tau", ctypes.c_float), ("eps", ctypes.c_float),
+                ("reserved", ctypes.c_int64),
+                ("store", ctypes.c_void_p), ("store_cap", ctypes.c_size_t),
+                ("workspace", ctypes.c_void_p), ("workspace_cap", ctypes.c_size_t),
+                ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t)]
+
+
+MIX_REGION_FIELDS = ("store_bytes", "workspace_bytes",
+                     "header", "slots", "packed", "meta", "info", "values", "indices", "huffman",
+                     "stats", "counts", "mask", "classify_ws", "raw", "sparse_ws", "indices_ws", "huffman_ws",
+                     "slots_bytes", "packed_bytes", "meta_bytes", "info_bytes", "values_cap", "indices_cap",
+                     "huffman_cap", "raw_bytes", "classify_ws_bytes", "sparse_ws_bytes", "huffman_ws_bytes")
+
+
+class fh_mix_regions(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_size_t) for name in MIX_REGION_FIELDS]
+
+
+_lib.fh_mix_layout.argtypes = [_P(fh_mix_item), _P(fh_mix_regions)]
+_lib.fh_mix_layout.restype = ctypes.c_int
+for _name in ("fh_mix_compress", "fh_mix_decompress"):
+    getattr(_lib, _name).argtypes = [_P(fh_mix_item), ctypes.c_void_p]
+    getattr(_lib, _name).restype = ctypes.c_int
+for _name in ("fh_mix_compress_batch", "fh_mix_decompress_batch"):
+    getattr(_lib, _name).argtypes = [_P(fh_mix_item), ctypes.c_int32, ctypes.c_void_p]
+    getattr(_lib, _name).restype = ctypes.c_int
 
 
 class FedHybridError(RuntimeError):
@@ -933,3 +970,119 @@ def fh_decompress_mixed_batch(batch: MixedBatch, stream=None) -> None:
     if batch.count:
         with torch.cuda.device(batch.device):
             _check(_lib.fh_decompress_mixed_batch(batch.items, batch.count, _stream_ptr(stream)))
+
+
+@dataclass
+class MixEntry:
+    """One tensor of the whole channel-wise mix compressor (fh_mix_compress / fh_mix_decompress):
+    `x` viewed as [outer][channels][inner]; its raw store viewed as `maps` maps of h x w."""
+    outer: int
+    channels: int
+    inner: int
+    raw_channels: int
+    group_size: int
+    bits: int
+    rounding: object = "nearest"
+    seed: int = 0
+    tensor_id: int = 0
+    k_sigma: float = 3.0
+    min_outliers: int = 1
+    maps: int = 0
+    h: int = 0
+    w: int = 0
+    window: int = 4
+    tau: float = 0.5
+    eps: float = 0.0
+    entropy: int = 1
+    x: Optional[torch.Tensor] = None
+    out: Optional[torch.Tensor] = None
+    store: Optional[torch.Tensor] = None
+    workspace: Optional[torch.Tensor] = None
+    dtype: Optional[torch.dtype] = None            # of x, when only decompressing
+    out_dtype: Optional[torch.dtype] = None
+
+
+class MixBatch:
+    """A marshalled fh_mix_item array.  `store` and `workspace` (uint8 device tensors) are
+    allocated here when an entry brings none; `regions[i]` says where the parts lie, and
+    `part(i, name)` returns a uint8 view of one of them."""
+
+    def __init__(self, entries: Sequence[MixEntry], device=None, shared_workspace: bool = False):
+        self.entries = list(entries)
+        self.count = len(self.entries)
+        self.items = (fh_mix_item * max(1, self.count))()
+        self.regions: List[fh_mix_regions] = []
+        self.device = device
+        for it, e in zip(self.items, self.entries):
+            ref = e.x if e.x is not None else (e.store if e.store is not None else e.out)
+            if ref is not None:
+                self.device = self.device or ref.device
+            x_dtype = e.x.dtype if e.x is not None else (e.dtype or torch.float32)
+            it.x_dtype = _DT[x_dtype]
+            it.out_dtype = _DT[e.out.dtype if e.out is not None else (e.out_dtype or torch.float32)]
+            it.outer, it.channels, it.inner = int(e.outer), int(e.channels), int(e.inner)
+            it.maps, it.h, it.w = int(e.maps), int(e.h), int(e.w)
+            it.quant = make_params(e.group_size, e.bits, e.rounding, e.seed, e.tensor_id)
+            it.k_sigma, it.min_outliers, it.raw_channels = float(e.k_sigma), int(e.min_outliers), int(e.raw_channels)
+            it.window, it.entropy, it.tau, it.eps, it.reserved = int(e.window), int(e.entropy), float(e.tau), float(e.eps), 0
+            r = fh_mix_regions()
+            _check(_lib.fh_mix_layout(ctypes.byref(it), ctypes.byref(r)))
+            self.regions.append(r)
+        if self.device is None:
+            raise ValueError("no device: give the batch a device or an entry a tensor")
+        shared = None
+        if shared_workspace and self.count:            # calls on one stream may share their scratch ... one item at a time
+            shared = torch.empty(max(r.workspace_bytes for r in self.regions), dtype=torch.uint8, device=self.device)
+        for it, e, r in zip(self.items, self.entries, self.regions):
+            if e.store is None:
+                e.store = torch.empty(max(256, r.store_bytes), dtype=torch.uint8, device=self.device)
+            if e.workspace is None:
+                e.workspace = shared if shared is not None else \
+                    torch.empty(max(256, r.workspace_bytes), dtype=torch.uint8, device=self.device)
+            for t, what in ((e.store, "store"), (e.workspace, "workspace")):
+                _device_tensor(t, what)
+            it.store, it.store_cap = e.store.data_ptr(), _nbytes(e.store)
+            it.workspace, it.workspace_cap = e.workspace.data_ptr(), _nbytes(e.workspace)
+            if e.x is not None:
+                _device_tensor(e.x, "x")
+                if e.x.numel() != e.outer * e.channels * e.inner:
+                    raise ValueError("x.numel() != outer * channels * inner")
+                it.x = _ptr(e.x)
+            if e.out is not None:
+                _device_tensor(e.out, "out")
+                it.out, it.out_cap = _ptr(e.out), _nbytes(e.out)
+
+    def part(self, i: int, name: str) -> torch.Tensor:
+        r = self.regions[i]
+        store_parts = {"header": 64, "slots": r.slots_bytes, "packed": r.packed_bytes, "meta": r.meta_bytes,
+                       "info": r.info_bytes, "values": r.values_cap, "indices": r.indices_cap, "huffman": r.huffman_cap}
+        work_parts = {"stats": 32, "counts": 4 * self.entries[i].channels, "mask": self.entries[i].channels,
+                      "raw": r.raw_bytes, "indices_ws": r.indices_cap}
+        if name in store_parts:
+            off = getattr(r, name)
+            return self.entries[i].store[off: off + store_parts[name]]
+        off = getattr(r, name)
+        return self.entries[i].workspace[off: off + work_parts[name]]
+
+    def header(self, i: int) -> torch.Tensor:
+        """int64[8] view of the stored form's header."""
+        return self.part(i, "header").view(torch.int64)
+
+    def _call(self, fn, stream) -> None:
+        if self.count:
+            with torch.cuda.device(self.device):
+                _check(fn(self.items, self.count, _stream_ptr(stream)))
+
+
+def mix_layout(item: fh_mix_item) -> fh_mix_regions:
+    r = fh_mix_regions()
+    _check(_lib.fh_mix_layout(ctypes.byref(item), ctypes.byref(r)))
+    return r
+
+
+def fh_mix_compress_batch(batch: MixBatch, stream=None) -> None:
+    batch._call(_lib.fh_mix_compress_batch, stream)
+
+
+def fh_mix_decompress_batch(batch: MixBatch, stream=None) -> None:
+    batch._call(_lib.fh_mix_decompress_batch, stream)

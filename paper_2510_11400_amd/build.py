@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfedhybrid.so")
 SOURCES = ("fh_abi.hip", "fh_compress.hip", "fh_decompress.hip", "fh_classify.hip", "fh_mixed.hip", "fh_sparse.hip",
-           "fh_huffman.hip")
+           "fh_huffman.hip", "fh_chain.hip")
 
 # Strict binary32 semantics on the device: no contraction (the one fused multiply-add
 # of the method is written explicitly), IEEE division, denormals kept.  Packed-fp32

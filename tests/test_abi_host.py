@@ -389,3 +389,37 @@ def test_static_scratch_entry_point_refuses_oversized_tensors_on_the_host():
     assert lib.fh_classify_channels_static(FAKE, 0, 1, 1, n_ok + 1, 3.0, 1, FAKE, FAKE, FAKE, None) == 13
     assert lib.fh_classify_channels_static(FAKE, 0, 4, 1024, 1 << 20, 3.0, 1, FAKE, FAKE, FAKE, None) == 13
     assert "static buffer" in api.status_string(13)
+
+
+def test_mix_item_layout_and_host_side_layout_call():
+    assert ctypes.sizeof(api.fh_mix_item) == 192 and api.fh_mix_item.quant.offset == 64
+    assert api.fh_mix_item.k_sigma.offset == 96 and api.fh_mix_item.window.offset == 120
+    assert api.fh_mix_item.store.offset == 144 and api.fh_mix_item.out_cap.offset == 184
+    assert ctypes.sizeof(api.fh_mix_regions) == 8 * len(api.MIX_REGION_FIELDS) == 232
+    it = api.fh_mix_item()
+    it.x_dtype = 0
+    it.outer, it.channels, it.inner = 8, 32, 196
+    it.maps, it.h, it.w = 32, 14, 14
+    it.quant = api.make_params(128, 4)
+    it.k_sigma, it.min_outliers, it.raw_channels = 3.0, 1, 4
+    it.window, it.entropy, it.tau, it.eps = 4, 1, 0.5, 0.02
+    r = api.mix_layout(it)
+    n = 8 * 32 * 196
+    assert r.packed_bytes == api.packed_bytes(n, 4) and r.meta_bytes == api.meta_bytes(n, 128)
+    assert r.raw_bytes == 8 * 4 * 196 * 4 == r.values_cap and r.slots_bytes == 64
+    assert r.info_bytes == api.sparse_info_bytes(32, 14, 14, 4) and r.indices_cap == api.sparse_index_bytes(32, 14, 14, 4)
+    assert r.huffman_cap == api.huffman_stream_bytes(r.indices_cap) and r.indices == 0 and r.huffman > r.values
+    offs = [r.header, r.slots, r.packed, r.meta, r.info, r.values, r.huffman]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs) and r.store_bytes % 256 == 0
+    assert r.store_bytes >= r.huffman + r.huffman_cap
+    it.entropy = 0
+    r0 = api.mix_layout(it)
+    assert r0.huffman_cap == 0 and r0.indices > r0.values and r0.store_bytes < r.store_bytes
+    it.raw_channels = 0
+    r1 = api.mix_layout(it)
+    assert r1.raw_bytes == r1.info_bytes == r1.values_cap == r1.indices_cap == 0
+    lib = api.raw_library()
+    it.raw_channels, it.maps = 4, 31
+    assert lib.fh_mix_layout(ctypes.byref(it), ctypes.byref(r)) == 11
+    assert lib.fh_mix_compress(None, None) == 1 and lib.fh_mix_compress_batch(None, -1, None) == 10
+    assert lib.fh_mix_compress_batch(None, 0, None) == 0 and lib.fh_mix_decompress_batch(None, 2, None) == 1
