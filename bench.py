@@ -56,7 +56,30 @@ def run_on_threads(fn, jobs, threads) -> float:
         return time.perf_counter() - t0
 
 
-def bench_classify(args, api, W, dev) -> int:
+def counted(fn):
+    """fn with a call counter (`calls`): how many steps a run executed in all, which is what a
+    per-dispatch counter total of the same run has to be divided by."""
+    def wrapper(*a, **k):
+        wrapper.calls += 1
+        return fn(*a, **k)
+    wrapper.calls = 0
+    return wrapper
+
+
+def copy_calibration(n, dev):
+    """n plain 1 GiB device copies: a rocprofv3 --pmc run scales FETCH_SIZE / WRITE_SIZE by what
+    the same counters read for them."""
+    import torch
+    if n <= 0:
+        return
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(n):
+        dst.copy_(src)                          # reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+
+
+def bench_classify(args, api, W, dev) -> dict:
     """Channel classification (three-sigma outliers, salient channels) over MobileNetV2-style
     NCHW activations at batch 64 with channel-clustered outliers; one step classifies every
     tensor of the set once (one batched call; --per-tensor: one call per tensor).  Two streaming
@@ -85,6 +108,7 @@ def bench_classify(args, api, W, dev) -> int:
     batch = api.ClassifyBatch([api.ClassifyEntry(xd, outer, C, inner, 3.0, mo, ws, stats, counts, mask)
                                for xd, outer, C, inner, mo, ws, stats, counts, mask in jobs])
 
+    @counted
     def step():
         if args.per_tensor:
             for xd, outer, C, inner, mo, ws, stats, counts, mask in jobs:
@@ -110,6 +134,7 @@ def bench_classify(args, api, W, dev) -> int:
         "config": {"workload": "classify_mobilenetv2_b64_outlier_channels", "tensors": len(jobs),
                    "input_bytes": nbytes, "k_sigma": 3.0,
                    "entry_point": "fh_classify_channels (per tensor)" if args.per_tensor else "fh_classify_channels_batch"},
+        "algorithmic_bytes_per_step": alg, "steps_executed": step.calls,
         "roofline": {"bound": "hbm", "kernel": "moments + count passes (whole call)",
                      "achieved": round(alg / elapsed / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(alg / elapsed / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},
@@ -126,11 +151,10 @@ def bench_classify(args, api, W, dev) -> int:
                 break
         result["cpu_baseline"] = {"value": round(done / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                                   "sample": f"{done / 2**20:.1f} MiB of the set, whole tensors, {t_cpu:.1f} s"}
-    print(json.dumps(result), flush=True)
-    return 0
+    return result
 
 
-def bench_mixed(args, api, W, dev) -> int:
+def bench_mixed(args, api, W, dev) -> dict:
     """Compress + decompress with salient channels routed around the quantiser, over the same
     MobileNetV2-style activations with channel-clustered outliers as the classification
     bench, or (--config 4) over the transformer set with outliers planted in 4 % of the hidden
@@ -181,6 +205,7 @@ def bench_mixed(args, api, W, dev) -> int:
                                            meta=meta, raw=raw, out=out)
                             for xd, outer, C, inner, slots, cap, packed, meta, raw, out, tid in jobs])
 
+    @counted
     def step(timed=False):
         if timed:
             ev[0].record(stream)
@@ -226,6 +251,7 @@ def bench_mixed(args, api, W, dev) -> int:
                                    else "fh_compress_mixed_batch + fh_decompress_mixed_batch"),
                    "kept_channels": [int(c) for _, _, c in host]},
         "round_trip_algorithmic_bytes": alg_c + alg_d,
+        "algorithmic_bytes_per_step": alg_c + alg_d, "steps_executed": step.calls,
         "hbm_frac_round_trip": round((alg_c + alg_d) / elapsed / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "kernel": dom[0] + " (event-timed)",
                      "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -249,11 +275,10 @@ def bench_mixed(args, api, W, dev) -> int:
                 break
         result["cpu_baseline"] = {"value": round(done / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                                   "sample": f"{done / 2**20:.1f} MiB of the set, whole tensors, {t_cpu:.1f} s"}
-    print(json.dumps(result), flush=True)
-    return 0
+    return result
 
 
-def bench_sparse(args, api, W, dev) -> int:
+def bench_sparse(args, api, W, dev) -> dict:
     """Sparse-block storage of salient-channel feature maps (non-zero mask, n x n average
     pooling against tau, CSR for sparse blocks): the kept channels (4 %) of the MobileNetV2-style
     set at batch 64, post-ReLU with clustered zeros.  One step = every map set encoded, then
@@ -291,6 +316,7 @@ def bench_sparse(args, api, W, dev) -> int:
     batch = api.SparseBatch([api.SparseEntry(maps, h, w, n, tau, eps, x=xd, buffers=bufs, values=vals, indices=idx,
                                              out=out) for xd, maps, h, w, bufs, out, (vals, idx) in jobs])
 
+    @counted
     def step(timed=False):
         if timed:
             ev[0].record(stream)
@@ -339,6 +365,7 @@ def bench_sparse(args, api, W, dev) -> int:
                    "entry_point": ("fh_sparse_encode + fh_sparse_decode (per set)" if args.per_tensor
                                    else "fh_sparse_encode_batch + fh_sparse_decode_batch"),
                    "window": n, "tau": tau, "eps": eps},
+        "algorithmic_bytes_per_step": alg_e + alg_d, "steps_executed": step.calls,
         "roofline": {"bound": "hbm", "kernel": dom[0] + ", all launches of a step, event-timed",
                      "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},
@@ -358,11 +385,10 @@ def bench_sparse(args, api, W, dev) -> int:
                 break
         result["cpu_baseline"] = {"value": round(done / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                                   "sample": f"{done / 2**20:.1f} MiB of the set, whole map sets, {t_cpu:.1f} s"}
-    print(json.dumps(result), flush=True)
-    return 0
+    return result
 
 
-def bench_huffman(args, api, W, dev) -> int:
+def bench_huffman(args, api, W, dev) -> dict:
     """The entropy stage of the predictive form (Section 4.4.1: Huffman coding of the quantisation
     codes): the index streams -- code bytes of dense blocks, CSR bytes of sparse ones -- that
     fh_sparse_encode writes for the sparse bench's map sets with an error bound (--eps, default
@@ -402,6 +428,7 @@ def bench_huffman(args, api, W, dev) -> int:
     torch.cuda.synchronize()
     batch.refresh()                                           # stream sizes (fixed: the input is)
 
+    @counted
     def step(timed=False):
         if timed:
             ev[0].record(stream)
@@ -436,8 +463,7 @@ def bench_huffman(args, api, W, dev) -> int:
         ms_d += ev[1].elapsed_time(ev[2]) / args.steps
     for k, (data, ni, out, totals, ws, used, back) in enumerate(jobs):
         if not torch.equal(back if args.per_tensor else batch.out[k], data):
-            print("bench.py: the Huffman round trip did not restore its input", file=sys.stderr)
-            return 1
+            raise RuntimeError("the Huffman round trip did not restore its input")
     alg_e = 3 * nbytes + stored                               # histogram, count and write passes read the bytes
     alg_d = stored + nbytes
     dom = ("encode (histogram + code + count + scan + write)", alg_e, ms_e) if ms_e >= ms_d else ("decode", alg_d, ms_d)
@@ -450,6 +476,7 @@ def bench_huffman(args, api, W, dev) -> int:
                    "streams": len(jobs), "input_bytes": nbytes, "stored_bytes": stored,
                    "entry_point": ("fh_huffman_encode + fh_huffman_decode (per stream)" if args.per_tensor
                                    else "fh_huffman_encode_batch + fh_huffman_decode_batch")},
+        "algorithmic_bytes_per_step": alg_e + alg_d, "steps_executed": step.calls,
         "roofline": {"bound": "hbm", "kernel": dom[0] + ", all launches of a step, event-timed",
                      "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},
@@ -470,11 +497,149 @@ def bench_huffman(args, api, W, dev) -> int:
                 break
         result["cpu_baseline"] = {"value": round(done / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
                                   "sample": f"leading {done / 2**20:.1f} MiB of the streams, {t_cpu:.1f} s"}
-    print(json.dumps(result), flush=True)
-    return 0
+    return result
 
 
-def bench_hooks(args, api, W, dev) -> int:
+def bench_chain(args, api, W, dev) -> dict:
+    """The whole channel-wise mix compressor (Section 4.4.1 end to end; Algorithm 1's compress and
+    decompress actions) through fh_mix_compress_batch / fh_mix_decompress_batch: classification,
+    routed quantiser, sparse / predictive storage of the salient channels' maps, Huffman stage,
+    and back.  Workload: the MobileNetV2-style set at batch 64 (G128, 4-bit, nearest) or, with
+    --config 4, the transformer set (bf16, G64, 2-bit, stochastic), each with outliers planted in
+    4 % of the channels; room for 1/16 of the channels in the raw store; window 4, tau 0.5,
+    error bound --eps (default 0.02).  Cold protocol as for the plain round trip."""
+    import numpy as np
+    import torch
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+    if args.config == 4:
+        shapes = tuple(s for _ in range(12) for s in ((16 * 512, 768, 1, None), (16 * 512, 3072, 1, None)))
+        G, B, rounding, dtype, dist = 64, 2, "stochastic", "bf16", ("gauss", "gelu")
+        workload = "chain_transformer_l12_b16_s512_bf16_outlier_channels_g64_b2_stochastic"
+    else:
+        shapes = ((64, 32, 112 * 112, (112, 112)), (64, 96, 112 * 112, (112, 112)), (64, 144, 56 * 56, (56, 56)),
+                  (64, 192, 28 * 28, (28, 28)), (64, 384, 14 * 14, (14, 14)))
+        G, B, rounding, dtype, dist = 128, 4, "nearest", "f32", ("relu", "relu")
+        workload = "chain_mobilenetv2_b64_outlier_channels_g128_b4_nearest"
+    eps = args.eps if args.eps > 0 else 0.02
+    window, tau, entropy = 4, 0.5, 1
+    tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+    esize = 2 if dtype == "bf16" else 4
+    t0 = time.time()
+    host, entries = [], []
+    for i, (outer, C, inner, hw) in enumerate(shapes):
+        x, planted = W.outlier_channel_tensor(outer, C, inner, seed=i, dist=dist[i % 2], dtype=dtype)
+        cap = max(1, C // 16)
+        maps, h, w = (outer * cap, hw[0], hw[1]) if hw else (1, outer, cap)
+        min_out = max(1, outer * inner // 100)
+        host.append((x, outer, C, inner, cap, maps, h, w, min_out, i))
+        xd = torch.from_numpy(x.view(np.int16) if dtype == "bf16" else x).to(dev)
+        if dtype == "bf16":
+            xd = xd.view(torch.bfloat16)
+        entries.append(api.MixEntry(outer, C, inner, cap, G, B, rounding, seed=1, tensor_id=i, k_sigma=3.0,
+                                    min_outliers=min_out, maps=maps, h=h, w=w, window=window, tau=tau, eps=eps,
+                                    entropy=entropy, x=xd, out=torch.empty(x.size, dtype=tdtype, device=dev)))
+    batch = api.MixBatch(entries, device=dev)
+    torch.cuda.synchronize()
+    nbytes = sum(h[0].nbytes for h in host)
+    print(f"[bench] chain: {len(entries)} tensors, {nbytes / 2**20:.1f} MiB resident, stores "
+          f"{sum(r.store_bytes for r in batch.regions) / 2**20:.1f} MiB + workspaces "
+          f"{sum(r.workspace_bytes for r in batch.regions) / 2**20:.1f} MiB allotted "
+          f"(generated + uploaded in {time.time() - t0:.1f} s)", file=sys.stderr, flush=True)
+    stream = torch.cuda.current_stream()
+    scrub = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+
+    @counted
+    def step(ev=None, displace=True):
+        if displace:
+            torch.amax(scrub)
+        if ev:
+            ev[0].record(stream)
+        api.fh_mix_compress_batch(batch, stream)
+        if ev:
+            ev[1].record(stream)
+        if displace:
+            torch.amax(scrub)
+        if ev:
+            ev[2].record(stream)
+        api.fh_mix_decompress_batch(batch, stream)
+        if ev:
+            ev[3].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    headers = [batch.header(i).cpu().tolist() for i in range(batch.count)]
+    stored = sum(int(h[6]) for h in headers)
+    kept_rows = [int(h[7]) for h in headers]
+
+    def timed(displace):
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for k in range(args.steps):
+            step(evs[k], displace)
+        torch.cuda.synchronize()
+        return (sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps,
+                sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps)
+
+    c_ms, d_ms = timed(True)
+    cw_ms, dw_ms = timed(False)
+    # what the method has to move: the tensor read three times on the way in (moments, outlier
+    # counts -- which need the moments --, quantiser -- which needs the mask), the stored form
+    # written; the stored form read and the tensor written on the way back
+    alg_c, alg_d = 3 * nbytes + stored, stored + nbytes
+    step_ms = c_ms + d_ms
+    dom = ("fh_mix_compress_batch", alg_c, c_ms) if c_ms >= d_ms else ("fh_mix_decompress_batch", alg_d, d_ms)
+    result = {
+        "metric": "whole channel-wise mix compressor, compress+decompress GB/s of input on 1 MI355X",
+        "value": round(nbytes / step_ms / 1e6, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(step_ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": workload, "tensors": len(entries), "input_bytes": nbytes,
+                   "entry_point": "fh_mix_compress_batch + fh_mix_decompress_batch",
+                   "window": window, "tau": tau, "eps": eps, "entropy": "huffman", "raw_store_rows": "channels / 16",
+                   "protocol": "cold: memory-side cache displaced by an untimed 1 GiB read pass before each call"},
+        "stored_bytes": stored, "compression_ratio": round(nbytes / stored, 3), "raw_store_rows_in_use": kept_rows,
+        "round_trip_algorithmic_bytes": alg_c + alg_d,
+        "algorithmic_bytes_per_step": alg_c + alg_d, "steps_executed": step.calls,
+        "hbm_frac_round_trip": round((alg_c + alg_d) / step_ms / 1e6 / HBM_PEAK_GBS, 4),
+        "roofline": {"bound": "hbm", "kernel": dom[0] + " (all launches of the call, event-timed)",
+                     "achieved": round(dom[1] / dom[2] / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(dom[1] / dom[2] / 1e6 / HBM_PEAK_GBS, 4), "traffic": None},
+        "kernels": {"fh_mix_compress_batch": {"ms": round(c_ms, 4), "bytes": alg_c, "GBps": round(alg_c / c_ms / 1e6, 1)},
+                    "fh_mix_decompress_batch": {"ms": round(d_ms, 4), "bytes": alg_d, "GBps": round(alg_d / d_ms / 1e6, 1)}},
+        "warm": {"compress_ms": round(cw_ms, 4), "decompress_ms": round(dw_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle_chain as OC
+
+        def one(job):
+            x, outer, C, inner, cap, maps, h, w, min_out, tid = job
+            st = OC.mix_compress(x, outer, C, inner, cap, G, B, rounding, 1, tid, 3.0, min_out, maps, h, w, window, tau,
+                                 eps, entropy, dtype=dtype)
+            OC.mix_decompress(st, outer, C, inner, cap, G, B, maps, h, w, window, eps, entropy, dtype=dtype, out_dtype=dtype)
+
+        sample, t_one = [], 0.0
+        for job in sorted(host, key=lambda j: j[0].nbytes):  # smallest first, until about 15 s are spent
+            t1 = time.perf_counter()
+            one(job)
+            t_one += time.perf_counter() - t1
+            sample.append(job)
+            if t_one > 15.0:
+                break
+        done = sum(j[0].nbytes for j in sample)
+        cores = host_threads()
+        t_all = run_on_threads(one, sorted(sample, key=lambda j: -j[0].nbytes), cores)
+        result["cpu_baseline"] = {"value": round(done / t_all / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+                                  "sample": f"{len(sample)} whole tensors ({done / 2**20:.1f} MiB), the oracle's stages "
+                                            f"composed, tensors handed to {cores} threads, {t_all:.1f} s",
+                                  "single_thread": {"value": round(done / t_one / 1e9, 4), "unit": "GB/s", "cores": 1,
+                                                    "seconds": round(t_one, 2)},
+                                  "host_cpu_count": os.cpu_count()}
+    return result
+
+
+def bench_hooks(args, api, W, dev) -> dict:
     """A training step with the compressor hooked into autograd (saved_tensors_hooks): the
     feed-forward half of a 12-layer transformer encoder at configuration 4's shapes (batch 16,
     sequence 512, hidden 768 / 3072, bf16; LayerNorm outputs and GELU inputs are what autograd
@@ -560,8 +725,7 @@ def bench_hooks(args, api, W, dev) -> int:
                      "unit": "GB/s", "frac": round((in_bytes * 2 + 2 * (in_bytes - sm)) / (pc + rc) / 1e9 / HBM_PEAK_GBS, 4),
                      "traffic": None},
     }
-    print(json.dumps(result), flush=True)
-    return 0
+    return result
 
 
 def main() -> int:
@@ -574,13 +738,14 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB device copies before the timed region, so that a "
                          "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE against a known size")
-    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed", "sparse", "hooks", "huffman"), default="roundtrip",
+    ap.add_argument("--op", choices=("roundtrip", "classify", "mixed", "sparse", "hooks", "huffman", "chain"), default="roundtrip",
                     help="roundtrip (default): compress + decompress of the tensor set; classify: the "
                          "channel classification step (moments + outlier counts), measured on its own; "
                          "mixed: the round trip with salient channels kept raw beside the quantised stream; "
                          "sparse: block-wise sparse storage of the kept channels' maps; hooks: a training "
                          "step with the compressor in autograd's saved-tensor hooks; huffman: the entropy "
-                         "stage over the predictive form's index streams")
+                         "stage over the predictive form's index streams; chain: the whole channel-wise mix compressor "
+                         "(fh_mix_compress / fh_mix_decompress) on a set with outlier channels")
     ap.add_argument("--eps", type=float, default=0.0,
                     help="--op sparse: error bound of the predictive form of dense blocks (0 = verbatim)")
     ap.add_argument("--maps-scale", type=int, default=1, metavar="K",
@@ -595,6 +760,8 @@ def main() -> int:
     ap.add_argument("--displace", choices=("read", "write"), default="read",
                     help="--op roundtrip, cold protocol: what the untimed pass that displaces the memory-side "
                          "cache does with its 1 GiB buffer")
+    ap.add_argument("--no-next-rows", action="store_true",
+                    help="default run only: leave out the short runs of the other ops (next_rows)")
     ap.add_argument("--per-tensor", action="store_true",
                     help="time single-tensor fh_roundtrip calls instead of the batched entry point")
     args = ap.parse_args()
@@ -619,16 +786,60 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
-    if args.op == "classify":
-        return bench_classify(args, api, W, dev)
-    if args.op == "mixed":
-        return bench_mixed(args, api, W, dev)
-    if args.op == "sparse":
-        return bench_sparse(args, api, W, dev)
-    if args.op == "hooks":
-        return bench_hooks(args, api, W, dev)
-    if args.op == "huffman":
-        return bench_huffman(args, api, W, dev)
+    copy_calibration(args.copy_calibration, dev)
+    ops = {"classify": bench_classify, "mixed": bench_mixed, "sparse": bench_sparse, "hooks": bench_hooks,
+           "huffman": bench_huffman, "chain": bench_chain, "roundtrip": bench_roundtrip}
+    result = ops[args.op](args, api, W, dev)
+    if args.op == "roundtrip" and args.config == 5 and not (args.no_next_rows or args.per_tensor):
+        result["next_rows"] = next_rows(args, api, W, dev, ops)
+    attach_traffic(result)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def attach_traffic(result) -> None:
+    """roofline.traffic of an op other than the plain round trip: measured HBM bytes per step from the
+    committed counter summary of this workload (None when there is none, or the kernels changed since)."""
+    from paper_2510_11400_amd.profile_summary import read_step_traffic
+    roof = result.get("roofline")
+    if roof is not None and roof.get("traffic") is None:
+        name = result["config"]["workload"]
+        roof["traffic"] = read_step_traffic(os.path.join(ROOT, "profiles", f"counters_{name}.txt"))
+
+
+def next_rows(args, api, W, dev, ops) -> dict:
+    """Short runs of the rows built around the hot path (classification, routed quantiser, sparse /
+    predictive storage, Huffman stage, the whole chain), so that one default run records them all:
+    GB/s of input, ms per step and the fraction of the HBM peak on each op's algorithmic bytes."""
+    import copy
+    import torch
+    rows = {}
+    for name, extra in (("classify", {}), ("mixed", {}), ("mixed_transformer", {"config": 4}), ("sparse", {"maps_scale": 16}),
+                        ("sparse_eps", {"maps_scale": 16, "eps": 0.02}), ("huffman", {"maps_scale": 16}),
+                        ("chain", {}), ("chain_transformer", {"config": 4})):
+        a = copy.copy(args)
+        a.steps, a.warmup, a.no_cpu_baseline, a.per_tensor, a.eps, a.maps_scale, a.config = 5, 2, True, False, 0.0, 1, 5
+        for k, v in extra.items():
+            setattr(a, k, v)
+        r = ops[name.split("_")[0]](a, api, W, dev)
+        attach_traffic(r)
+        seconds = r["ms_per_step"] * 1e-3
+        rows[name] = {"workload": r["config"]["workload"], "value": r["value"], "unit": r["unit"],
+                      "ms_per_step": r["ms_per_step"],
+                      "hbm_frac": round(r["algorithmic_bytes_per_step"] / seconds / 1e9 / HBM_PEAK_GBS, 4),
+                      "traffic": r["roofline"]["traffic"]}
+        for key in ("compression_ratio", "stored_bytes"):
+            if key in r:
+                rows[name][key] = r[key]
+        torch.cuda.empty_cache()
+    return rows
+
+
+def bench_roundtrip(args, api, W, dev) -> dict:
+    """The hot path: every tensor of the configuration compressed, then every tensor restored,
+    through the batched entry points (cold protocol unless --warm / --per-tensor)."""
+    import numpy as np
+    import torch
 
     w = W.full_config(args.config)
     t0 = time.time()
@@ -668,6 +879,7 @@ def main() -> int:
         else:
             torch.amax(scrub)
 
+    @counted
     def step(events=None, displace=None):
         if args.per_tensor:
             for e in entries:
@@ -692,14 +904,6 @@ def main() -> int:
     for _ in range(args.warmup):
         step(displace=args.displace if cold else None)
     torch.cuda.synchronize()
-
-    if args.copy_calibration > 0:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(args.copy_calibration):
-            dst.copy_(src)                      # plain device copy: reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
 
     def timed_loop(displace):
         evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
@@ -735,6 +939,7 @@ def main() -> int:
                                 "compress and before decompress; step time = event-timed compress + decompress") if cold
                    else "warm: compress and decompress back to back, wall clock"},
         "round_trip_algorithmic_bytes": cbytes + dbytes,
+        "algorithmic_bytes_per_step": cbytes + dbytes,
         "hbm_frac_round_trip": round((cbytes + dbytes) / step_s / 1e9 / HBM_PEAK_GBS, 4),
     }
     if cold:
@@ -805,8 +1010,7 @@ def main() -> int:
                               "seconds": round(t_one, 2)},
             "host_cpu_count": os.cpu_count()}
 
-    print(json.dumps(result), flush=True)
-    return 0
+    return result
 
 
 if __name__ == "__main__":
