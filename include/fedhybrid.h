@@ -209,6 +209,9 @@ fh_status fh_classify_channels_static(const void *x, fh_dtype x_dtype, int64_t o
  * and raw may be NULL.  Everything is enqueued on `stream`; nothing is allocated. */
 size_t    fh_raw_bytes(int64_t outer, int64_t raw_channels, int64_t inner, fh_dtype dtype);
 fh_status fh_channel_slots(const void *mask, int64_t channels, int64_t raw_channels, void *slots, void *stream);
+/* The same, and *used (device uint64, 8-byte aligned) = raw-store rows in use = min(salient channels, raw_channels). */
+fh_status fh_channel_slots_used(const void *mask, int64_t channels, int64_t raw_channels, void *slots, void *used,
+                                void *stream);
 fh_status fh_compress_mixed(const void *x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
                             const fh_params *params, const void *slots, int64_t raw_channels,
                             void *packed, size_t packed_cap, void *meta, size_t meta_cap,
@@ -234,6 +237,10 @@ typedef struct fh_mixed_item {
     void       *raw;        size_t raw_cap;    int32_t raw_dtype;   int32_t reserved;
     void       *out;        size_t out_cap;
     fh_params   params;
+    const void *rows_in_use;                    /* NULL, or device uint64 (8-byte aligned): raw-store rows in use, as
+                                                   fh_channel_slots_used writes it; when it reads 0 by the time the
+                                                   stream reaches the call the tensor takes the plain quantiser's
+                                                   code path (same bytes, no channel bookkeeping) */
 } fh_mixed_item;
 fh_status fh_compress_mixed_batch(const fh_mixed_item *items, int32_t count, void *stream);
 fh_status fh_decompress_mixed_batch(const fh_mixed_item *items, int32_t count, void *stream);

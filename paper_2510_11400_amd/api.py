@@ -32,7 +32,7 @@ EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "
            "fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch", "fh_batch_capacity",
            "fh_classify_workspace_bytes", "fh_classify_channels", "fh_classify_channels_batch",
            "fh_classify_batch_capacity", "fh_classify_static_scratch_bytes", "fh_classify_channels_static",
-           "fh_raw_bytes", "fh_channel_slots", "fh_compress_mixed", "fh_decompress_mixed",
+           "fh_raw_bytes", "fh_channel_slots", "fh_channel_slots_used", "fh_compress_mixed", "fh_decompress_mixed",
            "fh_compress_mixed_batch", "fh_decompress_mixed_batch", "fh_mixed_batch_capacity",
            "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
            "fh_sparse_decode", "fh_sparse_encode_batch", "fh_sparse_decode_batch", "fh_sparse_batch_capacity",
@@ -73,7 +73,7 @@ class fh_mixed_item(ctypes.Structure):
                 ("raw", ctypes.c_void_p), ("raw_cap", ctypes.c_size_t),
                 ("raw_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t),
-                ("params", fh_params)]
+                ("params", fh_params), ("rows_in_use", ctypes.c_void_p)]
 
 
 class fh_sparse_encode_item(ctypes.Structure):
@@ -134,6 +134,9 @@ _lib.fh_raw_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ct
 _lib.fh_raw_bytes.restype = ctypes.c_size_t
 _lib.fh_channel_slots.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
 _lib.fh_channel_slots.restype = ctypes.c_int
+_lib.fh_channel_slots_used.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p]
+_lib.fh_channel_slots_used.restype = ctypes.c_int
 _lib.fh_compress_mixed.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                    _P(fh_params), ctypes.c_void_p, ctypes.c_int64,
                                    ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
@@ -508,28 +511,38 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 
 
 def fh_channel_slots(mask: torch.Tensor, raw_channels: int, slots: Optional[torch.Tensor] = None,
-                     stream=None) -> torch.Tensor:
+                     stream=None, used: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Enqueue the numbering of the salient channels in `mask` (uint8[channels]); returns the
-    device tensor slots int16[channels]."""
+    device tensor slots int16[channels].  `used` (device int64[1], optional) receives the number
+    of raw-store rows in use, which the mixed calls take as `rows_in_use`."""
     _device_tensor(mask, "mask")
     channels = mask.numel()
     if slots is None:
         slots = torch.empty(channels, dtype=torch.int16, device=mask.device)
     _device_tensor(slots, "slots")
-    if mask.element_size() != 1 or _nbytes(slots) < 2 * channels:
+    if mask.element_size() != 1 or _nbytes(slots) < 2 * channels or (used is not None and _nbytes(used) < 8):
         raise FedHybridError(7)
     with torch.cuda.device(mask.device):
-        _check(_lib.fh_channel_slots(mask.data_ptr(), channels, int(raw_channels), slots.data_ptr(),
-                                     _stream_ptr(stream)))
+        _check(_lib.fh_channel_slots_used(mask.data_ptr(), channels, int(raw_channels), slots.data_ptr(),
+                                          None if used is None else used.data_ptr(), _stream_ptr(stream)))
     return slots
 
 
 def fh_compress_mixed(x: torch.Tensor, outer: int, channels: int, inner: int, slots: torch.Tensor,
                       raw_channels: int, group_size: int, bits: int, rounding="nearest", seed: int = 0,
                       tensor_id: int = 0, packed: Optional[torch.Tensor] = None,
-                      meta: Optional[torch.Tensor] = None, raw: Optional[torch.Tensor] = None, stream=None):
+                      meta: Optional[torch.Tensor] = None, raw: Optional[torch.Tensor] = None, stream=None,
+                      rows_in_use: Optional[torch.Tensor] = None):
     """Enqueue compression of `x` viewed as [outer][channels][inner] with the channels that
-    `slots` marks kept verbatim; returns (packed, meta, raw) device tensors."""
+    `slots` marks kept verbatim; returns (packed, meta, raw) device tensors.  `rows_in_use`
+    (device int64[1] written by fh_channel_slots(..., used=)): a tensor for which it reads 0
+    takes the plain quantiser's code path."""
+    if rows_in_use is not None:
+        b = MixedBatch([MixedEntry(outer, channels, inner, slots, raw_channels, group_size, bits, rounding, seed,
+                                   tensor_id, x=x, packed=packed, meta=meta, raw=raw, rows_in_use=rows_in_use)])
+        fh_compress_mixed_batch(b, stream)
+        e = b.entries[0]
+        return e.packed, e.meta, e.raw
     _device_tensor(x, "x")
     _device_tensor(slots, "slots")
     n = x.numel()
@@ -552,13 +565,19 @@ def fh_compress_mixed(x: torch.Tensor, outer: int, channels: int, inner: int, sl
 
 def fh_decompress_mixed(packed: torch.Tensor, meta: torch.Tensor, raw: torch.Tensor, outer: int, channels: int,
                         inner: int, slots: torch.Tensor, raw_channels: int, group_size: int, bits: int,
-                        out_dtype=torch.float32, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                        out_dtype=torch.float32, out: Optional[torch.Tensor] = None, stream=None,
+                        rows_in_use: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Enqueue the inverse of fh_compress_mixed; returns the flat restored tensor."""
     for t, what in ((packed, "packed"), (meta, "meta"), (raw, "raw"), (slots, "slots")):
         _device_tensor(t, what)
     n = outer * channels * inner
     if out is None:
         out = torch.empty(n, dtype=out_dtype, device=packed.device)
+    if rows_in_use is not None:
+        b = MixedBatch([MixedEntry(outer, channels, inner, slots, raw_channels, group_size, bits, packed=packed,
+                                   meta=meta, raw=raw, out=out, rows_in_use=rows_in_use)])
+        fh_decompress_mixed_batch(b, stream)
+        return out
     _device_tensor(out, "out")
     if _nbytes(packed) < packed_bytes(n, bits) or _nbytes(meta) < meta_bytes(n, group_size) \
             or _nbytes(slots) < 2 * channels or _nbytes(raw) < raw_bytes(outer, raw_channels, inner, raw.dtype):
@@ -915,6 +934,7 @@ class MixedEntry:
     meta: Optional[torch.Tensor] = None
     raw: Optional[torch.Tensor] = None
     out: Optional[torch.Tensor] = None
+    rows_in_use: Optional[torch.Tensor] = None     # device int64[1], as fh_channel_slots(..., used=) writes it
 
 
 def mixed_batch_capacity() -> int:
@@ -950,6 +970,9 @@ class MixedBatch:
             it.meta, it.meta_cap = _ptr(e.meta), _nbytes(e.meta)
             it.raw, it.raw_cap, it.raw_dtype = _ptr(e.raw), _nbytes(e.raw), _dtype_code(e.raw)
             it.params = make_params(e.group_size, e.bits, e.rounding, e.seed, e.tensor_id)
+            if e.rows_in_use is not None:
+                _device_tensor(e.rows_in_use, "rows_in_use")
+                it.rows_in_use = e.rows_in_use.data_ptr()
             if e.x is not None:
                 _device_tensor(e.x, "x")
                 if e.x.numel() != n:

@@ -262,6 +262,7 @@ fh_status fh_mix_compress_batch(const fh_mix_item* items, int32_t count, void* s
         m.meta = at(it.store, reg[i].meta); m.meta_cap = reg[i].meta_bytes;
         m.raw = at(it.workspace, reg[i].raw); m.raw_cap = reg[i].raw_bytes; m.raw_dtype = it.x_dtype;
         m.params = it.quant;
+        m.rows_in_use = at(it.store, reg[i].header) + 7 * sizeof(uint64_t);
     }
     if ((st = fh_compress_mixed_batch(mix.data(), count, stream)) != FH_OK) return st;
 
@@ -365,6 +366,7 @@ fh_status fh_mix_decompress_batch(const fh_mix_item* items, int32_t count, void*
         m.raw = at(it.workspace, reg[i].raw); m.raw_cap = reg[i].raw_bytes; m.raw_dtype = it.x_dtype;
         m.out = it.out; m.out_cap = it.out_cap;
         m.params = it.quant;
+        m.rows_in_use = at(it.store, reg[i].header) + 7 * sizeof(uint64_t);
     }
     return fh_decompress_mixed_batch(mix.data(), count, stream);
 }

@@ -62,6 +62,7 @@ struct ChannelMap {
     const int16_t* slots;      // device, [channels]: raw-store row of a kept channel, anything else = normal
     void*          raw;        // device, [outer][raw_channels][inner] elements of the tensor's dtype
     uint32_t       raw_channels;
+    const uint64_t* rows_in_use;  // device, or null: raw-store rows in use; 0 there = no channel of this tensor is kept
     ExactDiv       inner_exact, channels_exact;
     SmallDiv       inner, channels;
 };
@@ -92,6 +93,12 @@ __device__ __forceinline__ ElemPos advance(const ChannelMap& cm, const ElemPos& 
     q.c = cc - wraps * cm.channels.d;
     q.o = p.o + wraps;
     return q;
+}
+
+// Does the caller's count say that nothing is kept?  (wave-uniform: one scalar load)
+__device__ __forceinline__ bool nothing_kept(const ChannelMap& cm)
+{
+    return cm.rows_in_use != nullptr && *cm.rows_in_use == 0u;
 }
 
 __device__ __forceinline__ bool kept(const ChannelMap& cm, int16_t slot)

@@ -671,6 +671,18 @@ __global__ __launch_bounds__(kCBlock) void compress_mixed_kernel(const Batch<Mix
     const MixedCompressJob& job = batch.item[batch_item(batch, blockIdx.x, tile)];
     const CompressItem& it = job.it;
     const ChannelMap& cm = job.cm;
+    if (nothing_kept(cm)) {                                   // the classification found no salient channel: the plain code
+        switch (it.bits * 2 + it.stochastic) {
+            case 4:  compress_tile<InT, G, 2, false>(it, tile, stage); break;
+            case 5:  compress_tile<InT, G, 2, true >(it, tile, stage); break;
+            case 8:  compress_tile<InT, G, 4, false>(it, tile, stage); break;
+            case 9:  compress_tile<InT, G, 4, true >(it, tile, stage); break;
+            case 16: compress_tile<InT, G, 8, false>(it, tile, stage); break;
+            case 17: compress_tile<InT, G, 8, true >(it, tile, stage); break;
+            default: break;
+        }
+        return;
+    }
     switch (it.bits * 2 + it.stochastic) {
         case 4:  compress_tile<InT, G, 2, false, true>(it, tile, stage, &cm); break;
         case 5:  compress_tile<InT, G, 2, true , true>(it, tile, stage, &cm); break;

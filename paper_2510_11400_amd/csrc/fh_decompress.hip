@@ -270,6 +270,15 @@ __global__ __launch_bounds__(kDBlock) void decompress_mixed_kernel(const Batch<M
     const DecompressItem& it = job.it;
     const ChannelMap& cm = job.cm;
     const int raw_dtype = job.raw_dtype;
+    if (nothing_kept(cm)) {                                   // no channel of this tensor was kept: the plain code
+        switch (it.bits) {
+            case 2: decompress_tile<OutT, G, 2>(it, tile); break;
+            case 4: decompress_tile<OutT, G, 4>(it, tile); break;
+            case 8: decompress_tile<OutT, G, 8>(it, tile); break;
+            default: break;
+        }
+        return;
+    }
     switch (it.bits) {
         case 2: decompress_tile<OutT, G, 2, true>(it, tile, &cm, raw_dtype); break;
         case 4: decompress_tile<OutT, G, 4, true>(it, tile, &cm, raw_dtype); break;

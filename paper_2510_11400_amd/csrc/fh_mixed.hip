@@ -18,7 +18,8 @@ constexpr int kSlotPerThread = 16;                 // 1024 * 16 = the largest ch
 // below raw_channels; -1 for every other channel.  One workgroup: each thread owns 16
 // consecutive channels, the per-thread counts are scanned through LDS.
 __global__ __launch_bounds__(kSlotThreads) void channel_slots_kernel(const uint8_t* __restrict__ mask, int channels,
-                                                                      int raw_channels, int16_t* __restrict__ slots)
+                                                                      int raw_channels, int16_t* __restrict__ slots,
+                                                                      uint64_t* __restrict__ used)
 {
     __shared__ int scan[kSlotThreads];
     const int t = threadIdx.x;
@@ -44,6 +45,7 @@ __global__ __launch_bounds__(kSlotThreads) void channel_slots_kernel(const uint8
         else slots[c] = (int16_t)-1;
         if (mask[c] != 0) ++rank;
     }
+    if (used && t == kSlotThreads - 1) *used = (uint64_t)(scan[t] < raw_channels ? scan[t] : raw_channels);
 }
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -73,9 +75,11 @@ fh_status check_quantiser(const fh_params* p, bool need_round)
     return FH_OK;
 }
 
-ChannelMap make_map(const void* slots, void* raw, int64_t channels, int64_t inner, int64_t raw_channels)
+ChannelMap make_map(const void* slots, void* raw, int64_t channels, int64_t inner, int64_t raw_channels,
+                    const void* rows_in_use)
 {
     ChannelMap cm;
+    cm.rows_in_use = static_cast<const uint64_t*>(rows_in_use);
     cm.slots = static_cast<const int16_t*>(slots);
     cm.raw = raw;
     cm.raw_channels = (uint32_t)raw_channels;
@@ -98,15 +102,21 @@ size_t fh_raw_bytes(int64_t outer, int64_t raw_channels, int64_t inner, fh_dtype
     return (size_t)outer * (size_t)raw_channels * (size_t)inner * fh::elem_size(dtype);
 }
 
-fh_status fh_channel_slots(const void* mask, int64_t channels, int64_t raw_channels, void* slots, void* stream)
+fh_status fh_channel_slots_used(const void* mask, int64_t channels, int64_t raw_channels, void* slots, void* used,
+                                void* stream)
 {
     if (channels < 1 || channels > 16384 || raw_channels < 0 || raw_channels > channels) return FH_ERR_BAD_SHAPE;
     if (!mask || !slots) return FH_ERR_NULL;
-    if (!fh::aligned(slots, 16)) return FH_ERR_ALIGNMENT;
+    if (!fh::aligned(slots, 16) || !fh::aligned(used, 8)) return FH_ERR_ALIGNMENT;
     hipLaunchKernelGGL(fh::channel_slots_kernel, dim3(1), dim3(fh::kSlotThreads), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint8_t*>(mask), (int)channels, (int)raw_channels,
-                       static_cast<int16_t*>(slots));
+                       static_cast<int16_t*>(slots), static_cast<uint64_t*>(used));
     return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
+fh_status fh_channel_slots(const void* mask, int64_t channels, int64_t raw_channels, void* slots, void* stream)
+{
+    return fh_channel_slots_used(mask, channels, raw_channels, slots, nullptr, stream);
 }
 
 }  // extern "C"
@@ -120,6 +130,7 @@ fh_status check_compress(const fh_mixed_item& it, int64_t* numel)
     fh_status s;
     if ((s = check_quantiser(&it.params, true)) != FH_OK) return s;
     if (it.reserved != 0) return FH_ERR_BAD_PARAM;
+    if (!aligned(it.rows_in_use, 8)) return FH_ERR_ALIGNMENT;
     if (it.x_dtype != FH_F32 && it.x_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
     if ((s = check_shape(it.outer, it.channels, it.inner, it.raw_channels, numel)) != FH_OK) return s;
     if (*numel == 0) return FH_OK;
@@ -138,6 +149,7 @@ fh_status check_decompress(const fh_mixed_item& it, int64_t* numel)
     fh_status s;
     if ((s = check_quantiser(&it.params, false)) != FH_OK) return s;
     if (it.reserved != 0) return FH_ERR_BAD_PARAM;
+    if (!aligned(it.rows_in_use, 8)) return FH_ERR_ALIGNMENT;
     if (it.raw_dtype != FH_F32 && it.raw_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
     if (it.out_dtype != FH_F32 && it.out_dtype != FH_BF16) return FH_ERR_BAD_DTYPE;
     if ((s = check_shape(it.outer, it.channels, it.inner, it.raw_channels, numel)) != FH_OK) return s;
@@ -210,7 +222,7 @@ fh_status fh_compress_mixed_batch(const fh_mixed_item* items, int32_t count, voi
             job.it.tensor_id = it.params.tensor_id;
             job.it.bits = it.params.bits;
             job.it.stochastic = it.params.rounding == FH_ROUND_STOCHASTIC ? 1 : 0;
-            job.cm = make_map(it.slots, it.raw, it.channels, it.inner, it.raw_channels);
+            job.cm = make_map(it.slots, it.raw, it.channels, it.inner, it.raw_channels, it.rows_in_use);
             if (!push(b, job, (numel + tile - 1) / tile)) break;      // launch what is there, go on with this item
             ++i;
         }
@@ -269,7 +281,7 @@ fh_status fh_decompress_mixed_batch(const fh_mixed_item* items, int32_t count, v
             job.it.numel = numel;
             job.it.bits = it.params.bits;
             job.it.pad = 0;
-            job.cm = make_map(it.slots, it.raw, it.channels, it.inner, it.raw_channels);
+            job.cm = make_map(it.slots, it.raw, it.channels, it.inner, it.raw_channels, it.rows_in_use);
             job.raw_dtype = it.raw_dtype;
             job.pad = 0;
             if (!push(b, job, (numel + tile - 1) / tile)) break;

@@ -117,6 +117,8 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
         if not self._eligible(t):
             return t
         x = t.detach().contiguous()
+        if x.data_ptr() % 16:                     # a contiguous view at an odd storage offset: the kernels want 16-byte alignment
+            x = x.clone()
         tid = self.next_tensor_id
         self.next_tensor_id += 1
         stream = torch.cuda.current_stream(x.device)
@@ -133,11 +135,14 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
             min_outliers = max(1, int(outer * inner * self.outlier_share))
             _, _, mask = api.fh_classify_channels(x.view(-1), outer, channels, inner, self.k_sigma, min_outliers,
                                                   stream=stream)
-            slots = api.fh_channel_slots(mask, raw_channels, stream=stream)
+            used = torch.empty(1, dtype=torch.int64, device=x.device)
+            slots = api.fh_channel_slots(mask, raw_channels, stream=stream, used=used)
+            # a tensor in which the classification finds nothing salient (most layers) takes the plain
+            # quantiser's code path inside the same launch: `used` tells the kernels on the device
             packed, meta, raw = api.fh_compress_mixed(x.view(-1), outer, channels, inner, slots, raw_channels,
                                                       self.group_size, self.bits, self.rounding, self.seed, tid,
-                                                      stream=stream)
-            mixed = (outer, channels, inner, slots, raw_channels, raw)
+                                                      stream=stream, rows_in_use=used)
+            mixed = (outer, channels, inner, slots, raw_channels, raw, used)
             extra = raw.numel() * raw.element_size() + slots.numel() * slots.element_size()
         if self.record:
             ev[1].record(stream)
@@ -171,9 +176,9 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
             out = api.fh_decompress(h.packed, h.meta, h.numel, self.group_size, self.bits, out_dtype=h.dtype,
                                     stream=stream)
         else:
-            outer, channels, inner, slots, raw_channels, raw = h.mixed
+            outer, channels, inner, slots, raw_channels, raw, used = h.mixed
             out = api.fh_decompress_mixed(h.packed, h.meta, raw, outer, channels, inner, slots, raw_channels,
-                                          self.group_size, self.bits, out_dtype=h.dtype, stream=stream)
+                                          self.group_size, self.bits, out_dtype=h.dtype, stream=stream, rows_in_use=used)
         if h.record is not None:
             ev[1].record(stream)
             h.record._unpack = ev

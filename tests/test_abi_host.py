@@ -289,7 +289,8 @@ def test_sparse_item_layouts_and_batch_argument_checks():
 
 
 def test_mixed_item_layout_and_batch_argument_checks():
-    assert ctypes.sizeof(api.fh_mixed_item) == 16 + 24 + 16 + 3 * 16 + 8 + 16 + 32 == 160
+    assert ctypes.sizeof(api.fh_mixed_item) == 16 + 24 + 16 + 3 * 16 + 8 + 16 + 32 + 8 == 168
+    assert api.fh_mixed_item.rows_in_use.offset == 160
     assert api.fh_mixed_item.slots.offset == 40 and api.fh_mixed_item.raw_dtype.offset == 104
     assert api.fh_mixed_item.out.offset == 112 and api.fh_mixed_item.params.offset == 128
     assert api.mixed_batch_capacity() == 16

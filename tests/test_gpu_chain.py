@@ -182,3 +182,19 @@ def test_chain_rejects_bad_arguments_before_any_launch(api):
         setattr(it, field, old)
     torch.cuda.synchronize()
     assert torch.equal(b.entries[0].store, sentinel)
+
+
+def test_chain_on_tensors_without_salient_channels(api):
+    """Most layers have no outlier-rich channel: the slot numbering reports zero rows in use and the
+    routed quantiser takes the plain code path on the device; everything still equals the oracle chain."""
+    print("[chain] nothing salient", flush=True)
+    for dtype, case in (("f32", (6, 48, 784, (28, 28), 3, 128, 4, "stochastic", 4, 0.5, 0.02, 1, "f32", 10 ** 6)),
+                        ("bf16", (200, 512, 1, None, 32, 64, 2, "stochastic", 4, 0.5, 0.02, 1, "bf16", 10 ** 6))):
+        x = _input(case, 77)
+        batch = api.MixBatch([_entry(api, _device(x, dtype), case, dtype)], device=torch.device("cuda"))
+        api.fh_mix_compress_batch(batch)
+        api.fh_mix_decompress_batch(batch)
+        api.fh_mix_compress_batch(batch)
+        torch.cuda.synchronize()
+        st = _compare(api, batch, 0, x, case, dtype)
+        assert st.used == 0 and not st.mask.any()

@@ -219,3 +219,20 @@ def test_channel_wise_hooks_shrink_the_error_of_the_normal_channels(hooks):
         errs[name] = float((got[:, normal] - x_host[:, normal]).abs().max())
     print(f"[hooks] max error on normal channels: {errs}", flush=True)
     assert errs["channel-wise"] < errs["plain"] / 8
+
+
+def test_a_contiguous_view_at_an_odd_storage_offset_is_compressed_from_a_copy(hooks):
+    """The kernels want 16-byte aligned tensors; a saved view that starts 4 bytes into its storage is
+    contiguous but not aligned, and must neither raise inside the forward pass nor change the result."""
+    _Probe.seen.clear()
+    base = torch.randn(1 + 64 * 96, device="cuda")
+    x = base[1:].view(64, 96).requires_grad_(True)
+    assert x.is_contiguous() and x.data_ptr() % 16 != 0
+    ctx = hooks.SavedActivations(64, 8, min_numel=1, record=True)
+    with ctx:
+        y = _Probe.apply(x).sum()
+    y.backward()
+    torch.cuda.synchronize()
+    assert len(ctx.records) == 1
+    want = _oracle_roundtrip(x.detach().cpu().contiguous(), 64, 8, "nearest", 0, 0, "f32")
+    assert torch.equal(_Probe.seen[0].cpu().view(torch.int32), want.view(torch.int32))

@@ -255,3 +255,33 @@ def test_batched_calls_match_the_oracle_for_every_tensor(api):
         # restore with the oracle's raw store where unused rows are zero: kept rows are what matter
         want = oracle.decompress_mixed(p, m, raw, outer, C, inner, slots, cap, G, B, raw_dtype=dtype, out_dtype="f32")
         assert np.array_equal(e.out.cpu().numpy().view(np.uint32), want.view(np.uint32)), f"tensor {i}: restored"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rows_in_use_of_zero_takes_the_plain_code_path(api, dtype):
+    """The slot numbering also reports how many raw-store rows are in use; a tensor for which that is
+    zero runs the plain quantiser's code inside the mixed launches -- same bytes as the oracle's
+    mixed form with nothing kept (= the plain quantiser), raw store untouched -- and a tensor that
+    keeps something is unaffected by passing the count."""
+    outer, C, inner = 7, 64, 600
+    x, planted = W.outlier_channel_tensor(outer, C, inner, seed=4, dtype=dtype)
+    xd = _device(x, dtype)
+    for mask in (np.zeros(C, np.uint8), np.isin(np.arange(C), planted).astype(np.uint8)):
+        print(f"[mixed] rows_in_use {dtype} salient={int(mask.sum())}", flush=True)
+        used = torch.full((1,), -5, dtype=torch.int64, device="cuda")
+        slots = api.fh_channel_slots(torch.from_numpy(mask).cuda(), 4, used=used)
+        raw = torch.full((outer * 4 * inner,), 7.0, device="cuda").to(xd.dtype)
+        gp, gm, graw = api.fh_compress_mixed(xd, outer, C, inner, slots, 4, 128, 4, "stochastic", 5, 2, raw=raw,
+                                             rows_in_use=used)
+        outs = [api.fh_decompress_mixed(gp, gm, graw, outer, C, inner, slots, 4, 128, 4, out_dtype=_tdtype(od),
+                                        rows_in_use=used) for od in ("f32", "bf16")]
+        torch.cuda.synchronize()
+        want_slots, want_used = oracle.channel_slots(mask, 4)
+        assert int(used.item()) == want_used and np.array_equal(slots.cpu().numpy(), want_slots)
+        p, m, r = oracle.compress_mixed(x, outer, C, inner, want_slots, 4, 128, 4, "stochastic", 5, 2, dtype=dtype,
+                                        raw_fill=0x40E0 if dtype == "bf16" else 7.0)      # 7.0 as bf16 bits
+        assert np.array_equal(gp.cpu().numpy(), p) and np.array_equal(gm.cpu().numpy().view(np.uint32), m.view(np.uint32))
+        assert np.array_equal(_bits(_host(graw, dtype)), _bits(r)), "raw store differs"
+        for od, got in zip(("f32", "bf16"), outs):
+            want = oracle.decompress_mixed(p, m, r, outer, C, inner, want_slots, 4, 128, 4, raw_dtype=dtype, out_dtype=od)
+            assert np.array_equal(_bits(_host(got, od)), _bits(want)), f"restored {od} differs"
