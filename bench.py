@@ -760,6 +760,9 @@ def main() -> int:
     ap.add_argument("--displace", choices=("read", "write"), default="read",
                     help="--op roundtrip, cold protocol: what the untimed pass that displaces the memory-side "
                          "cache does with its 1 GiB buffer")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="--op roundtrip: only the headline protocol's steps (no warm_codes, no other displacing "
+                         "pass), so that a kernel trace of the run averages over one protocol")
     ap.add_argument("--no-next-rows", action="store_true",
                     help="default run only: leave out the short runs of the other ops (next_rows)")
     ap.add_argument("--per-tensor", action="store_true",
@@ -961,7 +964,7 @@ def bench_roundtrip(args, api, W, dev) -> dict:
                               "unit": "GB/s", "frac": round(kern[dom]["GBps"] / HBM_PEAK_GBS, 4),
                               "traffic": traffic}
         result["kernels"] = kern
-    if cold:
+    if cold and not args.headline_only:
         # the same steps back to back, where the backward side finds the most recently written
         # codes in the memory-side cache
         wall_w, cw_ms, dw_ms = timed_loop(None)

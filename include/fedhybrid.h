@@ -366,8 +366,7 @@ int32_t   fh_sparse_batch_capacity(void);
  * stream_cap >= fh_huffman_stream_bytes(n) (the worst case) and fh_huffman_workspace_bytes(n)
  * bytes of scratch; what was used is in totals once the stream has reached it.  The decoder is
  * given the valid prefix of the stream (at least the lengths and the offsets, else
- * FH_ERR_BUFFER_TOO_SMALL); words past it read as zero.  Nothing is allocated or synchronised;
- * `stream` is a stream of the current device (the decoder sizes its launch for that device). */
+ * FH_ERR_BUFFER_TOO_SMALL); words past it read as zero.  Nothing is allocated or synchronised. */
 size_t    fh_huffman_stream_bytes(uint64_t n);
 size_t    fh_huffman_workspace_bytes(uint64_t n);
 fh_status fh_huffman_encode(const void *bytes, uint64_t n, void *stream_out, size_t stream_cap, void *totals,

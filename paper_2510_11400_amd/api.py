@@ -537,12 +537,6 @@ def fh_compress_mixed(x: torch.Tensor, outer: int, channels: int, inner: int, sl
     `slots` marks kept verbatim; returns (packed, meta, raw) device tensors.  `rows_in_use`
     (device int64[1] written by fh_channel_slots(..., used=)): a tensor for which it reads 0
     takes the plain quantiser's code path."""
-    if rows_in_use is not None:
-        b = MixedBatch([MixedEntry(outer, channels, inner, slots, raw_channels, group_size, bits, rounding, seed,
-                                   tensor_id, x=x, packed=packed, meta=meta, raw=raw, rows_in_use=rows_in_use)])
-        fh_compress_mixed_batch(b, stream)
-        e = b.entries[0]
-        return e.packed, e.meta, e.raw
     _device_tensor(x, "x")
     _device_tensor(slots, "slots")
     n = x.numel()
@@ -556,6 +550,13 @@ def fh_compress_mixed(x: torch.Tensor, outer: int, channels: int, inner: int, sl
         raw = torch.empty(max(0, outer * raw_channels * inner), dtype=x.dtype, device=x.device)
     p = make_params(group_size, bits, rounding, seed, tensor_id)
     with torch.cuda.device(x.device):
+        if rows_in_use is not None:                           # the count travels in the item struct: a batch of one
+            _device_tensor(rows_in_use, "rows_in_use")
+            it = fh_mixed_item(x.data_ptr(), _dtype_code(x), FH_F32, outer, channels, inner, slots.data_ptr(),
+                               int(raw_channels), _ptr(packed), _nbytes(packed), _ptr(meta), _nbytes(meta),
+                               _ptr(raw), _nbytes(raw), _dtype_code(x), 0, None, 0, p, rows_in_use.data_ptr())
+            _check(_lib.fh_compress_mixed_batch(ctypes.byref(it), 1, _stream_ptr(stream)))
+            return packed, meta, raw
         _check(_lib.fh_compress_mixed(x.data_ptr(), _dtype_code(x), outer, channels, inner, ctypes.byref(p),
                                       slots.data_ptr(), int(raw_channels),
                                       _ptr(packed), _nbytes(packed), _ptr(meta), _nbytes(meta),
@@ -573,17 +574,20 @@ def fh_decompress_mixed(packed: torch.Tensor, meta: torch.Tensor, raw: torch.Ten
     n = outer * channels * inner
     if out is None:
         out = torch.empty(n, dtype=out_dtype, device=packed.device)
-    if rows_in_use is not None:
-        b = MixedBatch([MixedEntry(outer, channels, inner, slots, raw_channels, group_size, bits, packed=packed,
-                                   meta=meta, raw=raw, out=out, rows_in_use=rows_in_use)])
-        fh_decompress_mixed_batch(b, stream)
-        return out
     _device_tensor(out, "out")
     if _nbytes(packed) < packed_bytes(n, bits) or _nbytes(meta) < meta_bytes(n, group_size) \
             or _nbytes(slots) < 2 * channels or _nbytes(raw) < raw_bytes(outer, raw_channels, inner, raw.dtype):
         raise FedHybridError(7)
     p = make_params(group_size, bits)
     with torch.cuda.device(packed.device):
+        if rows_in_use is not None:
+            _device_tensor(rows_in_use, "rows_in_use")
+            it = fh_mixed_item(None, FH_F32, _dtype_code(out), outer, channels, inner, slots.data_ptr(),
+                               int(raw_channels), _ptr(packed), _nbytes(packed), _ptr(meta), _nbytes(meta),
+                               _ptr(raw), _nbytes(raw), _dtype_code(raw), 0, _ptr(out), _nbytes(out), p,
+                               rows_in_use.data_ptr())
+            _check(_lib.fh_decompress_mixed_batch(ctypes.byref(it), 1, _stream_ptr(stream)))
+            return out
         _check(_lib.fh_decompress_mixed(_ptr(packed), _ptr(meta), _ptr(raw), _dtype_code(raw),
                                         outer, channels, inner, ctypes.byref(p), slots.data_ptr(),
                                         int(raw_channels), _dtype_code(out), _ptr(out), _nbytes(out),

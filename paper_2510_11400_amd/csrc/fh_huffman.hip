@@ -46,7 +46,9 @@ constexpr int kWriteStageWords = 12288;            // encode: LDS for a workgrou
 // and the decode waits on dependent instructions, not on a unit: one workgroup with the whole LDS holds 768
 // chunks (twelve waves) where workgroups of 256 with their own tables held 512.
 constexpr int kDecodeThreads = 768;
-constexpr int kStageWords = kDecodeThreads * 48;   // decode: LDS for a workgroup's payload slice (48 words per chunk: 6 bits per symbol)
+constexpr int kDecodeThreadsSmall = 256;           // ... of a launch that would leave compute units idle with 768
+constexpr int kStageWordsPerChunk = 48;            // decode: LDS for a workgroup's payload slice: 6 bits per symbol
+constexpr int kComputeUnits = 256;                 // MI355X
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -179,7 +181,9 @@ __global__ __launch_bounds__(256) void huffman_code_kernel(const Batch<Layout> b
         if (wave == 0) {
             // The merges are one chain of dependent steps.  The whole first wave runs it with every value the same
             // in all lanes and made known as such (readfirstlane), so that counters, comparisons and branches are
-            // scalar instructions; the lanes' LDS stores write one value to one address.
+            // scalar instructions; the lanes' LDS stores write one value to one address.  (Both queues spread
+            // over the lanes of registers, read with v_readlane and a scalar select, measured slower -- 71 us
+            // against 58 for 250 merges: what a merge costs is its instruction count, not the LDS latency.)
             if (lane == 0) deepest = 0u;
             const uint32_t mm = (uint32_t)__builtin_amdgcn_readfirstlane(m);
             if (mm > 1u) {
@@ -577,8 +581,10 @@ __device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst
 // The stream may be foreign: the tables are built from whatever the 256 length bytes say
 // (lengths above 24 count as unused), reads of payload words are bounded by the stream's size
 // (words outside read as zero), and every loop is bounded by the symbol count.
+template <int kDecodeThreads>
 __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Batch<DecodeJob> batch)
 {
+    constexpr int kStageWords = kDecodeThreads * kStageWordsPerChunk;
     uint32_t block;
     const DecodeJob& job = batch.item[batch_item(batch, blockIdx.x, block)];
     const uint8_t* len_in = job.len;
@@ -799,22 +805,6 @@ void launch(Kernel kernel, const Batch<Item>& b, uint32_t grid, hipStream_t s)
 }
 
 
-// workgroups of the decode kernel that the current device holds at once (one per compute unit with its LDS)
-int decode_slots()
-{
-    static int cached[64] = {0};
-    int device = 0;
-    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 64) return 512;
-    if (cached[device] == 0) {
-        int per_unit = 0, units = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, huffman_decode_kernel, kDecodeThreads, 0) != hipSuccess || per_unit < 1)
-            per_unit = 1;
-        if (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || units < 1) units = 256;
-        cached[device] = per_unit * units;
-    }
-    return cached[device];
-}
-
 }  // namespace
 
 extern "C" {
@@ -881,7 +871,15 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
         if (st != FH_OK) return st;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t slots = (uint64_t)decode_slots();
+    // A workgroup of 768 threads (the whole LDS of a compute unit: one per unit) decodes 768 chunks at a time.
+    // A call whose streams together give fewer such groups than the device has compute units would leave
+    // units idle for the whole launch; it is cut into groups of 256 chunks instead (workgroups of 256 threads,
+    // two per unit): three times as many units at work, each building the tables for a third of the chunks.
+    uint64_t wide = 0;
+    for (int32_t i = 0; i < count; ++i) wide += (chunks_of(items[i].n) + kDecodeThreads - 1) / kDecodeThreads;
+    const bool small = wide < (uint64_t)kComputeUnits;
+    const uint64_t per_group = small ? kDecodeThreadsSmall : kDecodeThreads;
+    const uint64_t slots = small ? 2u * kComputeUnits : kComputeUnits;         // workgroups the device holds at once
     bool launched = false;
     for (int32_t i = 0; i < count;) {
         DecodeJob job[kBatch];
@@ -902,14 +900,14 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
             j.stream_bytes = it.stream_bytes;
             j.payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
             j.chunks = (uint32_t)chunks;
-            groups[jobs] = (chunks + kDecodeThreads - 1) / kDecodeThreads;   // the decoder's own groups
+            groups[jobs] = (chunks + per_group - 1) / per_group;   // the decoder's own groups
             total += groups[jobs];
             ++jobs;
         }
-        // A workgroup builds a stream's tables once and then decodes `groups_per_block` groups of 768 chunks.  With
-        // more groups in the launch than workgroups fit on the device at once, every stream gets its share of
-        // that many workgroups: all of them are resident from the start and finish together, whereas a launch of
-        // 1.4 times as many would run a second, mostly empty round.
+        // A workgroup builds a stream's tables once and then decodes `groups_per_block` groups.  With more groups
+        // in the launch than workgroups fit on the device at once, every stream gets its share of that many
+        // workgroups: all of them are resident from the start and finish together, whereas a launch of 1.4 times
+        // as many would run a second, mostly empty round.
         Batch<DecodeJob> b;
         reset(b);
         for (int k = 0; k < jobs; ++k) {
@@ -921,7 +919,12 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
         }
         seal(b);
         if (b.count > 0) {
-            hipLaunchKernelGGL(huffman_decode_kernel, dim3(b.block_start[b.count]), dim3(kDecodeThreads), 0, s, b);
+            if (small)
+                hipLaunchKernelGGL(huffman_decode_kernel<kDecodeThreadsSmall>, dim3(b.block_start[b.count]),
+                                   dim3(kDecodeThreadsSmall), 0, s, b);
+            else
+                hipLaunchKernelGGL(huffman_decode_kernel<kDecodeThreads>, dim3(b.block_start[b.count]),
+                                   dim3(kDecodeThreads), 0, s, b);
             launched = true;
         }
     }
