@@ -691,6 +691,8 @@ def bench_hooks(args, api, W, dev) -> dict:
 
     plain_s, plain_peak = measure(contextlib.nullcontext)
     extra = {"channel_dim": -1} if args.channel_wise else {}
+    if args.batch_mib > 0:
+        extra["batch_bytes"] = args.batch_mib << 20
     make = lambda record=False: hooks.SavedActivations(G, B, rounding, seed=1, record=record, exclude=params, **extra)
     hooked_s, hooked_peak = measure(make)
     step(make(record=True))                                   # events are created lazily: once untimed
@@ -709,7 +711,8 @@ def bench_hooks(args, api, W, dev) -> dict:
         "value": round(in_bytes / (pc + rc) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(hooked_s * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "hooks_transformer_ffn_l12_b16_s512_bf16_g64_b2_stochastic" + ("_channel_wise" if args.channel_wise else ""),
+        "config": {"workload": "hooks_transformer_ffn_l12_b16_s512_bf16_g64_b2_stochastic" + ("_channel_wise" if args.channel_wise else "")
+                   + (f"_batches_{args.batch_mib}MiB" if args.batch_mib > 0 else ""),
                    "layers": layers,
                    "tensors_compressed": len(recs), "input_bytes": in_bytes,
                    "entry_point": ("fh_classify_channels + fh_channel_slots + fh_compress_mixed / fh_decompress_mixed"
@@ -754,6 +757,8 @@ def main() -> int:
                     help="restore bf16 tensors to bf16 instead of fp32 (configuration 4's second figure)")
     ap.add_argument("--channel-wise", action="store_true",
                     help="--op hooks: classify every saved tensor's hidden channels and keep the salient ones raw")
+    ap.add_argument("--batch-mib", type=int, default=0, metavar="N",
+                    help="--op hooks: compress saved tensors in batches of N MiB through the batched entry points")
     ap.add_argument("--warm", action="store_true",
                     help="--op roundtrip: time compress and decompress back to back (codes still in the "
                          "memory-side cache) instead of the cold protocol")

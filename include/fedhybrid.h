@@ -212,6 +212,12 @@ fh_status fh_channel_slots(const void *mask, int64_t channels, int64_t raw_chann
 /* The same, and *used (device uint64, 8-byte aligned) = raw-store rows in use = min(salient channels, raw_channels). */
 fh_status fh_channel_slots_used(const void *mask, int64_t channels, int64_t raw_channels, void *slots, void *used,
                                 void *stream);
+/* The same for several tensors with one launch per fh_mixed_batch_capacity() of them (used may be NULL). */
+typedef struct fh_slots_item {
+    const void *mask;       int64_t channels, raw_channels;
+    void       *slots;      void *used;
+} fh_slots_item;
+fh_status fh_channel_slots_batch(const fh_slots_item *items, int32_t count, void *stream);
 fh_status fh_compress_mixed(const void *x, fh_dtype x_dtype, int64_t outer, int64_t channels, int64_t inner,
                             const fh_params *params, const void *slots, int64_t raw_channels,
                             void *packed, size_t packed_cap, void *meta, size_t meta_cap,

@@ -32,7 +32,7 @@ EXPORTS = ("fh_packed_bytes", "fh_meta_bytes", "fh_compress", "fh_decompress", "
            "fh_compress_batch", "fh_decompress_batch", "fh_roundtrip_batch", "fh_batch_capacity",
            "fh_classify_workspace_bytes", "fh_classify_channels", "fh_classify_channels_batch",
            "fh_classify_batch_capacity", "fh_classify_static_scratch_bytes", "fh_classify_channels_static",
-           "fh_raw_bytes", "fh_channel_slots", "fh_channel_slots_used", "fh_compress_mixed", "fh_decompress_mixed",
+           "fh_raw_bytes", "fh_channel_slots", "fh_channel_slots_used", "fh_channel_slots_batch", "fh_compress_mixed", "fh_decompress_mixed",
            "fh_compress_mixed_batch", "fh_decompress_mixed_batch", "fh_mixed_batch_capacity",
            "fh_sparse_info_bytes", "fh_sparse_index_bytes", "fh_sparse_workspace_bytes", "fh_sparse_encode",
            "fh_sparse_decode", "fh_sparse_encode_batch", "fh_sparse_decode_batch", "fh_sparse_batch_capacity",
@@ -74,6 +74,11 @@ class fh_mixed_item(ctypes.Structure):
                 ("raw_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("out", ctypes.c_void_p), ("out_cap", ctypes.c_size_t),
                 ("params", fh_params), ("rows_in_use", ctypes.c_void_p)]
+
+
+class fh_slots_item(ctypes.Structure):
+    _fields_ = [("mask", ctypes.c_void_p), ("channels", ctypes.c_int64), ("raw_channels", ctypes.c_int64),
+                ("slots", ctypes.c_void_p), ("used", ctypes.c_void_p)]
 
 
 class fh_sparse_encode_item(ctypes.Structure):
@@ -137,6 +142,8 @@ _lib.fh_channel_slots.restype = ctypes.c_int
 _lib.fh_channel_slots_used.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p]
 _lib.fh_channel_slots_used.restype = ctypes.c_int
+_lib.fh_channel_slots_batch.argtypes = [_P(fh_slots_item), ctypes.c_int32, ctypes.c_void_p]
+_lib.fh_channel_slots_batch.restype = ctypes.c_int
 _lib.fh_compress_mixed.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                    _P(fh_params), ctypes.c_void_p, ctypes.c_int64,
                                    ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
@@ -526,6 +533,24 @@ def fh_channel_slots(mask: torch.Tensor, raw_channels: int, slots: Optional[torc
         _check(_lib.fh_channel_slots_used(mask.data_ptr(), channels, int(raw_channels), slots.data_ptr(),
                                           None if used is None else used.data_ptr(), _stream_ptr(stream)))
     return slots
+
+
+def fh_channel_slots_batch(masks: Sequence[torch.Tensor], raw_channels: Sequence[int], stream=None):
+    """Slot numbering for several tensors with one launch per 16 of them; returns (slots, used): lists
+    of device tensors int16[channels] and int64[1] (raw-store rows in use)."""
+    if not masks:
+        return [], []
+    dev = masks[0].device
+    items = (fh_slots_item * len(masks))()
+    slots, used = [], torch.empty(len(masks), dtype=torch.int64, device=dev)
+    for k, (m, rc) in enumerate(zip(masks, raw_channels)):
+        _device_tensor(m, "mask")
+        s_k = torch.empty(m.numel(), dtype=torch.int16, device=dev)
+        slots.append(s_k)
+        items[k] = fh_slots_item(m.data_ptr(), m.numel(), int(rc), s_k.data_ptr(), used[k:].data_ptr())
+    with torch.cuda.device(dev):
+        _check(_lib.fh_channel_slots_batch(items, len(masks), _stream_ptr(stream)))
+    return slots, [used[k:k + 1] for k in range(len(masks))]
 
 
 def fh_compress_mixed(x: torch.Tensor, outer: int, channels: int, inner: int, slots: torch.Tensor,

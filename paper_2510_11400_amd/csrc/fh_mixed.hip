@@ -17,9 +17,8 @@ constexpr int kSlotPerThread = 16;                 // 1024 * 16 = the largest ch
 // slots[c] = number of salient channels before c, for salient channels while that number is
 // below raw_channels; -1 for every other channel.  One workgroup: each thread owns 16
 // consecutive channels, the per-thread counts are scanned through LDS.
-__global__ __launch_bounds__(kSlotThreads) void channel_slots_kernel(const uint8_t* __restrict__ mask, int channels,
-                                                                      int raw_channels, int16_t* __restrict__ slots,
-                                                                      uint64_t* __restrict__ used)
+__device__ __forceinline__ void number_slots(const uint8_t* __restrict__ mask, int channels, int raw_channels,
+                                             int16_t* __restrict__ slots, uint64_t* __restrict__ used)
 {
     __shared__ int scan[kSlotThreads];
     const int t = threadIdx.x;
@@ -46,6 +45,21 @@ __global__ __launch_bounds__(kSlotThreads) void channel_slots_kernel(const uint8
         if (mask[c] != 0) ++rank;
     }
     if (used && t == kSlotThreads - 1) *used = (uint64_t)(scan[t] < raw_channels ? scan[t] : raw_channels);
+}
+
+struct SlotsJob {
+    const uint8_t* mask;
+    int16_t*       slots;
+    uint64_t*      used;
+    int32_t        channels, raw_channels;
+};
+struct SlotsBatch { SlotsJob job[kBatch]; };
+
+// one workgroup per tensor
+__global__ __launch_bounds__(kSlotThreads) void channel_slots_kernel(const SlotsBatch batch)
+{
+    const SlotsJob& j = batch.job[blockIdx.x];
+    number_slots(j.mask, j.channels, j.raw_channels, j.slots, j.used);
 }
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -102,16 +116,37 @@ size_t fh_raw_bytes(int64_t outer, int64_t raw_channels, int64_t inner, fh_dtype
     return (size_t)outer * (size_t)raw_channels * (size_t)inner * fh::elem_size(dtype);
 }
 
+fh_status fh_channel_slots_batch(const fh_slots_item* items, int32_t count, void* stream)
+{
+    if (count < 0) return FH_ERR_BAD_COUNT;
+    if (count > 0 && !items) return FH_ERR_NULL;
+    for (int32_t i = 0; i < count; ++i) {                     // everything is checked before the first launch
+        const fh_slots_item& it = items[i];
+        if (it.channels < 1 || it.channels > 16384 || it.raw_channels < 0 || it.raw_channels > it.channels) return FH_ERR_BAD_SHAPE;
+        if (!it.mask || !it.slots) return FH_ERR_NULL;
+        if (!fh::aligned(it.slots, 16) || !fh::aligned(it.used, 8)) return FH_ERR_ALIGNMENT;
+    }
+    for (int32_t i = 0; i < count;) {
+        fh::SlotsBatch b;
+        int n = 0;
+        for (; i < count && n < fh::kBatch; ++i, ++n) {
+            const fh_slots_item& it = items[i];
+            b.job[n] = fh::SlotsJob{static_cast<const uint8_t*>(it.mask), static_cast<int16_t*>(it.slots),
+                                    static_cast<uint64_t*>(it.used), (int32_t)it.channels, (int32_t)it.raw_channels};
+        }
+        for (int k = n; k < fh::kBatch; ++k) b.job[k] = b.job[0];
+        hipLaunchKernelGGL(fh::channel_slots_kernel, dim3(n), dim3(fh::kSlotThreads), 0, static_cast<hipStream_t>(stream), b);
+    }
+    if (count == 0) return FH_OK;
+    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+}
+
 fh_status fh_channel_slots_used(const void* mask, int64_t channels, int64_t raw_channels, void* slots, void* used,
                                 void* stream)
 {
-    if (channels < 1 || channels > 16384 || raw_channels < 0 || raw_channels > channels) return FH_ERR_BAD_SHAPE;
-    if (!mask || !slots) return FH_ERR_NULL;
-    if (!fh::aligned(slots, 16) || !fh::aligned(used, 8)) return FH_ERR_ALIGNMENT;
-    hipLaunchKernelGGL(fh::channel_slots_kernel, dim3(1), dim3(fh::kSlotThreads), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint8_t*>(mask), (int)channels, (int)raw_channels,
-                       static_cast<int16_t*>(slots), static_cast<uint64_t*>(used));
-    return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
+    fh_slots_item it;
+    it.mask = mask; it.channels = channels; it.raw_channels = raw_channels; it.slots = slots; it.used = used;
+    return fh_channel_slots_batch(&it, 1, stream);
 }
 
 fh_status fh_channel_slots(const void* mask, int64_t channels, int64_t raw_channels, void* slots, void* stream)

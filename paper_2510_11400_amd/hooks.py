@@ -56,7 +56,10 @@ class TensorRecord:
 
     @property
     def purge_cost(self) -> Optional[float]:   # PC, seconds; call after the stream has drained
-        return None if self._pack is None else self._pack[0].elapsed_time(self._pack[1]) * 1e-3
+        if self._pack is None:
+            return None
+        share = self._pack[2] if len(self._pack) > 2 else 1.0     # this tensor's part of a batched call, by bytes
+        return self._pack[0].elapsed_time(self._pack[1]) * 1e-3 * share
 
     @property
     def regain_cost(self) -> Optional[float]:  # RC, seconds
@@ -77,6 +80,15 @@ class _Packed:
         self.mixed = mixed                 # (outer, channels, inner, slots, raw_channels, raw) on the channel-wise path
 
 
+class _Deferred:
+    """A tensor handed to the pack hook that waits for its batch: `handle` is the packed form once
+    the batch has been compressed, and the tensor itself is let go then."""
+    __slots__ = ("x", "tid", "shape", "dtype", "split", "handle")
+
+    def __init__(self, x, tid, shape, dtype, split):
+        self.x, self.tid, self.shape, self.dtype, self.split, self.handle = x, tid, shape, dtype, split, None
+
+
 class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
     """Context manager: tensors that autograd saves inside it are stored compressed.
 
@@ -94,13 +106,22 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
     ones, are kept verbatim beside the quantised stream, so that their outliers do not stretch
     the range of the groups they sit in.  All of it is enqueued on the stream; nothing waits
     for the classification's result.
+
+    With `batch_bytes` > 0 tensors are compressed in batches: the pack hook only notes a tensor,
+    and once `batch_bytes` of them wait (or one of them is needed back, or the context ends) the
+    whole batch goes through the batched entry points -- a handful of launches for the batch
+    instead of one to seven per tensor, at the price of holding up to `batch_bytes` of
+    activations uncompressed a little longer.  Results are the same bytes either way.
     """
 
     def __init__(self, group_size: int = 256, bits: int = 4, rounding="nearest", seed: int = 0,
                  min_numel: int = 4096, first_tensor_id: int = 0, record: bool = False, exclude=(),
                  channel_dim: Optional[int] = None, k_sigma: float = 3.0, outlier_share: float = 0.01,
-                 raw_share: float = 1.0 / 16.0):
+                 raw_share: float = 1.0 / 16.0, batch_bytes: int = 0):
         self.group_size, self.bits, self.rounding, self.seed = group_size, bits, rounding, seed
+        self.batch_bytes = int(batch_bytes)
+        self._pending: List[_Deferred] = []
+        self._pending_bytes = 0
         self.min_numel = min_numel
         self.channel_dim, self.k_sigma, self.outlier_share, self.raw_share = channel_dim, k_sigma, outlier_share, raw_share
         self.next_tensor_id = first_tensor_id
@@ -121,6 +142,13 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
             x = x.clone()
         tid = self.next_tensor_id
         self.next_tensor_id += 1
+        if self.batch_bytes > 0:
+            d = _Deferred(x, tid, t.shape, t.dtype, self._split(x))
+            self._pending.append(d)
+            self._pending_bytes += x.numel() * x.element_size()
+            if self._pending_bytes >= self.batch_bytes:
+                self.flush()
+            return d
         stream = torch.cuda.current_stream(x.device)
         rec = None
         if self.record:
@@ -151,6 +179,61 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
             self.records.append(rec)
         return _Packed(packed, meta, t.shape, t.dtype, x.numel(), rec, mixed)
 
+    def flush(self) -> None:
+        """Compress every tensor that waits for its batch (batched entry points, current stream)."""
+        pending, self._pending, self._pending_bytes = self._pending, [], 0
+        if not pending:
+            return
+        stream = torch.cuda.current_stream(pending[0].x.device)
+        ev = None
+        if self.record:
+            ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            ev[0].record(stream)
+        plain = [d for d in pending if d.split is None]
+        routed = [d for d in pending if d.split is not None]
+        stored = {}
+        if plain:
+            entries = []
+            for d in plain:
+                packed, meta = api.alloc_compressed(d.x.numel(), self.group_size, self.bits, d.x.device)
+                entries.append(api.BatchEntry(self.group_size, self.bits, self.rounding, self.seed, d.tid,
+                                              x=d.x.view(-1), packed=packed, meta=meta))
+            api.fh_compress_batch(api.Batch(entries), stream)
+            for d, e in zip(plain, entries):
+                d.handle = _Packed(e.packed, e.meta, d.shape, d.dtype, d.x.numel(), None)
+                stored[id(d)] = e.packed.numel() + e.meta.numel() * e.meta.element_size()
+        if routed:
+            cls = api.ClassifyBatch([api.ClassifyEntry(d.x.view(-1), d.split[0], d.split[1], d.split[2], self.k_sigma,
+                                                       max(1, int(d.split[0] * d.split[2] * self.outlier_share)))
+                                     for d in routed])
+            api.fh_classify_channels_batch(cls, stream)
+            slots, used = api.fh_channel_slots_batch([e.mask for e in cls.entries], [d.split[3] for d in routed], stream)
+            mixed = api.MixedBatch([api.MixedEntry(d.split[0], d.split[1], d.split[2], slots[k], d.split[3],
+                                                   self.group_size, self.bits, self.rounding, self.seed, d.tid,
+                                                   x=d.x.view(-1), rows_in_use=used[k])
+                                    for k, d in enumerate(routed)])
+            api.fh_compress_mixed_batch(mixed, stream)
+            for k, (d, e) in enumerate(zip(routed, mixed.entries)):
+                outer, channels, inner, raw_channels = d.split
+                d.handle = _Packed(e.packed, e.meta, d.shape, d.dtype, d.x.numel(), None,
+                                   (outer, channels, inner, slots[k], raw_channels, e.raw, used[k]))
+                stored[id(d)] = (e.packed.numel() + e.meta.numel() * e.meta.element_size()
+                                 + e.raw.numel() * e.raw.element_size() + slots[k].numel() * 2)
+        if ev is not None:
+            ev[1].record(stream)
+            total = float(sum(d.x.numel() * d.x.element_size() for d in pending))
+            for d in pending:
+                nbytes = d.x.numel() * d.x.element_size()
+                d.handle.record = TensorRecord(d.tid, d.x.numel(), d.x.dtype, nbytes, stored[id(d)],
+                                               _pack=(ev[0], ev[1], nbytes / total))
+                self.records.append(d.handle.record)
+        for d in pending:
+            d.x = None                                        # the activation itself may go now
+
+    def __exit__(self, *exc):
+        self.flush()
+        return super().__exit__(*exc)
+
     def _split(self, x: torch.Tensor):
         """(outer, channels, inner, raw_channels) of the channel-wise path, or None for the plain one."""
         if self.channel_dim is None or x.dim() == 0 or x.numel() > 2 ** 31:
@@ -166,6 +249,10 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
         return outer, channels, inner, max(1, min(channels, int(channels * self.raw_share + 0.5)))
 
     def _unpack(self, h):
+        if isinstance(h, _Deferred):
+            if h.handle is None:
+                self.flush()                                  # needed back before its batch was full
+            h = h.handle
         if not isinstance(h, _Packed):
             return h
         stream = torch.cuda.current_stream(h.packed.device)

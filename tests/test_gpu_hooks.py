@@ -236,3 +236,56 @@ def test_a_contiguous_view_at_an_odd_storage_offset_is_compressed_from_a_copy(ho
     assert len(ctx.records) == 1
     want = _oracle_roundtrip(x.detach().cpu().contiguous(), 64, 8, "nearest", 0, 0, "f32")
     assert torch.equal(_Probe.seen[0].cpu().view(torch.int32), want.view(torch.int32))
+
+
+@pytest.mark.parametrize("channel_wise", [False, True])
+@pytest.mark.parametrize("batch_bytes", [1, 300_000, 1 << 30])
+def test_tensors_compressed_in_batches_give_the_same_bytes(hooks, channel_wise, batch_bytes):
+    """batch_bytes > 0: the pack hook only notes a tensor; the batch goes through the batched entry points
+    when it is full (1: every tensor at once; 300 kB: every few), when the context ends (1 GiB), or when
+    a tensor is needed back first.  What backward sees is the oracle's result for each tensor's own id."""
+    from paper_2510_11400_amd import workloads as W
+    print(f"[hooks] batches of {batch_bytes} bytes, channel-wise {channel_wise}", flush=True)
+    shapes = [(6, 40, 10, 10), (50, 96), (3, 16, 33), (9000,), (12, 24, 7, 7), (64, 128)]
+    G, B, rounding, seed = 64, 4, "stochastic", 21
+    hosts = []
+    for k, shp in enumerate(shapes):
+        if len(shp) >= 2:
+            outer, C, inner = shp[0], shp[1], int(np.prod(shp[2:])) if len(shp) > 2 else 1
+            x_np, _ = W.outlier_channel_tensor(outer, C, inner, seed=k, dist="gauss", salient_fraction=0.1)
+        else:
+            x_np = np.random.default_rng(k).standard_normal(shp[0]).astype(np.float32)
+        hosts.append(torch.from_numpy(x_np).reshape(shp))
+    _Probe.seen.clear()
+    xs = [h.cuda().requires_grad_(True) for h in hosts]
+    kw = {"channel_dim": 1} if channel_wise else {}
+    ctx = hooks.SavedActivations(G, B, rounding, seed=seed, min_numel=1, first_tensor_id=3, batch_bytes=batch_bytes,
+                                 record=True, **kw)
+    with ctx:
+        total = sum(_Probe.apply(x).sum() for x in xs[:4])
+        if batch_bytes == 300_000:
+            early = torch.autograd.grad(_Probe.apply(xs[4]).sum(), xs[4])[0]     # needed back before its batch is full
+            assert early.shape == xs[4].shape
+            first_seen = _Probe.seen.pop()
+        else:
+            total = total + _Probe.apply(xs[4]).sum()
+            first_seen = None
+        total = total + _Probe.apply(xs[5]).sum()
+    total.backward()
+    torch.cuda.synchronize()
+    assert ctx.next_tensor_id == 3 + len(xs) and not ctx._pending
+    seen = {}
+    order = [5, 3, 2, 1, 0] if first_seen is not None else [5, 4, 3, 2, 1, 0]           # backward visits them in reverse
+    for k, got in zip(order, _Probe.seen):
+        seen[k] = got
+    if first_seen is not None:
+        seen[4] = first_seen
+    for k, h in enumerate(hosts):
+        shp = shapes[k]
+        if channel_wise:
+            outer, C, inner = (shp[0], shp[1], int(np.prod(shp[2:])) if len(shp) > 2 else 1) if len(shp) >= 2 else (1, shp[0], 1)
+            want, _ = _oracle_channel_wise(h, outer, C, inner, G, B, rounding, seed, 3 + k, "f32", 3.0, 0.01, 1.0 / 16.0)
+        else:
+            want = _oracle_roundtrip(h, G, B, rounding, seed, 3 + k, "f32")
+        assert torch.equal(seen[k].cpu().view(torch.int32), want.view(torch.int32)), f"tensor {k}"
+    assert len(ctx.records) == len(xs) and all(r.purge_cost is not None and r.purge_cost >= 0 for r in ctx.records)

@@ -166,3 +166,28 @@ def test_a_truncated_stream_is_refused():
         oracle.huffman_decode(stream[:-4], data.size)
     with pytest.raises(ValueError):
         oracle.huffman_decode(stream[:200], data.size)
+
+
+def test_room_the_encoder_asks_for_is_the_worst_case_of_the_layout():
+    """fho_huffman_stream_bytes: 256 length bytes, one offset per chunk of 256 symbols plus one,
+    and for every chunk 256 symbols of the longest code the limit allows (24 bits = 192 words).
+    Pinned by the layout's arithmetic and by streams that come as close to the bound as data can:
+    uniform bytes (8 bits per symbol) and the comb whose rarest symbols carry 24-bit codes."""
+    size = oracle.lib().fho_huffman_stream_bytes
+    for n in (0, 1, 255, 256, 257, 4096, 65_537, 10 ** 6 + 3):
+        chunks = -(-n // 256)
+        assert size(n) == 256 + 4 * (chunks + 1) + 4 * (256 * 24 // 32) * chunks
+    rng = np.random.default_rng(0)
+    uniform = rng.integers(0, 256, 70_001).astype(np.uint8)
+    fib = [1, 1]
+    while len(fib) < 28:
+        fib.append(fib[-1] + fib[-2])
+    comb = np.repeat(np.arange(10, 38, dtype=np.uint8), fib)
+    rare_first = comb[np.argsort(np.repeat(fib, fib), kind="stable")]      # the long codes crowd the first chunks
+    for data in (uniform, comb, rare_first, np.zeros(300, np.uint8)):
+        stream, bits = oracle.huffman_encode(data)
+        assert stream.size <= size(data.size)
+        lengths = stream[:256].astype(np.int64)
+        chunk_bits = [int(lengths[data[c:c + 256]].sum()) for c in range(0, data.size, 256)]
+        assert max(chunk_bits) <= 256 * 24 and bits == sum(chunk_bits)
+        assert stream.size == 256 + 4 * (len(chunk_bits) + 1) + 4 * sum(-(-b // 32) for b in chunk_bits)
