@@ -19,7 +19,9 @@ typedef float    f32x2 __attribute__((ext_vector_type(2)));
 // The activation and the restored tensor are each touched once per call and are far larger
 // than any cache: they are loaded and stored with the non-temporal hint (measured on MI355X:
 // ordinary loads of the activation evict the code stream from the memory-side cache and cost
-// the round trip 15 %).
+// the round trip 15 %; stores with the sc1 / sc0 sc1 scope bits, which write through, restore the
+// 2 GiB mixed set 2 % slower than the non-temporal ones when the codes are cold and 13 % slower
+// back to back, although they are 7-8 % faster on the two small-group sets).
 template <typename T>
 __device__ __forceinline__ T stream_load(const T* p) { return __builtin_nontemporal_load(p); }
 template <typename T>

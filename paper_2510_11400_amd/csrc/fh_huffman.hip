@@ -47,7 +47,10 @@ constexpr int kWriteStageWords = 12288;            // encode: LDS for a workgrou
 // chunks (twelve waves) where workgroups of 256 with their own tables held 512.
 constexpr int kDecodeThreads = 768;
 constexpr int kDecodeThreadsSmall = 256;           // ... of a launch that would leave compute units idle with 768
-constexpr int kStageWordsPerChunk = 48;            // decode: LDS for a workgroup's payload slice: 6 bits per symbol
+// decode: LDS for a workgroup's payload slice, in words per chunk: 48 (6 bits per symbol) is what fits beside the
+// tables when one workgroup of 768 takes the whole LDS; two workgroups of 256 per unit have room for 64 (8 bits per
+// symbol: any slice fits on average, and streams of 7-8 bits per symbol no longer fall back to the rings)
+template <int THREADS> struct StageWords { static constexpr int kPerChunk = THREADS >= 768 ? 48 : 64; };
 constexpr int kComputeUnits = 256;                 // MI355X
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -461,25 +464,48 @@ struct LongCodes {
     uint8_t  sorted[256];                                     // symbols by (length, symbol)
 };
 
-// The symbol whose code, longer than kFastBits, is on top of `window`, as symbol | length << 8 like an entry of the
-// fast table.  Such codes belong to symbols rarer than one in 2^kFastBits, so this is a call of a rolled loop that
-// reads LDS: the code of the common path around it stays short.  The shortest matching length wins and no match
-// consumes one bit (only a stream that no encoder wrote can have either).
-__device__ __noinline__ uint32_t decode_long(uint64_t window, const LongCodes* t)
+// The symbol whose code, longer than kFastBits, is on top of the stream, as symbol | length << 8 like an entry of the
+// fast table.  The shortest matching length wins and no match consumes one bit (only a stream that no encoder wrote
+// can have either).
+// No loop over LDS: the per-length tables of the lengths beyond the fast table's index, the same
+// for the whole workgroup, held in scalar registers.  A long code is rare per symbol, but a wave takes this path
+// whenever ANY of its 64 lanes meets one -- one step in six on streams of five bits per symbol -- so its cost is
+// paid by all: twelve lengths of shift, subtract, compare and select, then one LDS read, instead of a rolled
+// loop of dependent LDS reads.  `top`: the next 32 bits of the stream.
+struct LongRegs {
+    uint32_t first[kMaxLen - kFastBits], count[kMaxLen - kFastBits], start[kMaxLen - kFastBits];   // lengths kFastBits + 1 ...
+};
+__device__ __forceinline__ LongRegs long_regs(const LongCodes* t)
 {
-#pragma unroll 1
-    for (int k = kFastBits + 1; k <= kMaxLen; ++k) {
-        const uint32_t code = (uint32_t)(window >> (64 - k)), count = t->per_length[k], first = t->first[k];
-        if (count && code >= first && code - first < count)
-            return t->sorted[(t->start[k] + code - first) & 0xffu] | ((uint32_t)k << 8);
+    LongRegs r;
+#pragma unroll
+    for (int i = 0; i < kMaxLen - kFastBits; ++i) {
+        const int k = kFastBits + 1 + i;
+        r.first[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)t->first[k]);
+        r.count[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)t->per_length[k]);
+        r.start[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)t->start[k]);
     }
-    return 1u << 8;
+    return r;
+}
+__device__ __forceinline__ uint32_t decode_long(uint32_t top, const LongRegs& r, const uint8_t* sorted)
+{
+    uint32_t at = 0, length = 0;
+#pragma unroll
+    for (int i = kMaxLen - kFastBits - 1; i >= 0; --i) {      // downwards: the shortest matching length is the one that stays
+        const int k = kFastBits + 1 + i;
+        const uint32_t off = (top >> (32 - k)) - r.first[i];  // wraps to a huge value below the first code
+        const bool hit = off < r.count[i];
+        at = hit ? r.start[i] + off : at;
+        length = hit ? (uint32_t)k : length;
+    }
+    return length ? sorted[at & 0xffu] | (length << 8) : 1u << 8;   // no match consumes one bit (foreign streams only)
 }
 
 template <typename NextWord>
 __device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const uint16_t* fast, const LongCodes* tables,
                                              NextWord next_word)
 {
+    const LongRegs longer = long_regs(tables);
     uint32_t taken = 0;                                       // words moved into `buf`
     uint64_t buf = 0;                                         // pending bits, the next one on top
     uint32_t have = 0;
@@ -501,7 +527,7 @@ __device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const
                         have += 32u;
                     }
                     uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
-                    if (!e) e = decode_long(buf, tables);
+                    if (!e) e = decode_long((uint32_t)(buf >> 32), longer, tables->sorted);
                     const uint32_t symbol = e & 0xffu, used_bits = e >> 8;
                     buf <<= used_bits;
                     have -= used_bits;
@@ -535,6 +561,7 @@ __device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst
     // symbol advances by at most 24 bits, one word, so after it the registers move up by one at most, and w2 is
     // read again for the new position: that read is needed one symbol later, so that a symbol waits for one LDS
     // access in a row (the table) rather than two (words, then table).
+    const LongRegs longer = long_regs(tables);
     uint32_t pos = 0, at = 0;                                 // bits of the chunk consumed; at = pos / 32
     uint32_t w0 = words[0], w1 = words[1], w2 = words[2];
     for (uint32_t half = 0; half < valid; half += 16 * kBurst) {
@@ -550,7 +577,7 @@ __device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst
                 for (int b = 0; b < 4; ++b) {
                     const uint32_t top = (uint32_t)(((((uint64_t)w0 << 32) | w1) << (pos & 31u)) >> 32);   // the next 32 bits
                     uint32_t e = fast[top >> (32 - kFastBits)];
-                    if (!e) e = decode_long((uint64_t)top << 32, tables);   // rare (one test for four symbols was measured slower)
+                    if (!e) e = decode_long(top, longer, tables->sorted);
                     four |= (e & 0xffu) << (8 * b);
                     pos += e >> 8;
                     const bool crossed = (pos >> 5) != at;
@@ -584,7 +611,7 @@ __device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst
 template <int kDecodeThreads>
 __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Batch<DecodeJob> batch)
 {
-    constexpr int kStageWords = kDecodeThreads * kStageWordsPerChunk;
+    constexpr int kStageWords = kDecodeThreads * StageWords<kDecodeThreads>::kPerChunk;
     uint32_t block;
     const DecodeJob& job = batch.item[batch_item(batch, blockIdx.x, block)];
     const uint8_t* len_in = job.len;
