@@ -189,6 +189,8 @@ fh_status fh_classify_channels_static(const void *x, fh_dtype x_dtype, int64_t o
  *     channel (i / inner) mod channels;
  *   - slots[c] (int16) is the row of the raw store that keeps channel c, 0 <= slot <
  *     raw_channels; any other value (fh_channel_slots writes -1) means "normal channel";
+ *     no two channels may name the same row (for such a table every access still stays
+ *     inside the buffers, but which of the channels the row then holds is unspecified);
  *   - fh_channel_slots numbers the channels whose mask byte is non-zero 0, 1, 2, ... in
  *     channel order; once raw_channels slots are used the remaining ones stay normal;
  *   - raw is [outer][raw_channels][inner] in the input's dtype; an element of a kept channel

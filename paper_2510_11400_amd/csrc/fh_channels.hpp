@@ -64,7 +64,7 @@ struct ChannelMap {
     uint32_t       raw_channels;
     const uint64_t* rows_in_use;  // device, or null: raw-store rows in use; 0 there = no channel of this tensor is kept
     ExactDiv       inner_exact, channels_exact;
-    SmallDiv       inner, channels;
+    SmallDiv       inner, channels, raw_div;   // raw_div: by raw_channels (1 when there are none)
 };
 
 struct ElemPos {
@@ -180,75 +180,123 @@ __device__ __forceinline__ void kept_runs(const ChannelMap& cm, const ElemPos& w
     }
 }
 
-// ---- one channel per element --------------------------------------------------------------
-// With inner == 1, channels a multiple of N and at most 16384 raw-store rows, the N channels of
-// a lane's run never wrap and their table entries are one vector load; what the lane needs then
-// comes out of packed 16-bit arithmetic on the entry pairs, with no branch and no per-element
-// compare: an entry s names a row iff 0 <= s < raw_channels, i.e. iff bit 15 of ~s & (s - raw_channels)
-// is set (s - raw_channels cannot wrap: both are below 2^15 in magnitude).
-typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
-typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+// ---- one channel per element: the kept elements of a span, listed by raw-store row -----------
+// With inner == 1 a raw-store row holds one element per sample, and the kept elements of a
+// wave's span are few and scattered (a few per cent of the channels).  Instead of every lane
+// testing each of its elements, the workgroup lists once which channel each raw-store row keeps
+// (`rows`: LDS, uint16 per row, kNoChannel for a row that keeps none; two channels must not name
+// the same row), and the lanes of a wave walk the (sample, row) pairs of the span: the element's
+// position follows from the pair by one multiply-add, and the raw-store side of consecutive
+// lanes is contiguous.  The wave's elements themselves pass through LDS once, where the pairs
+// read or patch them.
+constexpr uint32_t kListedRows = 2048;                        // raw-store rows the list has room for
+constexpr uint32_t kNoChannel = 0xffffu;                      // channels are below 2^14
 
-template <int N> struct KeptVector {
-    uint32_t keep[N / 2];      // half-word j: 0xffff iff element j belongs to a kept channel
-    uint32_t slot[N / 2];      // half-word j: that channel's raw-store row times the element size, 0 for a normal channel
-    uint32_t row;              // byte offset of (the run's sample, row 0) from the row 0 of the wave's first sample
+__device__ __forceinline__ bool rows_listed(const ChannelMap& cm)
+{
+    return cm.inner.d == 1u && cm.raw_channels - 1u < kListedRows;
+}
+
+// The list is built in two steps so that a kernel can put its own loads between them: the table entries a
+// thread is responsible for are requested first (two channels per 4-byte load, the first kSlotRounds * 2 * THREADS
+// channels), and filed once they have arrived.  An entry names a row iff, read as an unsigned 16-bit number, it is
+// below raw_channels (<= 2048: negative entries read as 32768 or more).  Every thread of the workgroup calls both;
+// the second ends with a barrier.
+constexpr int kSlotRounds = 8;
+struct SlotWords { uint32_t w[kSlotRounds]; };
+
+template <int THREADS>
+__device__ __forceinline__ void list_rows_request(const ChannelMap& cm, SlotWords& words)
+{
+    const uint32_t C = cm.channels.d;
+    const uint32_t* table = reinterpret_cast<const uint32_t*>(cm.slots);   // 16-byte aligned
+#pragma unroll
+    for (int k = 0; k < kSlotRounds; ++k) {
+        const uint32_t c = 2u * (threadIdx.x + k * THREADS);
+        words.w[k] = 0xffffffffu;
+        if (2u * k * THREADS >= C) continue;                  // workgroup-uniform
+        if (c + 1u < C) words.w[k] = table[c >> 1];
+        else if (c < C) words.w[k] = 0xffff0000u | (uint16_t)cm.slots[c];  // an odd channel count's last entry
+    }
+}
+
+template <int THREADS>
+__device__ __forceinline__ void list_rows_file(const ChannelMap& cm, const SlotWords& words, uint16_t* rows)
+{
+    for (uint32_t s = threadIdx.x; s < cm.raw_channels; s += THREADS) rows[s] = (uint16_t)kNoChannel;
+    __syncthreads();
+    const uint32_t C = cm.channels.d, R = cm.raw_channels;
+#pragma unroll
+    for (int k = 0; k < kSlotRounds; ++k) {
+        const uint32_t c = 2u * (threadIdx.x + k * THREADS);
+        if (2u * k * THREADS >= C) break;                     // workgroup-uniform
+        const uint32_t lo = words.w[k] & 0xffffu, hi = words.w[k] >> 16;
+        if (lo < R) rows[lo] = (uint16_t)c;
+        if (hi < R) rows[hi] = (uint16_t)(c + 1u);
+    }
+    for (uint32_t c = 2u * kSlotRounds * THREADS + threadIdx.x; c < C; c += THREADS) {   // beyond 4096 channels
+        const uint32_t s = (uint16_t)cm.slots[c];
+        if (s < R) rows[s] = (uint16_t)c;
+    }
+    __syncthreads();
+}
+
+// The (sample, row) pairs a wave's span of `span` elements can hold: `samples` samples starting at the
+// first element's, each with raw_channels rows.  pairs <= span + 2 * raw_channels <= 6144.
+__device__ __forceinline__ uint32_t span_pairs(const ChannelMap& cm, const ElemPos& wave_pos, uint32_t span)
+{
+    const uint32_t samples = div_exact(wave_pos.c + span - 1u, cm.channels_exact) + 1u;
+    return samples * cm.raw_channels;
+}
+
+// A lane's walk over the pairs lane, lane + 64, lane + 128, ...: pair i is (sample i / raw_channels of the span,
+// row i % raw_channels), kept up to date by additions (64 = q * raw_channels + r, so a step adds r to the row, q -- or
+// q + 1 when the row wraps -- to the sample).  `u` is the offset inside the span of the sample's channel 0, so the
+// pair's element sits at offset u + (the row's channel); a row that keeps no channel (kNoChannel = 65535) and a
+// sample beyond the span's last both give an offset of `span` or more -- also when u is "negative", wrapped --, so
+// that one comparison decides whether the pair is a kept element of this span.  The pair's index in the raw store,
+// less that of (the span's first sample, row 0), is i itself.
+struct PairWalk {
+    uint32_t row, u;           // per lane
+    uint32_t row_step, u_step; // wave-uniform
 };
 
-template <int N>
-__device__ __forceinline__ bool one_channel_per_element(const ChannelMap& cm)
+__device__ __forceinline__ PairWalk pair_walk(const ChannelMap& cm, const ElemPos& wave_pos, uint32_t lane)
 {
-    return cm.inner.d == 1u && (cm.channels.d & (N - 1)) == 0u && cm.raw_channels - 1u < 16384u;
+    PairWalk p;
+    const uint32_t t = div_small(lane, cm.raw_div);
+    p.row = lane - t * cm.raw_channels;
+    p.u = t * cm.channels.d - wave_pos.c;
+    const uint32_t q = div_small(64u, cm.raw_div);
+    p.row_step = 64u - q * cm.raw_channels;
+    p.u_step = q * cm.channels.d;
+    return p;
 }
 
-// elem_shift: log2 of the raw store's element size (1 or 2; rows < 2^14, so the scaled rows fit 16 bits)
-template <int ROWS, int N>
-__device__ __forceinline__ void kept_vectors(const ChannelMap& cm, const ElemPos& wave_pos, uint32_t lane_off,
-                                             uint32_t row_stride, uint32_t elem_shift, KeptVector<N> (&kv)[ROWS])
+// offset inside the span of the current pair's element (>= span: not a kept element of this span); `rows` as listed
+__device__ __forceinline__ uint32_t pair_offset(const PairWalk& p, const uint16_t* rows) { return p.u + rows[p.row]; }
+
+__device__ __forceinline__ void pair_advance(const ChannelMap& cm, PairWalk& p)
 {
-    uint32_t w[ROWS][N / 2];
+    p.row += p.row_step;
+    p.u += p.u_step;
+    const bool wrap = p.row >= cm.raw_channels;
+    p.row = wrap ? p.row - cm.raw_channels : p.row;
+    p.u = wrap ? p.u + cm.channels.d : p.u;
+}
+
+// A lane's first kPairsAhead pairs, worked out before the span's data is needed; leaves the walk at the next pair.
+constexpr int kPairsAhead = 4;
+__device__ __forceinline__ void first_pairs(const ChannelMap& cm, PairWalk& p, const uint16_t* rows, uint32_t pairs,
+                                            uint32_t (&off)[kPairsAhead])
+{
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) {                          // all table loads first
-        const ElemPos p = advance(cm, wave_pos, r * row_stride + lane_off);
-        kv[r].row = ((p.o - wave_pos.o) * cm.raw_channels) << elem_shift;
-        if constexpr (N == 8) {
-            const u32x4 s = *reinterpret_cast<const u32x4*>(cm.slots + p.c);
-            w[r][0] = s.x; w[r][1] = s.y; w[r][2] = s.z; w[r][3] = s.w;
-        } else {
-            const u32x2 s = *reinterpret_cast<const u32x2*>(cm.slots + p.c);
-            w[r][0] = s.x; w[r][1] = s.y;
-        }
+    for (int k = 0; k < kPairsAhead; ++k) {
+        off[k] = 0xffffffffu;
+        if (k * 64u >= pairs) continue;                       // wave-uniform
+        off[k] = pair_offset(p, rows);
+        pair_advance(cm, p);
     }
-    const int16_t rows = (int16_t)cm.raw_channels;
-    const i16x2 limit = {rows, rows};
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r)
-#pragma unroll
-        for (int k = 0; k < N / 2; ++k) {
-            const i16x2 s = __builtin_bit_cast(i16x2, w[r][k]);
-            const i16x2 keep = (~s & (s - limit)) >> 15;      // arithmetic shift: 0xffff or 0 per half
-            kv[r].keep[k] = __builtin_bit_cast(uint32_t, keep);
-            const u16x2 scaled = __builtin_bit_cast(u16x2, w[r][k] & kv[r].keep[k]) << (uint16_t)elem_shift;
-            kv[r].slot[k] = __builtin_bit_cast(uint32_t, scaled);
-        }
-}
-
-// byte offset, from the raw-store row of the wave's first sample, of the entry element j of the run reads or writes
-// (a normal element gets row 0 of its sample, which exists: raw_channels >= 1)
-template <int N>
-__device__ __forceinline__ uint32_t raw_offset(const KeptVector<N>& kv, int j)
-{
-    return ((j & 1) ? kv.slot[j >> 1] >> 16 : kv.slot[j >> 1] & 0xffffu) + kv.row;
-}
-
-// does any lane of the wave hold a kept element in this run? (a wave-uniform answer keeps the branch scalar)
-template <int N>
-__device__ __forceinline__ bool any_kept(const KeptVector<N>& kv)
-{
-    uint32_t any = 0;
-#pragma unroll
-    for (int k = 0; k < N / 2; ++k) any |= kv.keep[k];
-    return __builtin_amdgcn_ballot_w64(any != 0u) != 0ull;
 }
 
 // index into the raw store of element j of the run (whose bit in run.mask must be set)

@@ -19,6 +19,8 @@
 // channels, same section) around the quantiser: their elements are copied to a raw store,
 // turned into NaN -- which v_min_f32 / v_max_f32 ignore -- before the statistics, and get
 // code 0.
+#include <type_traits>
+
 #include "fh_channels.hpp"
 #include "fh_device.hpp"
 #include "fh_kernels.hpp"
@@ -253,14 +255,20 @@ template <> struct Loader<float> {
         const f32x4 v = stream_load(reinterpret_cast<const f32x4*>(p));
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     }
+    __device__ static __forceinline__ void widen(const u32x4& a, float (&x)[4]) {
+        const f32x4 v = __builtin_bit_cast(f32x4, a);         // (a bit cast of one element of a vector reads element 0)
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    }
     __device__ static __forceinline__ float one(const float* base, uint32_t i) { return base[i]; }
 };
 
 template <> struct Loader<uint16_t> {   // bf16 bit patterns; widening is exact
-    __device__ static __forceinline__ void row(const uint16_t* p, float (&x)[8]) {
-        const u32x4 a = stream_load(reinterpret_cast<const u32x4*>(p));
+    __device__ static __forceinline__ void widen(const u32x4& a, float (&x)[8]) {
         x[0] = bf16_lo(a.x); x[1] = bf16_hi(a.x); x[2] = bf16_lo(a.y); x[3] = bf16_hi(a.y);
         x[4] = bf16_lo(a.z); x[5] = bf16_hi(a.z); x[6] = bf16_lo(a.w); x[7] = bf16_hi(a.w);
+    }
+    __device__ static __forceinline__ void row(const uint16_t* p, float (&x)[8]) {
+        widen(stream_load(reinterpret_cast<const u32x4*>(p)), x);
     }
     __device__ static __forceinline__ float one(const uint16_t* base, uint32_t i) {
         return __builtin_bit_cast(float, (uint32_t)base[i] << 16);
@@ -308,27 +316,51 @@ __device__ __forceinline__ void divert_kept(const ChannelMap& cm, const KeptRun<
     }
 }
 
-// The same for one channel per element (fh_channels.hpp).  A kept element becomes a quiet NaN by
-// setting its exponent and top mantissa bit; further down the clamp of the quantiser
-// (v_med3_f32, which returns the minimum of the other two operands for a NaN) turns it into
-// code 0, so nothing else has to know about it.  (Gathering a row's kept elements in LDS -- in
-// the wave's staging area, free at this point -- to store them with one instruction per 64
-// was measured twice: the gather costs more than the sparse stores it replaces.)
-template <typename InT, int N>
-__device__ __forceinline__ void divert_kept_vector(uint8_t* base, const KeptVector<N>& kv, float (&x)[N])
+// One channel per element (fh_channels.hpp): the span's ROWS * 64 * 16 bytes are parked in the wave's
+// staging area (free until the codes are staged), the lanes walk the span's (sample, row) pairs,
+// copy each kept element from there to the raw store -- consecutive lanes, consecutive rows -- and
+// leave a quiet NaN in its place; then every lane takes its elements back.  (The alternatives
+// measured: every lane testing its own elements and storing the kept ones with one predicated
+// 2- or 4-byte store each; the same with the kept elements compacted through LDS first.)
+template <typename InT, int ROWS>
+__device__ __forceinline__ void divert_listed(const ChannelMap& cm, const ElemPos& wave_pos, const uint16_t* rows,
+                                              uint8_t* area, uint32_t lane, u32x4 (&w)[ROWS])
 {
+    typedef typename std::conditional<sizeof(InT) == 4, uint32_t, uint16_t>::type __attribute__((may_alias)) Elem;
+    constexpr uint32_t SPAN = ROWS * kWave * 16 / sizeof(InT);
+    constexpr Elem kQuietNaN = sizeof(InT) == 4 ? (Elem)0x7fc00000u : (Elem)0x7fc0u;
+    // which pairs are this lane's, while the span's loads are still on their way
+    const uint32_t pairs = span_pairs(cm, wave_pos, SPAN);
+    PairWalk walk = pair_walk(cm, wave_pos, lane);
+    uint32_t off[kPairsAhead];
+    first_pairs(cm, walk, rows, pairs, off);
+    stage_u32x4* in = reinterpret_cast<stage_u32x4*>(area);
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-        const uint32_t keep = kv.keep[j >> 1];
-        const uint32_t bits = __builtin_bit_cast(uint32_t, x[j]);
-        if (keep & ((j & 1) ? 0xffff0000u : 0x0000ffffu)) {
-            uint8_t* p = base + raw_offset<N>(kv, j);
-            if constexpr (sizeof(InT) == 4) *reinterpret_cast<uint32_t*>(p) = bits;
-            else *reinterpret_cast<uint16_t*>(p) = (uint16_t)(bits >> 16);        // the original bits
+    for (int r = 0; r < ROWS; ++r) in[r * kWave + lane] = w[r];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");    // LDS operations of one wave complete in order
+    Elem* elems = reinterpret_cast<Elem*>(area);
+    Elem* raw = static_cast<Elem*>(cm.raw) + (uint64_t)wave_pos.o * cm.raw_channels + lane;
+    Elem v[kPairsAhead];
+#pragma unroll
+    for (int k = 0; k < kPairsAhead; ++k) v[k] = off[k] < SPAN ? elems[off[k]] : (Elem)0;
+#pragma unroll
+    for (int k = 0; k < kPairsAhead; ++k) {
+        if (off[k] < SPAN) {
+            raw[k * kWave] = v[k];                            // the original bits
+            elems[off[k]] = kQuietNaN;
         }
-        const uint32_t nan = ((j & 1) ? keep : keep << 16) & 0x7fc00000u;
-        x[j] = __builtin_bit_cast(float, bits | nan);
     }
+    for (uint32_t i = kPairsAhead * kWave; i < pairs; i += kWave) {            // wave-uniform trip count
+        const uint32_t o = pair_offset(walk, rows);
+        pair_advance(cm, walk);
+        if (o < SPAN) {
+            raw[i] = elems[o];
+            elems[o] = kQuietNaN;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) w[r] = in[r * kWave + lane];
 }
 
 // ---- interior spans: the 4-row layout --------------------------------------------------
@@ -347,7 +379,8 @@ template <typename InT, int G, int B, bool STOCH, bool MIXED>
 __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wave_base, const InT* xw,
                                               uint8_t* pw, float* mw, uint32_t lane,
                                               uint8_t* stage_codes, float* stage_meta,
-                                              const ChannelMap* cm, const ElemPos& wave_pos)
+                                              const ChannelMap* cm, const ElemPos& wave_pos, const uint16_t* rows,
+                                              u32x4 (&w)[4])
 {
     using L = Layout<InT>;
     constexpr int ROWS = 4, EPL = L::EPL, ROW = L::ROW;
@@ -360,18 +393,14 @@ __device__ __forceinline__ void compress_span(const CompressItem& it, int64_t wa
     const bool b0 = lane & 1u, b1 = lane & 2u;
 
     float x[ROWS][EPL];
+    if (MIXED && rows != nullptr) {                           // wave-uniform: one channel per element; `w` holds the span
+        divert_listed<InT, ROWS>(*cm, wave_pos, rows, stage_codes, lane, w);
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) Loader<InT>::row(xw + r * ROW + lane * EPL, x[r]);
-
-    if constexpr (MIXED) {
-        if (one_channel_per_element<EPL>(*cm)) {              // wave-uniform
-            KeptVector<EPL> kv[ROWS];
-            kept_vectors<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, sizeof(InT) == 4 ? 2u : 1u, kv);
-            uint8_t* base = static_cast<uint8_t*>(cm->raw) + (uint64_t)wave_pos.o * cm->raw_channels * sizeof(InT);
+        for (int r = 0; r < ROWS; ++r) Loader<InT>::widen(w[r], x[r]);
+    } else {
 #pragma unroll
-            for (int r = 0; r < ROWS; ++r)
-                if (any_kept<EPL>(kv[r])) divert_kept_vector<InT, EPL>(base, kv[r], x[r]);
-        } else {
+        for (int r = 0; r < ROWS; ++r) Loader<InT>::row(xw + r * ROW + lane * EPL, x[r]);
+        if constexpr (MIXED) {
             KeptRun<EPL> run[ROWS];
             kept_runs<ROWS, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
 #pragma unroll
@@ -610,9 +639,12 @@ __device__ __forceinline__ void compress_edge(const CompressItem& it, int64_t wa
     }
 }
 
+// `listed` (MIXED only): LDS for the list of raw-store rows, built here -- by every thread of the workgroup, which
+// all call this with the same arguments -- when the tensor has one channel per element.
 template <typename InT, int G, int B, bool STOCH, bool MIXED = false>
 __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t tile, uint32_t* stage,
-                                              const ChannelMap* cm = nullptr)
+                                              const ChannelMap* cm = nullptr, uint16_t* listed = nullptr,
+                                              uint32_t stage_dwords = kStageDwords)
 {
     using L = Layout<InT>;
     const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -623,17 +655,34 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
     const int64_t wave_base = (int64_t)tile * L::TILE + (int64_t)wave * L::SPAN;
     const int64_t padded_elems = (int64_t)(it.packed_padded * 8u / (unsigned)B);
     const int64_t extent = numel > padded_elems ? numel : padded_elems;
+    const bool interior = wave_base + L::SPAN <= numel;
+    const InT* xw = static_cast<const InT*>(it.x) + wave_base;
+    const uint16_t* rows = nullptr;
+    u32x4 w[4] = {};
+    if constexpr (MIXED) {
+        if (rows_listed(*cm)) {
+            // the table entries first, then the span (so that waiting for the former does not wait for the latter),
+            // and the list is filed while the span is on its way
+            SlotWords words;
+            list_rows_request<kCBlock>(*cm, words);
+            if (interior) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) w[r] = stream_load(reinterpret_cast<const u32x4*>(xw + r * L::ROW + lane * L::EPL));
+            }
+            list_rows_file<kCBlock>(*cm, words, listed);
+            rows = listed;
+        }
+    }
     if (wave_base >= extent) return;
 
-    const InT* xw = static_cast<const InT*>(it.x) + wave_base;
     uint8_t* pw = it.packed + ((uint64_t)wave_base * B >> 3);
     float* mw = it.meta + 2 * (wave_base >> Log2<G>::v);
     ElemPos wave_pos = {0u, 0u, 0u};
     if constexpr (MIXED) wave_pos = locate_base(*cm, (uint32_t)wave_base);
-    if (wave_base + L::SPAN <= numel) {
-        uint8_t* stage_codes = reinterpret_cast<uint8_t*>(stage + wave * kStageDwords);
+    if (interior) {
+        uint8_t* stage_codes = reinterpret_cast<uint8_t*>(stage + wave * stage_dwords);
         float* stage_meta = reinterpret_cast<float*>(stage_codes + kStageCodeBytes);
-        compress_span<InT, G, B, STOCH, MIXED>(it, wave_base, xw, pw, mw, lane, stage_codes, stage_meta, cm, wave_pos);
+        compress_span<InT, G, B, STOCH, MIXED>(it, wave_base, xw, pw, mw, lane, stage_codes, stage_meta, cm, wave_pos, rows, w);
     } else {
         compress_edge<InT, G, B, STOCH, MIXED>(it, wave_base, extent, xw, pw, mw, lane, cm, wave_pos);
     }
@@ -662,11 +711,17 @@ __global__ __launch_bounds__(kCBlock) void compress_kernel(const CompressBatch a
     }
 }
 
-// Tensors whose kept channels go to the raw store.
+// Tensors whose kept channels go to the raw store.  A wave's staging area also parks the span's
+// input while its kept elements are taken out (4 KiB: 2048 bf16 or 1024 fp32 elements).
+constexpr int kMixedStageDwords = 1024;
+static_assert(kMixedStageDwords >= kStageDwords && kMixedStageDwords * 4 == Layout<float>::SPAN * 4 &&
+              kMixedStageDwords * 4 == Layout<uint16_t>::SPAN * 2, "a span of either dtype is 4 KiB");
+
 template <typename InT, int G>
 __global__ __launch_bounds__(kCBlock) void compress_mixed_kernel(const Batch<MixedCompressJob> batch)
 {
-    __shared__ __attribute__((aligned(16))) uint32_t stage[kWaves * kStageDwords];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[kWaves * kMixedStageDwords];
+    __shared__ uint16_t listed[kListedRows];
     uint32_t tile;
     const MixedCompressJob& job = batch.item[batch_item(batch, blockIdx.x, tile)];
     const CompressItem& it = job.it;
@@ -684,12 +739,12 @@ __global__ __launch_bounds__(kCBlock) void compress_mixed_kernel(const Batch<Mix
         return;
     }
     switch (it.bits * 2 + it.stochastic) {
-        case 4:  compress_tile<InT, G, 2, false, true>(it, tile, stage, &cm); break;
-        case 5:  compress_tile<InT, G, 2, true , true>(it, tile, stage, &cm); break;
-        case 8:  compress_tile<InT, G, 4, false, true>(it, tile, stage, &cm); break;
-        case 9:  compress_tile<InT, G, 4, true , true>(it, tile, stage, &cm); break;
-        case 16: compress_tile<InT, G, 8, false, true>(it, tile, stage, &cm); break;
-        case 17: compress_tile<InT, G, 8, true , true>(it, tile, stage, &cm); break;
+        case 4:  compress_tile<InT, G, 2, false, true>(it, tile, stage, &cm, listed, kMixedStageDwords); break;
+        case 5:  compress_tile<InT, G, 2, true , true>(it, tile, stage, &cm, listed, kMixedStageDwords); break;
+        case 8:  compress_tile<InT, G, 4, false, true>(it, tile, stage, &cm, listed, kMixedStageDwords); break;
+        case 9:  compress_tile<InT, G, 4, true , true>(it, tile, stage, &cm, listed, kMixedStageDwords); break;
+        case 16: compress_tile<InT, G, 8, false, true>(it, tile, stage, &cm, listed, kMixedStageDwords); break;
+        case 17: compress_tile<InT, G, 8, true , true>(it, tile, stage, &cm, listed, kMixedStageDwords); break;
         default: break;
     }
 }

@@ -13,6 +13,8 @@
 //
 // The MIXED variants take the elements of kept (salient) channels from the raw store
 // instead.
+#include <type_traits>
+
 #include "fh_channels.hpp"
 #include "fh_device.hpp"
 #include "fh_kernels.hpp"
@@ -103,39 +105,30 @@ __device__ __forceinline__ void fetch_kept(const ChannelMap& cm, int raw_dtype, 
     }
 }
 
-// The same for one channel per element (fh_channels.hpp): every lane loads an entry per element
-// -- normal elements a harmless one -- and the kept ones are merged in by their masks.
-// `base`: the raw-store row of the wave's first sample (wave-uniform).
-template <int N, typename RawT>
-__device__ __forceinline__ void merge_kept(const uint8_t* base, const KeptVector<N>& kv, float (&v)[N])
+// One channel per element (fh_channels.hpp): the wave's restored span is parked in LDS in the output's
+// dtype, the lanes walk the span's (sample, row) pairs and overwrite the kept elements with the
+// raw store's values -- consecutive lanes, consecutive rows --, then every lane takes its 16 bytes
+// per row back and stores them.  The first pairs of a lane are loaded before the codes are
+// expanded, so that their latency overlaps that of the codes.  (The alternative measured: every lane
+// loading a raw entry for each of its elements and merging by masks.)
+typedef uint16_t __attribute__((may_alias)) park_u16;
+typedef uint32_t __attribute__((may_alias)) park_u32;
+typedef u32x4 __attribute__((may_alias)) park_u32x4;
+
+template <typename OutT>
+__device__ __forceinline__ OutT raw_as(const void* raw, uint64_t i, int raw_dtype)
 {
-    uint32_t bits[N];
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-        const RawT e = *reinterpret_cast<const RawT*>(base + raw_offset<N>(kv, j));
-        bits[j] = sizeof(RawT) == 4 ? (uint32_t)e : (uint32_t)e << 16;
-    }
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-        const int32_t pair = (int32_t)kv.keep[j >> 1];
-        const uint32_t m = (uint32_t)((j & 1) ? pair >> 16 : (pair << 16) >> 16);     // all ones iff kept
-        v[j] = __builtin_bit_cast(float, (bits[j] & m) | (__builtin_bit_cast(uint32_t, v[j]) & ~m));
+    if constexpr (sizeof(OutT) == 4) {
+        return raw_dtype == 0 ? static_cast<const uint32_t*>(raw)[i] : (uint32_t) static_cast<const uint16_t*>(raw)[i] << 16;
+    } else {
+        return raw_dtype == 0 ? (OutT)bf16_bits(static_cast<const float*>(raw)[i]) : static_cast<const uint16_t*>(raw)[i];
     }
 }
-// bf16 raw store into a bf16 tensor: the kept halves of each output word are the raw bits
-__device__ __forceinline__ u32x4 merge_kept_bf16(const uint8_t* base, const KeptVector<8>& kv, u32x4 o)
-{
-    uint32_t e[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) e[j] = *reinterpret_cast<const uint16_t*>(base + raw_offset<8>(kv, j));
-    uint32_t out[4] = {o.x, o.y, o.z, o.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) out[k] = ((e[2 * k] | (e[2 * k + 1] << 16)) & kv.keep[k]) | (out[k] & ~kv.keep[k]);
-    return u32x4{out[0], out[1], out[2], out[3]};
-}
+
 template <typename OutT, int G, int B, bool MIXED = false>
 __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32_t tile,
-                                                const ChannelMap* cm = nullptr, int raw_dtype = 0)
+                                                const ChannelMap* cm = nullptr, int raw_dtype = 0,
+                                                uint16_t* listed = nullptr, uint8_t* park = nullptr)
 {
     constexpr int EPL = OutTraits<OutT>::EPL;
     constexpr int kRowsPerWave = OutTraits<OutT>::ROWS;
@@ -146,44 +139,77 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t numel = it.numel;
     const int64_t wave_base = (int64_t)tile * TILE + (int64_t)wave * WAVE_SPAN;
-    if (wave_base >= numel) return;
-    ElemPos wave_pos = {0u, 0u, 0u};
-    if constexpr (MIXED) wave_pos = locate_base(*cm, (uint32_t)wave_base);
-
-    if (wave_base + WAVE_SPAN <= numel) {
-        // ---- interior: all loads first, then one 128-bit store per lane and row ----
-        uint32_t c0[kRowsPerWave], c1[kRowsPerWave];
-        f32x2 m[kRowsPerWave];
+    const bool interior = wave_base + WAVE_SPAN <= numel;
+    uint32_t c0[kRowsPerWave] = {}, c1[kRowsPerWave] = {};
+    f32x2 m[kRowsPerWave] = {};
+    const auto load_span = [&]() {                            // interior spans: all loads first
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r) {
             const int64_t i0 = wave_base + r * ROW + lane * EPL;
             load_codes<EPL, B>(it.packed, i0, c0[r], c1[r]);
             m[r] = code_load(reinterpret_cast<const f32x2*>(it.meta + 2 * (i0 >> Log2<G>::v)));
         }
+    };
+    const uint16_t* rows = nullptr;
+    if constexpr (MIXED) {
+        if (rows_listed(*cm)) {                               // the same for every thread of the workgroup, which all get here
+            // the table entries first, then the span's codes (so that waiting for the former does not wait for the
+            // latter), and the list is filed while the codes are on their way
+            SlotWords words;
+            list_rows_request<kDBlock>(*cm, words);
+            if (interior) load_span();
+            list_rows_file<kDBlock>(*cm, words, listed);
+            rows = listed;
+        }
+    }
+    if (wave_base >= numel) return;
+    ElemPos wave_pos = {0u, 0u, 0u};
+    if constexpr (MIXED) wave_pos = locate_base(*cm, (uint32_t)wave_base);
+
+    if (interior) {
+        // ---- interior: all loads first, then one 128-bit store per lane and row ----
+        if (!(MIXED && rows != nullptr)) load_span();
         if constexpr (MIXED) {
-            if (one_channel_per_element<EPL>(*cm)) {          // wave-uniform
-                KeptVector<EPL> kv[kRowsPerWave];
-                kept_vectors<kRowsPerWave, EPL>(*cm, wave_pos, lane * EPL, ROW, raw_dtype == 0 ? 2u : 1u, kv);
-                const uint8_t* base = static_cast<const uint8_t*>(cm->raw) +
-                                      (uint64_t)wave_pos.o * cm->raw_channels * (raw_dtype == 0 ? 4u : 2u);
+            if (rows != nullptr) {                            // wave-uniform: one channel per element
+                using Bits = typename std::conditional<sizeof(OutT) == 4, uint32_t, uint16_t>::type;
+                typedef Bits __attribute__((may_alias)) Parked;
+                const uint64_t raw0 = (uint64_t)wave_pos.o * cm->raw_channels;
+                const uint32_t pairs = span_pairs(*cm, wave_pos, WAVE_SPAN);
+                PairWalk walk = pair_walk(*cm, wave_pos, lane);
+                uint32_t off[kPairsAhead];
+                Bits val[kPairsAhead];
+                first_pairs(*cm, walk, rows, pairs, off);
+#pragma unroll
+                for (int k = 0; k < kPairsAhead; ++k)
+                    val[k] = off[k] < (uint32_t)WAVE_SPAN ? raw_as<Bits>(cm->raw, raw0 + k * kWave + lane, raw_dtype) : (Bits)0;
+                park_u32x4* mine = reinterpret_cast<park_u32x4*>(park + wave * (WAVE_SPAN * sizeof(OutT)));
+#pragma unroll
+                for (int r = 0; r < kRowsPerWave; ++r) {
+                    float v[EPL];
+                    restore<EPL, B>(c0[r], c1[r], m[r], v);
+                    if constexpr (EPL == 4) {
+                        mine[r * kWave + lane] = u32x4{__builtin_bit_cast(uint32_t, v[0]), __builtin_bit_cast(uint32_t, v[1]),
+                                                       __builtin_bit_cast(uint32_t, v[2]), __builtin_bit_cast(uint32_t, v[3])};
+                    } else {
+                        mine[r * kWave + lane] = pack_bf16x8(v);
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // LDS operations of one wave complete in order
+                Parked* elems = reinterpret_cast<Parked*>(mine);
+#pragma unroll
+                for (int k = 0; k < kPairsAhead; ++k)
+                    if (off[k] < (uint32_t)WAVE_SPAN) elems[off[k]] = val[k];
+                for (uint32_t i = kPairsAhead * kWave; i < pairs; i += kWave) {            // wave-uniform trip count
+                    const uint32_t o = pair_offset(walk, rows);
+                    pair_advance(*cm, walk);
+                    if (o < (uint32_t)WAVE_SPAN) elems[o] = raw_as<Bits>(cm->raw, raw0 + i + lane, raw_dtype);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
                 for (int r = 0; r < kRowsPerWave; ++r) {
                     const int64_t i0 = wave_base + r * ROW + lane * EPL;
-                    float v[EPL];
-                    restore<EPL, B>(c0[r], c1[r], m[r], v);
-                    const bool any = any_kept<EPL>(kv[r]);
-                    if constexpr (EPL == 4) {
-                        if (any) {
-                            if (raw_dtype == 0) merge_kept<EPL, uint32_t>(base, kv[r], v);
-                            else merge_kept<EPL, uint16_t>(base, kv[r], v);
-                        }
-                        stream_store(reinterpret_cast<f32x4*>(static_cast<float*>(it.out) + i0), f32x4{v[0], v[1], v[2], v[3]});
-                    } else {
-                        if (any && raw_dtype == 0) merge_kept<EPL, uint32_t>(base, kv[r], v);
-                        u32x4 o = pack_bf16x8(v);
-                        if (any && raw_dtype != 0) o = merge_kept_bf16(base, kv[r], o);
-                        stream_store(reinterpret_cast<u32x4*>(static_cast<uint16_t*>(it.out) + i0), o);
-                    }
+                    const u32x4 o = mine[r * kWave + lane];
+                    stream_store(reinterpret_cast<u32x4*>(static_cast<OutT*>(it.out) + i0), o);
                 }
                 return;
             }
@@ -273,6 +299,8 @@ __global__ __launch_bounds__(kDBlock) void decompress_mixed_kernel(const Batch<M
     const DecompressItem& it = job.it;
     const ChannelMap& cm = job.cm;
     const int raw_dtype = job.raw_dtype;
+    __shared__ __attribute__((aligned(16))) uint8_t park[tile_elems<OutT>() * sizeof(OutT)];
+    __shared__ uint16_t listed[kListedRows];
     if (nothing_kept(cm)) {                                   // no channel of this tensor was kept: the plain code
         switch (it.bits) {
             case 2: decompress_tile<OutT, G, 2>(it, tile); break;
@@ -283,9 +311,9 @@ __global__ __launch_bounds__(kDBlock) void decompress_mixed_kernel(const Batch<M
         return;
     }
     switch (it.bits) {
-        case 2: decompress_tile<OutT, G, 2, true>(it, tile, &cm, raw_dtype); break;
-        case 4: decompress_tile<OutT, G, 4, true>(it, tile, &cm, raw_dtype); break;
-        case 8: decompress_tile<OutT, G, 8, true>(it, tile, &cm, raw_dtype); break;
+        case 2: decompress_tile<OutT, G, 2, true>(it, tile, &cm, raw_dtype, listed, park); break;
+        case 4: decompress_tile<OutT, G, 4, true>(it, tile, &cm, raw_dtype, listed, park); break;
+        case 8: decompress_tile<OutT, G, 8, true>(it, tile, &cm, raw_dtype, listed, park); break;
         default: break;
     }
 }

@@ -101,6 +101,7 @@ ChannelMap make_map(const void* slots, void* raw, int64_t channels, int64_t inne
     cm.channels_exact = make_exact_div((uint32_t)channels);
     cm.inner = make_small_div((uint32_t)inner);
     cm.channels = make_small_div((uint32_t)channels);
+    cm.raw_div = make_small_div(raw_channels > 0 ? (uint32_t)raw_channels : 1u);
     return cm;
 }
 

@@ -87,7 +87,7 @@ def _roundtrip(api, x, outer, C, inner, mask, cap, G, B, rounding, dtype="f32", 
     return slots, used
 
 
-# (outer, channels, inner): one channel per element with and without the vector path, feature
+# (outer, channels, inner): one channel per element (even, odd and tiny channel counts), feature
 # maps whose rows are multiples of a lane's run, odd rows, rows shorter than a lane's run,
 # single channel, sizes that end inside a tile
 SHAPES = [(64, 768, 1), (33, 96, 1), (50, 100, 1), (7, 12, 1), (8, 32, 56 * 56), (4, 24, 49), (3, 16, 196),
@@ -103,6 +103,17 @@ def test_shapes_and_layouts(api, shape, dtype):
     mask[0] = 1
     cap = max(1, int(mask.sum()))
     _roundtrip(api, x, outer, C, inner, mask, cap, 64, 4, "stochastic", dtype=dtype, name="shape")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_one_channel_per_element_many_channels(api, dtype):
+    """inner = 1 with channel counts beyond what a workgroup requests up front (4096), an odd count, the largest
+    raw store whose rows are listed (2048) and one row more (which takes the per-element path)."""
+    for outer, C, cap, share in ((5, 16384, 64, 0.01), (3, 5001, 2048, 0.5), (4, 4100, 2049, 0.6), (40, 8190, 1, 0.02)):
+        x, _ = W.outlier_channel_tensor(outer, C, 1, seed=C, salient_fraction=0.1, dtype=dtype)
+        mask = _mask(C, share, C)
+        mask[C - 1] = 1
+        _roundtrip(api, x, outer, C, 1, mask, cap, 64, 4, "nearest", dtype=dtype, name="many-channels")
 
 
 @pytest.mark.parametrize("G", [64, 128, 256])
