@@ -10,7 +10,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "fh_device.hpp"
+#include "fh_types.hpp"
 
 namespace fh {
 

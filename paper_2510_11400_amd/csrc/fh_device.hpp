@@ -5,15 +5,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fh_types.hpp"
+
 namespace fh {
 
-constexpr int kWave = 64;
-
-// ---- 128-bit vectors -------------------------------------------------------------
-typedef float    f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef float    f32x2 __attribute__((ext_vector_type(2)));
 
 // ---- streaming memory access --------------------------------------------------------
 // The activation and the restored tensor are each touched once per call and are far larger
@@ -174,18 +169,6 @@ __device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
         k1 += W1;
     }
     return u32x4{c0, c1, c2, c3};
-}
-
-// ---- bf16 ------------------------------------------------------------------------
-__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __builtin_bit_cast(float, pair << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __builtin_bit_cast(float, pair & 0xFFFF0000u); }
-
-// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN kept quiet).
-__device__ __forceinline__ uint32_t bf16_bits(float f)
-{
-    const uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
 }  // namespace fh

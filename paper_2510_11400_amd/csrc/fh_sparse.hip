@@ -99,7 +99,10 @@ struct Job {
 // what a tile with this info byte adds to the streams
 __device__ __forceinline__ Sums tile_sums(uint32_t info, const TilePos& t, bool predictive)
 {
-    const uint32_t count = info & 0x7fu;                      // non-zeros | elements | outliers
+    // non-zeros | elements | outliers: never more than the tile has (an encoder cannot write more; a foreign byte
+    // that claims more must not make a workgroup's slice outgrow its staging area)
+    const uint32_t claimed = info & 0x7fu, room = t.rows * t.cols;
+    const uint32_t count = claimed < room ? claimed : room;
     if (info & 0x80u) return Sums{count, predictive ? t.rows * t.cols : 0u, 0u};
     return Sums{count, t.rows + 1u + count, 1u};
 }
@@ -661,7 +664,7 @@ __global__ __launch_bounds__(Group<N>::kTiles) void sparse_read_kernel(const Bat
 
     const StagedBits* v = reinterpret_cast<const StagedBits*>(stage_v + phase_of(value_slice)) + before.values;
     const uint8_t* idx = stage_i + phase_of(index_slice) + before.index_bytes;
-    const uint32_t count = byte & 0x7fu;
+    const uint32_t count = mine.values;                       // the byte's count, at most the tile's elements
     const uint32_t last = count > 0u ? count - 1u : 0u;       // reads of values are clamped to the tile's piece
     const bool in_bounds = before.values + mine.values <= have_v && before.index_bytes + mine.index_bytes <= have_i;
     Bits* out = static_cast<Bits*>(const_cast<void*>(s.x)) + t.origin;
