@@ -4,8 +4,8 @@
 // canonical codes, layout) is the one in include/fedhybrid.h.
 //
 // A variable-length code is sequential per symbol, so the stream is cut into chunks of 256
-// symbols that start on a 32-bit word; a thread owns a chunk.  Encoding is stream compaction
-// again:
+// symbols that start on a 32-bit word; the decoder gives a chunk to a thread, the encoder to
+// sixteen lanes.  Encoding is stream compaction again:
 //   histogram   LDS counters, one copy per bank and the copies interleaved, so that no two lanes
 //               of a half-wave meet in a bank whatever the bytes are; added to the global
 //               histogram at the end;
@@ -13,12 +13,14 @@
 //               lane runs the two-queue construction over the ranked leaves (at most 255
 //               merges) and walks the tree for the depths; counts are halved and the
 //               construction repeated while a code would exceed 24 bits; canonical codes;
-//   count       a thread adds up the code lengths of its chunk: its length in words;
+//   count       a wave reads four chunks at a time with one 16-byte load per lane and adds the
+//               code lengths up over each chunk's sixteen lanes: the chunk's length in words;
 //   scan        the sums of groups of 256 chunks (a workgroup of the count pass) are scanned by
 //               one workgroup;
-//   write       a thread turns its chunk's word count into its offset (group base + a scan
-//               over the workgroup) and produces its words; the workgroup's words, a contiguous
-//               slice, are collected in LDS and stored with consecutive lanes on consecutive words.
+//   write       word counts become offsets (group base + a scan over the workgroup); a wave
+//               then codes four chunks at a time, every lane placing the bits of its sixteen
+//               symbols in an LDS area by OR, and stores the four chunks' words -- one
+//               contiguous piece -- with consecutive lanes on consecutive words.
 // Decoding needs no pass but one: the offsets are part of the stream.  A workgroup rebuilds the
 // canonical tables from the 256 lengths (a 12-bit lookup table for the short codes, first-code /
 // count comparisons for the longer ones), stages the payload slice of 768 chunks in LDS (150 of
@@ -41,7 +43,6 @@ constexpr int kHistCopies = 32;                     // one per LDS bank
 constexpr int kHistBlocksMax = 640;                // histogram workgroups per stream: 2.5 per compute unit
 constexpr int kFastBits = 12;
 constexpr int kBurst = 8;                          // decode: 16-byte output vectors held back and stored together
-constexpr int kWriteStageWords = 12288;            // encode: LDS for a workgroup's payload slice (256 chunks of 48 words)
 // decode: chunks per workgroup.  The payload slice in LDS is what limits the chunks in flight on a compute unit,
 // and the decode waits on dependent instructions, not on a unit: one workgroup with the whole LDS holds 768
 // chunks (twelve waves) where workgroups of 256 with their own tables held 512.
@@ -316,6 +317,40 @@ __device__ __forceinline__ uint32_t workgroup_exclusive_scan(uint32_t mine, uint
 }
 
 // ---- count: words per chunk, sums per group -------------------------------------------------------
+// Sixteen lanes share a chunk: a wave reads four consecutive chunks, 1 KiB, with one 16-byte load per lane --
+// whole cache lines, each fetched once -- and does so for its 64 chunks in sixteen rounds.  (A thread per chunk,
+// walking its 256 bytes alone, asks for 16 bytes of every line its wave touches in a round and finds the rest
+// gone from the cache when it comes back: measured, that read 1.2 times the input here and 2.9 times in the
+// write pass.)
+struct PieceOfChunk {                              // what a lane reads in one round
+    uint32_t chunk;                                // the chunk (of the stream), which may not exist
+    uint32_t have;                                 // symbols of its 16 that exist: 0 .. 16
+    uint64_t first;                                // index of the first of them
+};
+__device__ __forceinline__ PieceOfChunk piece_of(const Layout& lay, uint32_t group, uint32_t wave, uint32_t round, uint32_t lane)
+{
+    PieceOfChunk p;
+    p.chunk = group * kThreads + wave * 64u + round * 4u + (lane >> 4);
+    p.first = (uint64_t)p.chunk * kChunk + (lane & 15u) * 16u;
+    p.have = p.first >= lay.n ? 0u : lay.n - p.first < 16u ? (uint32_t)(lay.n - p.first) : 16u;
+    return p;
+}
+// does every lane of the wave have all its 16 symbols in this round?  (wave-uniform, from scalar values)
+__device__ __forceinline__ bool round_is_whole(const Layout& lay, uint32_t group, uint32_t wave, uint32_t round)
+{
+    const uint64_t end = ((uint64_t)group * kThreads + wave * 64u + round * 4u + 4u) * kChunk;
+    return end <= lay.n;
+}
+// sum over the 16 lanes that share a chunk, in the last of them (row shifts: a row of the wave is those 16 lanes)
+__device__ __forceinline__ uint32_t sum_to_lane_15_of_row(uint32_t v)
+{
+    v = dpp_add<0x111, 0xf>(v);
+    v = dpp_add<0x112, 0xf>(v);
+    v = dpp_add<0x114, 0xf>(v);
+    v = dpp_add<0x118, 0xf>(v);
+    return v;                                                 // inclusive prefix inside the row
+}
+
 __global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Batch<Layout> batch)
 {
     uint32_t group;
@@ -325,42 +360,46 @@ __global__ __launch_bounds__(kThreads) void huffman_count_kernel(const Batch<Lay
     __shared__ uint32_t lds[4];
     len[threadIdx.x] = (uint8_t)(lay.table[threadIdx.x] & 0xffu);
     __syncthreads();
-    const uint32_t chunk = group * kThreads + threadIdx.x;
-    uint32_t words = 0;
-    if (chunk < lay.chunks) {
-        const uint64_t first = (uint64_t)chunk * kChunk;
-        const uint32_t valid = lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
-        uint32_t bits = 0;
-        if (valid == (uint32_t)kChunk) {                      // all sixteen loads in flight together
-            u32x4 v[kChunk / 16];
+    const uint32_t lane = threadIdx.x & 63u, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t closed = 0;                                      // words of the chunks this lane closed (lanes 15, 31, 47, 63)
+    constexpr int kRoundsInFlight = 8;
+    for (uint32_t round0 = 0; round0 < 16u; round0 += kRoundsInFlight) {
+        uint32_t word[kRoundsInFlight][4];
 #pragma unroll
-            for (int i = 0; i < kChunk / 16; ++i) v[i] = reinterpret_cast<const u32x4*>(lay.in + first)[i];
-#pragma unroll
-            for (int i = 0; i < kChunk / 16; ++i) {
-                const uint32_t word[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) bits += len[(word[k] >> (8 * b)) & 0xffu];
-            }
-        } else {
-            for (uint32_t i = 0; i < valid; i += 16) {        // the last chunk: at most 16 rounds
-                uint32_t word[4];
-                load_symbols(lay.in, first + i, valid - i, word);
-                const uint32_t here = valid - i < 16u ? valid - i : 16u;
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-#pragma unroll
-                    for (int b = 0; b < 4; ++b)
-                        if ((uint32_t)(4 * k + b) < here) bits += len[(word[k] >> (8 * b)) & 0xffu];
+        for (int k = 0; k < kRoundsInFlight; ++k) {
+            const PieceOfChunk p = piece_of(lay, group, wave, round0 + k, lane);
+            if (round_is_whole(lay, group, wave, round0 + k)) {
+                const u32x4 w = *reinterpret_cast<const u32x4*>(lay.in + p.first);
+                word[k][0] = w.x; word[k][1] = w.y; word[k][2] = w.z; word[k][3] = w.w;
+            } else {
+                word[k][0] = word[k][1] = word[k][2] = word[k][3] = 0u;
+                if (p.have) load_symbols(lay.in, p.first, p.have, word[k]);
             }
         }
-        words = (bits + 31u) >> 5;
-        lay.offsets[chunk] = words;                           // becomes the chunk's offset in the write pass
+#pragma unroll
+        for (int k = 0; k < kRoundsInFlight; ++k) {
+            const PieceOfChunk p = piece_of(lay, group, wave, round0 + k, lane);
+            uint32_t bits = 0;
+            if (round_is_whole(lay, group, wave, round0 + k)) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) bits += len[(word[k][j >> 2] >> (8 * (j & 3))) & 0xffu];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if ((uint32_t)j < p.have) bits += len[(word[k][j >> 2] >> (8 * (j & 3))) & 0xffu];
+            }
+            const uint32_t of_chunk = sum_to_lane_15_of_row(bits);
+            if ((lane & 15u) == 15u && p.chunk < lay.chunks) {
+                const uint32_t words = (of_chunk + 31u) >> 5;
+                lay.offsets[p.chunk] = words;                 // becomes the chunk's offset in the write pass
+                closed += words;
+            }
+        }
     }
-    uint32_t total;
-    workgroup_exclusive_scan(words, lds, &total);
-    if (threadIdx.x == 0) lay.group_sums[group] = total;
+    const uint32_t of_wave = wave_inclusive_scan(closed);
+    if (lane == 63u) lds[wave] = of_wave;
+    __syncthreads();
+    if (threadIdx.x == 0) lay.group_sums[group] = lds[0] + lds[1] + lds[2] + lds[3];
 }
 
 // ---- scan of the group sums (in place, exclusive); the stream's size --------------------------------
@@ -384,45 +423,14 @@ __global__ __launch_bounds__(kThreads) void huffman_scan_kernel(const Batch<Layo
 }
 
 // ---- write: offsets and payload -------------------------------------------------------------------
-// The code words of one chunk (symbols in[first .. first + valid)), MSB first, to out[0 .. words): `out` is LDS or
-// global memory, and the function is compiled once for each so that the LDS case uses LDS stores.
-template <typename Out>
-__device__ __forceinline__ void encode_chunk(const uint8_t* in, uint64_t first, uint32_t valid, const uint32_t* table,
-                                             uint32_t words, Out out)
-{
-    uint64_t acc = 0;                                         // the low `filled` bits are pending, oldest on top
-    uint32_t filled = 0, written = 0;
-    const auto put = [&](uint32_t e) {                        // e = code << 8 | length
-        const uint32_t l = e & 0xffu;
-        acc = (acc << l) | (e >> 8);
-        filled += l;
-        if (filled >= 32u) {                                  // filled < 32 + 24 before this
-            filled -= 32u;
-            if (written < words) out[written] = (uint32_t)(acc >> filled);
-            ++written;
-        }
-    };
-    uint32_t word[4], ahead[4];
-    if (valid) load_symbols(in, first, valid, ahead);
-    uint32_t i = 0;
-    for (; i + 16 <= valid; i += 16) {                        // whole vectors: sixteen table reads, then the serial part
-#pragma unroll
-        for (int k = 0; k < 4; ++k) word[k] = ahead[k];
-        // in flight while this vector is coded (four ahead, and all sixteen at once, were measured no faster)
-        if (i + 16 < valid) load_symbols(in, first + i + 16, valid - i - 16, ahead);
-        uint32_t e[16];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) e[k] = table[(word[k >> 2] >> (8 * (k & 3))) & 0xffu];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) put(e[k]);
-    }
-    if (i < valid) {                                          // the stream's last chunk may end inside a vector
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-            if (i + k < valid) put(table[(ahead[k >> 2] >> (8 * (k & 3))) & 0xffu]);
-    }
-    if (filled && written < words) out[written] = (uint32_t)(acc << (32u - filled));   // zero-padded to a whole word
-}
+// The same sharing as in the count pass: a wave codes four consecutive chunks per round, sixteen lanes to a chunk,
+// each lane its 16 symbols.  A lane looks its 16 codes up, the lengths are prefix-summed over the chunk's lanes,
+// and the lane then puts its bits where they belong in the wave's staging area in LDS -- whole words as they fill
+// up, with an OR, since the first and the last word of a lane's run are shared with its neighbours.  The four
+// chunks are one contiguous piece of the payload (each starts on a word); the wave copies it out with consecutive
+// lanes on consecutive words and leaves the area cleared for the next round.  A chunk is at most 192 words
+// (24 bits per symbol), so the area fits whatever the stream holds.
+constexpr int kRoundWordsMax = 4 * kChunkWordsMax;          // 768 words per wave
 
 __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Layout> batch)
 {
@@ -431,28 +439,68 @@ __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Lay
     if (group >= lay.groups) return;                          // workgroup-uniform: past the real extent
     __shared__ uint32_t table[256];
     __shared__ uint32_t lds[4];
+    __shared__ uint32_t chunk_at[kThreads + 4];               // word offset of every chunk inside the group's slice; [256..]: the total
+    __shared__ uint32_t area[kThreads / 64][kRoundWordsMax + 4];
     table[threadIdx.x] = lay.table[threadIdx.x];
-    const uint32_t chunk = group * kThreads + threadIdx.x;
-    const bool live = chunk < lay.chunks;
-    const uint32_t words = live ? lay.offsets[chunk] : 0u;
-    uint32_t total;
-    const uint32_t before = workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
-    const uint32_t base = lay.group_sums[group];
-    if (live) lay.offsets[chunk] = base + before;
-    const uint64_t first = (uint64_t)chunk * kChunk;
-    const uint32_t valid = !live ? 0u : lay.n - first < (uint64_t)kChunk ? (uint32_t)(lay.n - first) : (uint32_t)kChunk;
-    // The workgroup's chunks are one contiguous slice of the payload. It is put together in LDS and copied out
-    // with consecutive lanes on consecutive words; word by word from each thread the stores would be 4 bytes
-    // every ~100 bytes. A slice too long for the LDS (more than 6 bits per symbol on average) goes out directly.
-    __shared__ uint32_t stage[kWriteStageWords];
-    if (total > (uint32_t)kWriteStageWords) {                 // the same decision in every thread
-        encode_chunk(lay.in, first, valid, table, words, lay.payload + base + before);
-        return;
+    {
+        const uint32_t chunk = group * kThreads + threadIdx.x;
+        const bool live = chunk < lay.chunks;
+        const uint32_t words = live ? lay.offsets[chunk] : 0u;
+        uint32_t total;
+        const uint32_t before = workgroup_exclusive_scan(words, lds, &total);   // also the barrier for `table`
+        if (live) lay.offsets[chunk] = lay.group_sums[group] + before;
+        chunk_at[threadIdx.x] = before;
+        if (threadIdx.x < 4u) chunk_at[kThreads + threadIdx.x] = total;
     }
-    encode_chunk(lay.in, first, valid, table, words, &stage[before]);
+    const uint32_t lane = threadIdx.x & 63u, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t* mine = area[wave];
+    for (uint32_t w = lane; w < (uint32_t)kRoundWordsMax + 4u; w += 64u) mine[w] = 0u;
     __syncthreads();
-    uint32_t* slice = lay.payload + base;
-    for (uint32_t w = threadIdx.x; w < total; w += kThreads) slice[w] = stage[w];
+    uint32_t* slice = lay.payload + lay.group_sums[group];
+    for (uint32_t round = 0; round < 16u; ++round) {
+        const PieceOfChunk p = piece_of(lay, group, wave, round, lane);
+        const uint32_t chunk0 = wave * 64u + round * 4u;      // of the group: the first of this round's four
+        const uint32_t run_at = chunk_at[chunk0], run = chunk_at[chunk0 + 4u] - run_at;   // wave-uniform
+        if (run == 0u) break;                                 // nothing from here on (the stream has ended)
+        // the lane's codes
+        uint32_t word[4] = {0u, 0u, 0u, 0u};
+        if (round_is_whole(lay, group, wave, round)) {
+            const u32x4 w = *reinterpret_cast<const u32x4*>(lay.in + p.first);
+            word[0] = w.x; word[1] = w.y; word[2] = w.z; word[3] = w.w;
+        } else if (p.have) {
+            load_symbols(lay.in, p.first, p.have, word);
+        }
+        uint32_t e[16];
+        uint32_t bits = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            e[j] = (uint32_t)j < p.have ? table[(word[j >> 2] >> (8 * (j & 3))) & 0xffu] : 0u;   // code << 8 | length; nothing: length 0
+            bits += e[j] & 0xffu;
+        }
+        // where the lane's bits start: its chunk's word offset inside the round, then the lanes before it in the chunk
+        const uint32_t start = ((chunk_at[chunk0 + (lane >> 4)] - run_at) << 5) + (sum_to_lane_15_of_row(bits) - bits);
+        uint32_t at = start >> 5;                             // the word being filled
+        uint32_t filled = start & 31u;                        // bits of it that precede this lane's (left as zeros here)
+        uint64_t acc = 0;                                     // the low `filled` bits are pending, oldest on top
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t l = e[j] & 0xffu;
+            acc = (acc << l) | (e[j] >> 8);
+            filled += l;
+            if (filled >= 32u) {                              // filled < 32 + 24 before this
+                filled -= 32u;
+                atomicOr(&mine[at], (uint32_t)(acc >> filled));
+                ++at;
+            }
+        }
+        if (filled) atomicOr(&mine[at], (uint32_t)(acc << (32u - filled)));      // the rest, zero-padded to the word's end
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");     // LDS operations of one wave complete in order
+        for (uint32_t w = lane; w < run; w += 64u) {
+            slice[run_at + w] = mine[w];
+            mine[w] = 0u;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
 }
 
 // One chunk: `valid` symbols from the words next_word(0), next_word(1), ... to dst (16-byte aligned).

@@ -5,6 +5,7 @@
 //
 // case file: uint32 count, then per case
 //   'H' : uint64 n, stream_bytes, out_cap; stream bytes
+//   'E' : uint64 n; the bytes to encode (result: the stream's bytes in use, then the two totals)
 //   'S' : int32 dtype, window; int64 maps, h, w; float eps; uint64 info_bytes, values_bytes, indices_bytes; the three arrays
 // result file: per case int32 status, uint64 out bytes, the output.
 #include <cstdint>
@@ -63,6 +64,21 @@ int main(int argc, char** argv)
             put_result(out, (int32_t)st, dst, st == FH_OK ? out_cap : 0);
             std::free(stream);
             std::free(dst);
+        } else if (kind == 'E') {
+            const uint64_t n = take<uint64_t>(in);
+            void* bytes = take_bytes(in, n);
+            const size_t cap = fh_huffman_stream_bytes(n), ws_bytes = fh_huffman_workspace_bytes(n);
+            void* stream = exact(cap);
+            void* ws = exact(ws_bytes);
+            uint64_t* totals = static_cast<uint64_t*>(exact(16));
+            const fh_status st = fh_huffman_encode(bytes, n, stream, cap, totals, ws, ws_bytes, nullptr);
+            std::vector<unsigned char> result;
+            if (st == FH_OK) {
+                result.assign(static_cast<unsigned char*>(stream), static_cast<unsigned char*>(stream) + totals[0]);
+                result.insert(result.end(), reinterpret_cast<unsigned char*>(totals), reinterpret_cast<unsigned char*>(totals) + 16);
+            }
+            put_result(out, (int32_t)st, result.data(), result.size());
+            std::free(bytes); std::free(stream); std::free(ws); std::free(totals);
         } else if (kind == 'S') {
             const int32_t dtype = take<int32_t>(in), window = take<int32_t>(in);
             const int64_t maps = take<int64_t>(in), h = take<int64_t>(in), w = take<int64_t>(in);

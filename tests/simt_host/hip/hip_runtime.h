@@ -5,7 +5,7 @@
 //
 // What it models: threadIdx / blockIdx / blockDim / gridDim, __shared__ (one copy: workgroups run one
 // after the other), __syncthreads, atomics, and the wave-level operations the decoders use (__ballot,
-// readlane, the row_shr / row_bcast data-parallel-primitive controls, mbcnt) for waves of 64.  A
+// readlane, the row_shr / row_bcast data-parallel-primitive controls, mbcnt, the wavefront-scope fence) for waves of 64.  A
 // wave-level exchange needs every lane of the wave that has not left the kernel to take part, as on
 // the hardware when the wave is converged; readfirstlane is only used on wave-uniform values in the
 // sources compiled here and returns its argument.
@@ -184,6 +184,10 @@ template <typename T> inline T atomic_max(T* p, T v)
 #define __builtin_amdgcn_mbcnt_hi(m, a) (simt::mbcnt_hi((m), (a)))
 #define atomicAdd(p, v) (simt::atomic_add((p), (v)))
 #define atomicMax(p, v) (simt::atomic_max((p), (v)))
+#define atomicOr(p, v) (__atomic_fetch_or((p), (v), __ATOMIC_RELAXED))
+// where the sources rely on the LDS operations of one wave completing in order, they say so with a wavefront-scope
+// fence in converged code: here, where the lanes are threads of their own, that is a barrier over the wave
+#define __builtin_amdgcn_fence(order, scope) (simt::ctx.wave->bar.arrive_and_wait())
 
 #define hipLaunchKernelGGL(kernel, grid, block, lds, stream, ...) \
     simt::launch((grid), (block), [&] { kernel(__VA_ARGS__); })

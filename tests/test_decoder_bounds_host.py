@@ -103,6 +103,23 @@ def test_huffman_valid_streams_decode_as_the_oracle_does(decoders):
         assert np.array_equal(got, d), f"n = {d.size}"
 
 
+def test_huffman_encoder_on_the_cpu_writes_the_oracles_streams(decoders):
+    """The encoder's kernels through the same stand-in (histogram, code construction, count, scan, write): the
+    stream and its totals byte for byte, with the buffers sized to the byte."""
+    rng = np.random.default_rng(9)
+    datas = [_clustered(rng, n, s) for n, s in ((1, 3.0), (255, 3.0), (256, 1.0), (257, 6.0), (4096, 6.0), (70_001, 6.0),
+                                                  (300_001, 0.4), (65536 * 3 + 17, 20.0))]
+    datas.append(rng.integers(0, 256, 200_000, dtype=np.uint8))
+    datas.append(np.minimum(rng.geometric(0.5, 150_000) - 1, 255).astype(np.uint8))
+    datas.append(np.full(5000, 7, np.uint8))
+    cases = [b"E" + struct.pack("<Q", d.size) + d.tobytes() for d in datas]
+    for d, (st, got) in zip(datas, decoders(cases)):
+        want, bits = oracle.huffman_encode(d)
+        assert st == FH_OK
+        assert got[-16:].view(np.uint64).tolist() == [want.size, bits], f"n = {d.size}"
+        assert np.array_equal(got[:-16], want), f"n = {d.size}"
+
+
 def test_huffman_foreign_streams_stay_in_bounds(decoders):
     rng = np.random.default_rng(6)
     n = 200_003                                               # 782 chunks: four workgroups of 256 chunks
