@@ -6,6 +6,7 @@
 // case file: uint32 count, then per case
 //   'H' : uint64 n, stream_bytes, out_cap; stream bytes
 //   'E' : uint64 n; the bytes to encode (result: the stream's bytes in use, then the two totals)
+//   'Z' : int32 dtype, window; int64 maps, h, w; float tau, eps; the maps (result: info, uint64 totals[4], values and index bytes in use)
 //   'S' : int32 dtype, window; int64 maps, h, w; float eps; uint64 info_bytes, values_bytes, indices_bytes; the three arrays
 // result file: per case int32 status, uint64 out bytes, the output.
 #include <cstdint>
@@ -79,6 +80,31 @@ int main(int argc, char** argv)
             }
             put_result(out, (int32_t)st, result.data(), result.size());
             std::free(bytes); std::free(stream); std::free(ws); std::free(totals);
+        } else if (kind == 'Z') {
+            const int32_t dtype = take<int32_t>(in), window = take<int32_t>(in);
+            const int64_t maps = take<int64_t>(in), h = take<int64_t>(in), w = take<int64_t>(in);
+            const float tau = take<float>(in), eps = take<float>(in);
+            const size_t esize = dtype == FH_F32 ? 4u : 2u, numel = (size_t)(maps * h * w);
+            void* x = take_bytes(in, numel * esize);
+            const size_t info_bytes = fh_sparse_info_bytes(maps, h, w, window), index_cap = fh_sparse_index_bytes(maps, h, w, window);
+            const size_t ws_bytes = fh_sparse_workspace_bytes(maps, h, w, window);
+            void* info = exact(info_bytes);
+            void* values = exact(numel * esize);
+            void* indices = exact(index_cap);
+            void* ws = exact(ws_bytes);
+            uint64_t* totals = static_cast<uint64_t*>(exact(32));
+            const fh_status st = fh_sparse_encode(x, (fh_dtype)dtype, maps, h, w, window, tau, eps, info, info_bytes, values,
+                                                  numel * esize, indices, index_cap, totals, ws, ws_bytes, nullptr);
+            std::vector<unsigned char> result;
+            if (st == FH_OK) {
+                const auto add = [&](const void* p, size_t n) { result.insert(result.end(), (const unsigned char*)p, (const unsigned char*)p + n); };
+                add(info, info_bytes);
+                add(totals, 32);
+                add(values, (size_t)totals[0] * esize);
+                add(indices, (size_t)totals[1]);
+            }
+            put_result(out, (int32_t)st, result.data(), result.size());
+            std::free(x); std::free(info); std::free(values); std::free(indices); std::free(ws); std::free(totals);
         } else if (kind == 'S') {
             const int32_t dtype = take<int32_t>(in), window = take<int32_t>(in);
             const int64_t maps = take<int64_t>(in), h = take<int64_t>(in), w = take<int64_t>(in);

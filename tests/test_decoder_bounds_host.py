@@ -204,6 +204,20 @@ def test_sparse_valid_streams_decode_as_the_oracle_does(decoders):
         assert np.array_equal(got, want.view(np.uint8).reshape(-1)), f"{shape}"
 
 
+def test_sparse_encoder_on_the_cpu_writes_the_oracles_streams(decoders):
+    """The encoder's kernels through the same stand-in: block bytes, totals, and the two streams byte for byte."""
+    shapes = SPARSE_SHAPES + [(700, 56, 56, 4, "f32", 0.02)]
+    cases, wants = [], []
+    for k, (maps, h, w, n, dtype, eps) in enumerate(shapes):
+        x = _sparse_input(maps, h, w, dtype, 50 + k)
+        cases.append(b"Z" + struct.pack("<iiqqqff", 0 if dtype == "f32" else 1, n, maps, h, w, 0.5, eps) + x.tobytes())
+        info, values, indices, totals = oracle.sparse_encode(x, maps, h, w, n, 0.5, dtype=dtype, eps=eps)
+        wants.append(np.concatenate([info, totals.view(np.uint8), values.view(np.uint8).reshape(-1), indices]))
+    for shape, want, (st, got) in zip(shapes, wants, decoders(cases)):
+        assert st == FH_OK
+        assert got.size == want.size and np.array_equal(got, want), f"{shape}"
+
+
 def test_sparse_foreign_streams_stay_in_bounds(decoders):
     rng = np.random.default_rng(8)
     cases = []
