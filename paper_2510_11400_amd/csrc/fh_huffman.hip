@@ -470,13 +470,17 @@ __global__ __launch_bounds__(kThreads) void huffman_write_kernel(const Batch<Lay
         } else if (p.have) {
             load_symbols(lay.in, p.first, p.have, word);
         }
-        uint32_t e[16];
+        uint32_t e[16];                                       // code << 8 | length; a symbol that does not exist: length 0
         uint32_t bits = 0;
+        if (round_is_whole(lay, group, wave, round)) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            e[j] = (uint32_t)j < p.have ? table[(word[j >> 2] >> (8 * (j & 3))) & 0xffu] : 0u;   // code << 8 | length; nothing: length 0
-            bits += e[j] & 0xffu;
+            for (int j = 0; j < 16; ++j) e[j] = table[(word[j >> 2] >> (8 * (j & 3))) & 0xffu];
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) e[j] = (uint32_t)j < p.have ? table[(word[j >> 2] >> (8 * (j & 3))) & 0xffu] : 0u;
         }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) bits += e[j] & 0xffu;
         // where the lane's bits start: its chunk's word offset inside the round, then the lanes before it in the chunk
         const uint32_t start = ((chunk_at[chunk0 + (lane >> 4)] - run_at) << 5) + (sum_to_lane_15_of_row(bits) - bits);
         uint32_t at = start >> 5;                             // the word being filled
