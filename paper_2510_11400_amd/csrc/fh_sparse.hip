@@ -397,66 +397,44 @@ __device__ __forceinline__ typename TileMask<N>::type csr_mask(const uint8_t* si
 }
 
 // ---- pass 1: what each group of tiles (a workgroup of pass 3) will write -------------------------
-constexpr int kGroupsPerWorkgroup = 4;             // waves of a pass-1 workgroup, a group each
+constexpr int kGroupsPerWorkgroup = 4;             // decode: waves of a pass-1 workgroup, a group each
 
-// encode: non-zero count, density, info byte.  A wave owns a group (the tiles of one workgroup of pass 3): a lane
-// takes the tiles lane, lane + 64, ... of it, with the loads of kTilesInFlight of them issued together, and the
-// group's sums are a wave reduction with no barrier.  (A workgroup per group with a thread per tile -- 16 KiB of
-// input per workgroup, four loads per thread, then a barrier -- read at 3.2 TB/s.)
-template <int N> struct CountTiles { static constexpr int kInFlight = N == 8 ? 1 : 4; };
-
-template <typename Bits, int N>
-__device__ __forceinline__ uint32_t info_byte_of(const Bits (&e)[N][N], const TilePos& t, float tau, float two_eps)
-{
-    uint32_t nnz = 0;
-#pragma unroll
-    for (int r = 0; r < N; ++r)
-#pragma unroll
-        for (int c = 0; c < N; ++c) nnz += bits_of<Bits>(e[r][c]) != 0u ? 1u : 0u;       // padding is zero
-    const uint32_t area = t.rows * t.cols;
-    const float density = (float)nnz / (float)area;           // IEEE division: average pooling of the mask
-    uint32_t byte = density <= tau ? nnz : (0x80u | area);
-    if ((byte & 0x80u) && two_eps > 0.0f) {                   // dense, within the error bound: count the outliers
-        uint8_t code[N][N];
-        byte = 0x80u | lorenzo_codes<Bits, N>(e, t, two_eps, code);
-    }
-    return byte;
-}
-
+// encode: non-zero count, density, info byte; one thread per tile, one workgroup per group.  (A wave per group with
+// four tiles of a lane in flight and no barrier was measured: 7 % slower on 371 MB of maps, 35 % slower on 23 MB,
+// where it leaves too few waves.)
 template <typename Bits, int N, bool STREAM>
-__global__ __launch_bounds__(64 * kGroupsPerWorkgroup) void sparse_count_kernel(const Batch<Job> batch)
+__global__ __launch_bounds__(Group<N>::kTiles) void sparse_count_kernel(const Batch<Job> batch)
 {
-    constexpr int T = Group<N>::kTiles, PER_LANE = T / 64, FLY = CountTiles<N>::kInFlight;
-    static_assert(PER_LANE % FLY == 0, "a lane's tiles come in whole batches");
+    constexpr int T = Group<N>::kTiles, WAVES = Group<N>::kWaves;
+    __shared__ uint64_t lds[3 * kMaxWaves];
     uint32_t block;
     const Job& job = batch.item[batch_item(batch, blockIdx.x, block)];
     const MapShape& s = job.shape;
-    const uint32_t lane = threadIdx.x & 63u, group = block * kGroupsPerWorkgroup + (threadIdx.x >> 6);
-    if (group >= job.wg_count) return;                        // wave-uniform
-    const Bits* x = static_cast<const Bits*>(s.x);
+    const float tau = job.tau;
+    uint8_t* info = job.info;
+    const uint32_t b = block * T + threadIdx.x;
     Sums mine = {0, 0, 0};
+    if (b < s.tiles) {
+        const TilePos t = tile_pos(s, b);
+        Bits e[N][N];
+        load_tile<Bits, N, STREAM>(static_cast<const Bits*>(s.x) + t.origin, t, s.w, s.rows_are_vectors != 0u, e);
+        uint32_t nnz = 0;
 #pragma unroll
-    for (int j0 = 0; j0 < PER_LANE; j0 += FLY) {
-        Bits e[FLY][N][N];
-        TilePos t[FLY];
+        for (int r = 0; r < N; ++r)
 #pragma unroll
-        for (int j = 0; j < FLY; ++j) {
-            const uint32_t b = group * T + (j0 + j) * 64 + lane;
-            t[j] = tile_pos(s, b < s.tiles ? b : s.tiles - 1u);   // a tile that does not exist reads the last one's
-            load_tile<Bits, N, STREAM>(x + t[j].origin, t[j], s.w, s.rows_are_vectors != 0u, e[j]);
+            for (int c = 0; c < N; ++c) nnz += bits_of<Bits>(e[r][c]) != 0u ? 1u : 0u;   // padding is zero
+        const uint32_t area = t.rows * t.cols;
+        const float density = (float)nnz / (float)area;       // IEEE division: average pooling of the mask
+        uint32_t byte = density <= tau ? nnz : (0x80u | area);
+        if ((byte & 0x80u) && s.two_eps > 0.0f) {             // dense, within the error bound: count the outliers
+            uint8_t code[N][N];
+            byte = 0x80u | lorenzo_codes<Bits, N>(e, t, s.two_eps, code);
         }
-#pragma unroll
-        for (int j = 0; j < FLY; ++j) {
-            const uint32_t b = group * T + (j0 + j) * 64 + lane;
-            if (b < s.tiles) {
-                const uint32_t byte = info_byte_of<Bits, N>(e[j], t[j], job.tau, s.two_eps);
-                job.info[b] = (uint8_t)byte;
-                mine = mine + tile_sums(byte, t[j], s.two_eps > 0.0f);
-            }
-        }
+        info[b] = (uint8_t)byte;
+        mine = tile_sums(byte, t, s.two_eps > 0.0f);
     }
-    const Sums total = wave_total(wave_inclusive_scans(narrow(mine)));
-    if (lane == 0u) job.wg[group] = total;
+    const Sums total = workgroup_sum<WAVES>(mine, lds);
+    if (threadIdx.x == 0) job.wg[block] = total;
 }
 
 // decode: the same sums from the info bytes.  A wave owns a group: a lane takes the tiles lane,
@@ -943,8 +921,8 @@ fh_status fh_sparse_encode_batch(const fh_sparse_encode_item* items, int32_t cou
         seal(run.all);
 // maps that no cache will hold until the second pass are read with the non-temporal hint in both
         const bool streamed = run_bytes >= kStreamedFrom;
-        if (streamed) launch_tiles(FH_SPARSE_PICK_STREAM(sparse_count_kernel, dtype, n, true), run.grouped, 64 * kGroupsPerWorkgroup, s);
-        else launch_tiles(FH_SPARSE_PICK_STREAM(sparse_count_kernel, dtype, n, false), run.grouped, 64 * kGroupsPerWorkgroup, s);
+        if (streamed) launch_tiles(FH_SPARSE_PICK_STREAM(sparse_count_kernel, dtype, n, true), run.tiled, tiles_per_workgroup(n), s);
+        else launch_tiles(FH_SPARSE_PICK_STREAM(sparse_count_kernel, dtype, n, false), run.tiled, tiles_per_workgroup(n), s);
         if (run.any_scan)
             hipLaunchKernelGGL(sparse_scan_kernel, dim3(run.all.count), dim3(kScanThreads), 0, s, run.all);
         if (streamed) launch_tiles(FH_SPARSE_PICK_STREAM(sparse_write_kernel, dtype, n, true), run.tiled, tiles_per_workgroup(n), s);
