@@ -717,6 +717,8 @@ def bench_hooks(args, api, W, dev) -> dict:
                    "tensors_compressed": len(recs), "input_bytes": in_bytes,
                    "entry_point": ("fh_classify_channels + fh_channel_slots + fh_compress_mixed / fh_decompress_mixed"
                                    if args.channel_wise else "fh_compress / fh_decompress") + " from autograd's pack / unpack hooks"},
+        "algorithmic_bytes_per_step": int(in_bytes * 2 + 2 * (in_bytes - sm)),
+        "steps_executed": args.warmup + args.steps + 2,      # steps that ran the library's kernels
         "step_ms_without_hooks": round(plain_s * 1e3, 4),
         "peak_activation_bytes_without_hooks": int(plain_peak), "peak_activation_bytes_with_hooks": int(hooked_peak),
         "saved_bytes": int(sm), "purge_cost_ms": round(pc * 1e3, 4), "regain_cost_ms": round(rc * 1e3, 4),

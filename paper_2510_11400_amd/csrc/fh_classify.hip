@@ -152,12 +152,20 @@ template <> struct Span<float> {            // 4 rows of 256, 4 consecutive elem
         const f32x4 v = stream_load(reinterpret_cast<const f32x4*>(p));
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     }
+    __device__ static __forceinline__ void widen(const u32x4& w, float (&x)[EPL]) {
+        const f32x4 v = __builtin_bit_cast(f32x4, w);
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    }
     __device__ static __forceinline__ float one(const float* p) { return *p; }
 };
 template <> struct Span<uint16_t> {         // 2 rows of 512, 8 consecutive elements per lane
     static constexpr int ROWS = 2, EPL = 8;
     __device__ static __forceinline__ void load(const uint16_t* p, float (&x)[EPL]) {
         const u32x4 v = stream_load(reinterpret_cast<const u32x4*>(p));
+        x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
+        x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
+    }
+    __device__ static __forceinline__ void widen(const u32x4& v, float (&x)[EPL]) {
         x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
         x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
     }
@@ -310,7 +318,8 @@ struct CountArgs {
     int32_t spans_per_wave;                                   // consecutive spans one wave walks
 };
 
-template <typename InT>
+// AHEAD: a launch in which some wave walks more than one span.
+template <typename InT, bool AHEAD>
 __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const Batch<CountArgs> batch)
 {
     constexpr int ROWS = Span<InT>::ROWS, EPL = Span<InT>::EPL, ROW = kWave * EPL;
@@ -336,16 +345,29 @@ __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const Batch<Co
         rem = (uint32_t)((uint64_t)base - run * args.inner.d);
         chan = (uint32_t)(run % C);
     }
+    // The next span's rows are requested before this one's are looked at: a wave walks its spans one after the
+    // other, and with one span in flight per wave the device does not hold enough bytes in flight to cover the
+    // memory latency (measured on bf16 [tokens][hidden] tensors with 6 to 16 spans per wave: 32 -> 28 us per 80 MB).
+    u32x4 now[ROWS], next[ROWS];
+    const auto request = [&](int64_t at, u32x4 (&w)[ROWS]) {  // whole spans only: the last one of a tensor is read element by element
+        if (at + kSpan <= numel) {
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) w[r] = stream_load(reinterpret_cast<const u32x4*>(x + at + r * ROW + lane * EPL));
+        }
+    };
+    if (AHEAD && base < numel) request(base, now);
     for (int s = 0; s < args.spans_per_wave && base < numel; ++s, base += kSpan) {
         const InT* xs = x + base;
         const bool interior = base + kSpan <= numel;
+        if (AHEAD && s + 1 < args.spans_per_wave && base + kSpan < numel) request(base + kSpan, next);
+        if (!AHEAD) request(base, now);
         uint32_t bits = 0u;                                   // bit r * EPL + j: that element is an outlier
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             float v[EPL];
             const uint32_t e0 = r * ROW + lane * EPL;
             if (interior) {
-                Span<InT>::load(xs + e0, v);
+                Span<InT>::widen(now[r], v);
             } else {
 #pragma unroll
                 for (int j = 0; j < EPL; ++j)
@@ -356,6 +378,10 @@ __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const Batch<Co
                 const double d = (double)v[j] - mean;
                 if (d * d > threshold) bits |= 1u << (r * EPL + j);          // false for the NaN filler
             }
+        }
+        if (AHEAD) {
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) now[r] = next[r];
         }
         while (bits) {                                        // rare: about k-sigma tail mass * 16 per lane
             const uint32_t k = (uint32_t)__builtin_ctz(bits);
@@ -523,10 +549,12 @@ fh_status run_classify(const fh_classify_item* items, const int64_t* numels, int
         a.counts = static_cast<uint32_t*>(items[i].counts);
         a.inner = make_small_div((uint32_t)items[i].inner);
         a.channels = make_small_div((uint32_t)items[i].channels);
-        // a workgroup clears and flushes `channels` histogram bins: give it enough elements
-        // to make that cheap, but no more (short workgroups measured faster)
+        // a workgroup clears `channels` histogram bins and adds the non-zero ones to the tensor's counters with
+        // atomics that meet those of every other workgroup on a few cache lines: give it enough elements to make
+        // that cheap, but no more (short workgroups measured faster on feature maps; 128 elements per bin and
+        // wave on [tokens][hidden] tensors, where the outliers of ordinary activations touch most bins)
         const int64_t ch = items[i].channels;
-        a.spans_per_wave = ch <= 512 ? 1 : ch <= 2048 ? 2 : ch <= 8192 ? 4 : 8;
+        a.spans_per_wave = (int32_t)(ch <= 512 ? 1 : ch / 128 < 16 ? ch / 128 : 16);
         const int64_t per_block = (int64_t)a.spans_per_wave * kWavesPerBlock * kSpan;
         if (!push(cb, a, ceil_div(numels[i], per_block))) return FH_ERR_BAD_NUMEL;
         push(kb, MaskItem{a.counts, static_cast<uint8_t*>(items[i].mask), items[i].min_outliers, (int32_t)ch},
@@ -537,8 +565,15 @@ fh_status run_classify(const fh_classify_item* items, const int64_t* numels, int
         seal(cb);
         seal(kb);
         const dim3 grid(cb.block_start[cb.count]);
-        if (dtype == FH_F32) hipLaunchKernelGGL(count_outliers_kernel<float>, grid, block, lds, s, cb);
-        else hipLaunchKernelGGL(count_outliers_kernel<uint16_t>, grid, block, lds, s, cb);
+        bool ahead = false;
+        for (int k = 0; k < cb.count; ++k) ahead = ahead || cb.item[k].spans_per_wave > 1;
+        if (dtype == FH_F32) {
+            if (ahead) hipLaunchKernelGGL((count_outliers_kernel<float, true>), grid, block, lds, s, cb);
+            else hipLaunchKernelGGL((count_outliers_kernel<float, false>), grid, block, lds, s, cb);
+        } else {
+            if (ahead) hipLaunchKernelGGL((count_outliers_kernel<uint16_t, true>), grid, block, lds, s, cb);
+            else hipLaunchKernelGGL((count_outliers_kernel<uint16_t, false>), grid, block, lds, s, cb);
+        }
         hipLaunchKernelGGL(mask_kernel, dim3(kb.block_start[kb.count]), block, 0, s, kb);
     }
     return hipGetLastError() == hipSuccess ? FH_OK : FH_ERR_LAUNCH;
