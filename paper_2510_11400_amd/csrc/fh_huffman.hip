@@ -187,7 +187,13 @@ __global__ __launch_bounds__(256) void huffman_code_kernel(const Batch<Layout> b
             // in all lanes and made known as such (readfirstlane), so that counters, comparisons and branches are
             // scalar instructions; the lanes' LDS stores write one value to one address.  (Both queues spread
             // over the lanes of registers, read with v_readlane and a scalar select, measured slower -- 71 us
-            // against 58 for 250 merges: what a merge costs is its instruction count, not the LDS latency.)
+            // against 58 for 250 merges: what a merge costs is its instruction count, not the LDS latency.  So did
+            // a 64-node window of either queue in one register each, 59 us.  Merges that do not depend on each
+            // other done by the lanes at once -- the k leaves no heavier than the front node pair up in
+            // floor(k / 2) leaf-leaf merges, the k nodes lighter than the front leaf likewise -- give the same
+            // depths and take a uniform histogram's 255 merges from 46 to 7 us, but on the index streams of the
+            // predictive form leaves and nodes alternate, few steps find a batch, and the dearer step made the
+            // kernel slower: 64 us.)
             if (lane == 0) deepest = 0u;
             const uint32_t mm = (uint32_t)__builtin_amdgcn_readfirstlane(m);
             if (mm > 1u) {
