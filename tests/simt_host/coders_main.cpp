@@ -1,5 +1,6 @@
-// Runs the library's two stream decoders -- the real entry points, their kernels compiled for the CPU
-// against the stand-in hip_runtime.h of this folder -- on cases read from a file, with every buffer
+// Runs the library's stream coders -- the real entry points of the sparse / predictive storage and of the
+// Huffman stage, decoders and encoders, their kernels compiled for the CPU against the stand-in
+// hip_runtime.h of this folder -- on cases read from a file, with every buffer
 // allocated at exactly the size the call is told, so that AddressSanitizer sees any access the kernels'
 // index arithmetic lets out of bounds.  TEST INFRASTRUCTURE ONLY (test_decoder_bounds_host.py).
 //

@@ -50,7 +50,7 @@ def decoders(tmp_path_factory):
     for j in jobs:
         assert j.wait() == 0, "the kernels did not compile for the host"
     main_o = str(out / "main.o")
-    subprocess.run([cxx, *flags, "-c", os.path.join(SHIM, "decoders_main.cpp"), "-o", main_o], check=True)
+    subprocess.run([cxx, *flags, "-c", os.path.join(SHIM, "coders_main.cpp"), "-o", main_o], check=True)
     exe = str(out / "simt_decoders")
     subprocess.run([cxx, "-pthread", "-fsanitize=address,undefined", main_o, *objs, "-o", exe], check=True)
 
