@@ -96,6 +96,9 @@ class SavedActivations(torch.autograd.graph.saved_tensors_hooks):
     neither parameters nor listed in `exclude` (weights are saved for backward too, and must
     stay exact: pass `exclude=model.parameters()`; tensors are recognised by their storage
     address).  Everything else is saved as it is.  Non-contiguous tensors are made contiguous first (a copy by torch).
+    Under `torch.autocast` a layer saves the low-precision COPY of its weight, which is neither a Parameter
+    nor at a parameter's address: such copies are quantised like activations unless the caller keeps them
+    out (run the forward pass in the parameters' own dtype, or raise `min_numel` above the weights' sizes).
     Stochastic rounding draws its bits from (seed, tensor_id); tensor ids count up from
     `first_tensor_id` in the order tensors are saved, so a step is reproducible.
 
