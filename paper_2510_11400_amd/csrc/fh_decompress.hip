@@ -108,8 +108,8 @@ __device__ __forceinline__ void fetch_kept(const ChannelMap& cm, int raw_dtype, 
 // One channel per element (fh_channels.hpp): the wave's restored span is parked in LDS in the output's
 // dtype, the lanes walk the span's (sample, row) pairs and overwrite the kept elements with the
 // raw store's values -- consecutive lanes, consecutive rows --, then every lane takes its 16 bytes
-// per row back and stores them.  The first pairs of a lane are loaded before the codes are
-// expanded, so that their latency overlaps that of the codes.  (The alternative measured: every lane
+// per row back and stores them.  A lane's first raw-store entries are requested together with the
+// codes, before the list of rows exists, so that their latency overlaps that of the codes.  (The alternative measured: every lane
 // loading a raw entry for each of its elements and merging by masks.)
 typedef uint16_t __attribute__((may_alias)) park_u16;
 typedef uint32_t __attribute__((may_alias)) park_u32;
@@ -151,13 +151,28 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
         }
     };
     const uint16_t* rows = nullptr;
+    using RawBits = typename std::conditional<sizeof(OutT) == 4, uint32_t, uint16_t>::type;
+    RawBits ahead[kPairsAhead] = {};                          // MIXED: a lane's first raw-store entries, in the output's dtype
     if constexpr (MIXED) {
         if (rows_listed(*cm)) {                               // the same for every thread of the workgroup, which all get here
             // the table entries first, then the span's codes (so that waiting for the former does not wait for the
             // latter), and the list is filed while the codes are on their way
             SlotWords words;
             list_rows_request<kDBlock>(*cm, words);
-            if (interior) load_span();
+            if (interior) {
+                load_span();
+                // ... and the raw store's entries of the span's samples, all rows of them: which of them are kept
+                // elements of this span is known only once the list is there, but where they lie is not a
+                // question -- consecutive lanes, consecutive entries -- so they are on their way together with the codes
+                const ElemPos at = locate_base(*cm, (uint32_t)wave_base);
+                const uint64_t raw0 = (uint64_t)at.o * cm->raw_channels;
+                const uint32_t pairs = span_pairs(*cm, at, WAVE_SPAN);
+#pragma unroll
+                for (int k = 0; k < kPairsAhead; ++k) {
+                    const uint32_t i = k * kWave + lane;
+                    ahead[k] = i < pairs ? raw_as<RawBits>(cm->raw, raw0 + i, raw_dtype) : (RawBits)0;
+                }
+            }
             list_rows_file<kDBlock>(*cm, words, listed);
             rows = listed;
         }
@@ -177,11 +192,7 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
                 const uint32_t pairs = span_pairs(*cm, wave_pos, WAVE_SPAN);
                 PairWalk walk = pair_walk(*cm, wave_pos, lane);
                 uint32_t off[kPairsAhead];
-                Bits val[kPairsAhead];
                 first_pairs(*cm, walk, rows, pairs, off);
-#pragma unroll
-                for (int k = 0; k < kPairsAhead; ++k)
-                    val[k] = off[k] < (uint32_t)WAVE_SPAN ? raw_as<Bits>(cm->raw, raw0 + k * kWave + lane, raw_dtype) : (Bits)0;
                 park_u32x4* mine = reinterpret_cast<park_u32x4*>(park + wave * (WAVE_SPAN * sizeof(OutT)));
 #pragma unroll
                 for (int r = 0; r < kRowsPerWave; ++r) {
@@ -198,7 +209,7 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
                 Parked* elems = reinterpret_cast<Parked*>(mine);
 #pragma unroll
                 for (int k = 0; k < kPairsAhead; ++k)
-                    if (off[k] < (uint32_t)WAVE_SPAN) elems[off[k]] = val[k];
+                    if (off[k] < (uint32_t)WAVE_SPAN) elems[off[k]] = ahead[k];
                 for (uint32_t i = kPairsAhead * kWave; i < pairs; i += kWave) {            // wave-uniform trip count
                     const uint32_t o = pair_offset(walk, rows);
                     pair_advance(*cm, walk);
