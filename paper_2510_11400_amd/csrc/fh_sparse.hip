@@ -224,8 +224,11 @@ __device__ __forceinline__ Sums workgroup_sum(Sums part, uint64_t* lds /* [3 * W
 // memory-side cache what the first one read whenever a layer's kept channels fit there.  STREAM:
 // non-temporal loads, for the first pass over sets that fit no cache (measured on 371 MB of maps:
 // 68 us against 98 us with plain loads; on 23 MB plain loads are the faster by 5 %).
-template <typename Bits, int N> struct RowVec {               // N elements of Bits as one vector
-    typedef Bits type __attribute__((ext_vector_type(N)));
+// N elements of Bits as one vector.  A row of a tile is known to be 16-byte aligned at most (the maps are, and a
+// row is a multiple of 16 bytes), so the 32-byte vector of eight fp32 elements must not claim 32.
+template <typename Bits, int N> struct RowVec {
+    typedef Bits full __attribute__((ext_vector_type(N)));
+    typedef full type __attribute__((aligned(sizeof(full) < 16 ? sizeof(full) : 16)));
 };
 
 template <typename Bits, int N, bool STREAM = false>

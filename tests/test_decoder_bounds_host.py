@@ -239,3 +239,59 @@ def test_sparse_foreign_streams_stay_in_bounds(decoders):
             _sparse_case(info, values, indices, dtype, n, maps, h, w, 0.02 if eps == 0.0 else 0.0),           # read in the other form
         ]
     assert all(st == FH_OK for st, _ in decoders(cases))
+
+
+def test_sparse_random_shapes_on_the_cpu(decoders):
+    """Seeded random shapes, windows, thresholds, error bounds and dtypes (maps narrower or lower than the window,
+    single maps, ragged edges): the encoder's streams and the decoder's maps against the oracle's."""
+    rng = np.random.default_rng(77)
+    specs = []
+    for _ in range(40):
+        n = int(rng.choice([2, 4, 8]))
+        maps, h, w = int(rng.integers(1, 24)), int(rng.integers(1, 45)), int(rng.integers(1, 45))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        eps = float(rng.choice([0.0, 0.0, 0.02, 0.2]))
+        tau = float(rng.choice([0.0, 0.25, 0.5, 1.0]))
+        specs.append((maps, h, w, n, dtype, eps, tau))
+    enc_cases, dec_cases, enc_wants, dec_wants = [], [], [], []
+    for k, (maps, h, w, n, dtype, eps, tau) in enumerate(specs):
+        x = _sparse_input(maps, h, w, dtype, 200 + k)
+        info, values, indices, totals = oracle.sparse_encode(x, maps, h, w, n, tau, dtype=dtype, eps=eps)
+        enc_cases.append(b"Z" + struct.pack("<iiqqqff", 0 if dtype == "f32" else 1, n, maps, h, w, tau, eps) + x.tobytes())
+        enc_wants.append(np.concatenate([info, totals.view(np.uint8), values.view(np.uint8).reshape(-1), indices]))
+        dec_cases.append(_sparse_case(info, values, indices, dtype, n, maps, h, w, eps))
+        dec_wants.append(oracle.sparse_decode(info, values, indices, maps, h, w, n, dtype=dtype, eps=eps))
+    results = decoders(enc_cases + dec_cases)
+    for spec, want, (st, got) in zip(specs, enc_wants, results[: len(specs)]):
+        assert st == FH_OK and got.size == want.size and np.array_equal(got, want), f"encode {spec}"
+    for spec, want, (st, got) in zip(specs, dec_wants, results[len(specs):]):
+        assert st == FH_OK and np.array_equal(got, want.view(np.uint8).reshape(-1)), f"decode {spec}"
+
+
+def test_huffman_random_streams_round_trip_on_the_cpu(decoders):
+    """Seeded random lengths and byte distributions: the encoder's stream against the oracle's, and the decoder on
+    that stream back to the bytes."""
+    rng = np.random.default_rng(78)
+    datas = []
+    for _ in range(24):
+        n = int(rng.integers(1, 120_000))
+        kind = int(rng.integers(0, 4))
+        if kind == 0:
+            d = _clustered(rng, n, float(rng.uniform(0.3, 30.0)))
+        elif kind == 1:
+            d = rng.integers(0, int(rng.integers(1, 257)), n, dtype=np.uint16).astype(np.uint8)
+        elif kind == 2:
+            d = np.minimum(rng.geometric(float(rng.uniform(0.05, 0.9)), n) - 1, 255).astype(np.uint8)
+        else:
+            d = rng.choice(np.array([0, 7, 128, 255], np.uint8), n, p=[0.7, 0.2, 0.09, 0.01])
+        datas.append(d)
+    streams = [oracle.huffman_encode(d) for d in datas]
+    cases = [b"E" + struct.pack("<Q", d.size) + d.tobytes() for d in datas]
+    cases += [_huffman_case(st, d.size) for d, (st, _) in zip(datas, streams)]
+    results = decoders(cases)
+    for d, (want, bits), (st, got) in zip(datas, streams, results[: len(datas)]):
+        assert st == FH_OK and got[-16:].view(np.uint64).tolist() == [want.size, bits], f"encode n = {d.size}"
+        assert np.array_equal(got[:-16], want), f"encode n = {d.size}"
+    for d, (st, got) in zip(datas, results[len(datas):]):
+        assert st == FH_OK and np.array_equal(got, d), f"decode n = {d.size}"
+
