@@ -51,7 +51,8 @@ constexpr int kDecodeThreadsSmall = 256;           // ... of a launch that would
 // decode: LDS for a workgroup's payload slice, in words per chunk: 48 (6 bits per symbol) is what fits beside the
 // tables when one workgroup of 768 takes the whole LDS; two workgroups of 256 per unit have room for 64 (8 bits per
 // symbol: any slice fits on average, and streams of 7-8 bits per symbol no longer fall back to the rings)
-template <int THREADS> struct StageWords { static constexpr int kPerChunk = THREADS >= 768 ? 48 : 64; };
+template <int THREADS> struct StageWords { static constexpr int kPerChunk = THREADS >= 768 ? 46 : 64; };
+constexpr int kSecondEntries = 2048;               // decode: entries of the table behind the fast one
 constexpr int kComputeUnits = 256;                 // MI355X
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -523,47 +524,99 @@ struct LongCodes {
 };
 
 // The symbol whose code, longer than kFastBits, is on top of the stream, as symbol | length << 8 like an entry of the
-// fast table.  The shortest matching length wins and no match consumes one bit (only a stream that no encoder wrote
-// can have either).
-// No loop over LDS: the per-length tables of the lengths beyond the fast table's index, the same
-// for the whole workgroup, held in scalar registers.  A long code is rare per symbol, but a wave takes this path
-// whenever ANY of its 64 lanes meets one -- one step in six on streams of five bits per symbol -- so its cost is
-// paid by all: twelve lengths of shift, subtract, compare and select, then one LDS read, instead of a rolled
-// loop of dependent LDS reads.  `top`: the next 32 bits of the stream.
+// fast table.
+// Canonical codes grow with their length, so the 32-bit windows that start with a code of length <= k are those up
+// to last[k]: the length of the code on top is one more than the number of those bounds that the window exceeds -- a
+// compare and an add per length, the bounds (the same for the whole workgroup) in scalar registers -- and its place
+// among the symbols sorted by (length, symbol) is its value less `first - start` of its length.  `top`: the next
+// 32 bits of the stream.
 struct LongRegs {
-    uint32_t first[kMaxLen - kFastBits], count[kMaxLen - kFastBits], start[kMaxLen - kFastBits];   // lengths kFastBits + 1 ...
+    uint32_t last[kMaxLen - kFastBits - 1];        // [i]: the largest window that starts with a code of length <= kFastBits + 1 + i
 };
 __device__ __forceinline__ LongRegs long_regs(const LongCodes* t)
 {
     LongRegs r;
 #pragma unroll
-    for (int i = 0; i < kMaxLen - kFastBits; ++i) {
+    for (int i = 0; i < kMaxLen - kFastBits - 1; ++i) {
         const int k = kFastBits + 1 + i;
-        r.first[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)t->first[k]);
-        r.count[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)t->per_length[k]);
-        r.start[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)t->start[k]);
+        // left-justified: one past the windows of length <= k (lengths no encoder wrote can claim more than there is)
+        const uint64_t end = ((uint64_t)t->first[k] + t->per_length[k]) << (32 - k);
+        const uint32_t last = end > 0xffffffffull ? 0xffffffffu : end ? (uint32_t)end - 1u : 0u;
+        r.last[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)last);
     }
     return r;
 }
-__device__ __forceinline__ uint32_t decode_long(uint32_t top, const LongRegs& r, const uint8_t* sorted)
+// symbol | length << 8 like an entry of the fast table; the length is kFastBits + 1 at least, whatever the tables say
+__device__ __forceinline__ uint32_t decode_long(uint32_t top, const LongRegs& r, const LongCodes* t)
 {
-    uint32_t at = 0, length = 0;
+    uint32_t length = kFastBits + 1;
 #pragma unroll
-    for (int i = kMaxLen - kFastBits - 1; i >= 0; --i) {      // downwards: the shortest matching length is the one that stays
-        const int k = kFastBits + 1 + i;
-        const uint32_t off = (top >> (32 - k)) - r.first[i];  // wraps to a huge value below the first code
-        const bool hit = off < r.count[i];
-        at = hit ? r.start[i] + off : at;
-        length = hit ? (uint32_t)k : length;
+    for (int i = 0; i < kMaxLen - kFastBits - 1; ++i) length += top > r.last[i] ? 1u : 0u;
+    return t->sorted[((top >> (32u - length)) + t->start[length] - t->first[length]) & 0xffu] | (length << 8);
+}
+
+// A long code is rare per symbol, but a wave pays for one whenever ANY of its 64 lanes meets one -- one step in six
+// on streams of five bits per symbol -- and the walk over the lengths costs several times a short code's step.  So
+// there is a second table behind the fast one.  The long codes are the upper end of the code space: the windows
+// whose first kFastBits bits are `from` or more.  Those windows' first kFastBits + extra bits, less from << extra,
+// index the second table, whose entries are like the fast one's (0: longer still, walk the lengths).  `extra` is
+// as large as kSecondEntries allow, the longest code at most; with no long codes, or more long prefixes than
+// entries, there is no second table.
+struct Second {
+    uint32_t extra;                                // bits beyond kFastBits that index the table; 0: no table
+    uint32_t from;                                 // the first index (of kFastBits + extra bits) it covers
+    uint32_t entries;
+};
+__device__ __forceinline__ Second second_of(const LongCodes* t)
+{
+    Second s{0u, 0u, 0u};
+    uint32_t longest = 0;
+#pragma unroll
+    for (int k = kFastBits + 1; k <= kMaxLen; ++k)
+        if (__builtin_amdgcn_readfirstlane((int)t->per_length[k])) longest = (uint32_t)k;
+    const uint32_t first = (uint32_t)__builtin_amdgcn_readfirstlane((int)t->first[kFastBits + 1]) >> 1;   // as kFastBits bits
+    if (longest == 0u || first >= (1u << kFastBits)) return s;
+    const uint32_t prefixes = (1u << kFastBits) - first;
+    if (prefixes > (uint32_t)kSecondEntries / 2u) return s;
+    uint32_t extra = 1;
+    while (extra < longest - kFastBits && (prefixes << (extra + 1u)) <= (uint32_t)kSecondEntries) ++extra;
+    s.extra = extra;
+    s.from = first << extra;
+    s.entries = prefixes << extra;
+    return s;
+}
+
+// The tables of a stream in LDS, and what the threads hold of them in registers.
+struct Lookup {
+    const uint16_t*  fast;
+    const uint16_t*  second;
+    const LongCodes* tables;
+    Second           behind;
+};
+// What the next symbol's code decodes to, as symbol | length << 8, from the stream's next 32 bits.
+__device__ __forceinline__ uint32_t decode_symbol(const uint16_t* fast, const uint16_t* second, const Second& behind,
+                                                  const LongRegs& longer, const LongCodes* tables, uint32_t top)
+{
+    uint32_t e = fast[top >> (32 - kFastBits)];
+    if (!e) {
+        if (behind.extra) {                                   // workgroup-uniform
+            // below `from` only in a stream that no encoder wrote: any entry will do
+            const uint32_t i = (top >> (32u - kFastBits - behind.extra)) - behind.from;
+            e = second[i < behind.entries ? i : behind.entries - 1u];
+        }
+        if (!e) e = decode_long(top, longer, tables);
     }
-    return length ? sorted[at & 0xffu] | (length << 8) : 1u << 8;   // no match consumes one bit (foreign streams only)
+    return e;
 }
 
 template <typename NextWord>
-__device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const uint16_t* fast, const LongCodes* tables,
-                                             NextWord next_word)
+__device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const Lookup table, NextWord next_word)
 {
-    const LongRegs longer = long_regs(tables);
+    const LongRegs longer = long_regs(table.tables);
+    const Second behind = table.behind;
+    const uint16_t* fast = table.fast;
+    const uint16_t* second = table.second;
+    const LongCodes* tables = table.tables;
     uint32_t taken = 0;                                       // words moved into `buf`
     uint64_t buf = 0;                                         // pending bits, the next one on top
     uint32_t have = 0;
@@ -584,8 +637,7 @@ __device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const
                         buf |= (uint64_t)w << (32u - have);
                         have += 32u;
                     }
-                    uint32_t e = fast[(uint32_t)(buf >> (64 - kFastBits))];
-                    if (!e) e = decode_long((uint32_t)(buf >> 32), longer, tables->sorted);
+                    const uint32_t e = decode_symbol(fast, second, behind, longer, tables, (uint32_t)(buf >> 32));
                     const uint32_t symbol = e & 0xffu, used_bits = e >> 8;
                     buf <<= used_bits;
                     have -= used_bits;
@@ -612,14 +664,17 @@ __device__ __forceinline__ void decode_chunk(uint32_t valid, uint8_t* dst, const
 // The same from words in LDS: no bit buffer to refill (lanes would diverge on when) -- every
 // symbol reads the two words its bits start in and shifts them into place, so a step is two
 // dependent LDS reads and nothing data-dependent in the control flow.
-__device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst, const uint16_t* fast, const LongCodes* tables,
-                                                    const uint32_t* words)
+__device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst, const Lookup table, const uint32_t* words)
 {
+    const LongRegs longer = long_regs(table.tables);
+    const Second behind = table.behind;
+    const uint16_t* fast = table.fast;
+    const uint16_t* second = table.second;
+    const LongCodes* tables = table.tables;
     // Three words of the chunk stay in registers: w0 holds bit `pos`, w1 follows, w2 is the word after that.  A
     // symbol advances by at most 24 bits, one word, so after it the registers move up by one at most, and w2 is
     // read again for the new position: that read is needed one symbol later, so that a symbol waits for one LDS
     // access in a row (the table) rather than two (words, then table).
-    const LongRegs longer = long_regs(tables);
     uint32_t pos = 0, at = 0;                                 // bits of the chunk consumed; at = pos / 32
     uint32_t w0 = words[0], w1 = words[1], w2 = words[2];
     for (uint32_t half = 0; half < valid; half += 16 * kBurst) {
@@ -634,8 +689,7 @@ __device__ __forceinline__ void decode_chunk_staged(uint32_t valid, uint8_t* dst
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
                     const uint32_t top = (uint32_t)(((((uint64_t)w0 << 32) | w1) << (pos & 31u)) >> 32);   // the next 32 bits
-                    uint32_t e = fast[top >> (32 - kFastBits)];
-                    if (!e) e = decode_long(top, longer, tables->sorted);
+                    const uint32_t e = decode_symbol(fast, second, behind, longer, tables, top);
                     four |= (e & 0xffu) << (8 * b);
                     pos += e >> 8;
                     const bool crossed = (pos >> 5) != at;
@@ -687,12 +741,24 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
         payload_words = (uint32_t)(words < 0xffffffffu ? words : 0xffffffffu);
     }
     uint8_t* out = job.out;
-    __shared__ LongCodes tables;
+    // One object, so that the order is the one written here: the tables that every symbol is looked up in come first,
+    // at addresses small enough for the offset field of an LDS instruction (one addition less per symbol).
+    struct Local {
+        uint16_t  fast[1 << kFastBits];                       // next kFastBits bits -> symbol | length << 8; 0: longer code
+        uint16_t  second[kSecondEntries];                     // the same for the long codes' first kFastBits + extra bits
+        LongCodes tables;
+        uint32_t  in_wave[kThreads / 64][kMaxLen + 2];        // [w][k]: symbols of length k among wave w's 64
+        uint32_t  fitting;                                    // chunks of a pass whose slice fits the stage
+        __align__(16) uint32_t stage[kStageWords + kChunkWordsMax + 8];   // the workgroup's slice of the payload, or the rings
+    };
+    __shared__ Local local;
+    LongCodes& tables = local.tables;
     uint32_t (&per_length)[kMaxLen + 2] = tables.per_length, (&first)[kMaxLen + 2] = tables.first, (&start)[kMaxLen + 2] = tables.start;
     uint8_t (&sorted)[256] = tables.sorted;
-    __shared__ uint32_t in_wave[kThreads / 64][kMaxLen + 2];  // [w][k]: symbols of length k among wave w's 64
-    __shared__ uint16_t fast[1 << kFastBits];                 // next kFastBits bits -> symbol | length << 8; 0: longer code
-    __shared__ __align__(16) uint32_t stage[kStageWords + kChunkWordsMax + 8];   // the workgroup's slice of the payload, or the rings
+    uint32_t (&in_wave)[kThreads / 64][kMaxLen + 2] = local.in_wave;
+    uint16_t (&fast)[1 << kFastBits] = local.fast;
+    uint16_t (&second)[kSecondEntries] = local.second;
+    uint32_t (&stage)[kStageWords + kChunkWordsMax + 8] = local.stage;
     // threads 0..255 stand for the 256 symbols while the tables are built; the others only fill and wait
     const uint32_t s = threadIdx.x, wave = s >> 6, lane = s & 63u;
     const bool symbol = s < 256u;
@@ -753,21 +819,50 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
             fast[i] = length ? (uint16_t)(sorted[at & 0xffu] | (length << 8)) : (uint16_t)0;
         }
     }
+    Lookup table;
+    table.fast = fast;
+    table.second = second;
+    table.tables = &tables;
+    table.behind = second_of(&tables);
+    const LongRegs longer = long_regs(&tables);
+    for (uint32_t i = s; i < table.behind.entries; i += kDecodeThreads) {
+        const uint32_t width = (uint32_t)kFastBits + table.behind.extra;
+        const uint32_t e = decode_long((table.behind.from + i) << (32u - width), longer, &tables);
+        second[i] = (e >> 8) <= width ? (uint16_t)e : (uint16_t)0;
+    }
     __syncthreads();
 
-    // These tables serve `groups_per_block` groups of 768 chunks, one after the other.  The payload words of
-    // a group's chunks are one contiguous slice.  When it fits it is brought into LDS with contiguous loads and the
-    // threads read their words from there (a thread walking its chunk in memory would fetch a cache line per
-    // word); a longer slice, or offsets that do not describe one, go through per-thread rings instead.
-    const uint32_t groups = (chunks + kDecodeThreads - 1) / kDecodeThreads;
-    const uint32_t group_end = (block + 1u) * job.groups_per_block < groups ? (block + 1u) * job.groups_per_block : groups;
-    for (uint32_t group = block * job.groups_per_block; group < group_end; ++group) {
-        const uint32_t chunk0 = group * kDecodeThreads;
-        const uint32_t chunk1 = chunk0 + kDecodeThreads < chunks ? chunk0 + kDecodeThreads : chunks;
-        const uint32_t slice_at = offsets[chunk0], slice_end = offsets[chunk1];
-        const bool staged = slice_end >= slice_at && slice_end - slice_at <= (uint32_t)kStageWords && slice_end <= payload_words;
+    // These tables serve `groups_per_block` times 768 (256) chunks, in passes of as many chunks as there are threads
+    // at most.  The payload words of consecutive chunks are one contiguous slice.  A pass takes the chunks whose
+    // slice fits the stage -- all of them up to 46 (64) words per chunk on average, fewer on streams that hardly
+    // compress, where the threads beyond sit the pass out -- brings the slice into LDS with contiguous loads, and
+    // the threads read their words from there (a thread walking its chunk in memory would fetch a cache line per
+    // word).  A pass that could seat few of its chunks, and offsets that do not describe a slice (no encoder wrote
+    // them), go through per-thread rings instead.
+    const uint64_t share = (uint64_t)job.groups_per_block * kDecodeThreads;
+    const uint32_t chunk_stop = (uint32_t)((block + 1u) * share < chunks ? (block + 1u) * share : chunks);
+    for (uint32_t chunk0 = (uint32_t)(block * share < chunks ? block * share : chunks); chunk0 < chunk_stop;) {
+        const uint32_t want = chunk_stop - chunk0 < (uint32_t)kDecodeThreads ? chunk_stop - chunk0 : (uint32_t)kDecodeThreads;
+        const uint32_t slice_at = offsets[chunk0];
+        // the chunks before the first whose end lies outside the stage (or the payload, or before the slice's start)
+        const bool asked = threadIdx.x < want;
+        const uint32_t my_end = asked ? offsets[chunk0 + threadIdx.x + 1u] : 0u;
+        const bool fits = my_end >= slice_at && my_end - slice_at <= (uint32_t)kStageWords && my_end <= payload_words;
+        if (threadIdx.x == 0) local.fitting = want;
+        __syncthreads();
+        {
+            const uint64_t beyond = __ballot(asked && !fits);
+            if (beyond && lane == 0) atomicMin(&local.fitting, wave * 64u + (uint32_t)__builtin_ctzll(beyond));
+        }
+        __syncthreads();
+        const uint32_t fitting = local.fitting;
+        // (workgroup-uniform) Below three quarters of the threads the rings do better: at eight bits per symbol every
+        // chunk is 64 words long, the threads' words lie 64 apart in the stage and all in one LDS bank.
+        const bool staged = fitting > 0u && 4u * fitting >= 3u * want;
+        const uint32_t take = staged ? fitting : want;        // chunks of this pass
+        const uint32_t slice_end = staged ? offsets[chunk0 + fitting] : slice_at;
         const uint32_t chunk = chunk0 + threadIdx.x;
-        const bool live = chunk < chunks;
+        const bool live = threadIdx.x < take;
         const uint64_t base = (uint64_t)chunk * kChunk;
         const uint32_t valid = !live ? 0u : n - base < (uint64_t)kChunk ? (uint32_t)(n - base) : (uint32_t)kChunk;
         const uint32_t first_word = live ? offsets[chunk] : 0u;
@@ -802,7 +897,7 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
             __syncthreads();
             // anything at all for a foreign stream: clamped, the reads stay inside the array (a chunk is at most 192 words)
             const uint32_t at = first_word - slice_at < slice_words ? first_word - slice_at : slice_words;
-            decode_chunk_staged(valid, dst, fast, &tables, stage + phase + at);
+            decode_chunk_staged(valid, dst, table, stage + phase + at);
         } else if (live) {
             // a ring of eight words per thread: when four have been consumed, the four loaded at the
             // previous refill take their place and the next four are requested, so a load has the time
@@ -813,7 +908,7 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
             for (int k = 0; k < 8; ++k) mine[k * kDecodeThreads] = first_word + k < payload_words ? payload[first_word + k] : 0u;
 #pragma unroll
             for (int k = 0; k < 4; ++k) pending[k] = first_word + 8 + k < payload_words ? payload[first_word + 8 + k] : 0u;
-            decode_chunk(valid, dst, fast, &tables, [&](uint32_t taken) {
+            decode_chunk(valid, dst, table, [&](uint32_t taken) {
                 if ((taken & 3u) == 0u && taken != 0u) {      // a block of four used up: refill the half of the ring just freed
                     const uint32_t slot = (taken + 4u) & 7u;
 #pragma unroll
@@ -825,7 +920,8 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
                 return mine[(taken & 7u) * kDecodeThreads];
             });
         }
-        __syncthreads();                                      // the stage is the next group's
+        __syncthreads();                                      // the stage is the next pass's
+        chunk0 += take;
     }
 }
 

@@ -155,6 +155,12 @@ template <typename T> inline T atomic_max(T* p, T v)
     while (seen < v && !__atomic_compare_exchange_n(p, &seen, v, true, __ATOMIC_RELAXED, __ATOMIC_RELAXED)) {}
     return seen;
 }
+template <typename T> inline T atomic_min(T* p, T v)
+{
+    T seen = __atomic_load_n(p, __ATOMIC_RELAXED);
+    while (seen > v && !__atomic_compare_exchange_n(p, &seen, v, true, __ATOMIC_RELAXED, __ATOMIC_RELAXED)) {}
+    return seen;
+}
 
 }  // namespace simt
 
@@ -184,6 +190,7 @@ template <typename T> inline T atomic_max(T* p, T v)
 #define __builtin_amdgcn_mbcnt_hi(m, a) (simt::mbcnt_hi((m), (a)))
 #define atomicAdd(p, v) (simt::atomic_add((p), (v)))
 #define atomicMax(p, v) (simt::atomic_max((p), (v)))
+#define atomicMin(p, v) (simt::atomic_min((p), (v)))
 #define atomicOr(p, v) (__atomic_fetch_or((p), (v), __ATOMIC_RELAXED))
 // where the sources rely on the LDS operations of one wave completing in order, they say so with a wavefront-scope
 // fence in converged code: here, where the lanes are threads of their own, that is a barrier over the wave

@@ -165,11 +165,12 @@ def test_huffman_foreign_streams_stay_in_bounds(decoders):
 
 
 def test_huffman_large_launch_uses_the_wide_workgroups(decoders):
-    """More than 256 groups of 768 chunks: the launch with workgroups of 768 work-items and 48 staged words per
-    chunk; one valid stream, and the same stream with its offsets and payload replaced by noise."""
+    """More than 256 groups of 768 chunks: the launch with workgroups of 768 work-items and 46 staged words per
+    chunk; one valid stream -- its second half too wide for a pass to seat 768 chunks -- and the same stream with
+    its offsets and payload replaced by noise."""
     rng = np.random.default_rng(7)
     n = 256 * 768 * 256 + 77
-    data = _clustered(rng, n, 6.0)
+    data = np.concatenate([_clustered(rng, n // 2, 6.0), _clustered(rng, n - n // 2, 20.0)])
     stream, _ = oracle.huffman_encode(data)
     head = 256 + 4 * ((n + 255) // 256 + 1)
     noisy = stream.copy()

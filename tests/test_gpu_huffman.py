@@ -50,16 +50,23 @@ def test_sizes_around_vectors_chunks_and_groups(api, n):
     _check(api, data, "normal around 128")
 
 
-@pytest.mark.parametrize("spread", [2.5, 14.0, 0.0])
+@pytest.mark.parametrize("spread", [2.5, 14.0, 20.0, -1.0, 0.0])
 def test_streams_long_enough_that_a_workgroup_decodes_several_groups(api, spread):
     # The decoder takes 768 chunks per workgroup and one workgroup per compute unit: 300 such groups and a ragged
     # tail are more than the device holds at once, so a workgroup takes two and the last one the ragged one.
-    # spread 14: codes longer than the decoder's fast table occur; 0: uniform bytes, whose 64 words per chunk do
-    # not fit the LDS stage of either side (the direct payload stores and the per-thread rings)
+    # spread 14: codes longer than the decoder's fast table occur; 20: more words per chunk than the decoder's LDS
+    # stage holds for 768 chunks, so its passes seat fewer; -1: a clustered first half and noise behind it, passes of
+    # every kind in one launch; 0: uniform bytes, whose 64 words per chunk do not fit the LDS stage of either side
+    # (the direct payload stores and the per-thread rings)
     n = 256 * 768 * 300 + 77
-    rng = np.random.default_rng(int(spread * 10))
-    data = (np.clip(np.rint(rng.normal(128, spread, n)), 0, 255) if spread else rng.integers(0, 256, n)).astype(np.uint8)
-    _check(api, data, f"spread {spread}")
+    rng = np.random.default_rng(int(abs(spread) * 10))
+    if spread > 0:
+        data = np.clip(np.rint(rng.normal(128, spread, n)), 0, 255)
+    elif spread < 0:
+        data = np.concatenate([np.clip(np.rint(rng.normal(128, 3.0, n // 2)), 0, 255), rng.integers(0, 256, n - n // 2)])
+    else:
+        data = rng.integers(0, 256, n)
+    _check(api, data.astype(np.uint8), f"spread {spread}")
 
 
 @pytest.mark.parametrize("kind", ["uniform", "one", "two", "geometric", "all-once", "ties"])
