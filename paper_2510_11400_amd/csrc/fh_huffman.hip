@@ -100,7 +100,7 @@ struct DecodeJob {
     const uint64_t* n_dev;                                    // device: the symbol count; or null
     uint64_t        stream_bytes;                             // the valid prefix of the stream
     uint32_t        payload_words, chunks;
-    uint32_t        groups_per_block;                         // groups of 768 chunks a workgroup decodes with one set of tables
+    uint32_t        chunks_per_block;                         // chunks that a workgroup decodes with one set of tables
 };
 
 // Every pass serves up to kBatch streams (fh_batch.hpp); the per-stream passes take a workgroup per stream.
@@ -194,7 +194,9 @@ __global__ __launch_bounds__(256) void huffman_code_kernel(const Batch<Layout> b
             // floor(k / 2) leaf-leaf merges, the k nodes lighter than the front leaf likewise -- give the same
             // depths and take a uniform histogram's 255 merges from 46 to 7 us, but on the index streams of the
             // predictive form leaves and nodes alternate, few steps find a batch, and the dearer step made the
-            // kernel slower: 64 us.)
+            // kernel slower: 64 us.  And a merge without branches -- the next two nodes of both queues read from
+            // register windows by lane index, the two smallest of the four taken by selects -- is some 50
+            // instructions with no wait for LDS, and takes the same time to the microsecond.)
             if (lane == 0) deepest = 0u;
             const uint32_t mm = (uint32_t)__builtin_amdgcn_readfirstlane(m);
             if (mm > 1u) {
@@ -832,14 +834,13 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
     }
     __syncthreads();
 
-    // These tables serve `groups_per_block` times 768 (256) chunks, in passes of as many chunks as there are threads
-    // at most.  The payload words of consecutive chunks are one contiguous slice.  A pass takes the chunks whose
+    // These tables serve `chunks_per_block` chunks, in passes of as many chunks as there are threads at most.  The payload words of consecutive chunks are one contiguous slice.  A pass takes the chunks whose
     // slice fits the stage -- all of them up to 46 (64) words per chunk on average, fewer on streams that hardly
     // compress, where the threads beyond sit the pass out -- brings the slice into LDS with contiguous loads, and
     // the threads read their words from there (a thread walking its chunk in memory would fetch a cache line per
     // word).  A pass that could seat few of its chunks, and offsets that do not describe a slice (no encoder wrote
     // them), go through per-thread rings instead.
-    const uint64_t share = (uint64_t)job.groups_per_block * kDecodeThreads;
+    const uint64_t share = job.chunks_per_block;
     const uint32_t chunk_stop = (uint32_t)((block + 1u) * share < chunks ? (block + 1u) * share : chunks);
     for (uint32_t chunk0 = (uint32_t)(block * share < chunks ? block * share : chunks); chunk0 < chunk_stop;) {
         const uint32_t want = chunk_stop - chunk0 < (uint32_t)kDecodeThreads ? chunk_stop - chunk0 : (uint32_t)kDecodeThreads;
@@ -1085,17 +1086,19 @@ fh_status fh_huffman_decode_batch(const fh_huffman_decode_item* items, int32_t c
             total += groups[jobs];
             ++jobs;
         }
-        // A workgroup builds a stream's tables once and then decodes `groups_per_block` groups.  With more groups
+        // A workgroup builds a stream's tables once and then decodes `chunks_per_block` chunks.  With more groups
         // in the launch than workgroups fit on the device at once, every stream gets its share of that many
-        // workgroups: all of them are resident from the start and finish together, whereas a launch of 1.4 times
-        // as many would run a second, mostly empty round.
+        // workgroups, and its chunks are dealt out evenly among them: all of them are resident from the start and
+        // finish together (their last pass seats fewer chunks), whereas a launch of 1.4 times as many would run a
+        // second, mostly empty round, and whole groups per workgroup would leave compute units without any.
         Batch<DecodeJob> b;
         reset(b);
         for (int k = 0; k < jobs; ++k) {
             uint64_t blocks = total <= slots ? groups[k] : groups[k] * slots / total;
             if (blocks < 1u) blocks = 1u;
-            job[k].groups_per_block = (uint32_t)((groups[k] + blocks - 1u) / blocks);
-            if (!push(b, job[k], (int64_t)((groups[k] + job[k].groups_per_block - 1u) / job[k].groups_per_block)))
+            const uint64_t chunks = job[k].chunks;
+            job[k].chunks_per_block = (uint32_t)((chunks + blocks - 1u) / blocks);
+            if (!push(b, job[k], (int64_t)((chunks + job[k].chunks_per_block - 1u) / job[k].chunks_per_block)))
                 return FH_ERR_BAD_NUMEL;                      // cannot happen: a stream has at most 2^16 groups
         }
         seal(b);
