@@ -198,3 +198,37 @@ def test_chain_on_tensors_without_salient_channels(api):
         torch.cuda.synchronize()
         st = _compare(api, batch, 0, x, case, dtype)
         assert st.used == 0 and not st.mask.any()
+
+
+@pytest.mark.parametrize("which", ["mobilenetv2", "transformer"])
+def test_full_size_set_in_one_batch_as_it_is_timed(api, which):
+    """The two activation sets of `bench.py --op chain [--config 4]`, each through one batched call each way -- the
+    launch configuration that is timed -- and every tensor, whole, against the oracle chain: the MobileNetV2-style
+    set at batch 64 (0.57 GB of fp32; G128, 4-bit, nearest) and the transformer set (12 layers of [8192][768] and
+    [8192][3072] bf16, 0.75 GB; G64, 2-bit, stochastic), outliers planted in 4 % of the channels, room for 1/16 of
+    the channels in the raw store, window 4, tau 0.5, error bound 0.02, Huffman stage."""
+    from concurrent.futures import ThreadPoolExecutor
+    if which == "mobilenetv2":
+        shapes = ((64, 32, 112 * 112, (112, 112)), (64, 96, 112 * 112, (112, 112)), (64, 144, 56 * 56, (56, 56)),
+                  (64, 192, 28 * 28, (28, 28)), (64, 384, 14 * 14, (14, 14)))
+        G, B, rounding, dtype, dist = 128, 4, "nearest", "f32", ("relu", "relu")
+    else:
+        shapes = tuple(s for _ in range(12) for s in ((16 * 512, 768, 1, None), (16 * 512, 3072, 1, None)))
+        G, B, rounding, dtype, dist = 64, 2, "stochastic", "bf16", ("gauss", "gelu")
+    cases, xs, entries = [], [], []
+    for i, (outer, C, inner, hw) in enumerate(shapes):
+        print(f"[chain] full size, {which}: tensor {i} [{outer}][{C}][{inner}]", flush=True)
+        x, _ = W.outlier_channel_tensor(outer, C, inner, seed=i, dist=dist[i % 2], dtype=dtype)
+        case = (outer, C, inner, hw, max(1, C // 16), G, B, rounding, 4, 0.5, 0.02, 1, dtype, max(1, outer * inner // 100))
+        cases.append(case)
+        xs.append(x)
+        entries.append(_entry(api, _device(x, dtype), case, dtype))
+    batch = api.MixBatch(entries, device=torch.device("cuda"))
+    api.fh_mix_compress_batch(batch)
+    api.fh_mix_decompress_batch(batch)
+    api.fh_mix_compress_batch(batch)                # the classification's outputs live in the workspace
+    torch.cuda.synchronize()
+    print("[chain] full size: oracle chain on every tensor", flush=True)
+    with ThreadPoolExecutor(max_workers=8) as pool:   # the oracle's C routines run without the interpreter lock
+        kept = list(pool.map(lambda i: _compare(api, batch, i, xs[i], cases[i], dtype).used, range(len(cases))))
+    assert all(0 < k <= c[4] for k, c in zip(kept, cases)), kept
