@@ -319,6 +319,7 @@ struct CountArgs {
 };
 
 // AHEAD: a launch in which some wave walks more than one span.
+constexpr int kAhead = 3;                         // spans requested before the one that is looked at
 template <typename InT, bool AHEAD>
 __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const Batch<CountArgs> batch)
 {
@@ -345,22 +346,29 @@ __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const Batch<Co
         rem = (uint32_t)((uint64_t)base - run * args.inner.d);
         chan = (uint32_t)(run % C);
     }
-    // The next span's rows are requested before this one's are looked at: a wave walks its spans one after the
-    // other, and with one span in flight per wave the device does not hold enough bytes in flight to cover the
-    // memory latency (measured on bf16 [tokens][hidden] tensors with 6 to 16 spans per wave: 32 -> 28 us per 80 MB).
-    u32x4 now[ROWS], next[ROWS];
+    // The rows of the spans ahead are requested before this one's are looked at: a wave walks its spans one after
+    // the other, and with one span in flight per wave the device does not hold enough bytes in flight to cover the
+    // memory latency (measured on bf16 [tokens][hidden] tensors with 6 to 16 spans per wave: 32 -> 28 us per 80 MB
+    // with one span ahead; a single such tensor is 1.5 waves per SIMD, and with three spans ahead its pass takes
+    // as long as the first pass over it).  The ring of kAhead + 1 spans has constant indices: the walk is
+    // unrolled by that many.
+    constexpr int RING = AHEAD ? kAhead + 1 : 1;
+    u32x4 ring[RING][ROWS];
     const auto request = [&](int64_t at, u32x4 (&w)[ROWS]) {  // whole spans only: the last one of a tensor is read element by element
         if (at + kSpan <= numel) {
 #pragma unroll
             for (int r = 0; r < ROWS; ++r) w[r] = stream_load(reinterpret_cast<const u32x4*>(x + at + r * ROW + lane * EPL));
         }
     };
-    if (AHEAD && base < numel) request(base, now);
-    for (int s = 0; s < args.spans_per_wave && base < numel; ++s, base += kSpan) {
+    const int spans = args.spans_per_wave;
+    if (AHEAD) {
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k)
+            if (k < spans && base + (int64_t)k * kSpan < numel) request(base + (int64_t)k * kSpan, ring[k]);
+    }
+    // one span: the outliers of its rows into the histogram, then (rem, chan) and base move on by a span
+    const auto look = [&](const u32x4 (&now)[ROWS], bool interior) {
         const InT* xs = x + base;
-        const bool interior = base + kSpan <= numel;
-        if (AHEAD && s + 1 < args.spans_per_wave && base + kSpan < numel) request(base + kSpan, next);
-        if (!AHEAD) request(base, now);
         uint32_t bits = 0u;                                   // bit r * EPL + j: that element is an outlier
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
@@ -379,25 +387,45 @@ __global__ __launch_bounds__(kThreads) void count_outliers_kernel(const Batch<Co
                 if (d * d > threshold) bits |= 1u << (r * EPL + j);          // false for the NaN filler
             }
         }
-        if (AHEAD) {
-#pragma unroll
-            for (int r = 0; r < ROWS; ++r) now[r] = next[r];
-        }
         while (bits) {                                        // rare: about k-sigma tail mass * 16 per lane
-            const uint32_t k = (uint32_t)__builtin_ctz(bits);
+            const uint32_t k2 = (uint32_t)__builtin_ctz(bits);
             bits &= bits - 1u;
-            const uint32_t off = (k / EPL) * ROW + lane * EPL + (k % EPL);   // element offset inside the span
+            const uint32_t off = (k2 / EPL) * ROW + lane * EPL + (k2 % EPL);   // element offset inside the span
             const uint32_t runs = div_small(rem + off, args.inner);           // channel runs crossed from `chan`
             const uint32_t cc = chan + runs;
             const uint32_t c = cc - div_small(cc, args.channels) * C;
             atomicAdd(&hist[c], 1u);
         }
-        // advance (rem, chan) by one span
         const uint32_t t = rem + kSpan;
         const uint32_t runs = div_small(t, args.inner);
         rem = t - runs * args.inner.d;
         const uint32_t cc = chan + runs;
         chan = cc - div_small(cc, args.channels) * C;
+        base += kSpan;
+    };
+    for (int s0 = 0; s0 < spans && base < numel; s0 += RING) {
+        // A round whose spans, and the spans requested during it, are all whole and all this wave's runs without
+        // a test around any load: only then can the waits be for the oldest request alone and not for all of them.
+        if (AHEAD && s0 + RING + kAhead <= spans && base + (int64_t)(RING + kAhead) * kSpan <= numel) {
+#pragma unroll
+            for (int k = 0; k < RING; ++k) {
+                u32x4 (&ahead)[ROWS] = ring[(k + kAhead) % RING];
+#pragma unroll
+                for (int r = 0; r < ROWS; ++r)
+                    ahead[r] = stream_load(reinterpret_cast<const u32x4*>(x + base + (int64_t)kAhead * kSpan + r * ROW + lane * EPL));
+                look(ring[k], true);
+            }
+            continue;
+        }
+#pragma unroll
+        for (int k = 0; k < RING; ++k) {
+            const int s = s0 + k;
+            if (s >= spans || base >= numel) break;
+            if (AHEAD && s + kAhead < spans && base + (int64_t)kAhead * kSpan < numel)
+                request(base + (int64_t)kAhead * kSpan, ring[(k + kAhead) % RING]);
+            if (!AHEAD) request(base, ring[k]);
+            look(ring[k], base + kSpan <= numel);
+        }
     }
     __syncthreads();
     for (uint32_t c = threadIdx.x; c < C; c += kThreads) {
