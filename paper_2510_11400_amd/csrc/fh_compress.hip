@@ -665,11 +665,15 @@ __device__ __forceinline__ void compress_tile(const CompressItem& it, uint32_t t
             // and the list is filed while the span is on its way
             SlotWords words;
             list_rows_request<kCBlock>(*cm, words);
+            // (the filing is written out on both paths: behind their join the compiler could not tell how many loads
+            // are outstanding and would wait for the span before the table entries may be used)
             if (interior) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) w[r] = stream_load(reinterpret_cast<const u32x4*>(xw + r * L::ROW + lane * L::EPL));
+                list_rows_file<kCBlock>(*cm, words, listed);
+            } else {
+                list_rows_file<kCBlock>(*cm, words, listed);
             }
-            list_rows_file<kCBlock>(*cm, words, listed);
             rows = listed;
         }
     }

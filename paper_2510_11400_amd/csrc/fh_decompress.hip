@@ -172,8 +172,12 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
                     const uint32_t i = k * kWave + lane;
                     ahead[k] = i < pairs ? raw_as<RawBits>(cm->raw, raw0 + i, raw_dtype) : (RawBits)0;
                 }
+                // (the filing is written out on both paths: behind their join the compiler could not tell how many
+                // loads are outstanding and would wait for the codes before the table entries may be used)
+                list_rows_file<kDBlock>(*cm, words, listed);
+            } else {
+                list_rows_file<kDBlock>(*cm, words, listed);
             }
-            list_rows_file<kDBlock>(*cm, words, listed);
             rows = listed;
         }
     }

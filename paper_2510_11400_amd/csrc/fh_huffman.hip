@@ -869,17 +869,17 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
         const uint32_t first_word = live ? offsets[chunk] : 0u;
         uint8_t* dst = out + base;
         if (staged) {                                         // workgroup-uniform
-            // 16 bytes per load, eight loads of a thread in flight: one at a time, a slice of ~50 words per thread
+            // 16 bytes per load, twelve loads of a thread in flight: one at a time, a slice of ~50 words per thread
             // would cost as many memory latencies.  The stage starts at the 16-byte boundary at or below the
             // slice's first word (`phase` words earlier); what the vectors cover beyond the payload's ends is
             // read as zero.
             const uint32_t slice_words = slice_end - slice_at;
             const uint32_t phase = (uint32_t)(reinterpret_cast<uintptr_t>(payload + slice_at) >> 2) & 3u;
             const uint32_t vectors = (slice_words + phase + 3u) / 4u;
-            for (uint32_t v0 = 0; v0 < vectors; v0 += 8u * kDecodeThreads) {
-                u32x4 got[8];
+            for (uint32_t v0 = 0; v0 < vectors; v0 += 12u * kDecodeThreads) {
+                u32x4 got[12];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
+                for (int k = 0; k < 12; ++k) {
                     const uint32_t v = v0 + k * kDecodeThreads + threadIdx.x;
                     const int64_t w = (int64_t)slice_at + 4 * (int64_t)v - phase;  // below zero in the first vector at most
                     const auto word_at = [&](int64_t g) { return g >= 0 && g < (int64_t)payload_words ? payload[g] : 0u; };
@@ -890,7 +890,7 @@ __global__ __launch_bounds__(kDecodeThreads) void huffman_decode_kernel(const Ba
                     }
                 }
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
+                for (int k = 0; k < 12; ++k) {
                     const uint32_t v = v0 + k * kDecodeThreads + threadIdx.x;
                     if (v < vectors) *reinterpret_cast<u32x4*>(stage + 4u * v) = got[k];
                 }

@@ -327,20 +327,72 @@ __device__ __forceinline__ void stage_to_stream(const uint8_t* stage, uint8_t* d
     if (i < end) g0[i] = stage[i];
 }
 
-template <int THREADS>
-__device__ __forceinline__ void stream_to_stage(uint8_t* stage, const uint8_t* src, uint32_t nbytes)
+// A slice of a stream into LDS, in two steps so that the loads of both slices of a workgroup are requested before
+// the first of them is waited for: `request` asks for a thread's first K whole vectors and for the bytes before the
+// first and after the last whole vector, `commit` puts them into the stage and brings what is left K vectors at a
+// time.  (A loop of load, wait, LDS store costs one memory latency per iteration: up to ten in a row for the two
+// slices, 157 -> 137 us for the decode of 0.37 GB of maps.)
+template <int K> struct SliceLoads {
+    chunk16 got[K];
+    uint8_t head_byte, tail_byte;
+};
+struct SliceShape {
+    const uint8_t* g0;                             // the 16-byte boundary at or below the slice's first byte
+    uint32_t phase, end, first, last, head_end, tail;   // bytes [phase, end) from g0; whole vectors [first, last)
+};
+__device__ __forceinline__ SliceShape slice_shape(const uint8_t* src, uint32_t nbytes)
 {
-    const uint32_t phase = phase_of(src), end = phase + nbytes;
-    const uint8_t* g0 = src - phase;
-    const uint32_t first = (phase + 15u) >> 4, last = end >> 4;
-    for (uint32_t c = first + threadIdx.x; c < last; c += THREADS)
-        *reinterpret_cast<chunk16*>(stage + 16u * c) = *reinterpret_cast<const chunk16*>(g0 + 16u * c);
-    const uint32_t head_end = first * 16u < end ? first * 16u : end;
-    const uint32_t tail = last * 16u > head_end ? last * 16u : head_end;
-    uint32_t i = phase + threadIdx.x;
-    if (i < head_end) stage[i] = g0[i];
-    i = tail + threadIdx.x;
-    if (i < end) stage[i] = g0[i];
+    SliceShape s;
+    s.phase = phase_of(src);
+    s.end = s.phase + nbytes;
+    s.g0 = src - s.phase;
+    s.first = (s.phase + 15u) >> 4;
+    s.last = s.end >> 4;
+    s.head_end = s.first * 16u < s.end ? s.first * 16u : s.end;
+    s.tail = s.last * 16u > s.head_end ? s.last * 16u : s.head_end;
+    return s;
+}
+template <int THREADS, int K>
+__device__ __forceinline__ void slice_request(SliceLoads<K>& l, const uint8_t* src, uint32_t nbytes)
+{
+    const SliceShape s = slice_shape(src, nbytes);
+    const uint32_t ih = s.phase + threadIdx.x, it = s.tail + threadIdx.x;
+    l.head_byte = l.tail_byte = 0;
+    if (ih < s.head_end) l.head_byte = s.g0[ih];
+    if (it < s.end) l.tail_byte = s.g0[it];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t c = s.first + threadIdx.x + k * THREADS;
+        l.got[k] = chunk16{0u, 0u, 0u, 0u};
+        if (c < s.last) l.got[k] = *reinterpret_cast<const chunk16*>(s.g0 + 16u * c);
+    }
+}
+template <int THREADS, int K>
+__device__ __forceinline__ void slice_commit(const SliceLoads<K>& l, uint8_t* stage, const uint8_t* src, uint32_t nbytes)
+{
+    const SliceShape s = slice_shape(src, nbytes);
+    const uint32_t ih = s.phase + threadIdx.x, it = s.tail + threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t c = s.first + threadIdx.x + k * THREADS;
+        if (c < s.last) *reinterpret_cast<chunk16*>(stage + 16u * c) = l.got[k];
+    }
+    if (ih < s.head_end) stage[ih] = l.head_byte;
+    if (it < s.end) stage[it] = l.tail_byte;
+    for (uint32_t c0 = s.first + threadIdx.x + K * THREADS; c0 < s.last; c0 += K * THREADS) {
+        chunk16 more[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint32_t c = c0 + k * THREADS;
+            more[k] = chunk16{0u, 0u, 0u, 0u};
+            if (c < s.last) more[k] = *reinterpret_cast<const chunk16*>(s.g0 + 16u * c);
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint32_t c = c0 + k * THREADS;
+            if (c < s.last) *reinterpret_cast<chunk16*>(stage + 16u * c) = more[k];
+        }
+    }
 }
 
 // LDS of a workgroup: a tile puts at most N*N values and N*N + N + 1 index bytes into the streams
@@ -666,8 +718,15 @@ __global__ __launch_bounds__(Group<N>::kTiles) void sparse_read_kernel(const Bat
     uint64_t have_i = base.index_bytes < index_count ? index_count - base.index_bytes : 0u;
     if (have_v > total.values) have_v = total.values;
     if (have_i > total.index_bytes) have_i = total.index_bytes;
-    stream_to_stage<T>(stage_v, reinterpret_cast<const uint8_t*>(value_slice), (uint32_t)have_v * (uint32_t)sizeof(Bits));
-    stream_to_stage<T>(stage_i, index_slice, (uint32_t)have_i);
+    {
+        SliceLoads<4> of_values;
+        SliceLoads<2> of_indices;
+        const uint32_t value_bytes = (uint32_t)have_v * (uint32_t)sizeof(Bits);
+        slice_request<T, 4>(of_values, reinterpret_cast<const uint8_t*>(value_slice), value_bytes);
+        slice_request<T, 2>(of_indices, index_slice, (uint32_t)have_i);
+        slice_commit<T, 4>(of_values, stage_v, reinterpret_cast<const uint8_t*>(value_slice), value_bytes);
+        slice_commit<T, 2>(of_indices, stage_i, index_slice, (uint32_t)have_i);
+    }
     __syncthreads();
     if (!live) return;
 
