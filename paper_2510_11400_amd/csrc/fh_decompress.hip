@@ -105,6 +105,21 @@ __device__ __forceinline__ void fetch_kept(const ChannelMap& cm, int raw_dtype, 
     }
 }
 
+// The same in two steps: the loads alone (the raw values as fp32 bit patterns) ...
+template <int N>
+__device__ __forceinline__ void request_kept(const ChannelMap& cm, int raw_dtype, const KeptRun<N>& run, uint32_t (&bits)[N])
+{
+    if (raw_dtype == 0) {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (run.mask & (1u << j)) bits[j] = static_cast<const uint32_t*>(cm.raw)[raw_index<N>(cm, run, j)];
+    } else {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (run.mask & (1u << j)) bits[j] = (uint32_t) static_cast<const uint16_t*>(cm.raw)[raw_index<N>(cm, run, j)] << 16;
+    }
+}
+
 // One channel per element (fh_channels.hpp): the wave's restored span is parked in LDS in the output's
 // dtype, the lanes walk the span's (sample, row) pairs and overwrite the kept elements with the
 // raw store's values -- consecutive lanes, consecutive rows --, then every lane takes its 16 bytes
@@ -230,14 +245,25 @@ __device__ __forceinline__ void decompress_tile(const DecompressItem& it, uint32
             }
         }
         KeptRun<EPL> run[kRowsPerWave];
-        if constexpr (MIXED) kept_runs<kRowsPerWave, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
+        uint32_t kept[kRowsPerWave][EPL] = {};                // MIXED: the raw store's bits of the lane's kept elements
+        if constexpr (MIXED) {
+            // which elements are kept does not depend on the codes: their raw values are requested now, with the codes
+            // on their way, and not row by row after the codes have come (a wave with a kept run paid a second memory
+            // latency per row)
+            kept_runs<kRowsPerWave, EPL>(*cm, wave_pos, lane * EPL, ROW, run);
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r)
+                if (run[r].mask) request_kept<EPL>(*cm, raw_dtype, run[r], kept[r]);
+        }
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r) {
             const int64_t i0 = wave_base + r * ROW + lane * EPL;
             float v[EPL];
             restore<EPL, B>(c0[r], c1[r], m[r], v);
             if constexpr (MIXED) {
-                if (run[r].mask) fetch_kept<EPL>(*cm, raw_dtype, run[r], v);
+#pragma unroll
+                for (int j = 0; j < EPL; ++j)
+                    if (run[r].mask & (1u << j)) v[j] = __builtin_bit_cast(float, kept[r][j]);
             }
             if constexpr (EPL == 4) {
                 stream_store(reinterpret_cast<f32x4*>(static_cast<float*>(it.out) + i0), f32x4{v[0], v[1], v[2], v[3]});
